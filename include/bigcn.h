@@ -1,0 +1,188 @@
+/*
+ * bigcn.h - C ABI of the MI355X (gfx950) Bi-GCN forward library.
+ *
+ * The library implements the inference path of a binary graph convolutional network
+ * ("Bi-GCN", arXiv 2210.13149, Sec. 4.2): per layer, node activations are sign-binarised
+ * and bit-packed with one scale per node, weights are sign-binarised with one scale per
+ * output channel, the +-1 inner products are evaluated with XOR / population count, and
+ * the rescaled result is aggregated with the normalised adjacency
+ * A~ = D^-1/2 (A + I) D^-1/2 stored in CSR.
+ *
+ * Conventions common to every entry point
+ *  - Pointers marked DEVICE must be device (HBM) addresses valid on the current device,
+ *    allocated by the caller (e.g. torch.empty(..., device="cuda").data_ptr()).  Pointers
+ *    marked HOST are ordinary host pointers.  The library never takes ownership of a
+ *    caller buffer and, outside bigcn_plan_create, never allocates or frees device memory.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Kernels are
+ *    enqueued asynchronously on it; the function returns without synchronising unless
+ *    stated otherwise.
+ *  - Return value: BIGCN_OK (0) or a negative bigcn_status.  Argument errors are detected
+ *    on the host before anything is launched, so on error no output is touched.  The
+ *    library never aborts, throws or prints.
+ *  - Packed layout: a +-1 vector of length K occupies ceil(K/64) uint64 words; bit l
+ *    (LSB = bit 0) of word w is 1 iff element 64*w + l is +1; bits past K are 0.
+ *  - sign(0) = +1: an element is +1 iff value >= threshold.  NaN compares false (-1) and
+ *    poisons the scale of its row; inputs are not screened for NaN.
+ */
+#ifndef BIGCN_H
+#define BIGCN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BIGCN_OK = 0,
+    BIGCN_EINVAL = -1,     /* a size, stride or flag is out of range                    */
+    BIGCN_ENULL = -2,      /* a required pointer is NULL                               */
+    BIGCN_ESHAPE = -3,     /* the shape is valid but exceeds a documented limit        */
+    BIGCN_EWORKSPACE = -4, /* workspace missing, too small or misaligned               */
+    BIGCN_EGRAPH = -5,     /* the CSR pattern failed validation                        */
+    BIGCN_EHIP = -6        /* a HIP runtime call or kernel launch failed               */
+} bigcn_status;
+
+/* Static, NUL-terminated description of a status code (never NULL). */
+const char *bigcn_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int bigcn_version(void);
+
+/* Largest supported inner dimension (bits) of bigcn_binary_gemm / a layer's d_in, and
+ * largest d_out of a layer of bigcn_forward. */
+#define BIGCN_MAX_K_BITS 8192
+#define BIGCN_MAX_FORWARD_D_OUT 512
+
+/*
+ * Kernel 1 - binarise and pack the rows of a strided fp32 matrix
+ * (Sec. 4.1: V_B = sign(V), alpha = ||V||_1 / t; Sec. 4.2.2 for node features with
+ * t = d_in; Sec. 4.2.1 for the columns of a weight matrix, by passing its transpose view;
+ * Sec. 4.4 step 1 for the optional standardisation of the input).
+ *
+ *   element (r, c) is read at x[r*row_stride + c*col_stride]              (DEVICE, fp32)
+ *   x' = (x - shift[c]) * mul[c]      shift == NULL -> 0, mul == NULL -> 1  (DEVICE, cols)
+ *   bits[r*ld_words + w]  packed signs, +1 iff x >= shift[c]               (DEVICE, out)
+ *   scale[r] = (1/cols) * sum_c |x'|                                        (DEVICE, out)
+ *
+ * Packing W^T (d_out rows of length d_in) from a row-major W (d_in, d_out):
+ *   bigcn_pack(W, d_out, d_in, 1, d_out, NULL, NULL, bits, ld_words, alpha, stream).
+ * Only the first ceil(cols/64) words of each output row are written.
+ * Errors: ENULL (x, bits or scale NULL), EINVAL (rows < 0, cols <= 0, strides <= 0,
+ * ld_words < ceil(cols/64)).  rows == 0 is a no-op.
+ */
+int bigcn_pack(const float *x, int64_t rows, int64_t cols, int64_t row_stride,
+               int64_t col_stride, const float *shift, const float *mul, uint64_t *bits,
+               int64_t ld_words, float *scale, void *stream);
+
+/*
+ * Kernel 2 - binary matrix product with fused rescale (Sec. 4.2.3,
+ * zeta_ij = beta_i alpha_j F_i (*) B_j with (*) = XNOR + bit count).
+ *
+ *   a_bits: m rows of packed signs, row stride lda_words        (DEVICE)
+ *   b_bits: n rows of packed signs (row j = column j of B), row stride ldb_words (DEVICE)
+ *   acc[i*ld_acc + j] = k_bits - 2*popcount(a_i xor b_j)  (int32, exact)  (DEVICE, nullable)
+ *   out[i*ld_out + j] = a_scale[i] * b_scale[j] * acc_ij  (fp32)          (DEVICE, nullable)
+ * At least one of acc / out must be given; a_scale and b_scale are required iff out is.
+ * Pad bits (positions >= k_bits) must be equal in both operands (bigcn_pack writes 0).
+ * Errors: ENULL, EINVAL (negative sizes, k_bits <= 0, leading dimensions too small),
+ * ESHAPE (k_bits > BIGCN_MAX_K_BITS).  m == 0 or n == 0 is a no-op.
+ */
+int bigcn_binary_gemm(const uint64_t *a_bits, const float *a_scale, int64_t m,
+                      int64_t lda_words, const uint64_t *b_bits, const float *b_scale,
+                      int64_t n, int64_t ldb_words, int64_t k_bits, int32_t *acc,
+                      int64_t ld_acc, float *out, int64_t ld_out, void *stream);
+
+/*
+ * Normalisation coefficients of A~ = D^-1/2 (A+I) D^-1/2 (Sec. 3.1 Notations, Eq. (1)).
+ * The CSR arrays describe the pattern of A + I: symmetric, one self-loop per node,
+ * columns strictly increasing inside a row; D_ii is the number of stored entries of row i.
+ *
+ *   row_ptr int64[n+1], col_idx int32[nnz]                      (DEVICE)
+ *   dinv_sqrt[i] = D_ii^-1/2                                    (DEVICE, out, n)
+ *   vals[p] = dinv_sqrt[i] * dinv_sqrt[col_idx[p]]              (DEVICE, out, nnz, nullable)
+ * Errors: ENULL, EINVAL (n < 0).
+ */
+int bigcn_gcn_norm(const int64_t *row_ptr, const int32_t *col_idx, int64_t n,
+                   float *dinv_sqrt, float *vals, void *stream);
+
+/*
+ * Aggregation schedule for one graph: rows ordered by decreasing length so that long
+ * rows start first and the waves of a workgroup carry similar work.  The plan owns a
+ * small amount of device memory (4 bytes per row), is immutable after creation and may
+ * be used from any stream of the device it was created on.
+ *
+ * bigcn_plan_create copies row_ptr to the host and therefore SYNCHRONISES `stream`.
+ * With validate != 0 it also checks on the device that every column index lies in
+ * [0, n), columns increase strictly inside each row, every row holds its self-loop and
+ * the pattern is symmetric; a violation returns BIGCN_EGRAPH and creates nothing.
+ * Errors: ENULL, EINVAL (n < 0 or n >= 2^31, row_ptr not non-decreasing from 0),
+ * EGRAPH, EHIP.  *out is set only on success.  bigcn_plan_destroy(NULL) is a no-op.
+ */
+typedef struct bigcn_plan bigcn_plan;
+int bigcn_plan_create(const int64_t *row_ptr, const int32_t *col_idx, int64_t n, int validate,
+                      bigcn_plan **out, void *stream);
+void bigcn_plan_destroy(bigcn_plan *plan);
+/* Number of rows / stored entries the plan was built for. */
+int64_t bigcn_plan_rows(const bigcn_plan *plan);
+int64_t bigcn_plan_nnz(const bigcn_plan *plan);
+
+/*
+ * Kernel 3 - aggregation H = A~ Z as a CSR sparse-dense product (Sec. 4.2.3,
+ * H_b^(l+1) = A~ zeta^(l); the aggregation itself stays in floating point, Sec. 4):
+ *
+ *   out[i*ld_out + j] = sum_{p in row i} vals[p] * z[col_idx[p]*ld_z + j],  j < d
+ *
+ * vals == NULL means all ones.  z (n rows, d columns, fp32) and out must not overlap.
+ * Each output element is a sum in a fixed order, so results are run-to-run identical.
+ * `plan` must have been created from the same row_ptr / col_idx.
+ * Errors: ENULL, EINVAL (n differs from the plan's, d <= 0, ld_z < d, ld_out < d).
+ */
+int bigcn_spmm(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+               const float *vals, int64_t n, const float *z, int64_t d, int64_t ld_z,
+               float *out, int64_t ld_out, void *stream);
+
+/*
+ * One binarised graph-convolution layer (Sec. 4.2): packed weights and scales as produced
+ * by bigcn_pack on the transposed weight matrix, and the optional frozen standardisation
+ * (Sec. 4.4 step 1) applied to the layer's *input* before it is binarised.
+ */
+typedef struct {
+    const uint64_t *w_bits; /* DEVICE: d_out rows of packed signs of W[:, j], stride ld_words */
+    const float *alpha;     /* DEVICE: d_out scales alpha_j = ||W[:, j]||_1 / d_in           */
+    int64_t d_in;
+    int64_t d_out;
+    int64_t ld_words;       /* >= ceil(d_in/64)                                             */
+    const float *bn_shift;  /* DEVICE, d_in, nullable: threshold / mean of each input column */
+    const float *bn_mul;    /* DEVICE, d_in, nullable: 1/sqrt(var + eps) of each column      */
+} bigcn_layer;
+
+/*
+ * Fused L-layer forward (Eq. (1) with H^(0) = X; per layer Sec. 4.2.3):
+ *   for l = 0..L-1:  (F, beta) = binarise(standardise_l(H^(l)));  C = F (*) B_l;
+ *                    H^(l+1) = A~ (beta_i alpha_j C_ij)
+ * and logits = H^(L) (no bias, no ReLU, no softmax).  Hidden activations are never stored
+ * in fp32: the aggregation of layer l emits the packed signs and scales of layer l+1.
+ *
+ *   plan, row_ptr, col_idx : the graph (pattern of A + I)                 (DEVICE arrays)
+ *   dinv_sqrt              : output of bigcn_gcn_norm for the same graph   (DEVICE, n)
+ *   x                      : fp32 node features, n rows of layers[0].d_in, row stride ld_x (DEVICE)
+ *   layers                 : HOST array of n_layers descriptors; layers[l+1].d_in must equal
+ *                            layers[l].d_out
+ *   logits                 : n rows of layers[L-1].d_out fp32, row stride ld_logits (DEVICE, out)
+ *   workspace              : DEVICE scratch of at least bigcn_forward_workspace_bytes(...)
+ *                            bytes, 256-byte aligned; contents are undefined afterwards
+ * Errors: ENULL, EINVAL, ESHAPE (d_in > BIGCN_MAX_K_BITS or d_out > BIGCN_MAX_FORWARD_D_OUT),
+ * EWORKSPACE.  bigcn_forward_workspace_bytes returns 0 for invalid arguments.
+ */
+size_t bigcn_forward_workspace_bytes(int64_t n, const bigcn_layer *layers, int n_layers);
+int bigcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                  const float *dinv_sqrt, int64_t n, const float *x, int64_t ld_x,
+                  const bigcn_layer *layers, int n_layers, float *logits, int64_t ld_logits,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BIGCN_H */

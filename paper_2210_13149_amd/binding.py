@@ -1,0 +1,319 @@
+"""ctypes binding of ``libbigcn.so`` (see ``include/bigcn.h``).
+
+Argument marshalling only: every step of the forward path runs in the HIP kernels of the
+library.  PyTorch is used for device memory (``torch.empty``) and for the current stream.
+There is no CPU fallback: if the library has not been built, or no GPU is present, calls
+raise.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIBRARY = os.path.join(HERE, "libbigcn.so")
+
+BIGCN_OK = 0
+BIGCN_EINVAL = -1
+BIGCN_ENULL = -2
+BIGCN_ESHAPE = -3
+BIGCN_EWORKSPACE = -4
+BIGCN_EGRAPH = -5
+BIGCN_EHIP = -6
+MAX_K_BITS = 8192
+MAX_FORWARD_D_OUT = 512
+
+EXPORTS = (
+    "bigcn_status_string", "bigcn_version", "bigcn_pack", "bigcn_binary_gemm", "bigcn_gcn_norm",
+    "bigcn_plan_create", "bigcn_plan_destroy", "bigcn_plan_rows", "bigcn_plan_nnz", "bigcn_spmm",
+    "bigcn_forward_workspace_bytes", "bigcn_forward",
+)
+
+
+class BigcnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class LayerDesc(ctypes.Structure):
+    """Mirror of ``bigcn_layer``."""
+    _fields_ = [
+        ("w_bits", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
+        ("d_in", ctypes.c_int64), ("d_out", ctypes.c_int64), ("ld_words", ctypes.c_int64),
+        ("bn_shift", ctypes.c_void_p), ("bn_mul", ctypes.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIBRARY):
+            raise RuntimeError(
+                f"{LIBRARY} is missing: build it with `python -m paper_2210_13149_amd.build` "
+                "(or __graft_entry__.build()); there is no CPU fallback")
+        L = ctypes.CDLL(LIBRARY)
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        L.bigcn_status_string.restype = ctypes.c_char_p
+        L.bigcn_status_string.argtypes = [i32]
+        L.bigcn_version.restype = i32
+        L.bigcn_version.argtypes = []
+        L.bigcn_pack.restype = i32
+        L.bigcn_pack.argtypes = [vp, i64, i64, i64, i64, vp, vp, vp, i64, vp, vp]
+        L.bigcn_binary_gemm.restype = i32
+        L.bigcn_binary_gemm.argtypes = [vp, vp, i64, i64, vp, vp, i64, i64, i64, vp, i64, vp, i64, vp]
+        L.bigcn_gcn_norm.restype = i32
+        L.bigcn_gcn_norm.argtypes = [vp, vp, i64, vp, vp, vp]
+        L.bigcn_plan_create.restype = i32
+        L.bigcn_plan_create.argtypes = [vp, vp, i64, i32, ctypes.POINTER(vp), vp]
+        L.bigcn_plan_destroy.restype = None
+        L.bigcn_plan_destroy.argtypes = [vp]
+        L.bigcn_plan_rows.restype = i64
+        L.bigcn_plan_rows.argtypes = [vp]
+        L.bigcn_plan_nnz.restype = i64
+        L.bigcn_plan_nnz.argtypes = [vp]
+        L.bigcn_spmm.restype = i32
+        L.bigcn_spmm.argtypes = [vp, vp, vp, vp, i64, vp, i64, i64, vp, i64, vp]
+        L.bigcn_forward_workspace_bytes.restype = ctypes.c_size_t
+        L.bigcn_forward_workspace_bytes.argtypes = [i64, ctypes.POINTER(LayerDesc), i32]
+        L.bigcn_forward.restype = i32
+        L.bigcn_forward.argtypes = [vp, vp, vp, vp, i64, vp, i64, ctypes.POINTER(LayerDesc), i32, vp,
+                                    i64, vp, ctypes.c_size_t, vp]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().bigcn_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(lib().bigcn_version())
+
+
+def _check(status: int, where: str) -> None:
+    if status != BIGCN_OK:
+        raise BigcnError(status, where)
+
+
+def _stream() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a CUDA (HIP) tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    return t
+
+
+def n_words(k_bits: int) -> int:
+    return (int(k_bits) + 63) // 64
+
+
+# ------------------------------------------------------------------------------------------
+# kernel 1
+# ------------------------------------------------------------------------------------------
+def bigcn_pack(x: torch.Tensor, shift: Optional[torch.Tensor] = None,
+               mul: Optional[torch.Tensor] = None, ld_words: Optional[int] = None
+               ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Binarise + pack the rows of a 2-D fp32 tensor (any strides, e.g. ``W.t()``).
+    Returns ``(bits int64 (rows, ld_words) holding the uint64 words, scale fp32 (rows,))``."""
+    _dev(x, torch.float32, "x")
+    if x.dim() != 2:
+        raise ValueError("x must be a matrix")
+    rows, cols = x.shape
+    words = n_words(cols)
+    ld = words if ld_words is None else int(ld_words)
+    bits = torch.zeros((rows, max(ld, 1)), dtype=torch.int64, device=x.device)
+    scale = torch.empty((rows,), dtype=torch.float32, device=x.device)
+    for p, name in ((shift, "shift"), (mul, "mul")):
+        if p is not None:
+            _dev(p, torch.float32, name)
+            if p.shape != (cols,) or not p.is_contiguous():
+                raise ValueError(f"{name} must be a contiguous vector of length cols")
+    _check(lib().bigcn_pack(_ptr(x), rows, cols, x.stride(0), x.stride(1), _ptr(shift), _ptr(mul),
+                            _ptr(bits), ld, _ptr(scale), _stream()), "bigcn_pack")
+    return bits, scale
+
+
+def pack_weight(w: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Packed signs of the columns of W (d_in, d_out) and their scales alpha (d_out,)."""
+    return bigcn_pack(w.t())
+
+
+# ------------------------------------------------------------------------------------------
+# kernel 2
+# ------------------------------------------------------------------------------------------
+def bigcn_binary_gemm(a_bits: torch.Tensor, a_scale: Optional[torch.Tensor], b_bits: torch.Tensor,
+                      b_scale: Optional[torch.Tensor], k_bits: int, want_acc: bool = True,
+                      want_out: bool = True) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor]]:
+    """``acc = K - 2 popcount(a xor b)`` (int32) and / or ``out = a_scale_i b_scale_j acc``."""
+    _dev(a_bits, torch.int64, "a_bits")
+    _dev(b_bits, torch.int64, "b_bits")
+    m, n = a_bits.shape[0], b_bits.shape[0]
+    acc = torch.empty((m, n), dtype=torch.int32, device=a_bits.device) if want_acc else None
+    out = torch.empty((m, n), dtype=torch.float32, device=a_bits.device) if want_out else None
+    if want_out:
+        _dev(a_scale, torch.float32, "a_scale")
+        _dev(b_scale, torch.float32, "b_scale")
+    _check(lib().bigcn_binary_gemm(_ptr(a_bits), _ptr(a_scale), m, a_bits.stride(0), _ptr(b_bits),
+                                   _ptr(b_scale), n, b_bits.stride(0), int(k_bits), _ptr(acc), n,
+                                   _ptr(out), n, _stream()), "bigcn_binary_gemm")
+    return acc, out
+
+
+# ------------------------------------------------------------------------------------------
+# graph helpers and kernel 3
+# ------------------------------------------------------------------------------------------
+def bigcn_gcn_norm(row_ptr: torch.Tensor, col_idx: torch.Tensor, want_vals: bool = False
+                   ) -> Tuple[torch.Tensor, Optional[torch.Tensor]]:
+    _dev(row_ptr, torch.int64, "row_ptr")
+    _dev(col_idx, torch.int32, "col_idx")
+    n = row_ptr.numel() - 1
+    dinv = torch.empty((n,), dtype=torch.float32, device=row_ptr.device)
+    vals = torch.empty((col_idx.numel(),), dtype=torch.float32, device=row_ptr.device) if want_vals else None
+    _check(lib().bigcn_gcn_norm(_ptr(row_ptr), _ptr(col_idx), n, _ptr(dinv), _ptr(vals), _stream()),
+           "bigcn_gcn_norm")
+    return dinv, vals
+
+
+class Plan:
+    """Owner of a ``bigcn_plan`` (destroyed with the object)."""
+
+    def __init__(self, row_ptr: torch.Tensor, col_idx: torch.Tensor, validate: bool = True):
+        _dev(row_ptr, torch.int64, "row_ptr")
+        _dev(col_idx, torch.int32, "col_idx")
+        self.n = row_ptr.numel() - 1
+        handle = ctypes.c_void_p()
+        self._handle = None
+        _check(lib().bigcn_plan_create(_ptr(row_ptr), _ptr(col_idx), self.n, int(bool(validate)),
+                                       ctypes.byref(handle), _stream()), "bigcn_plan_create")
+        self._handle = handle
+
+    @property
+    def handle(self) -> ctypes.c_void_p:
+        if self._handle is None:
+            raise RuntimeError("plan was destroyed")
+        return self._handle
+
+    @property
+    def nnz(self) -> int:
+        return int(lib().bigcn_plan_nnz(self.handle))
+
+    def destroy(self) -> None:
+        if self._handle is not None:
+            lib().bigcn_plan_destroy(self._handle)
+            self._handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def bigcn_spmm(plan: Plan, row_ptr: torch.Tensor, col_idx: torch.Tensor,
+               vals: Optional[torch.Tensor], z: torch.Tensor) -> torch.Tensor:
+    """``out = sum_p vals[p] * z[col_idx[p], :]`` per CSR row (vals None = ones)."""
+    _dev(z, torch.float32, "z")
+    if z.dim() != 2 or (z.shape[1] > 1 and z.stride(1) != 1):
+        raise ValueError("z must be a row-major matrix")
+    if vals is not None:
+        _dev(vals, torch.float32, "vals")
+    n, d = z.shape
+    out = torch.empty((n, d), dtype=torch.float32, device=z.device)
+    _check(lib().bigcn_spmm(plan.handle, _ptr(row_ptr), _ptr(col_idx), _ptr(vals), n, _ptr(z), d,
+                            z.stride(0), _ptr(out), d, _stream()), "bigcn_spmm")
+    return out
+
+
+# ------------------------------------------------------------------------------------------
+# fused forward
+# ------------------------------------------------------------------------------------------
+class Layer:
+    """Device-resident parameters of one binarised layer."""
+
+    def __init__(self, w_bits: torch.Tensor, alpha: torch.Tensor, d_in: int, d_out: int,
+                 bn_shift: Optional[torch.Tensor] = None, bn_mul: Optional[torch.Tensor] = None):
+        self.w_bits = _dev(w_bits, torch.int64, "w_bits")
+        self.alpha = _dev(alpha, torch.float32, "alpha")
+        self.d_in, self.d_out = int(d_in), int(d_out)
+        self.bn_shift = None if bn_shift is None else _dev(bn_shift, torch.float32, "bn_shift").contiguous()
+        self.bn_mul = None if bn_mul is None else _dev(bn_mul, torch.float32, "bn_mul").contiguous()
+
+    @classmethod
+    def from_weight(cls, w: torch.Tensor, bn_shift=None, bn_mul=None) -> "Layer":
+        bits, alpha = pack_weight(w)
+        return cls(bits, alpha, w.shape[0], w.shape[1], bn_shift, bn_mul)
+
+    def desc(self) -> LayerDesc:
+        return LayerDesc(_ptr(self.w_bits), _ptr(self.alpha), self.d_in, self.d_out,
+                         self.w_bits.stride(0), _ptr(self.bn_shift), _ptr(self.bn_mul))
+
+
+def _descs(layers: Sequence[Layer]):
+    arr = (LayerDesc * len(layers))(*[l.desc() for l in layers])
+    return arr
+
+
+def bigcn_forward_workspace_bytes(n: int, layers: Sequence[Layer]) -> int:
+    return int(lib().bigcn_forward_workspace_bytes(int(n), _descs(layers), len(layers)))
+
+
+def bigcn_forward(plan: Plan, row_ptr: torch.Tensor, col_idx: torch.Tensor, dinv_sqrt: torch.Tensor,
+                  x: torch.Tensor, layers: Sequence[Layer], workspace: Optional[torch.Tensor] = None,
+                  logits: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """L-layer fused forward; returns fp32 logits (n, d_out of the last layer)."""
+    _dev(x, torch.float32, "x")
+    if x.dim() != 2 or (x.shape[1] > 1 and x.stride(1) != 1):
+        raise ValueError("x must be a row-major matrix")
+    n = x.shape[0]
+    descs = _descs(layers)
+    if workspace is None:
+        need = bigcn_forward_workspace_bytes(n, layers)
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=x.device)
+    if logits is None:
+        logits = torch.empty((n, layers[-1].d_out), dtype=torch.float32, device=x.device)
+    _check(lib().bigcn_forward(plan.handle, _ptr(row_ptr), _ptr(col_idx), _ptr(dinv_sqrt), n, _ptr(x),
+                               x.stride(0), descs, len(layers), _ptr(logits), logits.stride(0),
+                               _ptr(workspace), workspace.numel(), _stream()), "bigcn_forward")
+    return logits
+
+
+class BiGCN:
+    """Graph + packed layers + workspace, ready for repeated forward passes."""
+
+    def __init__(self, row_ptr: torch.Tensor, col_idx: torch.Tensor, weights: Sequence[torch.Tensor],
+                 bn: Optional[Sequence[Optional[Tuple[torch.Tensor, torch.Tensor]]]] = None,
+                 validate: bool = True):
+        self.row_ptr, self.col_idx = row_ptr, col_idx
+        self.n = row_ptr.numel() - 1
+        self.plan = Plan(row_ptr, col_idx, validate=validate)
+        self.dinv_sqrt, _ = bigcn_gcn_norm(row_ptr, col_idx)
+        bn = list(bn) if bn is not None else [None] * len(weights)
+        self.layers: List[Layer] = []
+        for w, p in zip(weights, bn):
+            shift, mul = p if p is not None else (None, None)
+            self.layers.append(Layer.from_weight(w, shift, mul))
+        need = bigcn_forward_workspace_bytes(self.n, self.layers)
+        self.workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=row_ptr.device)
+        self.logits = torch.empty((self.n, self.layers[-1].d_out), dtype=torch.float32,
+                                  device=row_ptr.device)
+
+    def forward(self, x: torch.Tensor) -> torch.Tensor:
+        return bigcn_forward(self.plan, self.row_ptr, self.col_idx, self.dinv_sqrt, x, self.layers,
+                             self.workspace, self.logits)

@@ -1,0 +1,107 @@
+// Internal declarations shared by the HIP translation units of libbigcn (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "bigcn.h"
+
+namespace bigcn {
+
+constexpr int kWave = 64;          // CDNA wavefront width
+constexpr int kBlock = 256;        // threads per workgroup used by every kernel here
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+// Rows at least this long are aggregated by a whole workgroup instead of one wavefront.
+constexpr int64_t kBlockRowDegree = 256;
+
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline int check_launch()
+{
+    return hipGetLastError() == hipSuccess ? BIGCN_OK : BIGCN_EHIP;
+}
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+
+// Wave-uniform index of this thread's wavefront inside its workgroup, as a scalar value.
+__device__ __forceinline__ int wave_in_block()
+{
+    return __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) >> 6);
+}
+
+// Sum over the 64 lanes of a wavefront in a fixed butterfly order (every lane gets the sum).
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1)
+        v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+// Layout in which the fused forward keeps the integer products C of one node:
+// `groups` lanes hold `vec` consecutive stored values each; stored position
+// g*vec + v holds output column g + groups*v.  With this interleaving one ballot per v
+// yields `groups` consecutive sign bits of the next layer's packed activation.
+struct RowLayout {
+    int groups;   // lanes that share one stored row (power of two, 2..64)
+    int vec;      // values per lane (4 or 8)
+    int half;     // 1: values stored as fp16 (exact for |c| <= 2048), 0: fp32
+    __host__ __device__ int positions() const { return groups * vec; }
+    __host__ __device__ int64_t row_bytes() const
+    {
+        return static_cast<int64_t>(positions()) * (half ? 2 : 4);
+    }
+};
+
+// Layout used for a layer with d_out columns and d_in input bits.
+RowLayout choose_layout(int64_t d_in, int64_t d_out);
+
+// ---- internal launchers (defined in the .hip files) ------------------------------------
+// pack: as bigcn_pack, plus an optional per-row factor folded into the scale.
+int launch_pack(const float *x, int64_t rows, int64_t cols, int64_t row_stride,
+                int64_t col_stride, const float *shift, const float *mul, const float *row_mul,
+                uint64_t *bits, int64_t ld_words, float *scale, hipStream_t stream);
+
+// bit-GEMM writing the integer products in a RowLayout (fused forward).
+int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits,
+                          int64_t n, int64_t ldb, int64_t k_bits, void *c_rows, RowLayout layout,
+                          hipStream_t stream);
+
+// Aggregation of layer l fused with the rescale and with the binarisation of layer l+1.
+struct FusedSpmmArgs {
+    const bigcn_plan *plan;
+    const int64_t *row_ptr;
+    const int32_t *col_idx;
+    const float *dinv_sqrt;     // n
+    const float *src_scale;     // n: dinv_sqrt[k] * beta_k of this layer's input
+    const void *c_rows;         // n rows in `layout`
+    RowLayout layout;
+    const float *alpha;         // d_out
+    int64_t d_out;
+    // last layer: fp32 logits
+    float *logits;
+    int64_t ld_logits;
+    // hidden layer: packed signs + scale of the next layer's input
+    const float *next_shift;    // d_out, nullable
+    const float *next_mul;      // d_out, nullable
+    uint64_t *next_bits;
+    int64_t next_ld_words;
+    float *next_scale;          // n: dinv_sqrt[i] * beta_i of the next layer
+};
+int launch_fused_spmm(const FusedSpmmArgs &args, hipStream_t stream);
+
+}  // namespace bigcn
+
+// The plan: row order by decreasing length (device copy) and the split between rows handled
+// by a whole workgroup and rows handled by one wavefront.
+struct bigcn_plan {
+    int64_t n;
+    int64_t nnz;
+    int device;
+    int32_t *row_order;      // DEVICE, n entries
+    int64_t n_block_rows;    // the first n_block_rows entries of row_order have degree >= kBlockRowDegree
+    int64_t max_degree;
+};

@@ -1,0 +1,138 @@
+// Fused L-layer driver (Eq. (1) with H^(0) = X, Sec. 4.2.3 per layer) and library metadata.
+//
+// Per layer l the stream carries two launches: the bit-GEMM, which turns the packed signs of
+// the layer input into the integer products C (one compact row per node), and the fused
+// aggregation, which gathers those rows over the graph, applies beta_k / alpha_j / degree
+// scaling and emits either the next layer's packed signs and scales or the final logits.
+// Only the first layer needs a separate binarise+pack pass over the fp32 features.
+#include <algorithm>
+
+#include "bigcn_internal.h"
+
+namespace bigcn {
+
+struct WorkspaceMap {
+    size_t bits_off, scale0_off, scale1_off, rows_off, total;
+};
+
+static size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
+
+static bool layers_ok(int64_t n, const bigcn_layer *layers, int n_layers, int *status)
+{
+    *status = BIGCN_OK;
+    if (layers == nullptr) { *status = BIGCN_ENULL; return false; }
+    if (n < 0 || n_layers <= 0) { *status = BIGCN_EINVAL; return false; }
+    for (int l = 0; l < n_layers; ++l) {
+        const bigcn_layer &L = layers[l];
+        if (L.w_bits == nullptr || L.alpha == nullptr) { *status = BIGCN_ENULL; return false; }
+        if (L.d_in <= 0 || L.d_out <= 0 || L.ld_words < (L.d_in + 63) / 64) { *status = BIGCN_EINVAL; return false; }
+        if (l > 0 && L.d_in != layers[l - 1].d_out) { *status = BIGCN_EINVAL; return false; }
+        if (L.d_in > BIGCN_MAX_K_BITS || L.d_out > BIGCN_MAX_FORWARD_D_OUT) { *status = BIGCN_ESHAPE; return false; }
+    }
+    return true;
+}
+
+static WorkspaceMap map_workspace(int64_t n, const bigcn_layer *layers, int n_layers)
+{
+    int64_t max_words = 0, max_row_bytes = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        max_words = std::max<int64_t>(max_words, (layers[l].d_in + 63) / 64);
+        max_row_bytes = std::max<int64_t>(max_row_bytes, choose_layout(layers[l].d_in, layers[l].d_out).row_bytes());
+    }
+    WorkspaceMap m;
+    size_t off = 0;
+    m.bits_off = off;   off = align_up(off + static_cast<size_t>(n) * max_words * sizeof(uint64_t));
+    m.scale0_off = off; off = align_up(off + static_cast<size_t>(n) * sizeof(float));
+    m.scale1_off = off; off = align_up(off + static_cast<size_t>(n) * sizeof(float));
+    m.rows_off = off;   off = align_up(off + static_cast<size_t>(n) * max_row_bytes);
+    m.total = off;
+    return m;
+}
+
+}  // namespace bigcn
+
+using namespace bigcn;
+
+extern "C" const char *bigcn_status_string(int status)
+{
+    switch (status) {
+    case BIGCN_OK: return "ok";
+    case BIGCN_EINVAL: return "invalid size, stride or flag";
+    case BIGCN_ENULL: return "required pointer is NULL";
+    case BIGCN_ESHAPE: return "shape exceeds a documented limit";
+    case BIGCN_EWORKSPACE: return "workspace missing, too small or misaligned";
+    case BIGCN_EGRAPH: return "CSR pattern failed validation";
+    case BIGCN_EHIP: return "HIP runtime call or kernel launch failed";
+    default: return "unknown status";
+    }
+}
+
+extern "C" int bigcn_version(void) { return 0 * 10000 + 1 * 100 + 0; }
+
+extern "C" size_t bigcn_forward_workspace_bytes(int64_t n, const bigcn_layer *layers, int n_layers)
+{
+    int status;
+    if (!layers_ok(n, layers, n_layers, &status)) return 0;
+    return map_workspace(n, layers, n_layers).total;
+}
+
+extern "C" int bigcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                             const float *dinv_sqrt, int64_t n, const float *x, int64_t ld_x,
+                             const bigcn_layer *layers, int n_layers, float *logits,
+                             int64_t ld_logits, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (plan == nullptr || row_ptr == nullptr || col_idx == nullptr || dinv_sqrt == nullptr ||
+        x == nullptr || logits == nullptr)
+        return BIGCN_ENULL;
+    int status;
+    if (!layers_ok(n, layers, n_layers, &status)) return status;
+    if (n != plan->n || ld_x < layers[0].d_in || ld_logits < layers[n_layers - 1].d_out) return BIGCN_EINVAL;
+    const WorkspaceMap map = map_workspace(n, layers, n_layers);
+    if (n == 0) return BIGCN_OK;
+    if (workspace == nullptr || workspace_bytes < map.total || reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
+        return BIGCN_EWORKSPACE;
+
+    hipStream_t s = as_stream(stream);
+    char *ws = static_cast<char *>(workspace);
+    uint64_t *bits = reinterpret_cast<uint64_t *>(ws + map.bits_off);
+    float *scale[2] = {reinterpret_cast<float *>(ws + map.scale0_off), reinterpret_cast<float *>(ws + map.scale1_off)};
+    void *c_rows = ws + map.rows_off;
+
+    // layer 0 input: binarise X; the stored scale is dinv_sqrt[i] * beta_i
+    int64_t words = (layers[0].d_in + 63) / 64;
+    int rc = launch_pack(x, n, layers[0].d_in, ld_x, 1, layers[0].bn_shift, layers[0].bn_mul, dinv_sqrt,
+                         bits, words, scale[0], s);
+    if (rc != BIGCN_OK) return rc;
+
+    for (int l = 0; l < n_layers; ++l) {
+        const bigcn_layer &L = layers[l];
+        const RowLayout layout = choose_layout(L.d_in, L.d_out);
+        rc = launch_bitgemm_layout(bits, n, words, L.w_bits, L.d_out, L.ld_words, L.d_in, c_rows, layout, s);
+        if (rc != BIGCN_OK) return rc;
+
+        FusedSpmmArgs a{};
+        a.plan = plan;
+        a.row_ptr = row_ptr;
+        a.col_idx = col_idx;
+        a.dinv_sqrt = dinv_sqrt;
+        a.src_scale = scale[l & 1];
+        a.c_rows = c_rows;
+        a.layout = layout;
+        a.alpha = L.alpha;
+        a.d_out = L.d_out;
+        if (l == n_layers - 1) {
+            a.logits = logits;
+            a.ld_logits = ld_logits;
+        } else {
+            words = (L.d_out + 63) / 64;
+            a.next_shift = layers[l + 1].bn_shift;
+            a.next_mul = layers[l + 1].bn_mul;
+            a.next_bits = bits;
+            a.next_ld_words = words;
+            a.next_scale = scale[(l + 1) & 1];
+        }
+        rc = launch_fused_spmm(a, s);
+        if (rc != BIGCN_OK) return rc;
+    }
+    return BIGCN_OK;
+}

@@ -1,0 +1,413 @@
+// Kernel 3: aggregation with the normalised adjacency, H = A~ Z (Sec. 4.2.3), as a CSR
+// sparse-dense product, and its fused form used by the layer driver.
+//
+// The kernel is a gather: for every stored neighbour k of node i one dense row of Z is read
+// from HBM and accumulated in fp32.  Mapping for wave64:
+//   * a stored row of Z occupies `G` lanes x `V` consecutive values (one 8- or 16-byte load
+//     per lane), so a wavefront covers 64/G neighbours per load instruction when rows are
+//     narrow, and one neighbour when a row spans all 64 lanes;
+//   * column indices (and the per-neighbour weights) of up to 64 neighbours are fetched with
+//     one coalesced load and handed out by lane broadcast, so the inner loop issues only row
+//     loads and FMAs, eight row loads in flight per wavefront;
+//   * rows are taken in order of decreasing length (plan): the longest rows are started
+//     first and each is shared by the four wavefronts of a workgroup (partial sums combined
+//     through LDS in a fixed order); every other row is owned by one wavefront.
+// All sums are evaluated in a fixed order, so results are bit-identical from run to run.
+#include "bigcn_internal.h"
+
+namespace bigcn {
+
+enum WeightMode { kWeightOne = 0, kWeightVals = 1, kWeightGather = 2 };
+
+// ---- one stored row segment: V values of T per lane, loaded as one vector ------------------
+template <typename T, int V>
+struct Segment;
+
+template <>
+struct Segment<float, 1> {
+    float raw;
+    __device__ __forceinline__ void load(const char *p) { raw = *reinterpret_cast<const float *>(p); }
+    __device__ __forceinline__ void fma(float w, float (&acc)[1]) const { acc[0] = fmaf(w, raw, acc[0]); }
+};
+template <>
+struct Segment<float, 4> {
+    float4 raw;
+    __device__ __forceinline__ void load(const char *p) { raw = *reinterpret_cast<const float4 *>(p); }
+    __device__ __forceinline__ void fma(float w, float (&acc)[4]) const
+    {
+        acc[0] = fmaf(w, raw.x, acc[0]);
+        acc[1] = fmaf(w, raw.y, acc[1]);
+        acc[2] = fmaf(w, raw.z, acc[2]);
+        acc[3] = fmaf(w, raw.w, acc[3]);
+    }
+};
+template <>
+struct Segment<float, 8> {
+    float4 lo, hi;
+    __device__ __forceinline__ void load(const char *p)
+    {
+        lo = *reinterpret_cast<const float4 *>(p);
+        hi = *reinterpret_cast<const float4 *>(p + 16);
+    }
+    __device__ __forceinline__ void fma(float w, float (&acc)[8]) const
+    {
+        acc[0] = fmaf(w, lo.x, acc[0]);
+        acc[1] = fmaf(w, lo.y, acc[1]);
+        acc[2] = fmaf(w, lo.z, acc[2]);
+        acc[3] = fmaf(w, lo.w, acc[3]);
+        acc[4] = fmaf(w, hi.x, acc[4]);
+        acc[5] = fmaf(w, hi.y, acc[5]);
+        acc[6] = fmaf(w, hi.z, acc[6]);
+        acc[7] = fmaf(w, hi.w, acc[7]);
+    }
+};
+template <>
+struct Segment<__half, 4> {
+    uint2 raw;
+    __device__ __forceinline__ void load(const char *p) { raw = *reinterpret_cast<const uint2 *>(p); }
+    __device__ __forceinline__ void fma(float w, float (&acc)[4]) const
+    {
+        const __half2 a = *reinterpret_cast<const __half2 *>(&raw.x);
+        const __half2 b = *reinterpret_cast<const __half2 *>(&raw.y);
+        acc[0] = fmaf(w, __low2float(a), acc[0]);
+        acc[1] = fmaf(w, __high2float(a), acc[1]);
+        acc[2] = fmaf(w, __low2float(b), acc[2]);
+        acc[3] = fmaf(w, __high2float(b), acc[3]);
+    }
+};
+template <>
+struct Segment<__half, 8> {
+    uint4 raw;
+    __device__ __forceinline__ void load(const char *p) { raw = *reinterpret_cast<const uint4 *>(p); }
+    __device__ __forceinline__ void fma(float w, float (&acc)[8]) const
+    {
+        const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            acc[2 * q] = fmaf(w, __low2float(h[q]), acc[2 * q]);
+            acc[2 * q + 1] = fmaf(w, __high2float(h[q]), acc[2 * q + 1]);
+        }
+    }
+};
+
+// ---- accumulate the neighbours p0..p1-1 of one node into acc (per lane: V positions) -------
+// active: this lane's positions exist in the stored row (lanes past the row width never load).
+template <typename T, int G, int V, int WM>
+__device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col_idx,
+                                                 const float *__restrict__ weights,
+                                                 const char *__restrict__ lane_base, int64_t row_bytes,
+                                                 int64_t p0, int64_t p1, int lane, bool active,
+                                                 float (&acc)[V])
+{
+    constexpr int S = kWave / G;      // neighbours covered by one load instruction
+    constexpr int U = 8;              // load instructions in flight
+    const int slot = lane / G;
+
+    for (int64_t pb = p0; pb < p1; pb += kWave) {
+        const int cnt = static_cast<int>(p1 - pb < kWave ? p1 - pb : kWave);     // wave-uniform
+        int k = 0;
+        float wk = 0.0f;
+        if (lane < cnt) {
+            k = col_idx[pb + lane];
+            if (WM == kWeightVals) wk = weights[pb + lane];
+            else if (WM == kWeightGather) wk = weights[k];
+            else wk = 1.0f;
+        }
+        int t = 0;
+        // full groups: S*U neighbours, all present
+        for (; t + S * U <= cnt; t += S * U) {
+            Segment<T, V> seg[U];
+            float w[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                int kk;
+                if (S == 1) {
+                    kk = __builtin_amdgcn_readlane(k, t + u);
+                    w[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wk), t + u));
+                } else {
+                    kk = __shfl(k, t + u * S + slot, kWave);
+                    w[u] = __shfl(wk, t + u * S + slot, kWave);
+                }
+                if (active) seg[u].load(lane_base + static_cast<int64_t>(kk) * row_bytes);
+            }
+            if (active) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) seg[u].fma(w[u], acc);
+            }
+        }
+        // tail: fewer than S*U neighbours left in this batch
+        for (; t < cnt; t += S) {
+            const int src = t + slot;
+            const int kk = __shfl(k, src < kWave ? src : 0, kWave);
+            const float ww = __shfl(wk, src < kWave ? src : 0, kWave);
+            if (active && src < cnt) {
+                Segment<T, V> seg;
+                seg.load(lane_base + static_cast<int64_t>(kk) * row_bytes);
+                seg.fma(ww, acc);
+            }
+        }
+    }
+}
+
+// Sum the partial results of the 64/G lane slots; afterwards every lane holds the total.
+template <int G, int V>
+__device__ __forceinline__ void reduce_slots(float (&acc)[V])
+{
+#pragma unroll
+    for (int off = G; off < kWave; off <<= 1)
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[v] += __shfl_xor(acc[v], off, kWave);
+}
+
+// ---- epilogues ---------------------------------------------------------------------------------
+// Public SpMM: stored position == output column, fp32 row-major output.
+struct EpiloguePlain {
+    float *out;
+    int64_t ld_out;
+    int d;                 // valid positions
+    int vector_store;      // 1: V floats of a lane can be written as one aligned vector
+    template <int G, int V>
+    __device__ __forceinline__ void operator()(int64_t row, int lane, const float (&acc)[V]) const
+    {
+        if (lane >= G) return;
+        float *dst = out + row * ld_out + lane * V;
+        if (V == 4 && vector_store) {
+            if (lane * V < d) *reinterpret_cast<float4 *>(dst) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        } else {
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+                if (lane * V + v < d) dst[v] = acc[v];
+        }
+    }
+};
+
+// Fused layer: stored position g*V + v holds column g + G*v of the integer products; the
+// result is rescaled by dinv_i * alpha_j and either written as fp32 logits or turned directly
+// into the packed signs and the scale of the next layer's input.
+struct EpilogueFused {
+    const float *dinv_sqrt;
+    const float *alpha;
+    int d_out;
+    float *logits;
+    int64_t ld_logits;
+    const float *next_shift;
+    const float *next_mul;
+    uint64_t *next_bits;
+    int64_t next_ld_words;
+    float *next_scale;
+    template <int G, int V>
+    __device__ __forceinline__ void operator()(int64_t row, int lane, const float (&acc)[V]) const
+    {
+        const float di = dinv_sqrt[row];
+        const int g = lane & (G - 1);
+        const bool first_slot = lane < G;
+        float h[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const int col = g + G * v;
+            h[v] = col < d_out ? di * alpha[col] * acc[v] : 0.0f;
+        }
+        if (logits != nullptr) {
+            if (first_slot) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    const int col = g + G * v;
+                    if (col < d_out) logits[row * ld_logits + col] = h[v];
+                }
+            }
+            return;
+        }
+        // binarise for the next layer: bit (G*v + g) of the row's bit string is column g + G*v
+        constexpr int kWords = (G * V + 63) / 64;
+        uint64_t words[kWords];
+#pragma unroll
+        for (int q = 0; q < kWords; ++q) words[q] = 0;
+        float sum = 0.0f;
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const int col = g + G * v;
+            const bool valid = first_slot && col < d_out;
+            const float th = (valid && next_shift != nullptr) ? next_shift[col] : 0.0f;
+            const float ml = (valid && next_mul != nullptr) ? next_mul[col] : 1.0f;
+            const uint64_t mask = __ballot(valid && h[v] >= th);   // only the low G lanes can be set
+            words[(G * v) / 64] |= mask << ((G * v) % 64);
+            sum += valid ? fabsf((h[v] - th) * ml) : 0.0f;
+        }
+        sum = wave_sum(sum);
+        const int n_words = (d_out + 63) >> 6;
+#pragma unroll
+        for (int q = 0; q < kWords; ++q)
+            if (lane == q && q < n_words) next_bits[row * next_ld_words + q] = words[q];
+        if (lane == 0) next_scale[row] = di * (sum / static_cast<float>(d_out));
+    }
+};
+
+// ---- the kernel ------------------------------------------------------------------------------
+template <typename T, int G, int V, int WM, class Epilogue>
+__global__ __launch_bounds__(kBlock) void spmm_kernel(
+    const int32_t *__restrict__ row_order, int64_t n, int64_t n_block_rows,
+    const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
+    const float *__restrict__ weights, const char *__restrict__ rows, int64_t row_bytes,
+    int valid_positions, Epilogue epi)
+{
+    __shared__ float partial[kWavesPerBlock - 1][kWave][V];
+    const int lane = lane_id();
+    const int wave = wave_in_block();
+    const int g = lane & (G - 1);
+    const bool active = g * V < valid_positions;
+    const char *lane_base = rows + static_cast<int64_t>(g) * V * sizeof(T);
+
+    float acc[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] = 0.0f;
+
+    if (static_cast<int64_t>(blockIdx.x) < n_block_rows) {
+        // one long row shared by the four wavefronts: contiguous quarters, multiples of 64
+        const int64_t row = row_order[blockIdx.x];
+        const int64_t p0 = row_ptr[row], p1 = row_ptr[row + 1];
+        int64_t chunk = (p1 - p0 + kWavesPerBlock - 1) / kWavesPerBlock;
+        chunk = (chunk + kWave - 1) / kWave * kWave;
+        int64_t q0 = p0 + wave * chunk;
+        int64_t q1 = q0 + chunk;
+        if (q0 > p1) q0 = p1;
+        if (q1 > p1) q1 = p1;
+        accumulate_range<T, G, V, WM>(col_idx, weights, lane_base, row_bytes, q0, q1, lane, active, acc);
+        reduce_slots<G, V>(acc);
+        if (wave > 0) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) partial[wave - 1][lane][v] = acc[v];
+        }
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int w = 0; w < kWavesPerBlock - 1; ++w)
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc[v] += partial[w][lane][v];
+            epi.template operator()<G, V>(row, lane, acc);
+        }
+        return;
+    }
+    const int64_t slot_index = n_block_rows + (static_cast<int64_t>(blockIdx.x) - n_block_rows) * kWavesPerBlock + wave;
+    if (slot_index >= n) return;
+    const int64_t row = row_order[slot_index];
+    const int64_t p0 = row_ptr[row], p1 = row_ptr[row + 1];
+    accumulate_range<T, G, V, WM>(col_idx, weights, lane_base, row_bytes, p0, p1, lane, active, acc);
+    reduce_slots<G, V>(acc);
+    epi.template operator()<G, V>(row, lane, acc);
+}
+
+template <typename T, int G, int V, int WM, class Epilogue>
+static int launch_spmm_one(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                           const float *weights, const void *rows, int64_t row_bytes,
+                           int valid_positions, const Epilogue &epi, hipStream_t stream)
+{
+    const int64_t wave_rows = plan->n - plan->n_block_rows;
+    const int64_t blocks = plan->n_block_rows + (wave_rows + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks == 0) return BIGCN_OK;
+    hipLaunchKernelGGL((spmm_kernel<T, G, V, WM, Epilogue>), dim3(static_cast<unsigned>(blocks)),
+                       dim3(kBlock), 0, stream, plan->row_order, plan->n, plan->n_block_rows, row_ptr,
+                       col_idx, weights, static_cast<const char *>(rows), row_bytes, valid_positions, epi);
+    return check_launch();
+}
+
+template <typename T, int V, int WM, class Epilogue>
+static int launch_spmm_groups(int groups, const bigcn_plan *plan, const int64_t *row_ptr,
+                              const int32_t *col_idx, const float *weights, const void *rows,
+                              int64_t row_bytes, int valid_positions, const Epilogue &epi,
+                              hipStream_t stream)
+{
+#define BIGCN_SPMM_CASE(GG)                                                                          \
+    case GG:                                                                                         \
+        return launch_spmm_one<T, GG, V, WM>(plan, row_ptr, col_idx, weights, rows, row_bytes,      \
+                                             valid_positions, epi, stream)
+    switch (groups) {
+        BIGCN_SPMM_CASE(2);
+        BIGCN_SPMM_CASE(4);
+        BIGCN_SPMM_CASE(8);
+        BIGCN_SPMM_CASE(16);
+        BIGCN_SPMM_CASE(32);
+        BIGCN_SPMM_CASE(64);
+    default:
+        return BIGCN_EINVAL;
+    }
+#undef BIGCN_SPMM_CASE
+}
+
+static int groups_for(int64_t positions, int vec)
+{
+    int g = 2;
+    while (g < 64 && static_cast<int64_t>(g) * vec < positions) g <<= 1;
+    return g;
+}
+
+RowLayout choose_layout(int64_t d_in, int64_t d_out)
+{
+    RowLayout l;
+    l.vec = d_out > 256 ? 8 : 4;
+    l.groups = groups_for(d_out, l.vec);
+    l.half = d_in <= 2048 ? 1 : 0;      // |c| <= d_in: every integer up to 2048 is exact in fp16
+    return l;
+}
+
+int launch_fused_spmm(const FusedSpmmArgs &a, hipStream_t stream)
+{
+    EpilogueFused epi{a.dinv_sqrt, a.alpha, static_cast<int>(a.d_out), a.logits, a.ld_logits,
+                      a.next_shift, a.next_mul, a.next_bits, a.next_ld_words, a.next_scale};
+    const RowLayout &l = a.layout;
+    const int valid = l.positions();
+    const int64_t rb = l.row_bytes();
+    if (l.half) {
+        if (l.vec == 8)
+            return launch_spmm_groups<__half, 8, kWeightGather>(l.groups, a.plan, a.row_ptr, a.col_idx,
+                                                                a.src_scale, a.c_rows, rb, valid, epi, stream);
+        return launch_spmm_groups<__half, 4, kWeightGather>(l.groups, a.plan, a.row_ptr, a.col_idx,
+                                                            a.src_scale, a.c_rows, rb, valid, epi, stream);
+    }
+    if (l.vec == 8)
+        return launch_spmm_groups<float, 8, kWeightGather>(l.groups, a.plan, a.row_ptr, a.col_idx,
+                                                           a.src_scale, a.c_rows, rb, valid, epi, stream);
+    return launch_spmm_groups<float, 4, kWeightGather>(l.groups, a.plan, a.row_ptr, a.col_idx,
+                                                       a.src_scale, a.c_rows, rb, valid, epi, stream);
+}
+
+}  // namespace bigcn
+
+using namespace bigcn;
+
+extern "C" int bigcn_spmm(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                          const float *vals, int64_t n, const float *z, int64_t d, int64_t ld_z,
+                          float *out, int64_t ld_out, void *stream)
+{
+    if (plan == nullptr || row_ptr == nullptr || col_idx == nullptr || z == nullptr || out == nullptr)
+        return BIGCN_ENULL;
+    if (n != plan->n || d <= 0 || ld_z < d || ld_out < d) return BIGCN_EINVAL;
+    if (n == 0) return BIGCN_OK;
+    hipStream_t s = as_stream(stream);
+    // 16-byte loads need aligned rows of a multiple of four columns; otherwise one float per lane
+    const bool vec4 = (d % 4 == 0) && (ld_z % 4 == 0) && (reinterpret_cast<uintptr_t>(z) % 16 == 0);
+    const bool vec_store = (ld_out % 4 == 0) && (reinterpret_cast<uintptr_t>(out) % 16 == 0);
+    const int64_t pass_cols = vec4 ? 256 : 64;
+    for (int64_t c0 = 0; c0 < d; c0 += pass_cols) {
+        const int64_t dc = d - c0 < pass_cols ? d - c0 : pass_cols;
+        EpiloguePlain epi{out + c0, ld_out, static_cast<int>(dc), vec_store ? 1 : 0};
+        const void *rows = z + c0;
+        int rc;
+        if (vec4) {
+            const int g = groups_for(dc, 4);
+            rc = vals != nullptr
+                     ? launch_spmm_groups<float, 4, kWeightVals>(g, plan, row_ptr, col_idx, vals, rows, ld_z * 4,
+                                                                 static_cast<int>(dc), epi, s)
+                     : launch_spmm_groups<float, 4, kWeightOne>(g, plan, row_ptr, col_idx, nullptr, rows, ld_z * 4,
+                                                                static_cast<int>(dc), epi, s);
+        } else {
+            const int g = groups_for(dc, 1);
+            rc = vals != nullptr
+                     ? launch_spmm_groups<float, 1, kWeightVals>(g, plan, row_ptr, col_idx, vals, rows, ld_z * 4,
+                                                                 static_cast<int>(dc), epi, s)
+                     : launch_spmm_groups<float, 1, kWeightOne>(g, plan, row_ptr, col_idx, nullptr, rows, ld_z * 4,
+                                                                static_cast<int>(dc), epi, s);
+        }
+        if (rc != BIGCN_OK) return rc;
+    }
+    return BIGCN_OK;
+}

@@ -1,0 +1,104 @@
+"""Shared pieces of the GPU parity tests: tolerance, device upload, and the protocol that
+compares a multi-layer forward when fp32 rounding may legitimately flip a sign bit."""
+from __future__ import annotations
+
+import numpy as np
+
+REL_TOL = 1e-5      # fp32 outputs: |gpu - ref| <= REL_TOL * |ref| + ABS_TOL
+ABS_TOL = 1e-6
+
+
+def close(gpu: np.ndarray, ref: np.ndarray):
+    """Boolean mask of elements within tolerance of the fp64 reference."""
+    ref = np.asarray(ref, dtype=np.float64)
+    gpu = np.asarray(gpu, dtype=np.float64)
+    return np.abs(gpu - ref) <= REL_TOL * np.abs(ref) + ABS_TOL
+
+
+def assert_close(gpu, ref, what=""):
+    ok = close(gpu, ref)
+    if not ok.all():
+        bad = np.argwhere(~ok)
+        i = tuple(bad[0])
+        raise AssertionError(f"{what}: {bad.shape[0]} of {ok.size} elements out of tolerance; "
+                             f"first at {i}: gpu={np.asarray(gpu)[i]!r} ref={np.asarray(ref)[i]!r}")
+
+
+def to_device(*arrays):
+    import torch
+    out = []
+    for a in arrays:
+        out.append(None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda())
+    return out if len(out) > 1 else out[0]
+
+
+def words_to_numpy(bits) -> np.ndarray:
+    """int64 device tensor of packed words -> uint64 numpy array."""
+    return bits.cpu().numpy().view(np.uint64)
+
+
+def neighbours_closed(row_ptr: np.ndarray, col_idx: np.ndarray, rows_mask: np.ndarray) -> np.ndarray:
+    """Mask of nodes that have a marked node in their closed neighbourhood (the pattern holds
+    the self-loop, so this is one hop over the stored entries)."""
+    marked_entry = rows_mask[col_idx]
+    counts = np.add.reduceat(marked_entry.astype(np.int64), row_ptr[:-1].clip(max=max(col_idx.size - 1, 0)))
+    counts[np.diff(row_ptr) == 0] = 0
+    return counts > 0
+
+
+def sign_error_bound(row_ptr, col_idx, a_tilde, zeta) -> np.ndarray:
+    """Bound on |fp32 result - exact result| of sum_k a_ik zeta_kj evaluated in fp32 in any
+    order: (terms + 4) * 2^-24 * sum_k |a_ik zeta_kj|.  Elements whose distance to the sign
+    threshold is below this bound may legitimately come out with either sign."""
+    import oracle
+    mag = oracle.aggregate(row_ptr, col_idx, a_tilde, np.abs(zeta))
+    terms = np.diff(row_ptr).astype(np.float64)[:, None]
+    return (terms + 4.0) * 2.0 ** -24 * mag
+
+
+def compare_forward_layerwise(work, bn, run_gpu_prefix):
+    """Layer-by-layer parity of the fused forward against the oracle.
+
+    ``run_gpu_prefix(l)`` must return the GPU result of the first ``l`` layers (fp32 H^(l),
+    numpy).  Every H^(l) is compared with the oracle's on all rows whose inputs were identical on
+    both sides.  Where the GPU's fp32 value of a hidden activation falls on the other side of its
+    threshold than the oracle's, the element must lie within the fp32 error bound of the
+    threshold (both signs are then valid results); such rows, and the rows they feed, are left
+    out of the comparison of later layers.  Returns per-layer statistics.
+    """
+    import oracle
+    n_layers = len(work.weights)
+    logits, recs = oracle.forward(work.row_ptr, work.col_idx, work.x, work.weights, bn=bn,
+                                  keep_trace=True)
+    a_tilde = oracle.gcn_norm(work.row_ptr, work.col_idx)
+    tainted = np.zeros(work.n, dtype=bool)
+    stats = []
+    for l in range(1, n_layers + 1):
+        ref = recs[l - 1]["out"]
+        gpu = run_gpu_prefix(l)
+        assert gpu.shape == ref.shape
+        ok = close(gpu, ref)
+        clean = ~tainted
+        if not ok[clean].all():
+            bad = np.argwhere(~ok & clean[:, None])
+            i = tuple(bad[0])
+            raise AssertionError(f"layer {l}: {bad.shape[0]} elements out of tolerance on rows with "
+                                 f"identical inputs; first at {i}: gpu={gpu[i]!r} ref={ref[i]!r}")
+        flips_rows = np.zeros(work.n, dtype=bool)
+        n_flips = 0
+        if l < n_layers:
+            shift = recs[l]["shift"]
+            th = np.zeros(ref.shape[1], dtype=np.float32) if shift is None else shift
+            gpu_sign = gpu >= th[None, :]
+            ref_sign = recs[l]["sign"] > 0
+            flips = gpu_sign != ref_sign
+            bound = sign_error_bound(work.row_ptr, work.col_idx, a_tilde, recs[l - 1]["zeta"])
+            margin = np.abs(ref - th[None, :].astype(np.float64))
+            illegal = flips & clean[:, None] & (margin > bound + 1e-30)
+            assert not illegal.any(), (f"layer {l}: {int(illegal.sum())} sign bits differ from the "
+                                       f"oracle outside the fp32 error bound")
+            flips_rows = flips.any(axis=1)
+            n_flips = int((flips & clean[:, None]).sum())
+        stats.append({"layer": l, "rows_compared": int(clean.sum()), "sign_flips": n_flips})
+        tainted = neighbours_closed(work.row_ptr, work.col_idx, tainted | flips_rows) if l < n_layers else tainted
+    return stats

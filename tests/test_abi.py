@@ -1,0 +1,148 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2210_13149_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "bigcn.h")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(binding.LIBRARY),
+                                reason="libbigcn.so not built (run __graft_entry__.build())")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bigcn_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_four_north_star_entry_points():
+    names = _declared_functions()
+    for required in ("bigcn_pack", "bigcn_binary_gemm", "bigcn_spmm", "bigcn_forward"):
+        assert required in names
+
+
+def test_library_exports_every_declared_symbol():
+    L = binding.lib()
+    for name in _declared_functions():
+        assert hasattr(L, name), f"{name} declared in bigcn.h but not exported"
+    assert set(binding.EXPORTS) == set(_declared_functions())
+
+
+def test_version_and_status_strings():
+    assert binding.version() >= 100
+    seen = set()
+    for code in range(0, -7, -1):
+        s = binding.status_string(code)
+        assert s and s != "unknown status" and s not in seen
+        seen.add(s)
+    assert binding.status_string(-99) == "unknown status"
+    assert binding.status_string(0) == "ok"
+
+
+FAKE = 0x1000  # a non-NULL address that is never dereferenced: argument checks come first
+
+
+def test_pack_rejects_bad_arguments():
+    L = binding.lib()
+    assert L.bigcn_pack(None, 4, 8, 8, 1, None, None, FAKE, 1, FAKE, None) == binding.BIGCN_ENULL
+    assert L.bigcn_pack(FAKE, 4, 8, 8, 1, None, None, None, 1, FAKE, None) == binding.BIGCN_ENULL
+    assert L.bigcn_pack(FAKE, 4, 8, 8, 1, None, None, FAKE, 1, None, None) == binding.BIGCN_ENULL
+    assert L.bigcn_pack(FAKE, -1, 8, 8, 1, None, None, FAKE, 1, FAKE, None) == binding.BIGCN_EINVAL
+    assert L.bigcn_pack(FAKE, 4, 0, 8, 1, None, None, FAKE, 1, FAKE, None) == binding.BIGCN_EINVAL
+    assert L.bigcn_pack(FAKE, 4, 8, 0, 1, None, None, FAKE, 1, FAKE, None) == binding.BIGCN_EINVAL
+    assert L.bigcn_pack(FAKE, 4, 65, 65, 1, None, None, FAKE, 1, FAKE, None) == binding.BIGCN_EINVAL
+    assert L.bigcn_pack(FAKE, 0, 8, 8, 1, None, None, FAKE, 1, FAKE, None) == binding.BIGCN_OK
+
+
+def test_binary_gemm_rejects_bad_arguments():
+    L = binding.lib()
+    ok = dict(a=FAKE, sa=FAKE, m=4, lda=2, b=FAKE, sb=FAKE, n=3, ldb=2, k=100, acc=FAKE, ldacc=3,
+              out=FAKE, ldout=3)
+
+    def call(**kw):
+        p = dict(ok, **kw)
+        return L.bigcn_binary_gemm(p["a"], p["sa"], p["m"], p["lda"], p["b"], p["sb"], p["n"], p["ldb"],
+                                   p["k"], p["acc"], p["ldacc"], p["out"], p["ldout"], None)
+
+    assert call(a=None) == binding.BIGCN_ENULL
+    assert call(b=None) == binding.BIGCN_ENULL
+    assert call(acc=None, out=None) == binding.BIGCN_ENULL
+    assert call(sa=None) == binding.BIGCN_ENULL
+    assert call(sb=None) == binding.BIGCN_ENULL
+    assert call(m=-1) == binding.BIGCN_EINVAL
+    assert call(k=0) == binding.BIGCN_EINVAL
+    assert call(lda=1) == binding.BIGCN_EINVAL
+    assert call(ldb=1) == binding.BIGCN_EINVAL
+    assert call(ldacc=2) == binding.BIGCN_EINVAL
+    assert call(ldout=2) == binding.BIGCN_EINVAL
+    assert call(k=binding.MAX_K_BITS + 1, lda=200, ldb=200) == binding.BIGCN_ESHAPE
+    assert call(m=0) == binding.BIGCN_OK
+    assert call(n=0, ldacc=0, ldout=0) == binding.BIGCN_OK
+
+
+def test_graph_entry_points_reject_bad_arguments():
+    L = binding.lib()
+    assert L.bigcn_gcn_norm(None, FAKE, 4, FAKE, None, None) == binding.BIGCN_ENULL
+    assert L.bigcn_gcn_norm(FAKE, FAKE, 4, None, None, None) == binding.BIGCN_ENULL
+    assert L.bigcn_gcn_norm(FAKE, None, 4, FAKE, FAKE, None) == binding.BIGCN_ENULL
+    assert L.bigcn_gcn_norm(FAKE, FAKE, -4, FAKE, None, None) == binding.BIGCN_EINVAL
+    assert L.bigcn_gcn_norm(FAKE, FAKE, 0, FAKE, None, None) == binding.BIGCN_OK
+    handle = ctypes.c_void_p()
+    assert L.bigcn_plan_create(None, FAKE, 4, 1, ctypes.byref(handle), None) == binding.BIGCN_ENULL
+    assert L.bigcn_plan_create(FAKE, FAKE, 4, 1, None, None) == binding.BIGCN_ENULL
+    assert L.bigcn_plan_create(FAKE, FAKE, -1, 1, ctypes.byref(handle), None) == binding.BIGCN_EINVAL
+    assert L.bigcn_plan_create(FAKE, FAKE, 1 << 31, 1, ctypes.byref(handle), None) == binding.BIGCN_EINVAL
+    assert handle.value is None
+    L.bigcn_plan_destroy(None)
+    assert L.bigcn_plan_rows(None) == -1 and L.bigcn_plan_nnz(None) == -1
+    assert L.bigcn_spmm(None, FAKE, FAKE, None, 4, FAKE, 8, 8, FAKE, 8, None) == binding.BIGCN_ENULL
+
+
+def _layers(dims, ld=None):
+    arr = (binding.LayerDesc * (len(dims) - 1))()
+    for l in range(len(dims) - 1):
+        arr[l] = binding.LayerDesc(FAKE, FAKE, dims[l], dims[l + 1],
+                                   (dims[l] + 63) // 64 if ld is None else ld, None, None)
+    return arr
+
+
+def test_forward_workspace_size_and_argument_checks():
+    L = binding.lib()
+    n = 1000
+    layers = _layers((100, 256, 256, 47))
+    need = L.bigcn_forward_workspace_bytes(n, layers, 3)
+    # packed signs (4 words), two scale vectors, and 256 fp16 products per node
+    assert need >= n * (4 * 8 + 2 * 4 + 256 * 2)
+    assert need <= n * (4 * 8 + 2 * 4 + 256 * 2) + 4 * 256
+    wide = L.bigcn_forward_workspace_bytes(n, _layers((3703, 64, 6)), 2)
+    assert wide >= n * (58 * 8 + 8 + 64 * 4)          # K > 2048: products kept in fp32
+    assert L.bigcn_forward_workspace_bytes(n, None, 3) == 0
+    assert L.bigcn_forward_workspace_bytes(n, _layers((100, 64, 32)), 0) == 0
+    bad_chain = _layers((100, 64, 7))
+    bad_chain[1].d_in = 65
+    assert L.bigcn_forward_workspace_bytes(n, bad_chain, 2) == 0
+    assert L.bigcn_forward_workspace_bytes(n, _layers((100, 513, 7)), 2) == 0
+    assert L.bigcn_forward_workspace_bytes(n, _layers((100, 64, 7), ld=1), 2) == 0
+
+    def fwd(plan=FAKE, rp=FAKE, ci=FAKE, dinv=FAKE, x=FAKE, lay=layers, nl=3, logits=FAKE):
+        return L.bigcn_forward(plan, rp, ci, dinv, n, x, 100, lay, nl, logits, 47, FAKE, need, None)
+
+    assert fwd(plan=None) == binding.BIGCN_ENULL
+    assert fwd(x=None) == binding.BIGCN_ENULL
+    assert fwd(logits=None) == binding.BIGCN_ENULL
+    assert fwd(lay=None) == binding.BIGCN_ENULL
+    assert fwd(nl=0) == binding.BIGCN_EINVAL
+    assert fwd(lay=_layers((100, 513, 47)), nl=2) == binding.BIGCN_ESHAPE
+    assert fwd(lay=_layers((9000, 64, 47), ld=200), nl=2) == binding.BIGCN_ESHAPE
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    with pytest.raises(TypeError):
+        binding.bigcn_pack(torch.zeros(2, 3))

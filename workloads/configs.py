@@ -59,8 +59,8 @@ def get_config(name: str) -> WorkloadConfig:
 
 
 def scaled_config(name: str, n_nodes: int) -> WorkloadConfig:
-    """The same recipe on fewer nodes: mean degree, dims, feature law and the shape of
-    the degree sequence are kept; the edge count shrinks with the node count."""
+    """The same recipe on fewer nodes: mean degree, dims, feature law and the head of the
+    power-law weight sequence (gamma, i0) are kept; the edge count shrinks with the node count."""
     cfg = get_config(name)
     if n_nodes >= cfg.n_nodes:
         return cfg
@@ -68,5 +68,4 @@ def scaled_config(name: str, n_nodes: int) -> WorkloadConfig:
     n_edges = max(1, int(round(cfg.n_edges * ratio)))
     # a simple graph on n nodes holds at most n(n-1)/2 edges; stay well below that
     n_edges = min(n_edges, n_nodes * (n_nodes - 1) // 4)
-    return replace(cfg, name=f"{cfg.name}@{n_nodes}", n_nodes=n_nodes, n_edges=n_edges,
-                   i0=max(1.0, cfg.i0 * ratio))
+    return replace(cfg, name=f"{cfg.name}@{n_nodes}", n_nodes=n_nodes, n_edges=n_edges)

@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused Bi-GCN forward on one MI355X.
+
+A "step" is one pass of the whole hot path (binarise+pack of X, then per layer bit-GEMM and
+fused aggregation) over one seeded synthetic graph, with every input already resident in
+HBM.  The default workload is the largest of the five (the OGBN-Products-shaped one), on which
+the aggregation's bandwidth target is stated.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1..c5]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+VALU_BINARY_MAC_PEAK = 256 * 4 * 16 * 2.4e9 * 32 / 2   # 2 VALU instructions per 32 binary MACs
+
+# HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc (FETCH_SIZE and
+# WRITE_SIZE, scaled by a copy kernel of known size); see profiles/.  None = not measured.
+MEASURED_TRAFFIC_BYTES = {"c5": 7.95e10}    # profiles/spmm_fused_c5.md
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def standardisation(t, eps=1e-5):
+    """Frozen per-column (shift, mul) from a device matrix (plumbing: the parameters are inputs
+    of the forward pass, like running statistics)."""
+    import torch
+    var, mean = torch.var_mean(t.double(), dim=0, unbiased=False)
+    return mean.float().contiguous(), (1.0 / torch.sqrt(var + eps)).float().contiguous()
+
+
+def build_model(work, B):
+    """Upload the workload, pack the weights and calibrate the standardisation of every layer
+    that has one with the library's own forward (untimed set-up)."""
+    import numpy as np
+    import torch
+    cfg = work.config
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    drp, dci, dx = dev(work.row_ptr), dev(work.col_idx), dev(work.x)
+    weights = [dev(w) for w in work.weights]
+    plan = B.Plan(drp, dci, validate=True)
+    dinv, _ = B.bigcn_gcn_norm(drp, dci)
+    layers = []
+    for l, w in enumerate(weights):
+        use_bn = l == 0 or cfg.bn_layers == "all"
+        shift = mul = None
+        if use_bn:
+            if l == 0:
+                shift, mul = standardisation(dx)
+            else:
+                h = B.bigcn_forward(plan, drp, dci, dinv, dx, layers)
+                shift, mul = standardisation(h)
+                del h
+        layers.append(B.Layer.from_weight(w, shift, mul))
+    need = B.bigcn_forward_workspace_bytes(work.n, layers)
+    workspace = torch.empty((need,), dtype=torch.uint8, device="cuda")
+    logits = torch.empty((work.n, layers[-1].d_out), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    return dict(plan=plan, row_ptr=drp, col_idx=dci, dinv=dinv, x=dx, layers=layers,
+                workspace=workspace, logits=logits)
+
+
+def aggregation_bytes(cfg, nnz, layer, B):
+    """Algorithmic bytes of one launch of the fused aggregation of `layer`: per stored entry a
+    4-byte column index, a 4-byte source scale and one gathered row of integer products; per node
+    8 bytes of row pointer, 4 bytes of row order and the output (packed signs + scale, or fp32
+    logits).  Also the compulsory minimum (every array read or written exactly once)."""
+    d_in, d_out = cfg.dims[layer], cfg.dims[layer + 1]
+    vec = 8 if d_out > 256 else 4
+    groups = 2
+    while groups < 64 and groups * vec < d_out:
+        groups *= 2
+    row_bytes = groups * vec * (2 if d_in <= 2048 else 4)
+    n = cfg.n_nodes
+    last = layer == cfg.n_layers - 1
+    out_bytes = 4 * d_out if last else 8 * ((d_out + 63) // 64) + 4
+    per_node = 8 + 4 + 4 + out_bytes            # row_ptr, row order, dinv_sqrt, output
+    gather = nnz * (4 + 4 + row_bytes) + n * per_node
+    minimum = nnz * 4 + n * (4 + row_bytes) + n * per_node
+    return gather, minimum, row_bytes
+
+
+def cpu_baseline(work, target_nodes):
+    """The plain oracle, as it stands, timed on the host cores: on the benchmark's own workload,
+    or on a smaller graph of the same recipe (same mean degree, dims, feature law); nodes/s."""
+    import oracle
+    from workloads import make_workload, scaled_config
+    cfg = work.config
+    small = work if target_nodes >= work.n else make_workload(scaled_config(cfg.name, target_nodes))
+    calibrate = [True] + [cfg.bn_layers == "all"] * (cfg.n_layers - 1)
+    t0 = time.perf_counter()
+    oracle.forward(small.row_ptr, small.col_idx, small.x, small.weights, calibrate=calibrate)
+    dt = time.perf_counter() - t0
+    return {"value": small.n / dt, "unit": "nodes/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"whole {cfg.n_layers}-layer oracle forward (with its calibration passes) on "
+                      + ("the benchmark's own graph" if small is work else
+                         f"a {small.n}-node, {small.config.n_edges}-edge graph of the same recipe")
+                      + f" ({dt:.1f} s)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c5")
+    ap.add_argument("--cpu-baseline-nodes", type=int, default=-1,
+                    help="nodes in the oracle's timed sample (-1 = the whole workload, about 10 s "
+                         "of CPU work for c5 on 16 cores; 0 = skip the cpu_baseline leg)")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run one device-to-device copy kernel of this many MiB (a known "
+                         "traffic figure to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings by)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+                 "(no collectives are part of it; see DESIGN.md, 'How the path would shard').")
+
+    import torch
+    from paper_2210_13149_amd import binding as B, cost_model
+    from workloads import get_config, make_workload
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    B.lib()
+    cfg = get_config(args.workload)
+    t0 = time.perf_counter()
+    work = make_workload(cfg)
+    log(f"[bench] generated {cfg.name}: {work.n} nodes, nnz {work.nnz} in {time.perf_counter() - t0:.1f} s")
+    t0 = time.perf_counter()
+    m = build_model(work, B)
+    log(f"[bench] set-up (upload, plan, weights, calibration) {time.perf_counter() - t0:.1f} s")
+    if args.copy_probe_mib > 0:
+        src = torch.ones((args.copy_probe_mib << 18,), dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # one elementwise copy kernel: reads and writes MiB each
+        torch.cuda.synchronize()
+        log(f"[bench] copy probe: {args.copy_probe_mib} MiB read + {args.copy_probe_mib} MiB written")
+        del src, dst
+    n_layers = cfg.n_layers
+    steps, warmup = max(1, args.steps), max(0, args.warmup)
+    profile = B.Profile(n_layers, steps)
+
+    def step(prof=None):
+        B.bigcn_forward(m["plan"], m["row_ptr"], m["col_idx"], m["dinv"], m["x"], m["layers"],
+                        m["workspace"], m["logits"], prof)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(steps):
+        step(profile)
+    stop.record()
+    torch.cuda.synchronize()
+    ms_per_step = start.elapsed_time(stop) / steps
+    launch_ms, calls = profile.read()
+    assert calls == steps
+
+    nodes_per_s = work.n / (ms_per_step * 1e-3)
+    # per-kernel figures from the events recorded inside the timed region
+    gemm = []
+    spmm = []
+    for l in range(n_layers):
+        t_gemm = launch_ms[1 + 2 * l] * 1e-3
+        t_spmm = launch_ms[2 + 2 * l] * 1e-3
+        macs = work.n * cfg.dims[l] * cfg.dims[l + 1]
+        gather, minimum, row_bytes = aggregation_bytes(cfg, work.nnz, l, B)
+        gemm.append({"layer": l, "ms": t_gemm * 1e3, "binary_op_per_s": macs / t_gemm,
+                     "frac_valu_peak": macs / t_gemm / VALU_BINARY_MAC_PEAK})
+        spmm.append({"layer": l, "ms": t_spmm * 1e3, "row_bytes": row_bytes,
+                     "gather_GBps": gather / t_spmm / 1e9, "compulsory_GBps": minimum / t_spmm / 1e9})
+    # dominant kernel: the aggregation launches with the widest rows (same kernel instantiation)
+    widest = max(s["row_bytes"] for s in spmm)
+    dom = [l for l in range(n_layers) if spmm[l]["row_bytes"] == widest and l < n_layers - 1] or \
+          [max(range(n_layers), key=lambda l: spmm[l]["ms"])]
+    dom_ms = sum(spmm[l]["ms"] for l in dom) / len(dom)
+    dom_bytes = sum(aggregation_bytes(cfg, work.nnz, l, B)[0] for l in dom) / len(dom)
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get(cfg.name)
+    roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                "kernel": "spmm_kernel (fused aggregation), layers " + ",".join(str(l) for l in dom),
+                "avg_launch_ms": dom_ms, "algorithmic_bytes_per_launch": dom_bytes}
+
+    result = {
+        "metric": "Bi-GCN forward nodes/s; bit-GEMM binary-op/s; SpMM HBM GB/s (% roofline)",
+        "value": nodes_per_s, "unit": "nodes/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u64 xor/popcount + f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.stands_in_for}-shaped Chung-Lu graph, {work.n} nodes, "
+                               f"{cfg.n_edges} undirected edges (+ self-loops), dims "
+                               + "-".join(str(d) for d in cfg.dims),
+                   "layers": n_layers, "nnz": work.nnz, "standardisation": cfg.bn_layers},
+        "pack_ms": launch_ms[0],
+        "pack_GBps": (work.n * (4 * cfg.dims[0] + 8 * ((cfg.dims[0] + 63) // 64) + 4)) / (launch_ms[0] * 1e-3) / 1e9,
+        "bit_gemm": gemm, "spmm": spmm,
+        "bit_gemm_binary_op_per_s": max(g["binary_op_per_s"] for g in gemm),
+        "spmm_GBps": achieved,
+        "roofline": roofline,
+        "paper_theory": {k: v for k, v in cost_model.summary(cfg.n_nodes, cfg.n_edges, cfg.dims).items()
+                         if k.endswith("ratio")},
+    }
+    if args.cpu_baseline_nodes != 0:
+        t0 = time.perf_counter()
+        del m
+        torch.cuda.empty_cache()
+        sample = cfg.n_nodes if args.cpu_baseline_nodes < 0 else min(args.cpu_baseline_nodes, cfg.n_nodes)
+        result["cpu_baseline"] = cpu_baseline(work, sample)
+        log(f"[bench] cpu_baseline leg {time.perf_counter() - t0:.1f} s")
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

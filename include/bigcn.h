@@ -182,6 +182,30 @@ int bigcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t 
                   const bigcn_layer *layers, int n_layers, float *logits, int64_t ld_logits,
                   void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Per-launch timing of the fused forward (measurement aid; HIP events on the caller's
+ * stream).  One forward issues 1 + 2L launches: slot 0 is the binarise+pack of X
+ * (Sec. 4.2.2), slot 1 + 2l the bit-GEMM of layer l and slot 2 + 2l its aggregation
+ * (Sec. 4.2.3).  A profile holds the events of up to max_calls (<= 4096) calls.
+ *
+ * bigcn_forward_profiled is bigcn_forward plus one event record before / after every
+ * launch; it fails with BIGCN_ESHAPE once max_calls calls are pending and BIGCN_EINVAL if
+ * the profile was created for another layer count.
+ * bigcn_profile_read waits for the recorded calls to finish (it SYNCHRONISES with them),
+ * writes the mean duration of every slot in milliseconds to launch_ms (HOST, 1 + 2L
+ * floats) and the number of calls averaged to *calls (HOST, nullable), and resets the
+ * profile.  A profile must not be used from two threads at once.
+ */
+typedef struct bigcn_profile bigcn_profile;
+int bigcn_profile_create(int n_layers, int max_calls, bigcn_profile **out);
+void bigcn_profile_destroy(bigcn_profile *profile);
+int bigcn_forward_profiled(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                           const float *dinv_sqrt, int64_t n, const float *x, int64_t ld_x,
+                           const bigcn_layer *layers, int n_layers, float *logits,
+                           int64_t ld_logits, void *workspace, size_t workspace_bytes,
+                           void *stream, bigcn_profile *profile);
+int bigcn_profile_read(bigcn_profile *profile, float *launch_ms, int *calls);
+
 #ifdef __cplusplus
 }
 #endif

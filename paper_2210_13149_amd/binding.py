@@ -30,7 +30,8 @@ MAX_FORWARD_D_OUT = 512
 EXPORTS = (
     "bigcn_status_string", "bigcn_version", "bigcn_pack", "bigcn_binary_gemm", "bigcn_gcn_norm",
     "bigcn_plan_create", "bigcn_plan_destroy", "bigcn_plan_rows", "bigcn_plan_nnz", "bigcn_spmm",
-    "bigcn_forward_workspace_bytes", "bigcn_forward",
+    "bigcn_forward_workspace_bytes", "bigcn_forward", "bigcn_profile_create",
+    "bigcn_profile_destroy", "bigcn_forward_profiled", "bigcn_profile_read",
 )
 
 
@@ -87,6 +88,14 @@ def lib() -> ctypes.CDLL:
         L.bigcn_forward.restype = i32
         L.bigcn_forward.argtypes = [vp, vp, vp, vp, i64, vp, i64, ctypes.POINTER(LayerDesc), i32, vp,
                                     i64, vp, ctypes.c_size_t, vp]
+        L.bigcn_profile_create.restype = i32
+        L.bigcn_profile_create.argtypes = [i32, i32, ctypes.POINTER(vp)]
+        L.bigcn_profile_destroy.restype = None
+        L.bigcn_profile_destroy.argtypes = [vp]
+        L.bigcn_forward_profiled.restype = i32
+        L.bigcn_forward_profiled.argtypes = L.bigcn_forward.argtypes + [vp]
+        L.bigcn_profile_read.restype = i32
+        L.bigcn_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         _lib = L
     return _lib
 
@@ -274,10 +283,48 @@ def bigcn_forward_workspace_bytes(n: int, layers: Sequence[Layer]) -> int:
     return int(lib().bigcn_forward_workspace_bytes(int(n), _descs(layers), len(layers)))
 
 
+class Profile:
+    """Owner of a ``bigcn_profile``: per-launch HIP-event timing of forward calls."""
+
+    def __init__(self, n_layers: int, max_calls: int):
+        self.n_layers = int(n_layers)
+        handle = ctypes.c_void_p()
+        self._handle = None
+        _check(lib().bigcn_profile_create(self.n_layers, int(max_calls), ctypes.byref(handle)),
+               "bigcn_profile_create")
+        self._handle = handle
+
+    @property
+    def handle(self):
+        if self._handle is None:
+            raise RuntimeError("profile was destroyed")
+        return self._handle
+
+    def read(self) -> Tuple[List[float], int]:
+        """Mean milliseconds per launch slot over the calls since the last read, and that count."""
+        ms = (ctypes.c_float * (1 + 2 * self.n_layers))()
+        calls = ctypes.c_int(0)
+        _check(lib().bigcn_profile_read(self.handle, ms, ctypes.byref(calls)), "bigcn_profile_read")
+        return [float(v) for v in ms], int(calls.value)
+
+    def destroy(self) -> None:
+        if self._handle is not None:
+            lib().bigcn_profile_destroy(self._handle)
+            self._handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
 def bigcn_forward(plan: Plan, row_ptr: torch.Tensor, col_idx: torch.Tensor, dinv_sqrt: torch.Tensor,
                   x: torch.Tensor, layers: Sequence[Layer], workspace: Optional[torch.Tensor] = None,
-                  logits: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """L-layer fused forward; returns fp32 logits (n, d_out of the last layer)."""
+                  logits: Optional[torch.Tensor] = None, profile: Optional[Profile] = None
+                  ) -> torch.Tensor:
+    """L-layer fused forward; returns fp32 logits (n, d_out of the last layer).  With
+    ``profile`` the call goes through ``bigcn_forward_profiled``."""
     _dev(x, torch.float32, "x")
     if x.dim() != 2 or (x.shape[1] > 1 and x.stride(1) != 1):
         raise ValueError("x must be a row-major matrix")
@@ -288,9 +335,12 @@ def bigcn_forward(plan: Plan, row_ptr: torch.Tensor, col_idx: torch.Tensor, dinv
         workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=x.device)
     if logits is None:
         logits = torch.empty((n, layers[-1].d_out), dtype=torch.float32, device=x.device)
-    _check(lib().bigcn_forward(plan.handle, _ptr(row_ptr), _ptr(col_idx), _ptr(dinv_sqrt), n, _ptr(x),
-                               x.stride(0), descs, len(layers), _ptr(logits), logits.stride(0),
-                               _ptr(workspace), workspace.numel(), _stream()), "bigcn_forward")
+    args = (plan.handle, _ptr(row_ptr), _ptr(col_idx), _ptr(dinv_sqrt), n, _ptr(x), x.stride(0), descs,
+            len(layers), _ptr(logits), logits.stride(0), _ptr(workspace), workspace.numel(), _stream())
+    if profile is None:
+        _check(lib().bigcn_forward(*args), "bigcn_forward")
+    else:
+        _check(lib().bigcn_forward_profiled(*args, profile.handle), "bigcn_forward_profiled")
     return logits
 
 
@@ -314,6 +364,6 @@ class BiGCN:
         self.logits = torch.empty((self.n, self.layers[-1].d_out), dtype=torch.float32,
                                   device=row_ptr.device)
 
-    def forward(self, x: torch.Tensor) -> torch.Tensor:
+    def forward(self, x: torch.Tensor, profile: Optional[Profile] = None) -> torch.Tensor:
         return bigcn_forward(self.plan, self.row_ptr, self.col_idx, self.dinv_sqrt, x, self.layers,
-                             self.workspace, self.logits)
+                             self.workspace, self.logits, profile)

@@ -6,6 +6,7 @@
 // scaling and emits either the next layer's packed signs and scales or the final logits.
 // Only the first layer needs a separate binarise+pack pass over the fp32 features.
 #include <algorithm>
+#include <new>
 
 #include "bigcn_internal.h"
 
@@ -51,6 +52,16 @@ static WorkspaceMap map_workspace(int64_t n, const bigcn_layer *layers, int n_la
 
 }  // namespace bigcn
 
+// Per-launch timing of forward passes: (1 + 2 L) launches per call bracketed by (2 + 2 L)
+// events, for up to max_calls calls between two reads.
+struct bigcn_profile {
+    int n_layers;
+    int max_calls;
+    int calls;
+    hipEvent_t *events;      // max_calls * (2 + 2 * n_layers)
+    int per_call() const { return 2 + 2 * n_layers; }
+};
+
 using namespace bigcn;
 
 extern "C" const char *bigcn_status_string(int status)
@@ -76,10 +87,10 @@ extern "C" size_t bigcn_forward_workspace_bytes(int64_t n, const bigcn_layer *la
     return map_workspace(n, layers, n_layers).total;
 }
 
-extern "C" int bigcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
-                             const float *dinv_sqrt, int64_t n, const float *x, int64_t ld_x,
-                             const bigcn_layer *layers, int n_layers, float *logits,
-                             int64_t ld_logits, void *workspace, size_t workspace_bytes, void *stream)
+static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                        const float *dinv_sqrt, int64_t n, const float *x, int64_t ld_x,
+                        const bigcn_layer *layers, int n_layers, float *logits, int64_t ld_logits,
+                        void *workspace, size_t workspace_bytes, void *stream, bigcn_profile *prof)
 {
     if (plan == nullptr || row_ptr == nullptr || col_idx == nullptr || dinv_sqrt == nullptr ||
         x == nullptr || logits == nullptr)
@@ -91,8 +102,16 @@ extern "C" int bigcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, con
     if (n == 0) return BIGCN_OK;
     if (workspace == nullptr || workspace_bytes < map.total || reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
         return BIGCN_EWORKSPACE;
+    hipEvent_t *ev = nullptr;
+    if (prof != nullptr) {
+        if (prof->n_layers != n_layers) return BIGCN_EINVAL;
+        if (prof->calls >= prof->max_calls) return BIGCN_ESHAPE;
+        ev = prof->events + static_cast<size_t>(prof->calls) * prof->per_call();
+        prof->calls++;
+    }
 
     hipStream_t s = as_stream(stream);
+#define BIGCN_MARK() do { if (ev != nullptr && hipEventRecord(*ev++, s) != hipSuccess) return BIGCN_EHIP; } while (0)
     char *ws = static_cast<char *>(workspace);
     uint64_t *bits = reinterpret_cast<uint64_t *>(ws + map.bits_off);
     float *scale[2] = {reinterpret_cast<float *>(ws + map.scale0_off), reinterpret_cast<float *>(ws + map.scale1_off)};
@@ -100,15 +119,18 @@ extern "C" int bigcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, con
 
     // layer 0 input: binarise X; the stored scale is dinv_sqrt[i] * beta_i
     int64_t words = (layers[0].d_in + 63) / 64;
+    BIGCN_MARK();
     int rc = launch_pack(x, n, layers[0].d_in, ld_x, 1, layers[0].bn_shift, layers[0].bn_mul, dinv_sqrt,
                          bits, words, scale[0], s);
     if (rc != BIGCN_OK) return rc;
+    BIGCN_MARK();
 
     for (int l = 0; l < n_layers; ++l) {
         const bigcn_layer &L = layers[l];
         const RowLayout layout = choose_layout(L.d_in, L.d_out);
         rc = launch_bitgemm_layout(bits, n, words, L.w_bits, L.d_out, L.ld_words, L.d_in, c_rows, layout, s);
         if (rc != BIGCN_OK) return rc;
+        BIGCN_MARK();
 
         FusedSpmmArgs a{};
         a.plan = plan;
@@ -133,6 +155,82 @@ extern "C" int bigcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, con
         }
         rc = launch_fused_spmm(a, s);
         if (rc != BIGCN_OK) return rc;
+        BIGCN_MARK();
     }
+#undef BIGCN_MARK
+    return BIGCN_OK;
+}
+
+extern "C" int bigcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                             const float *dinv_sqrt, int64_t n, const float *x, int64_t ld_x,
+                             const bigcn_layer *layers, int n_layers, float *logits,
+                             int64_t ld_logits, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return forward_impl(plan, row_ptr, col_idx, dinv_sqrt, n, x, ld_x, layers, n_layers, logits,
+                        ld_logits, workspace, workspace_bytes, stream, nullptr);
+}
+
+extern "C" int bigcn_forward_profiled(const bigcn_plan *plan, const int64_t *row_ptr,
+                                      const int32_t *col_idx, const float *dinv_sqrt, int64_t n,
+                                      const float *x, int64_t ld_x, const bigcn_layer *layers,
+                                      int n_layers, float *logits, int64_t ld_logits, void *workspace,
+                                      size_t workspace_bytes, void *stream, bigcn_profile *profile)
+{
+    if (profile == nullptr) return BIGCN_ENULL;
+    return forward_impl(plan, row_ptr, col_idx, dinv_sqrt, n, x, ld_x, layers, n_layers, logits,
+                        ld_logits, workspace, workspace_bytes, stream, profile);
+}
+
+extern "C" int bigcn_profile_create(int n_layers, int max_calls, bigcn_profile **out)
+{
+    if (out == nullptr) return BIGCN_ENULL;
+    if (n_layers <= 0 || max_calls <= 0 || max_calls > 4096) return BIGCN_EINVAL;
+    bigcn_profile *p = new (std::nothrow) bigcn_profile();
+    if (p == nullptr) return BIGCN_EHIP;
+    p->n_layers = n_layers;
+    p->max_calls = max_calls;
+    p->calls = 0;
+    const size_t count = static_cast<size_t>(max_calls) * p->per_call();
+    p->events = new (std::nothrow) hipEvent_t[count];
+    if (p->events == nullptr) { delete p; return BIGCN_EHIP; }
+    for (size_t i = 0; i < count; ++i) {
+        if (hipEventCreate(&p->events[i]) != hipSuccess) {
+            for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(p->events[j]);
+            delete[] p->events;
+            delete p;
+            return BIGCN_EHIP;
+        }
+    }
+    *out = p;
+    return BIGCN_OK;
+}
+
+extern "C" void bigcn_profile_destroy(bigcn_profile *profile)
+{
+    if (profile == nullptr) return;
+    const size_t count = static_cast<size_t>(profile->max_calls) * profile->per_call();
+    for (size_t i = 0; i < count; ++i) (void)hipEventDestroy(profile->events[i]);
+    delete[] profile->events;
+    delete profile;
+}
+
+extern "C" int bigcn_profile_read(bigcn_profile *profile, float *launch_ms, int *calls)
+{
+    if (profile == nullptr || launch_ms == nullptr) return BIGCN_ENULL;
+    const int slots = 1 + 2 * profile->n_layers;
+    for (int k = 0; k < slots; ++k) launch_ms[k] = 0.0f;
+    for (int c = 0; c < profile->calls; ++c) {
+        hipEvent_t *ev = profile->events + static_cast<size_t>(c) * profile->per_call();
+        if (hipEventSynchronize(ev[slots]) != hipSuccess) return BIGCN_EHIP;
+        for (int k = 0; k < slots; ++k) {
+            float ms = 0.0f;
+            if (hipEventElapsedTime(&ms, ev[k], ev[k + 1]) != hipSuccess) return BIGCN_EHIP;
+            launch_ms[k] += ms;
+        }
+    }
+    if (profile->calls > 0)
+        for (int k = 0; k < slots; ++k) launch_ms[k] /= static_cast<float>(profile->calls);
+    if (calls != nullptr) *calls = profile->calls;
+    profile->calls = 0;
     return BIGCN_OK;
 }

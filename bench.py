@@ -73,21 +73,19 @@ def build_model(work, B):
 
 def aggregation_bytes(cfg, nnz, layer, B):
     """Algorithmic bytes of one launch of the fused aggregation of `layer`: per stored entry a
-    4-byte column index, a 4-byte source scale and one gathered row of integer products; per node
-    8 bytes of row pointer, 4 bytes of row order and the output (packed signs + scale, or fp32
-    logits).  Also the compulsory minimum (every array read or written exactly once)."""
+    4-byte column index, one gathered row of integer products and (unless the row carries it) a
+    4-byte source scale; per node 8 bytes of row pointer, 4 bytes of row order, 4 bytes of
+    dinv_sqrt and the output (packed signs + scale, or fp32 logits).  Also the compulsory minimum
+    (every array read or written exactly once)."""
     d_in, d_out = cfg.dims[layer], cfg.dims[layer + 1]
-    vec = 8 if d_out > 256 else 4
-    groups = 2
-    while groups < 64 and groups * vec < d_out:
-        groups *= 2
-    row_bytes = groups * vec * (2 if d_in <= 2048 else 4)
+    row_bytes, embedded = B.bigcn_forward_row_bytes(d_in, d_out)
+    scale_bytes = 0 if embedded else 4
     n = cfg.n_nodes
     last = layer == cfg.n_layers - 1
     out_bytes = 4 * d_out if last else 8 * ((d_out + 63) // 64) + 4
-    per_node = 8 + 4 + 4 + out_bytes            # row_ptr, row order, dinv_sqrt, output
-    gather = nnz * (4 + 4 + row_bytes) + n * per_node
-    minimum = nnz * 4 + n * (4 + row_bytes) + n * per_node
+    per_node = 8 + 4 + 4 + out_bytes
+    gather = nnz * (4 + scale_bytes + row_bytes) + n * per_node
+    minimum = nnz * 4 + n * (scale_bytes + row_bytes) + n * per_node
     return gather, minimum, row_bytes
 
 

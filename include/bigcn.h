@@ -53,6 +53,7 @@ int bigcn_version(void);
 /* Largest supported inner dimension (bits) of bigcn_binary_gemm / a layer's d_in, and
  * largest d_out of a layer of bigcn_forward. */
 #define BIGCN_MAX_K_BITS 8192
+#define BIGCN_MAX_GEMM_N 4194304
 #define BIGCN_MAX_FORWARD_D_OUT 512
 
 /*
@@ -87,7 +88,7 @@ int bigcn_pack(const float *x, int64_t rows, int64_t cols, int64_t row_stride,
  * At least one of acc / out must be given; a_scale and b_scale are required iff out is.
  * Pad bits (positions >= k_bits) must be equal in both operands (bigcn_pack writes 0).
  * Errors: ENULL, EINVAL (negative sizes, k_bits <= 0, leading dimensions too small),
- * ESHAPE (k_bits > BIGCN_MAX_K_BITS).  m == 0 or n == 0 is a no-op.
+ * ESHAPE (k_bits > BIGCN_MAX_K_BITS or n > BIGCN_MAX_GEMM_N).  m == 0 or n == 0 is a no-op.
  */
 int bigcn_binary_gemm(const uint64_t *a_bits, const float *a_scale, int64_t m,
                       int64_t lda_words, const uint64_t *b_bits, const float *b_scale,
@@ -177,6 +178,11 @@ typedef struct {
  * EWORKSPACE.  bigcn_forward_workspace_bytes returns 0 for invalid arguments.
  */
 size_t bigcn_forward_workspace_bytes(int64_t n, const bigcn_layer *layers, int n_layers);
+/* Bytes of the compact row of integer products (Sec. 4.2.3, F_i (*) B_j for all j) that the
+ * fused forward keeps per node for a layer with d_in input bits and d_out columns, and
+ * whether the node's source scale is stored inside that row (*scale_embedded, HOST,
+ * nullable).  Used to size the aggregation's gather traffic; 0 for unsupported shapes. */
+int64_t bigcn_forward_row_bytes(int64_t d_in, int64_t d_out, int *scale_embedded);
 int bigcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
                   const float *dinv_sqrt, int64_t n, const float *x, int64_t ld_x,
                   const bigcn_layer *layers, int n_layers, float *logits, int64_t ld_logits,

@@ -30,7 +30,7 @@ MAX_FORWARD_D_OUT = 512
 EXPORTS = (
     "bigcn_status_string", "bigcn_version", "bigcn_pack", "bigcn_binary_gemm", "bigcn_gcn_norm",
     "bigcn_plan_create", "bigcn_plan_destroy", "bigcn_plan_rows", "bigcn_plan_nnz", "bigcn_spmm",
-    "bigcn_forward_workspace_bytes", "bigcn_forward", "bigcn_profile_create",
+    "bigcn_forward_workspace_bytes", "bigcn_forward_row_bytes", "bigcn_forward", "bigcn_profile_create",
     "bigcn_profile_destroy", "bigcn_forward_profiled", "bigcn_profile_read",
 )
 
@@ -85,6 +85,8 @@ def lib() -> ctypes.CDLL:
         L.bigcn_spmm.argtypes = [vp, vp, vp, vp, i64, vp, i64, i64, vp, i64, vp]
         L.bigcn_forward_workspace_bytes.restype = ctypes.c_size_t
         L.bigcn_forward_workspace_bytes.argtypes = [i64, ctypes.POINTER(LayerDesc), i32]
+        L.bigcn_forward_row_bytes.restype = i64
+        L.bigcn_forward_row_bytes.argtypes = [i64, i64, ctypes.POINTER(i32)]
         L.bigcn_forward.restype = i32
         L.bigcn_forward.argtypes = [vp, vp, vp, vp, i64, vp, i64, ctypes.POINTER(LayerDesc), i32, vp,
                                     i64, vp, ctypes.c_size_t, vp]
@@ -277,6 +279,13 @@ class Layer:
 def _descs(layers: Sequence[Layer]):
     arr = (LayerDesc * len(layers))(*[l.desc() for l in layers])
     return arr
+
+
+def bigcn_forward_row_bytes(d_in: int, d_out: int) -> Tuple[int, bool]:
+    """(bytes of the per-node product row of such a layer, whether the source scale is inside)."""
+    flag = ctypes.c_int(0)
+    size = int(lib().bigcn_forward_row_bytes(int(d_in), int(d_out), ctypes.byref(flag)))
+    return size, bool(flag.value)
 
 
 def bigcn_forward_workspace_bytes(n: int, layers: Sequence[Layer]) -> int:

@@ -41,19 +41,35 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// Layout in which the fused forward keeps the integer products C of one node:
-// `groups` lanes hold `vec` consecutive stored values each; stored position
-// g*vec + v holds output column g + groups*v.  With this interleaving one ballot per v
-// yields `groups` consecutive sign bits of the next layer's packed activation.
+// Layout in which the fused forward keeps the integer products C of one node.
+// `groups` lanes hold `vec` consecutive stored values each; stored position g*vec + v holds
+// output column g + groups*v.  With this interleaving one ballot per v yields `groups`
+// consecutive sign bits of the next layer's packed activation.
+//
+// Storage kinds (all exact):
+//   kI8  (K <= 256): q = floor(K'/2) - popcount over the first K' bits, so that the product
+//         over those bits is 2q + (K' mod 2).  K' = K, except K = 256 where K' = 255 and the
+//         last bit's contribution  f_{k,255} * b_{255,j}  is carried separately: the sign
+//         f_{k,255} rides on the sign of the node's stored scale, b_{255,j} is a per-column
+//         constant.  q always fits int8: [-128, 127].
+//   kF16 (K <= 2048): the product itself; every integer of magnitude <= 2048 is exact in fp16.
+//   kF32 : the product as fp32.
+enum RowKind { kI8 = 0, kF16 = 1, kF32 = 2 };
+
 struct RowLayout {
-    int groups;   // lanes that share one stored row (power of two, 2..64)
-    int vec;      // values per lane (4 or 8)
-    int half;     // 1: values stored as fp16 (exact for |c| <= 2048), 0: fp32
+    int groups;      // lanes that share one stored row (power of two, 2..64)
+    int vec;         // values per lane (4, 8 or 16)
+    int kind;        // RowKind
+    int k_eff;       // K': bits covered by the stored value
+    int fold_last;   // 1: bit K-1 is excluded from the stored value (K = 256, kI8)
+    int embed_scale; // 1: the last 4 bytes of a stored row hold the node's fp32 source scale
+                     //    (kI8 rows with at least 4 spare positions): no separate scale gather
     __host__ __device__ int positions() const { return groups * vec; }
-    __host__ __device__ int64_t row_bytes() const
-    {
-        return static_cast<int64_t>(positions()) * (half ? 2 : 4);
-    }
+    __host__ __device__ int elem_bytes() const { return kind == kI8 ? 1 : (kind == kF16 ? 2 : 4); }
+    __host__ __device__ int64_t row_bytes() const { return static_cast<int64_t>(positions()) * elem_bytes(); }
+    // sum_k w_k c_kj = mul * sum_k w_k stored_kj + bias * sum_k w_k (+ last-bit term)
+    __host__ __device__ float mul() const { return kind == kI8 ? 2.0f : 1.0f; }
+    __host__ __device__ float bias() const { return kind == kI8 ? static_cast<float>(k_eff & 1) : 0.0f; }
 };
 
 // Layout used for a layer with d_out columns and d_in input bits.
@@ -61,14 +77,17 @@ RowLayout choose_layout(int64_t d_in, int64_t d_out);
 
 // ---- internal launchers (defined in the .hip files) ------------------------------------
 // pack: as bigcn_pack, plus an optional per-row factor folded into the scale.
+// fold_last_sign: the stored scale additionally carries the sign of the row's last column.
 int launch_pack(const float *x, int64_t rows, int64_t cols, int64_t row_stride,
                 int64_t col_stride, const float *shift, const float *mul, const float *row_mul,
-                uint64_t *bits, int64_t ld_words, float *scale, hipStream_t stream);
+                int fold_last_sign, uint64_t *bits, int64_t ld_words, float *scale,
+                hipStream_t stream);
 
 // bit-GEMM writing the integer products in a RowLayout (fused forward).
+// src_scale (m floats) is copied into the rows when the layout embeds the scale.
 int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits,
-                          int64_t n, int64_t ldb, int64_t k_bits, void *c_rows, RowLayout layout,
-                          hipStream_t stream);
+                          int64_t n, int64_t ldb, int64_t k_bits, const float *src_scale, void *c_rows,
+                          RowLayout layout, hipStream_t stream);
 
 // Aggregation of layer l fused with the rescale and with the binarisation of layer l+1.
 struct FusedSpmmArgs {
@@ -81,6 +100,9 @@ struct FusedSpmmArgs {
     RowLayout layout;
     const float *alpha;         // d_out
     int64_t d_out;
+    const uint64_t *w_bits;     // this layer's packed weights (for the last-bit term)
+    int64_t w_ld_words;
+    int64_t d_in;
     // last layer: fp32 logits
     float *logits;
     int64_t ld_logits;
@@ -90,6 +112,7 @@ struct FusedSpmmArgs {
     uint64_t *next_bits;
     int64_t next_ld_words;
     float *next_scale;          // n: dinv_sqrt[i] * beta_i of the next layer
+    int next_fold_last_sign;    // the next layer's layout has fold_last: sign the stored scale
 };
 int launch_fused_spmm(const FusedSpmmArgs &args, hipStream_t stream);
 

@@ -2,16 +2,32 @@
 // rescale  zeta_ij = beta_i * alpha_j * c_ij  (Sec. 4.2.3: XNOR + bit count in place of the
 // floating-point inner product of two +-1 vectors).
 //
-// Mapping (wave64, integer VALU path): lane l of a wavefront owns output columns
-// l, l+64, ..., l+64(V-1); the packed rows of B for the workgroup's column block live in
-// LDS as [word][column] so that a wavefront reads 512 contiguous bytes per access; the
+// Mapping (wave64, integer VALU path): the 64 lanes of a wavefront own 64 * VB output
+// columns of a row block; the packed rows of B for those columns live in LDS as
+// [word][lane + 64 v] so that a wavefront reads 512 contiguous bytes per access; the
 // wavefront walks R rows of A at a time, and because all 64 lanes work on the same row of
 // A its words are wave-uniform (scalar loads, XOR with a scalar operand).  Per 64 binary
 // multiply-accumulates a lane issues two v_xor_b32 and two v_bcnt_u32_b32 (the bit count
 // accumulates for free), which is the integer-VALU roofline of the operation.
+//
+// Which columns a lane owns is a parameter (ColumnMap), so that the values a lane produces
+// are consecutive in the destination: row-major columns l, l+64, ... for the public entry
+// point, and the interleaved product-row layout of the fused forward otherwise.
 #include "bigcn_internal.h"
 
 namespace bigcn {
+
+// Lane l, local index v (0..VB-1), column block y:
+//   value index inside the stored row   vv  = per_group * (l / groups) + y * VB + v
+//   output column                       col = (l % groups) + groups * vv
+//   stored position                     pos = (l % groups) * vec + vv
+// The public entry point uses groups = 64, per_group = vec = VB * gridDim.y, i.e.
+// col = l + 64 * (y * VB + v), and ignores pos.
+struct ColumnMap {
+    int groups;
+    int vec;
+    int per_group;   // values of one lane across all column blocks
+};
 
 // ---- epilogues ---------------------------------------------------------------------------
 // Public entry point: int32 accumulators and / or rescaled fp32, row-major.
@@ -22,91 +38,120 @@ struct EpilogueApi {
     int64_t ld_acc;
     float *out;
     int64_t ld_out;
-    template <int V>
-    __device__ __forceinline__ void store(int64_t row, int col0, int lane, int n, const int (&c)[V]) const
+    int k_bits;
+    template <int VB>
+    __device__ __forceinline__ void store(int64_t row, const int (&col)[VB], int /*pos0*/, bool /*any*/,
+                                          int n, const int (&pop)[VB]) const
     {
         const float sa = out != nullptr ? a_scale[row] : 0.0f;
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-            const int j = col0 + lane + 64 * v;
-            if (j < n) {
-                if (acc != nullptr) acc[row * ld_acc + j] = c[v];
-                if (out != nullptr) out[row * ld_out + j] = sa * b_scale[j] * static_cast<float>(c[v]);
+        for (int v = 0; v < VB; ++v) {
+            const int j = col[v];
+            if (j >= 0 && j < n) {
+                const int c = k_bits - 2 * pop[v];
+                if (acc != nullptr) acc[row * ld_acc + j] = c;
+                if (out != nullptr) out[row * ld_out + j] = sa * b_scale[j] * static_cast<float>(c);
             }
         }
     }
 };
 
-// Fused forward: the integer products of a node in a RowLayout (fp16 or fp32 storage).
+// Fused forward: one product row per node in a RowLayout.  T = int8_t stores
+// floor(K'/2) - pop, T = __half / float store K' - 2 pop; a lane's VB values are consecutive.
 template <typename T>
 struct EpilogueLayout {
     T *rows;
-    int groups;      // RowLayout::groups
-    int vec;         // RowLayout::vec
-    template <int V>
-    __device__ __forceinline__ void store(int64_t row, int col0, int lane, int n, const int (&c)[V]) const
+    int positions;
+    int k_eff;
+    const float *embed;      // non-null (int8 rows only): scale[row] goes into the last 4 bytes
+    template <int VB>
+    __device__ __forceinline__ void store(int64_t row, const int (&col)[VB], int pos0, bool any, int n,
+                                          const int (&pop)[VB]) const
     {
-        const int positions = groups * vec;
-        T *dst = rows + row * positions;
-        if (groups == 64 && vec == V && col0 == 0) {
-            // this lane's V columns l, l+64, ... are V consecutive stored values
-            T tmp[V];
+        if (!any) return;
+        alignas(16) T tmp[VB];
 #pragma unroll
-            for (int v = 0; v < V; ++v)
-                tmp[v] = (lane + 64 * v < n) ? static_cast<T>(static_cast<float>(c[v])) : static_cast<T>(0.0f);
-            T *p = dst + lane * V;
-            if constexpr (sizeof(T) * V == 8) {
-                *reinterpret_cast<uint2 *>(p) = *reinterpret_cast<const uint2 *>(tmp);
-            } else if constexpr (sizeof(T) * V == 16) {
-                *reinterpret_cast<uint4 *>(p) = *reinterpret_cast<const uint4 *>(tmp);
-            } else {
+        for (int v = 0; v < VB; ++v) {
+            int value;
+            if constexpr (sizeof(T) == 1) value = (k_eff >> 1) - pop[v];
+            else value = k_eff - 2 * pop[v];
+            const bool live = col[v] >= 0 && col[v] < n;
+            if constexpr (sizeof(T) == 1) tmp[v] = static_cast<T>(live ? value : 0);
+            else tmp[v] = static_cast<T>(live ? static_cast<float>(value) : 0.0f);
+        }
+        if constexpr (sizeof(T) == 1) {
+            if (embed != nullptr) {
+                const uint32_t bits = __float_as_uint(embed[row]);
 #pragma unroll
-                for (int v = 0; v < V; ++v) p[v] = tmp[v];
-            }
-        } else {
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                const int j = col0 + lane + 64 * v;
-                if (j < positions) {
-                    const int pos = (j % groups) * vec + j / groups;
-                    dst[pos] = j < n ? static_cast<T>(static_cast<float>(c[v])) : static_cast<T>(0.0f);
+                for (int v = 0; v < VB; ++v) {
+                    const int byte = pos0 + v - (positions - 4);
+                    if (byte >= 0) tmp[v] = static_cast<T>((bits >> (8 * byte)) & 0xffu);
                 }
             }
+        }
+        T *p = rows + row * positions + pos0;
+        constexpr int kBytes = sizeof(T) * VB;
+        if constexpr (kBytes == 16) *reinterpret_cast<uint4 *>(p) = *reinterpret_cast<const uint4 *>(tmp);
+        else if constexpr (kBytes == 8) *reinterpret_cast<uint2 *>(p) = *reinterpret_cast<const uint2 *>(tmp);
+        else if constexpr (kBytes == 4) *reinterpret_cast<uint32_t *>(p) = *reinterpret_cast<const uint32_t *>(tmp);
+        else if constexpr (kBytes == 2) *reinterpret_cast<uint16_t *>(p) = *reinterpret_cast<const uint16_t *>(tmp);
+        else if constexpr (kBytes == 32) {
+            reinterpret_cast<uint4 *>(p)[0] = reinterpret_cast<const uint4 *>(tmp)[0];
+            reinterpret_cast<uint4 *>(p)[1] = reinterpret_cast<const uint4 *>(tmp)[1];
+        } else {
+#pragma unroll
+            for (int v = 0; v < VB; ++v) p[v] = tmp[v];
         }
     }
 };
 
 // ---- the kernel -----------------------------------------------------------------------------
-// grid.x walks row blocks (grid-stride), grid.y is the column block of 64*V columns.
-template <int V, int R, class Epilogue>
+// grid.x walks row blocks (grid-stride), grid.y is the column block.  last_mask is ANDed onto
+// the high half of the last word of both operands (all ones, or bit 31 cleared to leave the
+// last of 64*n_words bits out of the count).
+template <int VB, int R, class Epilogue>
 __global__ __launch_bounds__(kBlock) void bitgemm_kernel(
     const uint64_t *__restrict__ a, int64_t m, int64_t lda, const uint64_t *__restrict__ b, int n,
-    int64_t ldb, int k_bits, Epilogue epi)
+    int64_t ldb, int n_words, uint32_t last_mask, ColumnMap map, Epilogue epi)
 {
-    extern __shared__ uint64_t lds_b[];          // [n_words][64*V]
-    constexpr int CB = 64 * V;
-    const int n_words = (k_bits + 63) >> 6;
-    const int col0 = blockIdx.y * CB;
+    extern __shared__ uint64_t lds_b[];          // [n_words][64*VB]
+    constexpr int CB = 64 * VB;
+    const int y = blockIdx.y;
 
+    // stage the packed rows of B for the columns of this block; slot c belongs to lane c % 64
     for (int idx = threadIdx.x; idx < CB * n_words; idx += kBlock) {
         const int c = idx / n_words;
         const int w = idx - c * n_words;
-        const int j = col0 + c;
-        lds_b[w * CB + c] = j < n ? b[static_cast<int64_t>(j) * ldb + w] : 0ull;
+        const int l = c & 63, v = c >> 6;
+        const int vv = map.per_group * (l / map.groups) + y * VB + v;
+        const int j = (l % map.groups) + map.groups * vv;
+        uint64_t word = (vv < map.vec && j < n) ? b[static_cast<int64_t>(j) * ldb + w] : 0ull;
+        if (w == n_words - 1) word &= (static_cast<uint64_t>(last_mask) << 32) | 0xffffffffull;
+        lds_b[w * CB + c] = word;
     }
     __syncthreads();
     const uint2 *lds_b2 = reinterpret_cast<const uint2 *>(lds_b);
 
     const int lane = lane_id();
+    int col[VB];
+    bool any = false;
+#pragma unroll
+    for (int v = 0; v < VB; ++v) {
+        const int vv = map.per_group * (lane / map.groups) + y * VB + v;
+        col[v] = vv < map.vec ? (lane % map.groups) + map.groups * vv : -1;
+        any = any || vv < map.vec;
+    }
+    const int pos0 = (lane % map.groups) * map.vec + map.per_group * (lane / map.groups) + y * VB;
+
     const int64_t wave = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block();
     const int64_t n_waves = static_cast<int64_t>(gridDim.x) * kWavesPerBlock;
 
     for (int64_t row0 = wave * R; row0 < m; row0 += n_waves * R) {
-        int pop[R][V];
+        int pop[R][VB];
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int v = 0; v < V; ++v) pop[r][v] = 0;
+            for (int v = 0; v < VB; ++v) pop[r][v] = 0;
 
         const uint32_t *arow[R];
 #pragma unroll
@@ -125,29 +170,35 @@ __global__ __launch_bounds__(kBlock) void bitgemm_kernel(
             for (int r = 0; r < R; ++r)
 #pragma unroll
                 for (int q = 0; q < 2 * WC; ++q) aw[r][q] = arow[r][2 * w + q];
+            if (w + WC == n_words) {
+#pragma unroll
+                for (int r = 0; r < R; ++r) aw[r][2 * WC - 1] &= last_mask;
+            }
 #pragma unroll
             for (int u = 0; u < WC; ++u) {
-                uint2 bw[V];
+                uint2 bw[VB];
 #pragma unroll
-                for (int v = 0; v < V; ++v) bw[v] = lds_b2[(w + u) * CB + lane + 64 * v];
+                for (int v = 0; v < VB; ++v) bw[v] = lds_b2[(w + u) * CB + lane + 64 * v];
 #pragma unroll
                 for (int r = 0; r < R; ++r)
 #pragma unroll
-                    for (int v = 0; v < V; ++v) {
+                    for (int v = 0; v < VB; ++v) {
                         pop[r][v] = __popc(aw[r][2 * u] ^ bw[v].x) + pop[r][v];
                         pop[r][v] = __popc(aw[r][2 * u + 1] ^ bw[v].y) + pop[r][v];
                     }
             }
         }
         for (; w < n_words; ++w) {
-            uint2 bw[V];
+            uint2 bw[VB];
 #pragma unroll
-            for (int v = 0; v < V; ++v) bw[v] = lds_b2[w * CB + lane + 64 * v];
+            for (int v = 0; v < VB; ++v) bw[v] = lds_b2[w * CB + lane + 64 * v];
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                const uint32_t lo = arow[r][2 * w], hi = arow[r][2 * w + 1];
+                const uint32_t lo = arow[r][2 * w];
+                uint32_t hi = arow[r][2 * w + 1];
+                if (w == n_words - 1) hi &= last_mask;
 #pragma unroll
-                for (int v = 0; v < V; ++v) {
+                for (int v = 0; v < VB; ++v) {
                     pop[r][v] = __popc(lo ^ bw[v].x) + pop[r][v];
                     pop[r][v] = __popc(hi ^ bw[v].y) + pop[r][v];
                 }
@@ -156,68 +207,71 @@ __global__ __launch_bounds__(kBlock) void bitgemm_kernel(
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             if (row0 + r >= m) break;                               // wave-uniform
-            int c[V];
-#pragma unroll
-            for (int v = 0; v < V; ++v) c[v] = k_bits - 2 * pop[r][v];
-            epi.template store<V>(row0 + r, col0, lane, n, c);
+            epi.template store<VB>(row0 + r, col, pos0, any, n, pop[r]);
         }
     }
 }
 
-template <int V, int R, class Epilogue>
+template <int VB, int R, class Epilogue>
 static int launch_bitgemm(const uint64_t *a, int64_t m, int64_t lda, const uint64_t *b, int64_t n,
-                          int64_t ldb, int64_t k_bits, const Epilogue &epi, hipStream_t stream)
+                          int64_t ldb, int64_t k_bits, uint32_t last_mask, ColumnMap map,
+                          int col_blocks, const Epilogue &epi, hipStream_t stream)
 {
     const int n_words = static_cast<int>((k_bits + 63) / 64);
-    const size_t lds = static_cast<size_t>(64) * V * n_words * sizeof(uint64_t);
-    const int col_blocks = static_cast<int>((n + 64 * V - 1) / (64 * V));
+    const size_t lds = static_cast<size_t>(64) * VB * n_words * sizeof(uint64_t);
     // every workgroup stages its B block once: give each at least 16 row blocks per wave
     int64_t row_blocks = (m + R - 1) / R;
     int64_t blocks = (row_blocks + kWavesPerBlock * 16 - 1) / (kWavesPerBlock * 16);
     const int64_t cap = 256 * 8;
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL((bitgemm_kernel<V, R, Epilogue>), dim3(static_cast<unsigned>(blocks), col_blocks),
-                       dim3(kBlock), lds, stream, a, m, lda, b, static_cast<int>(n), ldb,
-                       static_cast<int>(k_bits), epi);
+    hipLaunchKernelGGL((bitgemm_kernel<VB, R, Epilogue>), dim3(static_cast<unsigned>(blocks), col_blocks),
+                       dim3(kBlock), lds, stream, a, m, lda, b, static_cast<int>(n), ldb, n_words,
+                       last_mask, map, epi);
     return check_launch();
 }
 
-// Columns per workgroup are limited by the 64 KB of LDS a workgroup may use:
-// 64 * V * n_words * 8 bytes <= 65536  <=>  V * n_words <= 128.
+// per_lane values of a lane are split into column blocks of VB values so that the B block
+// fits the 64 KB of LDS a workgroup may use: 64 * VB * n_words * 8 <= 65536  <=>
+// VB * n_words <= 128.
 template <class Epilogue>
-static int dispatch_bitgemm(int v_wanted, const uint64_t *a, int64_t m, int64_t lda, const uint64_t *b,
-                            int64_t n, int64_t ldb, int64_t k_bits, const Epilogue &epi,
-                            hipStream_t stream)
+static int dispatch_bitgemm(int per_lane, int groups, int vec, const uint64_t *a, int64_t m, int64_t lda,
+                            const uint64_t *b, int64_t n, int64_t ldb, int64_t k_bits,
+                            uint32_t last_mask, const Epilogue &epi, hipStream_t stream)
 {
     const int n_words = static_cast<int>((k_bits + 63) / 64);
-    int v = v_wanted;
-    while (v > 1 && v * n_words > 128) v >>= 1;
-    if (v >= 8) return launch_bitgemm<8, 2>(a, m, lda, b, n, ldb, k_bits, epi, stream);
-    if (v >= 4) return launch_bitgemm<4, 4>(a, m, lda, b, n, ldb, k_bits, epi, stream);
-    if (v >= 2) return launch_bitgemm<2, 4>(a, m, lda, b, n, ldb, k_bits, epi, stream);
-    return launch_bitgemm<1, 4>(a, m, lda, b, n, ldb, k_bits, epi, stream);
-}
-
-static int columns_per_lane(int64_t n)
-{
-    const int64_t v = (n + 63) / 64;
-    return v >= 8 ? 8 : (v >= 3 ? 4 : (v == 2 ? 2 : 1));
+    int vb = per_lane >= 8 ? 8 : (per_lane >= 4 ? 4 : (per_lane >= 2 ? 2 : 1));
+    while (vb > 1 && vb * n_words > 128) vb >>= 1;
+    const int col_blocks = (per_lane + vb - 1) / vb;
+    const ColumnMap map{groups, vec, per_lane};
+    if (vb == 8) return launch_bitgemm<8, 2>(a, m, lda, b, n, ldb, k_bits, last_mask, map, col_blocks, epi, stream);
+    if (vb == 4) return launch_bitgemm<4, 4>(a, m, lda, b, n, ldb, k_bits, last_mask, map, col_blocks, epi, stream);
+    if (vb == 2) return launch_bitgemm<2, 4>(a, m, lda, b, n, ldb, k_bits, last_mask, map, col_blocks, epi, stream);
+    return launch_bitgemm<1, 4>(a, m, lda, b, n, ldb, k_bits, last_mask, map, col_blocks, epi, stream);
 }
 
 int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits,
-                          int64_t n, int64_t ldb, int64_t k_bits, void *c_rows, RowLayout layout,
-                          hipStream_t stream)
+                          int64_t n, int64_t ldb, int64_t k_bits, const float *src_scale, void *c_rows,
+                          RowLayout layout, hipStream_t stream)
 {
     if (m == 0 || n == 0) return BIGCN_OK;
-    // with 64 groups the kernel's lane -> column map equals the layout's: use its vec
-    const int v = layout.groups == 64 ? layout.vec : columns_per_lane(layout.positions());
-    if (layout.half) {
-        EpilogueLayout<__half> epi{static_cast<__half *>(c_rows), layout.groups, layout.vec};
-        return dispatch_bitgemm(v, a_bits, m, lda, b_bits, n, ldb, k_bits, epi, stream);
+    // a stored row is spread over all 64 lanes: each lane produces positions/64 consecutive values
+    const int per_lane = layout.positions() >= 64 ? layout.positions() / 64 : 1;
+    const uint32_t last_mask = layout.fold_last ? 0x7fffffffu : 0xffffffffu;
+    if (layout.kind == kI8) {
+        EpilogueLayout<int8_t> epi{static_cast<int8_t *>(c_rows), layout.positions(), layout.k_eff,
+                                   layout.embed_scale ? src_scale : nullptr};
+        return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
+                                last_mask, epi, stream);
     }
-    EpilogueLayout<float> epi{static_cast<float *>(c_rows), layout.groups, layout.vec};
-    return dispatch_bitgemm(v, a_bits, m, lda, b_bits, n, ldb, k_bits, epi, stream);
+    if (layout.kind == kF16) {
+        EpilogueLayout<__half> epi{static_cast<__half *>(c_rows), layout.positions(), layout.k_eff, nullptr};
+        return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
+                                last_mask, epi, stream);
+    }
+    EpilogueLayout<float> epi{static_cast<float *>(c_rows), layout.positions(), layout.k_eff, nullptr};
+    return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
+                            last_mask, epi, stream);
 }
 
 }  // namespace bigcn
@@ -235,10 +289,11 @@ extern "C" int bigcn_binary_gemm(const uint64_t *a_bits, const float *a_scale, i
     if (lda_words < n_words || ldb_words < n_words) return BIGCN_EINVAL;
     if (acc != nullptr && ld_acc < n) return BIGCN_EINVAL;
     if (out != nullptr && ld_out < n) return BIGCN_EINVAL;
-    if (n > INT32_MAX) return BIGCN_EINVAL;
-    if (k_bits > BIGCN_MAX_K_BITS) return BIGCN_ESHAPE;
+    if (k_bits > BIGCN_MAX_K_BITS || n > BIGCN_MAX_GEMM_N) return BIGCN_ESHAPE;
     if (m == 0 || n == 0) return BIGCN_OK;
-    bigcn::EpilogueApi epi{a_scale, b_scale, acc, ld_acc, out, ld_out};
-    return bigcn::dispatch_bitgemm(bigcn::columns_per_lane(n), a_bits, m, lda_words, b_bits, n,
-                                   ldb_words, k_bits, epi, bigcn::as_stream(stream));
+    bigcn::EpilogueApi epi{a_scale, b_scale, acc, ld_acc, out, ld_out, static_cast<int>(k_bits)};
+    // row-major output: lane l owns columns l, l + 64, ...
+    const int per_lane = static_cast<int>((n + 63) / 64);
+    return bigcn::dispatch_bitgemm(per_lane, 64, per_lane, a_bits, m, lda_words, b_bits, n, ldb_words,
+                                   k_bits, 0xffffffffu, epi, bigcn::as_stream(stream));
 }

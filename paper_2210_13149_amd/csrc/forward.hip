@@ -80,6 +80,14 @@ extern "C" const char *bigcn_status_string(int status)
 
 extern "C" int bigcn_version(void) { return 0 * 10000 + 1 * 100 + 0; }
 
+extern "C" int64_t bigcn_forward_row_bytes(int64_t d_in, int64_t d_out, int *scale_embedded)
+{
+    if (d_in <= 0 || d_out <= 0 || d_in > BIGCN_MAX_K_BITS || d_out > BIGCN_MAX_FORWARD_D_OUT) return 0;
+    const RowLayout l = choose_layout(d_in, d_out);
+    if (scale_embedded != nullptr) *scale_embedded = l.embed_scale;
+    return l.row_bytes();
+}
+
 extern "C" size_t bigcn_forward_workspace_bytes(int64_t n, const bigcn_layer *layers, int n_layers)
 {
     int status;
@@ -121,14 +129,15 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
     int64_t words = (layers[0].d_in + 63) / 64;
     BIGCN_MARK();
     int rc = launch_pack(x, n, layers[0].d_in, ld_x, 1, layers[0].bn_shift, layers[0].bn_mul, dinv_sqrt,
-                         bits, words, scale[0], s);
+                         choose_layout(layers[0].d_in, layers[0].d_out).fold_last, bits, words, scale[0], s);
     if (rc != BIGCN_OK) return rc;
     BIGCN_MARK();
 
     for (int l = 0; l < n_layers; ++l) {
         const bigcn_layer &L = layers[l];
         const RowLayout layout = choose_layout(L.d_in, L.d_out);
-        rc = launch_bitgemm_layout(bits, n, words, L.w_bits, L.d_out, L.ld_words, L.d_in, c_rows, layout, s);
+        rc = launch_bitgemm_layout(bits, n, words, L.w_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1], c_rows,
+                                   layout, s);
         if (rc != BIGCN_OK) return rc;
         BIGCN_MARK();
 
@@ -142,6 +151,9 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
         a.layout = layout;
         a.alpha = L.alpha;
         a.d_out = L.d_out;
+        a.w_bits = L.w_bits;
+        a.w_ld_words = L.ld_words;
+        a.d_in = L.d_in;
         if (l == n_layers - 1) {
             a.logits = logits;
             a.ld_logits = ld_logits;
@@ -152,6 +164,7 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
             a.next_bits = bits;
             a.next_ld_words = words;
             a.next_scale = scale[(l + 1) & 1];
+            a.next_fold_last_sign = choose_layout(layers[l + 1].d_in, layers[l + 1].d_out).fold_last;
         }
         rc = launch_fused_spmm(a, s);
         if (rc != BIGCN_OK) return rc;

@@ -15,8 +15,8 @@ template <int NW>
 __global__ __launch_bounds__(kBlock) void pack_short_kernel(
     const float *__restrict__ x, int64_t rows, int cols, int64_t row_stride,
     const float *__restrict__ shift, const float *__restrict__ mul,
-    const float *__restrict__ row_mul, uint64_t *__restrict__ bits, int64_t ld_words,
-    float *__restrict__ scale)
+    const float *__restrict__ row_mul, int fold_last_sign, uint64_t *__restrict__ bits,
+    int64_t ld_words, float *__restrict__ scale)
 {
     constexpr int RB = 8 / NW;
     const int lane = lane_id();
@@ -48,12 +48,13 @@ __global__ __launch_bounds__(kBlock) void pack_short_kernel(
             const int64_t row = row0 + r;
             if (row >= rows) break;             // wave-uniform
             float sum = 0.0f;
-            uint64_t mine = 0;
+            uint64_t mine = 0, last_word = 0;
 #pragma unroll
             for (int w = 0; w < NW; ++w) {
                 const bool bit = in[w] && (v[r][w] >= th[w]);
                 const uint64_t word = __ballot(bit);
                 if (lane == w) mine = word;
+                last_word = word;
                 sum += in[w] ? fabsf((v[r][w] - th[w]) * ml[w]) : 0.0f;
             }
             sum = wave_sum(sum);
@@ -61,6 +62,7 @@ __global__ __launch_bounds__(kBlock) void pack_short_kernel(
             if (lane == 0) {
                 float s = sum * inv_cols;
                 if (row_mul != nullptr) s *= row_mul[row];
+                if (fold_last_sign && ((last_word >> ((cols - 1) & 63)) & 1ull) == 0) s = -s;
                 scale[row] = s;
             }
         }
@@ -71,8 +73,8 @@ __global__ __launch_bounds__(kBlock) void pack_short_kernel(
 __global__ __launch_bounds__(kBlock) void pack_generic_kernel(
     const float *__restrict__ x, int64_t rows, int64_t cols, int64_t row_stride,
     int64_t col_stride, const float *__restrict__ shift, const float *__restrict__ mul,
-    const float *__restrict__ row_mul, uint64_t *__restrict__ bits, int64_t ld_words,
-    float *__restrict__ scale)
+    const float *__restrict__ row_mul, int fold_last_sign, uint64_t *__restrict__ bits,
+    int64_t ld_words, float *__restrict__ scale)
 {
     constexpr int U = 4;
     const int lane = lane_id();
@@ -84,7 +86,7 @@ __global__ __launch_bounds__(kBlock) void pack_generic_kernel(
     for (int64_t row = wave; row < rows; row += n_waves) {
         const float *xr = x + row * row_stride;
         float sum = 0.0f;
-        uint64_t mine = 0;
+        uint64_t mine = 0, last_word = 0;
         for (int64_t w0 = 0; w0 < n_words; w0 += U) {
             float v[U], th[U], ml[U];
             bool in[U];
@@ -103,6 +105,7 @@ __global__ __launch_bounds__(kBlock) void pack_generic_kernel(
                 const bool bit = in[u] && (v[u] >= th[u]);
                 const uint64_t word = __ballot(bit);
                 if (lane == static_cast<int>(w & 63)) mine = word;
+                last_word = word;
                 sum += in[u] ? fabsf((v[u] - th[u]) * ml[u]) : 0.0f;
                 if ((w & 63) == 63 || w == n_words - 1) {
                     // lanes 0..(w & 63) hold words (w & ~63) .. w: one coalesced store
@@ -115,6 +118,7 @@ __global__ __launch_bounds__(kBlock) void pack_generic_kernel(
         if (lane == 0) {
             float s = sum * inv_cols;
             if (row_mul != nullptr) s *= row_mul[row];
+            if (fold_last_sign && ((last_word >> ((cols - 1) & 63)) & 1ull) == 0) s = -s;
             scale[row] = s;
         }
     }
@@ -130,7 +134,8 @@ static int grid_for_waves(int64_t waves_needed)
 
 int launch_pack(const float *x, int64_t rows, int64_t cols, int64_t row_stride,
                 int64_t col_stride, const float *shift, const float *mul, const float *row_mul,
-                uint64_t *bits, int64_t ld_words, float *scale, hipStream_t stream)
+                int fold_last_sign, uint64_t *bits, int64_t ld_words, float *scale,
+                hipStream_t stream)
 {
     if (rows == 0) return BIGCN_OK;
     const int64_t n_words = (cols + 63) / 64;
@@ -139,7 +144,7 @@ int launch_pack(const float *x, int64_t rows, int64_t cols, int64_t row_stride,
 #define BIGCN_PACK_SHORT(NW)                                                                  \
     hipLaunchKernelGGL(pack_short_kernel<NW>, dim3(grid_for_waves((rows + 8 / NW - 1) / (8 / NW))), \
                        dim3(kBlock), 0, stream, x, rows, icols, row_stride, shift, mul, row_mul, \
-                       bits, ld_words, scale)
+                       fold_last_sign, bits, ld_words, scale)
         switch (n_words) {
         case 1: BIGCN_PACK_SHORT(1); break;
         case 2: BIGCN_PACK_SHORT(2); break;
@@ -149,8 +154,8 @@ int launch_pack(const float *x, int64_t rows, int64_t cols, int64_t row_stride,
 #undef BIGCN_PACK_SHORT
     } else {
         hipLaunchKernelGGL(pack_generic_kernel, dim3(grid_for_waves(rows)), dim3(kBlock), 0, stream,
-                           x, rows, cols, row_stride, col_stride, shift, mul, row_mul, bits,
-                           ld_words, scale);
+                           x, rows, cols, row_stride, col_stride, shift, mul, row_mul, fold_last_sign,
+                           bits, ld_words, scale);
     }
     return check_launch();
 }
@@ -164,6 +169,6 @@ extern "C" int bigcn_pack(const float *x, int64_t rows, int64_t cols, int64_t ro
     if (x == nullptr || bits == nullptr || scale == nullptr) return BIGCN_ENULL;
     if (rows < 0 || cols <= 0 || row_stride <= 0 || col_stride <= 0) return BIGCN_EINVAL;
     if (ld_words < (cols + 63) / 64) return BIGCN_EINVAL;
-    return bigcn::launch_pack(x, rows, cols, row_stride, col_stride, shift, mul, nullptr, bits,
+    return bigcn::launch_pack(x, rows, cols, row_stride, col_stride, shift, mul, nullptr, 0, bits,
                               ld_words, scale, bigcn::as_stream(stream));
 }

@@ -17,7 +17,10 @@
 
 namespace bigcn {
 
-enum WeightMode { kWeightOne = 0, kWeightVals = 1, kWeightGather = 2 };
+// Where the per-neighbour weight comes from: all ones, a per-entry array, a per-node array
+// gathered through the column index, or the last four bytes of the gathered row itself.
+enum WeightMode { kWeightOne = 0, kWeightVals = 1, kWeightGather = 2, kWeightEmbedded = 3 };
+__host__ __device__ constexpr bool fused_weights(int wm) { return wm == kWeightGather || wm == kWeightEmbedded; }
 
 // ---- one stored row segment: V values of T per lane, loaded as one vector ------------------
 template <typename T, int V>
@@ -89,15 +92,75 @@ struct Segment<__half, 8> {
         }
     }
 };
+__device__ __forceinline__ void fma_bytes(float w, uint32_t word, float *acc)
+{
+    // four signed bytes -> fp32 (sign-extending bit-field extract, then convert)
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        acc[e] = fmaf(w, static_cast<float>(static_cast<int>(word << (24 - 8 * e)) >> 24), acc[e]);
+}
+template <>
+struct Segment<int8_t, 8> {
+    uint2 raw;
+    __device__ __forceinline__ void load(const char *p) { raw = *reinterpret_cast<const uint2 *>(p); }
+    __device__ __forceinline__ void fma(float w, float (&acc)[8]) const
+    {
+        fma_bytes(w, raw.x, acc);
+        fma_bytes(w, raw.y, acc + 4);
+    }
+    __device__ __forceinline__ uint32_t tail() const { return raw.y; }
+};
+template <>
+struct Segment<int8_t, 16> {
+    uint4 raw;
+    __device__ __forceinline__ void load(const char *p) { raw = *reinterpret_cast<const uint4 *>(p); }
+    __device__ __forceinline__ void fma(float w, float (&acc)[16]) const
+    {
+        fma_bytes(w, raw.x, acc);
+        fma_bytes(w, raw.y, acc + 4);
+        fma_bytes(w, raw.z, acc + 8);
+        fma_bytes(w, raw.w, acc + 12);
+    }
+    __device__ __forceinline__ uint32_t tail() const { return raw.w; }
+};
 
-// ---- accumulate the neighbours p0..p1-1 of one node into acc (per lane: V positions) -------
+// Last four bytes of a loaded row as the embedded fp32 weight, broadcast from the lane that
+// holds them (the last lane of each group of G) to the whole group.
+template <typename T, int G, int V>
+__device__ __forceinline__ float embedded_weight(const Segment<T, V> &seg, int lane)
+{
+    if constexpr (sizeof(T) == 1) {
+        return __uint_as_float(static_cast<uint32_t>(__shfl(static_cast<int>(seg.tail()), lane | (G - 1), kWave)));
+    } else {
+        return 0.0f;
+    }
+}
+
+// Per-node accumulators of a lane: V positions of the weighted row sum, plus (fused path only)
+// the sum of the weight magnitudes and the sum of the signed weights.
+template <int V>
+struct RowAcc {
+    float pos[V];
+    float sum_abs;      // sum_k |w_k|
+    float sum_signed;   // sum_k w_k   (the sign of w_k carries the last input bit of node k)
+    __device__ __forceinline__ void clear()
+    {
+#pragma unroll
+        for (int v = 0; v < V; ++v) pos[v] = 0.0f;
+        sum_abs = 0.0f;
+        sum_signed = 0.0f;
+    }
+};
+
+// ---- accumulate the neighbours p0..p1-1 of one node (per lane: V positions) ---------------
 // active: this lane's positions exist in the stored row (lanes past the row width never load).
+// In gather mode the row values are weighted by |w| and both sum |w| and sum w are kept.
 template <typename T, int G, int V, int WM>
 __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col_idx,
                                                  const float *__restrict__ weights,
                                                  const char *__restrict__ lane_base, int64_t row_bytes,
                                                  int64_t p0, int64_t p1, int lane, bool active,
-                                                 float (&acc)[V])
+                                                 RowAcc<V> &acc)
 {
     constexpr int S = kWave / G;      // neighbours covered by one load instruction
     constexpr int U = 8;              // load instructions in flight
@@ -111,7 +174,7 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
             k = col_idx[pb + lane];
             if (WM == kWeightVals) wk = weights[pb + lane];
             else if (WM == kWeightGather) wk = weights[k];
-            else wk = 1.0f;
+            else if (WM == kWeightOne) wk = 1.0f;
         }
         int t = 0;
         // full groups: S*U neighbours, all present
@@ -130,36 +193,70 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
                 }
                 if (active) seg[u].load(lane_base + static_cast<int64_t>(kk) * row_bytes);
             }
-            if (active) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) seg[u].fma(w[u], acc);
+            for (int u = 0; u < U; ++u) {
+                if (WM == kWeightEmbedded) w[u] = embedded_weight<T, G, V>(seg[u], lane);
+                if (fused_weights(WM)) {
+                    acc.sum_abs += fabsf(w[u]);
+                    acc.sum_signed += w[u];
+                    if (active) seg[u].fma(fabsf(w[u]), acc.pos);
+                } else {
+                    if (active) seg[u].fma(w[u], acc.pos);
+                }
             }
         }
-        // tail: fewer than S*U neighbours left in this batch
-        for (; t < cnt; t += S) {
-            const int src = t + slot;
-            const int kk = __shfl(k, src < kWave ? src : 0, kWave);
-            const float ww = __shfl(wk, src < kWave ? src : 0, kWave);
-            if (active && src < cnt) {
-                Segment<T, V> seg;
-                seg.load(lane_base + static_cast<int64_t>(kk) * row_bytes);
-                seg.fma(ww, acc);
+        // tail: fewer than S*U neighbours left in this batch; one predicated group so that
+        // the remaining loads are still issued back to back
+        if (t < cnt) {
+            Segment<T, V> seg[U];
+            float w[U];
+            bool present[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int src = t + u * S + slot;
+                present[u] = src < cnt;
+                const int from = present[u] ? src : 0;
+                const int kk = __shfl(k, from, kWave);
+                w[u] = __shfl(wk, from, kWave);
+                if (active && present[u]) seg[u].load(lane_base + static_cast<int64_t>(kk) * row_bytes);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                // the broadcast is executed by all lanes; slots without a neighbour discard it
+                if (WM == kWeightEmbedded) w[u] = embedded_weight<T, G, V>(seg[u], lane);
+                if (present[u]) {
+                    if (fused_weights(WM)) {
+                        acc.sum_abs += fabsf(w[u]);
+                        acc.sum_signed += w[u];
+                        if (active) seg[u].fma(fabsf(w[u]), acc.pos);
+                    } else {
+                        if (active) seg[u].fma(w[u], acc.pos);
+                    }
+                }
             }
         }
     }
 }
 
 // Sum the partial results of the 64/G lane slots; afterwards every lane holds the total.
-template <int G, int V>
-__device__ __forceinline__ void reduce_slots(float (&acc)[V])
+template <int G, int V, int WM>
+__device__ __forceinline__ void reduce_slots(RowAcc<V> &acc)
 {
 #pragma unroll
-    for (int off = G; off < kWave; off <<= 1)
+    for (int off = G; off < kWave; off <<= 1) {
 #pragma unroll
-        for (int v = 0; v < V; ++v) acc[v] += __shfl_xor(acc[v], off, kWave);
+        for (int v = 0; v < V; ++v) acc.pos[v] += __shfl_xor(acc.pos[v], off, kWave);
+        if (fused_weights(WM)) {
+            acc.sum_abs += __shfl_xor(acc.sum_abs, off, kWave);
+            acc.sum_signed += __shfl_xor(acc.sum_signed, off, kWave);
+        }
+    }
 }
 
 // ---- epilogues ---------------------------------------------------------------------------------
+// An epilogue has per-lane constants (`Lane<G, V>`, set up once per wavefront by `init`) and a
+// `finish` that turns the accumulators of one node into its outputs.
+
 // Public SpMM: stored position == output column, fp32 row-major output.
 struct EpiloguePlain {
     float *out;
@@ -167,27 +264,38 @@ struct EpiloguePlain {
     int d;                 // valid positions
     int vector_store;      // 1: V floats of a lane can be written as one aligned vector
     template <int G, int V>
-    __device__ __forceinline__ void operator()(int64_t row, int lane, const float (&acc)[V]) const
+    struct Lane {};
+    template <int G, int V>
+    __device__ __forceinline__ void init(int, Lane<G, V> &) const {}
+    template <int G, int V>
+    __device__ __forceinline__ void finish(const Lane<G, V> &, int64_t row, int lane, const RowAcc<V> &acc) const
     {
         if (lane >= G) return;
         float *dst = out + row * ld_out + lane * V;
         if (V == 4 && vector_store) {
-            if (lane * V < d) *reinterpret_cast<float4 *>(dst) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            if (lane * V < d)
+                *reinterpret_cast<float4 *>(dst) = make_float4(acc.pos[0], acc.pos[1], acc.pos[2], acc.pos[3]);
         } else {
 #pragma unroll
             for (int v = 0; v < V; ++v)
-                if (lane * V + v < d) dst[v] = acc[v];
+                if (lane * V + v < d) dst[v] = acc.pos[v];
         }
     }
 };
 
-// Fused layer: stored position g*V + v holds column g + G*v of the integer products; the
-// result is rescaled by dinv_i * alpha_j and either written as fp32 logits or turned directly
-// into the packed signs and the scale of the next layer's input.
+// Fused layer: stored position g*V + v holds column g + G*v of the stored products.  The
+// neighbour sum of the true products is  mul * acc + bias * sum|w| + (+-1)_j * sum w  (the last
+// term only with a folded last bit); it is rescaled by dinv_i * alpha_j and either written as
+// fp32 logits or turned directly into the packed signs and the scale of the next layer's input.
 struct EpilogueFused {
     const float *dinv_sqrt;
     const float *alpha;
     int d_out;
+    float mul;
+    float bias;
+    const uint64_t *last_bit_word;   // &w_bits[(K-1)/64] of column 0, or nullptr without folded bit
+    int64_t w_ld_words;
+    int last_bit_shift;              // (K-1) % 64
     float *logits;
     int64_t ld_logits;
     const float *next_shift;
@@ -195,17 +303,43 @@ struct EpilogueFused {
     uint64_t *next_bits;
     int64_t next_ld_words;
     float *next_scale;
+    int next_fold_last_sign;
+
     template <int G, int V>
-    __device__ __forceinline__ void operator()(int64_t row, int lane, const float (&acc)[V]) const
+    struct Lane {
+        float alpha[V];      // 0 for columns past d_out
+        float last[V];       // +-1: sign of the weight's last input bit, 0 without folded bit
+        float shift[V];
+        float mul[V];
+    };
+    template <int G, int V>
+    __device__ __forceinline__ void init(int lane, Lane<G, V> &c) const
+    {
+        const int g = lane & (G - 1);
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const int col = g + G * v;
+            const bool in = col < d_out;
+            c.alpha[v] = in ? alpha[col] : 0.0f;
+            c.last[v] = 0.0f;
+            if (in && last_bit_word != nullptr)
+                c.last[v] = ((last_bit_word[col * w_ld_words] >> last_bit_shift) & 1ull) ? 1.0f : -1.0f;
+            c.shift[v] = (in && next_shift != nullptr) ? next_shift[col] : 0.0f;
+            c.mul[v] = (in && next_mul != nullptr) ? next_mul[col] : 1.0f;
+        }
+    }
+    template <int G, int V>
+    __device__ __forceinline__ void finish(const Lane<G, V> &c, int64_t row, int lane, const RowAcc<V> &acc) const
     {
         const float di = dinv_sqrt[row];
         const int g = lane & (G - 1);
         const bool first_slot = lane < G;
+        const float base = bias * acc.sum_abs;
         float h[V];
 #pragma unroll
         for (int v = 0; v < V; ++v) {
-            const int col = g + G * v;
-            h[v] = col < d_out ? di * alpha[col] * acc[v] : 0.0f;
+            const float total = fmaf(mul, acc.pos[v], fmaf(c.last[v], acc.sum_signed, base));
+            h[v] = di * c.alpha[v] * total;
         }
         if (logits != nullptr) {
             if (first_slot) {
@@ -227,22 +361,35 @@ struct EpilogueFused {
         for (int v = 0; v < V; ++v) {
             const int col = g + G * v;
             const bool valid = first_slot && col < d_out;
-            const float th = (valid && next_shift != nullptr) ? next_shift[col] : 0.0f;
-            const float ml = (valid && next_mul != nullptr) ? next_mul[col] : 1.0f;
-            const uint64_t mask = __ballot(valid && h[v] >= th);   // only the low G lanes can be set
+            const uint64_t mask = __ballot(valid && h[v] >= c.shift[v]);   // only the low G lanes can be set
             words[(G * v) / 64] |= mask << ((G * v) % 64);
-            sum += valid ? fabsf((h[v] - th) * ml) : 0.0f;
+            sum += valid ? fabsf((h[v] - c.shift[v]) * c.mul[v]) : 0.0f;
         }
         sum = wave_sum(sum);
         const int n_words = (d_out + 63) >> 6;
 #pragma unroll
         for (int q = 0; q < kWords; ++q)
             if (lane == q && q < n_words) next_bits[row * next_ld_words + q] = words[q];
-        if (lane == 0) next_scale[row] = di * (sum / static_cast<float>(d_out));
+        if (lane == 0) {
+            float s = di * (sum / static_cast<float>(d_out));
+            if (next_fold_last_sign) {
+                uint64_t last = 0;
+#pragma unroll
+                for (int q = 0; q < kWords; ++q)
+                    if (q == ((d_out - 1) >> 6)) last = words[q];
+                if (((last >> ((d_out - 1) & 63)) & 1ull) == 0) s = -s;
+            }
+            next_scale[row] = s;
+        }
     }
 };
 
 // ---- the kernel ------------------------------------------------------------------------------
+// Rows are taken in plan order.  Workgroup b < n_block_rows owns one long row; every later
+// workgroup owns kRowsPerWave * 4 consecutive plan entries, wavefront w taking entries
+// base + w, base + w + 4, ... (neighbouring entries have similar lengths).
+constexpr int kRowsPerWave = 8;
+
 template <typename T, int G, int V, int WM, class Epilogue>
 __global__ __launch_bounds__(kBlock) void spmm_kernel(
     const int32_t *__restrict__ row_order, int64_t n, int64_t n_block_rows,
@@ -250,16 +397,16 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(
     const float *__restrict__ weights, const char *__restrict__ rows, int64_t row_bytes,
     int valid_positions, Epilogue epi)
 {
-    __shared__ float partial[kWavesPerBlock - 1][kWave][V];
+    __shared__ float partial[kWavesPerBlock - 1][V + 2][kWave];
     const int lane = lane_id();
     const int wave = wave_in_block();
     const int g = lane & (G - 1);
     const bool active = g * V < valid_positions;
     const char *lane_base = rows + static_cast<int64_t>(g) * V * sizeof(T);
 
-    float acc[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) acc[v] = 0.0f;
+    typename Epilogue::template Lane<G, V> ctx;
+    epi.template init<G, V>(lane, ctx);
+    RowAcc<V> acc;
 
     if (static_cast<int64_t>(blockIdx.x) < n_block_rows) {
         // one long row shared by the four wavefronts: contiguous quarters, multiples of 64
@@ -271,29 +418,40 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(
         int64_t q1 = q0 + chunk;
         if (q0 > p1) q0 = p1;
         if (q1 > p1) q1 = p1;
+        acc.clear();
         accumulate_range<T, G, V, WM>(col_idx, weights, lane_base, row_bytes, q0, q1, lane, active, acc);
-        reduce_slots<G, V>(acc);
+        reduce_slots<G, V, WM>(acc);
         if (wave > 0) {
 #pragma unroll
-            for (int v = 0; v < V; ++v) partial[wave - 1][lane][v] = acc[v];
+            for (int v = 0; v < V; ++v) partial[wave - 1][v][lane] = acc.pos[v];
+            partial[wave - 1][V][lane] = acc.sum_abs;
+            partial[wave - 1][V + 1][lane] = acc.sum_signed;
         }
         __syncthreads();
         if (wave == 0) {
 #pragma unroll
-            for (int w = 0; w < kWavesPerBlock - 1; ++w)
+            for (int w = 0; w < kWavesPerBlock - 1; ++w) {
 #pragma unroll
-                for (int v = 0; v < V; ++v) acc[v] += partial[w][lane][v];
-            epi.template operator()<G, V>(row, lane, acc);
+                for (int v = 0; v < V; ++v) acc.pos[v] += partial[w][v][lane];
+                acc.sum_abs += partial[w][V][lane];
+                acc.sum_signed += partial[w][V + 1][lane];
+            }
+            epi.template finish<G, V>(ctx, row, lane, acc);
         }
         return;
     }
-    const int64_t slot_index = n_block_rows + (static_cast<int64_t>(blockIdx.x) - n_block_rows) * kWavesPerBlock + wave;
-    if (slot_index >= n) return;
-    const int64_t row = row_order[slot_index];
-    const int64_t p0 = row_ptr[row], p1 = row_ptr[row + 1];
-    accumulate_range<T, G, V, WM>(col_idx, weights, lane_base, row_bytes, p0, p1, lane, active, acc);
-    reduce_slots<G, V>(acc);
-    epi.template operator()<G, V>(row, lane, acc);
+    const int64_t base = n_block_rows +
+                         (static_cast<int64_t>(blockIdx.x) - n_block_rows) * (kWavesPerBlock * kRowsPerWave);
+    for (int j = 0; j < kRowsPerWave; ++j) {
+        const int64_t entry = base + wave + j * kWavesPerBlock;
+        if (entry >= n) break;                                   // wave-uniform
+        const int64_t row = row_order[entry];
+        const int64_t p0 = row_ptr[row], p1 = row_ptr[row + 1];
+        acc.clear();
+        accumulate_range<T, G, V, WM>(col_idx, weights, lane_base, row_bytes, p0, p1, lane, active, acc);
+        reduce_slots<G, V, WM>(acc);
+        epi.template finish<G, V>(ctx, row, lane, acc);
+    }
 }
 
 template <typename T, int G, int V, int WM, class Epilogue>
@@ -302,7 +460,8 @@ static int launch_spmm_one(const bigcn_plan *plan, const int64_t *row_ptr, const
                            int valid_positions, const Epilogue &epi, hipStream_t stream)
 {
     const int64_t wave_rows = plan->n - plan->n_block_rows;
-    const int64_t blocks = plan->n_block_rows + (wave_rows + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t per_block = kWavesPerBlock * kRowsPerWave;
+    const int64_t blocks = plan->n_block_rows + (wave_rows + per_block - 1) / per_block;
     if (blocks == 0) return BIGCN_OK;
     hipLaunchKernelGGL((spmm_kernel<T, G, V, WM, Epilogue>), dim3(static_cast<unsigned>(blocks)),
                        dim3(kBlock), 0, stream, plan->row_order, plan->n, plan->n_block_rows, row_ptr,
@@ -343,31 +502,74 @@ static int groups_for(int64_t positions, int vec)
 RowLayout choose_layout(int64_t d_in, int64_t d_out)
 {
     RowLayout l;
-    l.vec = d_out > 256 ? 8 : 4;
+    if (d_in <= 256) {
+        l.kind = kI8;
+        l.vec = d_out > 256 ? 16 : 8;
+        l.fold_last = d_in == 256 ? 1 : 0;
+        l.k_eff = static_cast<int>(d_in) - l.fold_last;
+    } else {
+        l.kind = d_in <= 2048 ? kF16 : kF32;    // |c| <= d_in: integers up to 2048 are exact in fp16
+        l.vec = d_out > 256 ? 8 : 4;
+        l.fold_last = 0;
+        l.k_eff = static_cast<int>(d_in);
+    }
     l.groups = groups_for(d_out, l.vec);
-    l.half = d_in <= 2048 ? 1 : 0;      // |c| <= d_in: every integer up to 2048 is exact in fp16
+    l.embed_scale = 0;
+    if (l.kind == kI8) {
+        // The last four stored values belong to the last lane of the group and hold columns
+        // (G-1) + G*(V-4 .. V-1); when those lie past d_out the bytes are free for the scale.
+        // A row of at most 64 bytes is widened to make room: up to 128 bytes a row costs one
+        // cache line either way, and the separate scale gather (a second line) disappears.
+        if (d_out > l.groups * (l.vec - 3) - 1 && l.positions() <= 64) l.groups *= 2;
+        l.embed_scale = d_out <= l.groups * (l.vec - 3) - 1 ? 1 : 0;
+    }
     return l;
 }
 
 int launch_fused_spmm(const FusedSpmmArgs &a, hipStream_t stream)
 {
-    EpilogueFused epi{a.dinv_sqrt, a.alpha, static_cast<int>(a.d_out), a.logits, a.ld_logits,
-                      a.next_shift, a.next_mul, a.next_bits, a.next_ld_words, a.next_scale};
     const RowLayout &l = a.layout;
+    EpilogueFused epi{};
+    epi.dinv_sqrt = a.dinv_sqrt;
+    epi.alpha = a.alpha;
+    epi.d_out = static_cast<int>(a.d_out);
+    epi.mul = l.mul();
+    epi.bias = l.bias();
+    epi.last_bit_word = l.fold_last ? a.w_bits + (a.d_in - 1) / 64 : nullptr;
+    epi.w_ld_words = a.w_ld_words;
+    epi.last_bit_shift = static_cast<int>((a.d_in - 1) % 64);
+    epi.logits = a.logits;
+    epi.ld_logits = a.ld_logits;
+    epi.next_shift = a.next_shift;
+    epi.next_mul = a.next_mul;
+    epi.next_bits = a.next_bits;
+    epi.next_ld_words = a.next_ld_words;
+    epi.next_scale = a.next_scale;
+    epi.next_fold_last_sign = a.next_fold_last_sign;
     const int valid = l.positions();
     const int64_t rb = l.row_bytes();
-    if (l.half) {
-        if (l.vec == 8)
-            return launch_spmm_groups<__half, 8, kWeightGather>(l.groups, a.plan, a.row_ptr, a.col_idx,
-                                                                a.src_scale, a.c_rows, rb, valid, epi, stream);
-        return launch_spmm_groups<__half, 4, kWeightGather>(l.groups, a.plan, a.row_ptr, a.col_idx,
-                                                            a.src_scale, a.c_rows, rb, valid, epi, stream);
+#define BIGCN_FUSED(TT, VV)                                                                             \
+    return launch_spmm_groups<TT, VV, kWeightGather>(l.groups, a.plan, a.row_ptr, a.col_idx, a.src_scale, \
+                                                     a.c_rows, rb, valid, epi, stream)
+#define BIGCN_FUSED_EMBEDDED(TT, VV)                                                                    \
+    return launch_spmm_groups<TT, VV, kWeightEmbedded>(l.groups, a.plan, a.row_ptr, a.col_idx, nullptr, \
+                                                       a.c_rows, rb, valid, epi, stream)
+    if (l.kind == kI8 && l.embed_scale) {
+        if (l.vec == 16) BIGCN_FUSED_EMBEDDED(int8_t, 16);
+        BIGCN_FUSED_EMBEDDED(int8_t, 8);
     }
-    if (l.vec == 8)
-        return launch_spmm_groups<float, 8, kWeightGather>(l.groups, a.plan, a.row_ptr, a.col_idx,
-                                                           a.src_scale, a.c_rows, rb, valid, epi, stream);
-    return launch_spmm_groups<float, 4, kWeightGather>(l.groups, a.plan, a.row_ptr, a.col_idx,
-                                                       a.src_scale, a.c_rows, rb, valid, epi, stream);
+    if (l.kind == kI8) {
+        if (l.vec == 16) BIGCN_FUSED(int8_t, 16);
+        BIGCN_FUSED(int8_t, 8);
+    }
+    if (l.kind == kF16) {
+        if (l.vec == 8) BIGCN_FUSED(__half, 8);
+        BIGCN_FUSED(__half, 4);
+    }
+    if (l.vec == 8) BIGCN_FUSED(float, 8);
+    BIGCN_FUSED(float, 4);
+#undef BIGCN_FUSED
+#undef BIGCN_FUSED_EMBEDDED
 }
 
 }  // namespace bigcn

@@ -108,3 +108,33 @@ def test_forward_layer_chain_equals_separate_kernels(B):
     a_tilde = oracle.gcn_norm(work.row_ptr, work.col_idx)
     rec = oracle.layer(work.row_ptr, work.col_idx, a_tilde, work.x, work.weights[0], shift, mul)
     assert_close(h1, rec["out"], "H1 through separate kernels")
+
+
+@pytest.mark.parametrize("d_in", [64, 100, 254, 255, 256, 257, 2048, 2049])
+def test_forward_extreme_products(B, d_in):
+    """Nodes whose sign pattern equals, or is the exact opposite of, a weight column give the
+    extreme products +K and -K: the ends of the range of every compact product-row format
+    (one byte per product up to K = 256, where the last input bit is carried separately;
+    fp16 up to K = 2048; fp32 beyond)."""
+    from workloads import chung_lu_csr
+    from workloads.build import Workload
+    from workloads.configs import WorkloadConfig
+    rng = np.random.default_rng(d_in)
+    n, d_hidden, d_out = 400, 256, 5
+    rp, ci = chung_lu_csr(n, 3000, 2.5, 2.0, seed=d_in)
+    w0 = rng.uniform(-1, 1, size=(d_in, d_hidden)).astype(np.float32)
+    w1 = rng.uniform(-1, 1, size=(d_hidden, d_out)).astype(np.float32)
+    x = rng.standard_normal((n, d_in)).astype(np.float32)
+    for k in range(0, 120):
+        j = (7 * k) % d_hidden
+        x[k] = w0[:, j] if k % 2 == 0 else -w0[:, j]      # products +K / -K in column j
+    x[120] = np.abs(x[120])                                 # all +1
+    x[121] = -np.abs(x[121]) - 1e-3                         # all -1
+    cfg = WorkloadConfig("extreme", "none", n, 3000, 2.0, (d_in, d_hidden, d_out), "normal", 1.0,
+                         "first", 0)
+    work = Workload(cfg, rp, ci, x, [w0, w1])
+    bn = [None, None]
+    _, recs = oracle.forward(rp, ci, x, [w0, w1], bn=bn, keep_trace=True)
+    assert recs[0]["acc"].max() == d_in and recs[0]["acc"].min() == -d_in
+    stats = compare_forward_layerwise(work, bn, gpu_prefix_runner(B, work, bn), cancellation_aware=True)
+    assert stats[-1]["rows_compared"] >= 0.5 * n

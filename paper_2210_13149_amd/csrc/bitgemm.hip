@@ -40,8 +40,19 @@ struct EpilogueApi {
     int64_t ld_out;
     int k_bits;
     template <int VB>
-    __device__ __forceinline__ void store(int64_t row, const int (&col)[VB], int /*pos0*/, bool /*any*/,
-                                          int n, const int (&pop)[VB]) const
+    struct Lane {
+        float b_scale[VB];   // per-lane constants: the scales of this lane's columns
+    };
+    template <int VB>
+    __device__ __forceinline__ void init(const int (&col)[VB], int n, Lane<VB> &c) const
+    {
+#pragma unroll
+        for (int v = 0; v < VB; ++v)
+            c.b_scale[v] = (out != nullptr && col[v] >= 0 && col[v] < n) ? b_scale[col[v]] : 0.0f;
+    }
+    template <int VB>
+    __device__ __forceinline__ void store(const Lane<VB> &ctx, int64_t row, const int (&col)[VB], int /*pos0*/,
+                                          bool /*any*/, int n, const int (&pop)[VB]) const
     {
         const float sa = out != nullptr ? a_scale[row] : 0.0f;
 #pragma unroll
@@ -50,7 +61,7 @@ struct EpilogueApi {
             if (j >= 0 && j < n) {
                 const int c = k_bits - 2 * pop[v];
                 if (acc != nullptr) acc[row * ld_acc + j] = c;
-                if (out != nullptr) out[row * ld_out + j] = sa * b_scale[j] * static_cast<float>(c);
+                if (out != nullptr) out[row * ld_out + j] = sa * ctx.b_scale[v] * static_cast<float>(c);
             }
         }
     }
@@ -65,8 +76,12 @@ struct EpilogueLayout {
     int k_eff;
     const float *embed;      // non-null (int8 rows only): scale[row] goes into the last 4 bytes
     template <int VB>
-    __device__ __forceinline__ void store(int64_t row, const int (&col)[VB], int pos0, bool any, int n,
-                                          const int (&pop)[VB]) const
+    struct Lane {};
+    template <int VB>
+    __device__ __forceinline__ void init(const int (&)[VB], int, Lane<VB> &) const {}
+    template <int VB>
+    __device__ __forceinline__ void store(const Lane<VB> &, int64_t row, const int (&col)[VB], int pos0, bool any,
+                                          int n, const int (&pop)[VB]) const
     {
         if (!any) return;
         alignas(16) T tmp[VB];
@@ -142,6 +157,8 @@ __global__ __launch_bounds__(kBlock) void bitgemm_kernel(
         any = any || vv < map.vec;
     }
     const int pos0 = (lane % map.groups) * map.vec + map.per_group * (lane / map.groups) + y * VB;
+    typename Epilogue::template Lane<VB> ctx;
+    epi.template init<VB>(col, n, ctx);
 
     const int64_t wave = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block();
     const int64_t n_waves = static_cast<int64_t>(gridDim.x) * kWavesPerBlock;
@@ -207,7 +224,7 @@ __global__ __launch_bounds__(kBlock) void bitgemm_kernel(
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             if (row0 + r >= m) break;                               // wave-uniform
-            epi.template store<VB>(row0 + r, col, pos0, any, n, pop[r]);
+            epi.template store<VB>(ctx, row0 + r, col, pos0, any, n, pop[r]);
         }
     }
 }
@@ -219,10 +236,15 @@ static int launch_bitgemm(const uint64_t *a, int64_t m, int64_t lda, const uint6
 {
     const int n_words = static_cast<int>((k_bits + 63) / 64);
     const size_t lds = static_cast<size_t>(64) * VB * n_words * sizeof(uint64_t);
-    // every workgroup stages its B block once: give each at least 16 row blocks per wave
+    // one row block per wavefront until the chip is full, then grid-stride: every workgroup
+    // stages its B block once, so no more workgroups are launched than can be resident
+    // (8 per CU, fewer when the staged block is large; 160 KB of LDS per CU)
     int64_t row_blocks = (m + R - 1) / R;
-    int64_t blocks = (row_blocks + kWavesPerBlock * 16 - 1) / (kWavesPerBlock * 16);
-    const int64_t cap = 256 * 8;
+    int64_t blocks = (row_blocks + kWavesPerBlock - 1) / kWavesPerBlock;
+    int64_t resident = lds > 0 ? static_cast<int64_t>((160 * 1024) / lds) : 8;
+    resident = resident > 8 ? 8 : (resident < 1 ? 1 : resident);
+    int64_t cap = 256 * resident / col_blocks;
+    if (cap < 256) cap = 256;
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL((bitgemm_kernel<VB, R, Epilogue>), dim3(static_cast<unsigned>(blocks), col_blocks),

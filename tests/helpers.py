@@ -56,15 +56,20 @@ def sign_error_bound(row_ptr, col_idx, a_tilde, zeta) -> np.ndarray:
     return (terms + 4.0) * 2.0 ** -24 * mag
 
 
-def compare_forward_layerwise(work, bn, run_gpu_prefix, cancellation_aware=False):
+def compare_forward_layerwise(work, bn, run_gpu_prefix, cancellation_aware=False, log=None):
     """Layer-by-layer parity of the fused forward against the oracle.
 
-    ``run_gpu_prefix(l)`` must return the GPU result of the first ``l`` layers (fp32 H^(l),
-    numpy).  Every H^(l) is compared with the oracle's on all rows whose inputs were identical on
-    both sides.  Where the GPU's fp32 value of a hidden activation falls on the other side of its
-    threshold than the oracle's, the element must lie within the fp32 error bound of the
-    threshold (both signs are then valid results); such rows, and the rows they feed, are left
-    out of the comparison of later layers.  Returns per-layer statistics.
+    ``bn[l]`` is the frozen standardisation ``(shift, mul)`` of layer l's input, ``None`` for no
+    standardisation, or the string ``"calibrate"``: the parameters are then computed here from
+    the oracle's own input of that layer and handed to the GPU side as fp32.
+    ``run_gpu_prefix(l, params)`` must return the GPU result of the first ``l`` layers (fp32
+    H^(l), numpy) using ``params[:l]``.  Every H^(l) is compared with the oracle's on all rows
+    whose inputs were identical on both sides.  Where the GPU's fp32 value of a hidden activation
+    falls on the other side of its threshold than the oracle's, the element must lie within the
+    fp32 error bound of the threshold (both signs are then valid results); such rows, and the
+    rows they feed, are left out of the comparison of later layers.  The oracle runs one layer at
+    a time so that only one layer's intermediates are alive.  Nothing flows from the GPU into
+    the oracle.  Returns per-layer statistics.
 
     ``cancellation_aware`` (adversarial inputs only): an element also passes when its error is
     within the fp32 rounding bound of its own sum, ``sign_error_bound``; with products of
@@ -72,41 +77,49 @@ def compare_forward_layerwise(work, bn, run_gpu_prefix, cancellation_aware=False
     fp32 evaluation order resolves to 1e-5 of the result.
     """
     import oracle
+    say = log if log is not None else (lambda *a: None)
     n_layers = len(work.weights)
-    logits, recs = oracle.forward(work.row_ptr, work.col_idx, work.x, work.weights, bn=bn,
-                                  keep_trace=True)
     a_tilde = oracle.gcn_norm(work.row_ptr, work.col_idx)
     tainted = np.zeros(work.n, dtype=bool)
+    params = []
     stats = []
+    h = work.x
     for l in range(1, n_layers + 1):
-        ref = recs[l - 1]["out"]
-        gpu = run_gpu_prefix(l)
+        p = bn[l - 1]
+        if isinstance(p, str):
+            assert p == "calibrate"
+            p = oracle.column_standardisation(h)
+        params.append(p)
+        shift, mul = p if p is not None else (None, None)
+        if l > 1:
+            # signs of this layer's input as the oracle takes them, against the GPU's previous output
+            th = np.zeros(h.shape[1], dtype=np.float32) if shift is None else shift
+            flips = (gpu >= th[None, :]) != (h.astype(np.float32) >= th[None, :])
+            margin = np.abs(h - th[None, :].astype(np.float64))
+            illegal = flips & clean[:, None] & (margin > bound + 1e-30)
+            assert not illegal.any(), (f"layer {l - 1}: {int(illegal.sum())} sign bits differ from "
+                                       f"the oracle outside the fp32 error bound")
+            stats[-1]["sign_flips"] = int((flips & clean[:, None]).sum())
+            tainted = neighbours_closed(work.row_ptr, work.col_idx, tainted | flips.any(axis=1))
+            del flips, margin, illegal, bound, gpu
+        rec = oracle.layer(work.row_ptr, work.col_idx, a_tilde, h, work.weights[l - 1], shift, mul)
+        say(f"oracle layer {l} done")
+        ref = rec["out"]
+        bound = sign_error_bound(work.row_ptr, work.col_idx, a_tilde, rec["zeta"])
+        del rec
+        gpu = run_gpu_prefix(l, params)
+        say(f"gpu prefix {l} done")
         assert gpu.shape == ref.shape
         ok = close(gpu, ref)
         if cancellation_aware:
-            ok |= np.abs(gpu - ref) <= sign_error_bound(work.row_ptr, work.col_idx, a_tilde,
-                                                        recs[l - 1]["zeta"])
+            ok |= np.abs(gpu - ref) <= bound
         clean = ~tainted
         if not ok[clean].all():
             bad = np.argwhere(~ok & clean[:, None])
             i = tuple(bad[0])
             raise AssertionError(f"layer {l}: {bad.shape[0]} elements out of tolerance on rows with "
                                  f"identical inputs; first at {i}: gpu={gpu[i]!r} ref={ref[i]!r}")
-        flips_rows = np.zeros(work.n, dtype=bool)
-        n_flips = 0
-        if l < n_layers:
-            shift = recs[l]["shift"]
-            th = np.zeros(ref.shape[1], dtype=np.float32) if shift is None else shift
-            gpu_sign = gpu >= th[None, :]
-            ref_sign = recs[l]["sign"] > 0
-            flips = gpu_sign != ref_sign
-            bound = sign_error_bound(work.row_ptr, work.col_idx, a_tilde, recs[l - 1]["zeta"])
-            margin = np.abs(ref - th[None, :].astype(np.float64))
-            illegal = flips & clean[:, None] & (margin > bound + 1e-30)
-            assert not illegal.any(), (f"layer {l}: {int(illegal.sum())} sign bits differ from the "
-                                       f"oracle outside the fp32 error bound")
-            flips_rows = flips.any(axis=1)
-            n_flips = int((flips & clean[:, None]).sum())
-        stats.append({"layer": l, "rows_compared": int(clean.sum()), "sign_flips": n_flips})
-        tainted = neighbours_closed(work.row_ptr, work.col_idx, tainted | flips_rows) if l < n_layers else tainted
+        del ok
+        stats.append({"layer": l, "rows_compared": int(clean.sum()), "sign_flips": 0})
+        h = ref
     return stats

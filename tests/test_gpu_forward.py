@@ -24,26 +24,35 @@ def B():
     return binding
 
 
+def calibration_spec(work):
+    """Which layers standardise their input (first layer only, or every layer, as the workload
+    prescribes); the parameters themselves are computed by the oracle during the comparison."""
+    cfg = work.config
+    return ["calibrate"] + ["calibrate" if cfg.bn_layers == "all" else None] * (cfg.n_layers - 1)
+
+
 def calibrated_bn(work):
     """Frozen standardisation parameters per layer, computed by the oracle from its own
-    activations (first layer only, or every layer, as the workload prescribes)."""
-    cfg = work.config
-    calibrate = [True] + [cfg.bn_layers == "all"] * (cfg.n_layers - 1)
+    activations."""
+    calibrate = [p == "calibrate" for p in calibration_spec(work)]
     _, recs = oracle.forward(work.row_ptr, work.col_idx, work.x, work.weights, calibrate=calibrate)
     return [(r["shift"], r["mul"]) if r["shift"] is not None else None for r in recs]
 
 
-def gpu_prefix_runner(B, work, bn):
+def gpu_prefix_runner(B, work):
+    """run(l, params): fused forward over the first l layers with params[:l] as standardisation."""
     import torch
     drp, dci, dx = to_device(work.row_ptr, work.col_idx, work.x)
     dweights = [to_device(w) for w in work.weights]
-    dbn = [None if p is None else tuple(to_device(*p)) for p in bn]
     plan = B.Plan(drp, dci)
     dinv, _ = B.bigcn_gcn_norm(drp, dci)
-    layers = [B.Layer.from_weight(w, *(p if p is not None else (None, None)))
-              for w, p in zip(dweights, dbn)]
+    layers = []
 
-    def run(l):
+    def run(l, params):
+        while len(layers) < l:
+            p = params[len(layers)]
+            shift, mul = (None, None) if p is None else tuple(to_device(*p))
+            layers.append(B.Layer.from_weight(dweights[len(layers)], shift, mul))
         out = B.bigcn_forward(plan, drp, dci, dinv, dx, layers[:l])
         torch.cuda.synchronize()
         return out.cpu().numpy()
@@ -56,8 +65,7 @@ def gpu_prefix_runner(B, work, bn):
 def test_forward_matches_oracle(B, name, n_scaled):
     cfg = get_config(name) if n_scaled is None else scaled_config(name, n_scaled)
     work = make_workload(cfg)
-    bn = calibrated_bn(work)
-    stats = compare_forward_layerwise(work, bn, gpu_prefix_runner(B, work, bn))
+    stats = compare_forward_layerwise(work, calibration_spec(work), gpu_prefix_runner(B, work))
     print(name, stats)
     # a legal sign flip removes its two-hop neighbourhood from the comparison of later layers;
     # most rows must still take part in the comparison of the logits
@@ -68,10 +76,10 @@ def test_forward_without_standardisation_and_repeatability(B):
     import torch
     work = make_workload(scaled_config("c5", 5000))
     bn = [None] * work.config.n_layers
-    run = gpu_prefix_runner(B, work, bn)
+    run = gpu_prefix_runner(B, work)
     stats = compare_forward_layerwise(work, bn, run)
     assert stats[-1]["rows_compared"] >= 0.5 * work.n
-    a, b = run(work.config.n_layers), run(work.config.n_layers)
+    a, b = run(work.config.n_layers, bn), run(work.config.n_layers, bn)
     assert np.array_equal(a, b)
 
 
@@ -136,5 +144,5 @@ def test_forward_extreme_products(B, d_in):
     bn = [None, None]
     _, recs = oracle.forward(rp, ci, x, [w0, w1], bn=bn, keep_trace=True)
     assert recs[0]["acc"].max() == d_in and recs[0]["acc"].min() == -d_in
-    stats = compare_forward_layerwise(work, bn, gpu_prefix_runner(B, work, bn), cancellation_aware=True)
+    stats = compare_forward_layerwise(work, bn, gpu_prefix_runner(B, work), cancellation_aware=True)
     assert stats[-1]["rows_compared"] >= 0.5 * n

@@ -1,0 +1,74 @@
+"""Parity at the full size of the two large workloads, in the launch configuration that
+bench.py times (same generator, same fused driver, standardisation before every layer).
+
+The oracle runs the whole graph (tens of seconds of host time), one layer at a time; every
+layer's output is compared element by element on all rows whose inputs were identical on both
+sides (helpers.compare_forward_layerwise).  Properties that hold at any size are checked too:
+the aggregation reproduces sqrt(degree) under A~, and two runs are bit-identical.
+"""
+import sys
+import time
+
+import numpy as np
+import pytest
+
+from helpers import assert_close, compare_forward_layerwise, to_device
+from test_gpu_forward import calibration_spec, gpu_prefix_runner
+from workloads import make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    from paper_2210_13149_amd import binding
+    assert torch.cuda.is_available()
+    binding.lib()
+    return binding
+
+
+def _say(t0):
+    def say(msg):
+        print(f"[{time.time() - t0:6.1f} s] {msg}", file=sys.stderr, flush=True)
+    return say
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["c4", "c5"])
+def test_full_size_forward_matches_oracle(B, name):
+    import torch
+    t0 = time.time()
+    say = _say(t0)
+    say(f"{name}: generating")
+    work = make_workload(name)
+    say(f"{name}: {work.n} nodes, {work.nnz} stored entries")
+    run = gpu_prefix_runner(B, work)
+    stats = compare_forward_layerwise(work, calibration_spec(work), run, log=say)
+    say(f"{name}: {stats}")
+    print(name, stats)
+    # every layer compared on at least half of the nodes, the first on all of them
+    assert stats[0]["rows_compared"] == work.n
+    assert all(s["rows_compared"] >= 0.5 * work.n for s in stats)
+    # at most a few in a million hidden activations may fall on the other side of a threshold
+    for s, d in zip(stats[:-1], work.config.dims[1:-1]):
+        assert s["sign_flips"] <= 5e-6 * work.n * d + 5
+
+
+@pytest.mark.timeout(600)
+def test_full_size_aggregation_invariant_and_repeatability(B):
+    """A~ sqrt(d) = sqrt(d) on the largest graph through the public SpMM, twice, bit-identical."""
+    import torch
+    work = make_workload("c5")
+    drp, dci = to_device(work.row_ptr, work.col_idx)
+    plan = B.Plan(drp, dci)
+    _, vals = B.bigcn_gcn_norm(drp, dci, want_vals=True)
+    rootd = np.sqrt(np.diff(work.row_ptr).astype(np.float32))
+    z = np.repeat(rootd[:, None], 8, axis=1)
+    z[:, 1::2] *= -1.0
+    dz = to_device(np.ascontiguousarray(z))
+    out = B.bigcn_spmm(plan, drp, dci, vals, dz)
+    again = B.bigcn_spmm(plan, drp, dci, vals, dz)
+    torch.cuda.synchronize()
+    assert torch.equal(out, again)
+    assert_close(out.cpu().numpy(), z.astype(np.float64), "A~ sqrt(d)")

@@ -34,7 +34,8 @@ def make_workload(cfg) -> Workload:
     independent streams derived from the config's seed, so each can be regenerated alone."""
     if isinstance(cfg, str):
         cfg = get_config(cfg)
-    row_ptr, col_idx = chung_lu_csr(cfg.n_nodes, cfg.n_edges, cfg.gamma, cfg.i0, seed=cfg.seed)
+    row_ptr, col_idx = chung_lu_csr(cfg.n_nodes, cfg.n_edges, cfg.gamma, cfg.i0, seed=cfg.seed,
+                                    shuffle_ids=cfg.shuffle_ids)
     rng_x = np.random.Generator(np.random.PCG64([cfg.seed, 1]))
     rng_w = np.random.Generator(np.random.PCG64([cfg.seed, 2]))
     x = make_features(cfg.feature_kind, cfg.n_nodes, cfg.dims[0], cfg.feature_density, rng_x)

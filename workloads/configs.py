@@ -27,6 +27,7 @@ class WorkloadConfig:
     bn_layers: str             # "first" (input features only) or "all" (before every layer)
     seed: int
     gamma: float = 2.5         # power-law exponent of the expected-degree sequence
+    shuffle_ids: bool = True   # random node relabelling (False: ids by decreasing expected degree)
 
     @property
     def n_layers(self) -> int:

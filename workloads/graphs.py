@@ -66,13 +66,15 @@ def _sorted_unique_inplace(keys: np.ndarray) -> np.ndarray:
     return keys[keep]
 
 
-def chung_lu_edges(n: int, n_edges: int, gamma: float, i0: float, rng: np.random.Generator):
+def chung_lu_edges(n: int, n_edges: int, gamma: float, i0: float, rng: np.random.Generator,
+                   shuffle_ids: bool = True):
     """Exactly ``n_edges`` distinct undirected edges whose two endpoints are drawn
     independently from a power law over node ranks, w_i ~ (i + i0)^(-1/(gamma-1)).
 
     Pairs with equal endpoints and repeated pairs are rejected and redrawn, so the
     heaviest nodes end up somewhat below their expected degree when the graph is dense.
-    Node ids are randomly relabelled afterwards (real datasets are not degree-sorted).
+    Node ids are randomly relabelled afterwards (real datasets are not degree-sorted) unless
+    ``shuffle_ids`` is False, in which case ids follow decreasing expected degree.
     """
     if n < 2:
         raise ValueError("need at least two nodes")
@@ -105,15 +107,18 @@ def chung_lu_edges(n: int, n_edges: int, gamma: float, i0: float, rng: np.random
         keys = keys[keep]
     lo = keys // n
     hi = keys - lo * n
+    if not shuffle_ids:
+        return lo, hi
     relabel = rng.permutation(n)
     return relabel[lo], relabel[hi]
 
 
-def chung_lu_csr(n: int, n_edges: int, gamma: float = 2.5, i0: float = 1.0, seed: int = 0):
+def chung_lu_csr(n: int, n_edges: int, gamma: float = 2.5, i0: float = 1.0, seed: int = 0,
+                 shuffle_ids: bool = True):
     """Symmetric CSR pattern of A + I for a seeded Chung-Lu graph.
 
     Returns (row_ptr int64[n+1], col_idx int32[2*n_edges + n]).
     """
     rng = np.random.Generator(np.random.PCG64(seed))
-    u, v = chung_lu_edges(n, n_edges, gamma, i0, rng)
+    u, v = chung_lu_edges(n, n_edges, gamma, i0, rng, shuffle_ids)
     return csr_from_undirected_edges(n, u, v)

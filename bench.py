@@ -25,7 +25,7 @@ VALU_BINARY_MAC_PEAK = 256 * 4 * 16 * 2.4e9 * 32 / 2   # 2 VALU instructions per
 
 # HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE, scaled by a copy kernel of known size); see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"c5": 7.95e10}    # profiles/spmm_fused_c5.md
+MEASURED_TRAFFIC_BYTES = {"c5": 4.65e10}    # profiles/spmm_fused_c5.md
 
 
 def log(*a):

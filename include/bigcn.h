@@ -96,6 +96,20 @@ int bigcn_binary_gemm(const uint64_t *a_bits, const float *a_scale, int64_t m,
                       int64_t ld_acc, float *out, int64_t ld_out, void *stream);
 
 /*
+ * The same product with the evaluation path chosen by the caller (benchmarking and tests):
+ * BIGCN_GEMM_AUTO picks per shape (what bigcn_binary_gemm does), BIGCN_GEMM_VALU evaluates
+ * XOR + bit count on the vector ALU, BIGCN_GEMM_MFMA expands the bits to +-1 bytes and uses
+ * the int8 matrix cores.  All paths give bit-identical acc and identical out.
+ * Errors: as bigcn_binary_gemm, plus EINVAL for an unknown variant.
+ */
+enum { BIGCN_GEMM_AUTO = 0, BIGCN_GEMM_VALU = 1, BIGCN_GEMM_MFMA = 2 };
+int bigcn_binary_gemm_variant(const uint64_t *a_bits, const float *a_scale, int64_t m,
+                              int64_t lda_words, const uint64_t *b_bits, const float *b_scale,
+                              int64_t n, int64_t ldb_words, int64_t k_bits, int32_t *acc,
+                              int64_t ld_acc, float *out, int64_t ld_out, int variant,
+                              void *stream);
+
+/*
  * Normalisation coefficients of A~ = D^-1/2 (A+I) D^-1/2 (Sec. 3.1 Notations, Eq. (1)).
  * The CSR arrays describe the pattern of A + I: symmetric, one self-loop per node,
  * columns strictly increasing inside a row; D_ii is the number of stored entries of row i.

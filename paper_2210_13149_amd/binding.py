@@ -25,10 +25,12 @@ BIGCN_EWORKSPACE = -4
 BIGCN_EGRAPH = -5
 BIGCN_EHIP = -6
 MAX_K_BITS = 8192
+GEMM_AUTO, GEMM_VALU, GEMM_MFMA = 0, 1, 2
 MAX_FORWARD_D_OUT = 512
 
 EXPORTS = (
-    "bigcn_status_string", "bigcn_version", "bigcn_pack", "bigcn_binary_gemm", "bigcn_gcn_norm",
+    "bigcn_status_string", "bigcn_version", "bigcn_pack", "bigcn_binary_gemm",
+    "bigcn_binary_gemm_variant", "bigcn_gcn_norm",
     "bigcn_plan_create", "bigcn_plan_destroy", "bigcn_plan_rows", "bigcn_plan_nnz", "bigcn_spmm",
     "bigcn_forward_workspace_bytes", "bigcn_forward_row_bytes", "bigcn_forward", "bigcn_profile_create",
     "bigcn_profile_destroy", "bigcn_forward_profiled", "bigcn_profile_read",
@@ -71,6 +73,9 @@ def lib() -> ctypes.CDLL:
         L.bigcn_pack.argtypes = [vp, i64, i64, i64, i64, vp, vp, vp, i64, vp, vp]
         L.bigcn_binary_gemm.restype = i32
         L.bigcn_binary_gemm.argtypes = [vp, vp, i64, i64, vp, vp, i64, i64, i64, vp, i64, vp, i64, vp]
+        L.bigcn_binary_gemm_variant.restype = i32
+        L.bigcn_binary_gemm_variant.argtypes = [vp, vp, i64, i64, vp, vp, i64, i64, i64, vp, i64, vp, i64,
+                                                i32, vp]
         L.bigcn_gcn_norm.restype = i32
         L.bigcn_gcn_norm.argtypes = [vp, vp, i64, vp, vp, vp]
         L.bigcn_plan_create.restype = i32
@@ -171,8 +176,11 @@ def pack_weight(w: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
 # ------------------------------------------------------------------------------------------
 def bigcn_binary_gemm(a_bits: torch.Tensor, a_scale: Optional[torch.Tensor], b_bits: torch.Tensor,
                       b_scale: Optional[torch.Tensor], k_bits: int, want_acc: bool = True,
-                      want_out: bool = True) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor]]:
-    """``acc = K - 2 popcount(a xor b)`` (int32) and / or ``out = a_scale_i b_scale_j acc``."""
+                      want_out: bool = True, variant: int = 0
+                      ) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor]]:
+    """``acc = K - 2 popcount(a xor b)`` (int32) and / or ``out = a_scale_i b_scale_j acc``.
+    ``variant``: GEMM_AUTO (per shape), GEMM_VALU (XOR + bit count) or GEMM_MFMA (int8 matrix
+    cores)."""
     _dev(a_bits, torch.int64, "a_bits")
     _dev(b_bits, torch.int64, "b_bits")
     m, n = a_bits.shape[0], b_bits.shape[0]
@@ -181,9 +189,12 @@ def bigcn_binary_gemm(a_bits: torch.Tensor, a_scale: Optional[torch.Tensor], b_b
     if want_out:
         _dev(a_scale, torch.float32, "a_scale")
         _dev(b_scale, torch.float32, "b_scale")
-    _check(lib().bigcn_binary_gemm(_ptr(a_bits), _ptr(a_scale), m, a_bits.stride(0), _ptr(b_bits),
-                                   _ptr(b_scale), n, b_bits.stride(0), int(k_bits), _ptr(acc), n,
-                                   _ptr(out), n, _stream()), "bigcn_binary_gemm")
+    args = (_ptr(a_bits), _ptr(a_scale), m, a_bits.stride(0), _ptr(b_bits), _ptr(b_scale), n,
+            b_bits.stride(0), int(k_bits), _ptr(acc), n, _ptr(out), n)
+    if variant == GEMM_AUTO:
+        _check(lib().bigcn_binary_gemm(*args, _stream()), "bigcn_binary_gemm")
+    else:
+        _check(lib().bigcn_binary_gemm_variant(*args, int(variant), _stream()), "bigcn_binary_gemm_variant")
     return acc, out
 
 

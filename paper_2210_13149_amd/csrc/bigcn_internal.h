@@ -89,6 +89,12 @@ int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const 
                           int64_t n, int64_t ldb, int64_t k_bits, const float *src_scale, void *c_rows,
                           RowLayout layout, hipStream_t stream);
 
+// Matrix-core (int8 MFMA) variant of the public bit-GEMM: same arguments and results.
+int launch_bitgemm_mfma(const uint64_t *a_bits, const float *a_scale, int64_t m, int64_t lda,
+                        const uint64_t *b_bits, const float *b_scale, int64_t n, int64_t ldb,
+                        int64_t k_bits, int32_t *acc, int64_t ld_acc, float *out, int64_t ld_out,
+                        hipStream_t stream);
+
 // Aggregation of layer l fused with the rescale and with the binarisation of layer l+1.
 struct FusedSpmmArgs {
     const bigcn_plan *plan;

@@ -17,6 +17,8 @@
 
 namespace bigcn {
 
+bool prefer_mfma(int64_t m, int64_t n, int64_t k_bits);
+
 // Lane l, local index v (0..VB-1), column block y:
 //   value index inside the stored row   vv  = per_group * (l / groups) + y * VB + v
 //   output column                       col = (l % groups) + groups * vv
@@ -296,13 +298,22 @@ int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const 
                             last_mask, epi, stream);
 }
 
+// Shapes on which the matrix-core variant measured faster (see the design notes): enough
+// inner dimension to be compute-bound and enough rows and columns to fill its 256 x 64 tiles.
+bool prefer_mfma(int64_t m, int64_t n, int64_t k_bits)
+{
+    return k_bits >= 1024 && n >= 48 && m >= 4096;
+}
+
 }  // namespace bigcn
 
-extern "C" int bigcn_binary_gemm(const uint64_t *a_bits, const float *a_scale, int64_t m,
-                                 int64_t lda_words, const uint64_t *b_bits, const float *b_scale,
-                                 int64_t n, int64_t ldb_words, int64_t k_bits, int32_t *acc,
-                                 int64_t ld_acc, float *out, int64_t ld_out, void *stream)
+extern "C" int bigcn_binary_gemm_variant(const uint64_t *a_bits, const float *a_scale, int64_t m,
+                                         int64_t lda_words, const uint64_t *b_bits, const float *b_scale,
+                                         int64_t n, int64_t ldb_words, int64_t k_bits, int32_t *acc,
+                                         int64_t ld_acc, float *out, int64_t ld_out, int variant,
+                                         void *stream)
 {
+    if (variant < BIGCN_GEMM_AUTO || variant > BIGCN_GEMM_MFMA) return BIGCN_EINVAL;
     if (a_bits == nullptr || b_bits == nullptr) return BIGCN_ENULL;
     if (acc == nullptr && out == nullptr) return BIGCN_ENULL;
     if (out != nullptr && (a_scale == nullptr || b_scale == nullptr)) return BIGCN_ENULL;
@@ -313,9 +324,21 @@ extern "C" int bigcn_binary_gemm(const uint64_t *a_bits, const float *a_scale, i
     if (out != nullptr && ld_out < n) return BIGCN_EINVAL;
     if (k_bits > BIGCN_MAX_K_BITS || n > BIGCN_MAX_GEMM_N) return BIGCN_ESHAPE;
     if (m == 0 || n == 0) return BIGCN_OK;
+    if (variant == BIGCN_GEMM_MFMA || (variant == BIGCN_GEMM_AUTO && bigcn::prefer_mfma(m, n, k_bits)))
+        return bigcn::launch_bitgemm_mfma(a_bits, a_scale, m, lda_words, b_bits, b_scale, n, ldb_words, k_bits,
+                                          acc, ld_acc, out, ld_out, bigcn::as_stream(stream));
     bigcn::EpilogueApi epi{a_scale, b_scale, acc, ld_acc, out, ld_out, static_cast<int>(k_bits)};
     // row-major output: lane l owns columns l, l + 64, ...
     const int per_lane = static_cast<int>((n + 63) / 64);
     return bigcn::dispatch_bitgemm(per_lane, 64, per_lane, a_bits, m, lda_words, b_bits, n, ldb_words,
                                    k_bits, 0xffffffffu, epi, bigcn::as_stream(stream));
+}
+
+extern "C" int bigcn_binary_gemm(const uint64_t *a_bits, const float *a_scale, int64_t m,
+                                 int64_t lda_words, const uint64_t *b_bits, const float *b_scale,
+                                 int64_t n, int64_t ldb_words, int64_t k_bits, int32_t *acc,
+                                 int64_t ld_acc, float *out, int64_t ld_out, void *stream)
+{
+    return bigcn_binary_gemm_variant(a_bits, a_scale, m, lda_words, b_bits, b_scale, n, ldb_words, k_bits,
+                                     acc, ld_acc, out, ld_out, BIGCN_GEMM_AUTO, stream);
 }

@@ -1,0 +1,170 @@
+// Kernel 2, matrix-core variant: the +-1 inner products of Sec. 4.2.3 evaluated with the
+// int8 MFMA of gfx950 (v_mfma_i32_32x32x32_i8) instead of XOR + bit count.
+//
+// The packed operands are expanded on the fly.  A (node rows) is expanded to bytes in {0, 1}
+// (three VALU operations per four elements), B (weight columns) to bytes in {-1, +1}, once per
+// workgroup and K chunk, into LDS.  With a in {0,1} and f = 2a - 1:
+//     sum_k f_k b_k = 2 * sum_k a_k b_k - sum_k b_k ,
+// so the matrix core accumulates sum_k a_k b_k exactly in int32 and the epilogue subtracts the
+// column sum of B (2 popcount(B_j) - K).  Pad bits of A are 0 and therefore contribute nothing.
+//
+// Tiling for wave64: a workgroup of four wavefronts owns 256 rows x 64 columns; each wavefront
+// owns 64 rows x 64 columns as 2 x 2 MFMA tiles of 32 x 32 (64 accumulator registers), so every
+// expanded A operand and every B operand read from LDS feeds two MFMAs.  K advances in chunks
+// of 512 bits: the chunk of B is staged as [column][k] bytes with a 16-byte pad per column
+// (conflict-free 16-byte reads), the chunk of A is held as packed bits in registers.
+#include "bigcn_internal.h"
+
+namespace bigcn {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kMfmaChunkWords = 8;                       // 512 bits of K per stage
+constexpr int kMfmaChunkBytes = kMfmaChunkWords * 64;    // expanded bytes per column and chunk
+constexpr int kMfmaColStride = kMfmaChunkBytes + 16;     // LDS bytes per column
+constexpr int kMfmaCols = 64;                            // columns per workgroup
+constexpr int kMfmaRows = 256;                           // rows per workgroup
+
+// four packed bits -> four bytes in {0, 1}
+__device__ __forceinline__ uint32_t spread4(uint32_t nibble)
+{
+    return (nibble * 0x00204081u) & 0x01010101u;
+}
+// four packed bits -> four bytes in {-1, +1}
+__device__ __forceinline__ uint32_t spread4_pm1(uint32_t nibble)
+{
+    return ~(spread4(nibble) * 0xFEu);      // 1 -> 0x01, 0 -> 0xFF, no borrow between bytes
+}
+
+__global__ __launch_bounds__(kBlock) void bitgemm_mfma_kernel(
+    const uint64_t *__restrict__ a, int64_t m, int64_t lda, const uint64_t *__restrict__ b, int n,
+    int64_t ldb, int k_bits, const float *__restrict__ a_scale, const float *__restrict__ b_scale,
+    int32_t *__restrict__ acc_out, int64_t ld_acc, float *__restrict__ out, int64_t ld_out)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char lds_b[kMfmaCols * kMfmaColStride];
+    const int n_words = (k_bits + 63) >> 6;
+    const int lane = lane_id();
+    const int wave = wave_in_block();
+    const int i32 = lane & 31;          // row of an A tile / column of a B tile supplied by this lane
+    const int half = lane >> 5;         // which 16 of the 32 k values of an MFMA this lane supplies
+    const int64_t row0 = static_cast<int64_t>(blockIdx.x) * kMfmaRows + wave * 64;
+    const int col0 = blockIdx.y * kMfmaCols;
+
+    v16i acc[2][2];
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rt][ct][r] = 0;
+
+    const uint64_t *arow[2];
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+        int64_t row = row0 + 32 * rt + i32;
+        if (row >= m) row = m - 1;                          // clamped rows are never stored
+        arow[rt] = a + row * lda;
+    }
+
+    for (int w0 = 0; w0 < n_words; w0 += kMfmaChunkWords) {
+        // packed bits of A for this chunk (zero past the last word)
+        uint64_t abits[2][kMfmaChunkWords];
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int q = 0; q < kMfmaChunkWords; ++q)
+                abits[rt][q] = (w0 + q < n_words) ? arow[rt][w0 + q] : 0ull;
+
+        __syncthreads();                                     // previous chunk fully consumed
+        // expand the chunk of B: 64 columns x 8 words, two words per thread
+        for (int item = threadIdx.x; item < kMfmaCols * kMfmaChunkWords; item += kBlock) {
+            const int c = item / kMfmaChunkWords;
+            const int q = item - c * kMfmaChunkWords;
+            const int j = col0 + c;
+            const bool live = j < n && w0 + q < n_words;
+            const uint64_t word = live ? b[static_cast<int64_t>(j) * ldb + w0 + q] : 0ull;
+            uint4 *dst = reinterpret_cast<uint4 *>(lds_b + c * kMfmaColStride + q * 64);
+#pragma unroll
+            for (int part = 0; part < 4; ++part) {
+                const uint32_t bits16 = static_cast<uint32_t>(word >> (16 * part)) & 0xffffu;
+                uint4 v;
+                v.x = live ? spread4_pm1(bits16 & 0xf) : 0u;
+                v.y = live ? spread4_pm1((bits16 >> 4) & 0xf) : 0u;
+                v.z = live ? spread4_pm1((bits16 >> 8) & 0xf) : 0u;
+                v.w = live ? spread4_pm1((bits16 >> 12) & 0xf) : 0u;
+                dst[part] = v;
+            }
+        }
+        __syncthreads();
+
+#pragma unroll
+        for (int q = 0; q < kMfmaChunkWords; ++q) {
+            if (w0 + q >= n_words) break;                    // uniform
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                // 32 k values per step: bits [32 s, 32 s + 32) of the chunk, s = 2 q + sub;
+                // this lane supplies 16 of them
+                const int s = 2 * q + sub;
+                v4i aop[2], bop[2];
+#pragma unroll
+                for (int rt = 0; rt < 2; ++rt) {
+                    const uint32_t bits16 =
+                        static_cast<uint32_t>(abits[rt][q] >> (32 * sub + 16 * half)) & 0xffffu;
+                    aop[rt][0] = static_cast<int>(spread4(bits16 & 0xf));
+                    aop[rt][1] = static_cast<int>(spread4((bits16 >> 4) & 0xf));
+                    aop[rt][2] = static_cast<int>(spread4((bits16 >> 8) & 0xf));
+                    aop[rt][3] = static_cast<int>(spread4((bits16 >> 12) & 0xf));
+                }
+#pragma unroll
+                for (int ct = 0; ct < 2; ++ct)
+                    bop[ct] = *reinterpret_cast<const v4i *>(lds_b + (32 * ct + i32) * kMfmaColStride + 32 * s + 16 * half);
+#pragma unroll
+                for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                    for (int ct = 0; ct < 2; ++ct)
+                        acc[rt][ct] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aop[rt], bop[ct], acc[rt][ct], 0, 0, 0);
+            }
+        }
+    }
+
+    // epilogue: c = 2 * acc - (2 popcount(B_j) - K); accumulator register r of a 32x32 tile holds
+    // row 8 (r / 4) + 4 half + r % 4 and column lane % 32
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct) {
+        const int j = col0 + 32 * ct + i32;
+        if (j >= n) continue;
+        int ones = 0;
+        for (int w = 0; w < n_words; ++w) ones += __popcll(b[static_cast<int64_t>(j) * ldb + w]);
+        const int colsum = 2 * ones - k_bits;
+        const float sb = out != nullptr ? b_scale[j] : 0.0f;
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = row0 + 32 * rt + 8 * (r >> 2) + 4 * half + (r & 3);
+                if (row < m) {
+                    const int c = 2 * acc[rt][ct][r] - colsum;
+                    if (acc_out != nullptr) acc_out[row * ld_acc + j] = c;
+                    if (out != nullptr) out[row * ld_out + j] = a_scale[row] * sb * static_cast<float>(c);
+                }
+            }
+        }
+    }
+}
+
+int launch_bitgemm_mfma(const uint64_t *a_bits, const float *a_scale, int64_t m, int64_t lda,
+                        const uint64_t *b_bits, const float *b_scale, int64_t n, int64_t ldb,
+                        int64_t k_bits, int32_t *acc, int64_t ld_acc, float *out, int64_t ld_out,
+                        hipStream_t stream)
+{
+    const int64_t row_blocks = (m + kMfmaRows - 1) / kMfmaRows;
+    const int64_t col_blocks = (n + kMfmaCols - 1) / kMfmaCols;
+    if (row_blocks > 0x7fffffff || col_blocks > 65535) return BIGCN_ESHAPE;
+    hipLaunchKernelGGL(bitgemm_mfma_kernel, dim3(static_cast<unsigned>(row_blocks), static_cast<unsigned>(col_blocks)),
+                       dim3(kBlock), 0, stream, a_bits, m, lda, b_bits, static_cast<int>(n), ldb,
+                       static_cast<int>(k_bits), a_scale, b_scale, acc, ld_acc, out, ld_out);
+    return check_launch();
+}
+
+}  // namespace bigcn

@@ -84,6 +84,14 @@ def test_binary_gemm_rejects_bad_arguments():
     assert call(k=binding.MAX_K_BITS + 1, lda=200, ldb=200) == binding.BIGCN_ESHAPE
     assert call(m=0) == binding.BIGCN_OK
     assert call(n=0, ldacc=0, ldout=0) == binding.BIGCN_OK
+    p = ok
+    for variant, expect in ((3, binding.BIGCN_EINVAL), (-1, binding.BIGCN_EINVAL)):
+        assert L.bigcn_binary_gemm_variant(p["a"], p["sa"], p["m"], p["lda"], p["b"], p["sb"], p["n"],
+                                           p["ldb"], p["k"], p["acc"], p["ldacc"], p["out"], p["ldout"],
+                                           variant, None) == expect
+    assert L.bigcn_binary_gemm_variant(None, p["sa"], p["m"], p["lda"], p["b"], p["sb"], p["n"], p["ldb"],
+                                       p["k"], p["acc"], p["ldacc"], p["out"], p["ldout"],
+                                       binding.GEMM_MFMA, None) == binding.BIGCN_ENULL
 
 
 def test_graph_entry_points_reject_bad_arguments():

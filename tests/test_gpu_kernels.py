@@ -85,11 +85,13 @@ def test_pack_weight_columns(B, d_in, d_out):
 # ------------------------------------------------------------------------------------------
 GEMM_SHAPES = [(1, 1, 1), (5, 3, 64), (67, 7, 65), (300, 41, 128), (1000, 47, 256), (130, 64, 1433),
                (77, 64, 3703), (1025, 128, 602), (513, 256, 100), (260, 256, 256), (33, 300, 500),
-               (19, 512, 256), (21, 700, 130), (9, 64, 8192), (4099, 64, 64), (50, 130, 4096)]
+               (19, 512, 256), (21, 700, 130), (9, 64, 8192), (4099, 64, 64), (50, 130, 4096),
+               (4099, 130, 1433), (4200, 49, 1024), (4500, 64, 8192), (300, 70, 640)]
 
 
+@pytest.mark.parametrize("variant", ["auto", "valu", "mfma"])
 @pytest.mark.parametrize("m,n,k", GEMM_SHAPES)
-def test_binary_gemm(B, m, n, k):
+def test_binary_gemm(B, m, n, k, variant):
     import torch
     rng = _rng(m * 31 + n * 7 + k)
     f = rng.choice(np.array([-1, 1], dtype=np.int8), size=(m, k))
@@ -103,14 +105,15 @@ def test_binary_gemm(B, m, n, k):
     zeta = oracle.rescale(acc, beta.astype(np.float64), alpha.astype(np.float64))
     a_bits, b_bits, dbeta, dalpha = to_device(oracle.pack_bits(f).view(np.int64),
                                               oracle.pack_bits(bt).view(np.int64), beta, alpha)
-    dacc, dout = B.bigcn_binary_gemm(a_bits, dbeta, b_bits, dalpha, k)
+    v = {"auto": B.GEMM_AUTO, "valu": B.GEMM_VALU, "mfma": B.GEMM_MFMA}[variant]
+    dacc, dout = B.bigcn_binary_gemm(a_bits, dbeta, b_bits, dalpha, k, variant=v)
     torch.cuda.synchronize()
     assert np.array_equal(dacc.cpu().numpy(), acc)
     assert_close(dout.cpu().numpy(), zeta, "zeta")
     # each output alone
-    only_acc, none = B.bigcn_binary_gemm(a_bits, None, b_bits, None, k, want_out=False)
+    only_acc, none = B.bigcn_binary_gemm(a_bits, None, b_bits, None, k, want_out=False, variant=v)
     assert none is None and np.array_equal(only_acc.cpu().numpy(), acc)
-    none, only_out = B.bigcn_binary_gemm(a_bits, dbeta, b_bits, dalpha, k, want_acc=False)
+    none, only_out = B.bigcn_binary_gemm(a_bits, dbeta, b_bits, dalpha, k, want_acc=False, variant=v)
     assert none is None and np.array_equal(only_out.cpu().numpy(), dout.cpu().numpy())
 
 

@@ -12,7 +12,9 @@
 // owns 64 rows x 64 columns as 2 x 2 MFMA tiles of 32 x 32 (64 accumulator registers), so every
 // expanded A operand and every B operand read from LDS feeds two MFMAs.  K advances in chunks
 // of 512 bits: the chunk of B is staged as [column][k] bytes with a 16-byte pad per column
-// (conflict-free 16-byte reads), the chunk of A is held as packed bits in registers.
+// (conflict-free 16-byte reads), the chunk of A is held as packed bits in registers.  The
+// packed words of the next chunk (A and B) are fetched while the current chunk is multiplied,
+// and B is expanded into the second LDS buffer, so a chunk costs one barrier.
 #include "bigcn_internal.h"
 
 namespace bigcn {
@@ -37,12 +39,37 @@ __device__ __forceinline__ uint32_t spread4_pm1(uint32_t nibble)
     return ~(spread4(nibble) * 0xFEu);      // 1 -> 0x01, 0 -> 0xFF, no borrow between bytes
 }
 
+// Expand two packed words of B (this thread's share of a chunk) into +-1 bytes in LDS.
+__device__ __forceinline__ void stage_b_words(unsigned char *lds_b, const uint64_t (&word)[2],
+                                              const bool (&live)[2])
+{
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int item = static_cast<int>(threadIdx.x) + t * kBlock;
+        const int c = item / kMfmaChunkWords;
+        const int q = item - c * kMfmaChunkWords;
+        uint4 *dst = reinterpret_cast<uint4 *>(lds_b + c * kMfmaColStride + q * 64);
+#pragma unroll
+        for (int part = 0; part < 4; ++part) {
+            const uint32_t bits16 = static_cast<uint32_t>(word[t] >> (16 * part)) & 0xffffu;
+            uint4 v;
+            v.x = live[t] ? spread4_pm1(bits16 & 0xf) : 0u;
+            v.y = live[t] ? spread4_pm1((bits16 >> 4) & 0xf) : 0u;
+            v.z = live[t] ? spread4_pm1((bits16 >> 8) & 0xf) : 0u;
+            v.w = live[t] ? spread4_pm1((bits16 >> 12) & 0xf) : 0u;
+            dst[part] = v;
+        }
+    }
+}
+
 __global__ __launch_bounds__(kBlock) void bitgemm_mfma_kernel(
     const uint64_t *__restrict__ a, int64_t m, int64_t lda, const uint64_t *__restrict__ b, int n,
     int64_t ldb, int k_bits, const float *__restrict__ a_scale, const float *__restrict__ b_scale,
     int32_t *__restrict__ acc_out, int64_t ld_acc, float *__restrict__ out, int64_t ld_out)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds_b[kMfmaCols * kMfmaColStride];
+    // two buffers: the chunk being multiplied and the chunk being expanded for the next step
+    __shared__ __attribute__((aligned(16))) unsigned char lds_b[2][kMfmaCols * kMfmaColStride];
+    static_assert(kMfmaCols * kMfmaChunkWords == 2 * kBlock, "two words of B per thread and chunk");
     const int n_words = (k_bits + 63) >> 6;
     const int lane = lane_id();
     const int wave = wave_in_block();
@@ -66,38 +93,51 @@ __global__ __launch_bounds__(kBlock) void bitgemm_mfma_kernel(
         if (row >= m) row = m - 1;                          // clamped rows are never stored
         arow[rt] = a + row * lda;
     }
+    // this thread's two words of every B chunk: (column, word) = item / 8, item % 8
+    const uint64_t *bsrc[2];
+    bool bcol_live[2];
+    int bq[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int item = static_cast<int>(threadIdx.x) + t * kBlock;
+        const int c = item / kMfmaChunkWords;
+        bq[t] = item - c * kMfmaChunkWords;
+        const int j = col0 + c;
+        bcol_live[t] = j < n;
+        bsrc[t] = b + static_cast<int64_t>(bcol_live[t] ? j : 0) * ldb;
+    }
 
-    for (int w0 = 0; w0 < n_words; w0 += kMfmaChunkWords) {
-        // packed bits of A for this chunk (zero past the last word)
-        uint64_t abits[2][kMfmaChunkWords];
+    uint64_t a_next[2][kMfmaChunkWords];
+    uint64_t b_next[2];
+    bool b_live[2];
+    auto fetch = [&](int w0) {
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
             for (int q = 0; q < kMfmaChunkWords; ++q)
-                abits[rt][q] = (w0 + q < n_words) ? arow[rt][w0 + q] : 0ull;
-
-        __syncthreads();                                     // previous chunk fully consumed
-        // expand the chunk of B: 64 columns x 8 words, two words per thread
-        for (int item = threadIdx.x; item < kMfmaCols * kMfmaChunkWords; item += kBlock) {
-            const int c = item / kMfmaChunkWords;
-            const int q = item - c * kMfmaChunkWords;
-            const int j = col0 + c;
-            const bool live = j < n && w0 + q < n_words;
-            const uint64_t word = live ? b[static_cast<int64_t>(j) * ldb + w0 + q] : 0ull;
-            uint4 *dst = reinterpret_cast<uint4 *>(lds_b + c * kMfmaColStride + q * 64);
+                a_next[rt][q] = (w0 + q < n_words) ? arow[rt][w0 + q] : 0ull;   // zero past the last word
 #pragma unroll
-            for (int part = 0; part < 4; ++part) {
-                const uint32_t bits16 = static_cast<uint32_t>(word >> (16 * part)) & 0xffffu;
-                uint4 v;
-                v.x = live ? spread4_pm1(bits16 & 0xf) : 0u;
-                v.y = live ? spread4_pm1((bits16 >> 4) & 0xf) : 0u;
-                v.z = live ? spread4_pm1((bits16 >> 8) & 0xf) : 0u;
-                v.w = live ? spread4_pm1((bits16 >> 12) & 0xf) : 0u;
-                dst[part] = v;
-            }
+        for (int t = 0; t < 2; ++t) {
+            b_live[t] = bcol_live[t] && w0 + bq[t] < n_words;
+            b_next[t] = b_live[t] ? bsrc[t][w0 + bq[t]] : 0ull;
         }
-        __syncthreads();
+    };
 
+    fetch(0);
+    stage_b_words(lds_b[0], b_next, b_live);
+    __syncthreads();
+
+    int buf = 0;
+    for (int w0 = 0; w0 < n_words; w0 += kMfmaChunkWords, buf ^= 1) {
+        uint64_t abits[2][kMfmaChunkWords];
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int q = 0; q < kMfmaChunkWords; ++q) abits[rt][q] = a_next[rt][q];
+        const bool more = w0 + kMfmaChunkWords < n_words;       // uniform
+        if (more) fetch(w0 + kMfmaChunkWords);                  // in flight during the MFMAs below
+
+        const unsigned char *cur = lds_b[buf];
 #pragma unroll
         for (int q = 0; q < kMfmaChunkWords; ++q) {
             if (w0 + q >= n_words) break;                    // uniform
@@ -118,7 +158,7 @@ __global__ __launch_bounds__(kBlock) void bitgemm_mfma_kernel(
                 }
 #pragma unroll
                 for (int ct = 0; ct < 2; ++ct)
-                    bop[ct] = *reinterpret_cast<const v4i *>(lds_b + (32 * ct + i32) * kMfmaColStride + 32 * s + 16 * half);
+                    bop[ct] = *reinterpret_cast<const v4i *>(cur + (32 * ct + i32) * kMfmaColStride + 32 * s + 16 * half);
 #pragma unroll
                 for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
@@ -126,6 +166,10 @@ __global__ __launch_bounds__(kBlock) void bitgemm_mfma_kernel(
                         acc[rt][ct] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aop[rt], bop[ct], acc[rt][ct], 0, 0, 0);
             }
         }
+        // expand the next chunk of B into the other buffer: every wavefront left that buffer
+        // before the barrier that ended the previous iteration
+        if (more) stage_b_words(lds_b[buf ^ 1], b_next, b_live);
+        __syncthreads();
     }
 
     // epilogue: c = 2 * acc - (2 popcount(B_j) - K); accumulator register r of a 32x32 tile holds

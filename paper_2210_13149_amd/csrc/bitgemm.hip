@@ -302,7 +302,7 @@ int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const 
 // inner dimension to be compute-bound and enough rows and columns to fill its 256 x 64 tiles.
 bool prefer_mfma(int64_t m, int64_t n, int64_t k_bits)
 {
-    return k_bits >= 1024 && n >= 48 && m >= 4096;
+    return k_bits >= 512 && n >= 48 && m >= 4096;
 }
 
 }  // namespace bigcn

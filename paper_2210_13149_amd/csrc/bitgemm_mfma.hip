@@ -12,9 +12,9 @@
 // owns 64 rows x 64 columns as 2 x 2 MFMA tiles of 32 x 32 (64 accumulator registers), so every
 // expanded A operand and every B operand read from LDS feeds two MFMAs.  K advances in chunks
 // of 512 bits: the chunk of B is staged as [column][k] bytes with a 16-byte pad per column
-// (conflict-free 16-byte reads), the chunk of A is held as packed bits in registers.  The
-// packed words of the next chunk (A and B) are fetched while the current chunk is multiplied,
-// and B is expanded into the second LDS buffer, so a chunk costs one barrier.
+// (conflict-free 16-byte reads); the chunk of A (256 rows x 64 bytes of packed bits) is staged as
+// is, through coalesced loads.  The packed words of the next chunk (A and B) are fetched into
+// registers while the current chunk is multiplied and written to LDS between two barriers.
 #include "bigcn_internal.h"
 
 namespace bigcn {
@@ -62,20 +62,24 @@ __device__ __forceinline__ void stage_b_words(unsigned char *lds_b, const uint64
     }
 }
 
+constexpr int kMfmaARowStride = kMfmaChunkWords * 8 + 8;   // LDS bytes per row of the A chunk
+
 __global__ __launch_bounds__(kBlock) void bitgemm_mfma_kernel(
     const uint64_t *__restrict__ a, int64_t m, int64_t lda, const uint64_t *__restrict__ b, int n,
     int64_t ldb, int k_bits, const float *__restrict__ a_scale, const float *__restrict__ b_scale,
     int32_t *__restrict__ acc_out, int64_t ld_acc, float *__restrict__ out, int64_t ld_out)
 {
-    // two buffers: the chunk being multiplied and the chunk being expanded for the next step
-    __shared__ __attribute__((aligned(16))) unsigned char lds_b[2][kMfmaCols * kMfmaColStride];
+    __shared__ __attribute__((aligned(16))) unsigned char lds_b[kMfmaCols * kMfmaColStride];
+    __shared__ __attribute__((aligned(16))) unsigned char lds_a[kMfmaRows * kMfmaARowStride];
     static_assert(kMfmaCols * kMfmaChunkWords == 2 * kBlock, "two words of B per thread and chunk");
+    static_assert(kMfmaRows * kMfmaChunkWords == 8 * kBlock, "eight words of A per thread and chunk");
     const int n_words = (k_bits + 63) >> 6;
     const int lane = lane_id();
     const int wave = wave_in_block();
     const int i32 = lane & 31;          // row of an A tile / column of a B tile supplied by this lane
     const int half = lane >> 5;         // which 16 of the 32 k values of an MFMA this lane supplies
-    const int64_t row0 = static_cast<int64_t>(blockIdx.x) * kMfmaRows + wave * 64;
+    const int64_t block_row0 = static_cast<int64_t>(blockIdx.x) * kMfmaRows;
+    const int64_t row0 = block_row0 + wave * 64;
     const int col0 = blockIdx.y * kMfmaCols;
 
     v16i acc[2][2];
@@ -86,12 +90,18 @@ __global__ __launch_bounds__(kBlock) void bitgemm_mfma_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[rt][ct][r] = 0;
 
-    const uint64_t *arow[2];
+    // Packed words of A reach the wavefronts through LDS: thread t fetches words (2 p + t % 4 * 2)
+    // ... of row t / 4 + 64 p, i.e. four consecutive lanes read the 64 contiguous bytes a row
+    // contributes to a chunk, so global loads are coalesced per row instead of one 8-byte
+    // request per row and lane.
+    const int a_thread_row = static_cast<int>(threadIdx.x) >> 2;      // 0..63, + 64 p
+    const int a_thread_word = (static_cast<int>(threadIdx.x) & 3) * 2; // 0, 2, 4, 6
+    const uint64_t *asrc[4];
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt) {
-        int64_t row = row0 + 32 * rt + i32;
+    for (int p = 0; p < 4; ++p) {
+        int64_t row = block_row0 + a_thread_row + 64 * p;
         if (row >= m) row = m - 1;                          // clamped rows are never stored
-        arow[rt] = a + row * lda;
+        asrc[p] = a + row * lda + a_thread_word;
     }
     // this thread's two words of every B chunk: (column, word) = item / 8, item % 8
     const uint64_t *bsrc[2];
@@ -107,40 +117,49 @@ __global__ __launch_bounds__(kBlock) void bitgemm_mfma_kernel(
         bsrc[t] = b + static_cast<int64_t>(bcol_live[t] ? j : 0) * ldb;
     }
 
-    uint64_t a_next[2][kMfmaChunkWords];
+    uint64_t a_next[4][2];
     uint64_t b_next[2];
     bool b_live[2];
     auto fetch = [&](int w0) {
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
+        for (int p = 0; p < 4; ++p)
 #pragma unroll
-            for (int q = 0; q < kMfmaChunkWords; ++q)
-                a_next[rt][q] = (w0 + q < n_words) ? arow[rt][w0 + q] : 0ull;   // zero past the last word
+            for (int e = 0; e < 2; ++e)                       // zero past the last word
+                a_next[p][e] = (w0 + a_thread_word + e < n_words) ? asrc[p][w0 + e] : 0ull;
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             b_live[t] = bcol_live[t] && w0 + bq[t] < n_words;
             b_next[t] = b_live[t] ? bsrc[t][w0 + bq[t]] : 0ull;
         }
     };
+    auto stage = [&]() {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            uint2 *dst = reinterpret_cast<uint2 *>(lds_a + (a_thread_row + 64 * p) * kMfmaARowStride + a_thread_word * 8);
+            dst[0] = make_uint2(static_cast<uint32_t>(a_next[p][0]), static_cast<uint32_t>(a_next[p][0] >> 32));
+            dst[1] = make_uint2(static_cast<uint32_t>(a_next[p][1]), static_cast<uint32_t>(a_next[p][1] >> 32));
+        }
+        stage_b_words(lds_b, b_next, b_live);
+    };
 
     fetch(0);
-    stage_b_words(lds_b[0], b_next, b_live);
+    stage();
     __syncthreads();
 
-    int buf = 0;
-    for (int w0 = 0; w0 < n_words; w0 += kMfmaChunkWords, buf ^= 1) {
-        uint64_t abits[2][kMfmaChunkWords];
+    const unsigned char *a_lane[2];
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-            for (int q = 0; q < kMfmaChunkWords; ++q) abits[rt][q] = a_next[rt][q];
+    for (int rt = 0; rt < 2; ++rt) a_lane[rt] = lds_a + (wave * 64 + 32 * rt + i32) * kMfmaARowStride;
+
+    for (int w0 = 0; w0 < n_words; w0 += kMfmaChunkWords) {
         const bool more = w0 + kMfmaChunkWords < n_words;       // uniform
         if (more) fetch(w0 + kMfmaChunkWords);                  // in flight during the MFMAs below
 
-        const unsigned char *cur = lds_b[buf];
 #pragma unroll
         for (int q = 0; q < kMfmaChunkWords; ++q) {
             if (w0 + q >= n_words) break;                    // uniform
+            uint2 aw[2];
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt) aw[rt] = *reinterpret_cast<const uint2 *>(a_lane[rt] + 8 * q);
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub) {
                 // 32 k values per step: bits [32 s, 32 s + 32) of the chunk, s = 2 q + sub;
@@ -149,8 +168,7 @@ __global__ __launch_bounds__(kBlock) void bitgemm_mfma_kernel(
                 v4i aop[2], bop[2];
 #pragma unroll
                 for (int rt = 0; rt < 2; ++rt) {
-                    const uint32_t bits16 =
-                        static_cast<uint32_t>(abits[rt][q] >> (32 * sub + 16 * half)) & 0xffffu;
+                    const uint32_t bits16 = ((sub ? aw[rt].y : aw[rt].x) >> (16 * half)) & 0xffffu;
                     aop[rt][0] = static_cast<int>(spread4(bits16 & 0xf));
                     aop[rt][1] = static_cast<int>(spread4((bits16 >> 4) & 0xf));
                     aop[rt][2] = static_cast<int>(spread4((bits16 >> 8) & 0xf));
@@ -158,7 +176,7 @@ __global__ __launch_bounds__(kBlock) void bitgemm_mfma_kernel(
                 }
 #pragma unroll
                 for (int ct = 0; ct < 2; ++ct)
-                    bop[ct] = *reinterpret_cast<const v4i *>(cur + (32 * ct + i32) * kMfmaColStride + 32 * s + 16 * half);
+                    bop[ct] = *reinterpret_cast<const v4i *>(lds_b + (32 * ct + i32) * kMfmaColStride + 32 * s + 16 * half);
 #pragma unroll
                 for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
@@ -166,9 +184,8 @@ __global__ __launch_bounds__(kBlock) void bitgemm_mfma_kernel(
                         acc[rt][ct] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aop[rt], bop[ct], acc[rt][ct], 0, 0, 0);
             }
         }
-        // expand the next chunk of B into the other buffer: every wavefront left that buffer
-        // before the barrier that ended the previous iteration
-        if (more) stage_b_words(lds_b[buf ^ 1], b_next, b_live);
+        __syncthreads();                                     // every wavefront has left this chunk
+        if (more) stage();
         __syncthreads();
     }
 

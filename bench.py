@@ -89,6 +89,39 @@ def aggregation_bytes(cfg, nnz, layer, B):
     return gather, minimum, row_bytes
 
 
+MFMA_INT8_MAC_PEAK = 2.5e15     # MI355X dense int8: 5.0 POP/s, two operations per multiply-accumulate
+
+
+def gemm_sweep(B, m=262144, n=256, k=4096, reps=10):
+    """Compute-bound bit-GEMM outside the workloads (their GEMMs are bound by writing the product
+    rows): both evaluation paths of bigcn_binary_gemm on random bits, int32 accumulators only."""
+    import torch
+    words = (k + 63) // 64
+    gen = torch.Generator(device="cuda").manual_seed(1)
+    a = torch.randint(-2**62, 2**62, (m, words), dtype=torch.int64, device="cuda", generator=gen)
+    b = torch.randint(-2**62, 2**62, (n, words), dtype=torch.int64, device="cuda", generator=gen)
+    out = []
+    ref = None
+    for name, variant in (("valu_xor_popcount", B.GEMM_VALU), ("mfma_int8", B.GEMM_MFMA)):
+        acc, _ = B.bigcn_binary_gemm(a, None, b, None, k, want_out=False, variant=variant)
+        torch.cuda.synchronize()
+        if ref is None:
+            ref = acc
+        identical = bool(torch.equal(ref, acc))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            B.bigcn_binary_gemm(a, None, b, None, k, want_out=False, variant=variant)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        rate = m * n * k / (ms * 1e-3)
+        out.append({"path": name, "m": m, "n": n, "k_bits": k, "ms": ms, "binary_op_per_s": rate,
+                    "frac_valu_peak": rate / VALU_BINARY_MAC_PEAK,
+                    "frac_mfma_int8_peak": rate / MFMA_INT8_MAC_PEAK, "identical_to_first": identical})
+    return out
+
+
 def cpu_baseline(work, target_nodes):
     """The plain oracle, as it stands, timed on the host cores: on the benchmark's own workload,
     or on a smaller graph of the same recipe (same mean degree, dims, feature law); nodes/s."""
@@ -119,6 +152,8 @@ def main():
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one device-to-device copy kernel of this many MiB (a known "
                          "traffic figure to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings by)")
+    ap.add_argument("--no-gemm-sweep", action="store_true",
+                    help="skip the compute-bound bit-GEMM leg (both evaluation paths, M=262144, n=256, K=4096)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -210,6 +245,10 @@ def main():
         "paper_theory": {k: v for k, v in cost_model.summary(cfg.n_nodes, cfg.n_edges, cfg.dims).items()
                          if k.endswith("ratio")},
     }
+    if not args.no_gemm_sweep:
+        result["bit_gemm_sweep"] = gemm_sweep(B)
+        best = max(result["bit_gemm_sweep"], key=lambda r: r["binary_op_per_s"])
+        result["bit_gemm_binary_op_per_s"] = max(result["bit_gemm_binary_op_per_s"], best["binary_op_per_s"])
     if args.cpu_baseline_nodes != 0:
         t0 = time.perf_counter()
         del m

@@ -4,8 +4,8 @@ TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke()``
 ``cpu_baseline`` leg of ``bench.py``; never by the product package.  It shares no code with the
 HIP library.  Each function states the passage of the paper it follows.
 
-Pinned by ``tests/test_oracle_pins.py`` (brute force, closed forms, hand-built graphs, library
-routines, the cost figures the paper prints).  Not pinned by anything: accuracy on the real
+Pinned by ``tests/test_oracle_pins.py`` and ``tests/test_oracle_sage_pins.py`` (brute force,
+closed forms, hand-built graphs, library routines, the cost figures the paper prints).  Not pinned by anything: accuracy on the real
 datasets (parity unpinned: neither datasets nor trained weights are available).
 """
 
@@ -248,3 +248,53 @@ def forward(row_ptr, col_idx, x: np.ndarray, weights: Sequence[np.ndarray],
             rec = {k: rec[k] for k in ("shift", "mul", "beta", "alpha")}
         records.append(rec)
     return h, records
+
+
+# ---- Bi-GraphSAGE, mean aggregator (Sec. 4.4.2) ------------------------------------------------
+
+def mean_norm(row_ptr: np.ndarray, col_idx: np.ndarray) -> np.ndarray:
+    """Coefficients of the mean aggregator of Sec. 4.4.2: row i of the CSR lists N_i and every
+    stored entry of that row gets ``1/|N_i|`` (fp64).  A node without neighbours has no entries,
+    so its neighbour term is an empty sum."""
+    row_ptr, col_idx, n = _check_csr(row_ptr, col_idx)
+    deg = np.diff(row_ptr)
+    return np.repeat(1.0 / np.maximum(deg, 1).astype(np.float64), deg)
+
+
+def sage_layer(row_ptr, col_idx, mean_coeff, h: np.ndarray, w_self: np.ndarray, w_nbr: np.ndarray,
+               shift=None, mul=None) -> Dict[str, np.ndarray]:
+    """One Bi-GraphSAGE layer (Sec. 4.4.2, the binarised form of the mean-aggregator layer):
+    ``out_i = W~_theta (*) h~_i + (1/|N_i|) sum_{j in N_i} W~_n (*) h~_j`` where (*) is the
+    binarised product of Sec. 4.2 (signs, row scale beta, column scale alpha); no non-linearity.
+    Returns every intermediate."""
+    sign, beta = binarize_rows(h, shift, mul)
+    bt_self, alpha_self = binarize_weight(w_self)
+    bt_nbr, alpha_nbr = binarize_weight(w_nbr)
+    zeta_self = rescale(sign_matmul(sign, bt_self), beta, alpha_self)
+    zeta_nbr = rescale(sign_matmul(sign, bt_nbr), beta, alpha_nbr)
+    out = zeta_self + aggregate(row_ptr, col_idx, mean_coeff, zeta_nbr)
+    return {"sign": sign, "beta": beta, "alpha_self": alpha_self, "alpha_nbr": alpha_nbr,
+            "zeta_self": zeta_self, "zeta_nbr": zeta_nbr, "out": out}
+
+
+def sage_forward(row_ptr, col_idx, x: np.ndarray, weights: Sequence[Tuple[np.ndarray, np.ndarray]],
+                 bn: Optional[Sequence[Optional[Tuple[np.ndarray, np.ndarray]]]] = None,
+                 calibrate: Optional[Sequence[bool]] = None):
+    """L-layer Bi-GraphSAGE forward (Sec. 4.4.2; h^(L) is the prediction input): ``weights[l]``
+    is the pair ``(W_theta, W_n)`` of layer l; ``bn`` / ``calibrate`` as in :func:`forward`
+    (standardisation before each binarised layer, Sec. 7.2 Setups).  Returns the
+    fp64 output and the standardisation parameters used per layer."""
+    n_layers = len(weights)
+    bn = list(bn) if bn is not None else [None] * n_layers
+    calibrate = list(calibrate) if calibrate is not None else [False] * n_layers
+    coeff = mean_norm(row_ptr, col_idx)
+    h = np.asarray(x, dtype=np.float32)
+    used = []
+    for l in range(n_layers):
+        params = bn[l]
+        if calibrate[l]:
+            params = column_standardisation(h)
+        shift, mul = params if params is not None else (None, None)
+        h = sage_layer(row_ptr, col_idx, coeff, h, weights[l][0], weights[l][1], shift, mul)["out"]
+        used.append(params)
+    return h, used

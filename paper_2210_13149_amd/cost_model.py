@@ -67,6 +67,17 @@ def speedup_layer(d_in: int, mean_degree: float) -> float:
     return (64.0 * d_in + 32.0 * mean_degree) / (d_in + 128.0 + 32.0 * mean_degree)
 
 
+def sage_summary(n: int, n_edges: int, dims: Sequence[int]) -> Dict[str, float]:
+    """The same counts for the mean-aggregator GraphSAGE layer and its binarised form
+    (Sec. 4.4.2): two weight matrices per layer, so parameters and transform work double while
+    the aggregation term |E|*d_out and the loaded features stay as they are."""
+    ms, msb = 2.0 * model_size_bytes(dims), 2.0 * model_size_bytes_binary(dims)
+    co = float(sum(2 * n * a * b + n_edges * b for a, b in _layers(dims)))
+    cob = float(sum(2.0 * (n * a * b / 64.0 + 2.0 * n * b) + n_edges * b for a, b in _layers(dims)))
+    return {"model_size_bytes": ms, "model_size_bytes_binary": msb, "model_size_ratio": ms / msb,
+            "cycle_ops": co, "cycle_ops_binary": cob, "cycle_ops_ratio": co / cob}
+
+
 def summary(n: int, n_edges: int, dims: Sequence[int]) -> Dict[str, float]:
     ms, msb = model_size_bytes(dims), model_size_bytes_binary(dims)
     ds, dsb = data_size_bytes(n, dims[0]), data_size_bytes_binary(n, dims[0])

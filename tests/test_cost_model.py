@@ -51,6 +51,29 @@ def test_printed_sizes_and_cycle_ops(row):
     assert abs(s["cycle_ops_binary"] / cob - 1) < 5.1e-3
 
 
+def _sage_rows():
+    rows = []
+    with open(os.path.join(GOLDEN, "paper_cost_figures_sage.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            name, n, e, dims, *vals = line.split()
+            rows.append((name, int(n), int(e), tuple(int(d) for d in dims.split("-")),
+                         [float(v) for v in vals]))
+    return rows
+
+
+@pytest.mark.parametrize("row", _sage_rows(), ids=lambda r: r[0])
+def test_printed_sage_sizes_and_cycle_ops(row):
+    name, n, e, dims, (ms, msb, co, cob) = row
+    s = cm.sage_summary(n, e, dims)
+    assert abs(s["model_size_bytes"] / 1024 - ms) <= 0.005 + 1e-9
+    assert abs(s["model_size_bytes_binary"] / 1024 - msb) <= 0.0051
+    assert abs(s["cycle_ops"] / co - 1) < 5.1e-3
+    assert abs(s["cycle_ops_binary"] / cob - 1) < 5.1e-3
+
+
 def test_table1_exact_counts():
     t = _table1()
     dims = (1433, 64, 7)

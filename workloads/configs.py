@@ -1,9 +1,12 @@
-"""The five benchmark workloads, as data.
+"""The benchmark workloads, as data.
 
 Shapes follow the datasets table of the paper's evaluation section (Cora,
 CiteSeer, PubMed, Reddit, OGBN-Products); none of those datasets is reproduced:
 graphs are Chung-Lu random graphs and features are drawn from simple
-distributions with the same dimensions and density.
+distributions with the same dimensions and density.  c1..c5 are Bi-GCN models
+(graph stored as A + I); s4 and s5 are Bi-GraphSAGE models (graph stored as the
+neighbour lists, two weight matrices per layer) with the hidden widths of the
+paper's set-up: 256 on Reddit, 512 and three layers on OGBN-Products.
 """
 
 from __future__ import annotations
@@ -28,6 +31,8 @@ class WorkloadConfig:
     seed: int
     gamma: float = 2.5         # power-law exponent of the expected-degree sequence
     shuffle_ids: bool = True   # random node relabelling (False: ids by decreasing expected degree)
+    model: str = "gcn"         # "gcn": pattern of A + I, one weight per layer
+                               # "sage": pattern of A, a (W_theta, W_n) pair per layer
 
     @property
     def n_layers(self) -> int:
@@ -35,7 +40,7 @@ class WorkloadConfig:
 
     @property
     def nnz(self) -> int:
-        return 2 * self.n_edges + self.n_nodes
+        return 2 * self.n_edges + (self.n_nodes if self.model == "gcn" else 0)
 
 
 CONFIGS = {
@@ -49,6 +54,10 @@ CONFIGS = {
                          "normal", 1.0, "all", BASE_SEED + 4),
     "c5": WorkloadConfig("c5", "OGBN-Products", 2449029, 61_859_140, 77.0, (100, 256, 256, 47),
                          "normal", 1.0, "all", BASE_SEED + 5),
+    "s4": WorkloadConfig("s4", "Reddit", 232965, 57_300_000, 186.0, (602, 256, 41),
+                         "normal", 1.0, "all", BASE_SEED + 14, model="sage"),
+    "s5": WorkloadConfig("s5", "OGBN-Products", 2449029, 61_859_140, 77.0, (100, 512, 512, 47),
+                         "normal", 1.0, "all", BASE_SEED + 15, model="sage"),
 }
 
 

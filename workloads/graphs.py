@@ -1,8 +1,9 @@
-"""Seeded Chung-Lu power-law graphs in symmetric CSR form with self-loops.
+"""Seeded Chung-Lu power-law graphs in symmetric CSR form.
 
 The CSR produced here is the *pattern* of A + I (paper, Notations: the adjacency
-matrix of an undirected graph plus the identity).  No normalisation coefficient
-is computed in this module.
+matrix of an undirected graph plus the identity) or, with ``self_loops=False``,
+of A alone (row i lists the neighbours N_i).  No normalisation coefficient is
+computed in this module.
 """
 
 from __future__ import annotations
@@ -10,11 +11,12 @@ from __future__ import annotations
 import numpy as np
 
 
-def csr_from_undirected_edges(n: int, u: np.ndarray, v: np.ndarray):
-    """Pattern of A + I from a list of distinct undirected edges {u, v}, u != v.
+def csr_from_undirected_edges(n: int, u: np.ndarray, v: np.ndarray, self_loops: bool = True):
+    """Pattern of A + I (or of A, ``self_loops=False``) from a list of distinct undirected
+    edges {u, v}, u != v.
 
     Returns (row_ptr int64[n+1], col_idx int32[nnz]) with both directions of every edge,
-    one self-loop per node, and strictly increasing columns inside each row.
+    one self-loop per node unless switched off, and strictly increasing columns inside each row.
     """
     u = np.asarray(u, dtype=np.int64)
     v = np.asarray(v, dtype=np.int64)
@@ -24,7 +26,7 @@ def csr_from_undirected_edges(n: int, u: np.ndarray, v: np.ndarray):
         raise ValueError("edge endpoint out of range")
     if np.any(u == v):
         raise ValueError("self-pairs are not edges; the self-loop is added here")
-    loops = np.arange(n, dtype=np.int64)
+    loops = np.arange(n if self_loops else 0, dtype=np.int64)
     key = np.concatenate([u * n + v, v * n + u, loops * n + loops])
     key.sort()
     if key.size > 1 and np.any(key[1:] == key[:-1]):
@@ -114,11 +116,12 @@ def chung_lu_edges(n: int, n_edges: int, gamma: float, i0: float, rng: np.random
 
 
 def chung_lu_csr(n: int, n_edges: int, gamma: float = 2.5, i0: float = 1.0, seed: int = 0,
-                 shuffle_ids: bool = True):
-    """Symmetric CSR pattern of A + I for a seeded Chung-Lu graph.
+                 shuffle_ids: bool = True, self_loops: bool = True):
+    """Symmetric CSR pattern of A + I (of A with ``self_loops=False``) for a seeded Chung-Lu
+    graph.
 
-    Returns (row_ptr int64[n+1], col_idx int32[2*n_edges + n]).
+    Returns (row_ptr int64[n+1], col_idx int32[2*n_edges (+ n)]).
     """
     rng = np.random.Generator(np.random.PCG64(seed))
     u, v = chung_lu_edges(n, n_edges, gamma, i0, rng, shuffle_ids)
-    return csr_from_undirected_edges(n, u, v)
+    return csr_from_undirected_edges(n, u, v, self_loops)

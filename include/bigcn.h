@@ -55,6 +55,7 @@ int bigcn_version(void);
 #define BIGCN_MAX_K_BITS 8192
 #define BIGCN_MAX_GEMM_N 4194304
 #define BIGCN_MAX_FORWARD_D_OUT 512
+#define BIGCN_MAX_LAYERS 64
 
 /*
  * Kernel 1 - binarise and pack the rows of a strided fp32 matrix
@@ -129,13 +130,21 @@ int bigcn_gcn_norm(const int64_t *row_ptr, const int32_t *col_idx, int64_t n,
  * be used from any stream of the device it was created on.
  *
  * bigcn_plan_create copies row_ptr to the host and therefore SYNCHRONISES `stream`.
- * With validate != 0 it also checks on the device that every column index lies in
- * [0, n), columns increase strictly inside each row, every row holds its self-loop and
- * the pattern is symmetric; a violation returns BIGCN_EGRAPH and creates nothing.
- * Errors: ENULL, EINVAL (n < 0 or n >= 2^31, row_ptr not non-decreasing from 0),
+ * With validate = BIGCN_VALIDATE_GCN it also checks on the device that every column index
+ * lies in [0, n), columns increase strictly inside each row, every row holds its self-loop
+ * and the pattern is symmetric; BIGCN_VALIDATE_NEIGHBOURS checks the first two only (rows
+ * that list N_i for the mean aggregator of Sec. 4.4.2 hold no self-loop and may be empty).
+ * A violation returns BIGCN_EGRAPH and creates nothing.
+ * Errors: ENULL, EINVAL (n < 0 or n >= 2^31, row_ptr not non-decreasing from 0, unknown
+ * validate value),
  * EGRAPH, EHIP.  *out is set only on success.  bigcn_plan_destroy(NULL) is a no-op.
  */
 typedef struct bigcn_plan bigcn_plan;
+enum {
+    BIGCN_VALIDATE_NONE = 0,
+    BIGCN_VALIDATE_GCN = 1,        /* pattern of A + I: all four checks above            */
+    BIGCN_VALIDATE_NEIGHBOURS = 2  /* neighbour lists: index range and strict order only */
+};
 int bigcn_plan_create(const int64_t *row_ptr, const int32_t *col_idx, int64_t n, int validate,
                       bigcn_plan **out, void *stream);
 void bigcn_plan_destroy(bigcn_plan *plan);
@@ -188,8 +197,9 @@ typedef struct {
  *   logits                 : n rows of layers[L-1].d_out fp32, row stride ld_logits (DEVICE, out)
  *   workspace              : DEVICE scratch of at least bigcn_forward_workspace_bytes(...)
  *                            bytes, 256-byte aligned; contents are undefined afterwards
- * Errors: ENULL, EINVAL, ESHAPE (d_in > BIGCN_MAX_K_BITS or d_out > BIGCN_MAX_FORWARD_D_OUT),
- * EWORKSPACE.  bigcn_forward_workspace_bytes returns 0 for invalid arguments.
+ * Errors: ENULL, EINVAL (also n_layers > BIGCN_MAX_LAYERS), ESHAPE (d_in > BIGCN_MAX_K_BITS or
+ * d_out > BIGCN_MAX_FORWARD_D_OUT), EWORKSPACE.  bigcn_forward_workspace_bytes returns 0 for
+ * invalid arguments.
  */
 size_t bigcn_forward_workspace_bytes(int64_t n, const bigcn_layer *layers, int n_layers);
 /* Bytes of the compact row of integer products (Sec. 4.2.3, F_i (*) B_j for all j) that the
@@ -201,6 +211,43 @@ int bigcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t 
                   const float *dinv_sqrt, int64_t n, const float *x, int64_t ld_x,
                   const bigcn_layer *layers, int n_layers, float *logits, int64_t ld_logits,
                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Bi-GraphSAGE with the mean aggregator (Sec. 4.4.2, the binarised layer):
+ *
+ *   h_i^(l+1) = W~_theta (*) h~_i  +  (1/|N_i|) sum_{j in N_i} W~_n (*) h~_j
+ *
+ * with (*) the binarised product of Sec. 4.2 (beta_i alpha_j c_ij), no non-linearity, and
+ * the same optional standardisation of each layer's input.  Row i of the CSR lists N_i as
+ * given (pass the graph without self-loops for the usual aggregator); a node with an empty
+ * row keeps only its own term.
+ *
+ * bigcn_mean_norm: inv_deg[i] = 1/|N_i| (0 for an empty row).   row_ptr DEVICE int64[n+1],
+ * inv_deg DEVICE out, n floats.  Errors: ENULL, EINVAL (n < 0).
+ *
+ * bigcn_sage_forward: arguments as bigcn_forward, with inv_deg in place of dinv_sqrt, a plan
+ * created from the neighbour-list CSR, and `out` = h^(L) (n rows of layers[L-1].d_out fp32).
+ * Per layer two bit-GEMMs run (one per weight matrix) and one aggregation; the workspace
+ * holds two product arrays.  Errors as bigcn_forward.  Profiled variant: slot 1 + 2l covers
+ * both bit-GEMMs of layer l.
+ */
+typedef struct {
+    const uint64_t *w_self_bits; /* DEVICE: packed signs of W_theta[:, j], d_out rows        */
+    const float *alpha_self;     /* DEVICE: d_out scales of W_theta                          */
+    const uint64_t *w_nbr_bits;  /* DEVICE: packed signs of W_n[:, j], d_out rows            */
+    const float *alpha_nbr;      /* DEVICE: d_out scales of W_n                              */
+    int64_t d_in;
+    int64_t d_out;
+    int64_t ld_words;            /* row stride of both packed matrices, >= ceil(d_in/64)     */
+    const float *bn_shift;       /* DEVICE, d_in, nullable                                   */
+    const float *bn_mul;         /* DEVICE, d_in, nullable                                   */
+} bigcn_sage_layer;
+int bigcn_mean_norm(const int64_t *row_ptr, int64_t n, float *inv_deg, void *stream);
+size_t bigcn_sage_forward_workspace_bytes(int64_t n, const bigcn_sage_layer *layers, int n_layers);
+int bigcn_sage_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                       const float *inv_deg, int64_t n, const float *x, int64_t ld_x,
+                       const bigcn_sage_layer *layers, int n_layers, float *out, int64_t ld_out,
+                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Per-launch timing of the fused forward (measurement aid; HIP events on the caller's
@@ -224,6 +271,11 @@ int bigcn_forward_profiled(const bigcn_plan *plan, const int64_t *row_ptr, const
                            const bigcn_layer *layers, int n_layers, float *logits,
                            int64_t ld_logits, void *workspace, size_t workspace_bytes,
                            void *stream, bigcn_profile *profile);
+int bigcn_sage_forward_profiled(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                                const float *inv_deg, int64_t n, const float *x, int64_t ld_x,
+                                const bigcn_sage_layer *layers, int n_layers, float *out,
+                                int64_t ld_out, void *workspace, size_t workspace_bytes,
+                                void *stream, bigcn_profile *profile);
 int bigcn_profile_read(bigcn_profile *profile, float *launch_ms, int *calls);
 
 #ifdef __cplusplus

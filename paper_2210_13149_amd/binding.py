@@ -27,6 +27,7 @@ BIGCN_EHIP = -6
 MAX_K_BITS = 8192
 GEMM_AUTO, GEMM_VALU, GEMM_MFMA = 0, 1, 2
 MAX_FORWARD_D_OUT = 512
+VALIDATE_NONE, VALIDATE_GCN, VALIDATE_NEIGHBOURS = 0, 1, 2
 
 EXPORTS = (
     "bigcn_status_string", "bigcn_version", "bigcn_pack", "bigcn_binary_gemm",
@@ -34,6 +35,8 @@ EXPORTS = (
     "bigcn_plan_create", "bigcn_plan_destroy", "bigcn_plan_rows", "bigcn_plan_nnz", "bigcn_spmm",
     "bigcn_forward_workspace_bytes", "bigcn_forward_row_bytes", "bigcn_forward", "bigcn_profile_create",
     "bigcn_profile_destroy", "bigcn_forward_profiled", "bigcn_profile_read",
+    "bigcn_mean_norm", "bigcn_sage_forward_workspace_bytes", "bigcn_sage_forward",
+    "bigcn_sage_forward_profiled",
 )
 
 
@@ -47,6 +50,16 @@ class LayerDesc(ctypes.Structure):
     """Mirror of ``bigcn_layer``."""
     _fields_ = [
         ("w_bits", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
+        ("d_in", ctypes.c_int64), ("d_out", ctypes.c_int64), ("ld_words", ctypes.c_int64),
+        ("bn_shift", ctypes.c_void_p), ("bn_mul", ctypes.c_void_p),
+    ]
+
+
+class SageLayerDesc(ctypes.Structure):
+    """Mirror of ``bigcn_sage_layer``."""
+    _fields_ = [
+        ("w_self_bits", ctypes.c_void_p), ("alpha_self", ctypes.c_void_p),
+        ("w_nbr_bits", ctypes.c_void_p), ("alpha_nbr", ctypes.c_void_p),
         ("d_in", ctypes.c_int64), ("d_out", ctypes.c_int64), ("ld_words", ctypes.c_int64),
         ("bn_shift", ctypes.c_void_p), ("bn_mul", ctypes.c_void_p),
     ]
@@ -103,6 +116,15 @@ def lib() -> ctypes.CDLL:
         L.bigcn_forward_profiled.argtypes = L.bigcn_forward.argtypes + [vp]
         L.bigcn_profile_read.restype = i32
         L.bigcn_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+        L.bigcn_mean_norm.restype = i32
+        L.bigcn_mean_norm.argtypes = [vp, i64, vp, vp]
+        L.bigcn_sage_forward_workspace_bytes.restype = ctypes.c_size_t
+        L.bigcn_sage_forward_workspace_bytes.argtypes = [i64, ctypes.POINTER(SageLayerDesc), i32]
+        L.bigcn_sage_forward.restype = i32
+        L.bigcn_sage_forward.argtypes = [vp, vp, vp, vp, i64, vp, i64, ctypes.POINTER(SageLayerDesc), i32,
+                                         vp, i64, vp, ctypes.c_size_t, vp]
+        L.bigcn_sage_forward_profiled.restype = i32
+        L.bigcn_sage_forward_profiled.argtypes = L.bigcn_sage_forward.argtypes + [vp]
         _lib = L
     return _lib
 
@@ -216,13 +238,14 @@ def bigcn_gcn_norm(row_ptr: torch.Tensor, col_idx: torch.Tensor, want_vals: bool
 class Plan:
     """Owner of a ``bigcn_plan`` (destroyed with the object)."""
 
-    def __init__(self, row_ptr: torch.Tensor, col_idx: torch.Tensor, validate: bool = True):
+    def __init__(self, row_ptr: torch.Tensor, col_idx: torch.Tensor, validate=True):
+        """``validate``: False / True (pattern of A + I) or one of the ``VALIDATE_*`` values."""
         _dev(row_ptr, torch.int64, "row_ptr")
         _dev(col_idx, torch.int32, "col_idx")
         self.n = row_ptr.numel() - 1
         handle = ctypes.c_void_p()
         self._handle = None
-        _check(lib().bigcn_plan_create(_ptr(row_ptr), _ptr(col_idx), self.n, int(bool(validate)),
+        _check(lib().bigcn_plan_create(_ptr(row_ptr), _ptr(col_idx), self.n, int(validate),
                                        ctypes.byref(handle), _stream()), "bigcn_plan_create")
         self._handle = handle
 
@@ -387,3 +410,104 @@ class BiGCN:
     def forward(self, x: torch.Tensor, profile: Optional[Profile] = None) -> torch.Tensor:
         return bigcn_forward(self.plan, self.row_ptr, self.col_idx, self.dinv_sqrt, x, self.layers,
                              self.workspace, self.logits, profile)
+
+
+# ------------------------------------------------------------------------------------------
+# Bi-GraphSAGE (mean aggregator)
+# ------------------------------------------------------------------------------------------
+def bigcn_mean_norm(row_ptr: torch.Tensor) -> torch.Tensor:
+    """``1/|N_i|`` per CSR row (0 for an empty row)."""
+    _dev(row_ptr, torch.int64, "row_ptr")
+    n = row_ptr.numel() - 1
+    inv_deg = torch.empty((n,), dtype=torch.float32, device=row_ptr.device)
+    _check(lib().bigcn_mean_norm(_ptr(row_ptr), n, _ptr(inv_deg), _stream()), "bigcn_mean_norm")
+    return inv_deg
+
+
+class SageLayer:
+    """Device-resident parameters of one binarised mean-aggregator layer."""
+
+    def __init__(self, w_self_bits: torch.Tensor, alpha_self: torch.Tensor, w_nbr_bits: torch.Tensor,
+                 alpha_nbr: torch.Tensor, d_in: int, d_out: int,
+                 bn_shift: Optional[torch.Tensor] = None, bn_mul: Optional[torch.Tensor] = None):
+        self.w_self_bits = _dev(w_self_bits, torch.int64, "w_self_bits")
+        self.alpha_self = _dev(alpha_self, torch.float32, "alpha_self")
+        self.w_nbr_bits = _dev(w_nbr_bits, torch.int64, "w_nbr_bits")
+        self.alpha_nbr = _dev(alpha_nbr, torch.float32, "alpha_nbr")
+        if self.w_self_bits.stride(0) != self.w_nbr_bits.stride(0):
+            raise ValueError("both packed weight matrices must share one row stride")
+        self.d_in, self.d_out = int(d_in), int(d_out)
+        self.bn_shift = None if bn_shift is None else _dev(bn_shift, torch.float32, "bn_shift").contiguous()
+        self.bn_mul = None if bn_mul is None else _dev(bn_mul, torch.float32, "bn_mul").contiguous()
+
+    @classmethod
+    def from_weights(cls, w_self: torch.Tensor, w_nbr: torch.Tensor, bn_shift=None, bn_mul=None
+                     ) -> "SageLayer":
+        if w_self.shape != w_nbr.shape:
+            raise ValueError("W_theta and W_n must have the same shape")
+        bits_s, alpha_s = pack_weight(w_self)
+        bits_n, alpha_n = pack_weight(w_nbr)
+        return cls(bits_s, alpha_s, bits_n, alpha_n, w_self.shape[0], w_self.shape[1], bn_shift, bn_mul)
+
+    def desc(self) -> SageLayerDesc:
+        return SageLayerDesc(_ptr(self.w_self_bits), _ptr(self.alpha_self), _ptr(self.w_nbr_bits),
+                             _ptr(self.alpha_nbr), self.d_in, self.d_out, self.w_nbr_bits.stride(0),
+                             _ptr(self.bn_shift), _ptr(self.bn_mul))
+
+
+def _sage_descs(layers: Sequence[SageLayer]):
+    return (SageLayerDesc * len(layers))(*[l.desc() for l in layers])
+
+
+def bigcn_sage_forward_workspace_bytes(n: int, layers: Sequence[SageLayer]) -> int:
+    return int(lib().bigcn_sage_forward_workspace_bytes(int(n), _sage_descs(layers), len(layers)))
+
+
+def bigcn_sage_forward(plan: Plan, row_ptr: torch.Tensor, col_idx: torch.Tensor, inv_deg: torch.Tensor,
+                       x: torch.Tensor, layers: Sequence[SageLayer],
+                       workspace: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                       profile: Optional[Profile] = None) -> torch.Tensor:
+    """L-layer fused Bi-GraphSAGE forward; returns fp32 h^(L) (n, d_out of the last layer)."""
+    _dev(x, torch.float32, "x")
+    if x.dim() != 2 or (x.shape[1] > 1 and x.stride(1) != 1):
+        raise ValueError("x must be a row-major matrix")
+    n = x.shape[0]
+    descs = _sage_descs(layers)
+    if workspace is None:
+        need = bigcn_sage_forward_workspace_bytes(n, layers)
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = torch.empty((n, layers[-1].d_out), dtype=torch.float32, device=x.device)
+    args = (plan.handle, _ptr(row_ptr), _ptr(col_idx), _ptr(inv_deg), n, _ptr(x), x.stride(0), descs,
+            len(layers), _ptr(out), out.stride(0), _ptr(workspace), workspace.numel(), _stream())
+    if profile is None:
+        _check(lib().bigcn_sage_forward(*args), "bigcn_sage_forward")
+    else:
+        _check(lib().bigcn_sage_forward_profiled(*args, profile.handle), "bigcn_sage_forward_profiled")
+    return out
+
+
+class BiGraphSAGE:
+    """Neighbour-list graph + packed layer pairs + workspace, ready for repeated forward passes."""
+
+    def __init__(self, row_ptr: torch.Tensor, col_idx: torch.Tensor,
+                 weights: Sequence[Tuple[torch.Tensor, torch.Tensor]],
+                 bn: Optional[Sequence[Optional[Tuple[torch.Tensor, torch.Tensor]]]] = None,
+                 validate: bool = True):
+        self.row_ptr, self.col_idx = row_ptr, col_idx
+        self.n = row_ptr.numel() - 1
+        self.plan = Plan(row_ptr, col_idx, validate=VALIDATE_NEIGHBOURS if validate else VALIDATE_NONE)
+        self.inv_deg = bigcn_mean_norm(row_ptr)
+        bn = list(bn) if bn is not None else [None] * len(weights)
+        self.layers: List[SageLayer] = []
+        for (w_self, w_nbr), p in zip(weights, bn):
+            shift, mul = p if p is not None else (None, None)
+            self.layers.append(SageLayer.from_weights(w_self, w_nbr, shift, mul))
+        need = bigcn_sage_forward_workspace_bytes(self.n, self.layers)
+        self.workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=row_ptr.device)
+        self.out = torch.empty((self.n, self.layers[-1].d_out), dtype=torch.float32,
+                               device=row_ptr.device)
+
+    def forward(self, x: torch.Tensor, profile: Optional[Profile] = None) -> torch.Tensor:
+        return bigcn_sage_forward(self.plan, self.row_ptr, self.col_idx, self.inv_deg, x, self.layers,
+                                  self.workspace, self.out, profile)

@@ -96,12 +96,15 @@ int launch_bitgemm_mfma(const uint64_t *a_bits, const float *a_scale, int64_t m,
                         hipStream_t stream);
 
 // Aggregation of layer l fused with the rescale and with the binarisation of layer l+1.
+// Bi-GCN: dst_mul = next_row_mul = D^-1/2 and no own-row term.  Bi-GraphSAGE (mean aggregator):
+// dst_mul = 1/|N_i|, next_row_mul = nullptr, and the own-row term is described by self_*.
 struct FusedSpmmArgs {
     const bigcn_plan *plan;
     const int64_t *row_ptr;
     const int32_t *col_idx;
-    const float *dinv_sqrt;     // n
-    const float *src_scale;     // n: dinv_sqrt[k] * beta_k of this layer's input
+    const float *dst_mul;       // n: factor of the neighbour sum of node i
+    const float *src_scale;     // n: weight of source node k (its beta_k, times D^-1/2 for Bi-GCN;
+                                //    negative when the layout folds the last bit and that bit is -1)
     const void *c_rows;         // n rows in `layout`
     RowLayout layout;
     const float *alpha;         // d_out
@@ -117,8 +120,13 @@ struct FusedSpmmArgs {
     const float *next_mul;      // d_out, nullable
     uint64_t *next_bits;
     int64_t next_ld_words;
-    float *next_scale;          // n: dinv_sqrt[i] * beta_i of the next layer
+    float *next_scale;          // n: next_row_mul[i] * beta_i of the next layer
+    const float *next_row_mul;  // n, nullable (= 1)
     int next_fold_last_sign;    // the next layer's layout has fold_last: sign the stored scale
+    // own-row term, all nullptr when absent
+    const void *self_rows;      // n rows in `layout`: products with the second weight matrix
+    const float *self_alpha;    // d_out
+    const uint64_t *self_w_bits;// packed second weight matrix (for its last-bit term), stride w_ld_words
 };
 int launch_fused_spmm(const FusedSpmmArgs &args, hipStream_t stream);
 

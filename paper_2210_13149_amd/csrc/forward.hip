@@ -1,10 +1,12 @@
 // Fused L-layer driver (Eq. (1) with H^(0) = X, Sec. 4.2.3 per layer) and library metadata.
 //
-// Per layer l the stream carries two launches: the bit-GEMM, which turns the packed signs of
+// Per layer l the stream carries two steps: the bit-GEMM, which turns the packed signs of
 // the layer input into the integer products C (one compact row per node), and the fused
 // aggregation, which gathers those rows over the graph, applies beta_k / alpha_j / degree
 // scaling and emits either the next layer's packed signs and scales or the final logits.
 // Only the first layer needs a separate binarise+pack pass over the fp32 features.
+// The Bi-GraphSAGE driver (Sec. 4.4.2) is the same sequence with two bit-GEMMs per layer (one
+// product array per weight matrix) and an aggregation that adds the node's own row.
 #include <algorithm>
 #include <new>
 
@@ -13,19 +15,31 @@
 namespace bigcn {
 
 struct WorkspaceMap {
-    size_t bits_off, scale0_off, scale1_off, rows_off, total;
+    size_t bits_off, scale0_off, scale1_off, rows_off, self_rows_off, total;
 };
 
 static size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
-static bool layers_ok(int64_t n, const bigcn_layer *layers, int n_layers, int *status)
+// One layer as both drivers see it; w_self_bits == nullptr for Bi-GCN.
+struct LayerView {
+    const uint64_t *w_bits;
+    const float *alpha;
+    const uint64_t *w_self_bits;
+    const float *alpha_self;
+    int64_t d_in, d_out, ld_words;
+    const float *bn_shift, *bn_mul;
+};
+
+constexpr int kMaxLayers = BIGCN_MAX_LAYERS;
+
+static bool layers_ok(int64_t n, const LayerView *layers, int n_layers, bool own_term, int *status)
 {
     *status = BIGCN_OK;
-    if (layers == nullptr) { *status = BIGCN_ENULL; return false; }
-    if (n < 0 || n_layers <= 0) { *status = BIGCN_EINVAL; return false; }
+    if (n < 0 || n_layers <= 0 || n_layers > kMaxLayers) { *status = BIGCN_EINVAL; return false; }
     for (int l = 0; l < n_layers; ++l) {
-        const bigcn_layer &L = layers[l];
+        const LayerView &L = layers[l];
         if (L.w_bits == nullptr || L.alpha == nullptr) { *status = BIGCN_ENULL; return false; }
+        if (own_term && (L.w_self_bits == nullptr || L.alpha_self == nullptr)) { *status = BIGCN_ENULL; return false; }
         if (L.d_in <= 0 || L.d_out <= 0 || L.ld_words < (L.d_in + 63) / 64) { *status = BIGCN_EINVAL; return false; }
         if (l > 0 && L.d_in != layers[l - 1].d_out) { *status = BIGCN_EINVAL; return false; }
         if (L.d_in > BIGCN_MAX_K_BITS || L.d_out > BIGCN_MAX_FORWARD_D_OUT) { *status = BIGCN_ESHAPE; return false; }
@@ -33,7 +47,28 @@ static bool layers_ok(int64_t n, const bigcn_layer *layers, int n_layers, int *s
     return true;
 }
 
-static WorkspaceMap map_workspace(int64_t n, const bigcn_layer *layers, int n_layers)
+static int view_gcn(const bigcn_layer *layers, int n_layers, LayerView *out)
+{
+    if (layers == nullptr) return BIGCN_ENULL;
+    if (n_layers <= 0 || n_layers > kMaxLayers) return BIGCN_EINVAL;
+    for (int l = 0; l < n_layers; ++l)
+        out[l] = LayerView{layers[l].w_bits, layers[l].alpha, nullptr, nullptr, layers[l].d_in,
+                           layers[l].d_out, layers[l].ld_words, layers[l].bn_shift, layers[l].bn_mul};
+    return BIGCN_OK;
+}
+
+static int view_sage(const bigcn_sage_layer *layers, int n_layers, LayerView *out)
+{
+    if (layers == nullptr) return BIGCN_ENULL;
+    if (n_layers <= 0 || n_layers > kMaxLayers) return BIGCN_EINVAL;
+    for (int l = 0; l < n_layers; ++l)
+        out[l] = LayerView{layers[l].w_nbr_bits, layers[l].alpha_nbr, layers[l].w_self_bits,
+                           layers[l].alpha_self, layers[l].d_in, layers[l].d_out, layers[l].ld_words,
+                           layers[l].bn_shift, layers[l].bn_mul};
+    return BIGCN_OK;
+}
+
+static WorkspaceMap map_workspace(int64_t n, const LayerView *layers, int n_layers, bool own_term)
 {
     int64_t max_words = 0, max_row_bytes = 0;
     for (int l = 0; l < n_layers; ++l) {
@@ -46,6 +81,8 @@ static WorkspaceMap map_workspace(int64_t n, const bigcn_layer *layers, int n_la
     m.scale0_off = off; off = align_up(off + static_cast<size_t>(n) * sizeof(float));
     m.scale1_off = off; off = align_up(off + static_cast<size_t>(n) * sizeof(float));
     m.rows_off = off;   off = align_up(off + static_cast<size_t>(n) * max_row_bytes);
+    m.self_rows_off = off;
+    if (own_term) off = align_up(off + static_cast<size_t>(n) * max_row_bytes);
     m.total = off;
     return m;
 }
@@ -90,23 +127,35 @@ extern "C" int64_t bigcn_forward_row_bytes(int64_t d_in, int64_t d_out, int *sca
 
 extern "C" size_t bigcn_forward_workspace_bytes(int64_t n, const bigcn_layer *layers, int n_layers)
 {
+    LayerView view[kMaxLayers];
     int status;
-    if (!layers_ok(n, layers, n_layers, &status)) return 0;
-    return map_workspace(n, layers, n_layers).total;
+    if (view_gcn(layers, n_layers, view) != BIGCN_OK || !layers_ok(n, view, n_layers, false, &status)) return 0;
+    return map_workspace(n, view, n_layers, false).total;
 }
 
-static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
-                        const float *dinv_sqrt, int64_t n, const float *x, int64_t ld_x,
-                        const bigcn_layer *layers, int n_layers, float *logits, int64_t ld_logits,
-                        void *workspace, size_t workspace_bytes, void *stream, bigcn_profile *prof)
+extern "C" size_t bigcn_sage_forward_workspace_bytes(int64_t n, const bigcn_sage_layer *layers, int n_layers)
 {
-    if (plan == nullptr || row_ptr == nullptr || col_idx == nullptr || dinv_sqrt == nullptr ||
+    LayerView view[kMaxLayers];
+    int status;
+    if (view_sage(layers, n_layers, view) != BIGCN_OK || !layers_ok(n, view, n_layers, true, &status)) return 0;
+    return map_workspace(n, view, n_layers, true).total;
+}
+
+// dst_mul: factor of node i's neighbour sum; src_row_mul: factor folded into every stored source
+// scale (nullptr = 1).  Bi-GCN passes D^-1/2 for both; Bi-GraphSAGE passes 1/|N_i| and nullptr.
+static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                        const float *dst_mul, const float *src_row_mul, bool own_term, int64_t n,
+                        const float *x, int64_t ld_x, const LayerView *layers, int n_layers,
+                        float *logits, int64_t ld_logits, void *workspace, size_t workspace_bytes,
+                        void *stream, bigcn_profile *prof)
+{
+    if (plan == nullptr || row_ptr == nullptr || col_idx == nullptr || dst_mul == nullptr ||
         x == nullptr || logits == nullptr)
         return BIGCN_ENULL;
     int status;
-    if (!layers_ok(n, layers, n_layers, &status)) return status;
+    if (!layers_ok(n, layers, n_layers, own_term, &status)) return status;
     if (n != plan->n || ld_x < layers[0].d_in || ld_logits < layers[n_layers - 1].d_out) return BIGCN_EINVAL;
-    const WorkspaceMap map = map_workspace(n, layers, n_layers);
+    const WorkspaceMap map = map_workspace(n, layers, n_layers, own_term);
     if (n == 0) return BIGCN_OK;
     if (workspace == nullptr || workspace_bytes < map.total || reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
         return BIGCN_EWORKSPACE;
@@ -124,28 +173,34 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
     uint64_t *bits = reinterpret_cast<uint64_t *>(ws + map.bits_off);
     float *scale[2] = {reinterpret_cast<float *>(ws + map.scale0_off), reinterpret_cast<float *>(ws + map.scale1_off)};
     void *c_rows = ws + map.rows_off;
+    void *self_rows = own_term ? ws + map.self_rows_off : nullptr;
 
-    // layer 0 input: binarise X; the stored scale is dinv_sqrt[i] * beta_i
+    // layer 0 input: binarise X; the stored scale is src_row_mul[i] * beta_i
     int64_t words = (layers[0].d_in + 63) / 64;
     BIGCN_MARK();
-    int rc = launch_pack(x, n, layers[0].d_in, ld_x, 1, layers[0].bn_shift, layers[0].bn_mul, dinv_sqrt,
+    int rc = launch_pack(x, n, layers[0].d_in, ld_x, 1, layers[0].bn_shift, layers[0].bn_mul, src_row_mul,
                          choose_layout(layers[0].d_in, layers[0].d_out).fold_last, bits, words, scale[0], s);
     if (rc != BIGCN_OK) return rc;
     BIGCN_MARK();
 
     for (int l = 0; l < n_layers; ++l) {
-        const bigcn_layer &L = layers[l];
+        const LayerView &L = layers[l];
         const RowLayout layout = choose_layout(L.d_in, L.d_out);
         rc = launch_bitgemm_layout(bits, n, words, L.w_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1], c_rows,
                                    layout, s);
         if (rc != BIGCN_OK) return rc;
+        if (own_term) {
+            rc = launch_bitgemm_layout(bits, n, words, L.w_self_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1],
+                                       self_rows, layout, s);
+            if (rc != BIGCN_OK) return rc;
+        }
         BIGCN_MARK();
 
         FusedSpmmArgs a{};
         a.plan = plan;
         a.row_ptr = row_ptr;
         a.col_idx = col_idx;
-        a.dinv_sqrt = dinv_sqrt;
+        a.dst_mul = dst_mul;
         a.src_scale = scale[l & 1];
         a.c_rows = c_rows;
         a.layout = layout;
@@ -154,6 +209,11 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
         a.w_bits = L.w_bits;
         a.w_ld_words = L.ld_words;
         a.d_in = L.d_in;
+        if (own_term) {
+            a.self_rows = self_rows;
+            a.self_alpha = L.alpha_self;
+            a.self_w_bits = L.w_self_bits;
+        }
         if (l == n_layers - 1) {
             a.logits = logits;
             a.ld_logits = ld_logits;
@@ -164,6 +224,7 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
             a.next_bits = bits;
             a.next_ld_words = words;
             a.next_scale = scale[(l + 1) & 1];
+            a.next_row_mul = src_row_mul;
             a.next_fold_last_sign = choose_layout(layers[l + 1].d_in, layers[l + 1].d_out).fold_last;
         }
         rc = launch_fused_spmm(a, s);
@@ -174,13 +235,37 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
     return BIGCN_OK;
 }
 
+static int gcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                       const float *dinv_sqrt, int64_t n, const float *x, int64_t ld_x,
+                       const bigcn_layer *layers, int n_layers, float *logits, int64_t ld_logits,
+                       void *workspace, size_t workspace_bytes, void *stream, bigcn_profile *prof)
+{
+    LayerView view[kMaxLayers];
+    const int rc = view_gcn(layers, n_layers, view);
+    if (rc != BIGCN_OK) return rc;
+    return forward_impl(plan, row_ptr, col_idx, dinv_sqrt, dinv_sqrt, false, n, x, ld_x, view, n_layers,
+                        logits, ld_logits, workspace, workspace_bytes, stream, prof);
+}
+
+static int sage_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                        const float *inv_deg, int64_t n, const float *x, int64_t ld_x,
+                        const bigcn_sage_layer *layers, int n_layers, float *out, int64_t ld_out,
+                        void *workspace, size_t workspace_bytes, void *stream, bigcn_profile *prof)
+{
+    LayerView view[kMaxLayers];
+    const int rc = view_sage(layers, n_layers, view);
+    if (rc != BIGCN_OK) return rc;
+    return forward_impl(plan, row_ptr, col_idx, inv_deg, nullptr, true, n, x, ld_x, view, n_layers, out,
+                        ld_out, workspace, workspace_bytes, stream, prof);
+}
+
 extern "C" int bigcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
                              const float *dinv_sqrt, int64_t n, const float *x, int64_t ld_x,
                              const bigcn_layer *layers, int n_layers, float *logits,
                              int64_t ld_logits, void *workspace, size_t workspace_bytes, void *stream)
 {
-    return forward_impl(plan, row_ptr, col_idx, dinv_sqrt, n, x, ld_x, layers, n_layers, logits,
-                        ld_logits, workspace, workspace_bytes, stream, nullptr);
+    return gcn_forward(plan, row_ptr, col_idx, dinv_sqrt, n, x, ld_x, layers, n_layers, logits,
+                       ld_logits, workspace, workspace_bytes, stream, nullptr);
 }
 
 extern "C" int bigcn_forward_profiled(const bigcn_plan *plan, const int64_t *row_ptr,
@@ -190,8 +275,28 @@ extern "C" int bigcn_forward_profiled(const bigcn_plan *plan, const int64_t *row
                                       size_t workspace_bytes, void *stream, bigcn_profile *profile)
 {
     if (profile == nullptr) return BIGCN_ENULL;
-    return forward_impl(plan, row_ptr, col_idx, dinv_sqrt, n, x, ld_x, layers, n_layers, logits,
-                        ld_logits, workspace, workspace_bytes, stream, profile);
+    return gcn_forward(plan, row_ptr, col_idx, dinv_sqrt, n, x, ld_x, layers, n_layers, logits,
+                       ld_logits, workspace, workspace_bytes, stream, profile);
+}
+
+extern "C" int bigcn_sage_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                                  const float *inv_deg, int64_t n, const float *x, int64_t ld_x,
+                                  const bigcn_sage_layer *layers, int n_layers, float *out,
+                                  int64_t ld_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return sage_forward(plan, row_ptr, col_idx, inv_deg, n, x, ld_x, layers, n_layers, out, ld_out,
+                        workspace, workspace_bytes, stream, nullptr);
+}
+
+extern "C" int bigcn_sage_forward_profiled(const bigcn_plan *plan, const int64_t *row_ptr,
+                                           const int32_t *col_idx, const float *inv_deg, int64_t n,
+                                           const float *x, int64_t ld_x, const bigcn_sage_layer *layers,
+                                           int n_layers, float *out, int64_t ld_out, void *workspace,
+                                           size_t workspace_bytes, void *stream, bigcn_profile *profile)
+{
+    if (profile == nullptr) return BIGCN_ENULL;
+    return sage_forward(plan, row_ptr, col_idx, inv_deg, n, x, ld_x, layers, n_layers, out, ld_out,
+                        workspace, workspace_bytes, stream, profile);
 }
 
 extern "C" int bigcn_profile_create(int n_layers, int max_calls, bigcn_profile **out)

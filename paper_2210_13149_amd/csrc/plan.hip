@@ -1,6 +1,7 @@
-// Graph-side helpers: the coefficients of A~ = D^-1/2 (A+I) D^-1/2 (Sec. 3.1, Eq. (1)),
-// validation of the CSR pattern of A + I, and the aggregation plan (row order by decreasing
-// length for the power-law degree distributions of the paper's graphs).
+// Graph-side helpers: the coefficients of A~ = D^-1/2 (A+I) D^-1/2 (Sec. 3.1, Eq. (1)) and of
+// the mean aggregator 1/|N_i| (Sec. 4.4.2), validation of the CSR pattern, and the aggregation
+// plan (row order by decreasing length for the power-law degree distributions of the paper's
+// graphs).
 #include <algorithm>
 #include <new>
 #include <vector>
@@ -16,6 +17,16 @@ __global__ __launch_bounds__(kBlock) void dinv_sqrt_kernel(const int64_t *__rest
     if (i < n) {
         const float deg = static_cast<float>(row_ptr[i + 1] - row_ptr[i]);
         dinv[i] = 1.0f / sqrtf(deg);
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void inv_degree_kernel(const int64_t *__restrict__ row_ptr,
+                                                            int64_t n, float *__restrict__ inv_deg)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i < n) {
+        const int64_t deg = row_ptr[i + 1] - row_ptr[i];
+        inv_deg[i] = deg > 0 ? 1.0f / static_cast<float>(deg) : 0.0f;
     }
 }
 
@@ -36,9 +47,11 @@ __global__ __launch_bounds__(kBlock) void edge_norm_kernel(const int64_t *__rest
 }
 
 // Pattern checks; any violation sets *flag (plain store of a non-zero value: races are benign).
+// full_pattern: also require the self-loop and the symmetry of A + I.
 __global__ __launch_bounds__(kBlock) void validate_kernel(const int64_t *__restrict__ row_ptr,
                                                           const int32_t *__restrict__ col_idx,
-                                                          int64_t n, int *__restrict__ flag)
+                                                          int64_t n, int full_pattern,
+                                                          int *__restrict__ flag)
 {
     const int lane = lane_id();
     const int64_t wave = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block();
@@ -50,6 +63,7 @@ __global__ __launch_bounds__(kBlock) void validate_kernel(const int64_t *__restr
             const int64_t k = col_idx[p];
             if (k < 0 || k >= n) { *flag = 1; continue; }
             if (p > p0 && col_idx[p - 1] >= k) *flag = 2;          // not strictly increasing
+            if (!full_pattern) continue;
             if (k == i) { has_loop = true; continue; }
             // symmetry: binary search for i in row k
             int64_t lo = row_ptr[k], hi = row_ptr[k + 1];
@@ -62,7 +76,7 @@ __global__ __launch_bounds__(kBlock) void validate_kernel(const int64_t *__restr
             }
             if (!found) *flag = 3;
         }
-        if (__ballot(has_loop) == 0ull && lane == 0) *flag = 4;    // self-loop missing
+        if (full_pattern && __ballot(has_loop) == 0ull && lane == 0) *flag = 4;    // self-loop missing
     }
 }
 
@@ -89,11 +103,23 @@ extern "C" int bigcn_gcn_norm(const int64_t *row_ptr, const int32_t *col_idx, in
     return check_launch();
 }
 
+extern "C" int bigcn_mean_norm(const int64_t *row_ptr, int64_t n, float *inv_deg, void *stream)
+{
+    if (row_ptr == nullptr || inv_deg == nullptr) return BIGCN_ENULL;
+    if (n < 0) return BIGCN_EINVAL;
+    if (n == 0) return BIGCN_OK;
+    hipLaunchKernelGGL(inv_degree_kernel, dim3(static_cast<unsigned>((n + kBlock - 1) / kBlock)),
+                       dim3(kBlock), 0, as_stream(stream), row_ptr, n, inv_deg);
+    return check_launch();
+}
+
 extern "C" int bigcn_plan_create(const int64_t *row_ptr, const int32_t *col_idx, int64_t n,
                                  int validate, bigcn_plan **out, void *stream)
 {
     if (row_ptr == nullptr || col_idx == nullptr || out == nullptr) return BIGCN_ENULL;
     if (n < 0 || n >= (static_cast<int64_t>(1) << 31)) return BIGCN_EINVAL;
+    if (validate != BIGCN_VALIDATE_NONE && validate != BIGCN_VALIDATE_GCN && validate != BIGCN_VALIDATE_NEIGHBOURS)
+        return BIGCN_EINVAL;
     hipStream_t s = as_stream(stream);
 
     std::vector<int64_t> rp;
@@ -126,7 +152,7 @@ extern "C" int bigcn_plan_create(const int64_t *row_ptr, const int32_t *col_idx,
             int64_t blocks = (n + kWavesPerBlock - 1) / kWavesPerBlock;
             if (blocks > 256 * 32) blocks = 256 * 32;
             hipLaunchKernelGGL(validate_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s,
-                               row_ptr, col_idx, n, flag);
+                               row_ptr, col_idx, n, validate == BIGCN_VALIDATE_GCN ? 1 : 0, flag);
             ok = hipGetLastError() == hipSuccess &&
                  hipMemcpyAsync(&host_flag, flag, sizeof(int), hipMemcpyDeviceToHost, s) == hipSuccess &&
                  hipStreamSynchronize(s) == hipSuccess;

@@ -8,7 +8,7 @@
 //     narrow, and one neighbour when a row spans all 64 lanes;
 //   * column indices (and the per-neighbour weights) of up to 64 neighbours are fetched with
 //     one coalesced load and handed out by lane broadcast, so the inner loop issues only row
-//     loads and FMAs, eight row loads in flight per wavefront;
+//     loads and FMAs, four row loads in flight per wavefront;
 //   * rows are taken in order of decreasing length (plan): the longest rows are started
 //     first and each is shared by the four wavefronts of a workgroup (partial sums combined
 //     through LDS in a fixed order); every other row is owned by one wavefront.
@@ -238,6 +238,24 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
     }
 }
 
+// The node's own stored row (second product array of a layer with an own-row term), weighted by
+// the node's own scale exactly as a neighbour's row would be: pos = |t| * stored, sums of t.
+template <typename T, int G, int V, int WM>
+__device__ __forceinline__ void load_own_row(const char *__restrict__ own_lane_base, int64_t row_bytes,
+                                             const float *__restrict__ weights, int64_t row, int lane,
+                                             bool active, RowAcc<V> &own)
+{
+    own.clear();
+    Segment<T, V> seg;
+    if (active) seg.load(own_lane_base + row * row_bytes);
+    float t;
+    if (WM == kWeightEmbedded) t = embedded_weight<T, G, V>(seg, lane);
+    else t = weights[row];
+    own.sum_abs = fabsf(t);
+    own.sum_signed = t;
+    if (active) seg.fma(fabsf(t), own.pos);
+}
+
 // Sum the partial results of the 64/G lane slots; afterwards every lane holds the total.
 template <int G, int V, int WM>
 __device__ __forceinline__ void reduce_slots(RowAcc<V> &acc)
@@ -259,6 +277,7 @@ __device__ __forceinline__ void reduce_slots(RowAcc<V> &acc)
 
 // Public SpMM: stored position == output column, fp32 row-major output.
 struct EpiloguePlain {
+    static constexpr bool kSelf = false;
     float *out;
     int64_t ld_out;
     int d;                 // valid positions
@@ -268,7 +287,8 @@ struct EpiloguePlain {
     template <int G, int V>
     __device__ __forceinline__ void init(int, Lane<G, V> &) const {}
     template <int G, int V>
-    __device__ __forceinline__ void finish(const Lane<G, V> &, int64_t row, int lane, const RowAcc<V> &acc) const
+    __device__ __forceinline__ void finish(const Lane<G, V> &, int64_t row, int lane, const RowAcc<V> &acc,
+                                           const RowAcc<V> &) const
     {
         if (lane >= G) return;
         float *dst = out + row * ld_out + lane * V;
@@ -285,10 +305,15 @@ struct EpiloguePlain {
 
 // Fused layer: stored position g*V + v holds column g + G*v of the stored products.  The
 // neighbour sum of the true products is  mul * acc + bias * sum|w| + (+-1)_j * sum w  (the last
-// term only with a folded last bit); it is rescaled by dinv_i * alpha_j and either written as
-// fp32 logits or turned directly into the packed signs and the scale of the next layer's input.
-struct EpilogueFused {
-    const float *dinv_sqrt;
+// term only with a folded last bit); it is rescaled by dst_mul_i * alpha_j and either written as
+// fp32 output or turned directly into the packed signs and the scale of the next layer's input.
+//   Bi-GCN (Sec. 4.2.3):        dst_mul = D^-1/2, the source weights carry D^-1/2 beta.
+//   Bi-GraphSAGE (Sec. 4.4.2):  dst_mul = 1/|N_i|, the source weights carry beta, and the node's
+//                               own product row (second weight matrix) is added: kSelfTerm.
+template <bool kSelfTerm>
+struct EpilogueFusedT {
+    static constexpr bool kSelf = kSelfTerm;
+    const float *dst_mul;
     const float *alpha;
     int d_out;
     float mul;
@@ -303,7 +328,12 @@ struct EpilogueFused {
     uint64_t *next_bits;
     int64_t next_ld_words;
     float *next_scale;
+    const float *next_row_mul;       // nullable: per-node factor folded into the next stored scale
     int next_fold_last_sign;
+    // own-row term (kSelfTerm only): rows in the same layout, their column scales and last bits
+    const char *self_rows;
+    const float *self_alpha;
+    const uint64_t *self_last_bit_word;
 
     template <int G, int V>
     struct Lane {
@@ -311,6 +341,8 @@ struct EpilogueFused {
         float last[V];       // +-1: sign of the weight's last input bit, 0 without folded bit
         float shift[V];
         float mul[V];
+        float self_alpha[kSelfTerm ? V : 1];
+        float self_last[kSelfTerm ? V : 1];
     };
     template <int G, int V>
     __device__ __forceinline__ void init(int lane, Lane<G, V> &c) const
@@ -326,12 +358,19 @@ struct EpilogueFused {
                 c.last[v] = ((last_bit_word[col * w_ld_words] >> last_bit_shift) & 1ull) ? 1.0f : -1.0f;
             c.shift[v] = (in && next_shift != nullptr) ? next_shift[col] : 0.0f;
             c.mul[v] = (in && next_mul != nullptr) ? next_mul[col] : 1.0f;
+            if constexpr (kSelfTerm) {
+                c.self_alpha[v] = in ? self_alpha[col] : 0.0f;
+                c.self_last[v] = 0.0f;
+                if (in && self_last_bit_word != nullptr)
+                    c.self_last[v] = ((self_last_bit_word[col * w_ld_words] >> last_bit_shift) & 1ull) ? 1.0f : -1.0f;
+            }
         }
     }
     template <int G, int V>
-    __device__ __forceinline__ void finish(const Lane<G, V> &c, int64_t row, int lane, const RowAcc<V> &acc) const
+    __device__ __forceinline__ void finish(const Lane<G, V> &c, int64_t row, int lane, const RowAcc<V> &acc,
+                                           const RowAcc<V> &self) const
     {
-        const float di = dinv_sqrt[row];
+        const float di = dst_mul[row];
         const int g = lane & (G - 1);
         const bool first_slot = lane < G;
         const float base = bias * acc.sum_abs;
@@ -340,6 +379,11 @@ struct EpilogueFused {
         for (int v = 0; v < V; ++v) {
             const float total = fmaf(mul, acc.pos[v], fmaf(c.last[v], acc.sum_signed, base));
             h[v] = di * c.alpha[v] * total;
+            if constexpr (kSelfTerm) {
+                // the node's own products, weighted by its own scale (sign = its last input bit)
+                const float own = fmaf(mul, self.pos[v], fmaf(c.self_last[v], self.sum_signed, bias * self.sum_abs));
+                h[v] = fmaf(c.self_alpha[v], own, h[v]);
+            }
         }
         if (logits != nullptr) {
             if (first_slot) {
@@ -371,7 +415,8 @@ struct EpilogueFused {
         for (int q = 0; q < kWords; ++q)
             if (lane == q && q < n_words) next_bits[row * next_ld_words + q] = words[q];
         if (lane == 0) {
-            float s = di * (sum / static_cast<float>(d_out));
+            float s = sum / static_cast<float>(d_out);
+            if (next_row_mul != nullptr) s *= next_row_mul[row];
             if (next_fold_last_sign) {
                 uint64_t last = 0;
 #pragma unroll
@@ -407,6 +452,9 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(
     typename Epilogue::template Lane<G, V> ctx;
     epi.template init<G, V>(lane, ctx);
     RowAcc<V> acc;
+    RowAcc<V> own;      // only filled (and only read) by epilogues with an own-row term
+    const char *own_lane_base = nullptr;
+    if constexpr (Epilogue::kSelf) own_lane_base = epi.self_rows + static_cast<int64_t>(g) * V * sizeof(T);
 
     if (static_cast<int64_t>(blockIdx.x) < n_block_rows) {
         // one long row shared by the four wavefronts: contiguous quarters, multiples of 64
@@ -436,7 +484,9 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(
                 acc.sum_abs += partial[w][V][lane];
                 acc.sum_signed += partial[w][V + 1][lane];
             }
-            epi.template finish<G, V>(ctx, row, lane, acc);
+            if constexpr (Epilogue::kSelf)
+                load_own_row<T, G, V, WM>(own_lane_base, row_bytes, weights, row, lane, active, own);
+            epi.template finish<G, V>(ctx, row, lane, acc, own);
         }
         return;
     }
@@ -448,9 +498,11 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(
         const int64_t row = row_order[entry];
         const int64_t p0 = row_ptr[row], p1 = row_ptr[row + 1];
         acc.clear();
+        if constexpr (Epilogue::kSelf)
+            load_own_row<T, G, V, WM>(own_lane_base, row_bytes, weights, row, lane, active, own);
         accumulate_range<T, G, V, WM>(col_idx, weights, lane_base, row_bytes, p0, p1, lane, active, acc);
         reduce_slots<G, V, WM>(acc);
-        epi.template finish<G, V>(ctx, row, lane, acc);
+        epi.template finish<G, V>(ctx, row, lane, acc, own);
     }
 }
 
@@ -526,11 +578,12 @@ RowLayout choose_layout(int64_t d_in, int64_t d_out)
     return l;
 }
 
-int launch_fused_spmm(const FusedSpmmArgs &a, hipStream_t stream)
+template <bool kSelfTerm>
+static int launch_fused_spmm_t(const FusedSpmmArgs &a, hipStream_t stream)
 {
     const RowLayout &l = a.layout;
-    EpilogueFused epi{};
-    epi.dinv_sqrt = a.dinv_sqrt;
+    EpilogueFusedT<kSelfTerm> epi{};
+    epi.dst_mul = a.dst_mul;
     epi.alpha = a.alpha;
     epi.d_out = static_cast<int>(a.d_out);
     epi.mul = l.mul();
@@ -545,7 +598,11 @@ int launch_fused_spmm(const FusedSpmmArgs &a, hipStream_t stream)
     epi.next_bits = a.next_bits;
     epi.next_ld_words = a.next_ld_words;
     epi.next_scale = a.next_scale;
+    epi.next_row_mul = a.next_row_mul;
     epi.next_fold_last_sign = a.next_fold_last_sign;
+    epi.self_rows = static_cast<const char *>(a.self_rows);
+    epi.self_alpha = a.self_alpha;
+    epi.self_last_bit_word = (l.fold_last && a.self_w_bits != nullptr) ? a.self_w_bits + (a.d_in - 1) / 64 : nullptr;
     const int valid = l.positions();
     const int64_t rb = l.row_bytes();
 #define BIGCN_FUSED(TT, VV)                                                                             \
@@ -570,6 +627,12 @@ int launch_fused_spmm(const FusedSpmmArgs &a, hipStream_t stream)
     BIGCN_FUSED(float, 4);
 #undef BIGCN_FUSED
 #undef BIGCN_FUSED_EMBEDDED
+}
+
+int launch_fused_spmm(const FusedSpmmArgs &a, hipStream_t stream)
+{
+    if (a.self_rows != nullptr) return launch_fused_spmm_t<true>(a, stream);
+    return launch_fused_spmm_t<false>(a, stream);
 }
 
 }  // namespace bigcn

@@ -38,12 +38,12 @@ def words_to_numpy(bits) -> np.ndarray:
 
 
 def neighbours_closed(row_ptr: np.ndarray, col_idx: np.ndarray, rows_mask: np.ndarray) -> np.ndarray:
-    """Mask of nodes that have a marked node in their closed neighbourhood (the pattern holds
-    the self-loop, so this is one hop over the stored entries)."""
+    """Mask of nodes that are marked or have a marked node among their stored entries (the
+    closed neighbourhood, whether or not the pattern holds the self-loop)."""
     marked_entry = rows_mask[col_idx]
     counts = np.add.reduceat(marked_entry.astype(np.int64), row_ptr[:-1].clip(max=max(col_idx.size - 1, 0)))
     counts[np.diff(row_ptr) == 0] = 0
-    return counts > 0
+    return (counts > 0) | rows_mask
 
 
 def sign_error_bound(row_ptr, col_idx, a_tilde, zeta) -> np.ndarray:
@@ -56,8 +56,43 @@ def sign_error_bound(row_ptr, col_idx, a_tilde, zeta) -> np.ndarray:
     return (terms + 4.0) * 2.0 ** -24 * mag
 
 
+class _GcnOracle:
+    """Per-layer oracle of the Bi-GCN forward and the fp32 error bound of its output."""
+
+    def __init__(self, work):
+        import oracle
+        self.work = work
+        self.coeff = oracle.gcn_norm(work.row_ptr, work.col_idx)
+
+    def layer(self, l, h, shift, mul):
+        import oracle
+        w = self.work
+        rec = oracle.layer(w.row_ptr, w.col_idx, self.coeff, h, w.weights[l], shift, mul)
+        return rec["out"], sign_error_bound(w.row_ptr, w.col_idx, self.coeff, rec["zeta"])
+
+
+class _SageOracle:
+    """The same for the Bi-GraphSAGE forward: the own term is one more summand of the fp32 sum."""
+
+    def __init__(self, work):
+        import oracle
+        self.work = work
+        self.coeff = oracle.mean_norm(work.row_ptr, work.col_idx)
+
+    def layer(self, l, h, shift, mul):
+        import oracle
+        w = self.work
+        rec = oracle.sage_layer(w.row_ptr, w.col_idx, self.coeff, h, w.weights[l][0], w.weights[l][1],
+                                shift, mul)
+        mag = oracle.aggregate(w.row_ptr, w.col_idx, self.coeff, np.abs(rec["zeta_nbr"]))
+        mag += np.abs(rec["zeta_self"])
+        terms = np.diff(w.row_ptr).astype(np.float64)[:, None]
+        return rec["out"], (terms + 6.0) * 2.0 ** -24 * mag
+
+
 def compare_forward_layerwise(work, bn, run_gpu_prefix, cancellation_aware=False, log=None):
-    """Layer-by-layer parity of the fused forward against the oracle.
+    """Layer-by-layer parity of the fused forward against the oracle (Bi-GCN or Bi-GraphSAGE,
+    as the workload's config says).
 
     ``bn[l]`` is the frozen standardisation ``(shift, mul)`` of layer l's input, ``None`` for no
     standardisation, or the string ``"calibrate"``: the parameters are then computed here from
@@ -79,7 +114,7 @@ def compare_forward_layerwise(work, bn, run_gpu_prefix, cancellation_aware=False
     import oracle
     say = log if log is not None else (lambda *a: None)
     n_layers = len(work.weights)
-    a_tilde = oracle.gcn_norm(work.row_ptr, work.col_idx)
+    model = _SageOracle(work) if work.config.model == "sage" else _GcnOracle(work)
     tainted = np.zeros(work.n, dtype=bool)
     params = []
     stats = []
@@ -102,11 +137,8 @@ def compare_forward_layerwise(work, bn, run_gpu_prefix, cancellation_aware=False
             stats[-1]["sign_flips"] = int((flips & clean[:, None]).sum())
             tainted = neighbours_closed(work.row_ptr, work.col_idx, tainted | flips.any(axis=1))
             del flips, margin, illegal, bound, gpu
-        rec = oracle.layer(work.row_ptr, work.col_idx, a_tilde, h, work.weights[l - 1], shift, mul)
+        ref, bound = model.layer(l - 1, h, shift, mul)
         say(f"oracle layer {l} done")
-        ref = rec["out"]
-        bound = sign_error_bound(work.row_ptr, work.col_idx, a_tilde, rec["zeta"])
-        del rec
         gpu = run_gpu_prefix(l, params)
         say(f"gpu prefix {l} done")
         assert gpu.shape == ref.shape

@@ -1,0 +1,172 @@
+"""Parity of the Bi-GraphSAGE path (mean aggregator, Sec. 4.4.2) against the CPU oracle, through
+the C ABI: the degree coefficients, plan validation for neighbour lists, and the fused forward
+layer by layer (helpers.compare_forward_layerwise) on scaled-down versions of the two workloads
+and on small graphs that cover every product-row format, empty rows and the folded last bit."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import compare_forward_layerwise, to_device
+from workloads import chung_lu_csr, make_workload, scaled_config
+from workloads.build import Workload
+from workloads.configs import WorkloadConfig
+from workloads.features import make_weights
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    from paper_2210_13149_amd import binding
+    assert torch.cuda.is_available()
+    binding.lib()
+    return binding
+
+
+def sage_prefix_runner(B, work):
+    """run(l, params): fused Bi-GraphSAGE forward over the first l layers."""
+    import torch
+    drp, dci, dx = to_device(work.row_ptr, work.col_idx, work.x)
+    dweights = [(to_device(ws), to_device(wn)) for ws, wn in work.weights]
+    plan = B.Plan(drp, dci, validate=B.VALIDATE_NEIGHBOURS)
+    inv_deg = B.bigcn_mean_norm(drp)
+    layers = []
+
+    def run(l, params):
+        while len(layers) < l:
+            p = params[len(layers)]
+            shift, mul = (None, None) if p is None else tuple(to_device(*p))
+            ws, wn = dweights[len(layers)]
+            layers.append(B.SageLayer.from_weights(ws, wn, shift, mul))
+        out = B.bigcn_sage_forward(plan, drp, dci, inv_deg, dx, layers[:l])
+        torch.cuda.synchronize()
+        return out.cpu().numpy()
+
+    return run
+
+
+def small_sage_workload(n, n_edges, dims, seed, i0=2.0):
+    rng = np.random.Generator(np.random.PCG64([seed, 7]))
+    rp, ci = chung_lu_csr(n, n_edges, 2.5, i0, seed=seed, self_loops=False)
+    x = rng.standard_normal((n, dims[0])).astype(np.float32)
+    weights = list(zip(make_weights(dims, rng), make_weights(dims, rng)))
+    cfg = WorkloadConfig(f"sage-{seed}", "none", n, n_edges, i0, tuple(dims), "normal", 1.0, "all", seed,
+                         model="sage")
+    return Workload(cfg, rp, ci, x, weights)
+
+
+def test_mean_norm_matches_oracle_and_handles_empty_rows(B):
+    rp, ci = chung_lu_csr(5000, 4000, 2.5, 2.0, seed=11, self_loops=False)
+    deg = np.diff(rp)
+    assert (deg == 0).any() and deg.max() > 64
+    got = B.bigcn_mean_norm(to_device(rp)).cpu().numpy()
+    want = np.where(deg > 0, 1.0 / np.maximum(deg, 1), 0.0)
+    # one correctly rounded fp32 division
+    assert np.array_equal(got, want.astype(np.float32))
+    coeff = oracle.mean_norm(rp, ci)
+    assert np.allclose(np.repeat(got, deg), coeff, rtol=6e-8, atol=0)
+
+
+def test_plan_validation_modes(B):
+    rp, ci = chung_lu_csr(300, 900, 2.5, 2.0, seed=5, self_loops=False)
+    drp, dci = to_device(rp, ci)
+    B.Plan(drp, dci, validate=B.VALIDATE_NEIGHBOURS).destroy()
+    with pytest.raises(B.BigcnError) as err:
+        B.Plan(drp, dci, validate=B.VALIDATE_GCN)            # no self-loops
+    assert err.value.status == B.BIGCN_EGRAPH
+    bad = ci.copy()
+    bad[3] = 300                                             # out of range
+    with pytest.raises(B.BigcnError) as err:
+        B.Plan(drp, to_device(bad), validate=B.VALIDATE_NEIGHBOURS)
+    assert err.value.status == B.BIGCN_EGRAPH
+    row = int(np.argmax(np.diff(rp) >= 2))
+    swapped = ci.copy()
+    p = rp[row]
+    swapped[p], swapped[p + 1] = swapped[p + 1], swapped[p]  # order broken
+    with pytest.raises(B.BigcnError) as err:
+        B.Plan(drp, to_device(swapped), validate=B.VALIDATE_NEIGHBOURS)
+    assert err.value.status == B.BIGCN_EGRAPH
+    with pytest.raises(B.BigcnError) as err:
+        B.Plan(drp, dci, validate=7)
+    assert err.value.status == B.BIGCN_EINVAL
+
+
+@pytest.mark.parametrize("name,n_scaled", [("s4", 6000), ("s5", 20000)])
+def test_sage_forward_matches_oracle(B, name, n_scaled):
+    work = make_workload(scaled_config(name, n_scaled))
+    assert work.config.model == "sage" and not (work.col_idx == np.repeat(
+        np.arange(work.n), np.diff(work.row_ptr))).any()
+    bn = ["calibrate"] * work.config.n_layers
+    stats = compare_forward_layerwise(work, bn, sage_prefix_runner(B, work))
+    print(name, stats)
+    assert stats[0]["rows_compared"] == work.n
+    assert stats[-1]["rows_compared"] >= 0.5 * work.n
+
+
+# d_in / d_out pairs chosen to reach: one-byte rows with and without the embedded scale, the
+# folded last bit (d_in = 256), fp16 rows, fp32 rows, 16 values per lane (d_out > 256), and
+# graphs with empty rows and rows long enough for the workgroup-per-row path.
+@pytest.mark.parametrize("dims,n,n_edges,i0", [
+    ((64, 40, 7), 3000, 2500, 2.0),
+    ((100, 256, 47), 3000, 40000, 1.2),
+    ((255, 256, 256, 5), 2000, 9000, 2.0),
+    ((257, 300, 12), 2000, 9000, 2.0),
+    ((130, 512, 512, 9), 1500, 30000, 1.1),
+    ((2100, 33, 64, 3), 1200, 5000, 2.0),
+])
+def test_sage_forward_formats_and_edge_cases(B, dims, n, n_edges, i0):
+    work = small_sage_workload(n, n_edges, dims, seed=sum(dims), i0=i0)
+    deg = np.diff(work.row_ptr)
+    if n_edges < n:
+        assert (deg == 0).any()
+    if i0 < 1.5:
+        assert deg.max() >= 256
+    for bn in (["calibrate"] * (len(dims) - 1), [None] * (len(dims) - 1)):
+        stats = compare_forward_layerwise(work, bn, sage_prefix_runner(B, work))
+        assert stats[0]["rows_compared"] == n
+        assert stats[-1]["rows_compared"] >= 0.5 * n
+
+
+def test_sage_isolated_node_output_is_its_own_term_and_runs_are_identical(B):
+    import torch
+    work = small_sage_workload(2000, 1200, (96, 128, 10), seed=77)
+    deg = np.diff(work.row_ptr)
+    lonely = np.flatnonzero(deg == 0)
+    assert lonely.size > 0
+    run = sage_prefix_runner(B, work)
+    bn = [None, None]
+    h1 = run(1, bn)
+    sign, beta = oracle.binarize_rows(work.x)
+    bt, alpha = oracle.binarize_weight(work.weights[0][0])
+    own = oracle.rescale(oracle.sign_matmul(sign[lonely], bt), beta[lonely], alpha)
+    assert np.allclose(h1[lonely], own, rtol=1e-5, atol=1e-6)
+    a, b = run(2, bn), run(2, bn)
+    assert np.array_equal(a, b)
+
+
+def test_sage_model_wrapper_and_error_paths(B):
+    import torch
+    work = small_sage_workload(800, 3000, (70, 64, 6), seed=3)
+    drp, dci, dx = to_device(work.row_ptr, work.col_idx, work.x)
+    ref, used = oracle.sage_forward(work.row_ptr, work.col_idx, work.x, work.weights,
+                                    calibrate=[True, True])
+    model = B.BiGraphSAGE(drp, dci, [(to_device(a), to_device(b)) for a, b in work.weights],
+                          [tuple(to_device(*p)) for p in used])
+    first = model.forward(dx).clone()
+    second = model.forward(dx)
+    assert torch.equal(first, second) and second.data_ptr() == model.out.data_ptr()
+    ok = np.abs(first.cpu().numpy() - ref) <= 1e-5 * np.abs(ref) + 1e-6
+    assert ok.mean() > 0.9
+    # workspace too small / wrong layer chain are reported, not executed
+    with pytest.raises(B.BigcnError) as err:
+        B.bigcn_sage_forward(model.plan, drp, dci, model.inv_deg, dx, model.layers,
+                             workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert err.value.status == B.BIGCN_EWORKSPACE
+    with pytest.raises(B.BigcnError) as err:
+        B.bigcn_sage_forward(model.plan, drp, dci, model.inv_deg, dx, model.layers[::-1])
+    assert err.value.status == B.BIGCN_EINVAL
+    need = B.bigcn_sage_forward_workspace_bytes(work.n, model.layers)
+    gcn_like = B.bigcn_forward_workspace_bytes(
+        work.n, [B.Layer(l.w_nbr_bits, l.alpha_nbr, l.d_in, l.d_out) for l in model.layers])
+    assert need > gcn_like        # second product array

@@ -6,7 +6,10 @@ fused aggregation) over one seeded synthetic graph, with every input already res
 HBM.  The default workload is the largest of the five (the OGBN-Products-shaped one), on which
 the aggregation's bandwidth target is stated.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1..c5]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1..c5 | s4 | s5]
+
+s4 / s5 run the Bi-GraphSAGE forward (mean aggregator, two weight matrices per layer) through
+the same kernels; they are extra workloads, not the headline configuration.
 """
 from __future__ import annotations
 
@@ -48,6 +51,8 @@ def build_model(work, B):
     cfg = work.config
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     drp, dci, dx = dev(work.row_ptr), dev(work.col_idx), dev(work.x)
+    if cfg.model == "sage":
+        return build_sage_model(work, B, drp, dci, dx)
     weights = [dev(w) for w in work.weights]
     plan = B.Plan(drp, dci, validate=True)
     dinv, _ = B.bigcn_gcn_norm(drp, dci)
@@ -68,15 +73,43 @@ def build_model(work, B):
     logits = torch.empty((work.n, layers[-1].d_out), dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
     return dict(plan=plan, row_ptr=drp, col_idx=dci, dinv=dinv, x=dx, layers=layers,
-                workspace=workspace, logits=logits)
+                workspace=workspace, logits=logits, forward=B.bigcn_forward)
+
+
+def build_sage_model(work, B, drp, dci, dx):
+    """The same set-up for a Bi-GraphSAGE workload (neighbour-list graph, weight pairs)."""
+    import numpy as np
+    import torch
+    cfg = work.config
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    plan = B.Plan(drp, dci, validate=B.VALIDATE_NEIGHBOURS)
+    inv_deg = B.bigcn_mean_norm(drp)
+    layers = []
+    for l, (w_self, w_nbr) in enumerate(work.weights):
+        shift = mul = None
+        if l == 0 or cfg.bn_layers == "all":
+            if l == 0:
+                shift, mul = standardisation(dx)
+            else:
+                h = B.bigcn_sage_forward(plan, drp, dci, inv_deg, dx, layers)
+                shift, mul = standardisation(h)
+                del h
+        layers.append(B.SageLayer.from_weights(dev(w_self), dev(w_nbr), shift, mul))
+    need = B.bigcn_sage_forward_workspace_bytes(work.n, layers)
+    workspace = torch.empty((need,), dtype=torch.uint8, device="cuda")
+    out = torch.empty((work.n, layers[-1].d_out), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    return dict(plan=plan, row_ptr=drp, col_idx=dci, dinv=inv_deg, x=dx, layers=layers,
+                workspace=workspace, logits=out, forward=B.bigcn_sage_forward)
 
 
 def aggregation_bytes(cfg, nnz, layer, B):
     """Algorithmic bytes of one launch of the fused aggregation of `layer`: per stored entry a
     4-byte column index, one gathered row of integer products and (unless the row carries it) a
     4-byte source scale; per node 8 bytes of row pointer, 4 bytes of row order, 4 bytes of
-    dinv_sqrt and the output (packed signs + scale, or fp32 logits).  Also the compulsory minimum
-    (every array read or written exactly once)."""
+    per-node factor and the output (packed signs + scale, or fp32 logits); with an own-row term
+    (Bi-GraphSAGE) also the node's own product row and scale.  Also the compulsory minimum (every
+    array read or written exactly once)."""
     d_in, d_out = cfg.dims[layer], cfg.dims[layer + 1]
     row_bytes, embedded = B.bigcn_forward_row_bytes(d_in, d_out)
     scale_bytes = 0 if embedded else 4
@@ -84,6 +117,8 @@ def aggregation_bytes(cfg, nnz, layer, B):
     last = layer == cfg.n_layers - 1
     out_bytes = 4 * d_out if last else 8 * ((d_out + 63) // 64) + 4
     per_node = 8 + 4 + 4 + out_bytes
+    if cfg.model == "sage":
+        per_node += row_bytes + scale_bytes
     gather = nnz * (4 + scale_bytes + row_bytes) + n * per_node
     minimum = nnz * 4 + n * (scale_bytes + row_bytes) + n * per_node
     return gather, minimum, row_bytes
@@ -130,8 +165,9 @@ def cpu_baseline(work, target_nodes):
     cfg = work.config
     small = work if target_nodes >= work.n else make_workload(scaled_config(cfg.name, target_nodes))
     calibrate = [True] + [cfg.bn_layers == "all"] * (cfg.n_layers - 1)
+    run = oracle.sage_forward if cfg.model == "sage" else oracle.forward
     t0 = time.perf_counter()
-    oracle.forward(small.row_ptr, small.col_idx, small.x, small.weights, calibrate=calibrate)
+    run(small.row_ptr, small.col_idx, small.x, small.weights, calibrate=calibrate)
     dt = time.perf_counter() - t0
     return {"value": small.n / dt, "unit": "nodes/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"whole {cfg.n_layers}-layer oracle forward (with its calibration passes) on "
@@ -148,7 +184,8 @@ def main():
     ap.add_argument("--workload", default="c5")
     ap.add_argument("--cpu-baseline-nodes", type=int, default=-1,
                     help="nodes in the oracle's timed sample (-1 = the whole workload, about 10 s "
-                         "of CPU work for c5 on 16 cores; 0 = skip the cpu_baseline leg)")
+                         "of CPU work for c5 on 16 cores, except s5: 400000 nodes; 0 = skip the "
+                         "cpu_baseline leg)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one device-to-device copy kernel of this many MiB (a known "
                          "traffic figure to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings by)")
@@ -185,8 +222,8 @@ def main():
     profile = B.Profile(n_layers, steps)
 
     def step(prof=None):
-        B.bigcn_forward(m["plan"], m["row_ptr"], m["col_idx"], m["dinv"], m["x"], m["layers"],
-                        m["workspace"], m["logits"], prof)
+        m["forward"](m["plan"], m["row_ptr"], m["col_idx"], m["dinv"], m["x"], m["layers"],
+                     m["workspace"], m["logits"], prof)
 
     for _ in range(warmup):
         step()
@@ -208,7 +245,7 @@ def main():
     for l in range(n_layers):
         t_gemm = launch_ms[1 + 2 * l] * 1e-3
         t_spmm = launch_ms[2 + 2 * l] * 1e-3
-        macs = work.n * cfg.dims[l] * cfg.dims[l + 1]
+        macs = work.n * cfg.dims[l] * cfg.dims[l + 1] * (2 if cfg.model == "sage" else 1)
         gather, minimum, row_bytes = aggregation_bytes(cfg, work.nnz, l, B)
         gemm.append({"layer": l, "ms": t_gemm * 1e3, "binary_op_per_s": macs / t_gemm,
                      "frac_valu_peak": macs / t_gemm / VALU_BINARY_MAC_PEAK})
@@ -229,11 +266,14 @@ def main():
 
     result = {
         "metric": "Bi-GCN forward nodes/s; bit-GEMM binary-op/s; SpMM HBM GB/s (% roofline)",
+        "model": "Bi-GCN" if cfg.model == "gcn" else "Bi-GraphSAGE (mean aggregator)",
         "value": nodes_per_s, "unit": "nodes/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u64 xor/popcount + f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.stands_in_for}-shaped Chung-Lu graph, {work.n} nodes, "
-                               f"{cfg.n_edges} undirected edges (+ self-loops), dims "
+                               f"{cfg.n_edges} undirected edges "
+                               + ("(+ self-loops), Bi-GCN, dims " if cfg.model == "gcn" else
+                                  "(neighbour lists), Bi-GraphSAGE mean aggregator, dims ")
                                + "-".join(str(d) for d in cfg.dims),
                    "layers": n_layers, "nnz": work.nnz, "standardisation": cfg.bn_layers},
         "pack_ms": launch_ms[0],
@@ -242,7 +282,8 @@ def main():
         "bit_gemm_binary_op_per_s": max(g["binary_op_per_s"] for g in gemm),
         "spmm_GBps": achieved,
         "roofline": roofline,
-        "paper_theory": {k: v for k, v in cost_model.summary(cfg.n_nodes, cfg.n_edges, cfg.dims).items()
+        "paper_theory": {k: v for k, v in (cost_model.sage_summary if cfg.model == "sage" else
+                                           cost_model.summary)(cfg.n_nodes, cfg.n_edges, cfg.dims).items()
                          if k.endswith("ratio")},
     }
     if not args.no_gemm_sweep:
@@ -253,7 +294,8 @@ def main():
         t0 = time.perf_counter()
         del m
         torch.cuda.empty_cache()
-        sample = cfg.n_nodes if args.cpu_baseline_nodes < 0 else min(args.cpu_baseline_nodes, cfg.n_nodes)
+        whole = 400000 if cfg.name == "s5" else cfg.n_nodes
+        sample = whole if args.cpu_baseline_nodes < 0 else min(args.cpu_baseline_nodes, cfg.n_nodes)
         result["cpu_baseline"] = cpu_baseline(work, sample)
         log(f"[bench] cpu_baseline leg {time.perf_counter() - t0:.1f} s")
     print(json.dumps(result), flush=True)

@@ -58,7 +58,7 @@ enum RowKind { kI8 = 0, kF16 = 1, kF32 = 2 };
 
 struct RowLayout {
     int groups;      // lanes that share one stored row (power of two, 2..64)
-    int vec;         // values per lane (4, 8 or 16)
+    int vec;         // values per lane (4 or 8)
     int kind;        // RowKind
     int k_eff;       // K': bits covered by the stored value
     int fold_last;   // 1: bit K-1 is excluded from the stored value (K = 256, kI8)

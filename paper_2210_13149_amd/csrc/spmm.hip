@@ -110,20 +110,6 @@ struct Segment<int8_t, 8> {
     }
     __device__ __forceinline__ uint32_t tail() const { return raw.y; }
 };
-template <>
-struct Segment<int8_t, 16> {
-    uint4 raw;
-    __device__ __forceinline__ void load(const char *p) { raw = *reinterpret_cast<const uint4 *>(p); }
-    __device__ __forceinline__ void fma(float w, float (&acc)[16]) const
-    {
-        fma_bytes(w, raw.x, acc);
-        fma_bytes(w, raw.y, acc + 4);
-        fma_bytes(w, raw.z, acc + 8);
-        fma_bytes(w, raw.w, acc + 12);
-    }
-    __device__ __forceinline__ uint32_t tail() const { return raw.w; }
-};
-
 // Last four bytes of a loaded row as the embedded fp32 weight, broadcast from the lane that
 // holds them (the last lane of each group of G) to the whole group.
 template <typename T, int G, int V>
@@ -556,7 +542,7 @@ RowLayout choose_layout(int64_t d_in, int64_t d_out)
     RowLayout l;
     if (d_in <= 256) {
         l.kind = kI8;
-        l.vec = d_out > 256 ? 16 : 8;
+        l.vec = 8;
         l.fold_last = d_in == 256 ? 1 : 0;
         l.k_eff = static_cast<int>(d_in) - l.fold_last;
     } else {
@@ -612,11 +598,9 @@ static int launch_fused_spmm_t(const FusedSpmmArgs &a, hipStream_t stream)
     return launch_spmm_groups<TT, VV, kWeightEmbedded>(l.groups, a.plan, a.row_ptr, a.col_idx, nullptr, \
                                                        a.c_rows, rb, valid, epi, stream)
     if (l.kind == kI8 && l.embed_scale) {
-        if (l.vec == 16) BIGCN_FUSED_EMBEDDED(int8_t, 16);
         BIGCN_FUSED_EMBEDDED(int8_t, 8);
     }
     if (l.kind == kI8) {
-        if (l.vec == 16) BIGCN_FUSED(int8_t, 16);
         BIGCN_FUSED(int8_t, 8);
     }
     if (l.kind == kF16) {

@@ -55,6 +55,27 @@ def test_full_size_forward_matches_oracle(B, name):
         assert s["sign_flips"] <= 5e-6 * work.n * d + 5
 
 
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["s4", "s5"])
+def test_full_size_sage_forward_matches_oracle(B, name):
+    """The Bi-GraphSAGE workloads (Sec. 4.4.2; hidden widths of the paper's set-up) at full size,
+    with the same protocol."""
+    from test_gpu_sage import sage_prefix_runner
+    t0 = time.time()
+    say = _say(t0)
+    say(f"{name}: generating")
+    work = make_workload(name)
+    say(f"{name}: {work.n} nodes, {work.nnz} stored entries")
+    run = sage_prefix_runner(B, work)
+    stats = compare_forward_layerwise(work, ["calibrate"] * work.config.n_layers, run, log=say)
+    say(f"{name}: {stats}")
+    print(name, stats)
+    assert stats[0]["rows_compared"] == work.n
+    assert all(s["rows_compared"] >= 0.5 * work.n for s in stats)
+    for s, d in zip(stats[:-1], work.config.dims[1:-1]):
+        assert s["sign_flips"] <= 5e-6 * work.n * d + 5
+
+
 @pytest.mark.timeout(600)
 def test_full_size_aggregation_invariant_and_repeatability(B):
     """A~ sqrt(d) = sqrt(d) on the largest graph through the public SpMM, twice, bit-identical."""

@@ -105,7 +105,7 @@ def test_sage_forward_matches_oracle(B, name, n_scaled):
 
 
 # d_in / d_out pairs chosen to reach: one-byte rows with and without the embedded scale, the
-# folded last bit (d_in = 256), fp16 rows, fp32 rows, 16 values per lane (d_out > 256), and
+# folded last bit (d_in = 256), fp16 rows, fp32 rows, rows as wide as a wavefront (d_out = 512), and
 # graphs with empty rows and rows long enough for the workgroup-per-row path.
 @pytest.mark.parametrize("dims,n,n_edges,i0", [
     ((64, 40, 7), 3000, 2500, 2.0),

@@ -36,11 +36,10 @@ def log(*a):
 
 
 def standardisation(t, eps=1e-5):
-    """Frozen per-column (shift, mul) from a device matrix (plumbing: the parameters are inputs
-    of the forward pass, like running statistics)."""
-    import torch
-    var, mean = torch.var_mean(t.double(), dim=0, unbiased=False)
-    return mean.float().contiguous(), (1.0 / torch.sqrt(var + eps)).float().contiguous()
+    """Frozen per-column (shift, mul) of a device matrix, from the library's own statistics kernel
+    (the parameters are inputs of the forward pass, like running statistics)."""
+    from paper_2210_13149_amd import binding as B
+    return B.bigcn_column_stats(t, eps)
 
 
 def build_model(work, B):
@@ -154,6 +153,30 @@ def gemm_sweep(B, m=262144, n=256, k=4096, reps=10):
         out.append({"path": name, "m": m, "n": n, "k_bits": k, "ms": ms, "binary_op_per_s": rate,
                     "frac_valu_peak": rate / VALU_BINARY_MAC_PEAK,
                     "frac_mfma_int8_peak": rate / MFMA_INT8_MAC_PEAK, "identical_to_first": identical})
+    return out
+
+
+def steps_around(B, m, reps=5):
+    """The steps on either side of the path, timed on their own (not part of a step): column
+    statistics of X and the prediction from the logits; GB/s of the bytes each must read / write."""
+    import torch
+    x, logits = m["x"], m["logits"]
+    out = {}
+    for name, call, nbytes in (
+            ("column_stats", lambda: B.bigcn_column_stats(x), x.numel() * 4),
+            ("predict_labels", lambda: B.bigcn_predict(logits), logits.numel() * 4 + logits.shape[0] * 4),
+            ("predict_softmax", lambda: B.bigcn_predict(logits, want_probs=True),
+             logits.numel() * 8 + logits.shape[0] * 4)):
+        call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        out[name] = {"ms": ms, "GBps": nbytes / (ms * 1e-3) / 1e9}
     return out
 
 
@@ -286,6 +309,7 @@ def main():
                                            cost_model.summary)(cfg.n_nodes, cfg.n_edges, cfg.dims).items()
                          if k.endswith("ratio")},
     }
+    result["steps_around"] = steps_around(B, m)
     if not args.no_gemm_sweep:
         result["bit_gemm_sweep"] = gemm_sweep(B)
         best = max(result["bit_gemm_sweep"], key=lambda r: r["binary_op_per_s"])

@@ -213,6 +213,56 @@ int bigcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t 
                   void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same forward from an input that is already binarised (Sec. 5.2: the loaded features can
+ * be kept as N*d bits plus N scales, which is what makes the data-size reduction of that
+ * section usable at run time): (x_bits, x_beta) are the outputs of bigcn_pack on X, with the
+ * first layer's standardisation, if any, applied in that call.
+ *
+ *   x_bits : n rows of packed signs, row stride ld_x_words >= ceil(layers[0].d_in/64)  (DEVICE)
+ *   x_beta : n row scales                                                            (DEVICE)
+ * layers[0].bn_shift and bn_mul must be NULL (EINVAL otherwise).  The result is bit-identical
+ * to bigcn_forward on the fp32 X those bits came from.  Other arguments and errors as
+ * bigcn_forward; the same workspace size applies.
+ */
+int bigcn_forward_packed(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                         const float *dinv_sqrt, int64_t n, const uint64_t *x_bits,
+                         int64_t ld_x_words, const float *x_beta, const bigcn_layer *layers,
+                         int n_layers, float *logits, int64_t ld_logits, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
+/*
+ * Frozen standardisation parameters from data (Sec. 4.4, first step of the binarisation
+ * recipe: the input of a binarised layer is brought to zero mean and unit variance; Sec. 7.2):
+ * per column c of an fp32 matrix (rows x cols, row stride ld),
+ *
+ *   shift[c] = mean_r x[r, c],    mul[c] = 1 / sqrt(var_r x[r, c] + eps)   (biased variance)
+ *
+ * accumulated in fp64 in a fixed order (run-to-run identical) and rounded to fp32: the two
+ * vectors are what bigcn_pack and the layer descriptors take as bn_shift / bn_mul.
+ *   x DEVICE; shift, mul DEVICE out (cols floats each); workspace DEVICE scratch of at least
+ *   bigcn_column_stats_workspace_bytes(rows, cols) bytes, 8-byte aligned.
+ * Errors: ENULL, EINVAL (rows <= 0, cols <= 0, ld < cols, eps negative or NaN), ESHAPE
+ * (cols > 2^24), EWORKSPACE.  The size query returns 0 for invalid arguments.
+ */
+size_t bigcn_column_stats_workspace_bytes(int64_t rows, int64_t cols);
+int bigcn_column_stats(const float *x, int64_t rows, int64_t cols, int64_t ld, double eps,
+                       float *shift, float *mul, void *workspace, size_t workspace_bytes,
+                       void *stream);
+
+/*
+ * Prediction from the last layer's output (Sec. 3.2: Y~ = softmax(H^(L)); the predicted class
+ * of a node is the largest entry of its row):
+ *
+ *   labels[i] = argmax_c logits[i*ld + c]   (lowest c among equal maxima)   (DEVICE, int32, nullable)
+ *   probs[i*ld_probs + c] = softmax_c(logits[i, :])                          (DEVICE, fp32, nullable)
+ *
+ * At least one output must be given.  Rows containing NaN give unspecified results.
+ * Errors: ENULL, EINVAL (n < 0, d <= 0, ld < d, ld_probs < d with probs), ESHAPE (d > 2^20).
+ */
+int bigcn_predict(const float *logits, int64_t n, int64_t d, int64_t ld, int32_t *labels,
+                  float *probs, int64_t ld_probs, void *stream);
+
+/*
  * Bi-GraphSAGE with the mean aggregator (Sec. 4.4.2, the binarised layer):
  *
  *   h_i^(l+1) = W~_theta (*) h~_i  +  (1/|N_i|) sum_{j in N_i} W~_n (*) h~_j

@@ -250,6 +250,21 @@ def forward(row_ptr, col_idx, x: np.ndarray, weights: Sequence[np.ndarray],
     return h, records
 
 
+def predict(h: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Prediction from the last layer's output (Sec. 3.2: Y~ = softmax(H^(L)), the class of a
+    node being the largest entry of its row): returns ``(labels int32 (n,), probs fp64 (n, C))``.
+    The label is decided on the values as given (fp32 logits stay fp32 for the comparison); among
+    equal maxima the lowest class index wins.  The softmax is evaluated as
+    exp(h - max_row) / sum, which equals the definition for every finite input."""
+    h = np.asarray(h)
+    if h.ndim != 2 or h.shape[1] == 0:
+        raise ValueError("expected a matrix with at least one column")
+    labels = np.argmax(h, axis=1).astype(np.int32)
+    h64 = h.astype(np.float64)
+    e = np.exp(h64 - h64.max(axis=1, keepdims=True))
+    return labels, e / e.sum(axis=1, keepdims=True)
+
+
 # ---- Bi-GraphSAGE, mean aggregator (Sec. 4.4.2) ------------------------------------------------
 
 def mean_norm(row_ptr: np.ndarray, col_idx: np.ndarray) -> np.ndarray:

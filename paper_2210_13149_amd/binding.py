@@ -36,7 +36,8 @@ EXPORTS = (
     "bigcn_forward_workspace_bytes", "bigcn_forward_row_bytes", "bigcn_forward", "bigcn_profile_create",
     "bigcn_profile_destroy", "bigcn_forward_profiled", "bigcn_profile_read",
     "bigcn_mean_norm", "bigcn_sage_forward_workspace_bytes", "bigcn_sage_forward",
-    "bigcn_sage_forward_profiled",
+    "bigcn_sage_forward_profiled", "bigcn_forward_packed", "bigcn_column_stats_workspace_bytes",
+    "bigcn_column_stats", "bigcn_predict",
 )
 
 
@@ -116,6 +117,15 @@ def lib() -> ctypes.CDLL:
         L.bigcn_forward_profiled.argtypes = L.bigcn_forward.argtypes + [vp]
         L.bigcn_profile_read.restype = i32
         L.bigcn_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+        L.bigcn_forward_packed.restype = i32
+        L.bigcn_forward_packed.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, ctypes.POINTER(LayerDesc), i32,
+                                           vp, i64, vp, ctypes.c_size_t, vp]
+        L.bigcn_column_stats_workspace_bytes.restype = ctypes.c_size_t
+        L.bigcn_column_stats_workspace_bytes.argtypes = [i64, i64]
+        L.bigcn_column_stats.restype = i32
+        L.bigcn_column_stats.argtypes = [vp, i64, i64, i64, ctypes.c_double, vp, vp, vp, ctypes.c_size_t, vp]
+        L.bigcn_predict.restype = i32
+        L.bigcn_predict.argtypes = [vp, i64, i64, i64, vp, vp, i64, vp]
         L.bigcn_mean_norm.restype = i32
         L.bigcn_mean_norm.argtypes = [vp, i64, vp, vp]
         L.bigcn_sage_forward_workspace_bytes.restype = ctypes.c_size_t
@@ -385,6 +395,60 @@ def bigcn_forward(plan: Plan, row_ptr: torch.Tensor, col_idx: torch.Tensor, dinv
     else:
         _check(lib().bigcn_forward_profiled(*args, profile.handle), "bigcn_forward_profiled")
     return logits
+
+
+def bigcn_forward_packed(plan: Plan, row_ptr: torch.Tensor, col_idx: torch.Tensor,
+                         dinv_sqrt: torch.Tensor, x_bits: torch.Tensor, x_beta: torch.Tensor,
+                         layers: Sequence[Layer], workspace: Optional[torch.Tensor] = None,
+                         logits: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The fused forward from packed input signs and row scales (outputs of ``bigcn_pack``)."""
+    _dev(x_bits, torch.int64, "x_bits")
+    _dev(x_beta, torch.float32, "x_beta")
+    if x_bits.dim() != 2 or (x_bits.shape[1] > 1 and x_bits.stride(1) != 1):
+        raise ValueError("x_bits must be a row-major matrix of words")
+    n = x_bits.shape[0]
+    if x_beta.numel() != n:
+        raise ValueError("x_beta must hold one scale per row of x_bits")
+    descs = _descs(layers)
+    if workspace is None:
+        need = bigcn_forward_workspace_bytes(n, layers)
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=x_bits.device)
+    if logits is None:
+        logits = torch.empty((n, layers[-1].d_out), dtype=torch.float32, device=x_bits.device)
+    _check(lib().bigcn_forward_packed(plan.handle, _ptr(row_ptr), _ptr(col_idx), _ptr(dinv_sqrt), n,
+                                      _ptr(x_bits), x_bits.stride(0), _ptr(x_beta), descs, len(layers),
+                                      _ptr(logits), logits.stride(0), _ptr(workspace), workspace.numel(),
+                                      _stream()), "bigcn_forward_packed")
+    return logits
+
+
+def bigcn_column_stats(x: torch.Tensor, eps: float = 1e-5) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Per-column ``(mean, 1/sqrt(var + eps))`` of an fp32 device matrix, as fp32 vectors."""
+    _dev(x, torch.float32, "x")
+    if x.dim() != 2 or (x.shape[1] > 1 and x.stride(1) != 1):
+        raise ValueError("x must be a row-major matrix")
+    rows, cols = x.shape
+    need = int(lib().bigcn_column_stats_workspace_bytes(rows, cols))
+    workspace = torch.empty((max(need, 8) // 8,), dtype=torch.float64, device=x.device)
+    shift = torch.empty((cols,), dtype=torch.float32, device=x.device)
+    mul = torch.empty((cols,), dtype=torch.float32, device=x.device)
+    _check(lib().bigcn_column_stats(_ptr(x), rows, cols, x.stride(0), float(eps), _ptr(shift), _ptr(mul),
+                                    _ptr(workspace), workspace.numel() * 8, _stream()), "bigcn_column_stats")
+    return shift, mul
+
+
+def bigcn_predict(logits: torch.Tensor, want_probs: bool = False
+                  ) -> Tuple[torch.Tensor, Optional[torch.Tensor]]:
+    """``(labels int32 (n,), softmax probabilities (n, d) or None)`` of a row-major fp32 matrix."""
+    _dev(logits, torch.float32, "logits")
+    if logits.dim() != 2 or (logits.shape[1] > 1 and logits.stride(1) != 1):
+        raise ValueError("logits must be a row-major matrix")
+    n, d = logits.shape
+    labels = torch.empty((n,), dtype=torch.int32, device=logits.device)
+    probs = torch.empty((n, d), dtype=torch.float32, device=logits.device) if want_probs else None
+    _check(lib().bigcn_predict(_ptr(logits), n, d, logits.stride(0), _ptr(labels), _ptr(probs), d, _stream()),
+           "bigcn_predict")
+    return labels, probs
 
 
 class BiGCN:

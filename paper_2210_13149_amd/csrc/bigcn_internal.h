@@ -83,6 +83,11 @@ int launch_pack(const float *x, int64_t rows, int64_t cols, int64_t row_stride,
                 int fold_last_sign, uint64_t *bits, int64_t ld_words, float *scale,
                 hipStream_t stream);
 
+// Stored source scale of rows that are already packed: beta[i] * row_mul[i] (row_mul nullable),
+// negated when fold_last_sign is set and the row's last bit (column cols-1) is 0.
+int launch_source_scale(const float *beta, const float *row_mul, const uint64_t *bits, int64_t ld_words,
+                        int64_t cols, int fold_last_sign, float *scale, int64_t rows, hipStream_t stream);
+
 // bit-GEMM writing the integer products in a RowLayout (fused forward).
 // src_scale (m floats) is copied into the rows when the layout embeds the scale.
 int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits,

@@ -143,18 +143,32 @@ extern "C" size_t bigcn_sage_forward_workspace_bytes(int64_t n, const bigcn_sage
 
 // dst_mul: factor of node i's neighbour sum; src_row_mul: factor folded into every stored source
 // scale (nullptr = 1).  Bi-GCN passes D^-1/2 for both; Bi-GraphSAGE passes 1/|N_i| and nullptr.
+// The input is either fp32 features (x, ld_x) or their packed signs and row scales
+// (in.bits, in.ld_words, in.beta) with x == nullptr.
+struct PackedInput {
+    const uint64_t *bits;
+    int64_t ld_words;
+    const float *beta;
+};
+
 static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
                         const float *dst_mul, const float *src_row_mul, bool own_term, int64_t n,
-                        const float *x, int64_t ld_x, const LayerView *layers, int n_layers,
+                        const float *x, int64_t ld_x, PackedInput in, const LayerView *layers, int n_layers,
                         float *logits, int64_t ld_logits, void *workspace, size_t workspace_bytes,
                         void *stream, bigcn_profile *prof)
 {
-    if (plan == nullptr || row_ptr == nullptr || col_idx == nullptr || dst_mul == nullptr ||
-        x == nullptr || logits == nullptr)
+    const bool packed = x == nullptr;
+    if (plan == nullptr || row_ptr == nullptr || col_idx == nullptr || dst_mul == nullptr || logits == nullptr)
         return BIGCN_ENULL;
+    if (packed && (in.bits == nullptr || in.beta == nullptr)) return BIGCN_ENULL;
     int status;
     if (!layers_ok(n, layers, n_layers, own_term, &status)) return status;
-    if (n != plan->n || ld_x < layers[0].d_in || ld_logits < layers[n_layers - 1].d_out) return BIGCN_EINVAL;
+    if (n != plan->n || ld_logits < layers[n_layers - 1].d_out) return BIGCN_EINVAL;
+    if (!packed && ld_x < layers[0].d_in) return BIGCN_EINVAL;
+    // a packed input was standardised (if at all) when it was packed
+    if (packed && (in.ld_words < (layers[0].d_in + 63) / 64 || layers[0].bn_shift != nullptr ||
+                   layers[0].bn_mul != nullptr))
+        return BIGCN_EINVAL;
     const WorkspaceMap map = map_workspace(n, layers, n_layers, own_term);
     if (n == 0) return BIGCN_OK;
     if (workspace == nullptr || workspace_bytes < map.total || reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
@@ -175,22 +189,31 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
     void *c_rows = ws + map.rows_off;
     void *self_rows = own_term ? ws + map.self_rows_off : nullptr;
 
-    // layer 0 input: binarise X; the stored scale is src_row_mul[i] * beta_i
+    // layer 0 input: binarise X (or take it binarised); the stored scale is src_row_mul[i] * beta_i
     int64_t words = (layers[0].d_in + 63) / 64;
+    const uint64_t *in_bits = bits;
+    const int fold0 = choose_layout(layers[0].d_in, layers[0].d_out).fold_last;
     BIGCN_MARK();
-    int rc = launch_pack(x, n, layers[0].d_in, ld_x, 1, layers[0].bn_shift, layers[0].bn_mul, src_row_mul,
-                         choose_layout(layers[0].d_in, layers[0].d_out).fold_last, bits, words, scale[0], s);
+    int rc;
+    if (packed) {
+        in_bits = in.bits;
+        words = in.ld_words;
+        rc = launch_source_scale(in.beta, src_row_mul, in.bits, in.ld_words, layers[0].d_in, fold0, scale[0], n, s);
+    } else {
+        rc = launch_pack(x, n, layers[0].d_in, ld_x, 1, layers[0].bn_shift, layers[0].bn_mul, src_row_mul, fold0,
+                         bits, words, scale[0], s);
+    }
     if (rc != BIGCN_OK) return rc;
     BIGCN_MARK();
 
     for (int l = 0; l < n_layers; ++l) {
         const LayerView &L = layers[l];
         const RowLayout layout = choose_layout(L.d_in, L.d_out);
-        rc = launch_bitgemm_layout(bits, n, words, L.w_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1], c_rows,
+        rc = launch_bitgemm_layout(in_bits, n, words, L.w_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1], c_rows,
                                    layout, s);
         if (rc != BIGCN_OK) return rc;
         if (own_term) {
-            rc = launch_bitgemm_layout(bits, n, words, L.w_self_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1],
+            rc = launch_bitgemm_layout(in_bits, n, words, L.w_self_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1],
                                        self_rows, layout, s);
             if (rc != BIGCN_OK) return rc;
         }
@@ -219,6 +242,7 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
             a.ld_logits = ld_logits;
         } else {
             words = (L.d_out + 63) / 64;
+            in_bits = bits;
             a.next_shift = layers[l + 1].bn_shift;
             a.next_mul = layers[l + 1].bn_mul;
             a.next_bits = bits;
@@ -243,8 +267,8 @@ static int gcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int
     LayerView view[kMaxLayers];
     const int rc = view_gcn(layers, n_layers, view);
     if (rc != BIGCN_OK) return rc;
-    return forward_impl(plan, row_ptr, col_idx, dinv_sqrt, dinv_sqrt, false, n, x, ld_x, view, n_layers,
-                        logits, ld_logits, workspace, workspace_bytes, stream, prof);
+    return forward_impl(plan, row_ptr, col_idx, dinv_sqrt, dinv_sqrt, false, n, x, ld_x, PackedInput{}, view,
+                        n_layers, logits, ld_logits, workspace, workspace_bytes, stream, prof);
 }
 
 static int sage_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
@@ -255,8 +279,8 @@ static int sage_forward(const bigcn_plan *plan, const int64_t *row_ptr, const in
     LayerView view[kMaxLayers];
     const int rc = view_sage(layers, n_layers, view);
     if (rc != BIGCN_OK) return rc;
-    return forward_impl(plan, row_ptr, col_idx, inv_deg, nullptr, true, n, x, ld_x, view, n_layers, out,
-                        ld_out, workspace, workspace_bytes, stream, prof);
+    return forward_impl(plan, row_ptr, col_idx, inv_deg, nullptr, true, n, x, ld_x, PackedInput{}, view, n_layers,
+                        out, ld_out, workspace, workspace_bytes, stream, prof);
 }
 
 extern "C" int bigcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
@@ -266,6 +290,21 @@ extern "C" int bigcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, con
 {
     return gcn_forward(plan, row_ptr, col_idx, dinv_sqrt, n, x, ld_x, layers, n_layers, logits,
                        ld_logits, workspace, workspace_bytes, stream, nullptr);
+}
+
+extern "C" int bigcn_forward_packed(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                                    const float *dinv_sqrt, int64_t n, const uint64_t *x_bits,
+                                    int64_t ld_x_words, const float *x_beta, const bigcn_layer *layers,
+                                    int n_layers, float *logits, int64_t ld_logits, void *workspace,
+                                    size_t workspace_bytes, void *stream)
+{
+    if (x_bits == nullptr || x_beta == nullptr) return BIGCN_ENULL;
+    LayerView view[kMaxLayers];
+    const int rc = view_gcn(layers, n_layers, view);
+    if (rc != BIGCN_OK) return rc;
+    return forward_impl(plan, row_ptr, col_idx, dinv_sqrt, dinv_sqrt, false, n, nullptr, 0,
+                        PackedInput{x_bits, ld_x_words, x_beta}, view, n_layers, logits, ld_logits, workspace,
+                        workspace_bytes, stream, nullptr);
 }
 
 extern "C" int bigcn_forward_profiled(const bigcn_plan *plan, const int64_t *row_ptr,

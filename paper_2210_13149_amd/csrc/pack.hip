@@ -124,6 +124,32 @@ __global__ __launch_bounds__(kBlock) void pack_generic_kernel(
     }
 }
 
+// Source scale of an input that arrives already binarised: beta_i times the optional per-row
+// factor, negated when the layout folds the last input bit and that bit is -1.
+__global__ __launch_bounds__(kBlock) void source_scale_kernel(const float *__restrict__ beta,
+                                                              const float *__restrict__ row_mul,
+                                                              const uint64_t *__restrict__ bits,
+                                                              int64_t ld_words, int64_t cols,
+                                                              int fold_last_sign, float *__restrict__ scale,
+                                                              int64_t rows)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i >= rows) return;
+    float s = beta[i];
+    if (row_mul != nullptr) s *= row_mul[i];
+    if (fold_last_sign && ((bits[i * ld_words + ((cols - 1) >> 6)] >> ((cols - 1) & 63)) & 1ull) == 0) s = -s;
+    scale[i] = s;
+}
+
+int launch_source_scale(const float *beta, const float *row_mul, const uint64_t *bits, int64_t ld_words,
+                        int64_t cols, int fold_last_sign, float *scale, int64_t rows, hipStream_t stream)
+{
+    if (rows == 0) return BIGCN_OK;
+    hipLaunchKernelGGL(source_scale_kernel, dim3(static_cast<unsigned>((rows + kBlock - 1) / kBlock)), dim3(kBlock),
+                       0, stream, beta, row_mul, bits, ld_words, cols, fold_last_sign, scale, rows);
+    return check_launch();
+}
+
 static int grid_for_waves(int64_t waves_needed)
 {
     // enough workgroups to fill 256 CUs several times over; grid-stride loops take the rest

@@ -310,3 +310,28 @@ def test_forward_equivariances():
     x2[relabel] = x
     out2, _ = oracle.forward(rp2, ci2, x2, weights)
     assert np.allclose(out2[relabel], base, rtol=1e-9, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------------------
+# prediction (Sec. 3.2): softmax of the last layer's output, class = largest entry
+# ----------------------------------------------------------------------------------------
+def test_predict_hand_example_and_ties():
+    h = np.array([[0.0, np.log(3.0)], [2.0, 2.0], [-1.0, -5.0]], dtype=np.float32)
+    labels, probs = oracle.predict(h)
+    assert labels.tolist() == [1, 0, 0]                       # tie -> lowest class
+    assert np.allclose(probs[0], [0.25, 0.75], rtol=1e-6)     # fp32 log(3) in the input
+    assert np.allclose(probs[1], [0.5, 0.5], rtol=1e-15)
+
+
+def test_predict_matches_library_softmax_and_is_shift_invariant():
+    from scipy.special import softmax
+    h = (RNG.standard_normal((200, 47)) * 8).astype(np.float32)
+    labels, probs = oracle.predict(h)
+    assert np.allclose(probs, softmax(h.astype(np.float64), axis=1), rtol=1e-12, atol=1e-300)
+    assert np.allclose(probs.sum(axis=1), 1.0, rtol=1e-14)
+    assert np.array_equal(labels, probs.argmax(axis=1))
+    shifted_labels, shifted = oracle.predict(h.astype(np.float64) + 1000.0)
+    assert np.array_equal(shifted_labels, labels) and np.allclose(shifted, probs, rtol=1e-9)
+    # large logits do not overflow
+    _, big = oracle.predict(np.array([[1e4, 1e4 - 1.0]], dtype=np.float32))
+    assert np.allclose(big[0], [1 / (1 + np.exp(-1.0)), 1 / (1 + np.exp(1.0))], rtol=1e-12)

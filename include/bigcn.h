@@ -257,7 +257,8 @@ int bigcn_column_stats(const float *x, int64_t rows, int64_t cols, int64_t ld, d
  *   probs[i*ld_probs + c] = softmax_c(logits[i, :])                          (DEVICE, fp32, nullable)
  *
  * At least one output must be given.  Rows containing NaN give unspecified results.
- * Errors: ENULL, EINVAL (n < 0, d <= 0, ld < d, ld_probs < d with probs), ESHAPE (d > 2^20).
+ * Errors: ENULL, EINVAL (n < 0, d <= 0, ld < d, ld_probs < d with probs), ESHAPE (d > 2^20 or
+ * n > 2^38).
  */
 int bigcn_predict(const float *logits, int64_t n, int64_t d, int64_t ld, int32_t *labels,
                   float *probs, int64_t ld_probs, void *stream);

@@ -150,8 +150,8 @@ __global__ __launch_bounds__(kBlock) void column_finish_kernel(const float *__re
     mul[c] = static_cast<float>(1.0 / sqrt(var + eps));
 }
 
-// Prediction: G lanes share one row (lane g takes classes g, g + G, ...), 64/G rows per
-// wavefront and load instruction.  Among equal maxima the lowest class index wins.
+// Prediction, 64 classes or more: G lanes share one row (lane g takes classes g, g + G, ...).
+// Among equal maxima the lowest class index wins.
 // kOneLoad: d <= G, every lane holds at most one class; R such loads are issued back to back.
 template <int G, int R, bool kOneLoad>
 __global__ __launch_bounds__(kBlock) void predict_kernel(const float *__restrict__ logits, int64_t n, int d,
@@ -215,6 +215,63 @@ __global__ __launch_bounds__(kBlock) void predict_kernel(const float *__restrict
     }
 }
 
+// Fewer than 64 classes: a workgroup stages 256 rows in LDS (one row per load instruction of a
+// wavefront, eight in flight), then every thread scans its own row.  The LDS row stride is odd,
+// so the 64 lanes of a wavefront hit distinct banks.  Per row this costs a few instructions per
+// class on ONE lane, where the lanes-per-row form spends a butterfly of shuffles per row.
+constexpr int kPredictRows = kBlock;
+
+__global__ __launch_bounds__(kBlock) void predict_small_kernel(const float *__restrict__ logits, int64_t n, int d,
+                                                               int64_t ld, int32_t *__restrict__ labels,
+                                                               float *__restrict__ probs, int64_t ld_probs)
+{
+    extern __shared__ float tile[];                 // kPredictRows * stride floats
+    const int stride = d | 1;
+    const int lane = lane_id();
+    const int wave = wave_in_block();
+    const int64_t row0 = static_cast<int64_t>(blockIdx.x) * kPredictRows;
+    const int64_t left = n - row0;
+    const int rows_here = left < kPredictRows ? static_cast<int>(left) : kPredictRows;
+    constexpr int U = 8;
+    const bool col_in = lane < d;
+    // stage: wavefront w takes rows 64 w .. 64 w + 63 of the tile
+    for (int r0 = wave * kWave; r0 < wave * kWave + kWave; r0 += U) {
+        float v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            v[u] = (col_in && r0 + u < rows_here) ? logits[(row0 + r0 + u) * ld + lane] : 0.0f;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (col_in) tile[(r0 + u) * stride + lane] = v[u];
+    }
+    __syncthreads();
+    // scan: thread t owns row t of the tile
+    const int t = static_cast<int>(threadIdx.x);
+    float *mine = tile + t * stride;
+    float best = mine[0];
+    int arg = 0;
+    for (int c = 1; c < d; ++c) {
+        const float v = mine[c];
+        if (v > best) { best = v; arg = c; }
+    }
+    if (t < rows_here && labels != nullptr) labels[row0 + t] = arg;
+    if (probs == nullptr) return;                   // uniform over the grid
+    float sum = 0.0f;
+    for (int c = 0; c < d; ++c) {
+        const float e = expf(mine[c] - best);
+        mine[c] = e;
+        sum += e;
+    }
+    const float inv = 1.0f / sum;
+    for (int c = 0; c < d; ++c) mine[c] *= inv;
+    __syncthreads();
+    for (int r0 = wave * kWave; r0 < wave * kWave + kWave; r0 += U) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (col_in && r0 + u < rows_here) probs[(row0 + r0 + u) * ld_probs + lane] = tile[(r0 + u) * stride + lane];
+    }
+}
+
 }  // namespace bigcn
 
 using namespace bigcn;
@@ -265,36 +322,27 @@ extern "C" int bigcn_predict(const float *logits, int64_t n, int64_t d, int64_t 
 {
     if (logits == nullptr || (labels == nullptr && probs == nullptr)) return BIGCN_ENULL;
     if (n < 0 || d <= 0 || ld < d || (probs != nullptr && ld_probs < d)) return BIGCN_EINVAL;
-    if (d > (1 << 20)) return BIGCN_ESHAPE;
+    if (d > (1 << 20) || n > (static_cast<int64_t>(1) << 38)) return BIGCN_ESHAPE;
     if (n == 0) return BIGCN_OK;
-    int groups = 2;
-    while (groups < kWave && groups < d) groups <<= 1;
+    if (d < kWave) {
+        const size_t lds = static_cast<size_t>(kPredictRows) * (d | 1) * sizeof(float);    // < 64 KB
+        hipLaunchKernelGGL(predict_small_kernel, dim3(static_cast<unsigned>((n + kPredictRows - 1) / kPredictRows)),
+                           dim3(kBlock), lds, as_stream(stream), logits, n, static_cast<int>(d), ld, labels, probs,
+                           ld_probs);
+        return check_launch();
+    }
+    // 64 classes or more: all 64 lanes share a row
     constexpr int kRowsInFlight = 8;
-    const bool one_load = d <= groups;
-    const int64_t rows_per_wave = static_cast<int64_t>(kWave / groups) * (one_load ? kRowsInFlight : 1);
-    const int64_t rows_per_block = kWavesPerBlock * rows_per_wave;
+    const bool one_load = d == kWave;
+    const int64_t rows_per_block = static_cast<int64_t>(kWavesPerBlock) * (one_load ? kRowsInFlight : 1);
     int64_t blocks = (n + rows_per_block - 1) / rows_per_block;
     if (blocks > 256 * 64) blocks = 256 * 64;
     hipStream_t s = as_stream(stream);
-#define BIGCN_PREDICT_CASE(GG)                                                                               \
-    case GG:                                                                                                 \
-        if (one_load)                                                                                        \
-            hipLaunchKernelGGL((predict_kernel<GG, kRowsInFlight, true>), dim3(static_cast<unsigned>(blocks)), \
-                               dim3(kBlock), 0, s, logits, n, static_cast<int>(d), ld, labels, probs, ld_probs); \
-        else                                                                                                 \
-            hipLaunchKernelGGL((predict_kernel<GG, 1, false>), dim3(static_cast<unsigned>(blocks)),          \
-                               dim3(kBlock), 0, s, logits, n, static_cast<int>(d), ld, labels, probs, ld_probs); \
-        break
-    switch (groups) {
-        BIGCN_PREDICT_CASE(2);
-        BIGCN_PREDICT_CASE(4);
-        BIGCN_PREDICT_CASE(8);
-        BIGCN_PREDICT_CASE(16);
-        BIGCN_PREDICT_CASE(32);
-        BIGCN_PREDICT_CASE(64);
-    default:
-        return BIGCN_EINVAL;
-    }
-#undef BIGCN_PREDICT_CASE
+    if (one_load)
+        hipLaunchKernelGGL((predict_kernel<kWave, kRowsInFlight, true>), dim3(static_cast<unsigned>(blocks)),
+                           dim3(kBlock), 0, s, logits, n, static_cast<int>(d), ld, labels, probs, ld_probs);
+    else
+        hipLaunchKernelGGL((predict_kernel<kWave, 1, false>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0,
+                           s, logits, n, static_cast<int>(d), ld, labels, probs, ld_probs);
     return check_launch();
 }

@@ -48,22 +48,30 @@ __device__ __forceinline__ float wave_sum(float v)
 //
 // Storage kinds (all exact):
 //   kI8  (K <= 256): q = floor(K'/2) - popcount over the first K' bits, so that the product
-//         over those bits is 2q + (K' mod 2).  K' = K, except K = 256 where K' = 255 and the
-//         last bit's contribution  f_{k,255} * b_{255,j}  is carried separately: the sign
+//         over those bits is 2q + (K' mod 2).  K' = K, except K = 256 (and K = 128 with the scale
+//         in the top bits) where K' = K - 1 and the last bit's contribution  f_{k,255} * b_{255,j}  is carried separately: the sign
 //         f_{k,255} rides on the sign of the node's stored scale, b_{255,j} is a per-column
 //         constant.  q always fits int8: [-128, 127].
 //   kF16 (K <= 2048): the product itself; every integer of magnitude <= 2048 is exact in fp16.
 //   kF32 : the product as fp32.
 enum RowKind { kI8 = 0, kF16 = 1, kF32 = 2 };
 
+// Where the aggregation finds a node's fp32 source scale (kI8 rows may carry it themselves, so
+// that no second cache line is gathered per neighbour):
+//   kScaleSeparate   an array of n floats, gathered through the column index;
+//   kScaleInTail     the last 4 bytes of the stored row (rows with at least 4 spare positions);
+//   kScaleInTopBits  K' <= 127, so a stored value needs 7 bits: bit i of the scale is the top bit
+//                    of the first byte of lane i's segment, i < 32 (rows of 32 or 64 lanes).
+enum ScalePlace { kScaleSeparate = 0, kScaleInTail = 1, kScaleInTopBits = 2 };
+
 struct RowLayout {
     int groups;      // lanes that share one stored row (power of two, 2..64)
     int vec;         // values per lane (4 or 8)
     int kind;        // RowKind
     int k_eff;       // K': bits covered by the stored value
-    int fold_last;   // 1: bit K-1 is excluded from the stored value (K = 256, kI8)
-    int embed_scale; // 1: the last 4 bytes of a stored row hold the node's fp32 source scale
-                     //    (kI8 rows with at least 4 spare positions): no separate scale gather
+    int fold_last;   // 1: bit K-1 is excluded from the stored value (kI8 with K = 256, or K = 128
+                     //    when the scale sits in the top bits)
+    int embed_scale; // ScalePlace
     __host__ __device__ int positions() const { return groups * vec; }
     __host__ __device__ int elem_bytes() const { return kind == kI8 ? 1 : (kind == kF16 ? 2 : 4); }
     __host__ __device__ int64_t row_bytes() const { return static_cast<int64_t>(positions()) * elem_bytes(); }

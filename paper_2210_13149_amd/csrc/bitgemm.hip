@@ -46,17 +46,18 @@ struct EpilogueApi {
         float b_scale[VB];   // per-lane constants: the scales of this lane's columns
     };
     template <int VB>
-    __device__ __forceinline__ void init(const int (&col)[VB], int n, Lane<VB> &c) const
+    __device__ __forceinline__ void init(const int (&col)[VB], int /*pos0*/, int n, Lane<VB> &c) const
     {
 #pragma unroll
         for (int v = 0; v < VB; ++v)
             c.b_scale[v] = (out != nullptr && col[v] >= 0 && col[v] < n) ? b_scale[col[v]] : 0.0f;
     }
+    // per-row value needed by store(): fetched when the row block starts, not when it ends
+    __device__ __forceinline__ float row_value(int64_t row) const { return out != nullptr ? a_scale[row] : 0.0f; }
     template <int VB>
-    __device__ __forceinline__ void store(const Lane<VB> &ctx, int64_t row, const int (&col)[VB], int /*pos0*/,
-                                          bool /*any*/, int n, const int (&pop)[VB]) const
+    __device__ __forceinline__ void store(const Lane<VB> &ctx, int64_t row, float sa, const int (&col)[VB],
+                                          int /*pos0*/, bool /*any*/, int n, const int (&pop)[VB]) const
     {
-        const float sa = out != nullptr ? a_scale[row] : 0.0f;
 #pragma unroll
         for (int v = 0; v < VB; ++v) {
             const int j = col[v];
@@ -76,14 +77,24 @@ struct EpilogueLayout {
     T *rows;
     int positions;
     int k_eff;
-    const float *embed;      // non-null (int8 rows only): scale[row] goes into the last 4 bytes
+    const float *embed;      // non-null (int8 rows only): scale[row] is stored inside the row,
+    int top_bits_shift;      //   0: in its last 4 bytes; s > 0: bit i in the top bit of position i << s, i < 32
     template <int VB>
-    struct Lane {};
+    struct Lane {
+        int top_bit;         // which bit of the scale this lane's first value carries, or -1
+    };
     template <int VB>
-    __device__ __forceinline__ void init(const int (&)[VB], int, Lane<VB> &) const {}
+    __device__ __forceinline__ void init(const int (&)[VB], int pos0, int, Lane<VB> &c) const
+    {
+        // a lane's values are consecutive positions starting at a multiple of VB, so only its
+        // first value can sit on a position i << shift
+        const int i = pos0 >> top_bits_shift;
+        c.top_bit = (top_bits_shift > 0 && embed != nullptr && (i << top_bits_shift) == pos0 && i < 32) ? i : -1;
+    }
+    __device__ __forceinline__ float row_value(int64_t row) const { return embed != nullptr ? embed[row] : 0.0f; }
     template <int VB>
-    __device__ __forceinline__ void store(const Lane<VB> &, int64_t row, const int (&col)[VB], int pos0, bool any,
-                                          int n, const int (&pop)[VB]) const
+    __device__ __forceinline__ void store(const Lane<VB> &ctx, int64_t row, float row_scale, const int (&col)[VB],
+                                          int pos0, bool any, int n, const int (&pop)[VB]) const
     {
         if (!any) return;
         alignas(16) T tmp[VB];
@@ -97,13 +108,16 @@ struct EpilogueLayout {
             else tmp[v] = static_cast<T>(live ? static_cast<float>(value) : 0.0f);
         }
         if constexpr (sizeof(T) == 1) {
-            if (embed != nullptr) {
-                const uint32_t bits = __float_as_uint(embed[row]);
+            if (embed != nullptr && top_bits_shift == 0) {
+                const uint32_t bits = __float_as_uint(row_scale);
 #pragma unroll
                 for (int v = 0; v < VB; ++v) {
                     const int byte = pos0 + v - (positions - 4);
                     if (byte >= 0) tmp[v] = static_cast<T>((bits >> (8 * byte)) & 0xffu);
                 }
+            } else if (ctx.top_bit >= 0) {
+                const uint32_t bit = (__float_as_uint(row_scale) >> ctx.top_bit) & 1u;
+                tmp[0] = static_cast<T>((static_cast<uint32_t>(tmp[0]) & 0x7fu) | (bit << 7));
             }
         }
         T *p = rows + row * positions + pos0;
@@ -160,7 +174,7 @@ __global__ __launch_bounds__(kBlock) void bitgemm_kernel(
     }
     const int pos0 = (lane % map.groups) * map.vec + map.per_group * (lane / map.groups) + y * VB;
     typename Epilogue::template Lane<VB> ctx;
-    epi.template init<VB>(col, n, ctx);
+    epi.template init<VB>(col, pos0, n, ctx);
 
     const int64_t wave = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block();
     const int64_t n_waves = static_cast<int64_t>(gridDim.x) * kWavesPerBlock;
@@ -173,10 +187,12 @@ __global__ __launch_bounds__(kBlock) void bitgemm_kernel(
             for (int v = 0; v < VB; ++v) pop[r][v] = 0;
 
         const uint32_t *arow[R];
+        float row_value[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int64_t row = row0 + r < m ? row0 + r : m - 1;   // clamp: tail rows recompute the last row
             arow[r] = reinterpret_cast<const uint32_t *>(a + row * lda);
+            row_value[r] = epi.row_value(row);
         }
         // WC words of every row of A are fetched together (wave-uniform: scalar loads), then
         // combined with the lane's columns of B; 32-bit halves so that each half costs exactly
@@ -226,7 +242,7 @@ __global__ __launch_bounds__(kBlock) void bitgemm_kernel(
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             if (row0 + r >= m) break;                               // wave-uniform
-            epi.template store<VB>(ctx, row0 + r, col, pos0, any, n, pop[r]);
+            epi.template store<VB>(ctx, row0 + r, row_value[r], col, pos0, any, n, pop[r]);
         }
     }
 }
@@ -284,16 +300,17 @@ int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const 
     const uint32_t last_mask = layout.fold_last ? 0x7fffffffu : 0xffffffffu;
     if (layout.kind == kI8) {
         EpilogueLayout<int8_t> epi{static_cast<int8_t *>(c_rows), layout.positions(), layout.k_eff,
-                                   layout.embed_scale ? src_scale : nullptr};
+                                   layout.embed_scale != kScaleSeparate ? src_scale : nullptr,
+                                   layout.embed_scale == kScaleInTopBits ? (layout.vec == 8 ? 3 : 2) : 0};
         return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
                                 last_mask, epi, stream);
     }
     if (layout.kind == kF16) {
-        EpilogueLayout<__half> epi{static_cast<__half *>(c_rows), layout.positions(), layout.k_eff, nullptr};
+        EpilogueLayout<__half> epi{static_cast<__half *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0};
         return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
                                 last_mask, epi, stream);
     }
-    EpilogueLayout<float> epi{static_cast<float *>(c_rows), layout.positions(), layout.k_eff, nullptr};
+    EpilogueLayout<float> epi{static_cast<float *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0};
     return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
                             last_mask, epi, stream);
 }

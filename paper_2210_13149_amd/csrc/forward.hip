@@ -121,7 +121,7 @@ extern "C" int64_t bigcn_forward_row_bytes(int64_t d_in, int64_t d_out, int *sca
 {
     if (d_in <= 0 || d_out <= 0 || d_in > BIGCN_MAX_K_BITS || d_out > BIGCN_MAX_FORWARD_D_OUT) return 0;
     const RowLayout l = choose_layout(d_in, d_out);
-    if (scale_embedded != nullptr) *scale_embedded = l.embed_scale;
+    if (scale_embedded != nullptr) *scale_embedded = l.embed_scale != kScaleSeparate ? 1 : 0;
     return l.row_bytes();
 }
 

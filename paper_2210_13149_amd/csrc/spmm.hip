@@ -13,14 +13,18 @@
 //     first and each is shared by the four wavefronts of a workgroup (partial sums combined
 //     through LDS in a fixed order); every other row is owned by one wavefront.
 // All sums are evaluated in a fixed order, so results are bit-identical from run to run.
+#include <type_traits>
+
 #include "bigcn_internal.h"
 
 namespace bigcn {
 
 // Where the per-neighbour weight comes from: all ones, a per-entry array, a per-node array
-// gathered through the column index, or the last four bytes of the gathered row itself.
-enum WeightMode { kWeightOne = 0, kWeightVals = 1, kWeightGather = 2, kWeightEmbedded = 3 };
-__host__ __device__ constexpr bool fused_weights(int wm) { return wm == kWeightGather || wm == kWeightEmbedded; }
+// gathered through the column index, the last four bytes of the gathered row itself, or the top
+// bits of the first byte of each lane's segment of the gathered row (7-bit products).
+enum WeightMode { kWeightOne = 0, kWeightVals = 1, kWeightGather = 2, kWeightEmbedded = 3, kWeightTopBits = 4 };
+__host__ __device__ constexpr bool fused_weights(int wm) { return wm >= kWeightGather; }
+__host__ __device__ constexpr bool row_weights(int wm) { return wm == kWeightEmbedded || wm == kWeightTopBits; }
 
 // ---- one stored row segment: V values of T per lane, loaded as one vector ------------------
 template <typename T, int V>
@@ -109,14 +113,25 @@ struct Segment<int8_t, 8> {
         fma_bytes(w, raw.y, acc + 4);
     }
     __device__ __forceinline__ uint32_t tail() const { return raw.y; }
+    __device__ __forceinline__ uint32_t head() const { return raw.x; }
+    // first byte holds a 7-bit value under a foreign top bit: copy bit 6 into bit 7
+    __device__ __forceinline__ void restore_head_sign() { raw.x = (raw.x & ~0x80u) | ((raw.x << 1) & 0x80u); }
 };
-// Last four bytes of a loaded row as the embedded fp32 weight, broadcast from the lane that
-// holds them (the last lane of each group of G) to the whole group.
-template <typename T, int G, int V>
-__device__ __forceinline__ float embedded_weight(const Segment<T, V> &seg, int lane)
+// The fp32 weight stored inside a loaded row, handed to every lane of the row's group.
+//   kWeightEmbedded: the row's last four bytes, held by the last lane of the group;
+//   kWeightTopBits:  bit i of the weight is the top bit of the first byte of lane i's segment
+//                    (groups of 32 or 64 lanes); one ballot collects the bits of both rows that a
+//                    load instruction covers, and the segment's first byte gets its sign back.
+template <typename T, int G, int V, int WM>
+__device__ __forceinline__ float row_weight(Segment<T, V> &seg, int lane, bool loaded)
 {
-    if constexpr (sizeof(T) == 1) {
+    if constexpr (sizeof(T) == 1 && WM == kWeightEmbedded) {
         return __uint_as_float(static_cast<uint32_t>(__shfl(static_cast<int>(seg.tail()), lane | (G - 1), kWave)));
+    } else if constexpr (sizeof(T) == 1 && WM == kWeightTopBits) {
+        const uint64_t bits = __ballot(loaded && (seg.head() & 0x80u) != 0);
+        seg.restore_head_sign();
+        const uint32_t mine = (G == kWave || lane < 32) ? static_cast<uint32_t>(bits) : static_cast<uint32_t>(bits >> 32);
+        return __uint_as_float(mine);
     } else {
         return 0.0f;
     }
@@ -181,7 +196,7 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (WM == kWeightEmbedded) w[u] = embedded_weight<T, G, V>(seg[u], lane);
+                if (row_weights(WM)) w[u] = row_weight<T, G, V, WM>(seg[u], lane, active);
                 if (fused_weights(WM)) {
                     acc.sum_abs += fabsf(w[u]);
                     acc.sum_signed += w[u];
@@ -209,7 +224,7 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 // the broadcast is executed by all lanes; slots without a neighbour discard it
-                if (WM == kWeightEmbedded) w[u] = embedded_weight<T, G, V>(seg[u], lane);
+                if (row_weights(WM)) w[u] = row_weight<T, G, V, WM>(seg[u], lane, active && present[u]);
                 if (present[u]) {
                     if (fused_weights(WM)) {
                         acc.sum_abs += fabsf(w[u]);
@@ -235,7 +250,7 @@ __device__ __forceinline__ void load_own_row(const char *__restrict__ own_lane_b
     Segment<T, V> seg;
     if (active) seg.load(own_lane_base + row * row_bytes);
     float t;
-    if (WM == kWeightEmbedded) t = embedded_weight<T, G, V>(seg, lane);
+    if (row_weights(WM)) t = row_weight<T, G, V, WM>(seg, lane, active);
     else t = weights[row];
     own.sum_abs = fabsf(t);
     own.sum_signed = t;
@@ -258,8 +273,8 @@ __device__ __forceinline__ void reduce_slots(RowAcc<V> &acc)
 }
 
 // ---- epilogues ---------------------------------------------------------------------------------
-// An epilogue has per-lane constants (`Lane<G, V>`, set up once per wavefront by `init`) and a
-// `finish` that turns the accumulators of one node into its outputs.
+// An epilogue has per-lane constants (`Lane<G, V>`: a struct of floats, computed once per
+// workgroup by `init`) and a `finish` that turns the accumulators of one node into its outputs.
 
 // Public SpMM: stored position == output column, fp32 row-major output.
 struct EpiloguePlain {
@@ -415,6 +430,27 @@ struct EpilogueFusedT {
     }
 };
 
+// The per-lane constants of an epilogue are needed once per node, after the gather; held in
+// registers for the whole kernel they would cost occupancy in the loop that matters.  They are
+// parked in LDS ([constant][lane], conflict-free) and fetched back by `finish`.
+template <class L>
+struct ParkedLane {
+    static constexpr int kFloats = std::is_empty<L>::value ? 0 : static_cast<int>(sizeof(L) / sizeof(float));
+    static __device__ __forceinline__ void park(const L &c, float *lds, int lane)
+    {
+        const float *src = reinterpret_cast<const float *>(&c);
+#pragma unroll
+        for (int k = 0; k < kFloats; ++k) lds[k * kWave + lane] = src[k];
+    }
+    static __device__ __forceinline__ void fetch(L &c, const float *lds, int lane)
+    {
+        asm volatile("" ::: "memory");      // keep the reads here: not hoisted out of the row loop
+        float *dst = reinterpret_cast<float *>(&c);
+#pragma unroll
+        for (int k = 0; k < kFloats; ++k) dst[k] = lds[k * kWave + lane];
+    }
+};
+
 // ---- the kernel ------------------------------------------------------------------------------
 // Rows are taken in plan order.  Workgroup b < n_block_rows owns one long row; every later
 // workgroup owns kRowsPerWave * 4 consecutive plan entries, wavefront w taking entries
@@ -435,8 +471,15 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(
     const bool active = g * V < valid_positions;
     const char *lane_base = rows + static_cast<int64_t>(g) * V * sizeof(T);
 
-    typename Epilogue::template Lane<G, V> ctx;
-    epi.template init<G, V>(lane, ctx);
+    using LaneConsts = typename Epilogue::template Lane<G, V>;
+    using Parked = ParkedLane<LaneConsts>;
+    __shared__ float parked[Parked::kFloats > 0 ? Parked::kFloats * kWave : 1];
+    {
+        LaneConsts ctx;
+        epi.template init<G, V>(lane, ctx);
+        if (wave == 0) Parked::park(ctx, parked, lane);     // identical in all four wavefronts
+        __syncthreads();
+    }
     RowAcc<V> acc;
     RowAcc<V> own;      // only filled (and only read) by epilogues with an own-row term
     const char *own_lane_base = nullptr;
@@ -472,6 +515,8 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(
             }
             if constexpr (Epilogue::kSelf)
                 load_own_row<T, G, V, WM>(own_lane_base, row_bytes, weights, row, lane, active, own);
+            LaneConsts ctx;
+            Parked::fetch(ctx, parked, lane);
             epi.template finish<G, V>(ctx, row, lane, acc, own);
         }
         return;
@@ -488,6 +533,8 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(
             load_own_row<T, G, V, WM>(own_lane_base, row_bytes, weights, row, lane, active, own);
         accumulate_range<T, G, V, WM>(col_idx, weights, lane_base, row_bytes, p0, p1, lane, active, acc);
         reduce_slots<G, V, WM>(acc);
+        LaneConsts ctx;
+        Parked::fetch(ctx, parked, lane);
         epi.template finish<G, V>(ctx, row, lane, acc, own);
     }
 }
@@ -559,7 +606,17 @@ RowLayout choose_layout(int64_t d_in, int64_t d_out)
         // A row of at most 64 bytes is widened to make room: up to 128 bytes a row costs one
         // cache line either way, and the separate scale gather (a second line) disappears.
         if (d_out > l.groups * (l.vec - 3) - 1 && l.positions() <= 64) l.groups *= 2;
-        l.embed_scale = d_out <= l.groups * (l.vec - 3) - 1 ? 1 : 0;
+        l.embed_scale = d_out <= l.groups * (l.vec - 3) - 1 ? kScaleInTail : kScaleSeparate;
+        // Up to 128 input bits the stored value needs 7 bits (K = 128: with the last bit folded
+        // out, floor(127/2) - popcount lies in [-64, 63]), so the top bit of a byte is free.  Rows
+        // of at least 32 lanes carry the 32 bits of the scale there, one per lane.
+        if (l.embed_scale == kScaleSeparate && d_in <= 128 && l.groups >= 32) {
+            if (d_in == 128) {
+                l.fold_last = 1;
+                l.k_eff = 127;
+            }
+            l.embed_scale = kScaleInTopBits;
+        }
     }
     return l;
 }
@@ -597,7 +654,12 @@ static int launch_fused_spmm_t(const FusedSpmmArgs &a, hipStream_t stream)
 #define BIGCN_FUSED_EMBEDDED(TT, VV)                                                                    \
     return launch_spmm_groups<TT, VV, kWeightEmbedded>(l.groups, a.plan, a.row_ptr, a.col_idx, nullptr, \
                                                        a.c_rows, rb, valid, epi, stream)
-    if (l.kind == kI8 && l.embed_scale) {
+    if (l.kind == kI8 && l.embed_scale == kScaleInTopBits) {
+        if (l.groups < 32) return BIGCN_EINVAL;
+        return launch_spmm_groups<int8_t, 8, kWeightTopBits>(l.groups, a.plan, a.row_ptr, a.col_idx, nullptr,
+                                                             a.c_rows, rb, valid, epi, stream);
+    }
+    if (l.kind == kI8 && l.embed_scale == kScaleInTail) {
         BIGCN_FUSED_EMBEDDED(int8_t, 8);
     }
     if (l.kind == kI8) {

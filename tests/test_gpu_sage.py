@@ -104,8 +104,8 @@ def test_sage_forward_matches_oracle(B, name, n_scaled):
     assert stats[-1]["rows_compared"] >= 0.5 * work.n
 
 
-# d_in / d_out pairs chosen to reach: one-byte rows with and without the embedded scale, the
-# folded last bit (d_in = 256), fp16 rows, fp32 rows, rows as wide as a wavefront (d_out = 512), and
+# d_in / d_out pairs chosen to reach: one-byte rows with and without the embedded scale (in the
+# row's tail, or in the spare top bits when d_in <= 128), the folded last bit (d_in = 128, 256), fp16 rows, fp32 rows, rows as wide as a wavefront (d_out = 512), and
 # graphs with empty rows and rows long enough for the workgroup-per-row path.
 @pytest.mark.parametrize("dims,n,n_edges,i0", [
     ((64, 40, 7), 3000, 2500, 2.0),
@@ -114,6 +114,7 @@ def test_sage_forward_matches_oracle(B, name, n_scaled):
     ((257, 300, 12), 2000, 9000, 2.0),
     ((130, 512, 512, 9), 1500, 30000, 1.1),
     ((2100, 33, 64, 3), 1200, 5000, 2.0),
+    ((128, 300, 128, 256, 4), 1500, 20000, 1.1),
 ])
 def test_sage_forward_formats_and_edge_cases(B, dims, n, n_edges, i0):
     work = small_sage_workload(n, n_edges, dims, seed=sum(dims), i0=i0)

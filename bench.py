@@ -28,7 +28,7 @@ VALU_BINARY_MAC_PEAK = 256 * 4 * 16 * 2.4e9 * 32 / 2   # 2 VALU instructions per
 
 # HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE, scaled by a copy kernel of known size); see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"c5": 4.65e10}    # profiles/spmm_fused_c5.md
+MEASURED_TRAFFIC_BYTES = {"c5": 4.61e10}    # profiles/spmm_fused_c5.md (layer 1, the slowest launch)
 
 
 def log(*a):
@@ -273,18 +273,17 @@ def main():
         gemm.append({"layer": l, "ms": t_gemm * 1e3, "binary_op_per_s": macs / t_gemm,
                      "frac_valu_peak": macs / t_gemm / VALU_BINARY_MAC_PEAK})
         spmm.append({"layer": l, "ms": t_spmm * 1e3, "row_bytes": row_bytes,
-                     "gather_GBps": gather / t_spmm / 1e9, "compulsory_GBps": minimum / t_spmm / 1e9})
-    # dominant kernel: the aggregation launches with the widest rows (same kernel instantiation)
-    widest = max(s["row_bytes"] for s in spmm)
-    dom = [l for l in range(n_layers) if spmm[l]["row_bytes"] == widest and l < n_layers - 1] or \
-          [max(range(n_layers), key=lambda l: spmm[l]["ms"])]
-    dom_ms = sum(spmm[l]["ms"] for l in dom) / len(dom)
-    dom_bytes = sum(aggregation_bytes(cfg, work.nnz, l, B)[0] for l in dom) / len(dom)
+                     "gather_GBps": gather / t_spmm / 1e9, "frac_hbm_peak": gather / t_spmm / 1e9 / HBM_PEAK_GBPS,
+                     "compulsory_GBps": minimum / t_spmm / 1e9})
+    # dominant kernel: the slowest launch of a step (an aggregation on every workload here)
+    dom = max(range(n_layers), key=lambda l: spmm[l]["ms"])
+    dom_ms = spmm[dom]["ms"]
+    dom_bytes = aggregation_bytes(cfg, work.nnz, dom, B)[0]
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC_BYTES.get(cfg.name)
     roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                "kernel": "spmm_kernel (fused aggregation), layers " + ",".join(str(l) for l in dom),
+                "kernel": f"spmm_kernel (fused aggregation), layer {dom}",
                 "avg_launch_ms": dom_ms, "algorithmic_bytes_per_launch": dom_bytes}
 
     result = {

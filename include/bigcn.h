@@ -161,7 +161,7 @@ int64_t bigcn_plan_nnz(const bigcn_plan *plan);
  * vals == NULL means all ones.  z (n rows, d columns, fp32) and out must not overlap.
  * Each output element is a sum in a fixed order, so results are run-to-run identical.
  * `plan` must have been created from the same row_ptr / col_idx.
- * Errors: ENULL, EINVAL (n differs from the plan's, d <= 0, ld_z < d, ld_out < d).
+ * Errors: ENULL, EINVAL (n differs from the plan's, d <= 0, ld_z < d or ld_z >= 2^29, ld_out < d).
  */
 int bigcn_spmm(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
                const float *vals, int64_t n, const float *z, int64_t d, int64_t ld_z,

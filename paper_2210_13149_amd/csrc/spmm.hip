@@ -153,16 +153,26 @@ struct RowAcc {
     }
 };
 
+// Address of a lane's segment of stored row k: one 32 x 32 -> 64 bit multiply-add (row indices
+// and row strides are below 2^32; the launchers check the stride).
+__device__ __forceinline__ const char *row_address(const char *lane_base, int k, uint32_t row_bytes)
+{
+    return lane_base + static_cast<uint64_t>(static_cast<uint32_t>(k)) * row_bytes;
+}
+
 // ---- accumulate the neighbours p0..p1-1 of one node (per lane: V positions) ---------------
-// active: this lane's positions exist in the stored row (lanes past the row width never load).
+// active: this lane's positions exist in the stored row (lanes past the row width never load);
+// kAllActive: known at compile time to hold for every lane (stored rows of the fused path),
+// which keeps the loop free of per-lane predication.
 // In gather mode the row values are weighted by |w| and both sum |w| and sum w are kept.
-template <typename T, int G, int V, int WM>
+template <typename T, int G, int V, int WM, bool kAllActive>
 __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col_idx,
                                                  const float *__restrict__ weights,
-                                                 const char *__restrict__ lane_base, int64_t row_bytes,
-                                                 int64_t p0, int64_t p1, int lane, bool active,
+                                                 const char *__restrict__ lane_base, uint32_t row_bytes,
+                                                 int64_t p0, int64_t p1, int lane, bool active_in,
                                                  RowAcc<V> &acc)
 {
+    const bool active = kAllActive || active_in;
     constexpr int S = kWave / G;      // neighbours covered by one load instruction
     constexpr int U = 4;              // load instructions in flight (4 measured best: more costs occupancy)
     const int slot = lane / G;
@@ -192,7 +202,7 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
                     kk = __shfl(k, t + u * S + slot, kWave);
                     w[u] = __shfl(wk, t + u * S + slot, kWave);
                 }
-                if (active) seg[u].load(lane_base + static_cast<int64_t>(kk) * row_bytes);
+                if (active) seg[u].load(row_address(lane_base, kk, row_bytes));
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -219,7 +229,7 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
                 const int from = present[u] ? src : 0;
                 const int kk = __shfl(k, from, kWave);
                 w[u] = __shfl(wk, from, kWave);
-                if (active && present[u]) seg[u].load(lane_base + static_cast<int64_t>(kk) * row_bytes);
+                if (active && present[u]) seg[u].load(row_address(lane_base, kk, row_bytes));
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -242,13 +252,13 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
 // The node's own stored row (second product array of a layer with an own-row term), weighted by
 // the node's own scale exactly as a neighbour's row would be: pos = |t| * stored, sums of t.
 template <typename T, int G, int V, int WM>
-__device__ __forceinline__ void load_own_row(const char *__restrict__ own_lane_base, int64_t row_bytes,
+__device__ __forceinline__ void load_own_row(const char *__restrict__ own_lane_base, uint32_t row_bytes,
                                              const float *__restrict__ weights, int64_t row, int lane,
                                              bool active, RowAcc<V> &own)
 {
     own.clear();
     Segment<T, V> seg;
-    if (active) seg.load(own_lane_base + row * row_bytes);
+    if (active) seg.load(row_address(own_lane_base, static_cast<int>(row), row_bytes));
     float t;
     if (row_weights(WM)) t = row_weight<T, G, V, WM>(seg, lane, active);
     else t = weights[row];
@@ -457,18 +467,28 @@ struct ParkedLane {
 // base + w, base + w + 4, ... (neighbouring entries have similar lengths).
 constexpr int kRowsPerWave = 16;
 
+// Wavefronts per SIMD the register allocation aims for.  The gather hides HBM latency with
+// resident wavefronts, so the one-byte rows of the Bi-GCN path (which fit 64 registers without
+// spilling) ask for the maximum of 8; wider accumulators keep the compiler's own choice.
+template <typename T, int V, class Epilogue>
+constexpr int spmm_min_waves()
+{
+    return (sizeof(T) == 1 && V == 8 && !Epilogue::kSelf) ? 8 : 1;
+}
+
 template <typename T, int G, int V, int WM, class Epilogue>
-__global__ __launch_bounds__(kBlock) void spmm_kernel(
+__global__ __launch_bounds__(kBlock, (spmm_min_waves<T, V, Epilogue>())) void spmm_kernel(
     const int32_t *__restrict__ row_order, int64_t n, int64_t n_block_rows,
     const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
-    const float *__restrict__ weights, const char *__restrict__ rows, int64_t row_bytes,
+    const float *__restrict__ weights, const char *__restrict__ rows, uint32_t row_bytes,
     int valid_positions, Epilogue epi)
 {
+    constexpr bool kAllActive = fused_weights(WM);     // stored rows of the fused path fill G * V positions
     __shared__ float partial[kWavesPerBlock - 1][V + 2][kWave];
     const int lane = lane_id();
     const int wave = wave_in_block();
     const int g = lane & (G - 1);
-    const bool active = g * V < valid_positions;
+    const bool active = kAllActive || g * V < valid_positions;
     const char *lane_base = rows + static_cast<int64_t>(g) * V * sizeof(T);
 
     using LaneConsts = typename Epilogue::template Lane<G, V>;
@@ -496,7 +516,7 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(
         if (q0 > p1) q0 = p1;
         if (q1 > p1) q1 = p1;
         acc.clear();
-        accumulate_range<T, G, V, WM>(col_idx, weights, lane_base, row_bytes, q0, q1, lane, active, acc);
+        accumulate_range<T, G, V, WM, kAllActive>(col_idx, weights, lane_base, row_bytes, q0, q1, lane, active, acc);
         reduce_slots<G, V, WM>(acc);
         if (wave > 0) {
 #pragma unroll
@@ -531,7 +551,7 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(
         acc.clear();
         if constexpr (Epilogue::kSelf)
             load_own_row<T, G, V, WM>(own_lane_base, row_bytes, weights, row, lane, active, own);
-        accumulate_range<T, G, V, WM>(col_idx, weights, lane_base, row_bytes, p0, p1, lane, active, acc);
+        accumulate_range<T, G, V, WM, kAllActive>(col_idx, weights, lane_base, row_bytes, p0, p1, lane, active, acc);
         reduce_slots<G, V, WM>(acc);
         LaneConsts ctx;
         Parked::fetch(ctx, parked, lane);
@@ -544,13 +564,16 @@ static int launch_spmm_one(const bigcn_plan *plan, const int64_t *row_ptr, const
                            const float *weights, const void *rows, int64_t row_bytes,
                            int valid_positions, const Epilogue &epi, hipStream_t stream)
 {
+    if (row_bytes <= 0 || row_bytes > 0x7fffffff) return BIGCN_EINVAL;
+    if (fused_weights(WM) && valid_positions != G * V) return BIGCN_EINVAL;
     const int64_t wave_rows = plan->n - plan->n_block_rows;
     const int64_t per_block = kWavesPerBlock * kRowsPerWave;
     const int64_t blocks = plan->n_block_rows + (wave_rows + per_block - 1) / per_block;
     if (blocks == 0) return BIGCN_OK;
     hipLaunchKernelGGL((spmm_kernel<T, G, V, WM, Epilogue>), dim3(static_cast<unsigned>(blocks)),
                        dim3(kBlock), 0, stream, plan->row_order, plan->n, plan->n_block_rows, row_ptr,
-                       col_idx, weights, static_cast<const char *>(rows), row_bytes, valid_positions, epi);
+                       col_idx, weights, static_cast<const char *>(rows), static_cast<uint32_t>(row_bytes),
+                       valid_positions, epi);
     return check_launch();
 }
 

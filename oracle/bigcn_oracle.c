@@ -23,6 +23,9 @@
  *  - no bias, no ReLU, no dropout (Sec. 4.2.2: binarisation acts as the activation).
  */
 #include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 #include <stddef.h>
 #include <stdint.h>
 
@@ -143,9 +146,38 @@ void oracle_aggregate(int64_t n, const int64_t *row_ptr, const int32_t *col_idx,
     }
 }
 
+/* ------------------------------------------------------------------------- */
+/* Algorithm 1, first line:  dL/dzeta = A~^T dL/dH^(l+1), written as the          */
+/* transpose of the sum above: entry p of row i sends a_tilde[p] * g[i, :] to     */
+/* row col_idx[p].  No symmetry of the pattern is assumed.  Threads own disjoint  */
+/* column ranges, so every output element is summed in CSR order by one thread.   */
+/* ------------------------------------------------------------------------- */
+void oracle_aggregate_transposed(int64_t n, const int64_t *row_ptr, const int32_t *col_idx,
+                                 const double *a_tilde, const double *g, int64_t d, double *out)
+{
+    for (int64_t e = 0; e < n * d; ++e)
+        out[e] = 0.0;
+#pragma omp parallel
+    {
+#ifdef _OPENMP
+        int64_t t = omp_get_thread_num(), nt = omp_get_num_threads();
+#else
+        int64_t t = 0, nt = 1;
+#endif
+        int64_t j0 = d * t / nt, j1 = d * (t + 1) / nt;
+        for (int64_t i = 0; i < n; ++i) {
+            for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) {
+                double *ok = out + (int64_t)col_idx[p] * d;
+                double a = a_tilde[p];
+                for (int64_t j = j0; j < j1; ++j)
+                    ok[j] += a * g[i * d + j];
+            }
+        }
+    }
+}
+
 /* Number of threads the parallel loops above use (reported by the benchmark). */
 #ifdef _OPENMP
-#include <omp.h>
 int oracle_num_threads(void) { return omp_get_max_threads(); }
 void oracle_set_num_threads(int t) { if (t > 0) omp_set_num_threads(t); }
 #else

@@ -46,6 +46,9 @@ def _lib():
         lib.oracle_rescale.argtypes = [_i32p, _f64p, _f64p, ctypes.c_int64, ctypes.c_int64, _f64p]
         lib.oracle_aggregate.argtypes = [ctypes.c_int64, _i64p, _i32p, _f64p, _f64p,
                                          ctypes.c_int64, _f64p]
+        lib.oracle_aggregate_transposed.argtypes = [ctypes.c_int64, _i64p, _i32p, _f64p, _f64p,
+                                                    ctypes.c_int64, _f64p]
+        lib.oracle_aggregate_transposed.restype = None
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
         for name in ("oracle_gcn_norm", "oracle_binarize_rows_f32", "oracle_binarize_rows_f64",
@@ -263,6 +266,70 @@ def predict(h: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     h64 = h.astype(np.float64)
     e = np.exp(h64 - h64.max(axis=1, keepdims=True))
     return labels, e / e.sum(axis=1, keepdims=True)
+
+
+# ---- back propagation through one binarised layer (Sec. 4.3, Algorithm 1) -----------------------
+
+def aggregate_transposed(row_ptr, col_idx, a_tilde: np.ndarray, g: np.ndarray) -> np.ndarray:
+    """Algorithm 1, first line: ``A~^T g`` as the literal transpose of :func:`aggregate` (entry p
+    of row i sends ``a_tilde[p] * g[i]`` to row ``col_idx[p]``), fp64."""
+    row_ptr, col_idx, n = _check_csr(row_ptr, col_idx)
+    a_tilde = np.ascontiguousarray(a_tilde, dtype=np.float64)
+    g = np.ascontiguousarray(g, dtype=np.float64)
+    if g.ndim != 2 or g.shape[0] != n or a_tilde.shape != (col_idx.size,):
+        raise ValueError("shape mismatch")
+    out = np.empty_like(g)
+    _lib().oracle_aggregate_transposed(n, _ptr(row_ptr, _i64p), _ptr(col_idx, _i32p),
+                                       _ptr(a_tilde, _f64p), _ptr(g, _f64p), g.shape[1],
+                                       _ptr(out, _f64p))
+    return out
+
+
+def weight_gradient(w: np.ndarray, g_wt: np.ndarray) -> np.ndarray:
+    """Sec. 4.3, the gradient of the full-precision weights from the gradient of the binarised
+    ones (W~_:,j = alpha_j B_:,j, alpha_j = ||W_:,j||_1 / d_in, B = sign(W)):
+    ``dL/dW_ij = (1/d_in) B_ij sum_k g_wt[k, j] B_kj  +  alpha_j g_wt[i, j] 1[|W_ij| < 1]``
+    (first term: alpha_j depends on every entry of its column; second term: the straight-through
+    estimate d sign(r)/dr = 1[|r| < 1])."""
+    w = np.asarray(w, dtype=np.float32)
+    g_wt = np.asarray(g_wt, dtype=np.float64)
+    if w.shape != g_wt.shape:
+        raise ValueError("shape mismatch")
+    bt, alpha = binarize_weight(w)
+    b = bt.T.astype(np.float64)                      # (d_in, d_out)
+    d_in = w.shape[0]
+    column = (g_wt * b).sum(axis=0)                  # sum_k g_wt[k, j] B_kj
+    ste = (np.abs(w.astype(np.float64)) < 1.0).astype(np.float64)
+    return b * column[None, :] / d_in + alpha[None, :] * g_wt * ste
+
+
+def layer_backward(row_ptr, col_idx, a_tilde, g_out: np.ndarray, sign: np.ndarray, beta: np.ndarray,
+                   w: np.ndarray, mul=None) -> Dict[str, np.ndarray]:
+    """Back propagation through one binarised graph-convolution layer (Sec. 4.3, Algorithm 1),
+    fp64.  ``g_out`` = dL/dH^(l+1); ``sign``, ``beta`` are the layer's binarised input as the
+    forward produced them (H~ = beta_i F_i); ``w`` the full-precision weights.
+
+      g_zeta = A~^T g_out;   g_wt = H~^T g_zeta;   g_ht = g_zeta W~^T      (Algorithm 1)
+      g_h    = g_ht * 1[|g_ht| < 1]                                       (the clipped
+               straight-through estimate of Sec. 4.3, with the indicator on the gradient as
+               the paper prints it)
+      g_w    = weight_gradient(w, g_wt)
+
+    With ``mul`` (the layer input was standardised by a frozen per-column affine map) ``g_in`` is
+    the gradient with respect to the values before that map, ``g_h * mul``; else ``g_in = g_h``.
+    Returns every intermediate."""
+    sign = np.asarray(sign, dtype=np.float64)
+    beta = np.asarray(beta, dtype=np.float64)
+    bt, alpha = binarize_weight(w)
+    h_tilde = beta[:, None] * sign                                   # (n, d_in)
+    w_tilde = alpha[None, :] * bt.T.astype(np.float64)               # (d_in, d_out)
+    g_zeta = aggregate_transposed(row_ptr, col_idx, a_tilde, g_out)
+    g_wt = h_tilde.T @ g_zeta
+    g_ht = g_zeta @ w_tilde.T
+    g_h = g_ht * (np.abs(g_ht) < 1.0)
+    g_in = g_h if mul is None else g_h * np.asarray(mul, dtype=np.float64)[None, :]
+    return {"g_zeta": g_zeta, "g_wt": g_wt, "g_ht": g_ht, "g_h": g_h, "g_in": g_in,
+            "g_w": weight_gradient(w, g_wt), "h_tilde": h_tilde, "w_tilde": w_tilde}
 
 
 # ---- Bi-GraphSAGE, mean aggregator (Sec. 4.4.2) ------------------------------------------------

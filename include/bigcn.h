@@ -264,6 +264,41 @@ int bigcn_predict(const float *logits, int64_t n, int64_t d, int64_t ld, int32_t
                   float *probs, int64_t ld_probs, void *stream);
 
 /*
+ * Back propagation through one binarised graph-convolution layer (Sec. 4.3, Algorithm 1 and the
+ * two gradient rules of that section).  With g_out = dL/dH^(l+1):
+ *
+ *   g_zeta = A~^T g_out
+ *   g_wt   = H~^T g_zeta            H~ = beta_i F_i   (the layer input as bigcn_pack produced it)
+ *   g_ht   = g_zeta W~^T            W~ = alpha_j B_j  (from the fp32 weights w)
+ *   g_in   = g_ht * 1[|g_ht| < 1] * bn_mul[t]         (clipped straight-through rule; bn_mul, if
+ *                                                     given, is the frozen standardisation factor
+ *                                                     of the layer input)
+ *   g_w[t,j] = sign(w[t,j]) (sum_k g_wt[k,j] sign(w[k,j])) / d_in
+ *              + alpha_j g_wt[t,j] 1[|w[t,j]| < 1]
+ *
+ *   plan, row_ptr, col_idx, vals : the graph and the coefficients of A~ (bigcn_gcn_norm); vals
+ *                                  must be symmetric, as those are, so that A~^T = A~   (DEVICE)
+ *   g_out  : n rows of d_out fp32, row stride ld_g                                    (DEVICE)
+ *   f_bits : n rows of packed input signs, row stride ld_f_words; beta: n scales      (DEVICE)
+ *   w      : fp32 weights, d_in rows of d_out, row stride ld_w                        (DEVICE)
+ *   g_w    : d_in rows of d_out fp32, row stride ld_gw                                (DEVICE, out)
+ *   g_in   : n rows of d_in fp32, row stride ld_gin; NULL skips it (first layer)      (DEVICE, out)
+ *   workspace : at least bigcn_layer_backward_workspace_bytes(n, d_in, d_out) bytes, 256-byte
+ *               aligned (holds g_zeta, both packings of w and the partial sums over node chunks)
+ * Sums over the nodes are taken in a fixed order: results are run-to-run identical.
+ * Errors: ENULL, EINVAL (n differs from the plan's, sizes <= 0, leading dimensions too small),
+ * ESHAPE (d_in or d_out > BIGCN_MAX_K_BITS), EWORKSPACE.  The size query returns 0 for invalid
+ * arguments.
+ */
+size_t bigcn_layer_backward_workspace_bytes(int64_t n, int64_t d_in, int64_t d_out);
+int bigcn_layer_backward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                         const float *vals, int64_t n, const float *g_out, int64_t ld_g,
+                         const uint64_t *f_bits, int64_t ld_f_words, const float *beta,
+                         const float *w, int64_t ld_w, int64_t d_in, int64_t d_out,
+                         const float *bn_mul, float *g_w, int64_t ld_gw, float *g_in,
+                         int64_t ld_gin, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Bi-GraphSAGE with the mean aggregator (Sec. 4.4.2, the binarised layer):
  *
  *   h_i^(l+1) = W~_theta (*) h~_i  +  (1/|N_i|) sum_{j in N_i} W~_n (*) h~_j

@@ -37,7 +37,8 @@ EXPORTS = (
     "bigcn_profile_destroy", "bigcn_forward_profiled", "bigcn_profile_read",
     "bigcn_mean_norm", "bigcn_sage_forward_workspace_bytes", "bigcn_sage_forward",
     "bigcn_sage_forward_profiled", "bigcn_forward_packed", "bigcn_column_stats_workspace_bytes",
-    "bigcn_column_stats", "bigcn_predict",
+    "bigcn_column_stats", "bigcn_predict", "bigcn_layer_backward_workspace_bytes",
+    "bigcn_layer_backward",
 )
 
 
@@ -126,6 +127,11 @@ def lib() -> ctypes.CDLL:
         L.bigcn_column_stats.argtypes = [vp, i64, i64, i64, ctypes.c_double, vp, vp, vp, ctypes.c_size_t, vp]
         L.bigcn_predict.restype = i32
         L.bigcn_predict.argtypes = [vp, i64, i64, i64, vp, vp, i64, vp]
+        L.bigcn_layer_backward_workspace_bytes.restype = ctypes.c_size_t
+        L.bigcn_layer_backward_workspace_bytes.argtypes = [i64, i64, i64]
+        L.bigcn_layer_backward.restype = i32
+        L.bigcn_layer_backward.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, i64, vp, vp, i64, i64, i64, vp,
+                                           vp, i64, vp, i64, vp, ctypes.c_size_t, vp]
         L.bigcn_mean_norm.restype = i32
         L.bigcn_mean_norm.argtypes = [vp, i64, vp, vp]
         L.bigcn_sage_forward_workspace_bytes.restype = ctypes.c_size_t
@@ -449,6 +455,36 @@ def bigcn_predict(logits: torch.Tensor, want_probs: bool = False
     _check(lib().bigcn_predict(_ptr(logits), n, d, logits.stride(0), _ptr(labels), _ptr(probs), d, _stream()),
            "bigcn_predict")
     return labels, probs
+
+
+def bigcn_layer_backward(plan: Plan, row_ptr: torch.Tensor, col_idx: torch.Tensor, vals: torch.Tensor,
+                         g_out: torch.Tensor, f_bits: torch.Tensor, beta: torch.Tensor, w: torch.Tensor,
+                         bn_mul: Optional[torch.Tensor] = None, want_input_grad: bool = True,
+                         workspace: Optional[torch.Tensor] = None
+                         ) -> Tuple[torch.Tensor, Optional[torch.Tensor]]:
+    """Back propagation through one binarised layer: returns ``(g_w (d_in, d_out), g_in (n, d_in)
+    or None)`` from ``g_out (n, d_out)``, the layer's packed input ``(f_bits, beta)`` and its
+    fp32 weights ``w (d_in, d_out)``."""
+    for t, name in ((g_out, "g_out"), (beta, "beta"), (w, "w"), (vals, "vals")):
+        _dev(t, torch.float32, name)
+    _dev(f_bits, torch.int64, "f_bits")
+    if g_out.dim() != 2 or w.dim() != 2 or g_out.stride(1) != 1 or w.stride(1) != 1:
+        raise ValueError("g_out and w must be row-major matrices")
+    n, d_out = g_out.shape
+    d_in = w.shape[0]
+    if w.shape[1] != d_out or f_bits.shape[0] != n or beta.numel() != n:
+        raise ValueError("shape mismatch")
+    need = int(lib().bigcn_layer_backward_workspace_bytes(n, d_in, d_out))
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=g_out.device)
+    g_w = torch.empty((d_in, d_out), dtype=torch.float32, device=g_out.device)
+    g_in = torch.empty((n, d_in), dtype=torch.float32, device=g_out.device) if want_input_grad else None
+    _check(lib().bigcn_layer_backward(plan.handle, _ptr(row_ptr), _ptr(col_idx), _ptr(vals), n, _ptr(g_out),
+                                      g_out.stride(0), _ptr(f_bits), f_bits.stride(0), _ptr(beta), _ptr(w),
+                                      w.stride(0), d_in, d_out, _ptr(bn_mul), _ptr(g_w), g_w.stride(0),
+                                      _ptr(g_in), d_in, _ptr(workspace), workspace.numel(), _stream()),
+           "bigcn_layer_backward")
+    return g_w, g_in
 
 
 class BiGCN:

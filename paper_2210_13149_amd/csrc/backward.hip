@@ -1,0 +1,340 @@
+// Back propagation through one binarised graph-convolution layer (Sec. 4.3, Algorithm 1):
+//
+//   g_zeta = A~^T g_out                          (aggregation kernel; A~ is symmetric)
+//   g_wt   = H~^T g_zeta,   H~ = beta_i F_i      (d_in x d_out, a reduction over the nodes)
+//   g_ht   = g_zeta W~^T,   W~ = alpha_j B_j     (n x d_in)
+//   g_in   = g_ht 1[|g_ht| < 1] (* mul)          (clipped straight-through rule)
+//   g_w    = B_tj (sum_k g_wt[k,j] B_kj) / d_in + alpha_j g_wt[t,j] 1[|W_tj| < 1]
+//
+// The two dense products have one +-1 operand each.  They run on the fp32 matrix cores
+// (v_mfma_f32_32x32x2_f32): the +-1 operand is expanded from packed bits in registers (three
+// vector operations per value, hidden behind the 64-cycle multiply), the scales beta / alpha are
+// folded into the fp32 operand while it is staged through LDS.
+//
+// Operand layout of the 32x32x2 multiply, lane l:  A[i = l % 32][k = l / 32],
+// B[k = l / 32][j = l % 32]; accumulator register r holds row 8 (r / 4) + 4 (l / 32) + r % 4 and
+// column l % 32.
+#include "bigcn_internal.h"
+
+namespace bigcn {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kStageRows = 64;      // rows (of g_zeta, of the fp32 operand) staged per step
+
+// +1.0f where bit `pos` of `word` is set, else -1.0f.
+__device__ __forceinline__ float sign_from_bit(uint32_t word, int pos)
+{
+    return __uint_as_float(0xbf800000u ^ (((word >> pos) & 1u) << 31));
+}
+
+// ---- g_ht = (g_zeta alpha) B^T, clipped, times mul ---------------------------------------------
+// Workgroup: 128 rows (four wavefronts x 32) x 128 columns t of the layer input; wavefront: 32
+// rows x 4 column tiles.  K runs over the layer's output columns j in steps of 64 (one packed
+// word of the weights packed along j): the 128 x 64 slab of g_zeta * alpha_j goes through LDS, the
+// +-1 operand B[j][t] is bit j of the lane's own packed weight row t.
+__global__ __launch_bounds__(kBlock) void backward_input_kernel(
+    const float *__restrict__ g_zeta, int64_t n, int d_out, int64_t ld_gz, const float *__restrict__ alpha,
+    const uint64_t *__restrict__ wt_bits, int64_t ld_wt, int d_in, const float *__restrict__ mul,
+    float *__restrict__ g_in, int64_t ld_gin)
+{
+    constexpr int KC = 64;
+    __shared__ float slab[128][KC + 1];
+    const int lane = lane_id();
+    const int wave = wave_in_block();
+    const int i32 = lane & 31, half = lane >> 5;
+    const int64_t row0 = static_cast<int64_t>(blockIdx.x) * 128;
+    const int col0 = blockIdx.y * 128;
+
+    v16f acc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[q][r] = 0.0f;
+
+    int t[4];
+    bool t_in[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        t[q] = col0 + 32 * q + i32;
+        t_in[q] = t[q] < d_in;
+    }
+
+    for (int j0 = 0; j0 < d_out; j0 += KC) {
+        // stage g_zeta[row0 .. +128][j0 .. +64] * alpha_j: thread (r = tid / 64 + 4 it, c = tid % 64)
+        __syncthreads();
+        {
+            const int c = threadIdx.x & 63;
+            const int j = j0 + c;
+            const float a = j < d_out ? alpha[j] : 0.0f;
+#pragma unroll 8
+            for (int it = 0; it < 32; ++it) {
+                const int r = (threadIdx.x >> 6) + 4 * it;
+                const int64_t row = row0 + r;
+                slab[r][c] = (row < n && j < d_out) ? g_zeta[row * ld_gz + j] * a : 0.0f;
+            }
+        }
+        __syncthreads();
+        // this lane's packed weight words for the chunk: bit (j - j0) of word j0 / 64 of row t;
+        // pre-shifted by the lane's k offset (l / 32)
+        uint32_t lo[4], hi[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint64_t w = t_in[q] ? wt_bits[static_cast<int64_t>(t[q]) * ld_wt + (j0 >> 6)] : 0ull;
+            const uint64_t shifted = w >> half;
+            lo[q] = static_cast<uint32_t>(shifted);
+            hi[q] = static_cast<uint32_t>(shifted >> 32);
+        }
+        const float *arow = &slab[wave * 32 + i32][half];
+#pragma unroll
+        for (int s = 0; s < KC / 2; ++s) {
+            const float a = arow[2 * s];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                // k = 2 s + half; after the pre-shift it is bit 2 s of the 64-bit word (bit 31 of
+                // the low half has moved down from the high half's bit 0 only for half = 1, which
+                // the 64-bit shift above already did)
+                const float b = s < 16 ? sign_from_bit(lo[q], 2 * s) : sign_from_bit(hi[q], 2 * s - 32);
+                acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[q], 0, 0, 0);
+            }
+        }
+    }
+    // epilogue: clipped straight-through rule, optional per-column factor
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (!t_in[q]) continue;
+        const float m = mul != nullptr ? mul[t[q]] : 1.0f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = row0 + wave * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+            if (row < n) {
+                const float g = acc[q][r];
+                g_in[row * ld_gin + t[q]] = (fabsf(g) < 1.0f ? g : 0.0f) * m;
+            }
+        }
+    }
+}
+
+// ---- partial g_wt = H~^T g_zeta over a chunk of nodes -------------------------------------------
+// Workgroup (chunk, j block of 64, t block of 256): wavefront w owns t = 64 w .. 64 w + 63 (two
+// tiles) x two j tiles.  Per step 64 nodes are staged: g_zeta[i][j] * beta_i (fp32, LDS) and the
+// packed signs of the nodes' 256 input columns (LDS); operand A[t][i] is bit t of node i.
+__global__ __launch_bounds__(kBlock) void backward_weight_partial_kernel(
+    const float *__restrict__ g_zeta, int64_t n, int d_out, int64_t ld_gz, const float *__restrict__ beta,
+    const uint64_t *__restrict__ f_bits, int64_t ld_f, int d_in, int64_t rows_per_chunk,
+    float *__restrict__ partial)
+{
+    __shared__ float slab[kStageRows][64 + 1];          // [node][j]
+    __shared__ uint64_t signs[kStageRows][4 + 1];        // [node][word of the 256-column t block]
+    const int lane = lane_id();
+    const int wave = wave_in_block();
+    const int i32 = lane & 31, half = lane >> 5;
+    const int j0 = blockIdx.y * 64;
+    const int t0 = blockIdx.z * 256;
+    const int64_t i_begin = static_cast<int64_t>(blockIdx.x) * rows_per_chunk;
+    const int64_t i_end = i_begin + rows_per_chunk < n ? i_begin + rows_per_chunk : n;
+
+    v16f acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
+
+    // the lane's two t values, their word inside the 256-column block and bit inside the word
+    const int tw = wave;                              // 64 consecutive t per wavefront = one word
+    const int bit[2] = {i32, 32 + i32};
+
+    for (int64_t i0 = i_begin; i0 < i_end; i0 += kStageRows) {
+        __syncthreads();
+        {
+            const int c = threadIdx.x & 63;
+            const int j = j0 + c;
+#pragma unroll 4
+            for (int it = 0; it < kStageRows / 4; ++it) {
+                const int r = (threadIdx.x >> 6) + 4 * it;
+                const int64_t row = i0 + r;
+                const bool live = row < i_end && j < d_out;
+                slab[r][c] = live ? g_zeta[row * ld_gz + j] * beta[row] : 0.0f;
+            }
+            // 64 nodes x 4 words: one word per thread
+            const int r = threadIdx.x >> 2, w = threadIdx.x & 3;
+            const int64_t row = i0 + r;
+            const int word = (t0 >> 6) + w;
+            signs[r][w] = (row < i_end && word < (d_in + 63) / 64) ? f_bits[row * ld_f + word] : 0ull;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int s = 0; s < kStageRows / 2; ++s) {
+            const int node = 2 * s + half;
+            const uint64_t w = signs[node][tw];
+            const float b0 = slab[node][i32];
+            const float b1 = slab[node][32 + i32];
+            const uint32_t wlo = static_cast<uint32_t>(w), whi = static_cast<uint32_t>(w >> 32);
+            const float a0 = sign_from_bit(wlo, bit[0]);
+            const float a1 = sign_from_bit(whi, bit[1] - 32);
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+    }
+    // partial[chunk][t][j]; rows of nodes past i_end contributed zeros (slab = 0)
+    float *dst = partial + static_cast<int64_t>(blockIdx.x) * d_in * d_out;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int j = j0 + 32 * b + i32;
+            if (j >= d_out) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int t = t0 + 64 * wave + 32 * a + 8 * (r >> 2) + 4 * half + (r & 3);
+                if (t < d_in) dst[static_cast<int64_t>(t) * d_out + j] = acc[a][b][r];
+            }
+        }
+}
+
+// g_wt[t][j] = sum over chunks (in chunk order, fp64), written as fp32.
+__global__ __launch_bounds__(kBlock) void backward_weight_reduce_kernel(const float *__restrict__ partial,
+                                                                        int64_t chunks, int64_t elems,
+                                                                        float *__restrict__ g_wt)
+{
+    const int64_t e = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (e >= elems) return;
+    double s = 0.0;
+    for (int64_t c = 0; c < chunks; ++c) s += static_cast<double>(partial[c * elems + e]);
+    g_wt[e] = static_cast<float>(s);
+}
+
+// Sec. 4.3, gradient of the full-precision weights: workgroup per column j (64 lanes stride
+// over t): column sum of g_wt[t][j] B_tj, then both terms.
+__global__ __launch_bounds__(kWave) void backward_weight_finish_kernel(
+    const float *__restrict__ g_wt, const float *__restrict__ w, int64_t ld_w, const float *__restrict__ alpha,
+    int d_in, int d_out, float *__restrict__ g_w, int64_t ld_gw)
+{
+    const int j = blockIdx.x;
+    const int lane = threadIdx.x;
+    double s = 0.0;
+    for (int t = lane; t < d_in; t += kWave) {
+        const float b = w[static_cast<int64_t>(t) * ld_w + j] >= 0.0f ? 1.0f : -1.0f;
+        s += static_cast<double>(g_wt[static_cast<int64_t>(t) * d_out + j]) * b;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, kWave);
+    const float column = static_cast<float>(s / static_cast<double>(d_in));
+    const float a = alpha[j];
+    for (int t = lane; t < d_in; t += kWave) {
+        const float wv = w[static_cast<int64_t>(t) * ld_w + j];
+        const float b = wv >= 0.0f ? 1.0f : -1.0f;
+        const float g = g_wt[static_cast<int64_t>(t) * d_out + j];
+        g_w[static_cast<int64_t>(t) * ld_gw + j] = b * column + (fabsf(wv) < 1.0f ? a * g : 0.0f);
+    }
+}
+
+struct BackwardMap {
+    size_t g_zeta_off, wt_bits_off, scratch_scale_off, w_bits_off, alpha_off, g_wt_off, partial_off, total;
+    int64_t chunks, rows_per_chunk;
+};
+
+static size_t align256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
+
+static BackwardMap map_backward(int64_t n, int64_t d_in, int64_t d_out)
+{
+    BackwardMap m;
+    // enough workgroups to fill the chip a few times; whole staging steps per chunk
+    const int64_t blocks_per_chunk = ((d_out + 63) / 64) * ((d_in + 255) / 256);
+    int64_t chunks = (1024 + blocks_per_chunk - 1) / blocks_per_chunk;
+    const int64_t max_chunks = (n + kStageRows - 1) / kStageRows;
+    if (chunks > max_chunks) chunks = max_chunks;
+    if (chunks < 1) chunks = 1;
+    int64_t rpc = (n + chunks - 1) / chunks;
+    rpc = (rpc + kStageRows - 1) / kStageRows * kStageRows;
+    m.chunks = (n + rpc - 1) / rpc;
+    if (m.chunks < 1) m.chunks = 1;
+    m.rows_per_chunk = rpc;
+    size_t off = 0;
+    m.g_zeta_off = off;        off = align256(off + static_cast<size_t>(n) * d_out * sizeof(float));
+    m.wt_bits_off = off;       off = align256(off + static_cast<size_t>(d_in) * ((d_out + 63) / 64) * sizeof(uint64_t));
+    m.scratch_scale_off = off; off = align256(off + static_cast<size_t>(d_in) * sizeof(float));
+    m.w_bits_off = off;        off = align256(off + static_cast<size_t>(d_out) * ((d_in + 63) / 64) * sizeof(uint64_t));
+    m.alpha_off = off;         off = align256(off + static_cast<size_t>(d_out) * sizeof(float));
+    m.g_wt_off = off;          off = align256(off + static_cast<size_t>(d_in) * d_out * sizeof(float));
+    m.partial_off = off;       off = align256(off + static_cast<size_t>(m.chunks) * d_in * d_out * sizeof(float));
+    m.total = off;
+    return m;
+}
+
+}  // namespace bigcn
+
+using namespace bigcn;
+
+extern "C" size_t bigcn_layer_backward_workspace_bytes(int64_t n, int64_t d_in, int64_t d_out)
+{
+    if (n <= 0 || d_in <= 0 || d_out <= 0 || d_in > BIGCN_MAX_K_BITS || d_out > BIGCN_MAX_K_BITS) return 0;
+    return map_backward(n, d_in, d_out).total;
+}
+
+extern "C" int bigcn_layer_backward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                                    const float *vals, int64_t n, const float *g_out, int64_t ld_g,
+                                    const uint64_t *f_bits, int64_t ld_f_words, const float *beta,
+                                    const float *w, int64_t ld_w, int64_t d_in, int64_t d_out,
+                                    const float *bn_mul, float *g_w, int64_t ld_gw, float *g_in,
+                                    int64_t ld_gin, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (plan == nullptr || row_ptr == nullptr || col_idx == nullptr || vals == nullptr || g_out == nullptr ||
+        f_bits == nullptr || beta == nullptr || w == nullptr || g_w == nullptr)
+        return BIGCN_ENULL;
+    if (n != plan->n || d_in <= 0 || d_out <= 0 || ld_g < d_out || ld_w < d_out || ld_gw < d_out ||
+        ld_f_words < (d_in + 63) / 64 || (g_in != nullptr && ld_gin < d_in))
+        return BIGCN_EINVAL;
+    if (d_in > BIGCN_MAX_K_BITS || d_out > BIGCN_MAX_K_BITS) return BIGCN_ESHAPE;
+    if (n == 0) return BIGCN_OK;
+    const BackwardMap map = map_backward(n, d_in, d_out);
+    if (workspace == nullptr || workspace_bytes < map.total || reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
+        return BIGCN_EWORKSPACE;
+    hipStream_t s = as_stream(stream);
+    char *ws = static_cast<char *>(workspace);
+    float *g_zeta = reinterpret_cast<float *>(ws + map.g_zeta_off);
+    uint64_t *wt_bits = reinterpret_cast<uint64_t *>(ws + map.wt_bits_off);
+    float *row_scale = reinterpret_cast<float *>(ws + map.scratch_scale_off);
+    uint64_t *w_bits = reinterpret_cast<uint64_t *>(ws + map.w_bits_off);
+    float *alpha = reinterpret_cast<float *>(ws + map.alpha_off);
+    float *g_wt = reinterpret_cast<float *>(ws + map.g_wt_off);
+    float *partial = reinterpret_cast<float *>(ws + map.partial_off);
+    const int64_t wt_ld = (d_out + 63) / 64, wb_ld = (d_in + 63) / 64;
+
+    // weights packed both ways: along j for the input gradient (row t of W), and the column
+    // scales alpha_j from the transposed view (Sec. 4.2.1)
+    int rc = launch_pack(w, d_in, d_out, ld_w, 1, nullptr, nullptr, nullptr, 0, wt_bits, wt_ld, row_scale, s);
+    if (rc != BIGCN_OK) return rc;
+    rc = launch_pack(w, d_out, d_in, 1, ld_w, nullptr, nullptr, nullptr, 0, w_bits, wb_ld, alpha, s);
+    if (rc != BIGCN_OK) return rc;
+
+    // Algorithm 1, first line: A~ is symmetric (the plan's pattern check guarantees the pattern,
+    // the coefficients D^-1/2 (A+I) D^-1/2 are symmetric by construction), so A~^T g = A~ g
+    rc = bigcn_spmm(plan, row_ptr, col_idx, vals, n, g_out, d_out, ld_g, g_zeta, d_out, stream);
+    if (rc != BIGCN_OK) return rc;
+
+    const dim3 grid_w(static_cast<unsigned>(map.chunks), static_cast<unsigned>((d_out + 63) / 64),
+                      static_cast<unsigned>((d_in + 255) / 256));
+    hipLaunchKernelGGL(backward_weight_partial_kernel, grid_w, dim3(kBlock), 0, s, g_zeta, n, static_cast<int>(d_out),
+                       d_out, beta, f_bits, ld_f_words, static_cast<int>(d_in), map.rows_per_chunk, partial);
+    if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
+    const int64_t elems = d_in * d_out;
+    hipLaunchKernelGGL(backward_weight_reduce_kernel, dim3(static_cast<unsigned>((elems + kBlock - 1) / kBlock)),
+                       dim3(kBlock), 0, s, partial, map.chunks, elems, g_wt);
+    if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
+    hipLaunchKernelGGL(backward_weight_finish_kernel, dim3(static_cast<unsigned>(d_out)), dim3(kWave), 0, s, g_wt, w,
+                       ld_w, alpha, static_cast<int>(d_in), static_cast<int>(d_out), g_w, ld_gw);
+    if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
+
+    if (g_in != nullptr) {
+        const dim3 grid_i(static_cast<unsigned>((n + 127) / 128), static_cast<unsigned>((d_in + 127) / 128));
+        hipLaunchKernelGGL(backward_input_kernel, grid_i, dim3(kBlock), 0, s, g_zeta, n, static_cast<int>(d_out),
+                           d_out, alpha, wt_bits, wt_ld, static_cast<int>(d_in), bn_mul, g_in, ld_gin);
+        if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
+    }
+    return BIGCN_OK;
+}

@@ -180,6 +180,41 @@ def steps_around(B, m, reps=5):
     return out
 
 
+def backward_leg(B, m, cfg, reps=3):
+    """Back propagation through each layer of the workload (Sec. 4.3, Algorithm 1), timed on its
+    own with seeded stand-ins for the layer inputs and the upstream gradient (not part of a
+    step).  FLOP rate counts the two dense products (2 * 2 n d_in d_out)."""
+    import torch
+    n = m["x"].shape[0]
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    _, vals = B.bigcn_gcn_norm(m["row_ptr"], m["col_idx"], want_vals=True)
+    out = []
+    for l in range(cfg.n_layers):
+        d_in, d_out = cfg.dims[l], cfg.dims[l + 1]
+        x = m["x"] if l == 0 else torch.randn((n, d_in), dtype=torch.float32, device="cuda", generator=gen)
+        bits, beta = B.bigcn_pack(x)
+        w = torch.empty((d_in, d_out), dtype=torch.float32, device="cuda").uniform_(-1.5, 1.5, generator=gen)
+        g = torch.randn((n, d_out), dtype=torch.float32, device="cuda", generator=gen) * 0.1
+        need = int(B.lib().bigcn_layer_backward_workspace_bytes(n, d_in, d_out))
+        ws = torch.empty((need,), dtype=torch.uint8, device="cuda")
+        call = lambda: B.bigcn_layer_backward(m["plan"], m["row_ptr"], m["col_idx"], vals, g, bits, beta, w,
+                                              want_input_grad=l > 0, workspace=ws)
+        call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        products = 1 if l == 0 else 2
+        out.append({"layer": l, "d_in": d_in, "d_out": d_out, "ms": ms,
+                    "dense_TFLOPs": products * 2.0 * n * d_in * d_out / (ms * 1e-3) / 1e12})
+        del x, bits, beta, w, g, ws
+    return out
+
+
 def cpu_baseline(work, target_nodes):
     """The plain oracle, as it stands, timed on the host cores: on the benchmark's own workload,
     or on a smaller graph of the same recipe (same mean degree, dims, feature law); nodes/s."""
@@ -212,6 +247,8 @@ def main():
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one device-to-device copy kernel of this many MiB (a known "
                          "traffic figure to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings by)")
+    ap.add_argument("--no-backward", action="store_true",
+                    help="skip the back-propagation leg (one bigcn_layer_backward per layer, timed alone)")
     ap.add_argument("--no-gemm-sweep", action="store_true",
                     help="skip the compute-bound bit-GEMM leg (both evaluation paths, M=262144, n=256, K=4096)")
     args = ap.parse_args()
@@ -309,6 +346,8 @@ def main():
                          if k.endswith("ratio")},
     }
     result["steps_around"] = steps_around(B, m)
+    if not args.no_backward and cfg.model == "gcn":
+        result["backward"] = backward_leg(B, m, cfg)
     if not args.no_gemm_sweep:
         result["bit_gemm_sweep"] = gemm_sweep(B)
         best = max(result["bit_gemm_sweep"], key=lambda r: r["binary_op_per_s"])

@@ -72,6 +72,9 @@ struct RowLayout {
     int fold_last;   // 1: bit K-1 is excluded from the stored value (kI8 with K = 256, or K = 128
                      //    when the scale sits in the top bits)
     int embed_scale; // ScalePlace
+    int escape;      // 1 (kScaleInTopBits, K' > 127): a row whose values do not all fit 7 bits carries
+                     //    a NaN scale; its one-byte values live in an alternate row array and its
+                     //    scale in the per-node array
     __host__ __device__ int positions() const { return groups * vec; }
     __host__ __device__ int elem_bytes() const { return kind == kI8 ? 1 : (kind == kF16 ? 2 : 4); }
     __host__ __device__ int64_t row_bytes() const { return static_cast<int64_t>(positions()) * elem_bytes(); }
@@ -98,9 +101,10 @@ int launch_source_scale(const float *beta, const float *row_mul, const uint64_t 
 
 // bit-GEMM writing the integer products in a RowLayout (fused forward).
 // src_scale (m floats) is copied into the rows when the layout embeds the scale.
+// alt_rows (escape layouts only): receives the one-byte form of the rows that do not fit 7 bits.
 int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits,
                           int64_t n, int64_t ldb, int64_t k_bits, const float *src_scale, void *c_rows,
-                          RowLayout layout, hipStream_t stream);
+                          void *alt_rows, RowLayout layout, hipStream_t stream);
 
 // Matrix-core (int8 MFMA) variant of the public bit-GEMM: same arguments and results.
 int launch_bitgemm_mfma(const uint64_t *a_bits, const float *a_scale, int64_t m, int64_t lda,
@@ -137,6 +141,8 @@ struct FusedSpmmArgs {
     const float *next_row_mul;  // n, nullable (= 1)
     int next_fold_last_sign;    // the next layer's layout has fold_last: sign the stored scale
     // own-row term, all nullptr when absent
+    const void *alt_rows;       // escape layouts: one-byte form of the rows that did not fit 7 bits
+    const void *alt_self_rows;  //   (same for the own-row array)
     const void *self_rows;      // n rows in `layout`: products with the second weight matrix
     const float *self_alpha;    // d_out
     const uint64_t *self_w_bits;// packed second weight matrix (for its last-bit term), stride w_ld_words

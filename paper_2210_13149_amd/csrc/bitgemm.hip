@@ -54,6 +54,8 @@ struct EpilogueApi {
     }
     // per-row value needed by store(): fetched when the row block starts, not when it ends
     __device__ __forceinline__ float row_value(int64_t row) const { return out != nullptr ? a_scale[row] : 0.0f; }
+    // start value of the bit counters (store() receives counters that include it)
+    __device__ __forceinline__ int pop_init() const { return 0; }
     template <int VB>
     __device__ __forceinline__ void store(const Lane<VB> &ctx, int64_t row, float sa, const int (&col)[VB],
                                           int /*pos0*/, bool /*any*/, int n, const int (&pop)[VB]) const
@@ -79,6 +81,8 @@ struct EpilogueLayout {
     int k_eff;
     const float *embed;      // non-null (int8 rows only): scale[row] is stored inside the row,
     int top_bits_shift;      //   0: in its last 4 bytes; s > 0: bit i in the top bit of position i << s, i < 32
+    T *alt_rows;             // escape layouts: rows with a value outside [-64, 63] are written here in
+                             // one-byte form and get a NaN scale in the main array; else nullptr
     template <int VB>
     struct Lane {
         int top_bit;         // which bit of the scale this lane's first value carries, or -1
@@ -92,22 +96,39 @@ struct EpilogueLayout {
         c.top_bit = (top_bits_shift > 0 && embed != nullptr && (i << top_bits_shift) == pos0 && i < 32) ? i : -1;
     }
     __device__ __forceinline__ float row_value(int64_t row) const { return embed != nullptr ? embed[row] : 0.0f; }
+    // Escape layouts count from 63 - floor(K'/2): the stored value floor(K'/2) - popcount is then
+    // 63 - counter and fits 7 bits exactly when the counter lies in [0, 127], i.e. has no bit above
+    // bit 6, so one OR over a lane's counters and one test decide it.
+    __device__ __forceinline__ int pop_init() const { return alt_rows != nullptr ? 63 - (k_eff >> 1) : 0; }
     template <int VB>
     __device__ __forceinline__ void store(const Lane<VB> &ctx, int64_t row, float row_scale, const int (&col)[VB],
                                           int pos0, bool any, int n, const int (&pop)[VB]) const
     {
         if (!any) return;
         alignas(16) T tmp[VB];
+        const int bias = pop_init();
+        const int half_k = (k_eff >> 1) + bias;             // value = half_k - (counter incl. bias)
+        uint32_t spread = 0;                                 // OR of the live shifted counters
 #pragma unroll
         for (int v = 0; v < VB; ++v) {
-            int value;
-            if constexpr (sizeof(T) == 1) value = (k_eff >> 1) - pop[v];
-            else value = k_eff - 2 * pop[v];
             const bool live = col[v] >= 0 && col[v] < n;
-            if constexpr (sizeof(T) == 1) tmp[v] = static_cast<T>(live ? value : 0);
-            else tmp[v] = static_cast<T>(live ? static_cast<float>(value) : 0.0f);
+            if constexpr (sizeof(T) == 1) {
+                tmp[v] = static_cast<T>(live ? half_k - pop[v] : 0);
+                spread |= live ? static_cast<uint32_t>(pop[v]) : 0u;
+            } else {
+                const int value = k_eff - 2 * pop[v];
+                tmp[v] = static_cast<T>(live ? static_cast<float>(value) : 0.0f);
+            }
         }
         if constexpr (sizeof(T) == 1) {
+            if (alt_rows != nullptr) {
+                // one wavefront holds the whole row: if any value needs the eighth bit the row goes
+                // to the alternate array as it is and the main array gets a NaN scale
+                if (__ballot((spread & ~127u) != 0u) != 0ull) {
+                    write_values<VB>(alt_rows + row * positions + pos0, tmp);
+                    row_scale = __uint_as_float(0x7fc00000u);
+                }
+            }
             if (embed != nullptr && top_bits_shift == 0) {
                 const uint32_t bits = __float_as_uint(row_scale);
 #pragma unroll
@@ -120,7 +141,11 @@ struct EpilogueLayout {
                 tmp[0] = static_cast<T>((static_cast<uint32_t>(tmp[0]) & 0x7fu) | (bit << 7));
             }
         }
-        T *p = rows + row * positions + pos0;
+        write_values<VB>(rows + row * positions + pos0, tmp);
+    }
+    template <int VB>
+    static __device__ __forceinline__ void write_values(T *p, const T (&tmp)[VB])
+    {
         constexpr int kBytes = sizeof(T) * VB;
         if constexpr (kBytes == 16) *reinterpret_cast<uint4 *>(p) = *reinterpret_cast<const uint4 *>(tmp);
         else if constexpr (kBytes == 8) *reinterpret_cast<uint2 *>(p) = *reinterpret_cast<const uint2 *>(tmp);
@@ -184,7 +209,7 @@ __global__ __launch_bounds__(kBlock) void bitgemm_kernel(
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int v = 0; v < VB; ++v) pop[r][v] = 0;
+            for (int v = 0; v < VB; ++v) pop[r][v] = epi.pop_init();
 
         const uint32_t *arow[R];
         float row_value[R];
@@ -292,25 +317,27 @@ static int dispatch_bitgemm(int per_lane, int groups, int vec, const uint64_t *a
 
 int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits,
                           int64_t n, int64_t ldb, int64_t k_bits, const float *src_scale, void *c_rows,
-                          RowLayout layout, hipStream_t stream)
+                          void *alt_rows, RowLayout layout, hipStream_t stream)
 {
     if (m == 0 || n == 0) return BIGCN_OK;
+    if (layout.escape && alt_rows == nullptr) return BIGCN_ENULL;
     // a stored row is spread over all 64 lanes: each lane produces positions/64 consecutive values
     const int per_lane = layout.positions() >= 64 ? layout.positions() / 64 : 1;
     const uint32_t last_mask = layout.fold_last ? 0x7fffffffu : 0xffffffffu;
     if (layout.kind == kI8) {
         EpilogueLayout<int8_t> epi{static_cast<int8_t *>(c_rows), layout.positions(), layout.k_eff,
                                    layout.embed_scale != kScaleSeparate ? src_scale : nullptr,
-                                   layout.embed_scale == kScaleInTopBits ? (layout.vec == 8 ? 3 : 2) : 0};
+                                   layout.embed_scale == kScaleInTopBits ? (layout.vec == 8 ? 3 : 2) : 0,
+                                   layout.escape ? static_cast<int8_t *>(alt_rows) : nullptr};
         return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
                                 last_mask, epi, stream);
     }
     if (layout.kind == kF16) {
-        EpilogueLayout<__half> epi{static_cast<__half *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0};
+        EpilogueLayout<__half> epi{static_cast<__half *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, nullptr};
         return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
                                 last_mask, epi, stream);
     }
-    EpilogueLayout<float> epi{static_cast<float *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0};
+    EpilogueLayout<float> epi{static_cast<float *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, nullptr};
     return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
                             last_mask, epi, stream);
 }

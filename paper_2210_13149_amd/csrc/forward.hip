@@ -15,7 +15,8 @@
 namespace bigcn {
 
 struct WorkspaceMap {
-    size_t bits_off, scale0_off, scale1_off, rows_off, self_rows_off, total;
+    size_t bits_off, scale0_off, scale1_off, rows_off, self_rows_off, alt_rows_off, alt_self_rows_off, total;
+    bool escape;      // some layer keeps an alternate one-byte copy of rows that do not fit 7 bits
 };
 
 static size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
@@ -70,12 +71,15 @@ static int view_sage(const bigcn_sage_layer *layers, int n_layers, LayerView *ou
 
 static WorkspaceMap map_workspace(int64_t n, const LayerView *layers, int n_layers, bool own_term)
 {
-    int64_t max_words = 0, max_row_bytes = 0;
+    int64_t max_words = 0, max_row_bytes = 0, max_alt_bytes = 0;
     for (int l = 0; l < n_layers; ++l) {
+        const RowLayout layout = choose_layout(layers[l].d_in, layers[l].d_out);
         max_words = std::max<int64_t>(max_words, (layers[l].d_in + 63) / 64);
-        max_row_bytes = std::max<int64_t>(max_row_bytes, choose_layout(layers[l].d_in, layers[l].d_out).row_bytes());
+        max_row_bytes = std::max<int64_t>(max_row_bytes, layout.row_bytes());
+        if (layout.escape) max_alt_bytes = std::max<int64_t>(max_alt_bytes, layout.row_bytes());
     }
     WorkspaceMap m;
+    m.escape = max_alt_bytes > 0;
     size_t off = 0;
     m.bits_off = off;   off = align_up(off + static_cast<size_t>(n) * max_words * sizeof(uint64_t));
     m.scale0_off = off; off = align_up(off + static_cast<size_t>(n) * sizeof(float));
@@ -83,6 +87,10 @@ static WorkspaceMap map_workspace(int64_t n, const LayerView *layers, int n_laye
     m.rows_off = off;   off = align_up(off + static_cast<size_t>(n) * max_row_bytes);
     m.self_rows_off = off;
     if (own_term) off = align_up(off + static_cast<size_t>(n) * max_row_bytes);
+    m.alt_rows_off = off;
+    if (m.escape) off = align_up(off + static_cast<size_t>(n) * max_alt_bytes);
+    m.alt_self_rows_off = off;
+    if (m.escape && own_term) off = align_up(off + static_cast<size_t>(n) * max_alt_bytes);
     m.total = off;
     return m;
 }
@@ -188,6 +196,8 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
     float *scale[2] = {reinterpret_cast<float *>(ws + map.scale0_off), reinterpret_cast<float *>(ws + map.scale1_off)};
     void *c_rows = ws + map.rows_off;
     void *self_rows = own_term ? ws + map.self_rows_off : nullptr;
+    void *alt_rows = map.escape ? ws + map.alt_rows_off : nullptr;
+    void *alt_self_rows = (map.escape && own_term) ? ws + map.alt_self_rows_off : nullptr;
 
     // layer 0 input: binarise X (or take it binarised); the stored scale is src_row_mul[i] * beta_i
     int64_t words = (layers[0].d_in + 63) / 64;
@@ -210,11 +220,11 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
         const LayerView &L = layers[l];
         const RowLayout layout = choose_layout(L.d_in, L.d_out);
         rc = launch_bitgemm_layout(in_bits, n, words, L.w_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1], c_rows,
-                                   layout, s);
+                                   alt_rows, layout, s);
         if (rc != BIGCN_OK) return rc;
         if (own_term) {
             rc = launch_bitgemm_layout(in_bits, n, words, L.w_self_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1],
-                                       self_rows, layout, s);
+                                       self_rows, alt_self_rows, layout, s);
             if (rc != BIGCN_OK) return rc;
         }
         BIGCN_MARK();
@@ -226,6 +236,8 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
         a.dst_mul = dst_mul;
         a.src_scale = scale[l & 1];
         a.c_rows = c_rows;
+        a.alt_rows = alt_rows;
+        a.alt_self_rows = alt_self_rows;
         a.layout = layout;
         a.alpha = L.alpha;
         a.d_out = L.d_out;

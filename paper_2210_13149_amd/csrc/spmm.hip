@@ -22,9 +22,15 @@ namespace bigcn {
 // Where the per-neighbour weight comes from: all ones, a per-entry array, a per-node array
 // gathered through the column index, the last four bytes of the gathered row itself, or the top
 // bits of the first byte of each lane's segment of the gathered row (7-bit products).
-enum WeightMode { kWeightOne = 0, kWeightVals = 1, kWeightGather = 2, kWeightEmbedded = 3, kWeightTopBits = 4 };
+// kWeightTopBitsEscape: as kWeightTopBits for layers whose products usually, but not provably,
+// fit 7 bits: a row that does not is stored with a NaN scale, and its true values (one byte each)
+// and scale are fetched from an alternate row array and the per-node scale array.
+enum WeightMode {
+    kWeightOne = 0, kWeightVals = 1, kWeightGather = 2, kWeightEmbedded = 3, kWeightTopBits = 4,
+    kWeightTopBitsEscape = 5
+};
 __host__ __device__ constexpr bool fused_weights(int wm) { return wm >= kWeightGather; }
-__host__ __device__ constexpr bool row_weights(int wm) { return wm == kWeightEmbedded || wm == kWeightTopBits; }
+__host__ __device__ constexpr bool row_weights(int wm) { return wm >= kWeightEmbedded; }
 
 // ---- one stored row segment: V values of T per lane, loaded as one vector ------------------
 template <typename T, int V>
@@ -127,7 +133,7 @@ __device__ __forceinline__ float row_weight(Segment<T, V> &seg, int lane, bool l
 {
     if constexpr (sizeof(T) == 1 && WM == kWeightEmbedded) {
         return __uint_as_float(static_cast<uint32_t>(__shfl(static_cast<int>(seg.tail()), lane | (G - 1), kWave)));
-    } else if constexpr (sizeof(T) == 1 && WM == kWeightTopBits) {
+    } else if constexpr (sizeof(T) == 1 && (WM == kWeightTopBits || WM == kWeightTopBitsEscape)) {
         const uint64_t bits = __ballot(loaded && (seg.head() & 0x80u) != 0);
         seg.restore_head_sign();
         const uint32_t mine = (G == kWave || lane < 32) ? static_cast<uint32_t>(bits) : static_cast<uint32_t>(bits >> 32);
@@ -160,6 +166,27 @@ __device__ __forceinline__ const char *row_address(const char *lane_base, int k,
     return lane_base + static_cast<uint64_t>(static_cast<uint32_t>(k)) * row_bytes;
 }
 
+// The weight a loaded row carries; with kWeightTopBitsEscape also the rare replacement of a row
+// that did not fit 7 bits (NaN scale) by its one-byte form and its gathered scale.  Executed by
+// all lanes; `loaded` says whether this lane's segment was fetched.
+template <typename T, int G, int V, int WM>
+__device__ __forceinline__ float resolve_row(Segment<T, V> &seg, int lane, bool loaded, int k,
+                                             const char *__restrict__ alt_lane_base, uint32_t row_bytes,
+                                             const float *__restrict__ weights)
+{
+    float w = row_weight<T, G, V, WM>(seg, lane, loaded);
+    if constexpr (WM == kWeightTopBitsEscape) {
+        const bool escaped = loaded && !(fabsf(w) <= 3.0e38f);      // NaN (or Inf) marks the row
+        if (__ballot(escaped) != 0ull) {
+            if (escaped) {
+                seg.load(row_address(alt_lane_base, k, row_bytes));
+                w = weights[k];
+            }
+        }
+    }
+    return w;
+}
+
 // ---- accumulate the neighbours p0..p1-1 of one node (per lane: V positions) ---------------
 // active: this lane's positions exist in the stored row (lanes past the row width never load);
 // kAllActive: known at compile time to hold for every lane (stored rows of the fused path),
@@ -168,7 +195,8 @@ __device__ __forceinline__ const char *row_address(const char *lane_base, int k,
 template <typename T, int G, int V, int WM, bool kAllActive>
 __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col_idx,
                                                  const float *__restrict__ weights,
-                                                 const char *__restrict__ lane_base, uint32_t row_bytes,
+                                                 const char *__restrict__ lane_base,
+                                                 const char *__restrict__ alt_lane_base, uint32_t row_bytes,
                                                  int64_t p0, int64_t p1, int lane, bool active_in,
                                                  RowAcc<V> &acc)
 {
@@ -192,21 +220,22 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
         for (; t + S * U <= cnt; t += S * U) {
             Segment<T, V> seg[U];
             float w[U];
+            int kk[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                int kk;
                 if (S == 1) {
-                    kk = __builtin_amdgcn_readlane(k, t + u);
+                    kk[u] = __builtin_amdgcn_readlane(k, t + u);
                     w[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wk), t + u));
                 } else {
-                    kk = __shfl(k, t + u * S + slot, kWave);
+                    kk[u] = __shfl(k, t + u * S + slot, kWave);
                     w[u] = __shfl(wk, t + u * S + slot, kWave);
                 }
-                if (active) seg[u].load(row_address(lane_base, kk, row_bytes));
+                if (active) seg[u].load(row_address(lane_base, kk[u], row_bytes));
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (row_weights(WM)) w[u] = row_weight<T, G, V, WM>(seg[u], lane, active);
+                if (row_weights(WM))
+                    w[u] = resolve_row<T, G, V, WM>(seg[u], lane, active, kk[u], alt_lane_base, row_bytes, weights);
                 if (fused_weights(WM)) {
                     acc.sum_abs += fabsf(w[u]);
                     acc.sum_signed += w[u];
@@ -221,20 +250,23 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
         if (t < cnt) {
             Segment<T, V> seg[U];
             float w[U];
+            int kk[U];
             bool present[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int src = t + u * S + slot;
                 present[u] = src < cnt;
                 const int from = present[u] ? src : 0;
-                const int kk = __shfl(k, from, kWave);
+                kk[u] = __shfl(k, from, kWave);
                 w[u] = __shfl(wk, from, kWave);
-                if (active && present[u]) seg[u].load(row_address(lane_base, kk, row_bytes));
+                if (active && present[u]) seg[u].load(row_address(lane_base, kk[u], row_bytes));
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 // the broadcast is executed by all lanes; slots without a neighbour discard it
-                if (row_weights(WM)) w[u] = row_weight<T, G, V, WM>(seg[u], lane, active && present[u]);
+                if (row_weights(WM))
+                    w[u] = resolve_row<T, G, V, WM>(seg[u], lane, active && present[u], kk[u], alt_lane_base,
+                                                    row_bytes, weights);
                 if (present[u]) {
                     if (fused_weights(WM)) {
                         acc.sum_abs += fabsf(w[u]);
@@ -252,7 +284,8 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
 // The node's own stored row (second product array of a layer with an own-row term), weighted by
 // the node's own scale exactly as a neighbour's row would be: pos = |t| * stored, sums of t.
 template <typename T, int G, int V, int WM>
-__device__ __forceinline__ void load_own_row(const char *__restrict__ own_lane_base, uint32_t row_bytes,
+__device__ __forceinline__ void load_own_row(const char *__restrict__ own_lane_base,
+                                             const char *__restrict__ own_alt_lane_base, uint32_t row_bytes,
                                              const float *__restrict__ weights, int64_t row, int lane,
                                              bool active, RowAcc<V> &own)
 {
@@ -260,7 +293,8 @@ __device__ __forceinline__ void load_own_row(const char *__restrict__ own_lane_b
     Segment<T, V> seg;
     if (active) seg.load(row_address(own_lane_base, static_cast<int>(row), row_bytes));
     float t;
-    if (row_weights(WM)) t = row_weight<T, G, V, WM>(seg, lane, active);
+    if (row_weights(WM))
+        t = resolve_row<T, G, V, WM>(seg, lane, active, static_cast<int>(row), own_alt_lane_base, row_bytes, weights);
     else t = weights[row];
     own.sum_abs = fabsf(t);
     own.sum_signed = t;
@@ -343,6 +377,7 @@ struct EpilogueFusedT {
     int next_fold_last_sign;
     // own-row term (kSelfTerm only): rows in the same layout, their column scales and last bits
     const char *self_rows;
+    const char *alt_self_rows;       // one-byte form of own rows that did not fit 7 bits (escape layouts)
     const float *self_alpha;
     const uint64_t *self_last_bit_word;
 
@@ -480,8 +515,8 @@ template <typename T, int G, int V, int WM, class Epilogue>
 __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, V, Epilogue>())) void spmm_kernel(
     const int32_t *__restrict__ row_order, int64_t n, int64_t n_block_rows,
     const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
-    const float *__restrict__ weights, const char *__restrict__ rows, uint32_t row_bytes,
-    int valid_positions, Epilogue epi)
+    const float *__restrict__ weights, const char *__restrict__ rows, const char *__restrict__ alt_rows,
+    uint32_t row_bytes, int valid_positions, Epilogue epi)
 {
     constexpr bool kAllActive = fused_weights(WM);     // stored rows of the fused path fill G * V positions
     __shared__ float partial[kWavesPerBlock - 1][V + 2][kWave];
@@ -502,8 +537,15 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, V, Epilogue>())) void sp
     }
     RowAcc<V> acc;
     RowAcc<V> own;      // only filled (and only read) by epilogues with an own-row term
+    // alternate (one-byte) rows of nodes whose products did not fit 7 bits; only dereferenced by
+    // kWeightTopBitsEscape
+    const char *alt_lane_base = alt_rows + static_cast<int64_t>(g) * V * sizeof(T);
     const char *own_lane_base = nullptr;
-    if constexpr (Epilogue::kSelf) own_lane_base = epi.self_rows + static_cast<int64_t>(g) * V * sizeof(T);
+    const char *own_alt_lane_base = nullptr;
+    if constexpr (Epilogue::kSelf) {
+        own_lane_base = epi.self_rows + static_cast<int64_t>(g) * V * sizeof(T);
+        own_alt_lane_base = epi.alt_self_rows + static_cast<int64_t>(g) * V * sizeof(T);
+    }
 
     if (static_cast<int64_t>(blockIdx.x) < n_block_rows) {
         // one long row shared by the four wavefronts: contiguous quarters, multiples of 64
@@ -516,7 +558,8 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, V, Epilogue>())) void sp
         if (q0 > p1) q0 = p1;
         if (q1 > p1) q1 = p1;
         acc.clear();
-        accumulate_range<T, G, V, WM, kAllActive>(col_idx, weights, lane_base, row_bytes, q0, q1, lane, active, acc);
+        accumulate_range<T, G, V, WM, kAllActive>(col_idx, weights, lane_base, alt_lane_base, row_bytes, q0, q1, lane,
+                                                  active, acc);
         reduce_slots<G, V, WM>(acc);
         if (wave > 0) {
 #pragma unroll
@@ -534,7 +577,7 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, V, Epilogue>())) void sp
                 acc.sum_signed += partial[w][V + 1][lane];
             }
             if constexpr (Epilogue::kSelf)
-                load_own_row<T, G, V, WM>(own_lane_base, row_bytes, weights, row, lane, active, own);
+                load_own_row<T, G, V, WM>(own_lane_base, own_alt_lane_base, row_bytes, weights, row, lane, active, own);
             LaneConsts ctx;
             Parked::fetch(ctx, parked, lane);
             epi.template finish<G, V>(ctx, row, lane, acc, own);
@@ -550,8 +593,9 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, V, Epilogue>())) void sp
         const int64_t p0 = row_ptr[row], p1 = row_ptr[row + 1];
         acc.clear();
         if constexpr (Epilogue::kSelf)
-            load_own_row<T, G, V, WM>(own_lane_base, row_bytes, weights, row, lane, active, own);
-        accumulate_range<T, G, V, WM, kAllActive>(col_idx, weights, lane_base, row_bytes, p0, p1, lane, active, acc);
+            load_own_row<T, G, V, WM>(own_lane_base, own_alt_lane_base, row_bytes, weights, row, lane, active, own);
+        accumulate_range<T, G, V, WM, kAllActive>(col_idx, weights, lane_base, alt_lane_base, row_bytes, p0, p1, lane,
+                                                  active, acc);
         reduce_slots<G, V, WM>(acc);
         LaneConsts ctx;
         Parked::fetch(ctx, parked, lane);
@@ -562,9 +606,11 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, V, Epilogue>())) void sp
 template <typename T, int G, int V, int WM, class Epilogue>
 static int launch_spmm_one(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
                            const float *weights, const void *rows, int64_t row_bytes,
-                           int valid_positions, const Epilogue &epi, hipStream_t stream)
+                           int valid_positions, const Epilogue &epi, hipStream_t stream,
+                           const void *alt_rows)
 {
     if (row_bytes <= 0 || row_bytes > 0x7fffffff) return BIGCN_EINVAL;
+    if (WM == kWeightTopBitsEscape && (alt_rows == nullptr || weights == nullptr)) return BIGCN_ENULL;
     if (fused_weights(WM) && valid_positions != G * V) return BIGCN_EINVAL;
     const int64_t wave_rows = plan->n - plan->n_block_rows;
     const int64_t per_block = kWavesPerBlock * kRowsPerWave;
@@ -572,8 +618,8 @@ static int launch_spmm_one(const bigcn_plan *plan, const int64_t *row_ptr, const
     if (blocks == 0) return BIGCN_OK;
     hipLaunchKernelGGL((spmm_kernel<T, G, V, WM, Epilogue>), dim3(static_cast<unsigned>(blocks)),
                        dim3(kBlock), 0, stream, plan->row_order, plan->n, plan->n_block_rows, row_ptr,
-                       col_idx, weights, static_cast<const char *>(rows), static_cast<uint32_t>(row_bytes),
-                       valid_positions, epi);
+                       col_idx, weights, static_cast<const char *>(rows), static_cast<const char *>(alt_rows),
+                       static_cast<uint32_t>(row_bytes), valid_positions, epi);
     return check_launch();
 }
 
@@ -581,12 +627,12 @@ template <typename T, int V, int WM, class Epilogue>
 static int launch_spmm_groups(int groups, const bigcn_plan *plan, const int64_t *row_ptr,
                               const int32_t *col_idx, const float *weights, const void *rows,
                               int64_t row_bytes, int valid_positions, const Epilogue &epi,
-                              hipStream_t stream)
+                              hipStream_t stream, const void *alt_rows = nullptr)
 {
 #define BIGCN_SPMM_CASE(GG)                                                                          \
     case GG:                                                                                         \
         return launch_spmm_one<T, GG, V, WM>(plan, row_ptr, col_idx, weights, rows, row_bytes,      \
-                                             valid_positions, epi, stream)
+                                             valid_positions, epi, stream, alt_rows)
     switch (groups) {
         BIGCN_SPMM_CASE(2);
         BIGCN_SPMM_CASE(4);
@@ -622,7 +668,8 @@ RowLayout choose_layout(int64_t d_in, int64_t d_out)
         l.k_eff = static_cast<int>(d_in);
     }
     l.groups = groups_for(d_out, l.vec);
-    l.embed_scale = 0;
+    l.embed_scale = kScaleSeparate;
+    l.escape = 0;
     if (l.kind == kI8) {
         // The last four stored values belong to the last lane of the group and hold columns
         // (G-1) + G*(V-4 .. V-1); when those lie past d_out the bytes are free for the scale.
@@ -639,6 +686,14 @@ RowLayout choose_layout(int64_t d_in, int64_t d_out)
                 l.k_eff = 127;
             }
             l.embed_scale = kScaleInTopBits;
+        } else if (l.embed_scale == kScaleSeparate && l.groups >= 32) {
+            // 129..256 input bits: a product needs 8 bits in the worst case, but a row of them
+            // almost never does (the stored value has standard deviation sqrt(K)/2 <= 8 for
+            // uncorrelated signs; 7 bits hold +-8 sigma).  Rows are written in the 7-bit form
+            // when every value fits; a row that does not fit is marked by a NaN scale and kept in
+            // one-byte form in an alternate array.  Exact either way.
+            l.embed_scale = kScaleInTopBits;
+            l.escape = 1;
         }
     }
     return l;
@@ -667,6 +722,7 @@ static int launch_fused_spmm_t(const FusedSpmmArgs &a, hipStream_t stream)
     epi.next_row_mul = a.next_row_mul;
     epi.next_fold_last_sign = a.next_fold_last_sign;
     epi.self_rows = static_cast<const char *>(a.self_rows);
+    epi.alt_self_rows = static_cast<const char *>(a.alt_self_rows);
     epi.self_alpha = a.self_alpha;
     epi.self_last_bit_word = (l.fold_last && a.self_w_bits != nullptr) ? a.self_w_bits + (a.d_in - 1) / 64 : nullptr;
     const int valid = l.positions();
@@ -677,6 +733,13 @@ static int launch_fused_spmm_t(const FusedSpmmArgs &a, hipStream_t stream)
 #define BIGCN_FUSED_EMBEDDED(TT, VV)                                                                    \
     return launch_spmm_groups<TT, VV, kWeightEmbedded>(l.groups, a.plan, a.row_ptr, a.col_idx, nullptr, \
                                                        a.c_rows, rb, valid, epi, stream)
+    if (l.kind == kI8 && l.embed_scale == kScaleInTopBits && l.escape) {
+        if (l.groups < 32) return BIGCN_EINVAL;
+        if (kSelfTerm && a.alt_self_rows == nullptr) return BIGCN_ENULL;
+        return launch_spmm_groups<int8_t, 8, kWeightTopBitsEscape>(l.groups, a.plan, a.row_ptr, a.col_idx,
+                                                                   a.src_scale, a.c_rows, rb, valid, epi, stream,
+                                                                   a.alt_rows);
+    }
     if (l.kind == kI8 && l.embed_scale == kScaleInTopBits) {
         if (l.groups < 32) return BIGCN_EINVAL;
         return launch_spmm_groups<int8_t, 8, kWeightTopBits>(l.groups, a.plan, a.row_ptr, a.col_idx, nullptr,

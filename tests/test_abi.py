@@ -125,9 +125,12 @@ def test_forward_workspace_size_and_argument_checks():
     n = 1000
     layers = _layers((100, 256, 256, 47))
     need = L.bigcn_forward_workspace_bytes(n, layers, 3)
-    # packed signs (4 words), two scale vectors, and 256 one-byte products per node (K <= 256)
-    assert need >= n * (4 * 8 + 2 * 4 + 256)
-    assert need <= n * (4 * 8 + 2 * 4 + 256) + 4 * 256
+    # packed signs (4 words), two scale vectors, 256 one-byte products per node (K <= 256) and the
+    # alternate one-byte array of the K = 256 layer (rows that do not fit the 7-bit form)
+    assert need >= n * (4 * 8 + 2 * 4 + 2 * 256)
+    assert need <= n * (4 * 8 + 2 * 4 + 2 * 256) + 5 * 256
+    small = L.bigcn_forward_workspace_bytes(n, _layers((100, 256, 47)), 2)
+    assert small <= n * (4 * 8 + 2 * 4 + 256) + 4 * 256   # K = 100 -> 256 provably fits: no alternate array
     mid = L.bigcn_forward_workspace_bytes(n, _layers((602, 128, 41)), 2)
     assert mid >= n * (10 * 8 + 8 + 128 * 2)          # 256 < K <= 2048: products kept in fp16
     wide = L.bigcn_forward_workspace_bytes(n, _layers((3703, 64, 6)), 2)

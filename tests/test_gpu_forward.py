@@ -118,13 +118,14 @@ def test_forward_layer_chain_equals_separate_kernels(B):
     assert_close(h1, rec["out"], "H1 through separate kernels")
 
 
-@pytest.mark.parametrize("d_in", [64, 100, 127, 128, 129, 254, 255, 256, 257, 2048, 2049])
+@pytest.mark.parametrize("d_in", [64, 100, 127, 128, 129, 200, 254, 255, 256, 257, 2048, 2049])
 def test_forward_extreme_products(B, d_in):
     """Nodes whose sign pattern equals, or is the exact opposite of, a weight column give the
     extreme products +K and -K: the ends of the range of every compact product-row format
-    (seven bits per product up to K = 128 with the scale in the spare top bits, one byte up to
-    K = 256, with the last input bit carried separately at K = 128 and K = 256; fp16 up to
-    K = 2048; fp32 beyond)."""
+    (seven bits per product up to K = 128 with the scale in the spare top bits; up to K = 256 the
+    same form for rows that fit it and one byte per product in the alternate array for rows that
+    do not, which these inputs produce in numbers; the last input bit carried separately at
+    K = 128 and K = 256; fp16 up to K = 2048; fp32 beyond)."""
     from workloads import chung_lu_csr
     from workloads.build import Workload
     from workloads.configs import WorkloadConfig

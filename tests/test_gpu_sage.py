@@ -129,6 +129,28 @@ def test_sage_forward_formats_and_edge_cases(B, dims, n, n_edges, i0):
         assert stats[-1]["rows_compared"] >= 0.5 * n
 
 
+@pytest.mark.parametrize("d_in", [129, 200, 256])
+def test_sage_rows_that_do_not_fit_seven_bits(B, d_in):
+    """Nodes whose signs equal (or oppose) a column of W_theta or of W_n give products of +-K:
+    their product rows, own and neighbour, take the one-byte escape path of layers with
+    129..256 input bits."""
+    n, d_hidden, d_out = 600, 256, 6
+    rng = np.random.default_rng(1000 + d_in)
+    work = small_sage_workload(n, 4000, (d_in, d_hidden, d_out), seed=900 + d_in)
+    w_self, w_nbr = work.weights[0]
+    for k in range(0, 200):
+        src = w_self if k % 4 < 2 else w_nbr
+        col = src[:, (11 * k) % d_hidden]
+        work.x[k] = col if k % 2 == 0 else -col
+    sign, _ = oracle.binarize_rows(work.x)
+    bt, _ = oracle.binarize_weight(w_nbr)
+    acc = oracle.sign_matmul(sign, bt)
+    assert acc.max() == d_in and acc.min() == -d_in
+    for bn in ([None, None], ["calibrate", "calibrate"]):
+        stats = compare_forward_layerwise(work, bn, sage_prefix_runner(B, work), cancellation_aware=True)
+        assert stats[0]["rows_compared"] == n and stats[-1]["rows_compared"] >= 0.5 * n
+
+
 def test_sage_isolated_node_output_is_its_own_term_and_runs_are_identical(B):
     import torch
     work = small_sage_workload(2000, 1200, (96, 128, 10), seed=77)

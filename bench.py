@@ -247,6 +247,9 @@ def main():
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one device-to-device copy kernel of this many MiB (a known "
                          "traffic figure to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings by)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one forward in a HIP graph and time replays (launch-bound small "
+                         "workloads; per-kernel figures then come from a separate profiled pass)")
     ap.add_argument("--no-backward", action="store_true",
                     help="skip the back-propagation leg (one bigcn_layer_backward per layer, timed alone)")
     ap.add_argument("--no-gemm-sweep", action="store_true",
@@ -289,11 +292,31 @@ def main():
         step()
     torch.cuda.synchronize()
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    start.record()
-    for _ in range(steps):
-        step(profile)
-    stop.record()
-    torch.cuda.synchronize()
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        start.record()
+        for _ in range(steps):
+            graph.replay()
+        stop.record()
+        torch.cuda.synchronize()
+        for _ in range(steps):
+            step(profile)                     # per-kernel figures: eager, event-bracketed
+        torch.cuda.synchronize()
+    else:
+        start.record()
+        for _ in range(steps):
+            step(profile)
+        stop.record()
+        torch.cuda.synchronize()
     ms_per_step = start.elapsed_time(stop) / steps
     launch_ms, calls = profile.read()
     assert calls == steps
@@ -329,6 +352,7 @@ def main():
         "value": nodes_per_s, "unit": "nodes/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u64 xor/popcount + f32", "data": "synthetic",
+        "launch": "hip graph replay" if args.graph else "eager",
         "config": {"workload": f"{cfg.name}: {cfg.stands_in_for}-shaped Chung-Lu graph, {work.n} nodes, "
                                f"{cfg.n_edges} undirected edges "
                                + ("(+ self-loops), Bi-GCN, dims " if cfg.model == "gcn" else

@@ -148,3 +148,40 @@ def test_forward_extreme_products(B, d_in):
     assert recs[0]["acc"].max() == d_in and recs[0]["acc"].min() == -d_in
     stats = compare_forward_layerwise(work, bn, gpu_prefix_runner(B, work), cancellation_aware=True)
     assert stats[-1]["rows_compared"] >= 0.5 * n
+
+
+@pytest.mark.parametrize("name", ["c1", "c3"])
+def test_forward_captured_in_a_hip_graph_replays_identically(B, name):
+    """The fused forward allocates nothing, clears no memory and only launches kernels on the
+    caller's stream, so it can be captured once and replayed: every replay, with eager work and
+    synchronisation between replays and with new feature values in the same buffers, must equal
+    the eager result bit for bit."""
+    import torch
+    work = make_workload(name)
+    bn = calibrated_bn(work)
+    drp, dci, dx = to_device(work.row_ptr, work.col_idx, work.x)
+    model = B.BiGCN(drp, dci, [to_device(w) for w in work.weights],
+                    [None if p is None else tuple(to_device(*p)) for p in bn])
+    eager = model.forward(dx).clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        model.forward(dx)                         # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        model.forward(dx)
+    for rep in range(4):
+        model.logits.fill_(float("nan"))          # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(model.logits, eager), f"replay {rep} differs from the eager forward"
+    # new inputs in the captured buffers
+    dx.mul_(-0.5).add_(0.01)
+    want = None
+    graph.replay()
+    torch.cuda.synchronize()
+    got = model.logits.clone()
+    want = model.forward(dx).clone()
+    assert torch.equal(got, want)

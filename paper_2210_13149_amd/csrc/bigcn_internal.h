@@ -49,9 +49,9 @@ __device__ __forceinline__ float wave_sum(float v)
 // Storage kinds (all exact):
 //   kI8  (K <= 256): q = floor(K'/2) - popcount over the first K' bits, so that the product
 //         over those bits is 2q + (K' mod 2).  K' = K, except K = 256 (and K = 128 with the scale
-//         in the top bits) where K' = K - 1 and the last bit's contribution  f_{k,255} * b_{255,j}  is carried separately: the sign
-//         f_{k,255} rides on the sign of the node's stored scale, b_{255,j} is a per-column
-//         constant.  q always fits int8: [-128, 127].
+//         in the top bits) where K' = K - 1 and the contribution of the last bit,
+//         f_{k,K-1} * b_{K-1,j}, is carried separately: the sign f_{k,K-1} rides on the sign of the
+//         node's stored scale, b_{K-1,j} is a per-column constant.  q always fits int8.
 //   kF16 (K <= 2048): the product itself; every integer of magnitude <= 2048 is exact in fp16.
 //   kF32 : the product as fp32.
 enum RowKind { kI8 = 0, kF16 = 1, kF32 = 2 };
@@ -60,8 +60,9 @@ enum RowKind { kI8 = 0, kF16 = 1, kF32 = 2 };
 // that no second cache line is gathered per neighbour):
 //   kScaleSeparate   an array of n floats, gathered through the column index;
 //   kScaleInTail     the last 4 bytes of the stored row (rows with at least 4 spare positions);
-//   kScaleInTopBits  K' <= 127, so a stored value needs 7 bits: bit i of the scale is the top bit
-//                    of the first byte of lane i's segment, i < 32 (rows of 32 or 64 lanes).
+//   kScaleInTopBits  the stored values use 7 bits (always true for K' <= 127; checked per row
+//                    otherwise, see `escape`): bit i of the scale is the top bit of the first
+//                    byte of lane i's segment, i < 32 (rows of 32 or 64 lanes).
 enum ScalePlace { kScaleSeparate = 0, kScaleInTail = 1, kScaleInTopBits = 2 };
 
 struct RowLayout {

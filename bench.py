@@ -158,7 +158,8 @@ def gemm_sweep(B, m=262144, n=256, k=4096, reps=10):
 
 def steps_around(B, m, reps=5):
     """The steps on either side of the path, timed on their own (not part of a step): column
-    statistics of X and the prediction from the logits; GB/s of the bytes each must read / write."""
+    statistics of X, the prediction from the logits and the binning entropy estimate (run on X: two
+    passes over the matrix); GB/s of the bytes each must read / write."""
     import torch
     x, logits = m["x"], m["logits"]
     out = {}
@@ -166,7 +167,8 @@ def steps_around(B, m, reps=5):
             ("column_stats", lambda: B.bigcn_column_stats(x), x.numel() * 4),
             ("predict_labels", lambda: B.bigcn_predict(logits), logits.numel() * 4 + logits.shape[0] * 4),
             ("predict_softmax", lambda: B.bigcn_predict(logits, want_probs=True),
-             logits.numel() * 8 + logits.shape[0] * 4)):
+             logits.numel() * 8 + logits.shape[0] * 4),
+            ("entropy_1000_bins_of_x", lambda: B.bigcn_entropy(x, 1000), 2 * x.numel() * 4)):
         call()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

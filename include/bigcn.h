@@ -299,6 +299,27 @@ int bigcn_layer_backward(const bigcn_plan *plan, const int64_t *row_ptr, const i
                          int64_t ld_gin, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Entropy estimate of a hidden layer by binning (Sec. 6.2), used by the paper to choose the width
+ * of a binarised layer: neuron c (a column of h, one row per node) is discretised into `bins`
+ * equal-width intervals over its own [min, max],
+ *
+ *   per_neuron[c] = - sum_m p_m log2 p_m,  p_m = count_m / rows;     *total = sum_c per_neuron[c]
+ *
+ * The bin of a value is decided in fp32 as min(bins - 1, floor((x - lo) * (bins / (hi - lo)))),
+ * each operation rounded; a constant neuron falls into bin 0.  Counting is exact.
+ *   h DEVICE fp32 (rows x cols, row stride ld); per_neuron DEVICE out, cols doubles, nullable;
+ *   total DEVICE out, one double; counts DEVICE out, cols * bins uint32 (row c = neuron c),
+ *   nullable; workspace DEVICE, at least bigcn_entropy_workspace_bytes(cols, bins) bytes,
+ *   256-byte aligned.
+ * Errors: ENULL, EINVAL (rows <= 0, cols <= 0, ld < cols, bins < 1), ESHAPE (bins > 1024,
+ * cols > BIGCN_MAX_K_BITS, rows >= 2^32), EWORKSPACE.  The size query returns 0 for invalid arguments.
+ */
+size_t bigcn_entropy_workspace_bytes(int64_t cols, int bins);
+int bigcn_entropy(const float *h, int64_t rows, int64_t cols, int64_t ld, int bins,
+                  double *per_neuron, double *total, uint32_t *counts, void *workspace,
+                  size_t workspace_bytes, void *stream);
+
+/*
  * Bi-GraphSAGE with the mean aggregator (Sec. 4.4.2, the binarised layer):
  *
  *   h_i^(l+1) = W~_theta (*) h~_i  +  (1/|N_i|) sum_{j in N_i} W~_n (*) h~_j

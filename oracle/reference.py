@@ -268,6 +268,38 @@ def predict(h: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     return labels, e / e.sum(axis=1, keepdims=True)
 
 
+def binned_entropy(h: np.ndarray, bins: int) -> Tuple[np.ndarray, float, np.ndarray]:
+    """Entropy estimate of a hidden layer by binning (Sec. 6.2): each neuron (column of ``h``,
+    one row per input sample) is discretised into ``bins`` intervals, its empirical distribution
+    ``p_m = count_m / N`` gives ``H^(h_i) = - sum_m p_m log2 p_m``, and the layer's estimate is the
+    sum over its neurons (the independence estimate of that section).  Returns
+    ``(per-neuron entropies fp64, their sum, counts int64 (neurons, bins))``.
+
+    The intervals are equal-width over each neuron's own [min, max]; the bin of a value is decided
+    in fp32, the precision of the activations: ``m = min(bins - 1, floor((x - lo) * (bins / (hi - lo))))``
+    with every operation rounded to fp32; a constant neuron falls into bin 0.  Entropies are in
+    bits."""
+    h = np.ascontiguousarray(h, dtype=np.float32)
+    if h.ndim != 2 or h.shape[0] == 0 or bins < 1:
+        raise ValueError("expected a non-empty matrix and at least one bin")
+    n, d = h.shape
+    lo = h.min(axis=0)
+    hi = h.max(axis=0)
+    width = (hi - lo).astype(np.float32)
+    with np.errstate(divide="ignore"):
+        scale = np.where(width > 0, np.float32(bins) / width, np.float32(0)).astype(np.float32)
+    idx = np.floor(((h - lo[None, :]).astype(np.float32) * scale[None, :]).astype(np.float32))
+    idx = np.minimum(idx, bins - 1).astype(np.int64)
+    counts = np.zeros((d, bins), dtype=np.int64)
+    for c in range(d):
+        counts[c] = np.bincount(idx[:, c], minlength=bins)
+    p = counts.astype(np.float64) / n
+    with np.errstate(divide="ignore", invalid="ignore"):
+        terms = np.where(p > 0, -p * np.log2(p), 0.0)
+    per = terms.sum(axis=1)
+    return per, float(per.sum()), counts
+
+
 # ---- back propagation through one binarised layer (Sec. 4.3, Algorithm 1) -----------------------
 
 def aggregate_transposed(row_ptr, col_idx, a_tilde: np.ndarray, g: np.ndarray) -> np.ndarray:

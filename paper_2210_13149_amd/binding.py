@@ -38,7 +38,7 @@ EXPORTS = (
     "bigcn_mean_norm", "bigcn_sage_forward_workspace_bytes", "bigcn_sage_forward",
     "bigcn_sage_forward_profiled", "bigcn_forward_packed", "bigcn_column_stats_workspace_bytes",
     "bigcn_column_stats", "bigcn_predict", "bigcn_layer_backward_workspace_bytes",
-    "bigcn_layer_backward",
+    "bigcn_layer_backward", "bigcn_entropy_workspace_bytes", "bigcn_entropy",
 )
 
 
@@ -132,6 +132,10 @@ def lib() -> ctypes.CDLL:
         L.bigcn_layer_backward.restype = i32
         L.bigcn_layer_backward.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, i64, vp, vp, i64, i64, i64, vp,
                                            vp, i64, vp, i64, vp, ctypes.c_size_t, vp]
+        L.bigcn_entropy_workspace_bytes.restype = ctypes.c_size_t
+        L.bigcn_entropy_workspace_bytes.argtypes = [i64, i32]
+        L.bigcn_entropy.restype = i32
+        L.bigcn_entropy.argtypes = [vp, i64, i64, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.bigcn_mean_norm.restype = i32
         L.bigcn_mean_norm.argtypes = [vp, i64, vp, vp]
         L.bigcn_sage_forward_workspace_bytes.restype = ctypes.c_size_t
@@ -485,6 +489,24 @@ def bigcn_layer_backward(plan: Plan, row_ptr: torch.Tensor, col_idx: torch.Tenso
                                       _ptr(g_in), d_in, _ptr(workspace), workspace.numel(), _stream()),
            "bigcn_layer_backward")
     return g_w, g_in
+
+
+def bigcn_entropy(h: torch.Tensor, bins: int, want_counts: bool = False
+                  ) -> Tuple[torch.Tensor, torch.Tensor, Optional[torch.Tensor]]:
+    """Binning estimate of the entropy of a hidden layer: ``(per-neuron entropies in bits (fp64),
+    their sum (fp64 scalar tensor), counts (cols, bins) int32 or None)``."""
+    _dev(h, torch.float32, "h")
+    if h.dim() != 2 or (h.shape[1] > 1 and h.stride(1) != 1):
+        raise ValueError("h must be a row-major matrix")
+    rows, cols = h.shape
+    need = int(lib().bigcn_entropy_workspace_bytes(cols, int(bins)))
+    workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=h.device)
+    per = torch.empty((cols,), dtype=torch.float64, device=h.device)
+    total = torch.empty((1,), dtype=torch.float64, device=h.device)
+    counts = torch.empty((cols, int(bins)), dtype=torch.int32, device=h.device) if want_counts else None
+    _check(lib().bigcn_entropy(_ptr(h), rows, cols, h.stride(0), int(bins), _ptr(per), _ptr(total), _ptr(counts),
+                               _ptr(workspace), workspace.numel(), _stream()), "bigcn_entropy")
+    return per, total[0], counts
 
 
 class BiGCN:

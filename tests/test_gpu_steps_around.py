@@ -168,3 +168,49 @@ def test_predict_on_forward_output_with_padded_rows(B):
     assert_close(probs.cpu().numpy(), want_probs, "softmax of logits")
     assert B.lib().bigcn_predict(wide.data_ptr(), 4, 3, 2, labels.data_ptr(), None, 0, None) == B.BIGCN_EINVAL
     assert B.lib().bigcn_predict(wide.data_ptr(), 4, 3, 8, None, None, 0, None) == B.BIGCN_ENULL
+
+
+# ---- entropy of a hidden layer by binning -------------------------------------------------------
+@pytest.mark.parametrize("rows,cols,bins", [(1, 3, 4), (100, 1, 1), (5000, 9, 200), (40000, 64, 1000),
+                                            (12345, 130, 37), (3000, 512, 1024)])
+def test_entropy_matches_oracle(B, rows, cols, bins):
+    rng = np.random.default_rng(rows + 3 * cols + bins)
+    h = (rng.standard_normal((rows, cols)) * rng.uniform(0.1, 5.0, size=(1, cols))
+         + rng.uniform(-3, 3, size=(1, cols))).astype(np.float32)
+    if cols > 2:
+        h[:, 1] = -0.75                                           # constant neuron: one bin, entropy 0
+        h[:, 2] = np.where(np.arange(rows) % 2 == 0, 1.0, 2.0)    # two values: one bit (even rows)
+    per, total, counts = B.bigcn_entropy(to_device(h), bins, want_counts=True)
+    want_per, want_total, want_counts = oracle.binned_entropy(h, bins)
+    assert np.array_equal(counts.cpu().numpy().astype(np.int64), want_counts)      # integer work: exact
+    assert np.allclose(per.cpu().numpy(), want_per, rtol=1e-12, atol=1e-14)
+    assert float(total) == pytest.approx(want_total, rel=1e-12, abs=1e-14)
+    per2, total2, none = B.bigcn_entropy(to_device(h), bins)
+    assert none is None and float(total2) == float(total)
+
+
+def test_entropy_of_a_hidden_layer_at_full_width(B):
+    """The estimate on a hidden activation of the largest workload's shape (one million rows of
+    256 neurons, M = 1000 as in the paper's table), on a strided view."""
+    import torch
+    gen = torch.Generator(device="cuda").manual_seed(9)
+    wide = torch.randn((1_000_000, 260), dtype=torch.float32, device="cuda", generator=gen)
+    view = wide[:, 2:258]
+    per, total, counts = B.bigcn_entropy(view, 1000, want_counts=True)
+    want_per, want_total, want_counts = oracle.binned_entropy(view.cpu().numpy(), 1000)
+    assert np.array_equal(counts.cpu().numpy().astype(np.int64), want_counts)
+    assert float(total) == pytest.approx(want_total, rel=1e-12)
+    assert 256 * 7.0 < float(total) < 256 * np.log2(1000)
+
+
+def test_entropy_errors(B):
+    import torch
+    h = torch.zeros((8, 4), dtype=torch.float32, device="cuda")
+    out = torch.zeros((4,), dtype=torch.float64, device="cuda")
+    ws = torch.zeros((1 << 16,), dtype=torch.uint8, device="cuda")
+    L, p = B.lib(), lambda t: t.data_ptr()
+    assert L.bigcn_entropy(p(h), 8, 4, 4, 0, p(out), p(out), None, p(ws), ws.numel(), None) == B.BIGCN_EINVAL
+    assert L.bigcn_entropy(p(h), 8, 4, 4, 2000, p(out), p(out), None, p(ws), ws.numel(), None) == B.BIGCN_ESHAPE
+    assert L.bigcn_entropy(p(h), 8, 4, 4, 16, p(out), None, None, p(ws), ws.numel(), None) == B.BIGCN_ENULL
+    assert L.bigcn_entropy(p(h), 8, 4, 4, 16, p(out), p(out), None, p(ws), 16, None) == B.BIGCN_EWORKSPACE
+    assert L.bigcn_entropy_workspace_bytes(4, 0) == 0 and L.bigcn_entropy_workspace_bytes(4, 16) > 0

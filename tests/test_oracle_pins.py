@@ -335,3 +335,38 @@ def test_predict_matches_library_softmax_and_is_shift_invariant():
     # large logits do not overflow
     _, big = oracle.predict(np.array([[1e4, 1e4 - 1.0]], dtype=np.float32))
     assert np.allclose(big[0], [1 / (1 + np.exp(-1.0)), 1 / (1 + np.exp(1.0))], rtol=1e-12)
+
+
+# ----------------------------------------------------------------------------------------
+# entropy of a hidden layer by binning (Sec. 6.2)
+# ----------------------------------------------------------------------------------------
+def test_binned_entropy_closed_forms():
+    n, bins = 4096, 16
+    uniform = (np.arange(n) % bins).astype(np.float32)               # every bin equally often
+    two = np.where(np.arange(n) % 2 == 0, -3.0, 5.0).astype(np.float32)
+    const = np.full(n, 2.5, dtype=np.float32)
+    skew = np.where(np.arange(n) % 4 == 0, 1.0, 0.0).astype(np.float32)   # p = 1/4, 3/4
+    h = np.stack([uniform, two, const, skew], axis=1)
+    per, total, counts = oracle.binned_entropy(h, bins)
+    want = [4.0, 1.0, 0.0, 2.0 - 0.75 * np.log2(3.0)]
+    assert np.allclose(per, want, rtol=1e-12, atol=1e-15)
+    assert total == pytest.approx(sum(want), rel=1e-12)
+    assert counts.sum(axis=1).tolist() == [n] * 4
+    assert counts[2, 0] == n and counts[1, 0] == n // 2 and counts[1, bins - 1] == n // 2
+
+
+def test_binned_entropy_matches_library_histogram_and_entropy():
+    from scipy.stats import entropy
+    x = RNG.standard_normal((5000, 3)).astype(np.float32) * np.array([1.0, 7.0, 0.01], dtype=np.float32)
+    bins = 50
+    per, total, counts = oracle.binned_entropy(x, bins)
+    for c in range(3):
+        col = x[:, c].astype(np.float64)
+        ref_counts, _ = np.histogram(col, bins=bins, range=(col.min(), col.max()))
+        # fp32 and fp64 bin edges may disagree on a value that sits on an edge: at most a handful
+        assert np.abs(ref_counts - counts[c]).sum() <= 6
+        assert per[c] == pytest.approx(entropy(counts[c], base=2), rel=1e-12)
+    assert total == pytest.approx(per.sum(), rel=1e-15)
+    # more samples of the same law, finer bins: entropy grows by about log2 of the refinement
+    per2, _, _ = oracle.binned_entropy(x, 2 * bins)
+    assert np.all(per2 > per) and np.all(per2 < per + 1.0 + 1e-9)

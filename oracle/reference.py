@@ -412,3 +412,47 @@ def sage_forward(row_ptr, col_idx, x: np.ndarray, weights: Sequence[Tuple[np.nda
         h = sage_layer(row_ptr, col_idx, coeff, h, weights[l][0], weights[l][1], shift, mul)["out"]
         used.append(params)
     return h, used
+
+
+# ---- Bi-GAT (Sec. 4.4.1) ------------------------------------------------------------------------
+
+def gat_layer(row_ptr, col_idx, h: np.ndarray, w: np.ndarray, a_src: np.ndarray, a_dst: np.ndarray,
+              heads: int = 1, negative_slope: float = 0.2, shift=None, mul=None) -> Dict[str, np.ndarray]:
+    """One Bi-GAT layer (Sec. 4.4.1): with z_j = W~ (*) h~_j (the binarised product of Sec. 4.2,
+    ``heads`` blocks of d_out / heads columns, one weight block and one attention vector per
+    head),
+
+        e_ij  = LeakyReLU(a_src . z_i + a_dst . z_j)        (a^T (z_i || z_j), a not binarised)
+        a_ij  = softmax over j in N_i of e_ij               (row i of the CSR lists N_i)
+        out_i = sum_{j in N_i} a_ij z_j                     (no further non-linearity)
+
+    per head, the heads' outputs side by side.  ``a_src``, ``a_dst``: (heads, d_out / heads).
+    fp64 throughout; a node with an empty row gives zeros.  Returns every intermediate."""
+    row_ptr, col_idx, n = _check_csr(row_ptr, col_idx)
+    sign, beta = binarize_rows(h, shift, mul)
+    bt, alpha = binarize_weight(w)
+    zeta = rescale(sign_matmul(sign, bt), beta, alpha)               # (n, d_out)
+    d_out = zeta.shape[1]
+    if d_out % heads:
+        raise ValueError("d_out must be a multiple of heads")
+    dh = d_out // heads
+    a_src = np.asarray(a_src, dtype=np.float64).reshape(heads, dh)
+    a_dst = np.asarray(a_dst, dtype=np.float64).reshape(heads, dh)
+    z3 = zeta.reshape(n, heads, dh)
+    s = (z3 * a_src[None]).sum(axis=2)                               # (n, heads)
+    t = (z3 * a_dst[None]).sum(axis=2)
+    out = np.zeros((n, heads, dh), dtype=np.float64)
+    att = np.zeros((col_idx.size, heads), dtype=np.float64)
+    for i in range(n):
+        p0, p1 = int(row_ptr[i]), int(row_ptr[i + 1])
+        if p0 == p1:
+            continue
+        nb = col_idx[p0:p1]
+        e = s[i][None, :] + t[nb]                                    # (deg, heads)
+        e = np.where(e > 0, e, negative_slope * e)
+        e = np.exp(e - e.max(axis=0, keepdims=True))
+        a = e / e.sum(axis=0, keepdims=True)
+        att[p0:p1] = a
+        out[i] = np.einsum("kh,khd->hd", a, z3[nb])
+    return {"sign": sign, "beta": beta, "alpha": alpha, "zeta": zeta, "s": s, "t": t, "att": att,
+            "out": out.reshape(n, d_out)}

@@ -217,6 +217,32 @@ def backward_leg(B, m, cfg, reps=3):
     return out
 
 
+def gat_leg(B, m, cfg, reps=3):
+    """One Bi-GAT layer (Sec. 4.4.1) on the workload's graph and features, timed alone: first-layer
+    shape of the paper's OGBN-Products GAT (two heads of 128 columns) scaled to the workload's
+    input width."""
+    import torch
+    d_in, d_out, heads = cfg.dims[0], 256, 2
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    w = torch.empty((d_in, d_out), dtype=torch.float32, device="cuda").uniform_(-1, 1, generator=gen)
+    layer = B.Layer.from_weight(w)
+    a_src = torch.randn((heads, d_out // heads), dtype=torch.float32, device="cuda", generator=gen) * 0.1
+    a_dst = torch.randn((heads, d_out // heads), dtype=torch.float32, device="cuda", generator=gen) * 0.1
+    call = lambda: B.bigcn_gat_layer(m["plan"], m["row_ptr"], m["col_idx"], m["x"], layer, a_src, a_dst, heads=heads)
+    call()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    nnz = int(m["col_idx"].numel())
+    return {"d_in": d_in, "d_out": d_out, "heads": heads, "ms": ms,
+            "row_gather_GBps": nnz * (4 * d_out + 4 + 2 * 4 * heads) / (ms * 1e-3) / 1e9}
+
+
 def cpu_baseline(work, target_nodes):
     """The plain oracle, as it stands, timed on the host cores: on the benchmark's own workload,
     or on a smaller graph of the same recipe (same mean degree, dims, feature law); nodes/s."""
@@ -374,6 +400,7 @@ def main():
     result["steps_around"] = steps_around(B, m)
     if not args.no_backward and cfg.model == "gcn":
         result["backward"] = backward_leg(B, m, cfg)
+        result["gat_layer"] = gat_leg(B, m, cfg)
     if not args.no_gemm_sweep:
         result["bit_gemm_sweep"] = gemm_sweep(B)
         best = max(result["bit_gemm_sweep"], key=lambda r: r["binary_op_per_s"])

@@ -299,6 +299,34 @@ int bigcn_layer_backward(const bigcn_plan *plan, const int64_t *row_ptr, const i
                          int64_t ld_gin, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * One Bi-GAT layer (Sec. 4.4.1): z_j = W~ (*) h~_j (binarise+pack of x with the optional
+ * standardisation, then the binary product of Sec. 4.2.3) and, for each of `heads` blocks of
+ * d_out / heads columns,
+ *
+ *   e_ij = LeakyReLU(a_src . z_i + a_dst . z_j)     (a^T (z_i || z_j); a is not binarised)
+ *   a_ij = softmax over j in N_i of e_ij            (row i of the CSR lists N_i as given)
+ *   out_i = sum_{j in N_i} a_ij z_j                 (no further non-linearity)
+ *
+ *   plan, row_ptr, col_idx : the graph (any validated pattern)                       (DEVICE)
+ *   x : n rows of d_in fp32, row stride ld_x; bn_shift / bn_mul: d_in, nullable       (DEVICE)
+ *   w_bits, alpha, ld_words : packed weights as in bigcn_layer (d_out rows)           (DEVICE)
+ *   a_src, a_dst : d_out floats each, head-major (head h owns entries h*d_out/heads ..) (DEVICE)
+ *   out : n rows of d_out fp32, row stride ld_out; a node with an empty row gets zeros (DEVICE)
+ *   workspace : at least bigcn_gat_layer_workspace_bytes(...) bytes, 256-byte aligned
+ * Sums are taken in a fixed order: results are run-to-run identical.
+ * Errors: ENULL, EINVAL (sizes, strides, d_out not a multiple of heads), ESHAPE (heads not in
+ * {1, 2, 4, 8}, d_out > 512, d_in > BIGCN_MAX_K_BITS), EWORKSPACE.  The size query returns 0
+ * for invalid arguments.
+ */
+size_t bigcn_gat_layer_workspace_bytes(int64_t n, int64_t d_in, int64_t d_out, int heads);
+int bigcn_gat_layer(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx, int64_t n,
+                    const float *x, int64_t ld_x, const float *bn_shift, const float *bn_mul,
+                    const uint64_t *w_bits, const float *alpha, int64_t ld_words, int64_t d_in,
+                    int64_t d_out, int heads, const float *a_src, const float *a_dst,
+                    float negative_slope, float *out, int64_t ld_out, void *workspace,
+                    size_t workspace_bytes, void *stream);
+
+/*
  * Entropy estimate of a hidden layer by binning (Sec. 6.2), used by the paper to choose the width
  * of a binarised layer: neuron c (a column of h, one row per node) is discretised into `bins`
  * equal-width intervals over its own [min, max],

@@ -39,6 +39,7 @@ EXPORTS = (
     "bigcn_sage_forward_profiled", "bigcn_forward_packed", "bigcn_column_stats_workspace_bytes",
     "bigcn_column_stats", "bigcn_predict", "bigcn_layer_backward_workspace_bytes",
     "bigcn_layer_backward", "bigcn_entropy_workspace_bytes", "bigcn_entropy",
+    "bigcn_gat_layer_workspace_bytes", "bigcn_gat_layer",
 )
 
 
@@ -136,6 +137,11 @@ def lib() -> ctypes.CDLL:
         L.bigcn_entropy_workspace_bytes.argtypes = [i64, i32]
         L.bigcn_entropy.restype = i32
         L.bigcn_entropy.argtypes = [vp, i64, i64, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.bigcn_gat_layer_workspace_bytes.restype = ctypes.c_size_t
+        L.bigcn_gat_layer_workspace_bytes.argtypes = [i64, i64, i64, i32]
+        L.bigcn_gat_layer.restype = i32
+        L.bigcn_gat_layer.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp,
+                                      ctypes.c_float, vp, i64, vp, ctypes.c_size_t, vp]
         L.bigcn_mean_norm.restype = i32
         L.bigcn_mean_norm.argtypes = [vp, i64, vp, vp]
         L.bigcn_sage_forward_workspace_bytes.restype = ctypes.c_size_t
@@ -507,6 +513,30 @@ def bigcn_entropy(h: torch.Tensor, bins: int, want_counts: bool = False
     _check(lib().bigcn_entropy(_ptr(h), rows, cols, h.stride(0), int(bins), _ptr(per), _ptr(total), _ptr(counts),
                                _ptr(workspace), workspace.numel(), _stream()), "bigcn_entropy")
     return per, total[0], counts
+
+
+def bigcn_gat_layer(plan: Plan, row_ptr: torch.Tensor, col_idx: torch.Tensor, x: torch.Tensor,
+                    layer: "Layer", a_src: torch.Tensor, a_dst: torch.Tensor, heads: int = 1,
+                    negative_slope: float = 0.2) -> torch.Tensor:
+    """One Bi-GAT layer: ``layer`` holds the packed weights (and optional standardisation), ``a_src`` /
+    ``a_dst`` the attention vectors, shape (heads, d_out / heads).  Returns fp32 (n, d_out)."""
+    _dev(x, torch.float32, "x")
+    a_src = _dev(a_src, torch.float32, "a_src").contiguous()
+    a_dst = _dev(a_dst, torch.float32, "a_dst").contiguous()
+    if x.dim() != 2 or (x.shape[1] > 1 and x.stride(1) != 1):
+        raise ValueError("x must be a row-major matrix")
+    if a_src.numel() != layer.d_out or a_dst.numel() != layer.d_out:
+        raise ValueError("attention vectors must hold d_out entries each")
+    n = x.shape[0]
+    need = int(lib().bigcn_gat_layer_workspace_bytes(n, layer.d_in, layer.d_out, int(heads)))
+    workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=x.device)
+    out = torch.empty((n, layer.d_out), dtype=torch.float32, device=x.device)
+    _check(lib().bigcn_gat_layer(plan.handle, _ptr(row_ptr), _ptr(col_idx), n, _ptr(x), x.stride(0),
+                                 _ptr(layer.bn_shift), _ptr(layer.bn_mul), _ptr(layer.w_bits), _ptr(layer.alpha),
+                                 layer.w_bits.stride(0), layer.d_in, layer.d_out, int(heads), _ptr(a_src),
+                                 _ptr(a_dst), float(negative_slope), _ptr(out), out.stride(0), _ptr(workspace),
+                                 workspace.numel(), _stream()), "bigcn_gat_layer")
+    return out
 
 
 class BiGCN:

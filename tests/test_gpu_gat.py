@@ -1,0 +1,135 @@
+"""Parity of the Bi-GAT layer (Sec. 4.4.1) against the CPU oracle, through the C ABI.
+
+Tolerance: the standard bar |gpu - ref| <= 1e-5 |ref| + 1e-6, or the rounding bound of the fp32
+evaluation of that element.  With u = 2^-24: a score e_ij is a sum of 2 d_head products, so its
+error is at most eps_e = (2 d_head + 4) u (sum |a_src z_i| + sum |a_dst z_j|); exp turns an
+absolute error of its argument into the same relative error of the weight, the normalisation
+doubles it, and the weighted sum over deg_i neighbours adds (deg_i + 8) u: the output error is at
+most (2 eps_e + (deg_i + 8) u) * sum_j a_ij |z_j|.  An output that cancels to a small fraction of
+its terms cannot be resolved to 1e-5 of itself in fp32."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import assert_close, to_device
+from workloads import chung_lu_csr
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    from paper_2210_13149_amd import binding
+    assert torch.cuda.is_available()
+    binding.lib()
+    return binding
+
+
+def check_against(got, ref, rp, ci, a_src, a_dst, heads):
+    u = 2.0 ** -24
+    n, d_out = ref["out"].shape
+    dh = d_out // heads
+    z3 = np.abs(ref["zeta"]).reshape(n, heads, dh)
+    es = (z3 * np.abs(a_src).reshape(1, heads, dh)).sum(axis=2)          # (n, heads)
+    et = (z3 * np.abs(a_dst).reshape(1, heads, dh)).sum(axis=2)
+    deg = np.diff(rp)
+    bound = np.zeros_like(ref["out"])
+    for h in range(heads):
+        et_max = np.zeros(n)
+        nz = deg > 0
+        et_max[nz] = np.maximum.reduceat(et[ci, h], rp[:-1][nz])
+        eps_e = (2 * dh + 4) * u * (es[:, h] + et_max)
+        mag = oracle.aggregate(rp, ci, ref["att"][:, h].copy(), np.abs(ref["zeta"][:, h * dh:(h + 1) * dh]))
+        bound[:, h * dh:(h + 1) * dh] = (2 * eps_e + (deg + 8) * u)[:, None] * mag
+    diff = np.abs(got - ref["out"])
+    ok = (diff <= 1e-5 * np.abs(ref["out"]) + 1e-6) | (diff <= bound)
+    assert ok.all(), f"{int((~ok).sum())} of {ok.size} elements out of tolerance, worst {diff[~ok].max():.3e}"
+    # the bound is a worst case: nearly every element must meet the standard bar
+    assert (diff <= 1e-5 * np.abs(ref["out"]) + 1e-6).mean() > 0.995
+
+
+def run_gpu(B, rp, ci, x, w, a_src, a_dst, heads, slope, bn=None, self_loops=True):
+    import torch
+    drp, dci, dx, dw = to_device(rp, ci, x, w)
+    plan = B.Plan(drp, dci, validate=B.VALIDATE_GCN if self_loops else B.VALIDATE_NEIGHBOURS)
+    shift, mul = (None, None) if bn is None else to_device(*bn)
+    layer = B.Layer.from_weight(dw, shift, mul)
+    out = B.bigcn_gat_layer(plan, drp, dci, dx, layer, to_device(a_src.astype(np.float32)),
+                            to_device(a_dst.astype(np.float32)), heads=heads, negative_slope=slope)
+    torch.cuda.synchronize()
+    return out
+
+
+@pytest.mark.parametrize("n,n_edges,d_in,d_out,heads,self_loops,with_bn,i0", [
+    (400, 1500, 50, 8, 1, True, False, 2.0),
+    (3000, 40000, 100, 256, 2, True, True, 1.2),       # rows of more than 256 neighbours
+    (2500, 2000, 128, 64, 4, False, True, 2.0),        # neighbour lists with empty rows
+    (1500, 9000, 300, 512, 8, True, False, 2.0),
+    (700, 3000, 70, 47, 1, True, True, 2.0),
+    (1, 0, 5, 4, 2, True, False, 2.0),
+])
+def test_gat_layer_matches_oracle(B, n, n_edges, d_in, d_out, heads, self_loops, with_bn, i0):
+    rng = np.random.default_rng(n + d_in + d_out + heads)
+    if n > 1:
+        rp, ci = chung_lu_csr(n, n_edges, 2.5, i0, seed=n + heads, self_loops=self_loops)
+    else:
+        rp, ci = np.array([0, 1], dtype=np.int64), np.array([0], dtype=np.int32)
+    deg = np.diff(rp)
+    if not self_loops:
+        assert (deg == 0).any()
+    if i0 < 1.5:
+        assert deg.max() >= 256
+    x = rng.standard_normal((n, d_in)).astype(np.float32)
+    w = rng.uniform(-1, 1, size=(d_in, d_out)).astype(np.float32)
+    dh = d_out // heads
+    a_src = (rng.standard_normal((heads, dh)) / np.sqrt(dh)).astype(np.float32)
+    a_dst = (rng.standard_normal((heads, dh)) / np.sqrt(dh)).astype(np.float32)
+    bn = oracle.column_standardisation(x) if with_bn else None
+    shift, mul = bn if bn is not None else (None, None)
+    ref = oracle.gat_layer(rp, ci, x, w, a_src, a_dst, heads=heads, negative_slope=0.2, shift=shift, mul=mul)
+    assert np.abs(ref["att"]).max() <= 1.0 and (ref["att"].max() > 0.5 or n == 1 or deg.max() > 50)
+    got = run_gpu(B, rp, ci, x, w, a_src, a_dst, heads, 0.2, bn, self_loops).cpu().numpy()
+    check_against(got, ref, rp, ci, a_src, a_dst, heads)
+    if not self_loops:
+        assert np.array_equal(got[deg == 0], np.zeros((int((deg == 0).sum()), d_out), dtype=np.float32))
+
+
+def test_gat_with_zero_attention_is_the_mean_aggregator_and_runs_are_identical(B):
+    import torch
+    rng = np.random.default_rng(8)
+    n, d_in, d_out = 1200, 90, 32
+    rp, ci = chung_lu_csr(n, 6000, 2.5, 2.0, seed=8)
+    x = rng.standard_normal((n, d_in)).astype(np.float32)
+    w = rng.uniform(-1, 1, size=(d_in, d_out)).astype(np.float32)
+    zero = np.zeros((2, d_out // 2), dtype=np.float32)
+    got = run_gpu(B, rp, ci, x, w, zero, zero, 2, 0.2)
+    fwd = oracle.layer(rp, ci, oracle.gcn_norm(rp, ci), x, w)
+    want = oracle.aggregate(rp, ci, oracle.mean_norm(rp, ci), fwd["zeta"])
+    rec0 = oracle.gat_layer(rp, ci, x, w, zero, zero, heads=2)
+    assert np.allclose(rec0["out"], want, rtol=1e-13, atol=1e-15)
+    check_against(got.cpu().numpy(), rec0, rp, ci, zero, zero, 2)
+    a = rng.standard_normal((2, d_out // 2)).astype(np.float32)
+    first = run_gpu(B, rp, ci, x, w, a, -a, 2, 0.05)
+    second = run_gpu(B, rp, ci, x, w, a, -a, 2, 0.05)
+    assert torch.equal(first, second)
+
+
+def test_gat_argument_checks(B):
+    import torch
+    rng = np.random.default_rng(1)
+    n, d_in, d_out = 64, 20, 12
+    rp, ci = chung_lu_csr(n, 200, 2.5, 2.0, seed=1)
+    drp, dci, dx, dw = to_device(rp, ci, rng.standard_normal((n, d_in)).astype(np.float32),
+                                 rng.standard_normal((d_in, d_out)).astype(np.float32))
+    plan = B.Plan(drp, dci)
+    layer = B.Layer.from_weight(dw)
+    a = torch.zeros((d_out,), dtype=torch.float32, device="cuda")
+    with pytest.raises(B.BigcnError) as err:
+        B.bigcn_gat_layer(plan, drp, dci, dx, layer, a, a, heads=5)
+    assert err.value.status == B.BIGCN_EINVAL              # 12 columns do not split into 5 heads
+    with pytest.raises(B.BigcnError) as err:
+        B.bigcn_gat_layer(plan, drp, dci, dx, layer, a, a, heads=3)
+    assert err.value.status == B.BIGCN_ESHAPE              # head counts are powers of two up to 8
+    assert B.lib().bigcn_gat_layer_workspace_bytes(n, d_in, 1024, 1) == 0
+    assert B.lib().bigcn_gat_layer_workspace_bytes(n, d_in, d_out, 2) > 0

@@ -96,15 +96,23 @@ struct EpilogueLayout {
         c.top_bit = (top_bits_shift > 0 && embed != nullptr && (i << top_bits_shift) == pos0 && i < 32) ? i : -1;
     }
     __device__ __forceinline__ float row_value(int64_t row) const { return embed != nullptr ? embed[row] : 0.0f; }
-    // Escape layouts count from 63 - floor(K'/2): the stored value floor(K'/2) - popcount is then
-    // 63 - counter and fits 7 bits exactly when the counter lies in [0, 127], i.e. has no bit above
-    // bit 6, so one OR over a lane's counters and one test decide it.
-    __device__ __forceinline__ int pop_init() const { return alt_rows != nullptr ? 63 - (k_eff >> 1) : 0; }
+    // 7-bit layouts (scale in the top bits) count from 63 - floor(K'/2): the stored value
+    // floor(K'/2) - popcount is then 63 - counter.  It fits 7 bits exactly when the counter lies in
+    // [0, 127], i.e. has no bit above bit 6 (one OR over a lane's counters and one test decide it),
+    // and its 7-bit two's-complement code is then simply counter ^ 0x3f, so four counters are
+    // packed into bytes first and complemented, sign-extended and stamped as one word.
+    __device__ __forceinline__ int pop_init() const { return top_bits_shift > 0 ? 63 - (k_eff >> 1) : 0; }
     template <int VB>
     __device__ __forceinline__ void store(const Lane<VB> &ctx, int64_t row, float row_scale, const int (&col)[VB],
                                           int pos0, bool any, int n, const int (&pop)[VB]) const
     {
         if (!any) return;
+        if constexpr (sizeof(T) == 1 && (VB == 4 || VB == 8)) {
+            if (top_bits_shift > 0) {
+                store_seven_bit<VB>(ctx, row, row_scale, col, pos0, n, pop);
+                return;
+            }
+        }
         alignas(16) T tmp[VB];
         const int bias = pop_init();
         const int half_k = (k_eff >> 1) + bias;             // value = half_k - (counter incl. bias)
@@ -142,6 +150,48 @@ struct EpilogueLayout {
             }
         }
         write_values<VB>(rows + row * positions + pos0, tmp);
+    }
+    // Fast form of store() for the 7-bit layouts, VB a multiple of 4 (see pop_init).
+    template <int VB>
+    __device__ __forceinline__ void store_seven_bit(const Lane<VB> &ctx, int64_t row, float row_scale,
+                                                    const int (&col)[VB], int pos0, int n,
+                                                    const int (&pop)[VB]) const
+    {
+        uint32_t c[VB];
+        uint32_t spread = 0;
+#pragma unroll
+        for (int v = 0; v < VB; ++v) {
+            const bool live = col[v] >= 0 && col[v] < n;
+            c[v] = live ? static_cast<uint32_t>(pop[v]) : 63u;       // a dead position stores 0
+            spread |= c[v];
+        }
+        if (alt_rows != nullptr) {
+            // one wavefront holds the whole row: if any value needs the eighth bit the row goes to
+            // the alternate array in one-byte form and the main array gets a NaN scale
+            if (__ballot((spread & ~127u) != 0u) != 0ull) {
+                alignas(16) T tmp[VB];
+#pragma unroll
+                for (int v = 0; v < VB; ++v) tmp[v] = static_cast<T>(63 - static_cast<int>(c[v]));
+                write_values<VB>(alt_rows + row * positions + pos0, tmp);
+                row_scale = __uint_as_float(0x7fc00000u);
+            }
+        }
+        uint32_t words[VB / 4];
+#pragma unroll
+        for (int q = 0; q < VB / 4; ++q) {
+            uint32_t x = (c[4 * q] & 0xffu) | ((c[4 * q + 1] & 0xffu) << 8) | ((c[4 * q + 2] & 0xffu) << 16) |
+                         (c[4 * q + 3] << 24);
+            x ^= 0x3f3f3f3fu;
+            x = (x & 0x7f7f7f7fu) | ((x & 0x40404040u) << 1);          // copy bit 6 into bit 7
+            words[q] = x;
+        }
+        if (ctx.top_bit >= 0) {
+            const uint32_t bit = (__float_as_uint(row_scale) >> ctx.top_bit) & 1u;
+            words[0] = (words[0] & ~0x80u) | (bit << 7);
+        }
+        T *p = rows + row * positions + pos0;
+        if constexpr (VB == 4) *reinterpret_cast<uint32_t *>(p) = words[0];
+        else *reinterpret_cast<uint2 *>(p) = make_uint2(words[0], words[1]);
     }
     template <int VB>
     static __device__ __forceinline__ void write_values(T *p, const T (&tmp)[VB])
@@ -272,6 +322,108 @@ __global__ __launch_bounds__(kBlock) void bitgemm_kernel(
     }
 }
 
+// ---- rows of at most four packed words (K <= 256) ------------------------------------------
+// With so few words per row the scalar loads of A above are a chain of short, dependent fetches
+// and the kernel waits on memory latency.  Here a wavefront fetches the packed words (and the
+// per-row epilogue value) of 64 rows with coalesced vector loads, lane l holding row l, and the
+// next 64 rows are already in flight while the current ones are processed; a row's words reach
+// the scalar registers by lane broadcast.  B lives in registers (VB columns x NW words per lane).
+template <int VB, int NW, class Epilogue>
+__global__ __launch_bounds__(kBlock) void bitgemm_rows_kernel(
+    const uint64_t *__restrict__ a, int64_t m, int64_t lda, const uint64_t *__restrict__ b, int n,
+    int64_t ldb, uint32_t last_mask, ColumnMap map, Epilogue epi)
+{
+    constexpr int R = 4;                          // rows per inner step (share the loop overhead)
+    const int y = blockIdx.y;
+    const int lane = lane_id();
+    int col[VB];
+    bool any = false;
+    uint32_t bw[VB][2 * NW];
+#pragma unroll
+    for (int v = 0; v < VB; ++v) {
+        const int vv = map.per_group * (lane / map.groups) + y * VB + v;
+        col[v] = vv < map.vec ? (lane % map.groups) + map.groups * vv : -1;
+        any = any || vv < map.vec;
+        const bool live = col[v] >= 0 && col[v] < n;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            uint64_t word = live ? b[static_cast<int64_t>(col[v]) * ldb + w] : 0ull;
+            if (w == NW - 1) word &= (static_cast<uint64_t>(last_mask) << 32) | 0xffffffffull;
+            bw[v][2 * w] = static_cast<uint32_t>(word);
+            bw[v][2 * w + 1] = static_cast<uint32_t>(word >> 32);
+        }
+    }
+    const int pos0 = (lane % map.groups) * map.vec + map.per_group * (lane / map.groups) + y * VB;
+    typename Epilogue::template Lane<VB> ctx;
+    epi.template init<VB>(col, pos0, n, ctx);
+
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block();
+    const int64_t n_waves = static_cast<int64_t>(gridDim.x) * kWavesPerBlock;
+
+    // fetch of the 64 rows starting at `base`: lane l reads row base + l (clamped to the last row)
+    uint32_t aw[2 * NW], aw_next[2 * NW];
+    float rv, rv_next;
+    auto fetch = [&](int64_t base, uint32_t (&dst)[2 * NW], float &value) {
+        const int64_t row = base + lane < m ? base + lane : m - 1;
+        const uint2 *src = reinterpret_cast<const uint2 *>(a + row * lda);
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const uint2 word = src[w];
+            dst[2 * w] = word.x;
+            dst[2 * w + 1] = w == NW - 1 ? (word.y & last_mask) : word.y;
+        }
+        value = epi.row_value(row);
+    };
+    int64_t base = wave * kWave;
+    if (base < m) fetch(base, aw, rv);
+    for (; base < m; base += n_waves * kWave) {
+        const int64_t next = base + n_waves * kWave;
+        if (next < m) fetch(next, aw_next, rv_next);          // in flight during this batch
+        const int rows_here = static_cast<int>(m - base < kWave ? m - base : kWave);
+        for (int r0 = 0; r0 < rows_here; r0 += R) {
+            int pop[R][VB];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int v = 0; v < VB; ++v) pop[r][v] = epi.pop_init();
+            float value[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int src = r0 + r < rows_here ? r0 + r : rows_here - 1;
+                value[r] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, rv), src));
+#pragma unroll
+                for (int q = 0; q < 2 * NW; ++q) {
+                    const uint32_t word = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(aw[q]), src));
+#pragma unroll
+                    for (int v = 0; v < VB; ++v) pop[r][v] = __popc(word ^ bw[v][q]) + pop[r][v];
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (r0 + r >= rows_here) break;                 // wave-uniform
+                epi.template store<VB>(ctx, base + r0 + r, value[r], col, pos0, any, n, pop[r]);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 2 * NW; ++q) aw[q] = aw_next[q];
+        rv = rv_next;
+    }
+}
+
+template <int VB, int NW, class Epilogue>
+static int launch_bitgemm_rows(const uint64_t *a, int64_t m, int64_t lda, const uint64_t *b, int64_t n,
+                               int64_t ldb, uint32_t last_mask, ColumnMap map, int col_blocks,
+                               const Epilogue &epi, hipStream_t stream)
+{
+    int64_t blocks = (m + kBlock - 1) / kBlock;               // 64 rows per wavefront and batch
+    const int64_t cap = 256 * 8 / col_blocks > 256 ? 256 * 8 / col_blocks : 256;
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL((bitgemm_rows_kernel<VB, NW, Epilogue>), dim3(static_cast<unsigned>(blocks), col_blocks),
+                       dim3(kBlock), 0, stream, a, m, lda, b, static_cast<int>(n), ldb, last_mask, map, epi);
+    return check_launch();
+}
+
 template <int VB, int R, class Epilogue>
 static int launch_bitgemm(const uint64_t *a, int64_t m, int64_t lda, const uint64_t *b, int64_t n,
                           int64_t ldb, int64_t k_bits, uint32_t last_mask, ColumnMap map,
@@ -309,6 +461,16 @@ static int dispatch_bitgemm(int per_lane, int groups, int vec, const uint64_t *a
     while (vb > 1 && vb * n_words > 128) vb >>= 1;
     const int col_blocks = (per_lane + vb - 1) / vb;
     const ColumnMap map{groups, vec, per_lane};
+    if (n_words <= 4 && vb <= 4) {
+        // K <= 256: batched rows, B in registers
+#define BIGCN_ROWS_CASE(VV, WW)                                                                                \
+    if (vb == VV && n_words == WW)                                                                             \
+        return launch_bitgemm_rows<VV, WW>(a, m, lda, b, n, ldb, last_mask, map, col_blocks, epi, stream)
+        BIGCN_ROWS_CASE(4, 1); BIGCN_ROWS_CASE(4, 2); BIGCN_ROWS_CASE(4, 3); BIGCN_ROWS_CASE(4, 4);
+        BIGCN_ROWS_CASE(2, 1); BIGCN_ROWS_CASE(2, 2); BIGCN_ROWS_CASE(2, 3); BIGCN_ROWS_CASE(2, 4);
+        BIGCN_ROWS_CASE(1, 1); BIGCN_ROWS_CASE(1, 2); BIGCN_ROWS_CASE(1, 3); BIGCN_ROWS_CASE(1, 4);
+#undef BIGCN_ROWS_CASE
+    }
     if (vb == 8) return launch_bitgemm<8, 2>(a, m, lda, b, n, ldb, k_bits, last_mask, map, col_blocks, epi, stream);
     if (vb == 4) return launch_bitgemm<4, 4>(a, m, lda, b, n, ldb, k_bits, last_mask, map, col_blocks, epi, stream);
     if (vb == 2) return launch_bitgemm<2, 4>(a, m, lda, b, n, ldb, k_bits, last_mask, map, col_blocks, epi, stream);

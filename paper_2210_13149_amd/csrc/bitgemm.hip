@@ -80,7 +80,8 @@ struct EpilogueLayout {
     int positions;
     int k_eff;
     const float *embed;      // non-null (int8 rows only): scale[row] is stored inside the row,
-    int top_bits_shift;      //   0: in its last 4 bytes; s > 0: bit i in the top bit of position i << s, i < 32
+    int top_bits_shift;      //   0: in its last 4 bytes; 3: bit i in the top bit of position 8 i (i < 32) and,
+    int top_bits_groups;     //   for rows of 16 lanes, bits 16..31 in the top bit of position 8 (i - 16) + 4
     T *alt_rows;             // escape layouts: rows with a value outside [-64, 63] are written here in
                              // one-byte form and get a NaN scale in the main array; else nullptr
     template <int VB>
@@ -90,10 +91,14 @@ struct EpilogueLayout {
     template <int VB>
     __device__ __forceinline__ void init(const int (&)[VB], int pos0, int, Lane<VB> &c) const
     {
-        // a lane's values are consecutive positions starting at a multiple of VB, so only its
-        // first value can sit on a position i << shift
-        const int i = pos0 >> top_bits_shift;
-        c.top_bit = (top_bits_shift > 0 && embed != nullptr && (i << top_bits_shift) == pos0 && i < 32) ? i : -1;
+        // a lane's values are consecutive positions starting at a multiple of VB, and carriers sit
+        // on multiples of 4 (of 8 when VB = 8), so only a lane's first value can be a carrier
+        c.top_bit = -1;
+        if (top_bits_shift > 0 && embed != nullptr) {
+            const int segment = pos0 >> 3, offset = pos0 & 7;
+            if (offset == 0 && segment < 32) c.top_bit = segment;
+            else if (offset == 4 && top_bits_groups == 16) c.top_bit = 16 + segment;
+        }
     }
     __device__ __forceinline__ float row_value(int64_t row) const { return embed != nullptr ? embed[row] : 0.0f; }
     // 7-bit layouts (scale in the top bits) count from 63 - floor(K'/2): the stored value
@@ -107,7 +112,7 @@ struct EpilogueLayout {
                                           int pos0, bool any, int n, const int (&pop)[VB]) const
     {
         if (!any) return;
-        if constexpr (sizeof(T) == 1 && (VB == 4 || VB == 8)) {
+        if constexpr (sizeof(T) == 1) {
             if (top_bits_shift > 0) {
                 store_seven_bit<VB>(ctx, row, row_scale, col, pos0, n, pop);
                 return;
@@ -151,7 +156,7 @@ struct EpilogueLayout {
         }
         write_values<VB>(rows + row * positions + pos0, tmp);
     }
-    // Fast form of store() for the 7-bit layouts, VB a multiple of 4 (see pop_init).
+    // store() for the 7-bit layouts (see pop_init).
     template <int VB>
     __device__ __forceinline__ void store_seven_bit(const Lane<VB> &ctx, int64_t row, float row_scale,
                                                     const int (&col)[VB], int pos0, int n,
@@ -176,11 +181,13 @@ struct EpilogueLayout {
                 row_scale = __uint_as_float(0x7fc00000u);
             }
         }
-        uint32_t words[VB / 4];
+        constexpr int kWords = VB > 4 ? VB / 4 : 1;
+        uint32_t words[kWords];
 #pragma unroll
-        for (int q = 0; q < VB / 4; ++q) {
-            uint32_t x = (c[4 * q] & 0xffu) | ((c[4 * q + 1] & 0xffu) << 8) | ((c[4 * q + 2] & 0xffu) << 16) |
-                         (c[4 * q + 3] << 24);
+        for (int q = 0; q < kWords; ++q) {
+            uint32_t x = 0;
+#pragma unroll
+            for (int e = 0; e < 4 && 4 * q + e < VB; ++e) x |= (c[4 * q + e] & 0xffu) << (8 * e);
             x ^= 0x3f3f3f3fu;
             x = (x & 0x7f7f7f7fu) | ((x & 0x40404040u) << 1);          // copy bit 6 into bit 7
             words[q] = x;
@@ -190,8 +197,10 @@ struct EpilogueLayout {
             words[0] = (words[0] & ~0x80u) | (bit << 7);
         }
         T *p = rows + row * positions + pos0;
-        if constexpr (VB == 4) *reinterpret_cast<uint32_t *>(p) = words[0];
-        else *reinterpret_cast<uint2 *>(p) = make_uint2(words[0], words[1]);
+        if constexpr (VB == 8) *reinterpret_cast<uint2 *>(p) = make_uint2(words[0], words[1]);
+        else if constexpr (VB == 4) *reinterpret_cast<uint32_t *>(p) = words[0];
+        else if constexpr (VB == 2) *reinterpret_cast<uint16_t *>(p) = static_cast<uint16_t>(words[0]);
+        else *reinterpret_cast<uint8_t *>(p) = static_cast<uint8_t>(words[0]);
     }
     template <int VB>
     static __device__ __forceinline__ void write_values(T *p, const T (&tmp)[VB])
@@ -489,17 +498,17 @@ int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const 
     if (layout.kind == kI8) {
         EpilogueLayout<int8_t> epi{static_cast<int8_t *>(c_rows), layout.positions(), layout.k_eff,
                                    layout.embed_scale != kScaleSeparate ? src_scale : nullptr,
-                                   layout.embed_scale == kScaleInTopBits ? (layout.vec == 8 ? 3 : 2) : 0,
+                                   layout.embed_scale == kScaleInTopBits ? 3 : 0, layout.groups,
                                    layout.escape ? static_cast<int8_t *>(alt_rows) : nullptr};
         return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
                                 last_mask, epi, stream);
     }
     if (layout.kind == kF16) {
-        EpilogueLayout<__half> epi{static_cast<__half *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, nullptr};
+        EpilogueLayout<__half> epi{static_cast<__half *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, 0, nullptr};
         return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
                                 last_mask, epi, stream);
     }
-    EpilogueLayout<float> epi{static_cast<float *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, nullptr};
+    EpilogueLayout<float> epi{static_cast<float *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, 0, nullptr};
     return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
                             last_mask, epi, stream);
 }

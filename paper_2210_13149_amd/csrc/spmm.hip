@@ -122,12 +122,16 @@ struct Segment<int8_t, 8> {
     __device__ __forceinline__ uint32_t head() const { return raw.x; }
     // first byte holds a 7-bit value under a foreign top bit: copy bit 6 into bit 7
     __device__ __forceinline__ void restore_head_sign() { raw.x = (raw.x & ~0x80u) | ((raw.x << 1) & 0x80u); }
+    // the same for the fifth byte (rows of 16 lanes carry two scale bits per lane)
+    __device__ __forceinline__ uint32_t middle() const { return raw.y; }
+    __device__ __forceinline__ void restore_middle_sign() { raw.y = (raw.y & ~0x80u) | ((raw.y << 1) & 0x80u); }
 };
 // The fp32 weight stored inside a loaded row, handed to every lane of the row's group.
 //   kWeightEmbedded: the row's last four bytes, held by the last lane of the group;
 //   kWeightTopBits:  bit i of the weight is the top bit of the first byte of lane i's segment
-//                    (groups of 32 or 64 lanes); one ballot collects the bits of both rows that a
-//                    load instruction covers, and the segment's first byte gets its sign back.
+//                    (groups of 32 or 64 lanes; groups of 16 lanes keep bits 16..31 in the top
+//                    bit of the fifth byte); one ballot per carrier byte collects the bits of all
+//                    rows that a load instruction covers, and the carrier bytes get their sign back.
 template <typename T, int G, int V, int WM>
 __device__ __forceinline__ float row_weight(Segment<T, V> &seg, int lane, bool loaded)
 {
@@ -136,8 +140,17 @@ __device__ __forceinline__ float row_weight(Segment<T, V> &seg, int lane, bool l
     } else if constexpr (sizeof(T) == 1 && (WM == kWeightTopBits || WM == kWeightTopBitsEscape)) {
         const uint64_t bits = __ballot(loaded && (seg.head() & 0x80u) != 0);
         seg.restore_head_sign();
-        const uint32_t mine = (G == kWave || lane < 32) ? static_cast<uint32_t>(bits) : static_cast<uint32_t>(bits >> 32);
-        return __uint_as_float(mine);
+        if constexpr (G >= 32) {
+            const uint32_t mine = (G == kWave || lane < 32) ? static_cast<uint32_t>(bits) : static_cast<uint32_t>(bits >> 32);
+            return __uint_as_float(mine);
+        } else {
+            const uint64_t high = __ballot(loaded && (seg.middle() & 0x80u) != 0);
+            seg.restore_middle_sign();
+            const int shift = lane & ~(G - 1);           // first lane of this lane's group (G = 16)
+            const uint32_t mine = (static_cast<uint32_t>(bits >> shift) & 0xffffu) |
+                                  ((static_cast<uint32_t>(high >> shift) & 0xffffu) << 16);
+            return __uint_as_float(mine);
+        }
     } else {
         return 0.0f;
     }
@@ -679,14 +692,15 @@ RowLayout choose_layout(int64_t d_in, int64_t d_out)
         l.embed_scale = d_out <= l.groups * (l.vec - 3) - 1 ? kScaleInTail : kScaleSeparate;
         // Up to 128 input bits the stored value needs 7 bits (K = 128: with the last bit folded
         // out, floor(127/2) - popcount lies in [-64, 63]), so the top bit of a byte is free.  Rows
-        // of at least 32 lanes carry the 32 bits of the scale there, one per lane.
-        if (l.embed_scale == kScaleSeparate && d_in <= 128 && l.groups >= 32) {
+        // of at least 32 lanes carry the 32 bits of the scale there, one per lane, rows of 16 lanes
+        // two per lane (first and fifth byte).
+        if (l.embed_scale == kScaleSeparate && d_in <= 128 && l.groups >= 16) {
             if (d_in == 128) {
                 l.fold_last = 1;
                 l.k_eff = 127;
             }
             l.embed_scale = kScaleInTopBits;
-        } else if (l.embed_scale == kScaleSeparate && l.groups >= 32) {
+        } else if (l.embed_scale == kScaleSeparate && l.groups >= 16) {
             // 129..256 input bits: a product needs 8 bits in the worst case, but a row of them
             // almost never does (the stored value has standard deviation sqrt(K)/2 <= 8 for
             // uncorrelated signs; 7 bits hold +-8 sigma).  Rows are written in the 7-bit form
@@ -734,14 +748,14 @@ static int launch_fused_spmm_t(const FusedSpmmArgs &a, hipStream_t stream)
     return launch_spmm_groups<TT, VV, kWeightEmbedded>(l.groups, a.plan, a.row_ptr, a.col_idx, nullptr, \
                                                        a.c_rows, rb, valid, epi, stream)
     if (l.kind == kI8 && l.embed_scale == kScaleInTopBits && l.escape) {
-        if (l.groups < 32) return BIGCN_EINVAL;
+        if (l.groups < 16) return BIGCN_EINVAL;
         if (kSelfTerm && a.alt_self_rows == nullptr) return BIGCN_ENULL;
         return launch_spmm_groups<int8_t, 8, kWeightTopBitsEscape>(l.groups, a.plan, a.row_ptr, a.col_idx,
                                                                    a.src_scale, a.c_rows, rb, valid, epi, stream,
                                                                    a.alt_rows);
     }
     if (l.kind == kI8 && l.embed_scale == kScaleInTopBits) {
-        if (l.groups < 32) return BIGCN_EINVAL;
+        if (l.groups < 16) return BIGCN_EINVAL;
         return launch_spmm_groups<int8_t, 8, kWeightTopBits>(l.groups, a.plan, a.row_ptr, a.col_idx, nullptr,
                                                              a.c_rows, rb, valid, epi, stream);
     }

@@ -126,11 +126,22 @@ def test_forward_extreme_products(B, d_in):
     same form for rows that fit it and one byte per product in the alternate array for rows that
     do not, which these inputs produce in numbers; the last input bit carried separately at
     K = 128 and K = 256; fp16 up to K = 2048; fp32 beyond)."""
+    _extreme_products(B, d_in, 256)
+
+
+@pytest.mark.parametrize("d_in,d_hidden", [(100, 128), (128, 128), (200, 100), (256, 128), (64, 96)])
+def test_forward_extreme_products_rows_of_sixteen_lanes(B, d_in, d_hidden):
+    """The same with 80 to 128 hidden columns: product rows of 16 lanes, which carry two bits of
+    the scale per lane."""
+    _extreme_products(B, d_in, d_hidden)
+
+
+def _extreme_products(B, d_in, d_hidden):
     from workloads import chung_lu_csr
     from workloads.build import Workload
     from workloads.configs import WorkloadConfig
-    rng = np.random.default_rng(d_in)
-    n, d_hidden, d_out = 400, 256, 5
+    rng = np.random.default_rng(d_in + 7 * d_hidden)
+    n, d_out = 400, 5
     rp, ci = chung_lu_csr(n, 3000, 2.5, 2.0, seed=d_in)
     w0 = rng.uniform(-1, 1, size=(d_in, d_hidden)).astype(np.float32)
     w1 = rng.uniform(-1, 1, size=(d_hidden, d_out)).astype(np.float32)

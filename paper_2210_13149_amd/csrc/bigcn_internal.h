@@ -74,11 +74,17 @@ struct RowLayout {
                      //    when the scale sits in the top bits)
     int embed_scale; // ScalePlace
     int escape;      // 1 (kScaleInTopBits, K' > 127): a row whose values do not all fit 7 bits carries
-                     //    a NaN scale; its one-byte values live in an alternate row array and its
-                     //    scale in the per-node array
+                     //    a NaN scale; its values live in an alternate row array (same positions,
+                     //    element kind alt_kind) and its scale in the per-node array
+    int alt_kind;    // RowKind of the alternate array: kI8 (K <= 256), kF16 (K <= 4096: |value| <=
+                     //    2048 is exact in fp16), kF32
     __host__ __device__ int positions() const { return groups * vec; }
     __host__ __device__ int elem_bytes() const { return kind == kI8 ? 1 : (kind == kF16 ? 2 : 4); }
     __host__ __device__ int64_t row_bytes() const { return static_cast<int64_t>(positions()) * elem_bytes(); }
+    __host__ __device__ int64_t alt_row_bytes() const
+    {
+        return static_cast<int64_t>(positions()) * (alt_kind == kI8 ? 1 : (alt_kind == kF16 ? 2 : 4));
+    }
     // sum_k w_k c_kj = mul * sum_k w_k stored_kj + bias * sum_k w_k (+ last-bit term)
     __host__ __device__ float mul() const { return kind == kI8 ? 2.0f : 1.0f; }
     __host__ __device__ float bias() const { return kind == kI8 ? static_cast<float>(k_eff & 1) : 0.0f; }

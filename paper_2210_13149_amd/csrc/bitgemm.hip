@@ -82,8 +82,9 @@ struct EpilogueLayout {
     const float *embed;      // non-null (int8 rows only): scale[row] is stored inside the row,
     int top_bits_shift;      //   0: in its last 4 bytes; 3: bit i in the top bit of position 8 i (i < 32) and,
     int top_bits_groups;     //   for rows of 16 lanes, bits 16..31 in the top bit of position 8 (i - 16) + 4
-    T *alt_rows;             // escape layouts: rows with a value outside [-64, 63] are written here in
-                             // one-byte form and get a NaN scale in the main array; else nullptr
+    void *alt_rows;          // escape layouts: rows with a value outside [-64, 63] are written here (one
+    int alt_half;            // byte per value, or one fp16 when alt_half) and get a NaN scale in the
+                             // main array; else nullptr
     template <int VB>
     struct Lane {
         int top_bit;         // which bit of the scale this lane's first value carries, or -1
@@ -138,7 +139,7 @@ struct EpilogueLayout {
                 // one wavefront holds the whole row: if any value needs the eighth bit the row goes
                 // to the alternate array as it is and the main array gets a NaN scale
                 if (__ballot((spread & ~127u) != 0u) != 0ull) {
-                    write_values<VB>(alt_rows + row * positions + pos0, tmp);
+                    write_values<VB>(static_cast<T *>(alt_rows) + row * positions + pos0, tmp);
                     row_scale = __uint_as_float(0x7fc00000u);
                 }
             }
@@ -172,12 +173,21 @@ struct EpilogueLayout {
         }
         if (alt_rows != nullptr) {
             // one wavefront holds the whole row: if any value needs the eighth bit the row goes to
-            // the alternate array in one-byte form and the main array gets a NaN scale
+            // the alternate array (bytes or fp16) and the main array gets a NaN scale
             if (__ballot((spread & ~127u) != 0u) != 0ull) {
-                alignas(16) T tmp[VB];
+                if (alt_half) {
+                    alignas(16) __half tmp[VB];
 #pragma unroll
-                for (int v = 0; v < VB; ++v) tmp[v] = static_cast<T>(63 - static_cast<int>(c[v]));
-                write_values<VB>(alt_rows + row * positions + pos0, tmp);
+                    for (int v = 0; v < VB; ++v)
+                        tmp[v] = __float2half(static_cast<float>(63 - static_cast<int>(c[v])));
+                    EpilogueLayout<__half>::template write_values<VB>(
+                        static_cast<__half *>(alt_rows) + row * positions + pos0, tmp);
+                } else {
+                    alignas(16) T tmp[VB];
+#pragma unroll
+                    for (int v = 0; v < VB; ++v) tmp[v] = static_cast<T>(63 - static_cast<int>(c[v]));
+                    write_values<VB>(static_cast<T *>(alt_rows) + row * positions + pos0, tmp);
+                }
                 row_scale = __uint_as_float(0x7fc00000u);
             }
         }
@@ -499,16 +509,19 @@ int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const 
         EpilogueLayout<int8_t> epi{static_cast<int8_t *>(c_rows), layout.positions(), layout.k_eff,
                                    layout.embed_scale != kScaleSeparate ? src_scale : nullptr,
                                    layout.embed_scale == kScaleInTopBits ? 3 : 0, layout.groups,
-                                   layout.escape ? static_cast<int8_t *>(alt_rows) : nullptr};
+                                   layout.escape ? alt_rows : nullptr, layout.alt_kind == kF16 ? 1 : 0};
+        // the escape decision is taken by the one wavefront that holds the whole row
+        if (layout.escape && (per_lane > 8 || per_lane * ((k_bits + 63) / 64) > 128)) return BIGCN_EINVAL;
+        if (layout.escape && layout.alt_kind != kI8 && layout.alt_kind != kF16) return BIGCN_EINVAL;
         return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
                                 last_mask, epi, stream);
     }
     if (layout.kind == kF16) {
-        EpilogueLayout<__half> epi{static_cast<__half *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, 0, nullptr};
+        EpilogueLayout<__half> epi{static_cast<__half *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, 0, nullptr, 0};
         return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
                                 last_mask, epi, stream);
     }
-    EpilogueLayout<float> epi{static_cast<float *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, 0, nullptr};
+    EpilogueLayout<float> epi{static_cast<float *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, 0, nullptr, 0};
     return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
                             last_mask, epi, stream);
 }

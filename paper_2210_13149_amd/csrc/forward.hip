@@ -16,7 +16,7 @@ namespace bigcn {
 
 struct WorkspaceMap {
     size_t bits_off, scale0_off, scale1_off, rows_off, self_rows_off, alt_rows_off, alt_self_rows_off, total;
-    bool escape;      // some layer keeps an alternate one-byte copy of rows that do not fit 7 bits
+    bool escape;      // some layer keeps an alternate copy (bytes or fp16) of rows that do not fit 7 bits
 };
 
 static size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
@@ -76,7 +76,7 @@ static WorkspaceMap map_workspace(int64_t n, const LayerView *layers, int n_laye
         const RowLayout layout = choose_layout(layers[l].d_in, layers[l].d_out);
         max_words = std::max<int64_t>(max_words, (layers[l].d_in + 63) / 64);
         max_row_bytes = std::max<int64_t>(max_row_bytes, layout.row_bytes());
-        if (layout.escape) max_alt_bytes = std::max<int64_t>(max_alt_bytes, layout.row_bytes());
+        if (layout.escape) max_alt_bytes = std::max<int64_t>(max_alt_bytes, layout.alt_row_bytes());
     }
     WorkspaceMap m;
     m.escape = max_alt_bytes > 0;

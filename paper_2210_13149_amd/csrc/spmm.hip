@@ -27,8 +27,10 @@ namespace bigcn {
 // and scale are fetched from an alternate row array and the per-node scale array.
 enum WeightMode {
     kWeightOne = 0, kWeightVals = 1, kWeightGather = 2, kWeightEmbedded = 3, kWeightTopBits = 4,
-    kWeightTopBitsEscape = 5
+    kWeightTopBitsEscape = 5,        // alternate rows hold one byte per value
+    kWeightTopBitsEscapeF16 = 6      // ... one fp16 per value (layers of more than 256 input bits)
 };
+__host__ __device__ constexpr bool escape_weights(int wm) { return wm >= kWeightTopBitsEscape; }
 __host__ __device__ constexpr bool fused_weights(int wm) { return wm >= kWeightGather; }
 __host__ __device__ constexpr bool row_weights(int wm) { return wm >= kWeightEmbedded; }
 
@@ -123,6 +125,7 @@ struct Segment<int8_t, 8> {
     // first byte holds a 7-bit value under a foreign top bit: copy bit 6 into bit 7
     __device__ __forceinline__ void restore_head_sign() { raw.x = (raw.x & ~0x80u) | ((raw.x << 1) & 0x80u); }
     // the same for the fifth byte (rows of 16 lanes carry two scale bits per lane)
+    __device__ __forceinline__ void clear() { raw = make_uint2(0u, 0u); }
     __device__ __forceinline__ uint32_t middle() const { return raw.y; }
     __device__ __forceinline__ void restore_middle_sign() { raw.y = (raw.y & ~0x80u) | ((raw.y << 1) & 0x80u); }
 };
@@ -137,7 +140,7 @@ __device__ __forceinline__ float row_weight(Segment<T, V> &seg, int lane, bool l
 {
     if constexpr (sizeof(T) == 1 && WM == kWeightEmbedded) {
         return __uint_as_float(static_cast<uint32_t>(__shfl(static_cast<int>(seg.tail()), lane | (G - 1), kWave)));
-    } else if constexpr (sizeof(T) == 1 && (WM == kWeightTopBits || WM == kWeightTopBitsEscape)) {
+    } else if constexpr (sizeof(T) == 1 && WM >= kWeightTopBits) {
         const uint64_t bits = __ballot(loaded && (seg.head() & 0x80u) != 0);
         seg.restore_head_sign();
         if constexpr (G >= 32) {
@@ -179,21 +182,38 @@ __device__ __forceinline__ const char *row_address(const char *lane_base, int k,
     return lane_base + static_cast<uint64_t>(static_cast<uint32_t>(k)) * row_bytes;
 }
 
-// The weight a loaded row carries; with kWeightTopBitsEscape also the rare replacement of a row
-// that did not fit 7 bits (NaN scale) by its one-byte form and its gathered scale.  Executed by
-// all lanes; `loaded` says whether this lane's segment was fetched.
+// The weight a loaded row carries; with the escape modes also the rare replacement of a row that
+// did not fit 7 bits (NaN scale): its values come from the alternate array and its scale from the
+// per-node array.  One-byte alternates are loaded into the segment; fp16 alternates are
+// accumulated here (with |w|, as the caller would) and the segment is cleared.  Executed by all
+// lanes; `loaded` says whether this lane's segment was fetched; alt_row_bytes = bytes of an
+// alternate row, alt_lane_base already points at this lane's first value.
 template <typename T, int G, int V, int WM>
 __device__ __forceinline__ float resolve_row(Segment<T, V> &seg, int lane, bool loaded, int k,
-                                             const char *__restrict__ alt_lane_base, uint32_t row_bytes,
-                                             const float *__restrict__ weights)
+                                             const char *__restrict__ alt_lane_base, uint32_t alt_row_bytes,
+                                             const float *__restrict__ weights, float (&acc)[V])
 {
     float w = row_weight<T, G, V, WM>(seg, lane, loaded);
-    if constexpr (WM == kWeightTopBitsEscape) {
+    if constexpr (escape_weights(WM) && sizeof(T) == 1) {
         const bool escaped = loaded && !(fabsf(w) <= 3.0e38f);      // NaN (or Inf) marks the row
         if (__ballot(escaped) != 0ull) {
             if (escaped) {
-                seg.load(row_address(alt_lane_base, k, row_bytes));
+                const char *src = row_address(alt_lane_base, k, alt_row_bytes);
                 w = weights[k];
+                if constexpr (WM == kWeightTopBitsEscape) {
+                    seg.load(src);
+                } else {
+                    static_assert(V == 8, "fp16 alternates are read as one 16-byte vector per lane");
+                    const float aw = fabsf(w);
+                    const uint4 raw = *reinterpret_cast<const uint4 *>(src);
+                    const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        acc[2 * q] = fmaf(aw, __low2float(h[q]), acc[2 * q]);
+                        acc[2 * q + 1] = fmaf(aw, __high2float(h[q]), acc[2 * q + 1]);
+                    }
+                    seg.clear();
+                }
             }
         }
     }
@@ -210,8 +230,8 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
                                                  const float *__restrict__ weights,
                                                  const char *__restrict__ lane_base,
                                                  const char *__restrict__ alt_lane_base, uint32_t row_bytes,
-                                                 int64_t p0, int64_t p1, int lane, bool active_in,
-                                                 RowAcc<V> &acc)
+                                                 uint32_t alt_row_bytes, int64_t p0, int64_t p1, int lane,
+                                                 bool active_in, RowAcc<V> &acc)
 {
     const bool active = kAllActive || active_in;
     constexpr int S = kWave / G;      // neighbours covered by one load instruction
@@ -248,7 +268,8 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (row_weights(WM))
-                    w[u] = resolve_row<T, G, V, WM>(seg[u], lane, active, kk[u], alt_lane_base, row_bytes, weights);
+                    w[u] = resolve_row<T, G, V, WM>(seg[u], lane, active, kk[u], alt_lane_base, alt_row_bytes, weights,
+                                                    acc.pos);
                 if (fused_weights(WM)) {
                     acc.sum_abs += fabsf(w[u]);
                     acc.sum_signed += w[u];
@@ -279,7 +300,7 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
                 // the broadcast is executed by all lanes; slots without a neighbour discard it
                 if (row_weights(WM))
                     w[u] = resolve_row<T, G, V, WM>(seg[u], lane, active && present[u], kk[u], alt_lane_base,
-                                                    row_bytes, weights);
+                                                    alt_row_bytes, weights, acc.pos);
                 if (present[u]) {
                     if (fused_weights(WM)) {
                         acc.sum_abs += fabsf(w[u]);
@@ -299,15 +320,16 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
 template <typename T, int G, int V, int WM>
 __device__ __forceinline__ void load_own_row(const char *__restrict__ own_lane_base,
                                              const char *__restrict__ own_alt_lane_base, uint32_t row_bytes,
-                                             const float *__restrict__ weights, int64_t row, int lane,
-                                             bool active, RowAcc<V> &own)
+                                             uint32_t alt_row_bytes, const float *__restrict__ weights,
+                                             int64_t row, int lane, bool active, RowAcc<V> &own)
 {
     own.clear();
     Segment<T, V> seg;
     if (active) seg.load(row_address(own_lane_base, static_cast<int>(row), row_bytes));
     float t;
     if (row_weights(WM))
-        t = resolve_row<T, G, V, WM>(seg, lane, active, static_cast<int>(row), own_alt_lane_base, row_bytes, weights);
+        t = resolve_row<T, G, V, WM>(seg, lane, active, static_cast<int>(row), own_alt_lane_base, alt_row_bytes,
+                                     weights, own.pos);
     else t = weights[row];
     own.sum_abs = fabsf(t);
     own.sum_signed = t;
@@ -531,6 +553,8 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, V, Epilogue>())) void sp
     const float *__restrict__ weights, const char *__restrict__ rows, const char *__restrict__ alt_rows,
     uint32_t row_bytes, int valid_positions, Epilogue epi)
 {
+    constexpr int kAltElem = WM == kWeightTopBitsEscapeF16 ? 2 : static_cast<int>(sizeof(T));
+    const uint32_t alt_row_bytes = row_bytes / sizeof(T) * kAltElem;
     constexpr bool kAllActive = fused_weights(WM);     // stored rows of the fused path fill G * V positions
     __shared__ float partial[kWavesPerBlock - 1][V + 2][kWave];
     const int lane = lane_id();
@@ -550,14 +574,13 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, V, Epilogue>())) void sp
     }
     RowAcc<V> acc;
     RowAcc<V> own;      // only filled (and only read) by epilogues with an own-row term
-    // alternate (one-byte) rows of nodes whose products did not fit 7 bits; only dereferenced by
-    // kWeightTopBitsEscape
-    const char *alt_lane_base = alt_rows + static_cast<int64_t>(g) * V * sizeof(T);
+    // alternate rows of nodes whose products did not fit 7 bits; only dereferenced by the escape modes
+    const char *alt_lane_base = alt_rows + static_cast<int64_t>(g) * V * kAltElem;
     const char *own_lane_base = nullptr;
     const char *own_alt_lane_base = nullptr;
     if constexpr (Epilogue::kSelf) {
         own_lane_base = epi.self_rows + static_cast<int64_t>(g) * V * sizeof(T);
-        own_alt_lane_base = epi.alt_self_rows + static_cast<int64_t>(g) * V * sizeof(T);
+        own_alt_lane_base = epi.alt_self_rows + static_cast<int64_t>(g) * V * kAltElem;
     }
 
     if (static_cast<int64_t>(blockIdx.x) < n_block_rows) {
@@ -571,7 +594,7 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, V, Epilogue>())) void sp
         if (q0 > p1) q0 = p1;
         if (q1 > p1) q1 = p1;
         acc.clear();
-        accumulate_range<T, G, V, WM, kAllActive>(col_idx, weights, lane_base, alt_lane_base, row_bytes, q0, q1, lane,
+        accumulate_range<T, G, V, WM, kAllActive>(col_idx, weights, lane_base, alt_lane_base, row_bytes, alt_row_bytes, q0, q1, lane,
                                                   active, acc);
         reduce_slots<G, V, WM>(acc);
         if (wave > 0) {
@@ -590,7 +613,7 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, V, Epilogue>())) void sp
                 acc.sum_signed += partial[w][V + 1][lane];
             }
             if constexpr (Epilogue::kSelf)
-                load_own_row<T, G, V, WM>(own_lane_base, own_alt_lane_base, row_bytes, weights, row, lane, active, own);
+                load_own_row<T, G, V, WM>(own_lane_base, own_alt_lane_base, row_bytes, alt_row_bytes, weights, row, lane, active, own);
             LaneConsts ctx;
             Parked::fetch(ctx, parked, lane);
             epi.template finish<G, V>(ctx, row, lane, acc, own);
@@ -606,8 +629,8 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, V, Epilogue>())) void sp
         const int64_t p0 = row_ptr[row], p1 = row_ptr[row + 1];
         acc.clear();
         if constexpr (Epilogue::kSelf)
-            load_own_row<T, G, V, WM>(own_lane_base, own_alt_lane_base, row_bytes, weights, row, lane, active, own);
-        accumulate_range<T, G, V, WM, kAllActive>(col_idx, weights, lane_base, alt_lane_base, row_bytes, p0, p1, lane,
+            load_own_row<T, G, V, WM>(own_lane_base, own_alt_lane_base, row_bytes, alt_row_bytes, weights, row, lane, active, own);
+        accumulate_range<T, G, V, WM, kAllActive>(col_idx, weights, lane_base, alt_lane_base, row_bytes, alt_row_bytes, p0, p1, lane,
                                                   active, acc);
         reduce_slots<G, V, WM>(acc);
         LaneConsts ctx;
@@ -623,7 +646,7 @@ static int launch_spmm_one(const bigcn_plan *plan, const int64_t *row_ptr, const
                            const void *alt_rows)
 {
     if (row_bytes <= 0 || row_bytes > 0x7fffffff) return BIGCN_EINVAL;
-    if (WM == kWeightTopBitsEscape && (alt_rows == nullptr || weights == nullptr)) return BIGCN_ENULL;
+    if (escape_weights(WM) && (alt_rows == nullptr || weights == nullptr)) return BIGCN_ENULL;
     if (fused_weights(WM) && valid_positions != G * V) return BIGCN_EINVAL;
     const int64_t wave_rows = plan->n - plan->n_block_rows;
     const int64_t per_block = kWavesPerBlock * kRowsPerWave;
@@ -666,6 +689,10 @@ static int groups_for(int64_t positions, int vec)
     return g;
 }
 
+// Largest layer input for which products are stored in 7 bits with an fp16 alternate (see below);
+// with positions <= 512 the bit-GEMM then still holds a whole row in one wavefront.
+constexpr int64_t kMaxEscapeBits = 1024;
+
 RowLayout choose_layout(int64_t d_in, int64_t d_out)
 {
     RowLayout l;
@@ -683,6 +710,23 @@ RowLayout choose_layout(int64_t d_in, int64_t d_out)
     l.groups = groups_for(d_out, l.vec);
     l.embed_scale = kScaleSeparate;
     l.escape = 0;
+    l.alt_kind = kI8;
+    if (l.kind != kI8 && d_in <= kMaxEscapeBits) {
+        // 257..1024 input bits: the stored value floor(K/2) - popcount has standard deviation
+        // sqrt(K)/2 <= 16 for uncorrelated signs, so a whole row still fits 7 bits per value nearly
+        // always (+-4 sigma at K = 1024).  Same 7-bit rows with the scale in the top bits as for
+        // 129..256 bits; the alternate array keeps rows that do not fit as fp16 (|value| <= 512).
+        // Beyond 1024 bits too many rows would take the slow path and fp16 rows are kept.
+        // Narrow outputs are widened to 16 lanes (128 bytes, one cache line) to have room for
+        // the scale bits: cheaper than a second line per neighbour for a separate scale.
+        l.kind = kI8;
+        l.vec = 8;
+        l.groups = groups_for(d_out, 8) < 16 ? 16 : groups_for(d_out, 8);
+        l.embed_scale = kScaleInTopBits;
+        l.escape = 1;
+        l.alt_kind = kF16;
+        return l;
+    }
     if (l.kind == kI8) {
         // The last four stored values belong to the last lane of the group and hold columns
         // (G-1) + G*(V-4 .. V-1); when those lie past d_out the bytes are free for the scale.
@@ -750,6 +794,11 @@ static int launch_fused_spmm_t(const FusedSpmmArgs &a, hipStream_t stream)
     if (l.kind == kI8 && l.embed_scale == kScaleInTopBits && l.escape) {
         if (l.groups < 16) return BIGCN_EINVAL;
         if (kSelfTerm && a.alt_self_rows == nullptr) return BIGCN_ENULL;
+        if (l.alt_kind == kF16)
+            return launch_spmm_groups<int8_t, 8, kWeightTopBitsEscapeF16>(l.groups, a.plan, a.row_ptr, a.col_idx,
+                                                                          a.src_scale, a.c_rows, rb, valid, epi,
+                                                                          stream, a.alt_rows);
+        if (l.alt_kind != kI8) return BIGCN_EINVAL;
         return launch_spmm_groups<int8_t, 8, kWeightTopBitsEscape>(l.groups, a.plan, a.row_ptr, a.col_idx,
                                                                    a.src_scale, a.c_rows, rb, valid, epi, stream,
                                                                    a.alt_rows);

@@ -132,7 +132,7 @@ def test_forward_workspace_size_and_argument_checks():
     small = L.bigcn_forward_workspace_bytes(n, _layers((100, 256, 47)), 2)
     assert small <= n * (4 * 8 + 2 * 4 + 256) + 4 * 256   # K = 100 -> 256 provably fits: no alternate array
     mid = L.bigcn_forward_workspace_bytes(n, _layers((602, 128, 41)), 2)
-    assert mid >= n * (10 * 8 + 8 + 128 * 2)          # 256 < K <= 2048: products kept in fp16
+    assert mid >= n * (10 * 8 + 8 + 128 + 128 * 2)    # 256 < K <= 1024: 7-bit products, fp16 alternates
     wide = L.bigcn_forward_workspace_bytes(n, _layers((3703, 64, 6)), 2)
     assert wide >= n * (58 * 8 + 8 + 64 * 4)          # K > 2048: products kept in fp32
     assert L.bigcn_forward_workspace_bytes(n, None, 3) == 0

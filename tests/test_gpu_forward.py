@@ -118,21 +118,23 @@ def test_forward_layer_chain_equals_separate_kernels(B):
     assert_close(h1, rec["out"], "H1 through separate kernels")
 
 
-@pytest.mark.parametrize("d_in", [64, 100, 127, 128, 129, 200, 254, 255, 256, 257, 2048, 2049])
+@pytest.mark.parametrize("d_in", [64, 100, 127, 128, 129, 200, 254, 255, 256, 257, 602, 1023, 1024, 1025, 2048, 2049])
 def test_forward_extreme_products(B, d_in):
     """Nodes whose sign pattern equals, or is the exact opposite of, a weight column give the
     extreme products +K and -K: the ends of the range of every compact product-row format
     (seven bits per product up to K = 128 with the scale in the spare top bits; up to K = 256 the
     same form for rows that fit it and one byte per product in the alternate array for rows that
-    do not, which these inputs produce in numbers; the last input bit carried separately at
-    K = 128 and K = 256; fp16 up to K = 2048; fp32 beyond)."""
+    do not, which these inputs produce in numbers; up to K = 1024 again that form, with fp16
+    alternates; the last input bit carried separately at K = 128 and K = 256; plain fp16 rows up
+    to K = 2048; fp32 beyond)."""
     _extreme_products(B, d_in, 256)
 
 
-@pytest.mark.parametrize("d_in,d_hidden", [(100, 128), (128, 128), (200, 100), (256, 128), (64, 96)])
+@pytest.mark.parametrize("d_in,d_hidden", [(100, 128), (128, 128), (200, 100), (256, 128), (64, 96),
+                                           (300, 128), (1024, 90), (513, 20), (700, 3)])
 def test_forward_extreme_products_rows_of_sixteen_lanes(B, d_in, d_hidden):
     """The same with 80 to 128 hidden columns: product rows of 16 lanes, which carry two bits of
-    the scale per lane."""
+    the scale per lane; layers of 257..1024 input bits use such rows for any narrower output too."""
     _extreme_products(B, d_in, d_hidden)
 
 

@@ -129,11 +129,11 @@ def test_sage_forward_formats_and_edge_cases(B, dims, n, n_edges, i0):
         assert stats[-1]["rows_compared"] >= 0.5 * n
 
 
-@pytest.mark.parametrize("d_in", [129, 200, 256])
+@pytest.mark.parametrize("d_in", [129, 200, 256, 300, 1024])
 def test_sage_rows_that_do_not_fit_seven_bits(B, d_in):
     """Nodes whose signs equal (or oppose) a column of W_theta or of W_n give products of +-K:
-    their product rows, own and neighbour, take the one-byte escape path of layers with
-    129..256 input bits."""
+    their product rows, own and neighbour, take the escape path of layers with 129..1024 input
+    bits (one-byte alternates up to 256 bits, fp16 alternates beyond)."""
     n, d_hidden, d_out = 600, 256, 6
     rng = np.random.default_rng(1000 + d_in)
     work = small_sage_workload(n, 4000, (d_in, d_hidden, d_out), seed=900 + d_in)

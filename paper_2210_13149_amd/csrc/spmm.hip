@@ -539,15 +539,19 @@ constexpr int kRowsPerWave = 16;
 
 // Wavefronts per SIMD the register allocation aims for.  The gather hides HBM latency with
 // resident wavefronts, so the one-byte rows of the Bi-GCN path (which fit 64 registers without
-// spilling) ask for the maximum of 8; wider accumulators keep the compiler's own choice.
-template <typename T, int V, class Epilogue>
+// spilling) ask for the maximum of 8.  With an own-row term the second accumulator set does not
+// fit 64 registers: 6 wavefronts (80 registers) measured best, 7 (72 registers) for
+// full-wavefront rows with the escape test.  Wider element types keep the compiler's own choice.
+template <typename T, int G, int V, int WM, class Epilogue>
 constexpr int spmm_min_waves()
 {
-    return (sizeof(T) == 1 && V == 8 && !Epilogue::kSelf) ? 8 : 1;
+    if (sizeof(T) != 1 || V != 8) return 1;
+    if (!Epilogue::kSelf) return 8;
+    return (G == kWave && escape_weights(WM)) ? 7 : 6;
 }
 
 template <typename T, int G, int V, int WM, class Epilogue>
-__global__ __launch_bounds__(kBlock, (spmm_min_waves<T, V, Epilogue>())) void spmm_kernel(
+__global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) void spmm_kernel(
     const int32_t *__restrict__ row_order, int64_t n, int64_t n_block_rows,
     const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
     const float *__restrict__ weights, const char *__restrict__ rows, const char *__restrict__ alt_rows,

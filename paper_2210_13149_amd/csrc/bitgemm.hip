@@ -230,6 +230,52 @@ struct EpilogueLayout {
     }
 };
 
+// Stage the packed rows of B for the columns of column block y into LDS ([n_words][64*VB]; slot c
+// belongs to lane c % 64), with last_mask applied to the last word; ends with a barrier.
+template <int VB>
+__device__ __forceinline__ void stage_b_block(uint64_t *lds_b, const uint64_t *__restrict__ b, int n, int64_t ldb,
+                                              int n_words, uint32_t last_mask, const ColumnMap &map, int y)
+{
+    constexpr int CB = 64 * VB;
+    constexpr int kBatch = 4;         // loads of a thread in flight together
+    const int total = CB * n_words;
+    for (int idx0 = threadIdx.x; idx0 < total; idx0 += kBlock * kBatch) {
+        uint64_t word[kBatch];
+        int slot[kBatch];
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q) {
+            const int idx = idx0 + q * kBlock;
+            const int c = idx / n_words;
+            const int w = idx - c * n_words;
+            const int l = c & 63, v = c >> 6;
+            const int vv = map.per_group * (l / map.groups) + y * VB + v;
+            const int j = (l % map.groups) + map.groups * vv;
+            word[q] = (idx < total && vv < map.vec && j < n) ? b[static_cast<int64_t>(j) * ldb + w] : 0ull;
+            if (w == n_words - 1) word[q] &= (static_cast<uint64_t>(last_mask) << 32) | 0xffffffffull;
+            slot[q] = idx < total ? w * CB + c : -1;
+        }
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q)
+            if (slot[q] >= 0) lds_b[slot[q]] = word[q];
+    }
+    __syncthreads();
+}
+
+// The output columns of a lane's VB values in column block y (-1: none), whether it has any,
+// and (returned) the stored position of its first value.
+template <int VB>
+__device__ __forceinline__ int lane_columns(const ColumnMap &map, int y, int lane, int (&col)[VB], bool &any)
+{
+    any = false;
+#pragma unroll
+    for (int v = 0; v < VB; ++v) {
+        const int vv = map.per_group * (lane / map.groups) + y * VB + v;
+        col[v] = vv < map.vec ? (lane % map.groups) + map.groups * vv : -1;
+        any = any || vv < map.vec;
+    }
+    return (lane % map.groups) * map.vec + map.per_group * (lane / map.groups) + y * VB;
+}
+
 // ---- the kernel -----------------------------------------------------------------------------
 // grid.x walks row blocks (grid-stride), grid.y is the column block.  last_mask is ANDed onto
 // the high half of the last word of both operands (all ones, or bit 31 cleared to leave the
@@ -242,31 +288,13 @@ __global__ __launch_bounds__(kBlock) void bitgemm_kernel(
     extern __shared__ uint64_t lds_b[];          // [n_words][64*VB]
     constexpr int CB = 64 * VB;
     const int y = blockIdx.y;
-
-    // stage the packed rows of B for the columns of this block; slot c belongs to lane c % 64
-    for (int idx = threadIdx.x; idx < CB * n_words; idx += kBlock) {
-        const int c = idx / n_words;
-        const int w = idx - c * n_words;
-        const int l = c & 63, v = c >> 6;
-        const int vv = map.per_group * (l / map.groups) + y * VB + v;
-        const int j = (l % map.groups) + map.groups * vv;
-        uint64_t word = (vv < map.vec && j < n) ? b[static_cast<int64_t>(j) * ldb + w] : 0ull;
-        if (w == n_words - 1) word &= (static_cast<uint64_t>(last_mask) << 32) | 0xffffffffull;
-        lds_b[w * CB + c] = word;
-    }
-    __syncthreads();
+    stage_b_block<VB>(lds_b, b, n, ldb, n_words, last_mask, map, y);
     const uint2 *lds_b2 = reinterpret_cast<const uint2 *>(lds_b);
 
     const int lane = lane_id();
     int col[VB];
-    bool any = false;
-#pragma unroll
-    for (int v = 0; v < VB; ++v) {
-        const int vv = map.per_group * (lane / map.groups) + y * VB + v;
-        col[v] = vv < map.vec ? (lane % map.groups) + map.groups * vv : -1;
-        any = any || vv < map.vec;
-    }
-    const int pos0 = (lane % map.groups) * map.vec + map.per_group * (lane / map.groups) + y * VB;
+    bool any;
+    const int pos0 = lane_columns<VB>(map, y, lane, col, any);
     typename Epilogue::template Lane<VB> ctx;
     epi.template init<VB>(col, pos0, n, ctx);
 
@@ -429,6 +457,86 @@ __global__ __launch_bounds__(kBlock) void bitgemm_rows_kernel(
     }
 }
 
+// ---- few rows (small graphs) ---------------------------------------------------------------
+// With a few thousand rows neither kernel fills the chip and the time of a launch is the latency
+// of one wavefront's chain of dependent steps.  Here a wavefront owns one row at a time: lane l
+// fetches word 64 c + l of the row (one coalesced load per 4096 bits), the words reach the scalar
+// registers by lane broadcast, and B is staged in LDS as above.
+template <int VB, class Epilogue>
+__global__ __launch_bounds__(kBlock) void bitgemm_small_kernel(
+    const uint64_t *__restrict__ a, int64_t m, int64_t lda, const uint64_t *__restrict__ b, int n,
+    int64_t ldb, int n_words, uint32_t last_mask, ColumnMap map, Epilogue epi)
+{
+    extern __shared__ uint64_t lds_b[];          // [n_words][64*VB]
+    constexpr int CB = 64 * VB;
+    const int y = blockIdx.y;
+    stage_b_block<VB>(lds_b, b, n, ldb, n_words, last_mask, map, y);
+    const uint2 *lds_b2 = reinterpret_cast<const uint2 *>(lds_b);
+
+    const int lane = lane_id();
+    int col[VB];
+    bool any;
+    const int pos0 = lane_columns<VB>(map, y, lane, col, any);
+    typename Epilogue::template Lane<VB> ctx;
+    epi.template init<VB>(col, pos0, n, ctx);
+
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block();
+    const int64_t n_waves = static_cast<int64_t>(gridDim.x) * kWavesPerBlock;
+    // the first 64 words of the next row are fetched while the current row is processed
+    auto fetch = [&](int64_t row, int c0) {
+        const int w = c0 + lane;
+        uint2 words = (row < m && w < n_words) ? reinterpret_cast<const uint2 *>(a + row * lda)[w] : make_uint2(0u, 0u);
+        if (w == n_words - 1) words.y &= last_mask;
+        return words;
+    };
+    uint2 head = fetch(wave, 0);
+    for (int64_t row = wave; row < m; row += n_waves) {
+        const float row_value = epi.row_value(row);
+        uint2 mine = head;
+        head = fetch(row + n_waves, 0);
+        int pop[VB];
+#pragma unroll
+        for (int v = 0; v < VB; ++v) pop[v] = epi.pop_init();
+        for (int c0 = 0; c0 < n_words; c0 += kWave) {
+            if (c0 > 0) mine = fetch(row, c0);
+            const int cnt = n_words - c0 < kWave ? n_words - c0 : kWave;      // wave-uniform
+            for (int t = 0; t < cnt; ++t) {
+                const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(mine.x), t));
+                const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(mine.y), t));
+#pragma unroll
+                for (int v = 0; v < VB; ++v) {
+                    const uint2 bw = lds_b2[(c0 + t) * CB + lane + 64 * v];
+                    pop[v] = __popc(lo ^ bw.x) + pop[v];
+                    pop[v] = __popc(hi ^ bw.y) + pop[v];
+                }
+            }
+        }
+        epi.template store<VB>(ctx, row, row_value, col, pos0, any, n, pop);
+    }
+}
+
+// Row counts up to which bitgemm_small_kernel is used (one wavefront per row still fits the
+// resident wavefronts of the chip a few times over).
+constexpr int64_t kSmallRows = 32768;
+
+template <int VB, class Epilogue>
+static int launch_bitgemm_small(const uint64_t *a, int64_t m, int64_t lda, const uint64_t *b, int64_t n,
+                                int64_t ldb, int64_t k_bits, uint32_t last_mask, ColumnMap map,
+                                int col_blocks, const Epilogue &epi, hipStream_t stream)
+{
+    const int n_words = static_cast<int>((k_bits + 63) / 64);
+    const size_t lds = static_cast<size_t>(64) * VB * n_words * sizeof(uint64_t);
+    // one row per wavefront up to 8 workgroups per compute unit; more rows share the staged B
+    int64_t blocks = (m + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t cap = 256 * 8 / col_blocks > 256 ? 256 * 8 / col_blocks : 256;
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL((bitgemm_small_kernel<VB, Epilogue>), dim3(static_cast<unsigned>(blocks), col_blocks),
+                       dim3(kBlock), lds, stream, a, m, lda, b, static_cast<int>(n), ldb, n_words,
+                       last_mask, map, epi);
+    return check_launch();
+}
+
 template <int VB, int NW, class Epilogue>
 static int launch_bitgemm_rows(const uint64_t *a, int64_t m, int64_t lda, const uint64_t *b, int64_t n,
                                int64_t ldb, uint32_t last_mask, ColumnMap map, int col_blocks,
@@ -480,6 +588,12 @@ static int dispatch_bitgemm(int per_lane, int groups, int vec, const uint64_t *a
     while (vb > 1 && vb * n_words > 128) vb >>= 1;
     const int col_blocks = (per_lane + vb - 1) / vb;
     const ColumnMap map{groups, vec, per_lane};
+    if (m <= kSmallRows) {
+        if (vb == 8) return launch_bitgemm_small<8>(a, m, lda, b, n, ldb, k_bits, last_mask, map, col_blocks, epi, stream);
+        if (vb == 4) return launch_bitgemm_small<4>(a, m, lda, b, n, ldb, k_bits, last_mask, map, col_blocks, epi, stream);
+        if (vb == 2) return launch_bitgemm_small<2>(a, m, lda, b, n, ldb, k_bits, last_mask, map, col_blocks, epi, stream);
+        return launch_bitgemm_small<1>(a, m, lda, b, n, ldb, k_bits, last_mask, map, col_blocks, epi, stream);
+    }
     if (n_words <= 4 && vb <= 4) {
         // K <= 256: batched rows, B in registers
 #define BIGCN_ROWS_CASE(VV, WW)                                                                                \

@@ -533,9 +533,20 @@ struct ParkedLane {
 
 // ---- the kernel ------------------------------------------------------------------------------
 // Rows are taken in plan order.  Workgroup b < n_block_rows owns one long row; every later
-// workgroup owns kRowsPerWave * 4 consecutive plan entries, wavefront w taking entries
-// base + w, base + w + 4, ... (neighbouring entries have similar lengths).
-constexpr int kRowsPerWave = 16;
+// workgroup owns rows_per_wave * 4 consecutive plan entries, wavefront w taking entries
+// base + w, base + w + 4, ... (neighbouring entries have similar lengths).  A wavefront takes 16
+// rows one after the other when there are enough rows to fill the chip several times over (the
+// epilogue constants are fetched once per workgroup); on small graphs, where the time of a
+// launch is the latency of one wavefront's chain of dependent loads, it takes fewer, down to one.
+constexpr int kMaxRowsPerWave = 16;
+constexpr int64_t kResidentWaves = 256 * 4 * 8;      // compute units x SIMDs x wavefronts per SIMD
+static int rows_per_wave_for(int64_t wave_rows)
+{
+    // one row per wavefront until the rows fill the chip four times over (measured on the
+    // 19717- and 232965-node workloads), then proportionally more
+    const int64_t r = wave_rows / (4 * kResidentWaves);
+    return static_cast<int>(r < 1 ? 1 : (r > kMaxRowsPerWave ? kMaxRowsPerWave : r));
+}
 
 // Wavefronts per SIMD the register allocation aims for.  The gather hides HBM latency with
 // resident wavefronts, so the one-byte rows of the Bi-GCN path (which fit 64 registers without
@@ -555,7 +566,7 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) 
     const int32_t *__restrict__ row_order, int64_t n, int64_t n_block_rows,
     const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
     const float *__restrict__ weights, const char *__restrict__ rows, const char *__restrict__ alt_rows,
-    uint32_t row_bytes, int valid_positions, Epilogue epi)
+    uint32_t row_bytes, int valid_positions, int rows_per_wave, Epilogue epi)
 {
     constexpr int kAltElem = WM == kWeightTopBitsEscapeF16 ? 2 : static_cast<int>(sizeof(T));
     const uint32_t alt_row_bytes = row_bytes / sizeof(T) * kAltElem;
@@ -625,8 +636,8 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) 
         return;
     }
     const int64_t base = n_block_rows +
-                         (static_cast<int64_t>(blockIdx.x) - n_block_rows) * (kWavesPerBlock * kRowsPerWave);
-    for (int j = 0; j < kRowsPerWave; ++j) {
+                         (static_cast<int64_t>(blockIdx.x) - n_block_rows) * (kWavesPerBlock * rows_per_wave);
+    for (int j = 0; j < rows_per_wave; ++j) {
         const int64_t entry = base + wave + j * kWavesPerBlock;
         if (entry >= n) break;                                   // wave-uniform
         const int64_t row = row_order[entry];
@@ -653,13 +664,14 @@ static int launch_spmm_one(const bigcn_plan *plan, const int64_t *row_ptr, const
     if (escape_weights(WM) && (alt_rows == nullptr || weights == nullptr)) return BIGCN_ENULL;
     if (fused_weights(WM) && valid_positions != G * V) return BIGCN_EINVAL;
     const int64_t wave_rows = plan->n - plan->n_block_rows;
-    const int64_t per_block = kWavesPerBlock * kRowsPerWave;
+    const int rows_per_wave = rows_per_wave_for(wave_rows);
+    const int64_t per_block = kWavesPerBlock * rows_per_wave;
     const int64_t blocks = plan->n_block_rows + (wave_rows + per_block - 1) / per_block;
     if (blocks == 0) return BIGCN_OK;
     hipLaunchKernelGGL((spmm_kernel<T, G, V, WM, Epilogue>), dim3(static_cast<unsigned>(blocks)),
                        dim3(kBlock), 0, stream, plan->row_order, plan->n, plan->n_block_rows, row_ptr,
                        col_idx, weights, static_cast<const char *>(rows), static_cast<const char *>(alt_rows),
-                       static_cast<uint32_t>(row_bytes), valid_positions, epi);
+                       static_cast<uint32_t>(row_bytes), valid_positions, rows_per_wave, epi);
     return check_launch();
 }
 

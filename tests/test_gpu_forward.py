@@ -138,13 +138,22 @@ def test_forward_extreme_products_rows_of_sixteen_lanes(B, d_in, d_hidden):
     _extreme_products(B, d_in, d_hidden)
 
 
-def _extreme_products(B, d_in, d_hidden):
+@pytest.mark.parametrize("d_in,d_hidden", [(100, 256), (128, 100), (200, 256), (256, 256), (256, 128),
+                                           (602, 128), (1024, 300), (2049, 64)])
+def test_forward_extreme_products_many_rows(B, d_in, d_hidden):
+    """The same on 33000 nodes: beyond 32768 rows the bit-GEMM runs its kernels for large row
+    counts (64 rows fetched at a time up to 256 input bits, scalar row fetches beyond), which must
+    take the same per-row decisions."""
+    _extreme_products(B, d_in, d_hidden, n=33000, n_edges=150000)
+
+
+def _extreme_products(B, d_in, d_hidden, n=400, n_edges=3000):
     from workloads import chung_lu_csr
     from workloads.build import Workload
     from workloads.configs import WorkloadConfig
     rng = np.random.default_rng(d_in + 7 * d_hidden)
-    n, d_out = 400, 5
-    rp, ci = chung_lu_csr(n, 3000, 2.5, 2.0, seed=d_in)
+    d_out = 5
+    rp, ci = chung_lu_csr(n, n_edges, 2.5, 2.0, seed=d_in)
     w0 = rng.uniform(-1, 1, size=(d_in, d_hidden)).astype(np.float32)
     w1 = rng.uniform(-1, 1, size=(d_hidden, d_out)).astype(np.float32)
     x = rng.standard_normal((n, d_in)).astype(np.float32)
@@ -153,7 +162,7 @@ def _extreme_products(B, d_in, d_hidden):
         x[k] = w0[:, j] if k % 2 == 0 else -w0[:, j]      # products +K / -K in column j
     x[120] = np.abs(x[120])                                 # all +1
     x[121] = -np.abs(x[121]) - 1e-3                         # all -1
-    cfg = WorkloadConfig("extreme", "none", n, 3000, 2.0, (d_in, d_hidden, d_out), "normal", 1.0,
+    cfg = WorkloadConfig("extreme", "none", n, n_edges, 2.0, (d_in, d_hidden, d_out), "normal", 1.0,
                          "first", 0)
     work = Workload(cfg, rp, ci, x, [w0, w1])
     bn = [None, None]

@@ -31,7 +31,7 @@ def _rng(seed):
 # ------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("rows,cols", [(1, 1), (3, 63), (5, 64), (7, 65), (1001, 100), (513, 128),
                                        (130, 200), (257, 256), (66, 602), (31, 1433), (9, 3703),
-                                       (4, 4097), (2, 8192)])
+                                       (4, 4097), (2, 8192), (8193, 1100), (9000, 1024), (300, 1023)])
 @pytest.mark.parametrize("bn", [False, True])
 def test_pack_rows(B, rows, cols, bn):
     import torch
@@ -86,7 +86,11 @@ def test_pack_weight_columns(B, d_in, d_out):
 GEMM_SHAPES = [(1, 1, 1), (5, 3, 64), (67, 7, 65), (300, 41, 128), (1000, 47, 256), (130, 64, 1433),
                (77, 64, 3703), (1025, 128, 602), (513, 256, 100), (260, 256, 256), (33, 300, 500),
                (19, 512, 256), (21, 700, 130), (9, 64, 8192), (4099, 64, 64), (50, 130, 4096),
-               (4099, 130, 1433), (4200, 49, 1024), (4500, 64, 8192), (300, 70, 640)]
+               (4099, 130, 1433), (4200, 49, 1024), (4500, 64, 8192), (300, 70, 640),
+               # more than 32768 rows: the kernels for large row counts (up to 32768 rows one
+               # wavefront takes one row at a time)
+               (33001, 7, 64), (33003, 64, 500), (32800, 256, 256), (32801, 64, 1433), (32769, 300, 200),
+               (40000, 47, 256), (33000, 130, 3703)]
 
 
 @pytest.mark.parametrize("variant", ["auto", "valu", "mfma"])

@@ -113,6 +113,13 @@ int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const 
                           int64_t n, int64_t ldb, int64_t k_bits, const float *src_scale, void *c_rows,
                           void *alt_rows, RowLayout layout, hipStream_t stream);
 
+// bit-GEMM writing the integer products of a row in column order (`positions` stored values per
+// row, a multiple of 8 and >= n; multiples of 64 from 64 on): one byte per product holds
+// floor(K/2) - popcount (K <= 255 only), fp16 / fp32 hold K - 2 popcount.
+int launch_bitgemm_natural(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits, int64_t n,
+                           int64_t ldb, int64_t k_bits, void *rows, int positions, RowKind kind,
+                           hipStream_t stream);
+
 // Matrix-core (int8 MFMA) variant of the public bit-GEMM: same arguments and results.
 int launch_bitgemm_mfma(const uint64_t *a_bits, const float *a_scale, int64_t m, int64_t lda,
                         const uint64_t *b_bits, const float *b_scale, int64_t n, int64_t ldb,

@@ -640,6 +640,30 @@ int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const 
                             last_mask, epi, stream);
 }
 
+// Product rows in column order (stored position = output column) for consumers that read a row's
+// columns next to each other: lane l produces positions [per_lane l, per_lane (l + 1)).  One
+// byte per product stores floor(K/2) - popcount (K <= 255), fp16 / fp32 store K - 2 popcount.
+int launch_bitgemm_natural(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits, int64_t n,
+                           int64_t ldb, int64_t k_bits, void *rows, int positions, RowKind kind,
+                           hipStream_t stream)
+{
+    if (m == 0 || n == 0) return BIGCN_OK;
+    if (positions < n || positions % 8 != 0 || (positions >= 64 && positions % 64 != 0)) return BIGCN_EINVAL;
+    if (kind == kI8 && k_bits > 255) return BIGCN_EINVAL;
+    const int per_lane = positions >= 64 ? positions / 64 : 1;
+    const int k = static_cast<int>(k_bits);
+    if (kind == kI8) {
+        EpilogueLayout<int8_t> epi{static_cast<int8_t *>(rows), positions, k, nullptr, 0, 0, nullptr, 0};
+        return dispatch_bitgemm(per_lane, 1, positions, a_bits, m, lda, b_bits, n, ldb, k_bits, 0xffffffffu, epi, stream);
+    }
+    if (kind == kF16) {
+        EpilogueLayout<__half> epi{static_cast<__half *>(rows), positions, k, nullptr, 0, 0, nullptr, 0};
+        return dispatch_bitgemm(per_lane, 1, positions, a_bits, m, lda, b_bits, n, ldb, k_bits, 0xffffffffu, epi, stream);
+    }
+    EpilogueLayout<float> epi{static_cast<float *>(rows), positions, k, nullptr, 0, 0, nullptr, 0};
+    return dispatch_bitgemm(per_lane, 1, positions, a_bits, m, lda, b_bits, n, ldb, k_bits, 0xffffffffu, epi, stream);
+}
+
 // Shapes on which the matrix-core variant measured faster (see the design notes): enough
 // inner dimension to be compute-bound and enough rows and columns to fill its 256 x 64 tiles.
 bool prefer_mfma(int64_t m, int64_t n, int64_t k_bits)

@@ -2,10 +2,18 @@
 // (Sec. 4.2), then, per head,
 //   e_ij = LeakyReLU(a_src . z_i + a_dst . z_j),  a_ij = softmax_{j in N_i} e_ij,
 //   out_i = sum_{j in N_i} a_ij z_j.
-// The attention vectors are not binarised.  Two kernels follow the GEMM: the per-node scores
-// s_i = a_src . z_i and t_i = a_dst . z_i, and the aggregation, which owns a node per wavefront,
-// takes the row maximum of e_ij first and then accumulates exp(e_ij - max) z_j and its sum in a
-// fixed order (run-to-run identical).  A first version: z is kept in fp32 rows.
+// The attention vectors are not binarised.
+//
+// Compact path (every head a multiple of 8 columns wide): the bit-GEMM leaves the integer
+// products of a node as one compact row in column order (one byte per product up to 255 input
+// bits, fp16 up to 2048, fp32 beyond); the row scale beta_j and the scores t_j = a_dst . z_j sit
+// together in a small per-node record.  The aggregation makes ONE pass over the neighbours of
+// a node: per batch of 64 neighbours the running maximum of e_ij is raised and the accumulators
+// rescaled (once per batch and head), so no separate maximum pass gathers the records twice.
+// Long rows are shared by the four wavefronts of a workgroup and merged through LDS.  Sums are
+// taken in a fixed order (run-to-run identical).
+//
+// Plain path (any head width): z kept in fp32 rows, a maximum pass and an accumulation pass.
 #include "bigcn_internal.h"
 
 namespace bigcn {
@@ -14,7 +22,7 @@ constexpr int kGatMaxV = 8;              // columns per lane: d_out <= 512
 
 // s[i][h], t[i][h]: one wavefront per node, lane l takes columns l, l + 64, ...
 template <int H>
-__global__ __launch_bounds__(kBlock) void gat_scores_kernel(const float *__restrict__ z, int64_t n, int d_out, int d_head,
+__global__ __launch_bounds__(kBlock) void gat_scores_plain_kernel(const float *__restrict__ z, int64_t n, int d_out, int d_head,
                                                             const float *__restrict__ a_src,
                                                             const float *__restrict__ a_dst, float *__restrict__ s,
                                                             float *__restrict__ t)
@@ -58,7 +66,7 @@ __device__ __forceinline__ float leaky(float e, float slope) { return e > 0.0f ?
 
 // One wavefront per node, nodes in plan order (longest rows first).
 template <int H>
-__global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const int32_t *__restrict__ row_order, int64_t n,
+__global__ __launch_bounds__(kBlock) void gat_aggregate_plain_kernel(const int32_t *__restrict__ row_order, int64_t n,
                                                                const int64_t *__restrict__ row_ptr,
                                                                const int32_t *__restrict__ col_idx,
                                                                const float *__restrict__ z, int d_out, int d_head,
@@ -161,28 +169,448 @@ __global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const int32_t *__
     }
 }
 
-struct GatMap {
-    size_t bits_off, beta_off, z_off, s_off, t_off, total;
+
+// ---- compact path --------------------------------------------------------------------------
+// Eight stored values of a row -> fp32, multiplied and accumulated.
+template <typename T>
+struct GatSegment;
+template <>
+struct GatSegment<int8_t> {
+    uint2 raw;
+    __device__ __forceinline__ void load(const char *p) { raw = *reinterpret_cast<const uint2 *>(p); }
+    __device__ __forceinline__ float get(int v) const
+    {
+        const uint32_t word = v < 4 ? raw.x : raw.y;
+        return static_cast<float>(static_cast<int>(word << (24 - 8 * (v & 3))) >> 24);
+    }
+};
+template <>
+struct GatSegment<__half> {
+    uint4 raw;
+    __device__ __forceinline__ void load(const char *p) { raw = *reinterpret_cast<const uint4 *>(p); }
+    __device__ __forceinline__ float get(int v) const
+    {
+        const __half2 pair = reinterpret_cast<const __half2 *>(&raw)[v >> 1];
+        return (v & 1) ? __high2float(pair) : __low2float(pair);
+    }
+};
+template <>
+struct GatSegment<float> {
+    float4 lo, hi;
+    __device__ __forceinline__ void load(const char *p)
+    {
+        lo = *reinterpret_cast<const float4 *>(p);
+        hi = *reinterpret_cast<const float4 *>(p + 16);
+    }
+    __device__ __forceinline__ float get(int v) const
+    {
+        const float4 q = v < 4 ? lo : hi;
+        return (v & 3) == 0 ? q.x : ((v & 3) == 1 ? q.y : ((v & 3) == 2 ? q.z : q.w));
+    }
 };
 
-static GatMap map_gat(int64_t n, int64_t d_in, int64_t d_out, int heads)
+// select x[h] for a head index known only at run time (H is small)
+template <int H>
+__device__ __forceinline__ float pick(const float (&x)[H], int h)
 {
-    auto up = [](size_t v) { return (v + 255) & ~static_cast<size_t>(255); };
-    GatMap m;
-    size_t off = 0;
-    m.bits_off = off; off = up(off + static_cast<size_t>(n) * ((d_in + 63) / 64) * 8);
-    m.beta_off = off; off = up(off + static_cast<size_t>(n) * 4);
-    m.z_off = off;    off = up(off + static_cast<size_t>(n) * d_out * 4);
-    m.s_off = off;    off = up(off + static_cast<size_t>(n) * heads * 4);
-    m.t_off = off;    off = up(off + static_cast<size_t>(n) * heads * 4);
-    m.total = off;
-    return m;
+    float r = x[0];
+#pragma unroll
+    for (int q = 1; q < H; ++q) r = h == q ? x[q] : r;
+    return r;
 }
+
+// Scores of the compact path.  Stored value q of column c stands for the product
+// mul * q + bias (mul = 2, bias = K mod 2 for one-byte rows; 1, 0 otherwise), so
+//   s_i[h] = beta_i * (mul * sum_c a_src[c] alpha[c] q_ic + bias * sum_c a_src[c] alpha[c])
+// over the columns c of head h; t_i[h] likewise with a_dst.  One wavefront per node, lane g < G
+// holds columns 8 g .. 8 g + 7 (all in one head).  record[i] = {beta_i, t_i[0..H-1]}.
+template <typename T, int G, int H>
+__global__ __launch_bounds__(kBlock) void gat_scores_kernel(const char *__restrict__ rows, uint32_t row_bytes, int64_t n,
+                                                            int d_out, int d_head, float mul, float bias,
+                                                            const float *__restrict__ beta,
+                                                            const float *__restrict__ alpha,
+                                                            const float *__restrict__ a_src,
+                                                            const float *__restrict__ a_dst, float *__restrict__ s,
+                                                            float *__restrict__ record)
+{
+    constexpr int V = 8;
+    const int lane = lane_id();
+    const bool live = lane < G;
+    const int my_head = live ? (lane * V) / d_head : H;          // H: no head (lanes past the row)
+    float ca[V], cd[V];
+    float sum_a = 0.0f, sum_d = 0.0f;
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int c = lane * V + v;
+        const bool in = live && c < d_out;
+        const float al = in ? alpha[c] : 0.0f;
+        ca[v] = in ? a_src[c] * al : 0.0f;
+        cd[v] = in ? a_dst[c] * al : 0.0f;
+        sum_a += ca[v];
+        sum_d += cd[v];
+    }
+    float const_s[H], const_t[H];
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+        const_s[h] = bias * wave_sum(my_head == h ? sum_a : 0.0f);
+        const_t[h] = bias * wave_sum(my_head == h ? sum_d : 0.0f);
+    }
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block();
+    const int64_t n_waves = static_cast<int64_t>(gridDim.x) * kWavesPerBlock;
+    for (int64_t i = wave; i < n; i += n_waves) {
+        float ps = 0.0f, pt = 0.0f;
+        if (live) {
+            GatSegment<T> seg;
+            seg.load(rows + static_cast<uint64_t>(i) * row_bytes + lane * V * sizeof(T));
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const float q = seg.get(v);
+                ps = fmaf(ca[v], q, ps);
+                pt = fmaf(cd[v], q, pt);
+            }
+        }
+        const float b = beta[i];
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            const float ss = wave_sum(my_head == h ? ps : 0.0f);
+            const float tt = wave_sum(my_head == h ? pt : 0.0f);
+            if (lane == 0) {
+                s[i * H + h] = b * fmaf(mul, ss, const_s[h]);
+                record[i * (H + 1) + 1 + h] = b * fmaf(mul, tt, const_t[h]);
+            }
+        }
+        if (lane == 0) record[i * (H + 1)] = b;
+    }
+}
+
+// Softmax state of one node and head set while its neighbours stream by.
+template <int H>
+struct GatState {
+    float m[H];       // running maximum of e_ij (wave-uniform)
+    float l[H];       // sum of exp(e_ij - m), per-lane partial until reduced
+    float sw[H];      // sum of exp(e_ij - m) beta_j, per-lane partial until reduced
+    float acc[8];     // sum of exp(e_ij - m) beta_j q_j over this lane's columns and slot
+};
+
+// Neighbours p0..p1-1 of node `row`.  wbuf: this wavefront's H x 64 floats of LDS.
+template <typename T, int G, int H>
+__device__ __forceinline__ void gat_accumulate(const int32_t *__restrict__ col_idx, const char *__restrict__ lane_base,
+                                               uint32_t row_bytes, const float *__restrict__ record,
+                                               const float (&si)[H], float slope, int my_head, int64_t p0,
+                                               int64_t p1, int lane, float *wbuf, GatState<H> &st)
+{
+    constexpr int V = 8, S = kWave / G, U = 4;
+    const int slot = lane / G;
+#pragma unroll
+    for (int h = 0; h < H; ++h) { st.m[h] = -INFINITY; st.l[h] = 0.0f; st.sw[h] = 0.0f; }
+#pragma unroll
+    for (int v = 0; v < V; ++v) st.acc[v] = 0.0f;
+
+    for (int64_t pb = p0; pb < p1; pb += kWave) {
+        const int cnt = static_cast<int>(p1 - pb < kWave ? p1 - pb : kWave);     // wave-uniform, >= 1
+        int k = 0;
+        float bk = 0.0f;
+        float e[H];
+#pragma unroll
+        for (int h = 0; h < H; ++h) e[h] = -INFINITY;
+        if (lane < cnt) {
+            k = col_idx[pb + lane];
+            const float *rec = record + static_cast<int64_t>(k) * (H + 1);
+            bk = rec[0];
+#pragma unroll
+            for (int h = 0; h < H; ++h) e[h] = leaky(si[h] + rec[1 + h], slope);
+        }
+        float rescale[H], w[H];
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            const float mn = fmaxf(st.m[h], wave_max(e[h]));
+            rescale[h] = expf(st.m[h] - mn);                 // 0 on the first batch (m = -inf)
+            st.m[h] = mn;
+            const float pe = lane < cnt ? expf(e[h] - mn) : 0.0f;
+            w[h] = pe * bk;
+            st.l[h] = fmaf(st.l[h], rescale[h], pe);
+            st.sw[h] = fmaf(st.sw[h], rescale[h], w[h]);
+        }
+        const float my_rescale = pick<H>(rescale, my_head);
+#pragma unroll
+        for (int v = 0; v < V; ++v) st.acc[v] *= my_rescale;
+        if constexpr (H > 1) {
+            // the weights of this batch, [head][neighbour], for the lanes that load the rows
+#pragma unroll
+            for (int h = 0; h < H; ++h) wbuf[h * kWave + lane] = w[h];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        for (int t = 0; t < cnt; t += S * U) {
+            GatSegment<T> seg[U];
+            float wgt[U];
+            bool present[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int src = t + u * S + slot;
+                present[u] = src < cnt;
+                const int from = present[u] ? src : 0;
+                const int kk = __shfl(k, from, kWave);
+                if constexpr (H > 1) wgt[u] = wbuf[my_head * kWave + from];
+                else wgt[u] = __shfl(w[0], from, kWave);
+                if (present[u]) seg[u].load(lane_base + static_cast<uint64_t>(static_cast<uint32_t>(kk)) * row_bytes);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (present[u]) {
+#pragma unroll
+                    for (int v = 0; v < V; ++v) st.acc[v] = fmaf(wgt[u], seg[u].get(v), st.acc[v]);
+                }
+            }
+        }
+        if constexpr (H > 1) {
+            // the next batch overwrites wbuf: every lane has read its weights
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+    // totals over the lanes (l, sw) and over the slots (acc)
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+        st.l[h] = wave_sum(st.l[h]);
+        st.sw[h] = wave_sum(st.sw[h]);
+    }
+#pragma unroll
+    for (int off = G; off < kWave; off <<= 1)
+#pragma unroll
+        for (int v = 0; v < V; ++v) st.acc[v] += __shfl_xor(st.acc[v], off, kWave);
+}
+
+// out_i[c] = alpha[c] (mul * acc[c] + bias * sw[h]) / l[h]; an empty row gives zeros.
+template <int G, int H>
+__device__ __forceinline__ void gat_finish(const GatState<H> &st, int64_t row, int lane, int my_head, int d_out,
+                                           float mul, float bias, const float *__restrict__ alpha,
+                                           float *__restrict__ out, int64_t ld_out, int vector_store)
+{
+    constexpr int V = 8;
+    if (lane >= G) return;
+    const float l = pick<H>(st.l, my_head);
+    const float inv = l > 0.0f ? 1.0f / l : 0.0f;
+    const float base = bias * pick<H>(st.sw, my_head);
+    float r[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int c = lane * V + v;
+        r[v] = c < d_out ? alpha[c] * fmaf(mul, st.acc[v], base) * inv : 0.0f;
+    }
+    float *dst = out + row * ld_out + lane * V;
+    if (vector_store && lane * V + V <= d_out) {
+        reinterpret_cast<float4 *>(dst)[0] = make_float4(r[0], r[1], r[2], r[3]);
+        reinterpret_cast<float4 *>(dst)[1] = make_float4(r[4], r[5], r[6], r[7]);
+    } else {
+#pragma unroll
+        for (int v = 0; v < V; ++v)
+            if (lane * V + v < d_out) dst[v] = r[v];
+    }
+}
+
+// Nodes in plan order: workgroup b < n_block_rows owns one long row (four wavefronts, contiguous
+// quarters of the neighbour list); every later workgroup owns four nodes, one per wavefront.
+// One-byte rows with one or two heads fit 64 registers: ask for 8 wavefronts per SIMD (the
+// gather hides its latency with resident wavefronts; measured 6 % faster than 7).
+template <typename T, int H>
+constexpr int gat_min_waves()
+{
+    return (sizeof(T) == 1 && H <= 2) ? 8 : 1;
+}
+
+template <typename T, int G, int H>
+__global__ __launch_bounds__(kBlock, (gat_min_waves<T, H>())) void gat_aggregate_kernel(
+    const int32_t *__restrict__ row_order, int64_t n, int64_t n_block_rows, const int64_t *__restrict__ row_ptr,
+    const int32_t *__restrict__ col_idx, const char *__restrict__ rows, uint32_t row_bytes,
+    const float *__restrict__ s, const float *__restrict__ record, const float *__restrict__ alpha, int d_out,
+    int d_head, float mul, float bias, float slope, float *__restrict__ out, int64_t ld_out, int vector_store)
+{
+    constexpr int V = 8;
+    __shared__ float wbuf_all[kWavesPerBlock][H > 1 ? H * kWave : 1];
+    __shared__ float merge[kWavesPerBlock - 1][V + 3 * H][kWave];
+    const int lane = lane_id();
+    const int wave = wave_in_block();
+    const int g = lane & (G - 1);
+    const int my_head = (g * V) / d_head < H ? (g * V) / d_head : H - 1;   // lanes past d_out: any valid head
+    const char *lane_base = rows + static_cast<int64_t>(g) * V * sizeof(T);
+    float *wbuf = wbuf_all[wave];
+    GatState<H> st;
+    float si[H];
+
+    if (static_cast<int64_t>(blockIdx.x) < n_block_rows) {
+        const int64_t row = row_order[blockIdx.x];
+        const int64_t p0 = row_ptr[row], p1 = row_ptr[row + 1];
+        int64_t chunk = (p1 - p0 + kWavesPerBlock - 1) / kWavesPerBlock;
+        chunk = (chunk + kWave - 1) / kWave * kWave;
+        int64_t q0 = p0 + wave * chunk, q1 = q0 + chunk;
+        if (q0 > p1) q0 = p1;
+        if (q1 > p1) q1 = p1;
+#pragma unroll
+        for (int h = 0; h < H; ++h) si[h] = s[row * H + h];
+        gat_accumulate<T, G, H>(col_idx, lane_base, row_bytes, record, si, slope, my_head, q0, q1, lane, wbuf, st);
+        if (wave > 0) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) merge[wave - 1][v][lane] = st.acc[v];
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                merge[wave - 1][V + h][lane] = st.m[h];
+                merge[wave - 1][V + H + h][lane] = st.l[h];
+                merge[wave - 1][V + 2 * H + h][lane] = st.sw[h];
+            }
+        }
+        __syncthreads();
+        if (wave == 0) {
+            // bring the four partial states to the common maximum and add them
+            float top[H];
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                top[h] = st.m[h];
+#pragma unroll
+                for (int w = 0; w < kWavesPerBlock - 1; ++w) top[h] = fmaxf(top[h], merge[w][V + h][lane]);
+            }
+            float f0[H];
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                f0[h] = st.m[h] == -INFINITY ? 0.0f : expf(st.m[h] - top[h]);
+                st.l[h] *= f0[h];
+                st.sw[h] *= f0[h];
+            }
+            const float mine0 = pick<H>(f0, my_head);
+#pragma unroll
+            for (int v = 0; v < V; ++v) st.acc[v] *= mine0;
+#pragma unroll
+            for (int w = 0; w < kWavesPerBlock - 1; ++w) {
+                float f[H];
+#pragma unroll
+                for (int h = 0; h < H; ++h) {
+                    const float mw = merge[w][V + h][lane];
+                    f[h] = mw == -INFINITY ? 0.0f : expf(mw - top[h]);
+                    st.l[h] = fmaf(f[h], merge[w][V + H + h][lane], st.l[h]);
+                    st.sw[h] = fmaf(f[h], merge[w][V + 2 * H + h][lane], st.sw[h]);
+                }
+                const float mine = pick<H>(f, my_head);
+#pragma unroll
+                for (int v = 0; v < V; ++v) st.acc[v] = fmaf(mine, merge[w][v][lane], st.acc[v]);
+            }
+            gat_finish<G, H>(st, row, lane, my_head, d_out, mul, bias, alpha, out, ld_out, vector_store);
+        }
+        return;
+    }
+    const int64_t entry = n_block_rows + (static_cast<int64_t>(blockIdx.x) - n_block_rows) * kWavesPerBlock + wave;
+    if (entry >= n) return;                                    // wave-uniform
+    const int64_t row = row_order[entry];
+#pragma unroll
+    for (int h = 0; h < H; ++h) si[h] = s[row * H + h];
+    gat_accumulate<T, G, H>(col_idx, lane_base, row_bytes, record, si, slope, my_head, row_ptr[row], row_ptr[row + 1],
+                            lane, wbuf, st);
+    gat_finish<G, H>(st, row, lane, my_head, d_out, mul, bias, alpha, out, ld_out, vector_store);
+}
+
+struct GatMap {
+    size_t bits_off, beta_off, z_off, s_off, t_off, total;
+    // compact path: z_off holds the product rows, t_off the records {beta, t[0..H-1]}
+    bool compact;
+    RowKind kind;
+    int groups;           // lanes per row (8 values each)
+    int64_t row_bytes;
+};
 
 static bool gat_shape_ok(int64_t d_in, int64_t d_out, int heads)
 {
     return d_in > 0 && d_in <= BIGCN_MAX_K_BITS && d_out > 0 && d_out <= kWave * kGatMaxV &&
            (heads == 1 || heads == 2 || heads == 4 || heads == 8) && d_out % heads == 0;
+}
+
+static GatMap map_gat(int64_t n, int64_t d_in, int64_t d_out, int heads)
+{
+    auto up = [](size_t v) { return (v + 255) & ~static_cast<size_t>(255); };
+    GatMap m;
+    m.compact = (d_out / heads) % 8 == 0;
+    m.kind = d_in <= 255 ? kI8 : (d_in <= 2048 ? kF16 : kF32);
+    m.groups = 2;
+    while (m.groups < kWave && m.groups * 8 < d_out) m.groups <<= 1;
+    m.row_bytes = static_cast<int64_t>(m.groups) * 8 * (m.kind == kI8 ? 1 : (m.kind == kF16 ? 2 : 4));
+    size_t off = 0;
+    m.bits_off = off; off = up(off + static_cast<size_t>(n) * ((d_in + 63) / 64) * 8);
+    m.beta_off = off; off = up(off + static_cast<size_t>(n) * 4);
+    m.z_off = off;    off = up(off + static_cast<size_t>(n) * (m.compact ? m.row_bytes : d_out * 4));
+    m.s_off = off;    off = up(off + static_cast<size_t>(n) * heads * 4);
+    m.t_off = off;    off = up(off + static_cast<size_t>(n) * (heads + (m.compact ? 1 : 0)) * 4);
+    m.total = off;
+    return m;
+}
+
+template <typename T, int G, int H>
+static int launch_gat_compact(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx, int64_t n,
+                              const GatMap &map, const char *rows, const float *beta, const float *alpha,
+                              const float *a_src, const float *a_dst, float *s, float *record, int64_t d_in,
+                              int64_t d_out, float slope, float *out, int64_t ld_out, hipStream_t st)
+{
+    const float mul = sizeof(T) == 1 ? 2.0f : 1.0f;
+    const float bias = sizeof(T) == 1 ? static_cast<float>(d_in & 1) : 0.0f;
+    const int d_head = static_cast<int>(d_out / H);
+    const int64_t node_blocks = (n + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t score_blocks = node_blocks > 256 * 8 ? 256 * 8 : node_blocks;
+    hipLaunchKernelGGL((gat_scores_kernel<T, G, H>), dim3(static_cast<unsigned>(score_blocks)), dim3(kBlock), 0, st,
+                       rows, static_cast<uint32_t>(map.row_bytes), n, static_cast<int>(d_out), d_head, mul, bias, beta,
+                       alpha, a_src, a_dst, s, record);
+    if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
+    const int64_t wave_rows = n - plan->n_block_rows;
+    const int64_t blocks = plan->n_block_rows + (wave_rows + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int vector_store = (ld_out % 4 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0) ? 1 : 0;
+    hipLaunchKernelGGL((gat_aggregate_kernel<T, G, H>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st,
+                       plan->row_order, n, plan->n_block_rows, row_ptr, col_idx, rows,
+                       static_cast<uint32_t>(map.row_bytes), s, record, alpha, static_cast<int>(d_out), d_head, mul,
+                       bias, slope, out, ld_out, vector_store);
+    return check_launch();
+}
+
+template <typename T, int H>
+static int launch_gat_compact_groups(int groups, const bigcn_plan *plan, const int64_t *row_ptr,
+                                     const int32_t *col_idx, int64_t n, const GatMap &map, const char *rows,
+                                     const float *beta, const float *alpha, const float *a_src, const float *a_dst,
+                                     float *s, float *record, int64_t d_in, int64_t d_out, float slope, float *out,
+                                     int64_t ld_out, hipStream_t st)
+{
+#define BIGCN_GAT_GROUPS(GG)                                                                                        \
+    case GG:                                                                                                        \
+        return launch_gat_compact<T, GG, H>(plan, row_ptr, col_idx, n, map, rows, beta, alpha, a_src, a_dst, s,    \
+                                            record, d_in, d_out, slope, out, ld_out, st)
+    switch (groups) {
+        BIGCN_GAT_GROUPS(2);
+        BIGCN_GAT_GROUPS(4);
+        BIGCN_GAT_GROUPS(8);
+        BIGCN_GAT_GROUPS(16);
+        BIGCN_GAT_GROUPS(32);
+        BIGCN_GAT_GROUPS(64);
+    default:
+        return BIGCN_EINVAL;
+    }
+#undef BIGCN_GAT_GROUPS
+}
+
+template <typename T>
+static int launch_gat_compact_heads(int heads, int groups, const bigcn_plan *plan, const int64_t *row_ptr,
+                                    const int32_t *col_idx, int64_t n, const GatMap &map, const char *rows,
+                                    const float *beta, const float *alpha, const float *a_src, const float *a_dst,
+                                    float *s, float *record, int64_t d_in, int64_t d_out, float slope, float *out,
+                                    int64_t ld_out, hipStream_t st)
+{
+#define BIGCN_GAT_HEADS(HH)                                                                                         \
+    case HH:                                                                                                        \
+        return launch_gat_compact_groups<T, HH>(groups, plan, row_ptr, col_idx, n, map, rows, beta, alpha, a_src,  \
+                                                a_dst, s, record, d_in, d_out, slope, out, ld_out, st)
+    switch (heads) {
+        BIGCN_GAT_HEADS(1);
+        BIGCN_GAT_HEADS(2);
+        BIGCN_GAT_HEADS(4);
+        BIGCN_GAT_HEADS(8);
+    default:
+        return BIGCN_ESHAPE;
+    }
+#undef BIGCN_GAT_HEADS
 }
 
 }  // namespace bigcn
@@ -217,13 +645,30 @@ extern "C" int bigcn_gat_layer(const bigcn_plan *plan, const int64_t *row_ptr, c
     char *ws = static_cast<char *>(workspace);
     uint64_t *bits = reinterpret_cast<uint64_t *>(ws + map.bits_off);
     float *beta = reinterpret_cast<float *>(ws + map.beta_off);
-    float *z = reinterpret_cast<float *>(ws + map.z_off);
     float *s = reinterpret_cast<float *>(ws + map.s_off);
     float *t = reinterpret_cast<float *>(ws + map.t_off);
     const int64_t words = (d_in + 63) / 64;
 
     int rc = launch_pack(x, n, d_in, ld_x, 1, bn_shift, bn_mul, nullptr, 0, bits, words, beta, st);
     if (rc != BIGCN_OK) return rc;
+
+    if (map.compact) {
+        char *rows = ws + map.z_off;
+        rc = launch_bitgemm_natural(bits, n, words, w_bits, d_out, ld_words, d_in, rows, map.groups * 8, map.kind, st);
+        if (rc != BIGCN_OK) return rc;
+        if (map.kind == kI8)
+            return launch_gat_compact_heads<int8_t>(heads, map.groups, plan, row_ptr, col_idx, n, map, rows, beta,
+                                                    alpha, a_src, a_dst, s, t, d_in, d_out, negative_slope, out,
+                                                    ld_out, st);
+        if (map.kind == kF16)
+            return launch_gat_compact_heads<__half>(heads, map.groups, plan, row_ptr, col_idx, n, map, rows, beta,
+                                                    alpha, a_src, a_dst, s, t, d_in, d_out, negative_slope, out,
+                                                    ld_out, st);
+        return launch_gat_compact_heads<float>(heads, map.groups, plan, row_ptr, col_idx, n, map, rows, beta, alpha,
+                                               a_src, a_dst, s, t, d_in, d_out, negative_slope, out, ld_out, st);
+    }
+
+    float *z = reinterpret_cast<float *>(ws + map.z_off);
     rc = bigcn_binary_gemm(bits, beta, n, words, w_bits, alpha, d_out, ld_words, d_in, nullptr, 0, z, d_out, stream);
     if (rc != BIGCN_OK) return rc;
 
@@ -232,10 +677,10 @@ extern "C" int bigcn_gat_layer(const bigcn_plan *plan, const int64_t *row_ptr, c
     const int64_t score_blocks = blocks > 256 * 32 ? 256 * 32 : blocks;
 #define BIGCN_GAT_CASE(HH)                                                                                          \
     case HH:                                                                                                        \
-        hipLaunchKernelGGL(gat_scores_kernel<HH>, dim3(static_cast<unsigned>(score_blocks)), dim3(kBlock), 0, st, z, n, \
+        hipLaunchKernelGGL(gat_scores_plain_kernel<HH>, dim3(static_cast<unsigned>(score_blocks)), dim3(kBlock), 0, st, z, n, \
                            static_cast<int>(d_out), d_head, a_src, a_dst, s, t);                                    \
         if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;                                                     \
-        hipLaunchKernelGGL(gat_aggregate_kernel<HH>, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st,      \
+        hipLaunchKernelGGL(gat_aggregate_plain_kernel<HH>, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st,      \
                            plan->row_order, n, row_ptr, col_idx, z, static_cast<int>(d_out), d_head, s, t,          \
                            negative_slope, out, ld_out);                                                            \
         break

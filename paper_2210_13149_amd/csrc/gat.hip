@@ -222,8 +222,11 @@ __device__ __forceinline__ float pick(const float (&x)[H], int h)
 // Scores of the compact path.  Stored value q of column c stands for the product
 // mul * q + bias (mul = 2, bias = K mod 2 for one-byte rows; 1, 0 otherwise), so
 //   s_i[h] = beta_i * (mul * sum_c a_src[c] alpha[c] q_ic + bias * sum_c a_src[c] alpha[c])
-// over the columns c of head h; t_i[h] likewise with a_dst.  One wavefront per node, lane g < G
-// holds columns 8 g .. 8 g + 7 (all in one head).  record[i] = {beta_i, t_i[0..H-1]}.
+// over the columns c of head h; t_i[h] likewise with a_dst.  A wavefront takes 64 / G nodes at a
+// time, lane g of a node's G lanes holding columns 8 g .. 8 g + 7 (all in one head).  When a head
+// spans a power-of-two number of lanes its sums are a butterfly inside that lane group;
+// otherwise one masked sum over the wavefront per head (one node at a time).
+// record[i] = {beta_i, t_i[0..H-1]}.
 template <typename T, int G, int H>
 __global__ __launch_bounds__(kBlock) void gat_scores_kernel(const char *__restrict__ rows, uint32_t row_bytes, int64_t n,
                                                             int d_out, int d_head, float mul, float bias,
@@ -235,13 +238,18 @@ __global__ __launch_bounds__(kBlock) void gat_scores_kernel(const char *__restri
 {
     constexpr int V = 8;
     const int lane = lane_id();
-    const bool live = lane < G;
-    const int my_head = live ? (lane * V) / d_head : H;          // H: no head (lanes past the row)
+    const int g = lane & (G - 1);
+    const int lanes_per_head = d_head / V;
+    const bool butterfly = (lanes_per_head & (lanes_per_head - 1)) == 0;         // wave-uniform
+    const int nodes_per_step = butterfly ? kWave / G : 1;
+    const int slot = lane / G;
+    const int my_head = g / lanes_per_head;                    // >= H: lanes past the last head
+    const bool live = my_head < H && slot < nodes_per_step;
     float ca[V], cd[V];
     float sum_a = 0.0f, sum_d = 0.0f;
 #pragma unroll
     for (int v = 0; v < V; ++v) {
-        const int c = lane * V + v;
+        const int c = g * V + v;
         const bool in = live && c < d_out;
         const float al = in ? alpha[c] : 0.0f;
         ca[v] = in ? a_src[c] * al : 0.0f;
@@ -249,19 +257,32 @@ __global__ __launch_bounds__(kBlock) void gat_scores_kernel(const char *__restri
         sum_a += ca[v];
         sum_d += cd[v];
     }
+    // per-head constants bias * sum_c a[c] alpha[c]: this lane's own head (butterfly) or all heads
     float const_s[H], const_t[H];
+    if (butterfly) {
+        for (int off = 1; off < lanes_per_head; off <<= 1) {
+            sum_a += __shfl_xor(sum_a, off, kWave);
+            sum_d += __shfl_xor(sum_d, off, kWave);
+        }
 #pragma unroll
-    for (int h = 0; h < H; ++h) {
-        const_s[h] = bias * wave_sum(my_head == h ? sum_a : 0.0f);
-        const_t[h] = bias * wave_sum(my_head == h ? sum_d : 0.0f);
+        for (int h = 0; h < H; ++h) { const_s[h] = bias * sum_a; const_t[h] = bias * sum_d; }
+    } else {
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            const_s[h] = bias * wave_sum(live && my_head == h ? sum_a : 0.0f);
+            const_t[h] = bias * wave_sum(live && my_head == h ? sum_d : 0.0f);
+        }
     }
     const int64_t wave = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block();
     const int64_t n_waves = static_cast<int64_t>(gridDim.x) * kWavesPerBlock;
-    for (int64_t i = wave; i < n; i += n_waves) {
-        float ps = 0.0f, pt = 0.0f;
-        if (live) {
+    for (int64_t i0 = wave * nodes_per_step; i0 < n; i0 += n_waves * nodes_per_step) {
+        const int64_t i = i0 + (butterfly ? slot : 0);
+        const bool mine = live && i < n;
+        float ps = 0.0f, pt = 0.0f, b = 0.0f;
+        if (mine) {
             GatSegment<T> seg;
-            seg.load(rows + static_cast<uint64_t>(i) * row_bytes + lane * V * sizeof(T));
+            seg.load(rows + static_cast<uint64_t>(i) * row_bytes + g * V * sizeof(T));
+            b = beta[i];
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 const float q = seg.get(v);
@@ -269,17 +290,29 @@ __global__ __launch_bounds__(kBlock) void gat_scores_kernel(const char *__restri
                 pt = fmaf(cd[v], q, pt);
             }
         }
-        const float b = beta[i];
-#pragma unroll
-        for (int h = 0; h < H; ++h) {
-            const float ss = wave_sum(my_head == h ? ps : 0.0f);
-            const float tt = wave_sum(my_head == h ? pt : 0.0f);
-            if (lane == 0) {
-                s[i * H + h] = b * fmaf(mul, ss, const_s[h]);
-                record[i * (H + 1) + 1 + h] = b * fmaf(mul, tt, const_t[h]);
+        if (butterfly) {
+            for (int off = 1; off < lanes_per_head; off <<= 1) {
+                ps += __shfl_xor(ps, off, kWave);
+                pt += __shfl_xor(pt, off, kWave);
             }
+            if (mine && g == my_head * lanes_per_head) {            // first lane of the head's group
+                s[i * H + my_head] = b * fmaf(mul, ps, const_s[0]);
+                record[i * (H + 1) + 1 + my_head] = b * fmaf(mul, pt, const_t[0]);
+                if (g == 0) record[i * (H + 1)] = b;
+            }
+        } else {
+            const float b0 = __shfl(b, 0, kWave);
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                const float ss = wave_sum(mine && my_head == h ? ps : 0.0f);
+                const float tt = wave_sum(mine && my_head == h ? pt : 0.0f);
+                if (lane == 0) {
+                    s[i * H + h] = b0 * fmaf(mul, ss, const_s[h]);
+                    record[i * (H + 1) + 1 + h] = b0 * fmaf(mul, tt, const_t[h]);
+                }
+            }
+            if (lane == 0) record[i * (H + 1)] = b0;
         }
-        if (lane == 0) record[i * (H + 1)] = b;
     }
 }
 

@@ -286,6 +286,10 @@ int bigcn_predict(const float *logits, int64_t n, int64_t d, int64_t ld, int32_t
  *   workspace : at least bigcn_layer_backward_workspace_bytes(n, d_in, d_out) bytes, 256-byte
  *               aligned (holds g_zeta, both packings of w and the partial sums over node chunks)
  * Sums over the nodes are taken in a fixed order: results are run-to-run identical.
+ * Without g_in and with d_in <= d_out (the first layer of a model) g_wt is evaluated as
+ * (A~ H~)^T g_out, the same value since A~ is symmetric: the aggregation then gathers packed sign
+ * rows instead of fp32 gradient rows.  Its rounding differs from the other order's in the last
+ * bits, so g_w with and without g_in need not be bit-identical for such shapes.
  * Errors: ENULL, EINVAL (n differs from the plan's, sizes <= 0, leading dimensions too small),
  * ESHAPE (d_in or d_out > BIGCN_MAX_K_BITS), EWORKSPACE.  The size query returns 0 for invalid
  * arguments.

@@ -11,6 +11,11 @@
 // vector operations per value, hidden behind the 64-cycle multiply), the scales beta / alpha are
 // folded into the fp32 operand while it is staged through LDS.
 //
+// First layer (no input gradient wanted, d_in <= d_out): g_wt = H~^T (A~ g_out) = (A~ H~)^T g_out,
+// because A~ is symmetric.  U = A~ H~ gathers packed sign rows (d_in / 8 bytes + one scale per
+// neighbour) instead of fp32 gradient rows (4 d_out bytes): the packed word of a neighbour is used
+// directly as the lane mask of a conditional add (lane l owns column 64 w + l).
+//
 // Operand layout of the 32x32x2 multiply, lane l:  A[i = l % 32][k = l / 32],
 // B[k = l / 32][j = l % 32]; accumulator register r holds row 8 (r / 4) + 4 (l / 32) + r % 4 and
 // column l % 32.
@@ -196,6 +201,141 @@ __global__ __launch_bounds__(kBlock) void backward_weight_partial_kernel(
         }
 }
 
+// ---- U = A~ H~ from packed signs ---------------------------------------------------------------
+// U[i][c] = sum_p vals[p] beta_k (2 bit_kc - 1) = 2 P[i][c] - W_i over the neighbours k of node i,
+// P = sum over the neighbours whose bit is set, W = sum of all weights.  One wavefront per node
+// (plan order); 64 neighbours are fetched at a time, lane j holding neighbour j's weight and its
+// NW packed words of this pass; the words are broadcast one neighbour at a time and act as the
+// lane mask of the add.  Neighbours are added in list order (run-to-run identical).
+template <int NW>
+__global__ __launch_bounds__(kBlock) void aggregate_signs_kernel(
+    const int32_t *__restrict__ row_order, int64_t n, const int64_t *__restrict__ row_ptr,
+    const int32_t *__restrict__ col_idx, const float *__restrict__ vals, const uint64_t *__restrict__ f_bits,
+    int64_t ld_f, const float *__restrict__ beta, int d_in, int word0, float *__restrict__ u, int64_t ld_u)
+{
+    const int lane = lane_id();
+    const int64_t entry = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block();
+    if (entry >= n) return;                                    // wave-uniform
+    const int64_t row = row_order[entry];
+    const int64_t p0 = row_ptr[row], p1 = row_ptr[row + 1];
+    const int n_words = (d_in + 63) >> 6;
+
+    float set_sum[NW];
+#pragma unroll
+    for (int q = 0; q < NW; ++q) set_sum[q] = 0.0f;
+    float all_sum = 0.0f;                                      // per-lane partial of W
+    for (int64_t pb = p0; pb < p1; pb += kWave) {
+        const int cnt = static_cast<int>(p1 - pb < kWave ? p1 - pb : kWave);
+        float wk = 0.0f;
+        uint32_t lo[NW], hi[NW];
+#pragma unroll
+        for (int q = 0; q < NW; ++q) { lo[q] = 0u; hi[q] = 0u; }
+        if (lane < cnt) {
+            const int64_t k = col_idx[pb + lane];
+            wk = (vals != nullptr ? vals[pb + lane] : 1.0f) * beta[k];
+#pragma unroll
+            for (int q = 0; q < NW; ++q) {
+                if (word0 + q < n_words) {
+                    const uint64_t word = f_bits[k * ld_f + word0 + q];
+                    lo[q] = static_cast<uint32_t>(word);
+                    hi[q] = static_cast<uint32_t>(word >> 32);
+                }
+            }
+        }
+        all_sum += wk;
+        for (int t = 0; t < cnt; ++t) {
+            const float wt = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wk), t));
+#pragma unroll
+            for (int q = 0; q < NW; ++q) {
+                const uint64_t mask = static_cast<uint64_t>(static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(lo[q]), t))) |
+                                      (static_cast<uint64_t>(static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(hi[q]), t))) << 32);
+                set_sum[q] += __builtin_amdgcn_inverse_ballot_w64(mask) ? wt : 0.0f;
+            }
+        }
+    }
+    const float total = wave_sum(all_sum);
+#pragma unroll
+    for (int q = 0; q < NW; ++q) {
+        const int c = 64 * (word0 + q) + lane;
+        if (c < d_in) u[row * ld_u + c] = fmaf(2.0f, set_sum[q], -total);
+    }
+}
+
+// ---- partial g_wt = U^T g_out over a chunk of nodes (both operands fp32) --------------------------
+// Workgroup (chunk, j block of 64, t block of 128): wavefront w owns t = 32 w .. 32 w + 31 x two
+// j tiles.  Per step 32 nodes go through LDS: g_out[i][j] and U[i][t]; the next step's values are
+// fetched into registers while the current step is multiplied.
+constexpr int kDenseStage = 32;
+
+__global__ __launch_bounds__(kBlock) void backward_weight_dense_partial_kernel(
+    const float *__restrict__ g_out, int64_t n, int d_out, int64_t ld_g, const float *__restrict__ u, int64_t ld_u,
+    int d_in, int64_t rows_per_chunk, float *__restrict__ partial)
+{
+    __shared__ float slab[kDenseStage][64 + 1];           // [node][j]
+    __shared__ float utile[kDenseStage][128 + 1];         // [node][t]
+    const int lane = lane_id();
+    const int wave = wave_in_block();
+    const int i32 = lane & 31, half = lane >> 5;
+    const int j0 = blockIdx.y * 64;
+    const int t0 = blockIdx.z * 128;
+    const int64_t i_begin = static_cast<int64_t>(blockIdx.x) * rows_per_chunk;
+    const int64_t i_end = i_begin + rows_per_chunk < n ? i_begin + rows_per_chunk : n;
+
+    v16f acc[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[b][r] = 0.0f;
+
+    // this thread's share of a step: 8 values of g_out (rows gr + 4 it) and 16 of U (rows ur + 2 it)
+    const int gc = threadIdx.x & 63, gr = threadIdx.x >> 6;
+    const int uc = threadIdx.x & 127, ur = threadIdx.x >> 7;
+    const bool g_col_in = j0 + gc < d_out, u_col_in = t0 + uc < d_in;
+    float g_next[kDenseStage / 4], u_next[kDenseStage / 2];
+    auto fetch = [&](int64_t i0) {
+#pragma unroll
+        for (int it = 0; it < kDenseStage / 4; ++it) {
+            const int64_t row = i0 + gr + 4 * it;
+            g_next[it] = (row < i_end && g_col_in) ? g_out[row * ld_g + j0 + gc] : 0.0f;
+        }
+#pragma unroll
+        for (int it = 0; it < kDenseStage / 2; ++it) {
+            const int64_t row = i0 + ur + 2 * it;
+            u_next[it] = (row < i_end && u_col_in) ? u[row * ld_u + t0 + uc] : 0.0f;
+        }
+    };
+    if (i_begin < i_end) fetch(i_begin);
+    for (int64_t i0 = i_begin; i0 < i_end; i0 += kDenseStage) {
+        __syncthreads();                                  // every wavefront has left the previous step
+#pragma unroll
+        for (int it = 0; it < kDenseStage / 4; ++it) slab[gr + 4 * it][gc] = g_next[it];
+#pragma unroll
+        for (int it = 0; it < kDenseStage / 2; ++it) utile[ur + 2 * it][uc] = u_next[it];
+        __syncthreads();
+        if (i0 + kDenseStage < i_end) fetch(i0 + kDenseStage);       // in flight during the multiplies
+#pragma unroll 4
+        for (int s = 0; s < kDenseStage / 2; ++s) {
+            const int node = 2 * s + half;
+            const float a = utile[node][32 * wave + i32];
+            const float b0 = slab[node][i32];
+            const float b1 = slab[node][32 + i32];
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b0, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc[1], 0, 0, 0);
+        }
+    }
+    float *dst = partial + static_cast<int64_t>(blockIdx.x) * d_in * d_out;
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int j = j0 + 32 * b + i32;
+        if (j >= d_out) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int t = t0 + 32 * wave + 8 * (r >> 2) + 4 * half + (r & 3);
+            if (t < d_in) dst[static_cast<int64_t>(t) * d_out + j] = acc[b][r];
+        }
+    }
+}
+
 // g_wt[t][j] = sum over chunks (in chunk order, fp64), written as fp32.
 __global__ __launch_bounds__(kBlock) void backward_weight_reduce_kernel(const float *__restrict__ partial,
                                                                         int64_t chunks, int64_t elems,
@@ -312,16 +452,42 @@ extern "C" int bigcn_layer_backward(const bigcn_plan *plan, const int64_t *row_p
     rc = launch_pack(w, d_out, d_in, 1, ld_w, nullptr, nullptr, nullptr, 0, w_bits, wb_ld, alpha, s);
     if (rc != BIGCN_OK) return rc;
 
-    // Algorithm 1, first line: A~ is symmetric (the plan's pattern check guarantees the pattern,
-    // the coefficients D^-1/2 (A+I) D^-1/2 are symmetric by construction), so A~^T g = A~ g
-    rc = bigcn_spmm(plan, row_ptr, col_idx, vals, n, g_out, d_out, ld_g, g_zeta, d_out, stream);
-    if (rc != BIGCN_OK) return rc;
+    if (g_in == nullptr && d_in <= d_out) {
+        // first layer: g_wt = (A~ H~)^T g_out; U = A~ H~ (n x d_in) takes the place of g_zeta
+        float *u = g_zeta;
+        const int64_t node_blocks = (n + kWavesPerBlock - 1) / kWavesPerBlock;
+        const int n_words = static_cast<int>((d_in + 63) / 64);
+        for (int word0 = 0; word0 < n_words; word0 += 4) {
+#define BIGCN_SIGNS_CASE(NW)                                                                                        \
+    hipLaunchKernelGGL(aggregate_signs_kernel<NW>, dim3(static_cast<unsigned>(node_blocks)), dim3(kBlock), 0, s,   \
+                       plan->row_order, n, row_ptr, col_idx, vals, f_bits, ld_f_words, beta,                       \
+                       static_cast<int>(d_in), word0, u, d_in)
+            const int left = n_words - word0;
+            if (left >= 4) BIGCN_SIGNS_CASE(4);
+            else if (left == 3) BIGCN_SIGNS_CASE(3);
+            else if (left == 2) BIGCN_SIGNS_CASE(2);
+            else BIGCN_SIGNS_CASE(1);
+#undef BIGCN_SIGNS_CASE
+            if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
+        }
+        const dim3 grid_d(static_cast<unsigned>(map.chunks), static_cast<unsigned>((d_out + 63) / 64),
+                          static_cast<unsigned>((d_in + 127) / 128));
+        hipLaunchKernelGGL(backward_weight_dense_partial_kernel, grid_d, dim3(kBlock), 0, s, g_out, n,
+                           static_cast<int>(d_out), ld_g, u, d_in, static_cast<int>(d_in), map.rows_per_chunk, partial);
+        if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
+    } else {
+        // Algorithm 1, first line: A~ is symmetric (the plan's pattern check guarantees the pattern,
+        // the coefficients D^-1/2 (A+I) D^-1/2 are symmetric by construction), so A~^T g = A~ g
+        rc = bigcn_spmm(plan, row_ptr, col_idx, vals, n, g_out, d_out, ld_g, g_zeta, d_out, stream);
+        if (rc != BIGCN_OK) return rc;
 
-    const dim3 grid_w(static_cast<unsigned>(map.chunks), static_cast<unsigned>((d_out + 63) / 64),
-                      static_cast<unsigned>((d_in + 255) / 256));
-    hipLaunchKernelGGL(backward_weight_partial_kernel, grid_w, dim3(kBlock), 0, s, g_zeta, n, static_cast<int>(d_out),
-                       d_out, beta, f_bits, ld_f_words, static_cast<int>(d_in), map.rows_per_chunk, partial);
-    if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
+        const dim3 grid_w(static_cast<unsigned>(map.chunks), static_cast<unsigned>((d_out + 63) / 64),
+                          static_cast<unsigned>((d_in + 255) / 256));
+        hipLaunchKernelGGL(backward_weight_partial_kernel, grid_w, dim3(kBlock), 0, s, g_zeta, n,
+                           static_cast<int>(d_out), d_out, beta, f_bits, ld_f_words, static_cast<int>(d_in),
+                           map.rows_per_chunk, partial);
+        if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
+    }
     const int64_t elems = d_in * d_out;
     hipLaunchKernelGGL(backward_weight_reduce_kernel, dim3(static_cast<unsigned>((elems + kBlock - 1) / kBlock)),
                        dim3(kBlock), 0, s, partial, map.chunks, elems, g_wt);

@@ -336,6 +336,20 @@ __global__ __launch_bounds__(kBlock) void backward_weight_dense_partial_kernel(
     }
 }
 
+// Rows of d floats copied into rows of dp >= d floats (dp a multiple of 4), the tail zeroed: the
+// aggregation reads 16 bytes per lane only from rows that are 16-byte aligned.
+__global__ __launch_bounds__(kBlock) void pad_rows_kernel(const float *__restrict__ src, int64_t ld_src, int64_t n,
+                                                          int d, int dp, float *__restrict__ dst)
+{
+    const int64_t total = n * dp;
+    for (int64_t e = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; e < total;
+         e += static_cast<int64_t>(gridDim.x) * kBlock) {
+        const int64_t row = e / dp;
+        const int c = static_cast<int>(e - row * dp);
+        dst[e] = c < d ? src[row * ld_src + c] : 0.0f;
+    }
+}
+
 // g_wt[t][j] = sum over chunks (in chunk order, fp64), written as fp32.
 __global__ __launch_bounds__(kBlock) void backward_weight_reduce_kernel(const float *__restrict__ partial,
                                                                         int64_t chunks, int64_t elems,
@@ -374,7 +388,8 @@ __global__ __launch_bounds__(kWave) void backward_weight_finish_kernel(
 }
 
 struct BackwardMap {
-    size_t g_zeta_off, wt_bits_off, scratch_scale_off, w_bits_off, alpha_off, g_wt_off, partial_off, total;
+    size_t g_zeta_off, g_pad_off, wt_bits_off, scratch_scale_off, w_bits_off, alpha_off, g_wt_off, partial_off, total;
+    int64_t d_pad;        // row stride of g_zeta: d_out rounded up to a multiple of 4
     int64_t chunks, rows_per_chunk;
 };
 
@@ -395,7 +410,10 @@ static BackwardMap map_backward(int64_t n, int64_t d_in, int64_t d_out)
     if (m.chunks < 1) m.chunks = 1;
     m.rows_per_chunk = rpc;
     size_t off = 0;
-    m.g_zeta_off = off;        off = align256(off + static_cast<size_t>(n) * d_out * sizeof(float));
+    m.d_pad = (d_out + 3) / 4 * 4;
+    m.g_zeta_off = off;        off = align256(off + static_cast<size_t>(n) * m.d_pad * sizeof(float));
+    m.g_pad_off = off;         // padded copy of g_out, only when d_out is not a multiple of 4
+    if (m.d_pad != d_out) off = align256(off + static_cast<size_t>(n) * m.d_pad * sizeof(float));
     m.wt_bits_off = off;       off = align256(off + static_cast<size_t>(d_in) * ((d_out + 63) / 64) * sizeof(uint64_t));
     m.scratch_scale_off = off; off = align256(off + static_cast<size_t>(d_in) * sizeof(float));
     m.w_bits_off = off;        off = align256(off + static_cast<size_t>(d_out) * ((d_in + 63) / 64) * sizeof(uint64_t));
@@ -478,13 +496,26 @@ extern "C" int bigcn_layer_backward(const bigcn_plan *plan, const int64_t *row_p
     } else {
         // Algorithm 1, first line: A~ is symmetric (the plan's pattern check guarantees the pattern,
         // the coefficients D^-1/2 (A+I) D^-1/2 are symmetric by construction), so A~^T g = A~ g
-        rc = bigcn_spmm(plan, row_ptr, col_idx, vals, n, g_out, d_out, ld_g, g_zeta, d_out, stream);
+        if (map.d_pad != d_out) {
+            // rows of a width that is not a multiple of 4 floats (class counts such as 47) would take
+            // the one-float-per-lane path of the aggregation: aggregate a zero-padded copy instead
+            float *g_pad = reinterpret_cast<float *>(ws + map.g_pad_off);
+            const int64_t total = n * map.d_pad;
+            int64_t blocks = (total + kBlock - 1) / kBlock;
+            if (blocks > 256 * 32) blocks = 256 * 32;
+            hipLaunchKernelGGL(pad_rows_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s, g_out, ld_g, n,
+                               static_cast<int>(d_out), static_cast<int>(map.d_pad), g_pad);
+            if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
+            rc = bigcn_spmm(plan, row_ptr, col_idx, vals, n, g_pad, map.d_pad, map.d_pad, g_zeta, map.d_pad, stream);
+        } else {
+            rc = bigcn_spmm(plan, row_ptr, col_idx, vals, n, g_out, d_out, ld_g, g_zeta, map.d_pad, stream);
+        }
         if (rc != BIGCN_OK) return rc;
 
         const dim3 grid_w(static_cast<unsigned>(map.chunks), static_cast<unsigned>((d_out + 63) / 64),
                           static_cast<unsigned>((d_in + 255) / 256));
         hipLaunchKernelGGL(backward_weight_partial_kernel, grid_w, dim3(kBlock), 0, s, g_zeta, n,
-                           static_cast<int>(d_out), d_out, beta, f_bits, ld_f_words, static_cast<int>(d_in),
+                           static_cast<int>(d_out), map.d_pad, beta, f_bits, ld_f_words, static_cast<int>(d_in),
                            map.rows_per_chunk, partial);
         if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
     }
@@ -499,7 +530,7 @@ extern "C" int bigcn_layer_backward(const bigcn_plan *plan, const int64_t *row_p
     if (g_in != nullptr) {
         const dim3 grid_i(static_cast<unsigned>((n + 127) / 128), static_cast<unsigned>((d_in + 127) / 128));
         hipLaunchKernelGGL(backward_input_kernel, grid_i, dim3(kBlock), 0, s, g_zeta, n, static_cast<int>(d_out),
-                           d_out, alpha, wt_bits, wt_ld, static_cast<int>(d_in), bn_mul, g_in, ld_gin);
+                           map.d_pad, alpha, wt_bits, wt_ld, static_cast<int>(d_in), bn_mul, g_in, ld_gin);
         if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
     }
     return BIGCN_OK;

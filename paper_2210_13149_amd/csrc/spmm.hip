@@ -104,12 +104,18 @@ struct Segment<__half, 8> {
         }
     }
 };
+// four signed bytes -> fp32 (sign-extending bit-field extract, then convert), multiplied and
+// accumulated.  kCarrier: the first byte holds a 7-bit value under a foreign top bit (a bit of
+// the row's scale) and is sign-extended from its bit 6.
+template <bool kCarrier>
 __device__ __forceinline__ void fma_bytes(float w, uint32_t word, float *acc)
 {
-    // four signed bytes -> fp32 (sign-extending bit-field extract, then convert)
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-        acc[e] = fmaf(w, static_cast<float>(static_cast<int>(word << (24 - 8 * e)) >> 24), acc[e]);
+    for (int e = 0; e < 4; ++e) {
+        const int value = (kCarrier && e == 0) ? (static_cast<int>(word << 25) >> 25)
+                                               : (static_cast<int>(word << (24 - 8 * e)) >> 24);
+        acc[e] = fmaf(w, static_cast<float>(value), acc[e]);
+    }
 }
 template <>
 struct Segment<int8_t, 8> {
@@ -117,24 +123,28 @@ struct Segment<int8_t, 8> {
     __device__ __forceinline__ void load(const char *p) { raw = *reinterpret_cast<const uint2 *>(p); }
     __device__ __forceinline__ void fma(float w, float (&acc)[8]) const
     {
-        fma_bytes(w, raw.x, acc);
-        fma_bytes(w, raw.y, acc + 4);
+        fma_bytes<false>(w, raw.x, acc);
+        fma_bytes<false>(w, raw.y, acc + 4);
+    }
+    // rows that carry scale bits in the top bit of the first byte (and, kMiddle, of the fifth)
+    template <bool kMiddle>
+    __device__ __forceinline__ void fma_carrier(float w, float (&acc)[8]) const
+    {
+        fma_bytes<true>(w, raw.x, acc);
+        fma_bytes<kMiddle>(w, raw.y, acc + 4);
     }
     __device__ __forceinline__ uint32_t tail() const { return raw.y; }
     __device__ __forceinline__ uint32_t head() const { return raw.x; }
-    // first byte holds a 7-bit value under a foreign top bit: copy bit 6 into bit 7
-    __device__ __forceinline__ void restore_head_sign() { raw.x = (raw.x & ~0x80u) | ((raw.x << 1) & 0x80u); }
-    // the same for the fifth byte (rows of 16 lanes carry two scale bits per lane)
-    __device__ __forceinline__ void clear() { raw = make_uint2(0u, 0u); }
     __device__ __forceinline__ uint32_t middle() const { return raw.y; }
-    __device__ __forceinline__ void restore_middle_sign() { raw.y = (raw.y & ~0x80u) | ((raw.y << 1) & 0x80u); }
+    __device__ __forceinline__ void clear() { raw = make_uint2(0u, 0u); }
 };
 // The fp32 weight stored inside a loaded row, handed to every lane of the row's group.
 //   kWeightEmbedded: the row's last four bytes, held by the last lane of the group;
 //   kWeightTopBits:  bit i of the weight is the top bit of the first byte of lane i's segment
 //                    (groups of 32 or 64 lanes; groups of 16 lanes keep bits 16..31 in the top
 //                    bit of the fifth byte); one ballot per carrier byte collects the bits of all
-//                    rows that a load instruction covers, and the carrier bytes get their sign back.
+//                    rows that a load instruction covers.  The carrier bytes keep the foreign bit:
+//                    accumulate_segment sign-extends them from bit 6.
 template <typename T, int G, int V, int WM>
 __device__ __forceinline__ float row_weight(Segment<T, V> &seg, int lane, bool loaded)
 {
@@ -142,13 +152,11 @@ __device__ __forceinline__ float row_weight(Segment<T, V> &seg, int lane, bool l
         return __uint_as_float(static_cast<uint32_t>(__shfl(static_cast<int>(seg.tail()), lane | (G - 1), kWave)));
     } else if constexpr (sizeof(T) == 1 && WM >= kWeightTopBits) {
         const uint64_t bits = __ballot(loaded && (seg.head() & 0x80u) != 0);
-        seg.restore_head_sign();
         if constexpr (G >= 32) {
             const uint32_t mine = (G == kWave || lane < 32) ? static_cast<uint32_t>(bits) : static_cast<uint32_t>(bits >> 32);
             return __uint_as_float(mine);
         } else {
             const uint64_t high = __ballot(loaded && (seg.middle() & 0x80u) != 0);
-            seg.restore_middle_sign();
             const int shift = lane & ~(G - 1);           // first lane of this lane's group (G = 16)
             const uint32_t mine = (static_cast<uint32_t>(bits >> shift) & 0xffffu) |
                                   ((static_cast<uint32_t>(high >> shift) & 0xffffu) << 16);
@@ -175,22 +183,37 @@ struct RowAcc {
     }
 };
 
-// Address of a lane's segment of stored row k: one 32 x 32 -> 64 bit multiply-add (row indices
-// and row strides are below 2^32; the launchers check the stride).
-__device__ __forceinline__ const char *row_address(const char *lane_base, int k, uint32_t row_bytes)
+// Address of a lane's segment of stored row k: one 32 x 32 -> 64 bit multiply-add onto the array's
+// wave-uniform base (row indices and row strides are below 2^32; the launchers check the stride).
+// A 24-bit multiply with a 32-bit offset was measured on arrays below 4 GiB: 0.5 % faster, not
+// worth a second set of kernels.
+struct RowBase {
+    const char *base;      // wave-uniform
+    uint32_t lane_off;     // byte offset of this lane's segment inside a row
+};
+__device__ __forceinline__ const char *row_address(const RowBase &rb, int k, uint32_t row_bytes)
 {
-    return lane_base + static_cast<uint64_t>(static_cast<uint32_t>(k)) * row_bytes;
+    return rb.base + rb.lane_off + static_cast<uint64_t>(static_cast<uint32_t>(k)) * row_bytes;
+}
+
+// acc += w * (the V values of a loaded segment); rows with the scale in their top bits keep the
+// scale bits in their carrier bytes (first byte; fifth byte too for rows of 16 lanes).
+template <typename T, int G, int V, int WM>
+__device__ __forceinline__ void accumulate_segment(const Segment<T, V> &seg, float w, float (&acc)[V])
+{
+    if constexpr (sizeof(T) == 1 && WM >= kWeightTopBits) seg.template fma_carrier<(G < 32)>(w, acc);
+    else seg.fma(w, acc);
 }
 
 // The weight a loaded row carries; with the escape modes also the rare replacement of a row that
 // did not fit 7 bits (NaN scale): its values come from the alternate array and its scale from the
-// per-node array.  One-byte alternates are loaded into the segment; fp16 alternates are
-// accumulated here (with |w|, as the caller would) and the segment is cleared.  Executed by all
+// per-node array.  The alternate values (one byte or fp16 each) are accumulated here (with |w|,
+// as the caller would) and the segment is cleared.  Executed by all
 // lanes; `loaded` says whether this lane's segment was fetched; alt_row_bytes = bytes of an
 // alternate row, alt_lane_base already points at this lane's first value.
 template <typename T, int G, int V, int WM>
 __device__ __forceinline__ float resolve_row(Segment<T, V> &seg, int lane, bool loaded, int k,
-                                             const char *__restrict__ alt_lane_base, uint32_t alt_row_bytes,
+                                             const RowBase &alt_lane_base, uint32_t alt_row_bytes,
                                              const float *__restrict__ weights, float (&acc)[V])
 {
     float w = row_weight<T, G, V, WM>(seg, lane, loaded);
@@ -201,7 +224,11 @@ __device__ __forceinline__ float resolve_row(Segment<T, V> &seg, int lane, bool 
                 const char *src = row_address(alt_lane_base, k, alt_row_bytes);
                 w = weights[k];
                 if constexpr (WM == kWeightTopBitsEscape) {
-                    seg.load(src);
+                    // full one-byte values: accumulated here, the 7-bit segment is cleared
+                    Segment<T, V> alt;
+                    alt.load(src);
+                    alt.fma(fabsf(w), acc);
+                    seg.clear();
                 } else {
                     static_assert(V == 8, "fp16 alternates are read as one 16-byte vector per lane");
                     const float aw = fabsf(w);
@@ -228,8 +255,8 @@ __device__ __forceinline__ float resolve_row(Segment<T, V> &seg, int lane, bool 
 template <typename T, int G, int V, int WM, bool kAllActive>
 __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col_idx,
                                                  const float *__restrict__ weights,
-                                                 const char *__restrict__ lane_base,
-                                                 const char *__restrict__ alt_lane_base, uint32_t row_bytes,
+                                                 const RowBase &lane_base,
+                                                 const RowBase &alt_lane_base, uint32_t row_bytes,
                                                  uint32_t alt_row_bytes, int64_t p0, int64_t p1, int lane,
                                                  bool active_in, RowAcc<V> &acc)
 {
@@ -273,9 +300,9 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
                 if (fused_weights(WM)) {
                     acc.sum_abs += fabsf(w[u]);
                     acc.sum_signed += w[u];
-                    if (active) seg[u].fma(fabsf(w[u]), acc.pos);
+                    if (active) accumulate_segment<T, G, V, WM>(seg[u], fabsf(w[u]), acc.pos);
                 } else {
-                    if (active) seg[u].fma(w[u], acc.pos);
+                    if (active) accumulate_segment<T, G, V, WM>(seg[u], w[u], acc.pos);
                 }
             }
         }
@@ -305,9 +332,9 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
                     if (fused_weights(WM)) {
                         acc.sum_abs += fabsf(w[u]);
                         acc.sum_signed += w[u];
-                        if (active) seg[u].fma(fabsf(w[u]), acc.pos);
+                        if (active) accumulate_segment<T, G, V, WM>(seg[u], fabsf(w[u]), acc.pos);
                     } else {
-                        if (active) seg[u].fma(w[u], acc.pos);
+                        if (active) accumulate_segment<T, G, V, WM>(seg[u], w[u], acc.pos);
                     }
                 }
             }
@@ -318,8 +345,8 @@ __device__ __forceinline__ void accumulate_range(const int32_t *__restrict__ col
 // The node's own stored row (second product array of a layer with an own-row term), weighted by
 // the node's own scale exactly as a neighbour's row would be: pos = |t| * stored, sums of t.
 template <typename T, int G, int V, int WM>
-__device__ __forceinline__ void load_own_row(const char *__restrict__ own_lane_base,
-                                             const char *__restrict__ own_alt_lane_base, uint32_t row_bytes,
+__device__ __forceinline__ void load_own_row(const RowBase &own_lane_base,
+                                             const RowBase &own_alt_lane_base, uint32_t row_bytes,
                                              uint32_t alt_row_bytes, const float *__restrict__ weights,
                                              int64_t row, int lane, bool active, RowAcc<V> &own)
 {
@@ -333,7 +360,7 @@ __device__ __forceinline__ void load_own_row(const char *__restrict__ own_lane_b
     else t = weights[row];
     own.sum_abs = fabsf(t);
     own.sum_signed = t;
-    if (active) seg.fma(fabsf(t), own.pos);
+    if (active) accumulate_segment<T, G, V, WM>(seg, fabsf(t), own.pos);
 }
 
 // Sum the partial results of the 64/G lane slots; afterwards every lane holds the total.
@@ -576,7 +603,7 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) 
     const int wave = wave_in_block();
     const int g = lane & (G - 1);
     const bool active = kAllActive || g * V < valid_positions;
-    const char *lane_base = rows + static_cast<int64_t>(g) * V * sizeof(T);
+    const RowBase lane_base{rows, static_cast<uint32_t>(g * V * sizeof(T))};
 
     using LaneConsts = typename Epilogue::template Lane<G, V>;
     using Parked = ParkedLane<LaneConsts>;
@@ -590,12 +617,12 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) 
     RowAcc<V> acc;
     RowAcc<V> own;      // only filled (and only read) by epilogues with an own-row term
     // alternate rows of nodes whose products did not fit 7 bits; only dereferenced by the escape modes
-    const char *alt_lane_base = alt_rows + static_cast<int64_t>(g) * V * kAltElem;
-    const char *own_lane_base = nullptr;
-    const char *own_alt_lane_base = nullptr;
+    const RowBase alt_lane_base{alt_rows, static_cast<uint32_t>(g * V * kAltElem)};
+    RowBase own_lane_base{nullptr, 0u};
+    RowBase own_alt_lane_base{nullptr, 0u};
     if constexpr (Epilogue::kSelf) {
-        own_lane_base = epi.self_rows + static_cast<int64_t>(g) * V * sizeof(T);
-        own_alt_lane_base = epi.alt_self_rows + static_cast<int64_t>(g) * V * kAltElem;
+        own_lane_base = RowBase{epi.self_rows, static_cast<uint32_t>(g * V * sizeof(T))};
+        own_alt_lane_base = RowBase{epi.alt_self_rows, static_cast<uint32_t>(g * V * kAltElem)};
     }
 
     if (static_cast<int64_t>(blockIdx.x) < n_block_rows) {

@@ -367,12 +367,17 @@ def main():
         for _ in range(steps):
             step(profile)                     # per-kernel figures: eager, event-bracketed
         torch.cuda.synchronize()
+        per_step = None
     else:
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         start.record()
-        for _ in range(steps):
+        marks[0].record()
+        for i in range(steps):
             step(profile)
+            marks[i + 1].record()
         stop.record()
         torch.cuda.synchronize()
+        per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
     ms_per_step = start.elapsed_time(stop) / steps
     launch_ms, calls = profile.read()
     assert calls == steps
@@ -410,7 +415,9 @@ def main():
         "metric": "Bi-GCN forward nodes/s; bit-GEMM binary-op/s; SpMM HBM GB/s (% roofline)",
         "model": "Bi-GCN" if cfg.model == "gcn" else "Bi-GraphSAGE (mean aggregator)",
         "value": nodes_per_s, "unit": "nodes/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": ms_per_step, "ms_per_step_median": None if per_step is None else per_step[len(per_step) // 2],
+        "ms_per_step_min": None if per_step is None else per_step[0],
+        "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u64 xor/popcount + f32", "data": "synthetic",
         "launch": "hip graph replay" if args.graph else "eager",
         "config": {"workload": f"{cfg.name}: {cfg.stands_in_for}-shaped Chung-Lu graph, {work.n} nodes, "

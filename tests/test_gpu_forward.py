@@ -172,6 +172,45 @@ def _extreme_products(B, d_in, d_hidden, n=400, n_edges=3000):
     assert stats[-1]["rows_compared"] >= 0.5 * n
 
 
+def _hand_graph(kind):
+    from workloads import csr_from_undirected_edges
+    if kind == "single":                      # one node: only its self-loop
+        return csr_from_undirected_edges(1, np.zeros(0, dtype=np.int64), np.zeros(0, dtype=np.int64))
+    if kind == "isolated":                    # no edges at all: A~ is the identity
+        return csr_from_undirected_edges(70, np.zeros(0, dtype=np.int64), np.zeros(0, dtype=np.int64))
+    if kind == "star":                        # one hub of 700 neighbours: a row shared by a workgroup
+        return csr_from_undirected_edges(701, np.zeros(700, dtype=np.int64), np.arange(1, 701, dtype=np.int64))
+    if kind == "path":
+        return csr_from_undirected_edges(130, np.arange(129, dtype=np.int64), np.arange(1, 130, dtype=np.int64))
+    raise ValueError(kind)
+
+
+@pytest.mark.parametrize("kind", ["single", "isolated", "star", "path"])
+@pytest.mark.parametrize("dims", [(7, 3), (100, 512, 512, 10), (70, 64, 1), (256, 128, 47)])
+def test_forward_on_degenerate_graphs_and_extreme_widths(B, kind, dims):
+    """Hand-built graphs (one node, no edges, a star whose hub row is shared by a workgroup, a path)
+    with the narrowest and the widest layers the fused forward takes (1 and 512 columns)."""
+    from workloads.build import Workload
+    from workloads.configs import WorkloadConfig
+    from workloads.features import make_weights
+    rp, ci = _hand_graph(kind)
+    n = rp.size - 1
+    rng = np.random.default_rng(len(kind) + sum(dims))
+    x = rng.standard_normal((n, dims[0])).astype(np.float32)
+    weights = make_weights(dims, rng)
+    cfg = WorkloadConfig(kind, "none", n, (ci.size - n) // 2, 2.0, tuple(dims), "normal", 1.0, "first", 0)
+    work = Workload(cfg, rp, ci, x, weights)
+    bn = [None] * (len(dims) - 1)
+    stats = compare_forward_layerwise(work, bn, gpu_prefix_runner(B, work), cancellation_aware=True)
+    assert stats[0]["rows_compared"] == n
+    if kind == "isolated":
+        # A~ = I: the logits of the last layer are the node's own rescaled products
+        out = gpu_prefix_runner(B, work)(1, bn)
+        sign, beta = oracle.binarize_rows(x)
+        bt, alpha = oracle.binarize_weight(weights[0])
+        assert_close(out, oracle.rescale(oracle.sign_matmul(sign, bt), beta, alpha), "identity aggregation")
+
+
 @pytest.mark.parametrize("name", ["c1", "c3"])
 def test_forward_captured_in_a_hip_graph_replays_identically(B, name):
     """The fused forward allocates nothing, clears no memory and only launches kernels on the

@@ -38,7 +38,7 @@ __device__ __forceinline__ float sign_from_bit(uint32_t word, int pos)
 // rows x 4 column tiles.  K runs over the layer's output columns j in steps of 64 (one packed
 // word of the weights packed along j): the 128 x 64 slab of g_zeta * alpha_j goes through LDS, the
 // +-1 operand B[j][t] is bit j of the lane's own packed weight row t.
-__global__ __launch_bounds__(kBlock) void backward_input_kernel(
+__global__ __launch_bounds__(kBlock, 4) void backward_input_kernel(
     const float *__restrict__ g_zeta, int64_t n, int d_out, int64_t ld_gz, const float *__restrict__ alpha,
     const uint64_t *__restrict__ wt_bits, int64_t ld_wt, int d_in, const float *__restrict__ mul,
     float *__restrict__ g_in, int64_t ld_gin)

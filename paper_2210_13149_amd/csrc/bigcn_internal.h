@@ -108,7 +108,8 @@ int launch_source_scale(const float *beta, const float *row_mul, const uint64_t 
 
 // bit-GEMM writing the integer products in a RowLayout (fused forward).
 // src_scale (m floats) is copied into the rows when the layout embeds the scale.
-// alt_rows (escape layouts only): receives the one-byte form of the rows that do not fit 7 bits.
+// alt_rows (escape layouts only): receives the rows that do not fit 7 bits, one byte or fp16 per value
+// (layout.alt_kind).
 int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits,
                           int64_t n, int64_t ldb, int64_t k_bits, const float *src_scale, void *c_rows,
                           void *alt_rows, RowLayout layout, hipStream_t stream);
@@ -155,7 +156,7 @@ struct FusedSpmmArgs {
     const float *next_row_mul;  // n, nullable (= 1)
     int next_fold_last_sign;    // the next layer's layout has fold_last: sign the stored scale
     // own-row term, all nullptr when absent
-    const void *alt_rows;       // escape layouts: one-byte form of the rows that did not fit 7 bits
+    const void *alt_rows;       // escape layouts: the rows that did not fit 7 bits (bytes or fp16: alt_kind)
     const void *alt_self_rows;  //   (same for the own-row array)
     const void *self_rows;      // n rows in `layout`: products with the second weight matrix
     const float *self_alpha;    // d_out

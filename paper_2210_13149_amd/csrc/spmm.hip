@@ -439,7 +439,7 @@ struct EpilogueFusedT {
     int next_fold_last_sign;
     // own-row term (kSelfTerm only): rows in the same layout, their column scales and last bits
     const char *self_rows;
-    const char *alt_self_rows;       // one-byte form of own rows that did not fit 7 bits (escape layouts)
+    const char *alt_self_rows;       // own rows that did not fit 7 bits (escape layouts; bytes or fp16)
     const float *self_alpha;
     const uint64_t *self_last_bit_word;
 

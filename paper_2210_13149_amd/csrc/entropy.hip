@@ -48,7 +48,19 @@ __global__ __launch_bounds__(kBlock) void entropy_range_kernel(const float *__re
     const int64_t r0 = static_cast<int64_t>(blockIdx.y) * rows_per_chunk;
     const int64_t r1 = r0 + rows_per_chunk < rows ? r0 + rows_per_chunk : rows;
     float lo = INFINITY, hi = -INFINITY;
-    for (int64_t r = r0 + wave; r < r1; r += kWavesPerBlock) {
+    constexpr int U = 8;                          // loads in flight per lane
+    int64_t r = r0 + wave;
+    for (; r + (U - 1) * kWavesPerBlock < r1; r += U * kWavesPerBlock) {
+        float v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = h[(r + u * kWavesPerBlock) * ld + c];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            lo = fminf(lo, v[u]);
+            hi = fmaxf(hi, v[u]);
+        }
+    }
+    for (; r < r1; r += kWavesPerBlock) {
         const float v = h[r * ld + c];
         lo = fminf(lo, v);
         hi = fmaxf(hi, v);
@@ -81,13 +93,23 @@ __global__ __launch_bounds__(kBlock) void entropy_histogram_kernel(const float *
         const float width = key_float(hi_key[c]) - lo;
         const float scale = width > 0.0f ? static_cast<float>(bins) / width : 0.0f;
         uint32_t *mine = local + tc * bins;
-        for (int64_t r = r0 + tr; r < r1; r += kBlock / kEntropyTile) {
-            const float v = h[r * ld + c];
+        auto count = [&](float v) {
             const float pos = floorf((v - lo) * scale);
             int m = static_cast<int>(pos);
             m = m > bins - 1 ? bins - 1 : (m < 0 ? 0 : m);
             atomicAdd(&mine[m], 1u);
+        };
+        constexpr int U = 8;                      // loads in flight per lane
+        constexpr int kStep = kBlock / kEntropyTile;
+        int64_t r = r0 + tr;
+        for (; r + (U - 1) * kStep < r1; r += U * kStep) {
+            float v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = h[(r + u * kStep) * ld + c];
+#pragma unroll
+            for (int u = 0; u < U; ++u) count(v[u]);
         }
+        for (; r < r1; r += kStep) count(h[r * ld + c]);
     }
     __syncthreads();
     for (int i = threadIdx.x; i < kEntropyTile * bins; i += kBlock) {

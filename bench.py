@@ -125,11 +125,13 @@ def aggregation_bytes(cfg, nnz, layer, B):
 
 
 MFMA_INT8_MAC_PEAK = 2.5e15     # MI355X dense int8: 5.0 POP/s, two operations per multiply-accumulate
+MFMA_FP4_MAC_PEAK = 5.05e15     # MI355X dense fp4: 10.1 PFLOP/s
 
 
 def gemm_sweep(B, m=262144, n=256, k=4096, reps=10):
     """Compute-bound bit-GEMM outside the workloads (their GEMMs are bound by writing the product
-    rows): both evaluation paths of bigcn_binary_gemm on random bits, int32 accumulators only."""
+    rows): the three evaluation paths of bigcn_binary_gemm on random bits, int32 accumulators
+    only."""
     import torch
     words = (k + 63) // 64
     gen = torch.Generator(device="cuda").manual_seed(1)
@@ -137,7 +139,7 @@ def gemm_sweep(B, m=262144, n=256, k=4096, reps=10):
     b = torch.randint(-2**62, 2**62, (n, words), dtype=torch.int64, device="cuda", generator=gen)
     out = []
     ref = None
-    for name, variant in (("valu_xor_popcount", B.GEMM_VALU), ("mfma_int8", B.GEMM_MFMA)):
+    for name, variant in (("valu_xor_popcount", B.GEMM_VALU), ("mfma_int8", B.GEMM_MFMA), ("mfma_fp4", B.GEMM_FP4)):
         acc, _ = B.bigcn_binary_gemm(a, None, b, None, k, want_out=False, variant=variant)
         torch.cuda.synchronize()
         if ref is None:
@@ -153,7 +155,8 @@ def gemm_sweep(B, m=262144, n=256, k=4096, reps=10):
         rate = m * n * k / (ms * 1e-3)
         out.append({"path": name, "m": m, "n": n, "k_bits": k, "ms": ms, "binary_op_per_s": rate,
                     "frac_valu_peak": rate / VALU_BINARY_MAC_PEAK,
-                    "frac_mfma_int8_peak": rate / MFMA_INT8_MAC_PEAK, "identical_to_first": identical})
+                    "frac_mfma_int8_peak": rate / MFMA_INT8_MAC_PEAK,
+                    "frac_mfma_fp4_peak": rate / MFMA_FP4_MAC_PEAK, "identical_to_first": identical})
     return out
 
 

@@ -100,10 +100,12 @@ int bigcn_binary_gemm(const uint64_t *a_bits, const float *a_scale, int64_t m,
  * The same product with the evaluation path chosen by the caller (benchmarking and tests):
  * BIGCN_GEMM_AUTO picks per shape (what bigcn_binary_gemm does), BIGCN_GEMM_VALU evaluates
  * XOR + bit count on the vector ALU, BIGCN_GEMM_MFMA expands the bits to +-1 bytes and uses
- * the int8 matrix cores.  All paths give bit-identical acc and identical out.
+ * the int8 matrix cores, BIGCN_GEMM_FP4 expands them to FP4 codes of +-1 and uses the
+ * block-scaled matrix cores with unit scales (exact: the partial sums are integers below 2^24).
+ * All paths give bit-identical acc and identical out.
  * Errors: as bigcn_binary_gemm, plus EINVAL for an unknown variant.
  */
-enum { BIGCN_GEMM_AUTO = 0, BIGCN_GEMM_VALU = 1, BIGCN_GEMM_MFMA = 2 };
+enum { BIGCN_GEMM_AUTO = 0, BIGCN_GEMM_VALU = 1, BIGCN_GEMM_MFMA = 2, BIGCN_GEMM_FP4 = 3 };
 int bigcn_binary_gemm_variant(const uint64_t *a_bits, const float *a_scale, int64_t m,
                               int64_t lda_words, const uint64_t *b_bits, const float *b_scale,
                               int64_t n, int64_t ldb_words, int64_t k_bits, int32_t *acc,

@@ -25,7 +25,7 @@ BIGCN_EWORKSPACE = -4
 BIGCN_EGRAPH = -5
 BIGCN_EHIP = -6
 MAX_K_BITS = 8192
-GEMM_AUTO, GEMM_VALU, GEMM_MFMA = 0, 1, 2
+GEMM_AUTO, GEMM_VALU, GEMM_MFMA, GEMM_FP4 = 0, 1, 2, 3
 MAX_FORWARD_D_OUT = 512
 VALIDATE_NONE, VALIDATE_GCN, VALIDATE_NEIGHBOURS = 0, 1, 2
 
@@ -227,8 +227,8 @@ def bigcn_binary_gemm(a_bits: torch.Tensor, a_scale: Optional[torch.Tensor], b_b
                       want_out: bool = True, variant: int = 0
                       ) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor]]:
     """``acc = K - 2 popcount(a xor b)`` (int32) and / or ``out = a_scale_i b_scale_j acc``.
-    ``variant``: GEMM_AUTO (per shape), GEMM_VALU (XOR + bit count) or GEMM_MFMA (int8 matrix
-    cores)."""
+    ``variant``: GEMM_AUTO (per shape), GEMM_VALU (XOR + bit count), GEMM_MFMA (int8 matrix
+    cores) or GEMM_FP4 (FP4 codes of +-1 on the block-scaled matrix cores)."""
     _dev(a_bits, torch.int64, "a_bits")
     _dev(b_bits, torch.int64, "b_bits")
     m, n = a_bits.shape[0], b_bits.shape[0]

@@ -127,6 +127,12 @@ int launch_bitgemm_mfma(const uint64_t *a_bits, const float *a_scale, int64_t m,
                         int64_t k_bits, int32_t *acc, int64_t ld_acc, float *out, int64_t ld_out,
                         hipStream_t stream);
 
+// The same on the FP4 path of the block-scaled matrix cores (unit scales).
+int launch_bitgemm_fp4(const uint64_t *a_bits, const float *a_scale, int64_t m, int64_t lda,
+                       const uint64_t *b_bits, const float *b_scale, int64_t n, int64_t ldb,
+                       int64_t k_bits, int32_t *acc, int64_t ld_acc, float *out, int64_t ld_out,
+                       hipStream_t stream);
+
 // Aggregation of layer l fused with the rescale and with the binarisation of layer l+1.
 // Bi-GCN: dst_mul = next_row_mul = D^-1/2 and no own-row term.  Bi-GraphSAGE (mean aggregator):
 // dst_mul = 1/|N_i|, next_row_mul = nullptr, and the own-row term is described by self_*.

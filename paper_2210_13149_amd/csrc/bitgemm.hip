@@ -679,7 +679,7 @@ extern "C" int bigcn_binary_gemm_variant(const uint64_t *a_bits, const float *a_
                                          int64_t ld_acc, float *out, int64_t ld_out, int variant,
                                          void *stream)
 {
-    if (variant < BIGCN_GEMM_AUTO || variant > BIGCN_GEMM_MFMA) return BIGCN_EINVAL;
+    if (variant < BIGCN_GEMM_AUTO || variant > BIGCN_GEMM_FP4) return BIGCN_EINVAL;
     if (a_bits == nullptr || b_bits == nullptr) return BIGCN_ENULL;
     if (acc == nullptr && out == nullptr) return BIGCN_ENULL;
     if (out != nullptr && (a_scale == nullptr || b_scale == nullptr)) return BIGCN_ENULL;
@@ -690,6 +690,9 @@ extern "C" int bigcn_binary_gemm_variant(const uint64_t *a_bits, const float *a_
     if (out != nullptr && ld_out < n) return BIGCN_EINVAL;
     if (k_bits > BIGCN_MAX_K_BITS || n > BIGCN_MAX_GEMM_N) return BIGCN_ESHAPE;
     if (m == 0 || n == 0) return BIGCN_OK;
+    if (variant == BIGCN_GEMM_FP4)
+        return bigcn::launch_bitgemm_fp4(a_bits, a_scale, m, lda_words, b_bits, b_scale, n, ldb_words, k_bits,
+                                         acc, ld_acc, out, ld_out, bigcn::as_stream(stream));
     if (variant == BIGCN_GEMM_MFMA || (variant == BIGCN_GEMM_AUTO && bigcn::prefer_mfma(m, n, k_bits)))
         return bigcn::launch_bitgemm_mfma(a_bits, a_scale, m, lda_words, b_bits, b_scale, n, ldb_words, k_bits,
                                           acc, ld_acc, out, ld_out, bigcn::as_stream(stream));

@@ -214,6 +214,271 @@ __global__ __launch_bounds__(kBlock) void bitgemm_mfma_kernel(
     }
 }
 
+// ---- FP4 matrix cores -------------------------------------------------------------------------
+// The same product on the block-scaled multiply of gfx950 (v_mfma_scale_f32_32x32x64_f8f6f4 with
+// both operands in FP4 E2M1 and unit scales): 64 values of K per instruction at twice the int8
+// rate.  +1 is the FP4 code 0x2, -1 is 0xA, 0 is 0x0; a lane supplies 32 consecutive k values =
+// 32 bits of a packed row = four dwords of eight codes.  A is expanded to {0, +1} (so pad bits
+// contribute nothing), B to {-1, +1} with the bits past K set to 0, and, as above,
+// sum_k f_k b_k = 2 sum_k a_k b_k - sum_k b_k.  The partial sums are integers below 2^24: the fp32
+// accumulators are exact.
+//
+// Eight packed bits become eight codes in four vector operations: the bits are spread to one
+// 2-bit index per byte (two shift-ors and a mask) and a byte permute looks each index up in a
+// four-entry table held in a register (entry = the two codes of a bit pair).
+//
+// Operand layout (checked on the device): A[i][k] is supplied by lane i + 32 (k / 32) as code
+// number k % 32 of its 128 bits, B[k][j] by lane j + 32 (k / 32) likewise; accumulator register r
+// of lane l holds row 8 (r / 4) + 4 (l / 32) + r % 4 and column l % 32.
+//
+// Tiling: wavefront 32 RT rows x 32 CT columns (RT x CT tiles of 32 x 32), workgroup four
+// wavefronts high; K in chunks of 512 bits; the chunk of B is staged as [column][256 bytes of codes +
+// 16 pad]; the number of set bits of every column is collected during the staging for the
+// epilogue.
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kFp4ColStride = kMfmaChunkWords * 32 + 16;   // LDS bytes per column of B codes
+constexpr uint32_t kFp4TableA = 0x22200200u;               // bit pair -> codes of {0, +1}
+constexpr uint32_t kFp4TableB = 0x222aa2aau;               // bit pair -> codes of {-1, +1}
+
+// eight packed bits (byte `index` of `word`) -> eight FP4 codes, through `table`
+__device__ __forceinline__ uint32_t fp4_codes(uint32_t word, int index, uint32_t table)
+{
+    uint32_t x = (word >> (8 * index)) & 0xffu;
+    x |= x << 6;
+    x |= x << 12;                                  // bit pair p now also sits at bits 8 p, 8 p + 1
+    return __builtin_amdgcn_perm(0u, table, x & 0x03030303u);
+}
+
+template <int RT, int CT>
+__global__ __launch_bounds__(kBlock, 2) void bitgemm_fp4_kernel(
+    const uint64_t *__restrict__ a, int64_t m, int64_t lda, const uint64_t *__restrict__ b, int n,
+    int64_t ldb, int k_bits, const float *__restrict__ a_scale, const float *__restrict__ b_scale,
+    int32_t *__restrict__ acc_out, int64_t ld_acc, float *__restrict__ out, int64_t ld_out)
+{
+    constexpr int kRows = kWavesPerBlock * 32 * RT;         // rows per workgroup
+    constexpr int kCols = 32 * CT;                          // columns per workgroup
+    constexpr int kAWords = kRows * kMfmaChunkWords / kBlock;   // words of A per thread and chunk (4 or 8)
+    constexpr int kBWords = kCols * kMfmaChunkWords / kBlock;   // words of B per thread and chunk
+    __shared__ __attribute__((aligned(16))) unsigned char lds_b[kCols * kFp4ColStride];
+    __shared__ __attribute__((aligned(16))) unsigned char lds_a[kRows * kMfmaARowStride];
+    __shared__ int col_ones[kCols];
+    const int n_words = (k_bits + 63) >> 6;
+    const int lane = lane_id();
+    const int wave = wave_in_block();
+    const int i32 = lane & 31;
+    const int half = lane >> 5;
+    const int64_t block_row0 = static_cast<int64_t>(blockIdx.x) * kRows;
+    const int64_t row0 = block_row0 + wave * 32 * RT;
+    const int col0 = blockIdx.y * kCols;
+
+    if (threadIdx.x < kCols) col_ones[threadIdx.x] = 0;
+
+    v16f acc[RT][CT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rt][ct][r] = 0.0f;
+
+    // staging shares of a thread: kAWords consecutive words of one row of A (256 / kRows threads
+    // per row... kMfmaChunkWords / kAWords threads share a row), kBWords words of B (column
+    // item / 8, word item % 8, item = t + 256 u).  Addresses are recomputed at every fetch: the
+    // registers are needed for the accumulators.
+    static_assert(kMfmaChunkWords == 8, "item -> (column, word) below uses shifts");
+    constexpr int kThreadsPerRow = kMfmaChunkWords / kAWords;            // 2 or 1
+    const int a_thread_row = static_cast<int>(threadIdx.x) / kThreadsPerRow;
+    const int a_thread_word = (static_cast<int>(threadIdx.x) % kThreadsPerRow) * kAWords;
+
+    // two chunks are fetched ahead of the one being multiplied (one multiply phase is shorter than
+    // a trip to memory): two register sets, used alternately
+    struct Fetched {
+        uint64_t a[kAWords];
+        uint64_t b[kBWords];
+    };
+    Fetched set0, set1;
+    auto fetch = [&](int w0, Fetched &f) {
+        uint64_t (&a_next)[kAWords] = f.a;
+        uint64_t (&b_next)[kBWords] = f.b;
+        int64_t row = block_row0 + a_thread_row;
+        if (row >= m) row = m - 1;                              // clamped rows are never stored
+        const uint64_t *src = a + row * lda + w0 + a_thread_word;
+#pragma unroll
+        for (int e = 0; e < kAWords; ++e) a_next[e] = (w0 + a_thread_word + e < n_words) ? src[e] : 0ull;
+#pragma unroll
+        for (int t = 0; t < kBWords; ++t) {
+            const int item = static_cast<int>(threadIdx.x) + t * kBlock;
+            const int j = col0 + (item >> 3);
+            const int w = w0 + (item & 7);
+            b_next[t] = (j < n && w < n_words) ? b[static_cast<int64_t>(j) * ldb + w] : 0ull;
+        }
+    };
+    // w0: first word of the chunk that fetch() brought into f
+    auto stage = [&](int w0, const Fetched &f) {
+        const uint64_t (&a_next)[kAWords] = f.a;
+        const uint64_t (&b_next)[kBWords] = f.b;
+        uint2 *adst = reinterpret_cast<uint2 *>(lds_a + a_thread_row * kMfmaARowStride + a_thread_word * 8);
+#pragma unroll
+        for (int e = 0; e < kAWords; ++e)
+            adst[e] = make_uint2(static_cast<uint32_t>(a_next[e]), static_cast<uint32_t>(a_next[e] >> 32));
+        // 64 bits -> 64 codes (32 bytes): +1 -> 0x2, -1 -> 0xA, past K or past the last column -> 0x0
+        const bool whole = (w0 + kMfmaChunkWords) * 64 <= k_bits && col0 + kCols <= n;   // uniform
+        if (whole) {
+            // every bit of the chunk counts: no masks
+#pragma unroll
+            for (int t = 0; t < kBWords; ++t) {
+                const int item = static_cast<int>(threadIdx.x) + t * kBlock;
+                const int c = item >> 3, q = item & 7;
+                uint4 *dst = reinterpret_cast<uint4 *>(lds_b + c * kFp4ColStride + q * 32);
+                atomicAdd(&col_ones[c], __popcll(b_next[t]));
+#pragma unroll
+                for (int part = 0; part < 2; ++part) {
+                    const uint32_t bits = static_cast<uint32_t>(b_next[t] >> (32 * part));
+                    dst[part] = make_uint4(fp4_codes(bits, 0, kFp4TableB), fp4_codes(bits, 1, kFp4TableB),
+                                           fp4_codes(bits, 2, kFp4TableB), fp4_codes(bits, 3, kFp4TableB));
+                }
+            }
+            return;
+        }
+#pragma unroll
+        for (int t = 0; t < kBWords; ++t) {
+            const int item = static_cast<int>(threadIdx.x) + t * kBlock;
+            const int c = item >> 3, q = item & 7;
+            const int left = (col0 + c < n) ? k_bits - 64 * (w0 + q) : 0;        // bits of this word below K
+            const uint64_t valid_bits = left >= 64 ? ~0ull : (left <= 0 ? 0ull : ((1ull << left) - 1ull));
+            uint4 *dst = reinterpret_cast<uint4 *>(lds_b + c * kFp4ColStride + q * 32);
+            const uint64_t word = b_next[t] & valid_bits;
+            if (word != 0ull) atomicAdd(&col_ones[c], __popcll(word));
+#pragma unroll
+            for (int part = 0; part < 2; ++part) {
+                const uint32_t bits = static_cast<uint32_t>(b_next[t] >> (32 * part));
+                const uint32_t valid = static_cast<uint32_t>(valid_bits >> (32 * part));
+                uint32_t code[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)      // 0xF per code that stays
+                    code[e] = fp4_codes(bits, e, kFp4TableB) & ((fp4_codes(valid, e, kFp4TableA) >> 1) * 0xfu);
+                dst[part] = make_uint4(code[0], code[1], code[2], code[3]);
+            }
+        }
+    };
+
+    fetch(0, set0);
+    if (kMfmaChunkWords < n_words) fetch(kMfmaChunkWords, set1);
+    __syncthreads();                                      // col_ones cleared
+    stage(0, set0);
+    __syncthreads();
+
+    const unsigned char *a_lane = lds_a + (wave * 32 * RT + i32) * kMfmaARowStride + 4 * half;
+    const unsigned char *b_lane = lds_b + i32 * kFp4ColStride + 16 * half;
+
+    // multiply the chunk that starts at word w0 (it is in LDS)
+    auto multiply = [&](int w0) {
+        auto step = [&](int q) {
+            v8i aop[RT], bop[CT];
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                // this lane's 32 k of row 32 rt + i32
+                const uint32_t bits = *reinterpret_cast<const uint32_t *>(a_lane + 32 * rt * kMfmaARowStride + 8 * q);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) aop[rt][e] = static_cast<int>(fp4_codes(bits, e, kFp4TableA));
+                aop[rt][4] = aop[rt][5] = aop[rt][6] = aop[rt][7] = 0;
+            }
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                const uint4 codes = *reinterpret_cast<const uint4 *>(b_lane + 32 * ct * kFp4ColStride + 32 * q);
+                bop[ct][0] = static_cast<int>(codes.x);
+                bop[ct][1] = static_cast<int>(codes.y);
+                bop[ct][2] = static_cast<int>(codes.z);
+                bop[ct][3] = static_cast<int>(codes.w);
+                bop[ct][4] = bop[ct][5] = bop[ct][6] = bop[ct][7] = 0;
+            }
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct)
+                    acc[rt][ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        aop[rt], bop[ct], acc[rt][ct], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+        };
+        if (w0 + kMfmaChunkWords <= n_words) {
+            // a whole chunk: no exit between the steps, so their operands can be prepared ahead
+#pragma unroll
+            for (int q = 0; q < kMfmaChunkWords; ++q) step(q);
+        } else {
+            for (int q = 0; w0 + q < n_words; ++q) step(q);
+        }
+    };
+    // chunk c is multiplied while chunk c + 1 waits in a register set and chunk c + 2 is fetched
+    // into the other; two chunks per turn so that the sets keep their names
+    for (int w0 = 0; w0 < n_words; w0 += 2 * kMfmaChunkWords) {
+        const int w1 = w0 + kMfmaChunkWords, w2 = w0 + 2 * kMfmaChunkWords, w3 = w0 + 3 * kMfmaChunkWords;
+        if (w2 < n_words) fetch(w2, set0);                  // set0 was staged before this turn
+        multiply(w0);
+        __syncthreads();                                    // every wavefront has left this chunk
+        if (w1 < n_words) stage(w1, set1);
+        __syncthreads();
+        if (w1 >= n_words) break;                           // uniform
+        if (w3 < n_words) fetch(w3, set1);
+        multiply(w1);
+        __syncthreads();
+        if (w2 < n_words) stage(w2, set0);
+        __syncthreads();
+    }
+
+    // epilogue: c = 2 * acc - (2 popcount(B_j) - K)
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        const int j = col0 + 32 * ct + i32;
+        if (j >= n) continue;
+        const int colsum = 2 * col_ones[32 * ct + i32] - k_bits;
+        const float sb = out != nullptr ? b_scale[j] : 0.0f;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = row0 + 32 * rt + 8 * (r >> 2) + 4 * half + (r & 3);
+                if (row < m) {
+                    const int c = 2 * static_cast<int>(acc[rt][ct][r]) - colsum;
+                    if (acc_out != nullptr) acc_out[row * ld_acc + j] = c;
+                    if (out != nullptr) out[row * ld_out + j] = a_scale[row] * sb * static_cast<float>(c);
+                }
+            }
+        }
+    }
+}
+
+template <int RT, int CT>
+static int launch_bitgemm_fp4_t(const uint64_t *a_bits, const float *a_scale, int64_t m, int64_t lda,
+                                const uint64_t *b_bits, const float *b_scale, int64_t n, int64_t ldb,
+                                int64_t k_bits, int32_t *acc, int64_t ld_acc, float *out, int64_t ld_out,
+                                hipStream_t stream)
+{
+    constexpr int kRows = kWavesPerBlock * 32 * RT, kCols = 32 * CT;
+    const int64_t row_blocks = (m + kRows - 1) / kRows;
+    const int64_t col_blocks = (n + kCols - 1) / kCols;
+    if (row_blocks > 0x7fffffff || col_blocks > 65535) return BIGCN_ESHAPE;
+    hipLaunchKernelGGL((bitgemm_fp4_kernel<RT, CT>), dim3(static_cast<unsigned>(row_blocks), static_cast<unsigned>(col_blocks)),
+                       dim3(kBlock), 0, stream, a_bits, m, lda, b_bits, static_cast<int>(n), ldb,
+                       static_cast<int>(k_bits), a_scale, b_scale, acc, ld_acc, out, ld_out);
+    return check_launch();
+}
+
+// More than 64 columns: a wavefront owns 32 rows x 128 columns, so that an expanded A operand
+// feeds four multiplies; otherwise 64 rows x 64 columns.  Either way 64 accumulator registers
+// and three wavefronts per SIMD.
+int launch_bitgemm_fp4(const uint64_t *a_bits, const float *a_scale, int64_t m, int64_t lda,
+                       const uint64_t *b_bits, const float *b_scale, int64_t n, int64_t ldb,
+                       int64_t k_bits, int32_t *acc, int64_t ld_acc, float *out, int64_t ld_out,
+                       hipStream_t stream)
+{
+    if (n > 64)
+        return launch_bitgemm_fp4_t<1, 4>(a_bits, a_scale, m, lda, b_bits, b_scale, n, ldb, k_bits, acc, ld_acc, out,
+                                          ld_out, stream);
+    return launch_bitgemm_fp4_t<2, 2>(a_bits, a_scale, m, lda, b_bits, b_scale, n, ldb, k_bits, acc, ld_acc, out,
+                                      ld_out, stream);
+}
+
 int launch_bitgemm_mfma(const uint64_t *a_bits, const float *a_scale, int64_t m, int64_t lda,
                         const uint64_t *b_bits, const float *b_scale, int64_t n, int64_t ldb,
                         int64_t k_bits, int32_t *acc, int64_t ld_acc, float *out, int64_t ld_out,

@@ -85,7 +85,7 @@ def test_binary_gemm_rejects_bad_arguments():
     assert call(m=0) == binding.BIGCN_OK
     assert call(n=0, ldacc=0, ldout=0) == binding.BIGCN_OK
     p = ok
-    for variant, expect in ((3, binding.BIGCN_EINVAL), (-1, binding.BIGCN_EINVAL)):
+    for variant, expect in ((4, binding.BIGCN_EINVAL), (-1, binding.BIGCN_EINVAL)):
         assert L.bigcn_binary_gemm_variant(p["a"], p["sa"], p["m"], p["lda"], p["b"], p["sb"], p["n"],
                                            p["ldb"], p["k"], p["acc"], p["ldacc"], p["out"], p["ldout"],
                                            variant, None) == expect

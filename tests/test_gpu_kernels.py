@@ -93,7 +93,7 @@ GEMM_SHAPES = [(1, 1, 1), (5, 3, 64), (67, 7, 65), (300, 41, 128), (1000, 47, 25
                (40000, 47, 256), (33000, 130, 3703)]
 
 
-@pytest.mark.parametrize("variant", ["auto", "valu", "mfma"])
+@pytest.mark.parametrize("variant", ["auto", "valu", "mfma", "fp4"])
 @pytest.mark.parametrize("m,n,k", GEMM_SHAPES)
 def test_binary_gemm(B, m, n, k, variant):
     import torch
@@ -109,7 +109,7 @@ def test_binary_gemm(B, m, n, k, variant):
     zeta = oracle.rescale(acc, beta.astype(np.float64), alpha.astype(np.float64))
     a_bits, b_bits, dbeta, dalpha = to_device(oracle.pack_bits(f).view(np.int64),
                                               oracle.pack_bits(bt).view(np.int64), beta, alpha)
-    v = {"auto": B.GEMM_AUTO, "valu": B.GEMM_VALU, "mfma": B.GEMM_MFMA}[variant]
+    v = {"auto": B.GEMM_AUTO, "valu": B.GEMM_VALU, "mfma": B.GEMM_MFMA, "fp4": B.GEMM_FP4}[variant]
     dacc, dout = B.bigcn_binary_gemm(a_bits, dbeta, b_bits, dalpha, k, variant=v)
     torch.cuda.synchronize()
     assert np.array_equal(dacc.cpu().numpy(), acc)

@@ -664,11 +664,12 @@ int launch_bitgemm_natural(const uint64_t *a_bits, int64_t m, int64_t lda, const
     return dispatch_bitgemm(per_lane, 1, positions, a_bits, m, lda, b_bits, n, ldb, k_bits, 0xffffffffu, epi, stream);
 }
 
-// Shapes on which the matrix-core variant measured faster (see the design notes): enough
-// inner dimension to be compute-bound and enough rows and columns to fill its 256 x 64 tiles.
+// Shapes on which the matrix cores measured faster than XOR + bit count (the FP4 path is the
+// faster of the two matrix-core paths on all of them): enough inner dimension to pay for the
+// expansion of the bits and enough rows and columns to fill the tiles.
 bool prefer_mfma(int64_t m, int64_t n, int64_t k_bits)
 {
-    return k_bits >= 512 && n >= 48 && m >= 4096;
+    return k_bits >= 512 && n >= 48 && m >= 16384;
 }
 
 }  // namespace bigcn
@@ -690,10 +691,10 @@ extern "C" int bigcn_binary_gemm_variant(const uint64_t *a_bits, const float *a_
     if (out != nullptr && ld_out < n) return BIGCN_EINVAL;
     if (k_bits > BIGCN_MAX_K_BITS || n > BIGCN_MAX_GEMM_N) return BIGCN_ESHAPE;
     if (m == 0 || n == 0) return BIGCN_OK;
-    if (variant == BIGCN_GEMM_FP4)
+    if (variant == BIGCN_GEMM_FP4 || (variant == BIGCN_GEMM_AUTO && bigcn::prefer_mfma(m, n, k_bits)))
         return bigcn::launch_bitgemm_fp4(a_bits, a_scale, m, lda_words, b_bits, b_scale, n, ldb_words, k_bits,
                                          acc, ld_acc, out, ld_out, bigcn::as_stream(stream));
-    if (variant == BIGCN_GEMM_MFMA || (variant == BIGCN_GEMM_AUTO && bigcn::prefer_mfma(m, n, k_bits)))
+    if (variant == BIGCN_GEMM_MFMA)
         return bigcn::launch_bitgemm_mfma(a_bits, a_scale, m, lda_words, b_bits, b_scale, n, ldb_words, k_bits,
                                           acc, ld_acc, out, ld_out, bigcn::as_stream(stream));
     bigcn::EpilogueApi epi{a_scale, b_scale, acc, ld_acc, out, ld_out, static_cast<int>(k_bits)};

@@ -223,12 +223,9 @@ __global__ __launch_bounds__(kBlock) void bitgemm_mfma_kernel(
 // sum_k f_k b_k = 2 sum_k a_k b_k - sum_k b_k.  The partial sums are integers below 2^24: the fp32
 // accumulators are exact.
 //
-// Eight packed bits become eight codes in four vector operations: the bits are spread to one
-// 2-bit index per byte (two shift-ors and a mask) and a byte permute looks each index up in a
-// four-entry table held in a register (entry = the two codes of a bit pair).
-//
 // Operand layout (checked on the device): A[i][k] is supplied by lane i + 32 (k / 32) as code
-// number k % 32 of its 128 bits, B[k][j] by lane j + 32 (k / 32) likewise; accumulator register r
+// number k % 32 of its 128 bits, B[k][j] by lane j + 32 (k / 32) likewise (the order inside the
+// 32 is permuted on both sides, see fp4_codes_a); accumulator register r
 // of lane l holds row 8 (r / 4) + 4 (l / 32) + r % 4 and column l % 32.
 //
 // Tiling: wavefront 32 RT rows x 32 CT columns (RT x CT tiles of 32 x 32), workgroup four
@@ -239,16 +236,30 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kFp4ColStride = kMfmaChunkWords * 32 + 16;   // LDS bytes per column of B codes
-constexpr uint32_t kFp4TableA = 0x22200200u;               // bit pair -> codes of {0, +1}
-constexpr uint32_t kFp4TableB = 0x222aa2aau;               // bit pair -> codes of {-1, +1}
-
-// eight packed bits (byte `index` of `word`) -> eight FP4 codes, through `table`
-__device__ __forceinline__ uint32_t fp4_codes(uint32_t word, int index, uint32_t table)
+// The order of the k values inside a lane's operand is free as long as A and B agree, so the 32
+// bits x of a packed half-word are not spread out bit by bit: dword d of the operand takes the
+// bits d, d + 4, ..., d + 28 of x (code number i of dword d <-> bit 4 i + d), which is one mask
+// and at most one shift per dword.
+// {0, +1} codes (A): code = bit << 1.
+__device__ __forceinline__ void fp4_codes_a(uint32_t x, int (&op)[4])
 {
-    uint32_t x = (word >> (8 * index)) & 0xffu;
-    x |= x << 6;
-    x |= x << 12;                                  // bit pair p now also sits at bits 8 p, 8 p + 1
-    return __builtin_amdgcn_perm(0u, table, x & 0x03030303u);
+    op[0] = static_cast<int>((x & 0x11111111u) << 1);
+    op[1] = static_cast<int>(x & 0x22222222u);
+    op[2] = static_cast<int>((x & 0x44444444u) >> 1);
+    op[3] = static_cast<int>((x & 0x88888888u) >> 2);
+}
+// {-1, +1} codes (B): code = 0x2 | (!bit << 3).
+__device__ __forceinline__ uint4 fp4_codes_b(uint32_t x)
+{
+    const uint32_t n = ~x;
+    return make_uint4(((n & 0x11111111u) << 3) | 0x22222222u, ((n & 0x22222222u) << 2) | 0x22222222u,
+                      ((n & 0x44444444u) << 1) | 0x22222222u, (n & 0x88888888u) | 0x22222222u);
+}
+// 0xF for every code whose bit of `valid` is set, in the same order.
+__device__ __forceinline__ uint4 fp4_code_mask(uint32_t valid)
+{
+    return make_uint4((valid & 0x11111111u) * 0xfu, ((valid >> 1) & 0x11111111u) * 0xfu,
+                      ((valid >> 2) & 0x11111111u) * 0xfu, ((valid >> 3) & 0x11111111u) * 0xfu);
 }
 
 template <int RT, int CT>
@@ -334,11 +345,7 @@ __global__ __launch_bounds__(kBlock, 2) void bitgemm_fp4_kernel(
                 uint4 *dst = reinterpret_cast<uint4 *>(lds_b + c * kFp4ColStride + q * 32);
                 atomicAdd(&col_ones[c], __popcll(b_next[t]));
 #pragma unroll
-                for (int part = 0; part < 2; ++part) {
-                    const uint32_t bits = static_cast<uint32_t>(b_next[t] >> (32 * part));
-                    dst[part] = make_uint4(fp4_codes(bits, 0, kFp4TableB), fp4_codes(bits, 1, kFp4TableB),
-                                           fp4_codes(bits, 2, kFp4TableB), fp4_codes(bits, 3, kFp4TableB));
-                }
+                for (int part = 0; part < 2; ++part) dst[part] = fp4_codes_b(static_cast<uint32_t>(b_next[t] >> (32 * part)));
             }
             return;
         }
@@ -353,13 +360,9 @@ __global__ __launch_bounds__(kBlock, 2) void bitgemm_fp4_kernel(
             if (word != 0ull) atomicAdd(&col_ones[c], __popcll(word));
 #pragma unroll
             for (int part = 0; part < 2; ++part) {
-                const uint32_t bits = static_cast<uint32_t>(b_next[t] >> (32 * part));
-                const uint32_t valid = static_cast<uint32_t>(valid_bits >> (32 * part));
-                uint32_t code[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e)      // 0xF per code that stays
-                    code[e] = fp4_codes(bits, e, kFp4TableB) & ((fp4_codes(valid, e, kFp4TableA) >> 1) * 0xfu);
-                dst[part] = make_uint4(code[0], code[1], code[2], code[3]);
+                const uint4 code = fp4_codes_b(static_cast<uint32_t>(b_next[t] >> (32 * part)));
+                const uint4 keep = fp4_code_mask(static_cast<uint32_t>(valid_bits >> (32 * part)));
+                dst[part] = make_uint4(code.x & keep.x, code.y & keep.y, code.z & keep.z, code.w & keep.w);
             }
         }
     };
@@ -381,8 +384,10 @@ __global__ __launch_bounds__(kBlock, 2) void bitgemm_fp4_kernel(
             for (int rt = 0; rt < RT; ++rt) {
                 // this lane's 32 k of row 32 rt + i32
                 const uint32_t bits = *reinterpret_cast<const uint32_t *>(a_lane + 32 * rt * kMfmaARowStride + 8 * q);
+                int codes[4];
+                fp4_codes_a(bits, codes);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) aop[rt][e] = static_cast<int>(fp4_codes(bits, e, kFp4TableA));
+                for (int e = 0; e < 4; ++e) aop[rt][e] = codes[e];
                 aop[rt][4] = aop[rt][5] = aop[rt][6] = aop[rt][7] = 0;
             }
 #pragma unroll

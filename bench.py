@@ -312,7 +312,9 @@ def main():
     ap.add_argument("--no-backward", action="store_true",
                     help="skip the back-propagation leg (one bigcn_layer_backward per layer, timed alone)")
     ap.add_argument("--no-gemm-sweep", action="store_true",
-                    help="skip the compute-bound bit-GEMM leg (both evaluation paths, M=262144, n=256, K=4096)")
+                    help="skip the compute-bound bit-GEMM leg (three evaluation paths, M=262144, n=256, K=4096)")
+    ap.add_argument("--gemm-sweep-only", action="store_true",
+                    help="run only the compute-bound bit-GEMM leg and print it (for counter collection)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -325,6 +327,9 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     B.lib()
+    if args.gemm_sweep_only:
+        print(json.dumps({"bit_gemm_sweep": gemm_sweep(B)}), flush=True)
+        return
     cfg = get_config(args.workload)
     t0 = time.perf_counter()
     work = make_workload(cfg)

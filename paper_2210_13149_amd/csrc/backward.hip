@@ -205,13 +205,28 @@ __global__ __launch_bounds__(kBlock) void backward_weight_partial_kernel(
 // U[i][c] = sum_p vals[p] beta_k (2 bit_kc - 1) = 2 P[i][c] - W_i over the neighbours k of node i,
 // P = sum over the neighbours whose bit is set, W = sum of all weights.  One wavefront per node
 // (plan order); 64 neighbours are fetched at a time, lane j holding neighbour j's weight and its
-// NW packed words of this pass; the words are broadcast one neighbour at a time and act as the
+// NW packed words of this pass (both from the neighbour's record, see sign_records_kernel); the words are broadcast one neighbour at a time and act as the
 // lane mask of the add.  Neighbours are added in list order (run-to-run identical).
+// records[k] = {packed words of node k (n_words of them), beta_k in the low half of one more word}:
+// bits and scale of a neighbour arrive with one gather instead of two.
+__global__ __launch_bounds__(kBlock) void sign_records_kernel(const uint64_t *__restrict__ f_bits, int64_t ld_f,
+                                                              const float *__restrict__ beta, int64_t n, int n_words,
+                                                              uint64_t *__restrict__ records)
+{
+    const int64_t total = n * (n_words + 1);
+    for (int64_t e = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; e < total;
+         e += static_cast<int64_t>(gridDim.x) * kBlock) {
+        const int64_t row = e / (n_words + 1);
+        const int w = static_cast<int>(e - row * (n_words + 1));
+        records[e] = w < n_words ? f_bits[row * ld_f + w] : static_cast<uint64_t>(__float_as_uint(beta[row]));
+    }
+}
+
 template <int NW>
 __global__ __launch_bounds__(kBlock) void aggregate_signs_kernel(
     const int32_t *__restrict__ row_order, int64_t n, const int64_t *__restrict__ row_ptr,
-    const int32_t *__restrict__ col_idx, const float *__restrict__ vals, const uint64_t *__restrict__ f_bits,
-    int64_t ld_f, const float *__restrict__ beta, int d_in, int word0, float *__restrict__ u, int64_t ld_u)
+    const int32_t *__restrict__ col_idx, const float *__restrict__ vals, const uint64_t *__restrict__ records,
+    int d_in, int word0, float *__restrict__ u, int64_t ld_u)
 {
     const int lane = lane_id();
     const int64_t entry = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block();
@@ -231,12 +246,12 @@ __global__ __launch_bounds__(kBlock) void aggregate_signs_kernel(
 #pragma unroll
         for (int q = 0; q < NW; ++q) { lo[q] = 0u; hi[q] = 0u; }
         if (lane < cnt) {
-            const int64_t k = col_idx[pb + lane];
-            wk = (vals != nullptr ? vals[pb + lane] : 1.0f) * beta[k];
+            const uint64_t *rec = records + static_cast<int64_t>(col_idx[pb + lane]) * (n_words + 1);
+            wk = (vals != nullptr ? vals[pb + lane] : 1.0f) * __uint_as_float(static_cast<uint32_t>(rec[n_words]));
 #pragma unroll
             for (int q = 0; q < NW; ++q) {
                 if (word0 + q < n_words) {
-                    const uint64_t word = f_bits[k * ld_f + word0 + q];
+                    const uint64_t word = rec[word0 + q];
                     lo[q] = static_cast<uint32_t>(word);
                     hi[q] = static_cast<uint32_t>(word >> 32);
                 }
@@ -388,7 +403,7 @@ __global__ __launch_bounds__(kWave) void backward_weight_finish_kernel(
 }
 
 struct BackwardMap {
-    size_t g_zeta_off, g_pad_off, wt_bits_off, scratch_scale_off, w_bits_off, alpha_off, g_wt_off, partial_off, total;
+    size_t g_zeta_off, g_pad_off, records_off, wt_bits_off, scratch_scale_off, w_bits_off, alpha_off, g_wt_off, partial_off, total;
     int64_t d_pad;        // row stride of g_zeta: d_out rounded up to a multiple of 4
     int64_t chunks, rows_per_chunk;
 };
@@ -414,6 +429,8 @@ static BackwardMap map_backward(int64_t n, int64_t d_in, int64_t d_out)
     m.g_zeta_off = off;        off = align256(off + static_cast<size_t>(n) * m.d_pad * sizeof(float));
     m.g_pad_off = off;         // padded copy of g_out, only when d_out is not a multiple of 4
     if (m.d_pad != d_out) off = align256(off + static_cast<size_t>(n) * m.d_pad * sizeof(float));
+    m.records_off = off;       // {packed signs, scale} per node, only for the first-layer order (d_in <= d_out)
+    if (d_in <= d_out) off = align256(off + static_cast<size_t>(n) * ((d_in + 63) / 64 + 1) * sizeof(uint64_t));
     m.wt_bits_off = off;       off = align256(off + static_cast<size_t>(d_in) * ((d_out + 63) / 64) * sizeof(uint64_t));
     m.scratch_scale_off = off; off = align256(off + static_cast<size_t>(d_in) * sizeof(float));
     m.w_bits_off = off;        off = align256(off + static_cast<size_t>(d_out) * ((d_in + 63) / 64) * sizeof(uint64_t));
@@ -475,11 +492,20 @@ extern "C" int bigcn_layer_backward(const bigcn_plan *plan, const int64_t *row_p
         float *u = g_zeta;
         const int64_t node_blocks = (n + kWavesPerBlock - 1) / kWavesPerBlock;
         const int n_words = static_cast<int>((d_in + 63) / 64);
+        uint64_t *records = reinterpret_cast<uint64_t *>(ws + map.records_off);
+        {
+            const int64_t total = n * (n_words + 1);
+            int64_t blocks = (total + kBlock - 1) / kBlock;
+            if (blocks > 256 * 32) blocks = 256 * 32;
+            hipLaunchKernelGGL(sign_records_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s, f_bits,
+                               ld_f_words, beta, n, n_words, records);
+            if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
+        }
         for (int word0 = 0; word0 < n_words; word0 += 4) {
 #define BIGCN_SIGNS_CASE(NW)                                                                                        \
     hipLaunchKernelGGL(aggregate_signs_kernel<NW>, dim3(static_cast<unsigned>(node_blocks)), dim3(kBlock), 0, s,   \
-                       plan->row_order, n, row_ptr, col_idx, vals, f_bits, ld_f_words, beta,                       \
-                       static_cast<int>(d_in), word0, u, d_in)
+                       plan->row_order, n, row_ptr, col_idx, vals, records, static_cast<int>(d_in), word0, u,      \
+                       d_in)
             const int left = n_words - word0;
             if (left >= 4) BIGCN_SIGNS_CASE(4);
             else if (left == 3) BIGCN_SIGNS_CASE(3);

@@ -229,13 +229,13 @@ __global__ __launch_bounds__(kBlock) void bitgemm_mfma_kernel(
 // of lane l holds row 8 (r / 4) + 4 (l / 32) + r % 4 and column l % 32.
 //
 // Tiling: wavefront 32 RT rows x 32 CT columns (RT x CT tiles of 32 x 32), workgroup four
-// wavefronts high; K in chunks of 512 bits; the chunk of B is staged as [column][256 bytes of codes +
-// 16 pad]; the number of set bits of every column is collected during the staging for the
-// epilogue.
+// wavefronts high; K in chunks of 256 bits in two LDS buffers (a chunk is staged while the one
+// before it is multiplied; one barrier per chunk); the chunk of B is staged as [column][128 bytes
+// of codes + 16 pad]; the number of set bits of every column is collected during the staging
+// for the epilogue.
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-constexpr int kFp4ColStride = kMfmaChunkWords * 32 + 16;   // LDS bytes per column of B codes
 // The order of the k values inside a lane's operand is free as long as A and B agree, so the 32
 // bits x of a packed half-word are not spread out bit by bit: dword d of the operand takes the
 // bits d, d + 4, ..., d + 28 of x (code number i of dword d <-> bit 4 i + d), which is one mask
@@ -262,6 +262,10 @@ __device__ __forceinline__ uint4 fp4_code_mask(uint32_t valid)
                       ((valid >> 2) & 0x11111111u) * 0xfu, ((valid >> 3) & 0x11111111u) * 0xfu);
 }
 
+constexpr int kFp4ChunkWords = 4;                           // 256 bits of K per stage
+constexpr int kFp4ColStride = kFp4ChunkWords * 32 + 16;     // LDS bytes per column of B codes
+constexpr int kFp4ARowStride = kFp4ChunkWords * 8 + 8;      // LDS bytes per row of packed A
+
 template <int RT, int CT>
 __global__ __launch_bounds__(kBlock, 2) void bitgemm_fp4_kernel(
     const uint64_t *__restrict__ a, int64_t m, int64_t lda, const uint64_t *__restrict__ b, int n,
@@ -270,10 +274,11 @@ __global__ __launch_bounds__(kBlock, 2) void bitgemm_fp4_kernel(
 {
     constexpr int kRows = kWavesPerBlock * 32 * RT;         // rows per workgroup
     constexpr int kCols = 32 * CT;                          // columns per workgroup
-    constexpr int kAWords = kRows * kMfmaChunkWords / kBlock;   // words of A per thread and chunk (4 or 8)
-    constexpr int kBWords = kCols * kMfmaChunkWords / kBlock;   // words of B per thread and chunk
-    __shared__ __attribute__((aligned(16))) unsigned char lds_b[kCols * kFp4ColStride];
-    __shared__ __attribute__((aligned(16))) unsigned char lds_a[kRows * kMfmaARowStride];
+    constexpr int kAWords = kRows * kFp4ChunkWords / kBlock;    // words of A per thread and chunk (2 or 4)
+    constexpr int kBWords = kCols * kFp4ChunkWords / kBlock;    // words of B per thread and chunk
+    // two buffers: chunk c + 1 is staged while chunk c is multiplied
+    __shared__ __attribute__((aligned(16))) unsigned char lds_b[2][kCols * kFp4ColStride];
+    __shared__ __attribute__((aligned(16))) unsigned char lds_a[2][kRows * kFp4ARowStride];
     __shared__ int col_ones[kCols];
     const int n_words = (k_bits + 63) >> 6;
     const int lane = lane_id();
@@ -294,73 +299,68 @@ __global__ __launch_bounds__(kBlock, 2) void bitgemm_fp4_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[rt][ct][r] = 0.0f;
 
-    // staging shares of a thread: kAWords consecutive words of one row of A (256 / kRows threads
-    // per row... kMfmaChunkWords / kAWords threads share a row), kBWords words of B (column
-    // item / 8, word item % 8, item = t + 256 u).  Addresses are recomputed at every fetch: the
-    // registers are needed for the accumulators.
-    static_assert(kMfmaChunkWords == 8, "item -> (column, word) below uses shifts");
-    constexpr int kThreadsPerRow = kMfmaChunkWords / kAWords;            // 2 or 1
+    // staging shares of a thread: kAWords consecutive words of one row of A
+    // (kFp4ChunkWords / kAWords threads share a row), kBWords words of B (column item / 4, word
+    // item % 4, item = t + 256 u).  Addresses are recomputed at every fetch: the registers are
+    // needed for the accumulators.
+    static_assert(kFp4ChunkWords == 4, "item -> (column, word) below uses shifts");
+    constexpr int kThreadsPerRow = kFp4ChunkWords / kAWords;
     const int a_thread_row = static_cast<int>(threadIdx.x) / kThreadsPerRow;
     const int a_thread_word = (static_cast<int>(threadIdx.x) % kThreadsPerRow) * kAWords;
 
-    // two chunks are fetched ahead of the one being multiplied (one multiply phase is shorter than
-    // a trip to memory): two register sets, used alternately
+    // two chunks are fetched ahead of the one being multiplied: two register sets, used alternately
     struct Fetched {
         uint64_t a[kAWords];
         uint64_t b[kBWords];
     };
     Fetched set0, set1;
     auto fetch = [&](int w0, Fetched &f) {
-        uint64_t (&a_next)[kAWords] = f.a;
-        uint64_t (&b_next)[kBWords] = f.b;
         int64_t row = block_row0 + a_thread_row;
         if (row >= m) row = m - 1;                              // clamped rows are never stored
         const uint64_t *src = a + row * lda + w0 + a_thread_word;
 #pragma unroll
-        for (int e = 0; e < kAWords; ++e) a_next[e] = (w0 + a_thread_word + e < n_words) ? src[e] : 0ull;
+        for (int e = 0; e < kAWords; ++e) f.a[e] = (w0 + a_thread_word + e < n_words) ? src[e] : 0ull;
 #pragma unroll
         for (int t = 0; t < kBWords; ++t) {
             const int item = static_cast<int>(threadIdx.x) + t * kBlock;
-            const int j = col0 + (item >> 3);
-            const int w = w0 + (item & 7);
-            b_next[t] = (j < n && w < n_words) ? b[static_cast<int64_t>(j) * ldb + w] : 0ull;
+            const int j = col0 + (item >> 2);
+            const int w = w0 + (item & 3);
+            f.b[t] = (j < n && w < n_words) ? b[static_cast<int64_t>(j) * ldb + w] : 0ull;
         }
     };
-    // w0: first word of the chunk that fetch() brought into f
-    auto stage = [&](int w0, const Fetched &f) {
-        const uint64_t (&a_next)[kAWords] = f.a;
-        const uint64_t (&b_next)[kBWords] = f.b;
-        uint2 *adst = reinterpret_cast<uint2 *>(lds_a + a_thread_row * kMfmaARowStride + a_thread_word * 8);
+    // w0: first word of the chunk that fetch() brought into f; buf: the LDS buffer to fill
+    auto stage = [&](int w0, const Fetched &f, int buf) {
+        uint2 *adst = reinterpret_cast<uint2 *>(lds_a[buf] + a_thread_row * kFp4ARowStride + a_thread_word * 8);
 #pragma unroll
         for (int e = 0; e < kAWords; ++e)
-            adst[e] = make_uint2(static_cast<uint32_t>(a_next[e]), static_cast<uint32_t>(a_next[e] >> 32));
+            adst[e] = make_uint2(static_cast<uint32_t>(f.a[e]), static_cast<uint32_t>(f.a[e] >> 32));
         // 64 bits -> 64 codes (32 bytes): +1 -> 0x2, -1 -> 0xA, past K or past the last column -> 0x0
-        const bool whole = (w0 + kMfmaChunkWords) * 64 <= k_bits && col0 + kCols <= n;   // uniform
+        const bool whole = (w0 + kFp4ChunkWords) * 64 <= k_bits && col0 + kCols <= n;   // uniform
         if (whole) {
             // every bit of the chunk counts: no masks
 #pragma unroll
             for (int t = 0; t < kBWords; ++t) {
                 const int item = static_cast<int>(threadIdx.x) + t * kBlock;
-                const int c = item >> 3, q = item & 7;
-                uint4 *dst = reinterpret_cast<uint4 *>(lds_b + c * kFp4ColStride + q * 32);
-                atomicAdd(&col_ones[c], __popcll(b_next[t]));
+                const int c = item >> 2, q = item & 3;
+                uint4 *dst = reinterpret_cast<uint4 *>(lds_b[buf] + c * kFp4ColStride + q * 32);
+                atomicAdd(&col_ones[c], __popcll(f.b[t]));
 #pragma unroll
-                for (int part = 0; part < 2; ++part) dst[part] = fp4_codes_b(static_cast<uint32_t>(b_next[t] >> (32 * part)));
+                for (int part = 0; part < 2; ++part) dst[part] = fp4_codes_b(static_cast<uint32_t>(f.b[t] >> (32 * part)));
             }
             return;
         }
 #pragma unroll
         for (int t = 0; t < kBWords; ++t) {
             const int item = static_cast<int>(threadIdx.x) + t * kBlock;
-            const int c = item >> 3, q = item & 7;
+            const int c = item >> 2, q = item & 3;
             const int left = (col0 + c < n) ? k_bits - 64 * (w0 + q) : 0;        // bits of this word below K
             const uint64_t valid_bits = left >= 64 ? ~0ull : (left <= 0 ? 0ull : ((1ull << left) - 1ull));
-            uint4 *dst = reinterpret_cast<uint4 *>(lds_b + c * kFp4ColStride + q * 32);
-            const uint64_t word = b_next[t] & valid_bits;
+            uint4 *dst = reinterpret_cast<uint4 *>(lds_b[buf] + c * kFp4ColStride + q * 32);
+            const uint64_t word = f.b[t] & valid_bits;
             if (word != 0ull) atomicAdd(&col_ones[c], __popcll(word));
 #pragma unroll
             for (int part = 0; part < 2; ++part) {
-                const uint4 code = fp4_codes_b(static_cast<uint32_t>(b_next[t] >> (32 * part)));
+                const uint4 code = fp4_codes_b(static_cast<uint32_t>(f.b[t] >> (32 * part)));
                 const uint4 keep = fp4_code_mask(static_cast<uint32_t>(valid_bits >> (32 * part)));
                 dst[part] = make_uint4(code.x & keep.x, code.y & keep.y, code.z & keep.z, code.w & keep.w);
             }
@@ -368,22 +368,22 @@ __global__ __launch_bounds__(kBlock, 2) void bitgemm_fp4_kernel(
     };
 
     fetch(0, set0);
-    if (kMfmaChunkWords < n_words) fetch(kMfmaChunkWords, set1);
+    if (kFp4ChunkWords < n_words) fetch(kFp4ChunkWords, set1);
     __syncthreads();                                      // col_ones cleared
-    stage(0, set0);
+    stage(0, set0, 0);
     __syncthreads();
 
-    const unsigned char *a_lane = lds_a + (wave * 32 * RT + i32) * kMfmaARowStride + 4 * half;
-    const unsigned char *b_lane = lds_b + i32 * kFp4ColStride + 16 * half;
+    const int a_lane = (wave * 32 * RT + i32) * kFp4ARowStride + 4 * half;
+    const int b_lane = i32 * kFp4ColStride + 16 * half;
 
-    // multiply the chunk that starts at word w0 (it is in LDS)
-    auto multiply = [&](int w0) {
+    // multiply the chunk that starts at word w0 (it is in LDS buffer buf)
+    auto multiply = [&](int w0, int buf) {
         auto step = [&](int q) {
             v8i aop[RT], bop[CT];
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
                 // this lane's 32 k of row 32 rt + i32
-                const uint32_t bits = *reinterpret_cast<const uint32_t *>(a_lane + 32 * rt * kMfmaARowStride + 8 * q);
+                const uint32_t bits = *reinterpret_cast<const uint32_t *>(lds_a[buf] + a_lane + 32 * rt * kFp4ARowStride + 8 * q);
                 int codes[4];
                 fp4_codes_a(bits, codes);
 #pragma unroll
@@ -392,7 +392,7 @@ __global__ __launch_bounds__(kBlock, 2) void bitgemm_fp4_kernel(
             }
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
-                const uint4 codes = *reinterpret_cast<const uint4 *>(b_lane + 32 * ct * kFp4ColStride + 32 * q);
+                const uint4 codes = *reinterpret_cast<const uint4 *>(lds_b[buf] + b_lane + 32 * ct * kFp4ColStride + 32 * q);
                 bop[ct][0] = static_cast<int>(codes.x);
                 bop[ct][1] = static_cast<int>(codes.y);
                 bop[ct][2] = static_cast<int>(codes.z);
@@ -406,30 +406,31 @@ __global__ __launch_bounds__(kBlock, 2) void bitgemm_fp4_kernel(
                     acc[rt][ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
                         aop[rt], bop[ct], acc[rt][ct], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
         };
-        if (w0 + kMfmaChunkWords <= n_words) {
+        if (w0 + kFp4ChunkWords <= n_words) {
             // a whole chunk: no exit between the steps, so their operands can be prepared ahead
 #pragma unroll
-            for (int q = 0; q < kMfmaChunkWords; ++q) step(q);
+            for (int q = 0; q < kFp4ChunkWords; ++q) step(q);
         } else {
             for (int q = 0; w0 + q < n_words; ++q) step(q);
         }
     };
-    // chunk c is multiplied while chunk c + 1 waits in a register set and chunk c + 2 is fetched
-    // into the other; two chunks per turn so that the sets keep their names
-    for (int w0 = 0; w0 < n_words; w0 += 2 * kMfmaChunkWords) {
-        const int w1 = w0 + kMfmaChunkWords, w2 = w0 + 2 * kMfmaChunkWords, w3 = w0 + 3 * kMfmaChunkWords;
-        if (w2 < n_words) fetch(w2, set0);                  // set0 was staged before this turn
-        multiply(w0);
-        __syncthreads();                                    // every wavefront has left this chunk
-        if (w1 < n_words) stage(w1, set1);
-        __syncthreads();
+    // Turn c: chunk c + 2 is fetched into the register set that chunk c was staged from, chunk c
+    // (LDS buffer c % 2) is multiplied, chunk c + 1 is staged into the other buffer, one barrier.
+    // That barrier publishes chunk c + 1 and tells that nobody reads buffer c % 2 any more, which
+    // the next turn overwrites.  Two chunks per loop turn so that sets and buffers keep their names.
+    for (int w0 = 0; w0 < n_words; w0 += 2 * kFp4ChunkWords) {
+        const int w1 = w0 + kFp4ChunkWords, w2 = w0 + 2 * kFp4ChunkWords, w3 = w0 + 3 * kFp4ChunkWords;
+        if (w2 < n_words) fetch(w2, set0);
+        multiply(w0, 0);
         if (w1 >= n_words) break;                           // uniform
-        if (w3 < n_words) fetch(w3, set1);
-        multiply(w1);
+        stage(w1, set1, 1);
         __syncthreads();
-        if (w2 < n_words) stage(w2, set0);
+        if (w3 < n_words) fetch(w3, set1);
+        multiply(w1, 1);
+        if (w2 < n_words) stage(w2, set0, 0);
         __syncthreads();
     }
+    __syncthreads();                                        // col_ones complete for every wavefront
 
     // epilogue: c = 2 * acc - (2 popcount(B_j) - K)
 #pragma unroll

@@ -318,7 +318,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-                 "(no collectives are part of it; see DESIGN.md, 'How the path would shard').")
+                 "(no collectives are part of it).")
 
     import torch
     from paper_2210_13149_amd import binding as B, cost_model

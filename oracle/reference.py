@@ -417,7 +417,8 @@ def sage_forward(row_ptr, col_idx, x: np.ndarray, weights: Sequence[Tuple[np.nda
 # ---- Bi-GAT (Sec. 4.4.1) ------------------------------------------------------------------------
 
 def gat_layer(row_ptr, col_idx, h: np.ndarray, w: np.ndarray, a_src: np.ndarray, a_dst: np.ndarray,
-              heads: int = 1, negative_slope: float = 0.2, shift=None, mul=None) -> Dict[str, np.ndarray]:
+              heads: int = 1, negative_slope: float = 0.2, shift=None, mul=None,
+              nodes=None) -> Dict[str, np.ndarray]:
     """One Bi-GAT layer (Sec. 4.4.1): with z_j = W~ (*) h~_j (the binarised product of Sec. 4.2,
     ``heads`` blocks of d_out / heads columns, one weight block and one attention vector per
     head),
@@ -427,7 +428,9 @@ def gat_layer(row_ptr, col_idx, h: np.ndarray, w: np.ndarray, a_src: np.ndarray,
         out_i = sum_{j in N_i} a_ij z_j                     (no further non-linearity)
 
     per head, the heads' outputs side by side.  ``a_src``, ``a_dst``: (heads, d_out / heads).
-    fp64 throughout; a node with an empty row gives zeros.  Returns every intermediate."""
+    fp64 throughout; a node with an empty row gives zeros.  Returns every intermediate.
+    ``nodes``: if given, ``out`` and ``att`` are computed for these nodes only (the other rows
+    stay zero); ``zeta``, ``s`` and ``t`` always cover every node."""
     row_ptr, col_idx, n = _check_csr(row_ptr, col_idx)
     sign, beta = binarize_rows(h, shift, mul)
     bt, alpha = binarize_weight(w)
@@ -443,7 +446,7 @@ def gat_layer(row_ptr, col_idx, h: np.ndarray, w: np.ndarray, a_src: np.ndarray,
     t = (z3 * a_dst[None]).sum(axis=2)
     out = np.zeros((n, heads, dh), dtype=np.float64)
     att = np.zeros((col_idx.size, heads), dtype=np.float64)
-    for i in range(n):
+    for i in (range(n) if nodes is None else (int(v) for v in nodes)):
         p0, p1 = int(row_ptr[i]), int(row_ptr[i + 1])
         if p0 == p1:
             continue

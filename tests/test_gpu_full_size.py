@@ -12,6 +12,8 @@ import time
 import numpy as np
 import pytest
 
+import oracle
+
 from helpers import assert_close, compare_forward_layerwise, to_device
 from test_gpu_forward import calibration_spec, gpu_prefix_runner
 from workloads import make_workload
@@ -93,3 +95,54 @@ def test_full_size_aggregation_invariant_and_repeatability(B):
     torch.cuda.synchronize()
     assert torch.equal(out, again)
     assert_close(out.cpu().numpy(), z.astype(np.float64), "A~ sqrt(d)")
+
+
+@pytest.mark.timeout(900)
+def test_full_size_gat_layer_on_sampled_nodes(B):
+    """One Bi-GAT layer (100 -> 256 columns, two heads) on the whole c5 graph: the oracle evaluates
+    the definition for 3000 sampled nodes, among them the 200 longest rows (shared by a workgroup
+    on the GPU) and nodes of the smallest degree; the rounding bound is that of test_gpu_gat."""
+    import torch
+    from helpers import to_device
+    t0 = time.time()
+    say = _say(t0)
+    work = make_workload("c5")
+    n, d_in, d_out, heads = work.n, work.config.dims[0], 256, 2
+    rng = np.random.default_rng(17)
+    w = rng.uniform(-1, 1, size=(d_in, d_out)).astype(np.float32)
+    dh = d_out // heads
+    a_src = (rng.standard_normal((heads, dh)) / np.sqrt(dh)).astype(np.float32)
+    a_dst = (rng.standard_normal((heads, dh)) / np.sqrt(dh)).astype(np.float32)
+    deg = np.diff(work.row_ptr)
+    order = np.argsort(deg)
+    nodes = np.unique(np.concatenate([order[-200:], order[:300], rng.choice(n, 2500, replace=False)]))
+    say(f"oracle on {nodes.size} of {n} nodes")
+    ref = oracle.gat_layer(work.row_ptr, work.col_idx, work.x, w, a_src, a_dst, heads=heads, negative_slope=0.2,
+                           nodes=nodes)
+    say("GPU")
+    drp, dci, dx, dw = to_device(work.row_ptr, work.col_idx, work.x, w)
+    plan = B.Plan(drp, dci)
+    layer = B.Layer.from_weight(dw)
+    got = B.bigcn_gat_layer(plan, drp, dci, dx, layer, to_device(a_src), to_device(a_dst), heads=heads,
+                            negative_slope=0.2)
+    torch.cuda.synchronize()
+    got = got[torch.from_numpy(nodes).cuda()].cpu().numpy()
+    say("compare")
+    u = 2.0 ** -24
+    want = ref["out"][nodes]
+    z3 = np.abs(ref["zeta"]).reshape(n, heads, dh)
+    es = (z3 * np.abs(a_src).reshape(1, heads, dh)).sum(axis=2)
+    et = (z3 * np.abs(a_dst).reshape(1, heads, dh)).sum(axis=2)
+    bound = np.zeros_like(want)
+    for r, i in enumerate(nodes):
+        p0, p1 = int(work.row_ptr[i]), int(work.row_ptr[i + 1])
+        nb = work.col_idx[p0:p1]
+        for h in range(heads):
+            eps_e = (2 * dh + 4) * u * (es[i, h] + et[nb, h].max())
+            mag = ref["att"][p0:p1, h] @ np.abs(ref["zeta"][nb, h * dh:(h + 1) * dh])
+            bound[r, h * dh:(h + 1) * dh] = (2 * eps_e + (p1 - p0 + 8) * u) * mag
+    diff = np.abs(got - want)
+    ok = (diff <= 1e-5 * np.abs(want) + 1e-6) | (diff <= bound)
+    assert ok.all(), f"{int((~ok).sum())} of {ok.size} elements out of tolerance, worst {diff[~ok].max():.3e}"
+    assert (diff <= 1e-5 * np.abs(want) + 1e-6).mean() > 0.99
+    assert deg[nodes].max() >= 256 and np.abs(want).max() > 0

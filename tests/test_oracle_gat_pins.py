@@ -96,3 +96,25 @@ def test_empty_row_and_single_neighbour():
     rec = oracle.gat_layer(rp, ci, h, w, RNG.standard_normal((2, 2)), RNG.standard_normal((2, 2)), heads=2)
     assert np.array_equal(rec["out"][2], np.zeros(4))
     assert np.allclose(rec["out"][0], rec["zeta"][1], rtol=1e-15)
+
+
+def test_gat_on_a_subset_of_nodes_equals_the_rows_of_the_full_result():
+    rng = np.random.default_rng(21)
+    n, d_in, d_out, heads = 60, 20, 8, 2
+    u = rng.integers(0, n, 200)
+    v = rng.integers(0, n, 200)
+    keep = u != v
+    pairs = np.unique(np.sort(np.stack([u[keep], v[keep]], axis=1), axis=1), axis=0)
+    from workloads import csr_from_undirected_edges
+    rp, ci = csr_from_undirected_edges(n, pairs[:, 0], pairs[:, 1])
+    x = rng.standard_normal((n, d_in))
+    w = rng.standard_normal((d_in, d_out))
+    a_src = rng.standard_normal((heads, d_out // heads))
+    a_dst = rng.standard_normal((heads, d_out // heads))
+    full = oracle.gat_layer(rp, ci, x, w, a_src, a_dst, heads=heads)
+    nodes = np.array([3, 17, 59, 0])
+    part = oracle.gat_layer(rp, ci, x, w, a_src, a_dst, heads=heads, nodes=nodes)
+    assert np.array_equal(part["out"][nodes], full["out"][nodes])
+    rest = np.setdiff1d(np.arange(n), nodes)
+    assert not part["out"][rest].any()
+    assert np.array_equal(part["zeta"], full["zeta"])

@@ -114,6 +114,15 @@ int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const 
                           int64_t n, int64_t ldb, int64_t k_bits, const float *src_scale, void *c_rows,
                           void *alt_rows, RowLayout layout, hipStream_t stream);
 
+// First layer of a small graph: binarise the fp32 rows of x and multiply in one launch; writes
+// the product rows and scale[i] = row_mul[i] * beta_i (negated for a folded last bit of -1).
+// BIGCN_EINVAL: shape not covered (more than 32768 rows, or a row wider than one wavefront's
+// column block); nothing was launched.
+bool pack_bitgemm_covers(int64_t m, int64_t k_bits, const RowLayout &layout);
+int launch_pack_bitgemm_layout(const float *x, int64_t m, int64_t ld_x, const float *shift, const float *mul,
+                               const float *row_mul, float *scale, const uint64_t *b_bits, int64_t n, int64_t ldb,
+                               int64_t k_bits, void *c_rows, void *alt_rows, RowLayout layout, hipStream_t stream);
+
 // bit-GEMM writing the integer products of a row in column order (`positions` stored values per
 // row, a multiple of 8 and >= n; multiples of 64 from 64 on): one byte per product holds
 // floor(K/2) - popcount (K <= 255 only), fp16 / fp32 hold K - 2 popcount.

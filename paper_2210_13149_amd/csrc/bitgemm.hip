@@ -515,6 +515,100 @@ __global__ __launch_bounds__(kBlock) void bitgemm_small_kernel(
     }
 }
 
+// The same for the first layer of a small graph, with the binarisation folded in: the wavefront
+// reads its row of the fp32 input itself (lane l reads column 64 w + l), the 64-bit ballot of
+// "x >= threshold" is word w of the row (already wave-uniform: no broadcast), and the row scale
+// mean |(x - shift) mul| times the optional per-row factor is known when the row ends, in time for
+// the epilogue.  One launch instead of two and no packed input written or read.
+// fold_last: the row's last bit is left out of the product (last_mask) and carried by the sign of
+// the stored scale, as the binarise+pack kernel does.
+template <int VB, class Epilogue>
+__global__ __launch_bounds__(kBlock) void pack_bitgemm_small_kernel(
+    const float *__restrict__ x, int64_t m, int64_t ld_x, int k_bits, const float *__restrict__ shift,
+    const float *__restrict__ mul, const float *__restrict__ row_mul, int fold_last, float *__restrict__ scale,
+    const uint64_t *__restrict__ b, int n, int64_t ldb, uint32_t last_mask, ColumnMap map, Epilogue epi)
+{
+    extern __shared__ uint64_t lds_b[];          // [n_words][64*VB]
+    constexpr int CB = 64 * VB;
+    constexpr int U = 4;                         // row loads in flight
+    const int n_words = (k_bits + 63) >> 6;
+    const int y = blockIdx.y;
+    stage_b_block<VB>(lds_b, b, n, ldb, n_words, last_mask, map, y);
+    const uint2 *lds_b2 = reinterpret_cast<const uint2 *>(lds_b);
+
+    const int lane = lane_id();
+    int col[VB];
+    bool any;
+    const int pos0 = lane_columns<VB>(map, y, lane, col, any);
+    typename Epilogue::template Lane<VB> ctx;
+    epi.template init<VB>(col, pos0, n, ctx);
+    const float inv_cols = 1.0f / static_cast<float>(k_bits);
+
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block();
+    const int64_t n_waves = static_cast<int64_t>(gridDim.x) * kWavesPerBlock;
+    for (int64_t row = wave; row < m; row += n_waves) {
+        const float *xr = x + row * ld_x;
+        int pop[VB];
+#pragma unroll
+        for (int v = 0; v < VB; ++v) pop[v] = epi.pop_init();
+        float sum = 0.0f;
+        uint64_t last_word = 0;
+        for (int w0 = 0; w0 < n_words; w0 += U) {
+            float xv[U], th[U], ml[U];
+            bool in[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = 64 * (w0 + u) + lane;
+                in[u] = c < k_bits;
+                xv[u] = in[u] ? xr[c] : 0.0f;
+                th[u] = (shift != nullptr && in[u]) ? shift[c] : 0.0f;
+                ml[u] = (mul != nullptr && in[u]) ? mul[c] : 1.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int w = w0 + u;
+                if (w >= n_words) break;                      // wave-uniform
+                const uint64_t word = __ballot(in[u] && xv[u] >= th[u]);
+                sum += in[u] ? fabsf((xv[u] - th[u]) * ml[u]) : 0.0f;
+                last_word = word;
+                const uint32_t lo = static_cast<uint32_t>(word);
+                uint32_t hi = static_cast<uint32_t>(word >> 32);
+                if (w == n_words - 1) hi &= last_mask;
+#pragma unroll
+                for (int v = 0; v < VB; ++v) {
+                    const uint2 bw = lds_b2[w * CB + lane + 64 * v];
+                    pop[v] = __popc(lo ^ bw.x) + pop[v];
+                    pop[v] = __popc(hi ^ bw.y) + pop[v];
+                }
+            }
+        }
+        sum = wave_sum(sum);
+        float s = sum * inv_cols;
+        if (row_mul != nullptr) s *= row_mul[row];
+        if (fold_last && ((last_word >> ((k_bits - 1) & 63)) & 1ull) == 0) s = -s;
+        if (lane == 0 && y == 0) scale[row] = s;
+        epi.template store<VB>(ctx, row, s, col, pos0, any, n, pop);
+    }
+}
+
+template <int VB, class Epilogue>
+static int launch_pack_bitgemm_small(const float *x, int64_t m, int64_t ld_x, int64_t k_bits, const float *shift,
+                                     const float *mul, const float *row_mul, int fold_last, float *scale,
+                                     const uint64_t *b, int64_t n, int64_t ldb, uint32_t last_mask, ColumnMap map,
+                                     int col_blocks, const Epilogue &epi, hipStream_t stream)
+{
+    const int n_words = static_cast<int>((k_bits + 63) / 64);
+    const size_t lds = static_cast<size_t>(64) * VB * n_words * sizeof(uint64_t);
+    int64_t blocks = (m + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t cap = 256 * 8 / col_blocks > 256 ? 256 * 8 / col_blocks : 256;
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL((pack_bitgemm_small_kernel<VB, Epilogue>), dim3(static_cast<unsigned>(blocks), col_blocks),
+                       dim3(kBlock), lds, stream, x, m, ld_x, static_cast<int>(k_bits), shift, mul, row_mul, fold_last,
+                       scale, b, static_cast<int>(n), ldb, last_mask, map, epi);
+    return check_launch();
+}
+
 // Row counts up to which bitgemm_small_kernel is used (one wavefront per row still fits the
 // resident wavefronts of the chip a few times over).
 constexpr int64_t kSmallRows = 32768;
@@ -638,6 +732,64 @@ int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const 
     EpilogueLayout<float> epi{static_cast<float *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, 0, nullptr, 0};
     return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
                             last_mask, epi, stream);
+}
+
+// Binarisation of the fp32 input fused into the first layer's bit-GEMM (graphs of at most
+// kSmallRows nodes): writes the product rows of `layout` and the source scales, nothing else.
+// Returns BIGCN_EINVAL when the shape is not covered (the caller then runs the two kernels).
+// Whether launch_pack_bitgemm_layout takes the shape: a small graph, and a row's products within
+// one wavefront's column block (several blocks would each re-read the fp32 row).
+bool pack_bitgemm_covers(int64_t m, int64_t k_bits, const RowLayout &layout)
+{
+    if (m > kSmallRows) return false;
+    const int per_lane = layout.positions() >= 64 ? layout.positions() / 64 : 1;
+    const int n_words = static_cast<int>((k_bits + 63) / 64);
+    int vb = per_lane >= 8 ? 8 : (per_lane >= 4 ? 4 : (per_lane >= 2 ? 2 : 1));
+    while (vb > 1 && vb * n_words > 128) vb >>= 1;
+    return (per_lane + vb - 1) / vb == 1;
+}
+
+int launch_pack_bitgemm_layout(const float *x, int64_t m, int64_t ld_x, const float *shift, const float *mul,
+                               const float *row_mul, float *scale, const uint64_t *b_bits, int64_t n, int64_t ldb,
+                               int64_t k_bits, void *c_rows, void *alt_rows, RowLayout layout, hipStream_t stream)
+{
+    if (m == 0 || n == 0) return BIGCN_OK;
+    if (!pack_bitgemm_covers(m, k_bits, layout)) return BIGCN_EINVAL;
+    if (layout.escape && alt_rows == nullptr) return BIGCN_ENULL;
+    const int per_lane = layout.positions() >= 64 ? layout.positions() / 64 : 1;
+    const int n_words = static_cast<int>((k_bits + 63) / 64);
+    int vb = per_lane >= 8 ? 8 : (per_lane >= 4 ? 4 : (per_lane >= 2 ? 2 : 1));
+    while (vb > 1 && vb * n_words > 128) vb >>= 1;
+    const int col_blocks = 1;
+    const uint32_t last_mask = layout.fold_last ? 0x7fffffffu : 0xffffffffu;
+    const ColumnMap map{layout.groups, layout.vec, per_lane};
+#define BIGCN_PACK_GEMM(EPI)                                                                                       \
+    switch (vb) {                                                                                                  \
+    case 8: return launch_pack_bitgemm_small<8>(x, m, ld_x, k_bits, shift, mul, row_mul, layout.fold_last, scale,  \
+                                                b_bits, n, ldb, last_mask, map, col_blocks, EPI, stream);          \
+    case 4: return launch_pack_bitgemm_small<4>(x, m, ld_x, k_bits, shift, mul, row_mul, layout.fold_last, scale,  \
+                                                b_bits, n, ldb, last_mask, map, col_blocks, EPI, stream);          \
+    case 2: return launch_pack_bitgemm_small<2>(x, m, ld_x, k_bits, shift, mul, row_mul, layout.fold_last, scale,  \
+                                                b_bits, n, ldb, last_mask, map, col_blocks, EPI, stream);          \
+    default: return launch_pack_bitgemm_small<1>(x, m, ld_x, k_bits, shift, mul, row_mul, layout.fold_last, scale, \
+                                                 b_bits, n, ldb, last_mask, map, col_blocks, EPI, stream);         \
+    }
+    if (layout.kind == kI8) {
+        if (layout.escape && layout.alt_kind != kI8 && layout.alt_kind != kF16) return BIGCN_EINVAL;
+        // the scale is computed inside the kernel: `embed` only says that the layout wants it in the row
+        EpilogueLayout<int8_t> epi{static_cast<int8_t *>(c_rows), layout.positions(), layout.k_eff,
+                                   layout.embed_scale != kScaleSeparate ? scale : nullptr,
+                                   layout.embed_scale == kScaleInTopBits ? 3 : 0, layout.groups,
+                                   layout.escape ? alt_rows : nullptr, layout.alt_kind == kF16 ? 1 : 0};
+        BIGCN_PACK_GEMM(epi)
+    }
+    if (layout.kind == kF16) {
+        EpilogueLayout<__half> epi{static_cast<__half *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, 0, nullptr, 0};
+        BIGCN_PACK_GEMM(epi)
+    }
+    EpilogueLayout<float> epi{static_cast<float *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, 0, nullptr, 0};
+    BIGCN_PACK_GEMM(epi)
+#undef BIGCN_PACK_GEMM
 }
 
 // Product rows in column order (stored position = output column) for consumers that read a row's

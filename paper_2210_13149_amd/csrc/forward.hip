@@ -202,10 +202,16 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
     // layer 0 input: binarise X (or take it binarised); the stored scale is src_row_mul[i] * beta_i
     int64_t words = (layers[0].d_in + 63) / 64;
     const uint64_t *in_bits = bits;
-    const int fold0 = choose_layout(layers[0].d_in, layers[0].d_out).fold_last;
+    const RowLayout layout0 = choose_layout(layers[0].d_in, layers[0].d_out);
+    const int fold0 = layout0.fold_last;
+    // small graphs: the binarisation of X is folded into the first bit-GEMM (one launch fewer, no
+    // packed input written); not with an own-row term, whose two products share the packed input
+    const bool fuse0 = !packed && !own_term && pack_bitgemm_covers(n, layers[0].d_in, layout0);
     BIGCN_MARK();
-    int rc;
-    if (packed) {
+    int rc = BIGCN_OK;
+    if (fuse0) {
+        // nothing to launch here
+    } else if (packed) {
         in_bits = in.bits;
         words = in.ld_words;
         rc = launch_source_scale(in.beta, src_row_mul, in.bits, in.ld_words, layers[0].d_in, fold0, scale[0], n, s);
@@ -219,8 +225,12 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
     for (int l = 0; l < n_layers; ++l) {
         const LayerView &L = layers[l];
         const RowLayout layout = choose_layout(L.d_in, L.d_out);
-        rc = launch_bitgemm_layout(in_bits, n, words, L.w_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1], c_rows,
-                                   alt_rows, layout, s);
+        if (l == 0 && fuse0)
+            rc = launch_pack_bitgemm_layout(x, n, ld_x, L.bn_shift, L.bn_mul, src_row_mul, scale[0], L.w_bits, L.d_out,
+                                            L.ld_words, L.d_in, c_rows, alt_rows, layout, s);
+        else
+            rc = launch_bitgemm_layout(in_bits, n, words, L.w_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1], c_rows,
+                                       alt_rows, layout, s);
         if (rc != BIGCN_OK) return rc;
         if (own_term) {
             rc = launch_bitgemm_layout(in_bits, n, words, L.w_self_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1],

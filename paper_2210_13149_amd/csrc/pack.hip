@@ -124,66 +124,6 @@ __global__ __launch_bounds__(kBlock) void pack_generic_kernel(
     }
 }
 
-// Few long rows (the input features of a small graph): the four wavefronts of a workgroup share
-// one row, wavefront q taking the groups of U words q, q + 4, ..., so that the launch costs the
-// latency of one or two rounds of loads instead of a walk along the whole row.
-__global__ __launch_bounds__(kBlock) void pack_split_kernel(
-    const float *__restrict__ x, int64_t rows, int64_t cols, int64_t row_stride,
-    int64_t col_stride, const float *__restrict__ shift, const float *__restrict__ mul,
-    const float *__restrict__ row_mul, int fold_last_sign, uint64_t *__restrict__ bits,
-    int64_t ld_words, float *__restrict__ scale)
-{
-    constexpr int U = 8;
-    __shared__ float partial[kWavesPerBlock];
-    __shared__ uint64_t last_shared;
-    const int lane = lane_id();
-    const int wave = wave_in_block();
-    const int64_t n_words = (cols + 63) / 64;
-    const float inv_cols = 1.0f / static_cast<float>(cols);
-
-    for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
-        const float *xr = x + row * row_stride;
-        float sum = 0.0f;
-        for (int64_t w0 = static_cast<int64_t>(wave) * U; w0 < n_words; w0 += kWavesPerBlock * U) {
-            float v[U], th[U], ml[U];
-            bool in[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int64_t c = 64 * (w0 + u) + lane;
-                in[u] = c < cols;
-                v[u] = in[u] ? xr[c * col_stride] : 0.0f;
-                th[u] = (shift != nullptr && in[u]) ? shift[c] : 0.0f;
-                ml[u] = (mul != nullptr && in[u]) ? mul[c] : 1.0f;
-            }
-            uint64_t mine = 0;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint64_t word = __ballot(in[u] && (v[u] >= th[u]));
-                if (lane == u) mine = word;
-                sum += in[u] ? fabsf((v[u] - th[u]) * ml[u]) : 0.0f;
-            }
-            // lanes 0..U-1 hold words w0 .. w0 + U - 1: one store
-            if (lane < U && w0 + lane < n_words) {
-                bits[row * ld_words + w0 + lane] = mine;
-                if (w0 + lane == n_words - 1) last_shared = mine;
-            }
-        }
-        sum = wave_sum(sum);
-        if (lane == 0) partial[wave] = sum;
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            float total = 0.0f;
-#pragma unroll
-            for (int q = 0; q < kWavesPerBlock; ++q) total += partial[q];
-            float s = total * inv_cols;
-            if (row_mul != nullptr) s *= row_mul[row];
-            if (fold_last_sign && ((last_shared >> ((cols - 1) & 63)) & 1ull) == 0) s = -s;
-            scale[row] = s;
-        }
-        __syncthreads();          // partial[] and last_shared are reused by the next row
-    }
-}
-
 // Source scale of an input that arrives already binarised: beta_i times the optional per-row
 // factor, negated when the layout folds the last input bit and that bit is -1.
 __global__ __launch_bounds__(kBlock) void source_scale_kernel(const float *__restrict__ beta,
@@ -218,10 +158,6 @@ static int grid_for_waves(int64_t waves_needed)
     return static_cast<int>(blocks < 1 ? 1 : (blocks > cap ? cap : blocks));
 }
 
-// Row counts up to which a long row (at least 16 words: work for two wavefronts or more) is shared
-// by the wavefronts of a workgroup (pack_split_kernel); beyond, one wavefront per row fills the chip.
-constexpr int64_t kSplitRows = 8192;
-
 int launch_pack(const float *x, int64_t rows, int64_t cols, int64_t row_stride,
                 int64_t col_stride, const float *shift, const float *mul, const float *row_mul,
                 int fold_last_sign, uint64_t *bits, int64_t ld_words, float *scale,
@@ -242,10 +178,6 @@ int launch_pack(const float *x, int64_t rows, int64_t cols, int64_t row_stride,
         default: BIGCN_PACK_SHORT(4); break;
         }
 #undef BIGCN_PACK_SHORT
-    } else if (n_words >= 4 * 4 && rows <= kSplitRows) {
-        hipLaunchKernelGGL(pack_split_kernel, dim3(static_cast<unsigned>(rows)), dim3(kBlock), 0, stream,
-                           x, rows, cols, row_stride, col_stride, shift, mul, row_mul, fold_last_sign,
-                           bits, ld_words, scale);
     } else {
         hipLaunchKernelGGL(pack_generic_kernel, dim3(grid_for_waves(rows)), dim3(kBlock), 0, stream,
                            x, rows, cols, row_stride, col_stride, shift, mul, row_mul, fold_last_sign,

@@ -499,4 +499,245 @@ int launch_bitgemm_mfma(const uint64_t *a_bits, const float *a_scale, int64_t m,
     return check_launch();
 }
 
+// ---- product rows of the fused forward on the FP4 matrix cores (K <= 256) ----------------------
+// Two kernels.  fp4_weight_codes_kernel expands the packed weights once per call into FP4 codes
+// ordered by stored position (position p of a RowLayout holds column p / vec + groups (p % vec)),
+// with the per-position constant 128 - h, h = (2 popcount - K' + K' mod 2) / 2: the stored value
+// of a one-byte row, floor(K'/2) - popcount(f xor b), equals sum_k a_k b_k - h with a in {0, 1}.
+// bitgemm_fp4_rows_kernel: a block keeps the weight codes (32 KB at most) and the constants in
+// LDS for its whole life; a wavefront owns 32 rows at a time and all positions of them.  The
+// weights are the first operand of the multiply, so that the four accumulator registers of a
+// group hold four consecutive positions of one row: the accumulators start at 128 - h, come out
+// as value + 128 in 0..255, are packed four to a dword by the saturating byte conversion, flipped
+// back to two's complement and written into the wavefront's own LDS buffer [row][position].
+// Then the wavefront walks its rows: the lanes of a row take 8 bytes each, test the 7-bit range
+// where the layout asks for it (bit 7 differs from bit 6), stamp the scale (top bits of the
+// carrier bytes, or the last four bytes) and write whole rows with coalesced 8-byte stores; rows
+// that do not fit go to the alternate array with a NaN scale in the main row, as in the
+// vector-ALU kernels.  The bits and the scale of the next 32 rows are fetched while the current
+// ones are multiplied.
+struct Fp4RowsParams {
+    int positions;        // 128 or 256
+    int groups, vec;      // of the RowLayout
+    int k_bits;           // K' (without a folded last bit)
+    int n_steps;          // ceil(K' / 64)
+    int seven_bit;        // scale bits in the top bits of the carrier bytes
+    int tail_scale;       // scale in the last four bytes
+    int escape;           // rows outside the 7-bit range go to alt_rows
+};
+
+// codes: [step][position / 32][2 halves][position % 32] of 16 bytes; bias: [position] floats.
+// One thread per (position, step).
+__global__ __launch_bounds__(kBlock) void fp4_weight_codes_kernel(const uint64_t *__restrict__ b, int n, int64_t ldb,
+                                                                  Fp4RowsParams p, uint4 *__restrict__ codes,
+                                                                  float *__restrict__ bias)
+{
+    const int item = blockIdx.x * kBlock + threadIdx.x;
+    if (item >= p.positions * p.n_steps) return;
+    const int pos = item / p.n_steps, q = item - pos * p.n_steps;
+    const int col = pos / p.vec + p.groups * (pos % p.vec);
+    const int left = col < n ? p.k_bits - 64 * q : 0;                     // bits of this word below K'
+    const uint64_t valid = left >= 64 ? ~0ull : (left <= 0 ? 0ull : ((1ull << left) - 1ull));
+    const uint64_t word = (col < n ? b[static_cast<int64_t>(col) * ldb + q] : 0ull) & valid;
+    uint4 *dst = codes + (static_cast<size_t>(q) * (p.positions / 32) + pos / 32) * 64 + pos % 32;
+#pragma unroll
+    for (int part = 0; part < 2; ++part) {
+        const uint4 code = fp4_codes_b(static_cast<uint32_t>(word >> (32 * part)));
+        const uint4 keep = fp4_code_mask(static_cast<uint32_t>(valid >> (32 * part)));
+        dst[32 * part] = make_uint4(code.x & keep.x, code.y & keep.y, code.z & keep.z, code.w & keep.w);
+    }
+    if (q == 0) {
+        int ones = 0;
+        for (int w = 0; w < p.n_steps; ++w) {
+            const int l = p.k_bits - 64 * w;
+            const uint64_t v = l >= 64 ? ~0ull : ((1ull << l) - 1ull);
+            if (col < n) ones += __popcll(b[static_cast<int64_t>(col) * ldb + w] & v);
+        }
+        bias[pos] = 128.0f - (col < n ? static_cast<float>((2 * ones - p.k_bits + (p.k_bits & 1)) / 2) : 0.0f);
+    }
+}
+
+template <int P>        // stored positions per row: 128 or 256
+__global__ __launch_bounds__(kBlock, 2) void bitgemm_fp4_rows_kernel(
+    const uint64_t *__restrict__ a, int64_t m, int64_t lda, const uint4 *__restrict__ codes,
+    const float *__restrict__ bias, const float *__restrict__ src_scale, Fp4RowsParams p,
+    unsigned char *__restrict__ rows, unsigned char *__restrict__ alt_rows)
+{
+    constexpr int kStride = P + 8;                           // bytes per row of the LDS buffer
+    constexpr int kSeg = P / 8;                              // 8-byte segments (lanes) per row
+    constexpr int kRowsPerStep = kWave / kSeg;               // rows written per store instruction
+    constexpr int kTiles = P / 32;
+    __shared__ uint4 wcodes[4 * kTiles * 64];                // [step][tile][half][position % 32]
+    __shared__ __attribute__((aligned(16))) float wbias[P];
+    __shared__ __attribute__((aligned(16))) unsigned char buffer[kWavesPerBlock][32 * kStride];
+    const int lane = lane_id();
+    const int wave = wave_in_block();
+    const int i32 = lane & 31, half = lane >> 5;
+    unsigned char *mine = buffer[wave];
+    const int64_t wave_id = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kWavesPerBlock * 32;
+
+    for (int i = threadIdx.x; i < p.n_steps * kTiles * 64; i += kBlock) wcodes[i] = codes[i];
+    for (int i = threadIdx.x; i < P; i += kBlock) wbias[i] = bias[i];
+    __syncthreads();
+
+    // bits 64 q + 32 half .. + 32 and scale of row r0 + i32 (clamped: such rows are never stored)
+    uint32_t bits[4], scale_bits;
+    auto fetch = [&](int64_t r0) {
+        int64_t arow = r0 + i32;
+        if (arow >= m) arow = m - 1;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            bits[q] = 0;
+            if (q < p.n_steps) {
+                const uint2 w = reinterpret_cast<const uint2 *>(a + arow * lda)[q];
+                bits[q] = half ? w.y : w.x;
+            }
+        }
+        scale_bits = src_scale != nullptr ? __float_as_uint(src_scale[arow]) : 0u;
+    };
+    int64_t row0 = wave_id * 32;
+    fetch(row0);
+    for (; row0 < m; row0 += stride) {
+        int fcodes[4][4];                                     // the features as {0, +1} codes
+#pragma unroll
+        for (int q = 0; q < 4; ++q) fp4_codes_a(bits[q], fcodes[q]);
+        if (half == 0) *reinterpret_cast<uint32_t *>(mine + i32 * kStride + P) = scale_bits;
+        fetch(row0 + stride);
+#pragma unroll
+        for (int t = 0; t < P / 128; ++t) {
+            // register 4 g + e of tile ct: position 128 t + 32 ct + 8 g + 4 half + e, row i32
+            v16f acc[4];
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const float4 c = *reinterpret_cast<const float4 *>(wbias + 128 * t + 32 * ct + 8 * g + 4 * half);
+                    acc[ct][4 * g + 0] = c.x;
+                    acc[ct][4 * g + 1] = c.y;
+                    acc[ct][4 * g + 2] = c.z;
+                    acc[ct][4 * g + 3] = c.w;
+                }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (q >= p.n_steps) break;                    // uniform
+                v8i fop;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) fop[e] = fcodes[q][e];
+                fop[4] = fop[5] = fop[6] = fop[7] = 0;
+#pragma unroll
+                for (int ct = 0; ct < 4; ++ct) {
+                    const uint4 c = wcodes[(q * kTiles + 4 * t + ct) * 64 + lane];
+                    v8i wop;
+                    wop[0] = static_cast<int>(c.x);
+                    wop[1] = static_cast<int>(c.y);
+                    wop[2] = static_cast<int>(c.z);
+                    wop[3] = static_cast<int>(c.w);
+                    wop[4] = wop[5] = wop[6] = wop[7] = 0;
+                    acc[ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wop, fop, acc[ct], 4, 4, 0, 0x7f7f7f7f, 0,
+                                                                             0x7f7f7f7f);
+                }
+            }
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    uint32_t packed = 0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) packed = __builtin_amdgcn_cvt_pk_u8_f32(acc[ct][4 * g + e], e, packed);
+                    *reinterpret_cast<uint32_t *>(mine + i32 * kStride + 128 * t + 32 * ct + 8 * g + 4 * half) =
+                        packed ^ 0x80808080u;
+                }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // rows out: kSeg lanes per row, 8 bytes each
+        const int seg = lane & (kSeg - 1);
+        const int sub = lane / kSeg;
+#pragma unroll 4
+        for (int j = 0; j < 32; j += kRowsPerStep) {
+            const int local = j + sub;
+            const int64_t row = row0 + local;
+            uint2 v = *reinterpret_cast<const uint2 *>(mine + local * kStride + 8 * seg);
+            uint32_t row_scale = *reinterpret_cast<const uint32_t *>(mine + local * kStride + P);
+            const bool live = row < m;
+            if (p.seven_bit) {
+                // a byte fits 7 bits when its bits 7 and 6 agree
+                const bool misfit = (((v.x ^ (v.x << 1)) | (v.y ^ (v.y << 1))) & 0x80808080u) != 0u;
+                const uint64_t any = __ballot(misfit);
+                const uint64_t row_mask = kSeg == 64 ? ~0ull : (((1ull << kSeg) - 1ull) << (sub * kSeg));
+                const bool escaped = (any & row_mask) != 0ull;
+                if (escaped && p.escape) {
+                    if (live) *reinterpret_cast<uint2 *>(alt_rows + row * P + 8 * seg) = v;
+                    row_scale = 0x7fc00000u;
+                }
+                // carrier bytes: byte 0 of segment i carries bit i (i < 32); rows of 16 lanes carry
+                // bits 16..31 in byte 4
+                if (seg < 32) v.x = (v.x & ~0x80u) | (((row_scale >> seg) & 1u) << 7);
+                if (kSeg == 16) v.y = (v.y & ~0x80u) | (((row_scale >> (16 + seg)) & 1u) << 7);
+            } else if (p.tail_scale) {
+                if (seg == kSeg - 1) v.y = row_scale;
+            }
+            if (live) *reinterpret_cast<uint2 *>(rows + row * P + 8 * seg) = v;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();                      // the buffer is rewritten by the next 32 rows
+    }
+}
+
+// Product rows of `layout` (one byte per value, K <= 256, 128 or 256 positions) on the FP4 matrix
+// cores.  codes_ws: device scratch of bigcn::fp4_rows_scratch_bytes(layout) bytes, 256-byte
+// aligned.  Returns BIGCN_EINVAL without launching anything when the shape is not covered.
+size_t fp4_rows_scratch_bytes(const RowLayout &layout)
+{
+    const int n_steps = (layout.k_eff + 63) / 64;
+    return static_cast<size_t>(layout.positions()) * n_steps * 32 + static_cast<size_t>(layout.positions()) * sizeof(float);
+}
+
+bool fp4_rows_covers(int64_t m, int64_t k_bits, const RowLayout &layout)
+{
+    const int pos = layout.positions();
+    return layout.kind == kI8 && k_bits <= 256 && (pos == 128 || pos == 256) && m > 32768 &&
+           (!layout.escape || layout.alt_kind == kI8);
+}
+
+int launch_bitgemm_fp4_rows(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits, int64_t n,
+                            int64_t ldb, int64_t k_bits, const float *src_scale, void *c_rows, void *alt_rows,
+                            RowLayout layout, void *codes_ws, hipStream_t stream)
+{
+    if (!fp4_rows_covers(m, k_bits, layout) || codes_ws == nullptr) return BIGCN_EINVAL;
+    if (layout.escape && alt_rows == nullptr) return BIGCN_ENULL;
+    if (layout.embed_scale != kScaleSeparate && src_scale == nullptr) return BIGCN_ENULL;
+    Fp4RowsParams p;
+    p.positions = layout.positions();
+    p.groups = layout.groups;
+    p.vec = layout.vec;
+    p.k_bits = layout.k_eff;
+    p.n_steps = (layout.k_eff + 63) / 64;
+    p.seven_bit = layout.embed_scale == kScaleInTopBits ? 1 : 0;
+    p.tail_scale = layout.embed_scale == kScaleInTail ? 1 : 0;
+    p.escape = layout.escape;
+    uint4 *codes = static_cast<uint4 *>(codes_ws);
+    float *bias = reinterpret_cast<float *>(codes + static_cast<size_t>(p.positions) * p.n_steps * 2);
+    const int items = p.positions * p.n_steps;
+    hipLaunchKernelGGL(fp4_weight_codes_kernel, dim3((items + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, b_bits,
+                       static_cast<int>(n), ldb, p, codes, bias);
+    if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
+    int64_t blocks = (m + 127) / 128;
+    // the blocks stay for the whole call (each loads the codes once): as many as are resident at once
+    const int64_t resident = 256 * (p.positions == 256 ? 2 : 4);
+    if (blocks > resident) blocks = resident;
+    const float *scale = layout.embed_scale != kScaleSeparate ? src_scale : nullptr;
+    if (p.positions == 256)
+        hipLaunchKernelGGL(bitgemm_fp4_rows_kernel<256>, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream,
+                           a_bits, m, lda, codes, bias, scale, p, static_cast<unsigned char *>(c_rows),
+                           static_cast<unsigned char *>(alt_rows));
+    else
+        hipLaunchKernelGGL(bitgemm_fp4_rows_kernel<128>, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream,
+                           a_bits, m, lda, codes, bias, scale, p, static_cast<unsigned char *>(c_rows),
+                           static_cast<unsigned char *>(alt_rows));
+    return check_launch();
+}
+
 }  // namespace bigcn

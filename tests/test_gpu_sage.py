@@ -134,9 +134,20 @@ def test_sage_rows_that_do_not_fit_seven_bits(B, d_in):
     """Nodes whose signs equal (or oppose) a column of W_theta or of W_n give products of +-K:
     their product rows, own and neighbour, take the escape path of layers with 129..1024 input
     bits (one-byte alternates up to 256 bits, fp16 alternates beyond)."""
-    n, d_hidden, d_out = 600, 256, 6
-    rng = np.random.default_rng(1000 + d_in)
-    work = small_sage_workload(n, 4000, (d_in, d_hidden, d_out), seed=900 + d_in)
+    _sage_rows_that_do_not_fit(B, d_in, 256, 600, 4000)
+
+
+@pytest.mark.parametrize("d_in,d_hidden", [(100, 128), (128, 256), (200, 256), (256, 256), (200, 72)])
+def test_sage_rows_that_do_not_fit_seven_bits_many_rows(B, d_in, d_hidden):
+    """The same on 33000 nodes, where both products of a layer of at most 256 input bits are
+    written by the matrix-core kernel (rows of 128 and of 256 stored values; scale in the top
+    bits, in the row's tail, or separate)."""
+    _sage_rows_that_do_not_fit(B, d_in, d_hidden, 33000, 150000)
+
+
+def _sage_rows_that_do_not_fit(B, d_in, d_hidden, n, n_edges):
+    d_out = 6
+    work = small_sage_workload(n, n_edges, (d_in, d_hidden, d_out), seed=900 + d_in)
     w_self, w_nbr = work.weights[0]
     for k in range(0, 200):
         src = w_self if k % 4 < 2 else w_nbr
@@ -149,6 +160,8 @@ def test_sage_rows_that_do_not_fit_seven_bits(B, d_in):
     for bn in ([None, None], ["calibrate", "calibrate"]):
         stats = compare_forward_layerwise(work, bn, sage_prefix_runner(B, work), cancellation_aware=True)
         assert stats[0]["rows_compared"] == n and stats[-1]["rows_compared"] >= 0.5 * n
+        if n > 10000:
+            break                                             # one pass of the oracle is enough at this size
 
 
 def test_sage_isolated_node_output_is_its_own_term_and_runs_are_identical(B):

@@ -142,14 +142,12 @@ int launch_bitgemm_fp4(const uint64_t *a_bits, const float *a_scale, int64_t m, 
                        int64_t k_bits, int32_t *acc, int64_t ld_acc, float *out, int64_t ld_out,
                        hipStream_t stream);
 
-// Product rows of a one-byte RowLayout on the FP4 matrix cores (K <= 256, 128 or 256 stored
-// positions, more than 32768 rows): fp4_rows_covers says whether the shape is taken,
-// fp4_rows_scratch_bytes how much device scratch (256-byte aligned) the expanded weights need.
+// Product rows of a one-byte RowLayout on the FP4 matrix cores (K <= 1024, 128 / 256 / 512 stored
+// positions, more than 32768 rows): fp4_rows_covers says whether the shape is taken.
 bool fp4_rows_covers(int64_t m, int64_t k_bits, const RowLayout &layout);
-size_t fp4_rows_scratch_bytes(const RowLayout &layout);
 int launch_bitgemm_fp4_rows(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits, int64_t n,
                             int64_t ldb, int64_t k_bits, const float *src_scale, void *c_rows, void *alt_rows,
-                            RowLayout layout, void *codes_ws, hipStream_t stream);
+                            RowLayout layout, hipStream_t stream);
 
 // Aggregation of layer l fused with the rescale and with the binarisation of layer l+1.
 // Bi-GCN: dst_mul = next_row_mul = D^-1/2 and no own-row term.  Bi-GraphSAGE (mean aggregator):

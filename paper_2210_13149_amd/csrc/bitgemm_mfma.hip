@@ -17,6 +17,8 @@
 // registers while the current chunk is multiplied and written to LDS between two barriers.
 #include "bigcn_internal.h"
 
+#include <atomic>
+
 namespace bigcn {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -499,140 +501,139 @@ int launch_bitgemm_mfma(const uint64_t *a_bits, const float *a_scale, int64_t m,
     return check_launch();
 }
 
-// ---- product rows of the fused forward on the FP4 matrix cores (K <= 256) ----------------------
-// Two kernels.  fp4_weight_codes_kernel expands the packed weights once per call into FP4 codes
-// ordered by stored position (position p of a RowLayout holds column p / vec + groups (p % vec)),
-// with the per-position constant 128 - h, h = (2 popcount - K' + K' mod 2) / 2: the stored value
-// of a one-byte row, floor(K'/2) - popcount(f xor b), equals sum_k a_k b_k - h with a in {0, 1}.
-// bitgemm_fp4_rows_kernel: a block keeps the weight codes (32 KB at most) and the constants in
-// LDS for its whole life; a wavefront owns 32 rows at a time and all positions of them.  The
-// weights are the first operand of the multiply, so that the four accumulator registers of a
-// group hold four consecutive positions of one row: the accumulators start at 128 - h, come out
-// as value + 128 in 0..255, are packed four to a dword by the saturating byte conversion, flipped
-// back to two's complement and written into the wavefront's own LDS buffer [row][position].
-// Then the wavefront walks its rows: the lanes of a row take 8 bytes each, test the 7-bit range
-// where the layout asks for it (bit 7 differs from bit 6), stamp the scale (top bits of the
-// carrier bytes, or the last four bytes) and write whole rows with coalesced 8-byte stores; rows
-// that do not fit go to the alternate array with a NaN scale in the main row, as in the
-// vector-ALU kernels.  The bits and the scale of the next 32 rows are fetched while the current
-// ones are multiplied.
+// ---- product rows of the fused forward on the FP4 matrix cores (K <= 1024) ---------------------
+// One-byte product rows of 128, 256 or 512 stored positions (position p of a RowLayout holds
+// column p / vec + groups (p % vec)).  Here the weights are the {0, +1} operand and the features
+// the {-1, +1} one: with S = sum over the set weight bits of f_k and F = sum_k f_k, the product is
+// 2 S - F and the stored value floor(K'/2) - popcount(f xor b) equals S - (F + K' mod 2) / 2, a
+// constant per row, so the accumulators of a row start at 128 minus that constant and come out
+// as value + 128.
+// A block keeps the packed weights of all positions in LDS for its whole life, as
+// [half-word of K][position] dwords (a lane's read is one dword, turned into codes by four
+// masks); a wavefront owns 32 rows at a time.  Per tile of 128 positions: 4 multiplies per 64
+// bits of K with the weights as first operand, so that the four registers of a group hold four
+// consecutive positions of one row; the saturating byte conversion packs them, a flip of the top
+// bits gives two's complement (values beyond a byte saturate and are caught by the 7-bit test),
+// positions past the last column are zeroed, and the bytes go to the wavefront's LDS buffer
+// [row][128 positions].  Then 16 lanes per row take 8 bytes each, test the 7-bit range where the
+// layout asks for it (bit 7 differs from bit 6), stamp the scale (top bits of the carrier bytes,
+// or the last four bytes of the row) and write 128-byte pieces of rows.  Rows with a value outside
+// 7 bits are noted and, after the last tile, redone one at a time with XOR and bit counts from
+// the same LDS weights: their values go to the alternate array (bytes or fp16) and the carrier
+// bytes of the main row get a NaN scale, as in the vector-ALU kernels.  The bits and the scale
+// of the next 32 rows are fetched while the current ones are multiplied.
 struct Fp4RowsParams {
-    int positions;        // 128 or 256
+    int positions;        // 128, 256 or 512
     int groups, vec;      // of the RowLayout
+    int n;                // columns
     int k_bits;           // K' (without a folded last bit)
     int n_steps;          // ceil(K' / 64)
     int seven_bit;        // scale bits in the top bits of the carrier bytes
     int tail_scale;       // scale in the last four bytes
     int escape;           // rows outside the 7-bit range go to alt_rows
+    int alt_half;         // ... as fp16 (else as bytes)
 };
 
-// codes: [step][position / 32][2 halves][position % 32] of 16 bytes; bias: [position] floats.
-// One thread per (position, step).
-__global__ __launch_bounds__(kBlock) void fp4_weight_codes_kernel(const uint64_t *__restrict__ b, int n, int64_t ldb,
-                                                                  Fp4RowsParams p, uint4 *__restrict__ codes,
-                                                                  float *__restrict__ bias)
+constexpr int kFp4RowsStride = 128 + 8;                     // bytes per row of a wavefront's LDS tile
+
+__host__ __device__ inline size_t fp4_rows_lds_bytes(int positions, int n_steps)
 {
-    const int item = blockIdx.x * kBlock + threadIdx.x;
-    if (item >= p.positions * p.n_steps) return;
-    const int pos = item / p.n_steps, q = item - pos * p.n_steps;
-    const int col = pos / p.vec + p.groups * (pos % p.vec);
-    const int left = col < n ? p.k_bits - 64 * q : 0;                     // bits of this word below K'
-    const uint64_t valid = left >= 64 ? ~0ull : (left <= 0 ? 0ull : ((1ull << left) - 1ull));
-    const uint64_t word = (col < n ? b[static_cast<int64_t>(col) * ldb + q] : 0ull) & valid;
-    uint4 *dst = codes + (static_cast<size_t>(q) * (p.positions / 32) + pos / 32) * 64 + pos % 32;
-#pragma unroll
-    for (int part = 0; part < 2; ++part) {
-        const uint4 code = fp4_codes_b(static_cast<uint32_t>(word >> (32 * part)));
-        const uint4 keep = fp4_code_mask(static_cast<uint32_t>(valid >> (32 * part)));
-        dst[32 * part] = make_uint4(code.x & keep.x, code.y & keep.y, code.z & keep.z, code.w & keep.w);
-    }
-    if (q == 0) {
-        int ones = 0;
-        for (int w = 0; w < p.n_steps; ++w) {
-            const int l = p.k_bits - 64 * w;
-            const uint64_t v = l >= 64 ? ~0ull : ((1ull << l) - 1ull);
-            if (col < n) ones += __popcll(b[static_cast<int64_t>(col) * ldb + w] & v);
-        }
-        bias[pos] = 128.0f - (col < n ? static_cast<float>((2 * ones - p.k_bits + (p.k_bits & 1)) / 2) : 0.0f);
-    }
+    return static_cast<size_t>(8) * n_steps * positions + positions +
+           static_cast<size_t>(kWavesPerBlock) * 32 * kFp4RowsStride;
 }
 
-template <int P>        // stored positions per row: 128 or 256
-__global__ __launch_bounds__(kBlock, 2) void bitgemm_fp4_rows_kernel(
-    const uint64_t *__restrict__ a, int64_t m, int64_t lda, const uint4 *__restrict__ codes,
-    const float *__restrict__ bias, const float *__restrict__ src_scale, Fp4RowsParams p,
-    unsigned char *__restrict__ rows, unsigned char *__restrict__ alt_rows)
+// bits of the half-word (q, half) that lie below K'
+__device__ __forceinline__ uint32_t fp4_rows_valid(int k_bits, int q, int half)
 {
-    constexpr int kStride = P + 8;                           // bytes per row of the LDS buffer
-    constexpr int kSeg = P / 8;                              // 8-byte segments (lanes) per row
-    constexpr int kRowsPerStep = kWave / kSeg;               // rows written per store instruction
-    constexpr int kTiles = P / 32;
-    __shared__ uint4 wcodes[4 * kTiles * 64];                // [step][tile][half][position % 32]
-    __shared__ __attribute__((aligned(16))) float wbias[P];
-    __shared__ __attribute__((aligned(16))) unsigned char buffer[kWavesPerBlock][32 * kStride];
+    const int left = k_bits - 64 * q - 32 * half;
+    return left >= 32 ? ~0u : (left <= 0 ? 0u : ((1u << left) - 1u));
+}
+
+template <int P, int kMaxSteps>        // P stored positions; kMaxSteps 4: K' <= 256, 16: K' <= 1024
+__global__ __launch_bounds__(kBlock, 3) void bitgemm_fp4_rows_kernel(
+    const uint64_t *__restrict__ a, int64_t m, int64_t lda, const uint64_t *__restrict__ b, int64_t ldb,
+    const float *__restrict__ src_scale, Fp4RowsParams p, unsigned char *__restrict__ rows,
+    void *__restrict__ alt_rows)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char fp4_rows_lds[];
+    constexpr int n_tiles = P / 128;
+    uint32_t *wbits = reinterpret_cast<uint32_t *>(fp4_rows_lds);               // [2 n_steps][P]
+    unsigned char *live = fp4_rows_lds + static_cast<size_t>(8) * p.n_steps * P;   // [P]: 0xff below n columns
     const int lane = lane_id();
     const int wave = wave_in_block();
     const int i32 = lane & 31, half = lane >> 5;
-    unsigned char *mine = buffer[wave];
+    unsigned char *mine = live + P + wave * 32 * kFp4RowsStride;
+    const uint32_t *wlane = wbits + half * P + i32;           // this lane's weight words: + 2 q P + position of tile
+    const unsigned char *live_lane = live + 4 * half;
+    unsigned char *mine_lane = mine + i32 * kFp4RowsStride + 4 * half;
     const int64_t wave_id = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave;
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kWavesPerBlock * 32;
 
-    for (int i = threadIdx.x; i < p.n_steps * kTiles * 64; i += kBlock) wcodes[i] = codes[i];
-    for (int i = threadIdx.x; i < P; i += kBlock) wbias[i] = bias[i];
+    for (int item = threadIdx.x; item < P * p.n_steps; item += kBlock) {
+        const int q = item / P, pos = item - q * P;
+        const int col = pos / p.vec + p.groups * (pos % p.vec);
+        const uint64_t word = col < p.n ? b[static_cast<int64_t>(col) * ldb + q] : 0ull;
+        wbits[(2 * q) * P + pos] = static_cast<uint32_t>(word);
+        wbits[(2 * q + 1) * P + pos] = static_cast<uint32_t>(word >> 32);
+        if (q == 0) live[pos] = col < p.n ? 0xffu : 0u;
+    }
     __syncthreads();
 
-    // bits 64 q + 32 half .. + 32 and scale of row r0 + i32 (clamped: such rows are never stored)
-    uint32_t bits[4], scale_bits;
+    // half-words 2 q + half and scale of row r0 + i32 (clamped: such rows are never stored)
+    uint32_t next[kMaxSteps], next_scale;
     auto fetch = [&](int64_t r0) {
         int64_t arow = r0 + i32;
         if (arow >= m) arow = m - 1;
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(a + arow * lda) + half;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            bits[q] = 0;
-            if (q < p.n_steps) {
-                const uint2 w = reinterpret_cast<const uint2 *>(a + arow * lda)[q];
-                bits[q] = half ? w.y : w.x;
-            }
-        }
-        scale_bits = src_scale != nullptr ? __float_as_uint(src_scale[arow]) : 0u;
+        for (int q = 0; q < kMaxSteps; ++q) next[q] = q < p.n_steps ? src[2 * q] : 0u;
+        next_scale = src_scale != nullptr ? __float_as_uint(src_scale[arow]) : 0u;
     };
     int64_t row0 = wave_id * 32;
     fetch(row0);
     for (; row0 < m; row0 += stride) {
-        int fcodes[4][4];                                     // the features as {0, +1} codes
+        uint32_t cur[kMaxSteps];
+        int ones = 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) fp4_codes_a(bits[q], fcodes[q]);
-        if (half == 0) *reinterpret_cast<uint32_t *>(mine + i32 * kStride + P) = scale_bits;
+        for (int q = 0; q < kMaxSteps; ++q) {
+            cur[q] = next[q] & fp4_rows_valid(p.k_bits, q, half);
+            ones += __popc(cur[q]);
+        }
+        ones += __shfl_xor(ones, 32);
+        // (F + K' mod 2) / 2 with F = 2 ones - K': an even number halved
+        const float start = 128.0f - static_cast<float>((2 * ones - p.k_bits + (p.k_bits & 1)) / 2);
+        if (half == 0) *reinterpret_cast<uint32_t *>(mine + i32 * kFp4RowsStride + 128) = next_scale;
         fetch(row0 + stride);
-#pragma unroll
-        for (int t = 0; t < P / 128; ++t) {
+        uint32_t escaped = 0;                                 // rows of this wavefront's 32 that need the alternate array
+#pragma unroll 1
+        for (int t = 0; t < n_tiles; ++t) {
             // register 4 g + e of tile ct: position 128 t + 32 ct + 8 g + 4 half + e, row i32
             v16f acc[4];
 #pragma unroll
             for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const float4 c = *reinterpret_cast<const float4 *>(wbias + 128 * t + 32 * ct + 8 * g + 4 * half);
-                    acc[ct][4 * g + 0] = c.x;
-                    acc[ct][4 * g + 1] = c.y;
-                    acc[ct][4 * g + 2] = c.z;
-                    acc[ct][4 * g + 3] = c.w;
-                }
+                for (int r = 0; r < 16; ++r) acc[ct][r] = start;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < kMaxSteps; ++q) {
                 if (q >= p.n_steps) break;                    // uniform
+                uint4 code = fp4_codes_b(cur[q]);
+                if (q == p.n_steps - 1) {
+                    const uint4 keep = fp4_code_mask(fp4_rows_valid(p.k_bits, q, half));
+                    code = make_uint4(code.x & keep.x, code.y & keep.y, code.z & keep.z, code.w & keep.w);
+                }
                 v8i fop;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) fop[e] = fcodes[q][e];
+                fop[0] = static_cast<int>(code.x);
+                fop[1] = static_cast<int>(code.y);
+                fop[2] = static_cast<int>(code.z);
+                fop[3] = static_cast<int>(code.w);
                 fop[4] = fop[5] = fop[6] = fop[7] = 0;
 #pragma unroll
                 for (int ct = 0; ct < 4; ++ct) {
-                    const uint4 c = wcodes[(q * kTiles + 4 * t + ct) * 64 + lane];
+                    int wcodes[4];
+                    fp4_codes_a(wlane[2 * q * P + 128 * t + 32 * ct], wcodes);
                     v8i wop;
-                    wop[0] = static_cast<int>(c.x);
-                    wop[1] = static_cast<int>(c.y);
-                    wop[2] = static_cast<int>(c.z);
-                    wop[3] = static_cast<int>(c.w);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) wop[e] = wcodes[e];
                     wop[4] = wop[5] = wop[6] = wop[7] = 0;
                     acc[ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wop, fop, acc[ct], 4, 4, 0, 0x7f7f7f7f, 0,
                                                                              0x7f7f7f7f);
@@ -645,99 +646,145 @@ __global__ __launch_bounds__(kBlock, 2) void bitgemm_fp4_rows_kernel(
                     uint32_t packed = 0;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) packed = __builtin_amdgcn_cvt_pk_u8_f32(acc[ct][4 * g + e], e, packed);
-                    *reinterpret_cast<uint32_t *>(mine + i32 * kStride + 128 * t + 32 * ct + 8 * g + 4 * half) =
-                        packed ^ 0x80808080u;
+                    const uint32_t keep = *reinterpret_cast<const uint32_t *>(live_lane + 128 * t + 32 * ct + 8 * g);
+                    *reinterpret_cast<uint32_t *>(mine_lane + 32 * ct + 8 * g) = (packed ^ 0x80808080u) & keep;
                 }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        // rows out: kSeg lanes per row, 8 bytes each
-        const int seg = lane & (kSeg - 1);
-        const int sub = lane / kSeg;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            // this tile's 128 bytes of every row: 16 lanes per row, 8 bytes each
+            const int seg = lane & 15, sub = lane >> 4;
+            const int row_seg = 16 * t + seg;                 // 8-byte segment of the whole row
 #pragma unroll 4
-        for (int j = 0; j < 32; j += kRowsPerStep) {
-            const int local = j + sub;
-            const int64_t row = row0 + local;
-            uint2 v = *reinterpret_cast<const uint2 *>(mine + local * kStride + 8 * seg);
-            uint32_t row_scale = *reinterpret_cast<const uint32_t *>(mine + local * kStride + P);
-            const bool live = row < m;
-            if (p.seven_bit) {
-                // a byte fits 7 bits when its bits 7 and 6 agree
-                const bool misfit = (((v.x ^ (v.x << 1)) | (v.y ^ (v.y << 1))) & 0x80808080u) != 0u;
-                const uint64_t any = __ballot(misfit);
-                const uint64_t row_mask = kSeg == 64 ? ~0ull : (((1ull << kSeg) - 1ull) << (sub * kSeg));
-                const bool escaped = (any & row_mask) != 0ull;
-                if (escaped && p.escape) {
-                    if (live) *reinterpret_cast<uint2 *>(alt_rows + row * P + 8 * seg) = v;
-                    row_scale = 0x7fc00000u;
+            for (int j = 0; j < 32; j += 4) {
+                const int local = j + sub;
+                const int64_t row = row0 + local;
+                uint2 v = *reinterpret_cast<const uint2 *>(mine + local * kFp4RowsStride + 8 * seg);
+                const uint32_t row_scale = *reinterpret_cast<const uint32_t *>(mine + local * kFp4RowsStride + 128);
+                if (p.seven_bit) {
+                    if (p.escape) {
+                        // a byte fits 7 bits when its bits 7 and 6 agree
+                        const bool misfit = (((v.x ^ (v.x << 1)) | (v.y ^ (v.y << 1))) & 0x80808080u) != 0u;
+                        const uint64_t any = __ballot(misfit);
+                        const uint32_t four = ((any & 0xffffull) != 0ull ? 1u : 0u) | ((any & 0xffff0000ull) != 0ull ? 2u : 0u) |
+                                              ((any & 0xffff00000000ull) != 0ull ? 4u : 0u) | ((any >> 48) != 0ull ? 8u : 0u);
+                        escaped |= four << j;
+                    }
+                    // carrier bytes: byte 0 of segment i carries bit i (i < 32); rows of 16 lanes carry
+                    // bits 16..31 in byte 4
+                    if (row_seg < 32) v.x = (v.x & ~0x80u) | (((row_scale >> row_seg) & 1u) << 7);
+                    if (P == 128) v.y = (v.y & ~0x80u) | (((row_scale >> (16 + seg)) & 1u) << 7);
+                } else if (p.tail_scale) {
+                    if (t == n_tiles - 1 && seg == 15) v.y = row_scale;
                 }
-                // carrier bytes: byte 0 of segment i carries bit i (i < 32); rows of 16 lanes carry
-                // bits 16..31 in byte 4
-                if (seg < 32) v.x = (v.x & ~0x80u) | (((row_scale >> seg) & 1u) << 7);
-                if (kSeg == 16) v.y = (v.y & ~0x80u) | (((row_scale >> (16 + seg)) & 1u) << 7);
-            } else if (p.tail_scale) {
-                if (seg == kSeg - 1) v.y = row_scale;
+                if (row < m) *reinterpret_cast<uint2 *>(rows + row * P + 128 * t + 8 * seg) = v;
             }
-            if (live) *reinterpret_cast<uint2 *>(rows + row * P + 8 * seg) = v;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();                  // the buffer is rewritten by the next tile
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();                      // the buffer is rewritten by the next 32 rows
+        if (escaped != 0u) {
+            // the main rows are complete in memory before their carrier bytes are written again
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            uint32_t todo = escaped;
+            while (todo != 0u) {
+                const int local = __builtin_amdgcn_readfirstlane(__builtin_ctz(todo));
+                todo &= todo - 1u;
+                const int64_t row = row0 + local;
+                if (row >= m) continue;
+                const uint64_t *bits_of_row = a + row * lda;  // uniform: every lane reads the same words
+                for (int pos = lane; pos < P; pos += kWave) {
+                    int pop = 0;
+                    for (int q = 0; q < p.n_steps; ++q) {
+                        const uint64_t f = bits_of_row[q];
+                        pop += __popc((static_cast<uint32_t>(f) ^ wbits[(2 * q) * P + pos]) & fp4_rows_valid(p.k_bits, q, 0));
+                        pop += __popc((static_cast<uint32_t>(f >> 32) ^ wbits[(2 * q + 1) * P + pos]) &
+                                      fp4_rows_valid(p.k_bits, q, 1));
+                    }
+                    const int value = live[pos] != 0 ? (p.k_bits >> 1) - pop : 0;
+                    if (p.alt_half)
+                        static_cast<__half *>(alt_rows)[row * P + pos] = __float2half(static_cast<float>(value));
+                    else
+                        static_cast<signed char *>(alt_rows)[row * P + pos] = static_cast<signed char>(value);
+                    const int segment = pos >> 3, offset = pos & 7;
+                    int bit = -1;
+                    if (offset == 0 && segment < 32) bit = segment;
+                    else if (offset == 4 && P == 128) bit = 16 + segment;
+                    if (bit >= 0)
+                        rows[row * P + pos] = static_cast<unsigned char>((static_cast<uint32_t>(value) & 0x7fu) |
+                                                                        (((0x7fc00000u >> bit) & 1u) << 7));
+                }
+            }
+        }
     }
 }
 
-// Product rows of `layout` (one byte per value, K <= 256, 128 or 256 positions) on the FP4 matrix
-// cores.  codes_ws: device scratch of bigcn::fp4_rows_scratch_bytes(layout) bytes, 256-byte
-// aligned.  Returns BIGCN_EINVAL without launching anything when the shape is not covered.
-size_t fp4_rows_scratch_bytes(const RowLayout &layout)
-{
-    const int n_steps = (layout.k_eff + 63) / 64;
-    return static_cast<size_t>(layout.positions()) * n_steps * 32 + static_cast<size_t>(layout.positions()) * sizeof(float);
-}
-
+// Product rows of `layout` on the FP4 matrix cores: one byte per value, 128 / 256 / 512 stored
+// positions, K <= 1024 with the packed weights fitting 64 KB of LDS beside the row tiles, more
+// than 32768 rows.  Returns BIGCN_EINVAL without launching anything when the shape is not covered.
 bool fp4_rows_covers(int64_t m, int64_t k_bits, const RowLayout &layout)
 {
     const int pos = layout.positions();
-    return layout.kind == kI8 && k_bits <= 256 && (pos == 128 || pos == 256) && m > 32768 &&
-           (!layout.escape || layout.alt_kind == kI8);
+    if (layout.kind != kI8 || k_bits > 1024 || m <= 32768) return false;
+    if (pos != 128 && pos != 256 && pos != 512) return false;
+    if (layout.escape && layout.alt_kind != kI8 && layout.alt_kind != kF16) return false;
+    if (layout.escape && layout.embed_scale != kScaleInTopBits) return false;
+    return fp4_rows_lds_bytes(pos, (layout.k_eff + 63) / 64) <= 64 * 1024;
+}
+
+// blocks of the kernel that a compute unit holds at once (asked once per LDS size)
+template <int P, int kMaxSteps>
+static int launch_fp4_rows(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits, int64_t ldb,
+                           const float *scale, const Fp4RowsParams &p, void *c_rows, void *alt_rows, hipStream_t stream)
+{
+    const size_t lds_bytes = fp4_rows_lds_bytes(P, p.n_steps);
+    static std::atomic<int> known[257];
+    const size_t slot = lds_bytes / 256;
+    int per_cu = known[slot].load(std::memory_order_relaxed);
+    if (per_cu == 0) {
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bitgemm_fp4_rows_kernel<P, kMaxSteps>, kBlock,
+                                                         lds_bytes) != hipSuccess || per_cu < 1)
+            per_cu = 1;
+        known[slot].store(per_cu, std::memory_order_relaxed);
+    }
+    // the blocks stay for the whole call (each loads the weights once): as many as are resident at once
+    int64_t blocks = (m + 127) / 128;
+    if (blocks > 256 * per_cu) blocks = 256 * per_cu;
+    hipLaunchKernelGGL((bitgemm_fp4_rows_kernel<P, kMaxSteps>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), lds_bytes,
+                       stream, a_bits, m, lda, b_bits, ldb, scale, p, static_cast<unsigned char *>(c_rows), alt_rows);
+    return check_launch();
 }
 
 int launch_bitgemm_fp4_rows(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits, int64_t n,
                             int64_t ldb, int64_t k_bits, const float *src_scale, void *c_rows, void *alt_rows,
-                            RowLayout layout, void *codes_ws, hipStream_t stream)
+                            RowLayout layout, hipStream_t stream)
 {
-    if (!fp4_rows_covers(m, k_bits, layout) || codes_ws == nullptr) return BIGCN_EINVAL;
+    if (!fp4_rows_covers(m, k_bits, layout)) return BIGCN_EINVAL;
     if (layout.escape && alt_rows == nullptr) return BIGCN_ENULL;
     if (layout.embed_scale != kScaleSeparate && src_scale == nullptr) return BIGCN_ENULL;
     Fp4RowsParams p;
     p.positions = layout.positions();
     p.groups = layout.groups;
     p.vec = layout.vec;
+    p.n = static_cast<int>(n);
     p.k_bits = layout.k_eff;
     p.n_steps = (layout.k_eff + 63) / 64;
     p.seven_bit = layout.embed_scale == kScaleInTopBits ? 1 : 0;
     p.tail_scale = layout.embed_scale == kScaleInTail ? 1 : 0;
     p.escape = layout.escape;
-    uint4 *codes = static_cast<uint4 *>(codes_ws);
-    float *bias = reinterpret_cast<float *>(codes + static_cast<size_t>(p.positions) * p.n_steps * 2);
-    const int items = p.positions * p.n_steps;
-    hipLaunchKernelGGL(fp4_weight_codes_kernel, dim3((items + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, b_bits,
-                       static_cast<int>(n), ldb, p, codes, bias);
-    if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
-    int64_t blocks = (m + 127) / 128;
-    // the blocks stay for the whole call (each loads the codes once): as many as are resident at once
-    const int64_t resident = 256 * (p.positions == 256 ? 2 : 4);
-    if (blocks > resident) blocks = resident;
+    p.alt_half = layout.alt_kind == kF16 ? 1 : 0;
     const float *scale = layout.embed_scale != kScaleSeparate ? src_scale : nullptr;
-    if (p.positions == 256)
-        hipLaunchKernelGGL(bitgemm_fp4_rows_kernel<256>, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream,
-                           a_bits, m, lda, codes, bias, scale, p, static_cast<unsigned char *>(c_rows),
-                           static_cast<unsigned char *>(alt_rows));
-    else
-        hipLaunchKernelGGL(bitgemm_fp4_rows_kernel<128>, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream,
-                           a_bits, m, lda, codes, bias, scale, p, static_cast<unsigned char *>(c_rows),
-                           static_cast<unsigned char *>(alt_rows));
-    return check_launch();
+    const bool narrow = p.n_steps <= 4;
+    switch (p.positions) {
+    case 128:
+        return narrow ? launch_fp4_rows<128, 4>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream)
+                      : launch_fp4_rows<128, 16>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream);
+    case 256:
+        return narrow ? launch_fp4_rows<256, 4>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream)
+                      : launch_fp4_rows<256, 16>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream);
+    default:
+        return narrow ? launch_fp4_rows<512, 4>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream)
+                      : launch_fp4_rows<512, 16>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream);
+    }
 }
 
 }  // namespace bigcn

@@ -15,7 +15,7 @@
 namespace bigcn {
 
 struct WorkspaceMap {
-    size_t bits_off, scale0_off, scale1_off, rows_off, self_rows_off, alt_rows_off, alt_self_rows_off, codes_off, total;
+    size_t bits_off, scale0_off, scale1_off, rows_off, self_rows_off, alt_rows_off, alt_self_rows_off, total;
     bool escape;      // some layer keeps an alternate copy (bytes or fp16) of rows that do not fit 7 bits
 };
 
@@ -72,13 +72,11 @@ static int view_sage(const bigcn_sage_layer *layers, int n_layers, LayerView *ou
 static WorkspaceMap map_workspace(int64_t n, const LayerView *layers, int n_layers, bool own_term)
 {
     int64_t max_words = 0, max_row_bytes = 0, max_alt_bytes = 0;
-    size_t max_codes = 0;      // expanded weights of the layers whose product rows come from the FP4 matrix cores
     for (int l = 0; l < n_layers; ++l) {
         const RowLayout layout = choose_layout(layers[l].d_in, layers[l].d_out);
         max_words = std::max<int64_t>(max_words, (layers[l].d_in + 63) / 64);
         max_row_bytes = std::max<int64_t>(max_row_bytes, layout.row_bytes());
         if (layout.escape) max_alt_bytes = std::max<int64_t>(max_alt_bytes, layout.alt_row_bytes());
-        if (fp4_rows_covers(n, layers[l].d_in, layout)) max_codes = std::max(max_codes, fp4_rows_scratch_bytes(layout));
     }
     WorkspaceMap m;
     m.escape = max_alt_bytes > 0;
@@ -93,8 +91,6 @@ static WorkspaceMap map_workspace(int64_t n, const LayerView *layers, int n_laye
     if (m.escape) off = align_up(off + static_cast<size_t>(n) * max_alt_bytes);
     m.alt_self_rows_off = off;
     if (m.escape && own_term) off = align_up(off + static_cast<size_t>(n) * max_alt_bytes);
-    m.codes_off = off;
-    if (max_codes > 0) off = align_up(off + max_codes);
     m.total = off;
     return m;
 }
@@ -234,7 +230,7 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
                                             L.ld_words, L.d_in, c_rows, alt_rows, layout, s);
         else if (fp4_rows_covers(n, L.d_in, layout))
             rc = launch_bitgemm_fp4_rows(in_bits, n, words, L.w_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1], c_rows,
-                                         alt_rows, layout, ws + map.codes_off, s);
+                                         alt_rows, layout, s);
         else
             rc = launch_bitgemm_layout(in_bits, n, words, L.w_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1], c_rows,
                                        alt_rows, layout, s);
@@ -242,7 +238,7 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
         if (own_term) {
             if (fp4_rows_covers(n, L.d_in, layout))
                 rc = launch_bitgemm_fp4_rows(in_bits, n, words, L.w_self_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1],
-                                             self_rows, alt_self_rows, layout, ws + map.codes_off, s);
+                                             self_rows, alt_self_rows, layout, s);
             else
                 rc = launch_bitgemm_layout(in_bits, n, words, L.w_self_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1],
                                            self_rows, alt_self_rows, layout, s);

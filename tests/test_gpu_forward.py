@@ -140,13 +140,15 @@ def test_forward_extreme_products_rows_of_sixteen_lanes(B, d_in, d_hidden):
 
 @pytest.mark.parametrize("d_in,d_hidden", [(100, 256), (128, 100), (200, 256), (256, 256), (256, 128),
                                            (602, 128), (1024, 300), (2049, 64), (200, 70), (64, 75),
-                                           (255, 200), (65, 256), (192, 160)])
+                                           (255, 200), (65, 256), (192, 160), (512, 512), (600, 400),
+                                           (1024, 256), (700, 200), (257, 90), (100, 512)])
 def test_forward_extreme_products_many_rows(B, d_in, d_hidden):
     """The same on 33000 nodes: beyond 32768 rows the bit-GEMM runs its kernels for large row
-    counts (the matrix-core row kernel for rows of 128 or 256 one-byte values up to 256 input
-    bits, with the scale in the top bits, in the row's tail (70 and 75 columns) or separate;
-    64 rows fetched at a time otherwise; scalar row fetches beyond 256 bits), which must take the
-    same per-row decisions."""
+    counts (the matrix-core row kernel for rows of 128, 256 or 512 one-byte values up to 1024 input
+    bits, with the scale in the top bits, in the row's tail (70 and 75 columns) or separate, and
+    one-byte or fp16 alternates; the vector-ALU kernels where the weights of a layer do not fit
+    its LDS budget (1024 bits x 300 columns) and for fp16 and fp32 rows), which must take the same
+    per-row decisions."""
     _extreme_products(B, d_in, d_hidden, n=33000, n_edges=150000)
 
 

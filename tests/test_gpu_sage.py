@@ -137,11 +137,12 @@ def test_sage_rows_that_do_not_fit_seven_bits(B, d_in):
     _sage_rows_that_do_not_fit(B, d_in, 256, 600, 4000)
 
 
-@pytest.mark.parametrize("d_in,d_hidden", [(100, 128), (128, 256), (200, 256), (256, 256), (200, 72)])
+@pytest.mark.parametrize("d_in,d_hidden", [(100, 128), (128, 256), (200, 256), (256, 256), (200, 72),
+                                           (512, 512), (300, 100), (100, 512)])
 def test_sage_rows_that_do_not_fit_seven_bits_many_rows(B, d_in, d_hidden):
-    """The same on 33000 nodes, where both products of a layer of at most 256 input bits are
-    written by the matrix-core kernel (rows of 128 and of 256 stored values; scale in the top
-    bits, in the row's tail, or separate)."""
+    """The same on 33000 nodes, where both products of a layer are written by the matrix-core
+    kernel (rows of 128, 256 and 512 stored values; scale in the top bits, in the row's tail, or
+    separate; one-byte and fp16 alternates)."""
     _sage_rows_that_do_not_fit(B, d_in, d_hidden, 33000, 150000)
 
 

@@ -1,5 +1,7 @@
-// Kernel 2, matrix-core variant: the +-1 inner products of Sec. 4.2.3 evaluated with the
-// int8 MFMA of gfx950 (v_mfma_i32_32x32x32_i8) instead of XOR + bit count.
+// Kernel 2, matrix-core variants: the +-1 inner products of Sec. 4.2.3 evaluated on the matrix
+// cores of gfx950 instead of XOR + bit count.  Three kernels: int8 (v_mfma_i32_32x32x32_i8, described
+// first), FP4 on the block-scaled path (bitgemm_fp4_kernel, same outputs as the int8 one) and the
+// FP4 kernel that writes the one-byte product rows of the fused forward (bitgemm_fp4_rows_kernel).
 //
 // The packed operands are expanded on the fly.  A (node rows) is expanded to bytes in {0, 1}
 // (three VALU operations per four elements), B (weight columns) to bytes in {-1, +1}, once per

@@ -399,8 +399,14 @@ def main():
         t_spmm = launch_ms[2 + 2 * l] * 1e-3
         macs = work.n * cfg.dims[l] * cfg.dims[l + 1] * (2 if cfg.model == "sage" else 1)
         gather, minimum, row_bytes = aggregation_bytes(cfg, work.nnz, l, B)
+        # the products are written as rows of row_bytes per node (and per product for Bi-GraphSAGE):
+        # on the large workloads this step is bound by those writes, not by the multiplies
+        rows_written = work.n * row_bytes * (2 if cfg.model == "sage" else 1)
         gemm.append({"layer": l, "ms": t_gemm * 1e3, "binary_op_per_s": macs / t_gemm,
-                     "frac_valu_peak": macs / t_gemm / VALU_BINARY_MAC_PEAK})
+                     "frac_valu_peak": macs / t_gemm / VALU_BINARY_MAC_PEAK,
+                     "frac_mfma_fp4_peak": macs / t_gemm / MFMA_FP4_MAC_PEAK,
+                     "rows_written_GBps": rows_written / t_gemm / 1e9,
+                     "frac_hbm_peak": rows_written / t_gemm / 1e9 / HBM_PEAK_GBPS})
         spmm.append({"layer": l, "ms": t_spmm * 1e3, "row_bytes": row_bytes,
                      "gather_GBps": gather / t_spmm / 1e9, "frac_hbm_peak": gather / t_spmm / 1e9 / HBM_PEAK_GBPS,
                      "compulsory_GBps": minimum / t_spmm / 1e9,

@@ -512,8 +512,8 @@ int launch_bitgemm_mfma(const uint64_t *a_bits, const float *a_scale, int64_t m,
 // as value + 128.
 // A block keeps the packed weights of all positions in LDS for its whole life, as
 // [half-word of K][position] dwords (a lane's read is one dword, turned into codes by four
-// masks); a wavefront owns 32 rows at a time.  Per tile of 128 positions: 4 multiplies per 64
-// bits of K with the weights as first operand, so that the four registers of a group hold four
+// masks and a shift, see fp4_rows_weight_codes); a wavefront owns 32 rows at a time.  Per tile of
+// 128 positions: 4 multiplies per 64 bits of K with the weights as first operand, so that the four registers of a group hold four
 // consecutive positions of one row; the saturating byte conversion packs them, a flip of the top
 // bits gives two's complement (values beyond a byte saturate and are caught by the 7-bit test),
 // positions past the last column are zeroed, and the bytes go to the wavefront's LDS buffer
@@ -542,6 +542,25 @@ __host__ __device__ inline size_t fp4_rows_lds_bytes(int positions, int n_steps)
 {
     return static_cast<size_t>(8) * n_steps * positions + positions +
            static_cast<size_t>(kWavesPerBlock) * 32 * kFp4RowsStride;
+}
+
+// Codes of the rows kernel.  A set weight bit only has to multiply its feature by one, so the
+// weight of dword d stays where its bit is inside the nibble (0x1 = 0.5, 0x2 = 1, 0x4 = 2; the
+// fourth bit is moved to 0x2) and the feature codes of that dword carry the inverse magnitude
+// (+-2, +-1, +-0.5, +-1): every product is exactly +-1 or 0, and a weight word costs four masks
+// and one shift.  Same order of the k values as fp4_codes_a / fp4_codes_b.
+__device__ __forceinline__ void fp4_rows_weight_codes(uint32_t x, int (&op)[4])
+{
+    op[0] = static_cast<int>(x & 0x11111111u);
+    op[1] = static_cast<int>(x & 0x22222222u);
+    op[2] = static_cast<int>(x & 0x44444444u);
+    op[3] = static_cast<int>((x & 0x88888888u) >> 2);
+}
+__device__ __forceinline__ uint4 fp4_rows_feature_codes(uint32_t x)
+{
+    const uint32_t n = ~x;                                  // a clear bit is -1: sign bit of the code
+    return make_uint4(((n & 0x11111111u) << 3) | 0x44444444u, ((n & 0x22222222u) << 2) | 0x22222222u,
+                      ((n & 0x44444444u) << 1) | 0x11111111u, (n & 0x88888888u) | 0x22222222u);
 }
 
 // bits of the half-word (q, half) that lie below K'
@@ -618,7 +637,7 @@ __global__ __launch_bounds__(kBlock, 3) void bitgemm_fp4_rows_kernel(
 #pragma unroll
             for (int q = 0; q < kMaxSteps; ++q) {
                 if (q >= p.n_steps) break;                    // uniform
-                uint4 code = fp4_codes_b(cur[q]);
+                uint4 code = fp4_rows_feature_codes(cur[q]);
                 if (q == p.n_steps - 1) {
                     const uint4 keep = fp4_code_mask(fp4_rows_valid(p.k_bits, q, half));
                     code = make_uint4(code.x & keep.x, code.y & keep.y, code.z & keep.z, code.w & keep.w);
@@ -632,7 +651,7 @@ __global__ __launch_bounds__(kBlock, 3) void bitgemm_fp4_rows_kernel(
 #pragma unroll
                 for (int ct = 0; ct < 4; ++ct) {
                     int wcodes[4];
-                    fp4_codes_a(wlane[2 * q * P + 128 * t + 32 * ct], wcodes);
+                    fp4_rows_weight_codes(wlane[2 * q * P + 128 * t + 32 * ct], wcodes);
                     v8i wop;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) wop[e] = wcodes[e];
@@ -744,8 +763,10 @@ static int launch_fp4_rows(const uint64_t *a_bits, int64_t m, int64_t lda, const
     int per_cu = known[slot].load(std::memory_order_relaxed);
     if (per_cu == 0) {
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bitgemm_fp4_rows_kernel<P, kMaxSteps>, kBlock,
-                                                         lds_bytes) != hipSuccess || per_cu < 1)
+                                                         lds_bytes) != hipSuccess || per_cu < 1) {
+            (void)hipGetLastError();                          // the query's failure is not the launch's
             per_cu = 1;
+        }
         known[slot].store(per_cu, std::memory_order_relaxed);
     }
     // the blocks stay for the whole call (each loads the weights once): as many as are resident at once

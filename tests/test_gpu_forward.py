@@ -152,7 +152,15 @@ def test_forward_extreme_products_many_rows(B, d_in, d_hidden):
     _extreme_products(B, d_in, d_hidden, n=33000, n_edges=150000)
 
 
-def _extreme_products(B, d_in, d_hidden, n=400, n_edges=3000):
+@pytest.mark.parametrize("d_in,d_hidden", [(200, 256), (512, 128)])
+def test_forward_every_row_outside_seven_bits_many_rows(B, d_in, d_hidden):
+    """Every node equals (or opposes) a weight column: all 33000 product rows of the first layer
+    leave the 7-bit form and take the alternate array (one-byte and fp16), in the bit-GEMM and in
+    the aggregation."""
+    _extreme_products(B, d_in, d_hidden, n=33000, n_edges=150000, planted=33000)
+
+
+def _extreme_products(B, d_in, d_hidden, n=400, n_edges=3000, planted=120):
     from workloads import chung_lu_csr
     from workloads.build import Workload
     from workloads.configs import WorkloadConfig
@@ -162,11 +170,12 @@ def _extreme_products(B, d_in, d_hidden, n=400, n_edges=3000):
     w0 = rng.uniform(-1, 1, size=(d_in, d_hidden)).astype(np.float32)
     w1 = rng.uniform(-1, 1, size=(d_hidden, d_out)).astype(np.float32)
     x = rng.standard_normal((n, d_in)).astype(np.float32)
-    for k in range(0, 120):
+    for k in range(0, planted):
         j = (7 * k) % d_hidden
         x[k] = w0[:, j] if k % 2 == 0 else -w0[:, j]      # products +K / -K in column j
-    x[120] = np.abs(x[120])                                 # all +1
-    x[121] = -np.abs(x[121]) - 1e-3                         # all -1
+    if planted + 2 <= n:
+        x[planted] = np.abs(x[planted])                     # all +1
+        x[planted + 1] = -np.abs(x[planted + 1]) - 1e-3     # all -1
     cfg = WorkloadConfig("extreme", "none", n, n_edges, 2.0, (d_in, d_hidden, d_out), "normal", 1.0,
                          "first", 0)
     work = Workload(cfg, rp, ci, x, [w0, w1])

@@ -63,7 +63,11 @@ enum RowKind { kI8 = 0, kF16 = 1, kF32 = 2 };
 //   kScaleInTopBits  the stored values use 7 bits (always true for K' <= 127; checked per row
 //                    otherwise, see `escape`): bit i of the scale is the top bit of the first
 //                    byte of lane i's segment, i < 32 (rows of 32 or 64 lanes).
-enum ScalePlace { kScaleSeparate = 0, kScaleInTail = 1, kScaleInTopBits = 2 };
+//   kScaleInLastBytes  64-byte rows of 40..60 columns (8 lanes of 8 values): the last value of
+//                    each of the last four lanes belongs to a column past the last one; byte i
+//                    of the scale is stored there (lane 4 + i).  Keeps such rows in half a cache
+//                    line's worth of lanes instead of widening them to 16 lanes for a tail.
+enum ScalePlace { kScaleSeparate = 0, kScaleInTail = 1, kScaleInTopBits = 2, kScaleInLastBytes = 3 };
 
 struct RowLayout {
     int groups;      // lanes that share one stored row (power of two, 2..64)

@@ -81,7 +81,8 @@ struct EpilogueLayout {
     int k_eff;
     const float *embed;      // non-null (int8 rows only): scale[row] is stored inside the row,
     int top_bits_shift;      //   0: in its last 4 bytes; 3: bit i in the top bit of position 8 i (i < 32) and,
-    int top_bits_groups;     //   for rows of 16 lanes, bits 16..31 in the top bit of position 8 (i - 16) + 4
+    int top_bits_groups;     //   for rows of 16 lanes, bits 16..31 in the top bit of position 8 (i - 16) + 4;
+                             //   -1: byte i at position 8 (groups - 4 + i) + 7 (rows of 8 lanes x 8 values)
     void *alt_rows;          // escape layouts: rows with a value outside [-64, 63] are written here (one
     int alt_half;            // byte per value, or one fp16 when alt_half) and get a NaN scale in the
                              // main array; else nullptr
@@ -149,6 +150,13 @@ struct EpilogueLayout {
                 for (int v = 0; v < VB; ++v) {
                     const int byte = pos0 + v - (positions - 4);
                     if (byte >= 0) tmp[v] = static_cast<T>((bits >> (8 * byte)) & 0xffu);
+                }
+            } else if (embed != nullptr && top_bits_shift < 0) {
+                const uint32_t bits = __float_as_uint(row_scale);
+#pragma unroll
+                for (int v = 0; v < VB; ++v) {
+                    const int p = pos0 + v, byte = (p >> 3) - (top_bits_groups - 4);
+                    if ((p & 7) == 7 && byte >= 0) tmp[v] = static_cast<T>((bits >> (8 * byte)) & 0xffu);
                 }
             } else if (ctx.top_bit >= 0) {
                 const uint32_t bit = (__float_as_uint(row_scale) >> ctx.top_bit) & 1u;
@@ -716,7 +724,7 @@ int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const 
     if (layout.kind == kI8) {
         EpilogueLayout<int8_t> epi{static_cast<int8_t *>(c_rows), layout.positions(), layout.k_eff,
                                    layout.embed_scale != kScaleSeparate ? src_scale : nullptr,
-                                   layout.embed_scale == kScaleInTopBits ? 3 : 0, layout.groups,
+                                   layout.embed_scale == kScaleInTopBits ? 3 : (layout.embed_scale == kScaleInLastBytes ? -1 : 0), layout.groups,
                                    layout.escape ? alt_rows : nullptr, layout.alt_kind == kF16 ? 1 : 0};
         // the escape decision is taken by the one wavefront that holds the whole row
         if (layout.escape && (per_lane > 8 || per_lane * ((k_bits + 63) / 64) > 128)) return BIGCN_EINVAL;
@@ -779,7 +787,7 @@ int launch_pack_bitgemm_layout(const float *x, int64_t m, int64_t ld_x, const fl
         // the scale is computed inside the kernel: `embed` only says that the layout wants it in the row
         EpilogueLayout<int8_t> epi{static_cast<int8_t *>(c_rows), layout.positions(), layout.k_eff,
                                    layout.embed_scale != kScaleSeparate ? scale : nullptr,
-                                   layout.embed_scale == kScaleInTopBits ? 3 : 0, layout.groups,
+                                   layout.embed_scale == kScaleInTopBits ? 3 : (layout.embed_scale == kScaleInLastBytes ? -1 : 0), layout.groups,
                                    layout.escape ? alt_rows : nullptr, layout.alt_kind == kF16 ? 1 : 0};
         BIGCN_PACK_GEMM(epi)
     }

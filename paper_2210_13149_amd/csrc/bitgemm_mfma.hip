@@ -532,16 +532,19 @@ struct Fp4RowsParams {
     int n_steps;          // ceil(K' / 64)
     int seven_bit;        // scale bits in the top bits of the carrier bytes
     int tail_scale;       // scale in the last four bytes
+    int last_bytes;       // rows of 64 positions: scale byte i in the last byte of lane 4 + i
     int escape;           // rows outside the 7-bit range go to alt_rows
     int alt_half;         // ... as fp16 (else as bytes)
 };
 
-constexpr int kFp4RowsStride = 128 + 8;                     // bytes per row of a wavefront's LDS tile
+// A tile is 128 positions wide (64 for rows of 64 positions); bytes per row of a wavefront's LDS tile
+__host__ __device__ constexpr int fp4_rows_tile(int positions) { return positions < 128 ? positions : 128; }
+__host__ __device__ constexpr int fp4_rows_stride(int positions) { return fp4_rows_tile(positions) + 8; }
 
 __host__ __device__ inline size_t fp4_rows_lds_bytes(int positions, int n_steps)
 {
     return static_cast<size_t>(8) * n_steps * positions + positions +
-           static_cast<size_t>(kWavesPerBlock) * 32 * kFp4RowsStride;
+           static_cast<size_t>(kWavesPerBlock) * 32 * fp4_rows_stride(positions);
 }
 
 // Codes of the rows kernel.  A set weight bit only has to multiply its feature by one, so the
@@ -577,16 +580,20 @@ __global__ __launch_bounds__(kBlock, 3) void bitgemm_fp4_rows_kernel(
     void *__restrict__ alt_rows)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char fp4_rows_lds[];
-    constexpr int n_tiles = P / 128;
+    constexpr int kTile = fp4_rows_tile(P);                  // positions per tile
+    constexpr int kCt = kTile / 32;                          // 32 x 32 products per tile
+    constexpr int kStride = fp4_rows_stride(P);
+    constexpr int kSegs = kTile / 8;                         // lanes that write one row's piece of a tile
+    constexpr int n_tiles = P / kTile;
     uint32_t *wbits = reinterpret_cast<uint32_t *>(fp4_rows_lds);               // [2 n_steps][P]
     unsigned char *live = fp4_rows_lds + static_cast<size_t>(8) * p.n_steps * P;   // [P]: 0xff below n columns
     const int lane = lane_id();
     const int wave = wave_in_block();
     const int i32 = lane & 31, half = lane >> 5;
-    unsigned char *mine = live + P + wave * 32 * kFp4RowsStride;
+    unsigned char *mine = live + P + wave * 32 * kStride;
     const uint32_t *wlane = wbits + half * P + i32;           // this lane's weight words: + 2 q P + position of tile
     const unsigned char *live_lane = live + 4 * half;
-    unsigned char *mine_lane = mine + i32 * kFp4RowsStride + 4 * half;
+    unsigned char *mine_lane = mine + i32 * kStride + 4 * half;
     const int64_t wave_id = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave;
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kWavesPerBlock * 32;
 
@@ -623,15 +630,15 @@ __global__ __launch_bounds__(kBlock, 3) void bitgemm_fp4_rows_kernel(
         ones += __shfl_xor(ones, 32);
         // (F + K' mod 2) / 2 with F = 2 ones - K': an even number halved
         const float start = 128.0f - static_cast<float>((2 * ones - p.k_bits + (p.k_bits & 1)) / 2);
-        if (half == 0) *reinterpret_cast<uint32_t *>(mine + i32 * kFp4RowsStride + 128) = next_scale;
+        if (half == 0) *reinterpret_cast<uint32_t *>(mine + i32 * kStride + kTile) = next_scale;
         fetch(row0 + stride);
         uint32_t escaped = 0;                                 // rows of this wavefront's 32 that need the alternate array
 #pragma unroll 1
         for (int t = 0; t < n_tiles; ++t) {
             // register 4 g + e of tile ct: position 128 t + 32 ct + 8 g + 4 half + e, row i32
-            v16f acc[4];
+            v16f acc[kCt];
 #pragma unroll
-            for (int ct = 0; ct < 4; ++ct)
+            for (int ct = 0; ct < kCt; ++ct)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[ct][r] = start;
 #pragma unroll
@@ -649,9 +656,9 @@ __global__ __launch_bounds__(kBlock, 3) void bitgemm_fp4_rows_kernel(
                 fop[3] = static_cast<int>(code.w);
                 fop[4] = fop[5] = fop[6] = fop[7] = 0;
 #pragma unroll
-                for (int ct = 0; ct < 4; ++ct) {
+                for (int ct = 0; ct < kCt; ++ct) {
                     int wcodes[4];
-                    fp4_rows_weight_codes(wlane[2 * q * P + 128 * t + 32 * ct], wcodes);
+                    fp4_rows_weight_codes(wlane[2 * q * P + kTile * t + 32 * ct], wcodes);
                     v8i wop;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) wop[e] = wcodes[e];
@@ -661,29 +668,29 @@ __global__ __launch_bounds__(kBlock, 3) void bitgemm_fp4_rows_kernel(
                 }
             }
 #pragma unroll
-            for (int ct = 0; ct < 4; ++ct)
+            for (int ct = 0; ct < kCt; ++ct)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     uint32_t packed = 0;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) packed = __builtin_amdgcn_cvt_pk_u8_f32(acc[ct][4 * g + e], e, packed);
-                    const uint32_t keep = *reinterpret_cast<const uint32_t *>(live_lane + 128 * t + 32 * ct + 8 * g);
+                    const uint32_t keep = *reinterpret_cast<const uint32_t *>(live_lane + kTile * t + 32 * ct + 8 * g);
                     *reinterpret_cast<uint32_t *>(mine_lane + 32 * ct + 8 * g) = (packed ^ 0x80808080u) & keep;
                 }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            // this tile's 128 bytes of every row: 16 lanes per row, 8 bytes each
-            const int seg = lane & 15, sub = lane >> 4;
-            const int row_seg = 16 * t + seg;                 // 8-byte segment of the whole row
+            // this tile's piece of every row: kSegs lanes per row, 8 bytes each
+            const int seg = lane & (kSegs - 1), sub = lane / kSegs;
+            const int row_seg = kSegs * t + seg;              // 8-byte segment of the whole row
 #pragma unroll 4
-            for (int j = 0; j < 32; j += 4) {
+            for (int j = 0; j < 32; j += kWave / kSegs) {
                 const int local = j + sub;
                 const int64_t row = row0 + local;
-                uint2 v = *reinterpret_cast<const uint2 *>(mine + local * kFp4RowsStride + 8 * seg);
-                const uint32_t row_scale = *reinterpret_cast<const uint32_t *>(mine + local * kFp4RowsStride + 128);
+                uint2 v = *reinterpret_cast<const uint2 *>(mine + local * kStride + 8 * seg);
+                const uint32_t row_scale = *reinterpret_cast<const uint32_t *>(mine + local * kStride + kTile);
                 if (p.seven_bit) {
-                    if (p.escape) {
+                    if (kSegs == 16 && p.escape) {
                         // a byte fits 7 bits when its bits 7 and 6 agree
                         const bool misfit = (((v.x ^ (v.x << 1)) | (v.y ^ (v.y << 1))) & 0x80808080u) != 0u;
                         const uint64_t any = __ballot(misfit);
@@ -696,9 +703,12 @@ __global__ __launch_bounds__(kBlock, 3) void bitgemm_fp4_rows_kernel(
                     if (row_seg < 32) v.x = (v.x & ~0x80u) | (((row_scale >> row_seg) & 1u) << 7);
                     if (P == 128) v.y = (v.y & ~0x80u) | (((row_scale >> (16 + seg)) & 1u) << 7);
                 } else if (p.tail_scale) {
-                    if (t == n_tiles - 1 && seg == 15) v.y = row_scale;
+                    if (t == n_tiles - 1 && seg == kSegs - 1) v.y = row_scale;
+                } else if (p.last_bytes) {
+                    // rows of 8 lanes: byte i of the scale is the last byte of lane 4 + i
+                    if (seg >= kSegs - 4) v.y = (v.y & 0x00ffffffu) | (((row_scale >> (8 * (seg - (kSegs - 4)))) & 0xffu) << 24);
                 }
-                if (row < m) *reinterpret_cast<uint2 *>(rows + row * P + 128 * t + 8 * seg) = v;
+                if (row < m) *reinterpret_cast<uint2 *>(rows + row * P + kTile * t + 8 * seg) = v;
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();                  // the buffer is rewritten by the next tile
@@ -746,7 +756,9 @@ bool fp4_rows_covers(int64_t m, int64_t k_bits, const RowLayout &layout)
 {
     const int pos = layout.positions();
     if (layout.kind != kI8 || k_bits > 1024 || m <= 32768) return false;
-    if (pos != 128 && pos != 256 && pos != 512) return false;
+    if (pos != 64 && pos != 128 && pos != 256 && pos != 512) return false;
+    if (pos == 64 && (layout.embed_scale == kScaleInTopBits || layout.groups != 8)) return false;
+    if (layout.embed_scale == kScaleInLastBytes && pos != 64) return false;
     if (layout.escape && layout.alt_kind != kI8 && layout.alt_kind != kF16) return false;
     if (layout.escape && layout.embed_scale != kScaleInTopBits) return false;
     return fp4_rows_lds_bytes(pos, (layout.k_eff + 63) / 64) <= 64 * 1024;
@@ -793,11 +805,15 @@ int launch_bitgemm_fp4_rows(const uint64_t *a_bits, int64_t m, int64_t lda, cons
     p.n_steps = (layout.k_eff + 63) / 64;
     p.seven_bit = layout.embed_scale == kScaleInTopBits ? 1 : 0;
     p.tail_scale = layout.embed_scale == kScaleInTail ? 1 : 0;
+    p.last_bytes = layout.embed_scale == kScaleInLastBytes ? 1 : 0;
     p.escape = layout.escape;
     p.alt_half = layout.alt_kind == kF16 ? 1 : 0;
     const float *scale = layout.embed_scale != kScaleSeparate ? src_scale : nullptr;
     const bool narrow = p.n_steps <= 4;
     switch (p.positions) {
+    case 64:
+        return narrow ? launch_fp4_rows<64, 4>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream)
+                      : launch_fp4_rows<64, 16>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream);
     case 128:
         return narrow ? launch_fp4_rows<128, 4>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream)
                       : launch_fp4_rows<128, 16>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream);

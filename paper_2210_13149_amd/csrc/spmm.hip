@@ -28,9 +28,11 @@ namespace bigcn {
 enum WeightMode {
     kWeightOne = 0, kWeightVals = 1, kWeightGather = 2, kWeightEmbedded = 3, kWeightTopBits = 4,
     kWeightTopBitsEscape = 5,        // alternate rows hold one byte per value
-    kWeightTopBitsEscapeF16 = 6      // ... one fp16 per value (layers of more than 256 input bits)
+    kWeightTopBitsEscapeF16 = 6,     // ... one fp16 per value (layers of more than 256 input bits)
+    kWeightLastBytes = 7             // rows of 8 lanes: byte i of the weight is the last byte of lane 4 + i
 };
-__host__ __device__ constexpr bool escape_weights(int wm) { return wm >= kWeightTopBitsEscape; }
+__host__ __device__ constexpr bool top_bit_weights(int wm) { return wm >= kWeightTopBits && wm <= kWeightTopBitsEscapeF16; }
+__host__ __device__ constexpr bool escape_weights(int wm) { return wm == kWeightTopBitsEscape || wm == kWeightTopBitsEscapeF16; }
 __host__ __device__ constexpr bool fused_weights(int wm) { return wm >= kWeightGather; }
 __host__ __device__ constexpr bool row_weights(int wm) { return wm >= kWeightEmbedded; }
 
@@ -140,6 +142,7 @@ struct Segment<int8_t, 8> {
 };
 // The fp32 weight stored inside a loaded row, handed to every lane of the row's group.
 //   kWeightEmbedded: the row's last four bytes, held by the last lane of the group;
+//   kWeightLastBytes: rows of 8 lanes; byte i of the weight is the last byte of lane 4 + i;
 //   kWeightTopBits:  bit i of the weight is the top bit of the first byte of lane i's segment
 //                    (groups of 32 or 64 lanes; groups of 16 lanes keep bits 16..31 in the top
 //                    bit of the fifth byte); one ballot per carrier byte collects the bits of all
@@ -150,7 +153,19 @@ __device__ __forceinline__ float row_weight(Segment<T, V> &seg, int lane, bool l
 {
     if constexpr (sizeof(T) == 1 && WM == kWeightEmbedded) {
         return __uint_as_float(static_cast<uint32_t>(__shfl(static_cast<int>(seg.tail()), lane | (G - 1), kWave)));
-    } else if constexpr (sizeof(T) == 1 && WM >= kWeightTopBits) {
+    } else if constexpr (sizeof(T) == 1 && WM == kWeightLastBytes) {
+        static_assert(sizeof(T) != 1 || WM != kWeightLastBytes || (G == 8 && V == 8), "rows of 8 lanes x 8 values");
+        // lanes 4..7 of a row are one quad: each of them collects the four bytes by quad
+        // broadcasts (data-parallel moves, no LDS traffic), then one shuffle hands the word of
+        // lane 4 to the row's eight lanes
+        const int top = static_cast<int>(seg.tail() >> 24);
+        const uint32_t b0 = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, top, 0x00, 0xf, 0xf, false));
+        const uint32_t b1 = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, top, 0x55, 0xf, 0xf, false));
+        const uint32_t b2 = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, top, 0xaa, 0xf, 0xf, false));
+        const uint32_t b3 = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, top, 0xff, 0xf, 0xf, false));
+        const int word = static_cast<int>(b0 | (b1 << 8) | (b2 << 16) | (b3 << 24));
+        return __uint_as_float(static_cast<uint32_t>(__shfl(word, (lane & ~(G - 1)) + G - 4, kWave)));
+    } else if constexpr (sizeof(T) == 1 && top_bit_weights(WM)) {
         const uint64_t bits = __ballot(loaded && (seg.head() & 0x80u) != 0);
         if constexpr (G >= 32) {
             const uint32_t mine = (G == kWave || lane < 32) ? static_cast<uint32_t>(bits) : static_cast<uint32_t>(bits >> 32);
@@ -201,7 +216,7 @@ __device__ __forceinline__ const char *row_address(const RowBase &rb, int k, uin
 template <typename T, int G, int V, int WM>
 __device__ __forceinline__ void accumulate_segment(const Segment<T, V> &seg, float w, float (&acc)[V])
 {
-    if constexpr (sizeof(T) == 1 && WM >= kWeightTopBits) seg.template fma_carrier<(G < 32)>(w, acc);
+    if constexpr (sizeof(T) == 1 && top_bit_weights(WM)) seg.template fma_carrier<(G < 32)>(w, acc);
     else seg.fma(w, acc);
 }
 
@@ -775,6 +790,12 @@ RowLayout choose_layout(int64_t d_in, int64_t d_out)
         // (G-1) + G*(V-4 .. V-1); when those lie past d_out the bytes are free for the scale.
         // A row of at most 64 bytes is widened to make room: up to 128 bytes a row costs one
         // cache line either way, and the separate scale gather (a second line) disappears.
+        // 40..60 columns in a 64-byte row: the tail is taken (column 39 sits there), but the last
+        // value of each of the last four lanes is free and holds one byte of the scale each.
+        if (l.groups == 8 && d_out > l.groups * (l.vec - 3) - 1 && d_out <= l.positions() - 4) {
+            l.embed_scale = kScaleInLastBytes;
+            return l;
+        }
         if (d_out > l.groups * (l.vec - 3) - 1 && l.positions() <= 64) l.groups *= 2;
         l.embed_scale = d_out <= l.groups * (l.vec - 3) - 1 ? kScaleInTail : kScaleSeparate;
         // Up to 128 input bits the stored value needs 7 bits (K = 128: with the last bit folded
@@ -853,6 +874,11 @@ static int launch_fused_spmm_t(const FusedSpmmArgs &a, hipStream_t stream)
     }
     if (l.kind == kI8 && l.embed_scale == kScaleInTail) {
         BIGCN_FUSED_EMBEDDED(int8_t, 8);
+    }
+    if (l.kind == kI8 && l.embed_scale == kScaleInLastBytes) {
+        if (l.groups != 8 || l.vec != 8) return BIGCN_EINVAL;
+        return launch_spmm_one<int8_t, 8, 8, kWeightLastBytes>(a.plan, a.row_ptr, a.col_idx, nullptr, a.c_rows, rb, valid,
+                                                             epi, stream, nullptr);
     }
     if (l.kind == kI8) {
         BIGCN_FUSED(int8_t, 8);

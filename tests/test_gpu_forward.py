@@ -138,6 +138,16 @@ def test_forward_extreme_products_rows_of_sixteen_lanes(B, d_in, d_hidden):
     _extreme_products(B, d_in, d_hidden)
 
 
+@pytest.mark.parametrize("d_in,d_hidden,n", [(100, 40, 400), (128, 47, 400), (200, 56, 400), (256, 60, 400),
+                                             (255, 61, 400), (64, 41, 400), (256, 47, 33000),
+                                             (100, 60, 33000)])
+def test_forward_extreme_products_rows_of_eight_lanes(B, d_in, d_hidden, n):
+    """The same with 40 to 60 hidden columns and at most 256 input bits: 64-byte rows of 8 lanes
+    whose scale is spread over the last value of the last four lanes (61 columns: widened to 16
+    lanes with the scale in the tail, as before)."""
+    _extreme_products(B, d_in, d_hidden, n=n, n_edges=3000 if n < 1000 else 150000)
+
+
 @pytest.mark.parametrize("d_in,d_hidden", [(100, 256), (128, 100), (200, 256), (256, 256), (256, 128),
                                            (602, 128), (1024, 300), (2049, 64), (200, 70), (64, 75),
                                            (255, 200), (65, 256), (192, 160), (512, 512), (600, 400),
@@ -200,7 +210,8 @@ def _hand_graph(kind):
 
 
 @pytest.mark.parametrize("kind", ["single", "isolated", "star", "path"])
-@pytest.mark.parametrize("dims", [(7, 3), (100, 512, 512, 10), (70, 64, 1), (256, 128, 47)])
+@pytest.mark.parametrize("dims", [(7, 3), (100, 512, 512, 10), (70, 64, 1), (256, 128, 47), (100, 56, 60),
+                                  (200, 40, 41)])
 def test_forward_on_degenerate_graphs_and_extreme_widths(B, kind, dims):
     """Hand-built graphs (one node, no edges, a star whose hub row is shared by a workgroup, a path)
     with the narrowest and the widest layers the fused forward takes (1 and 512 columns)."""

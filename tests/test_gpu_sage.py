@@ -115,6 +115,8 @@ def test_sage_forward_matches_oracle(B, name, n_scaled):
     ((130, 512, 512, 9), 1500, 30000, 1.1),
     ((2100, 33, 64, 3), 1200, 5000, 2.0),
     ((128, 300, 128, 256, 4), 1500, 20000, 1.1),
+    ((100, 47, 41), 3000, 40000, 1.2),
+    ((256, 60, 40, 56), 2000, 9000, 2.0),
 ])
 def test_sage_forward_formats_and_edge_cases(B, dims, n, n_edges, i0):
     work = small_sage_workload(n, n_edges, dims, seed=sum(dims), i0=i0)

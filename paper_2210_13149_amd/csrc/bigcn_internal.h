@@ -146,7 +146,7 @@ int launch_bitgemm_fp4(const uint64_t *a_bits, const float *a_scale, int64_t m, 
                        int64_t k_bits, int32_t *acc, int64_t ld_acc, float *out, int64_t ld_out,
                        hipStream_t stream);
 
-// Product rows of a one-byte RowLayout on the FP4 matrix cores (K <= 1024, 128 / 256 / 512 stored
+// Product rows of a one-byte RowLayout on the FP4 matrix cores (K <= 1024, 64 / 128 / 256 / 512 stored
 // positions, more than 32768 rows): fp4_rows_covers says whether the shape is taken.
 bool fp4_rows_covers(int64_t m, int64_t k_bits, const RowLayout &layout);
 int launch_bitgemm_fp4_rows(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits, int64_t n,

@@ -504,7 +504,7 @@ int launch_bitgemm_mfma(const uint64_t *a_bits, const float *a_scale, int64_t m,
 }
 
 // ---- product rows of the fused forward on the FP4 matrix cores (K <= 1024) ---------------------
-// One-byte product rows of 128, 256 or 512 stored positions (position p of a RowLayout holds
+// One-byte product rows of 64, 128, 256 or 512 stored positions (position p of a RowLayout holds
 // column p / vec + groups (p % vec)).  Here the weights are the {0, +1} operand and the features
 // the {-1, +1} one: with S = sum over the set weight bits of f_k and F = sum_k f_k, the product is
 // 2 S - F and the stored value floor(K'/2) - popcount(f xor b) equals S - (F + K' mod 2) / 2, a
@@ -513,19 +513,21 @@ int launch_bitgemm_mfma(const uint64_t *a_bits, const float *a_scale, int64_t m,
 // A block keeps the packed weights of all positions in LDS for its whole life, as
 // [half-word of K][position] dwords (a lane's read is one dword, turned into codes by four
 // masks and a shift, see fp4_rows_weight_codes); a wavefront owns 32 rows at a time.  Per tile of
-// 128 positions: 4 multiplies per 64 bits of K with the weights as first operand, so that the four registers of a group hold four
-// consecutive positions of one row; the saturating byte conversion packs them, a flip of the top
-// bits gives two's complement (values beyond a byte saturate and are caught by the 7-bit test),
-// positions past the last column are zeroed, and the bytes go to the wavefront's LDS buffer
-// [row][128 positions].  Then 16 lanes per row take 8 bytes each, test the 7-bit range where the
+// 128 positions (rows of 64 positions: one tile of 64): 4 (2) multiplies per 64 bits of K with
+// the weights as first operand, so that the four registers of a group hold four consecutive
+// positions of one row; the saturating byte conversion packs them, a flip of the top bits gives
+// two's complement (values beyond a byte saturate and are caught by the 7-bit test), positions
+// past the last column are zeroed, and the bytes go to the wavefront's LDS buffer
+// [row][tile + 8].  Then 16 (8) lanes per row take 8 bytes each, test the 7-bit range where the
 // layout asks for it (bit 7 differs from bit 6), stamp the scale (top bits of the carrier bytes,
-// or the last four bytes of the row) and write 128-byte pieces of rows.  Rows with a value outside
-// 7 bits are noted and, after the last tile, redone one at a time with XOR and bit counts from
-// the same LDS weights: their values go to the alternate array (bytes or fp16) and the carrier
-// bytes of the main row get a NaN scale, as in the vector-ALU kernels.  The bits and the scale
-// of the next 32 rows are fetched while the current ones are multiplied.
+// the last four bytes of the row, or the last byte of each of the last four lanes) and write
+// the rows' pieces of the tile.  Rows with a value outside 7 bits are noted and, after the last
+// tile, redone one at a time with XOR and bit counts from the same LDS weights: their values go
+// to the alternate array (bytes or fp16) and the carrier bytes of the main row get a NaN scale,
+// as in the vector-ALU kernels.  The bits and the scale of the next 32 rows are fetched while
+// the current ones are multiplied.
 struct Fp4RowsParams {
-    int positions;        // 128, 256 or 512
+    int positions;        // 64, 128, 256 or 512
     int groups, vec;      // of the RowLayout
     int n;                // columns
     int k_bits;           // K' (without a folded last bit)
@@ -749,7 +751,7 @@ __global__ __launch_bounds__(kBlock, 3) void bitgemm_fp4_rows_kernel(
     }
 }
 
-// Product rows of `layout` on the FP4 matrix cores: one byte per value, 128 / 256 / 512 stored
+// Product rows of `layout` on the FP4 matrix cores: one byte per value, 64 / 128 / 256 / 512 stored
 // positions, K <= 1024 with the packed weights fitting 64 KB of LDS beside the row tiles, more
 // than 32768 rows.  Returns BIGCN_EINVAL without launching anything when the shape is not covered.
 bool fp4_rows_covers(int64_t m, int64_t k_bits, const RowLayout &layout)

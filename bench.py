@@ -407,8 +407,11 @@ def main():
                      "frac_mfma_fp4_peak": macs / t_gemm / MFMA_FP4_MAC_PEAK,
                      "rows_written_GBps": rows_written / t_gemm / 1e9,
                      "frac_hbm_peak": rows_written / t_gemm / 1e9 / HBM_PEAK_GBPS})
+        # a gathered row moves whole 128-byte lines: rows of 64 bytes cost one line each
+        line_bytes = work.nnz * (-(-row_bytes // 128) * 128)
         spmm.append({"layer": l, "ms": t_spmm * 1e3, "row_bytes": row_bytes,
                      "gather_GBps": gather / t_spmm / 1e9, "frac_hbm_peak": gather / t_spmm / 1e9 / HBM_PEAK_GBPS,
+                     "row_lines_GBps": line_bytes / t_spmm / 1e9,
                      "compulsory_GBps": minimum / t_spmm / 1e9,
                      # a row array that fits the 256 MB Infinity Cache is gathered from there: the
                      # algorithmic bytes over the HBM peak can then exceed 1 and is no HBM figure

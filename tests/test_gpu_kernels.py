@@ -121,6 +121,23 @@ def test_binary_gemm(B, m, n, k, variant):
     assert none is None and np.array_equal(only_out.cpu().numpy(), dout.cpu().numpy())
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_binary_gemm_random_shapes(B, seed):
+    """Seeded random shapes on either side of the tile sizes of the four evaluation paths (32-row
+    and 128-row tiles, 32 / 64 / 128 columns, 64 / 256 / 512-bit chunks of K, the 32768-row switch)."""
+    rng = _rng(900 + seed)
+    for _ in range(12):
+        m = int(rng.choice([1, 31, 32, 33, 127, 128, 129, 255, 257, 1000, 4099, int(rng.integers(1, 5000)),
+                            32769 + int(rng.integers(0, 3000))]))
+        n = int(rng.choice([1, 2, 31, 32, 33, 47, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300, 512, 700]))
+        k = int(rng.choice([1, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513, 767, 768, 1023, 1024,
+                            1025, 2047, 2048, 2049, 4096, int(rng.integers(1, 6000))]))
+        if m * n * k > 3e9:
+            continue
+        for variant in ("auto", "valu", "mfma", "fp4"):
+            test_binary_gemm(B, m, n, k, variant)
+
+
 def test_binary_gemm_unit_scales_give_exact_integers(B):
     rng = _rng(5)
     f = rng.choice(np.array([-1, 1], dtype=np.int8), size=(64, 1433))

@@ -32,7 +32,7 @@ def B():
     return binding
 
 
-@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("seed", range(16))
 def test_forward_random_shapes(B, seed):
     rng = np.random.default_rng(7000 + seed)
     for it in range(CASES_PER_SEED):

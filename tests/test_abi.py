@@ -155,6 +155,27 @@ def test_forward_workspace_size_and_argument_checks():
     assert fwd(lay=_layers((9000, 64, 47), ld=200), nl=2) == binding.BIGCN_ESHAPE
 
 
+def test_product_row_formats_by_layer_shape():
+    """The per-node product row of the fused forward, by (input bits, columns): one byte per
+    product up to 1024 input bits (rows of 2..64 lanes of 8 values, the source scale inside the
+    row: in its tail, in the last bytes of four lanes for 40..60 columns, or in the spare top
+    bits), fp16 products up to 2048 bits and fp32 beyond (scale gathered separately).  A host
+    function: no GPU needed."""
+    B = binding
+    expect = {
+        (100, 256): (256, True), (256, 256): (256, True), (100, 512): (512, True), (1024, 512): (512, True),
+        # the class counts of the large workloads: 64-byte rows up to 256 input bits
+        (128, 41): (64, True), (256, 47): (64, True), (256, 39): (64, True), (256, 40): (64, True),
+        (256, 60): (64, True), (256, 61): (128, True), (256, 64): (128, True),
+        # beyond 256 bits a row has at least 16 lanes, for the bits of the scale
+        (257, 47): (128, True), (512, 47): (128, True), (602, 128): (128, True),
+        (64, 7): (16, True), (100, 3): (16, True), (100, 79): (128, True), (100, 80): (128, True),
+        (1025, 64): (128, False), (2048, 64): (128, False), (2049, 64): (256, False), (3703, 64): (256, False),
+    }
+    for (d_in, d_out), want in expect.items():
+        assert B.bigcn_forward_row_bytes(d_in, d_out) == want, (d_in, d_out)
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(TypeError):

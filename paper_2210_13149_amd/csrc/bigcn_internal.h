@@ -113,10 +113,11 @@ int launch_source_scale(const float *beta, const float *row_mul, const uint64_t 
 // bit-GEMM writing the integer products in a RowLayout (fused forward).
 // src_scale (m floats) is copied into the rows when the layout embeds the scale.
 // alt_rows (escape layouts only): receives the rows that do not fit 7 bits, one byte or fp16 per value
-// (layout.alt_kind).
+// (layout.alt_kind).  escape_flag (DEVICE, nullable): set to 1 when any row went to alt_rows; never
+// cleared here.
 int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits,
                           int64_t n, int64_t ldb, int64_t k_bits, const float *src_scale, void *c_rows,
-                          void *alt_rows, RowLayout layout, hipStream_t stream);
+                          void *alt_rows, RowLayout layout, hipStream_t stream, int *escape_flag = nullptr);
 
 // First layer of a small graph: binarise the fp32 rows of x and multiply in one launch; writes
 // the product rows and scale[i] = row_mul[i] * beta_i (negated for a folded last bit of -1).
@@ -151,7 +152,7 @@ int launch_bitgemm_fp4(const uint64_t *a_bits, const float *a_scale, int64_t m, 
 bool fp4_rows_covers(int64_t m, int64_t k_bits, const RowLayout &layout);
 int launch_bitgemm_fp4_rows(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits, int64_t n,
                             int64_t ldb, int64_t k_bits, const float *src_scale, void *c_rows, void *alt_rows,
-                            RowLayout layout, hipStream_t stream);
+                            RowLayout layout, hipStream_t stream, int *escape_flag = nullptr);
 
 // Aggregation of layer l fused with the rescale and with the binarisation of layer l+1.
 // Bi-GCN: dst_mul = next_row_mul = D^-1/2 and no own-row term.  Bi-GraphSAGE (mean aggregator):
@@ -187,6 +188,11 @@ struct FusedSpmmArgs {
     const void *self_rows;      // n rows in `layout`: products with the second weight matrix
     const float *self_alpha;    // d_out
     const uint64_t *self_w_bits;// packed second weight matrix (for its last-bit term), stride w_ld_words
+    // escape layouts: *escape_flag == 0 (DEVICE, nullable) promises that no row of c_rows / self_rows
+    // went to the alternate arrays, and the kernel then runs without the per-row test.  clear_flag
+    // (DEVICE, nullable) is set to 0 by this launch: the flag of the layer that follows.
+    const int *escape_flag;
+    int *clear_flag;
 };
 int launch_fused_spmm(const FusedSpmmArgs &args, hipStream_t stream);
 

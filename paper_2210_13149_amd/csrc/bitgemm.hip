@@ -86,6 +86,7 @@ struct EpilogueLayout {
     void *alt_rows;          // escape layouts: rows with a value outside [-64, 63] are written here (one
     int alt_half;            // byte per value, or one fp16 when alt_half) and get a NaN scale in the
                              // main array; else nullptr
+    int *escape_flag;        // nullable: set to 1 whenever a row goes to alt_rows
     template <int VB>
     struct Lane {
         int top_bit;         // which bit of the scale this lane's first value carries, or -1
@@ -140,6 +141,7 @@ struct EpilogueLayout {
                 // one wavefront holds the whole row: if any value needs the eighth bit the row goes
                 // to the alternate array as it is and the main array gets a NaN scale
                 if (__ballot((spread & ~127u) != 0u) != 0ull) {
+                    if (escape_flag != nullptr) *escape_flag = 1;
                     write_values<VB>(static_cast<T *>(alt_rows) + row * positions + pos0, tmp);
                     row_scale = __uint_as_float(0x7fc00000u);
                 }
@@ -183,6 +185,7 @@ struct EpilogueLayout {
             // one wavefront holds the whole row: if any value needs the eighth bit the row goes to
             // the alternate array (bytes or fp16) and the main array gets a NaN scale
             if (__ballot((spread & ~127u) != 0u) != 0ull) {
+                if (escape_flag != nullptr) *escape_flag = 1;
                 if (alt_half) {
                     alignas(16) __half tmp[VB];
 #pragma unroll
@@ -714,7 +717,7 @@ static int dispatch_bitgemm(int per_lane, int groups, int vec, const uint64_t *a
 
 int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits,
                           int64_t n, int64_t ldb, int64_t k_bits, const float *src_scale, void *c_rows,
-                          void *alt_rows, RowLayout layout, hipStream_t stream)
+                          void *alt_rows, RowLayout layout, hipStream_t stream, int *escape_flag)
 {
     if (m == 0 || n == 0) return BIGCN_OK;
     if (layout.escape && alt_rows == nullptr) return BIGCN_ENULL;
@@ -725,7 +728,7 @@ int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const 
         EpilogueLayout<int8_t> epi{static_cast<int8_t *>(c_rows), layout.positions(), layout.k_eff,
                                    layout.embed_scale != kScaleSeparate ? src_scale : nullptr,
                                    layout.embed_scale == kScaleInTopBits ? 3 : (layout.embed_scale == kScaleInLastBytes ? -1 : 0), layout.groups,
-                                   layout.escape ? alt_rows : nullptr, layout.alt_kind == kF16 ? 1 : 0};
+                                   layout.escape ? alt_rows : nullptr, layout.alt_kind == kF16 ? 1 : 0, escape_flag};
         // the escape decision is taken by the one wavefront that holds the whole row
         if (layout.escape && (per_lane > 8 || per_lane * ((k_bits + 63) / 64) > 128)) return BIGCN_EINVAL;
         if (layout.escape && layout.alt_kind != kI8 && layout.alt_kind != kF16) return BIGCN_EINVAL;
@@ -733,11 +736,11 @@ int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const 
                                 last_mask, epi, stream);
     }
     if (layout.kind == kF16) {
-        EpilogueLayout<__half> epi{static_cast<__half *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, 0, nullptr, 0};
+        EpilogueLayout<__half> epi{static_cast<__half *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, 0, nullptr, 0, nullptr};
         return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
                                 last_mask, epi, stream);
     }
-    EpilogueLayout<float> epi{static_cast<float *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, 0, nullptr, 0};
+    EpilogueLayout<float> epi{static_cast<float *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, 0, nullptr, 0, nullptr};
     return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
                             last_mask, epi, stream);
 }
@@ -788,14 +791,14 @@ int launch_pack_bitgemm_layout(const float *x, int64_t m, int64_t ld_x, const fl
         EpilogueLayout<int8_t> epi{static_cast<int8_t *>(c_rows), layout.positions(), layout.k_eff,
                                    layout.embed_scale != kScaleSeparate ? scale : nullptr,
                                    layout.embed_scale == kScaleInTopBits ? 3 : (layout.embed_scale == kScaleInLastBytes ? -1 : 0), layout.groups,
-                                   layout.escape ? alt_rows : nullptr, layout.alt_kind == kF16 ? 1 : 0};
+                                   layout.escape ? alt_rows : nullptr, layout.alt_kind == kF16 ? 1 : 0, nullptr};
         BIGCN_PACK_GEMM(epi)
     }
     if (layout.kind == kF16) {
-        EpilogueLayout<__half> epi{static_cast<__half *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, 0, nullptr, 0};
+        EpilogueLayout<__half> epi{static_cast<__half *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, 0, nullptr, 0, nullptr};
         BIGCN_PACK_GEMM(epi)
     }
-    EpilogueLayout<float> epi{static_cast<float *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, 0, nullptr, 0};
+    EpilogueLayout<float> epi{static_cast<float *>(c_rows), layout.positions(), layout.k_eff, nullptr, 0, 0, nullptr, 0, nullptr};
     BIGCN_PACK_GEMM(epi)
 #undef BIGCN_PACK_GEMM
 }

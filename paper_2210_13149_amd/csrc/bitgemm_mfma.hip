@@ -579,7 +579,7 @@ template <int P, int kMaxSteps>        // P stored positions; kMaxSteps 4: K' <=
 __global__ __launch_bounds__(kBlock, 3) void bitgemm_fp4_rows_kernel(
     const uint64_t *__restrict__ a, int64_t m, int64_t lda, const uint64_t *__restrict__ b, int64_t ldb,
     const float *__restrict__ src_scale, Fp4RowsParams p, unsigned char *__restrict__ rows,
-    void *__restrict__ alt_rows)
+    void *__restrict__ alt_rows, int *__restrict__ escape_flag)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char fp4_rows_lds[];
     constexpr int kTile = fp4_rows_tile(P);                  // positions per tile
@@ -716,6 +716,7 @@ __global__ __launch_bounds__(kBlock, 3) void bitgemm_fp4_rows_kernel(
             __builtin_amdgcn_wave_barrier();                  // the buffer is rewritten by the next tile
         }
         if (escaped != 0u) {
+            if (escape_flag != nullptr) *escape_flag = 1;
             // the main rows are complete in memory before their carrier bytes are written again
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
             uint32_t todo = escaped;
@@ -769,7 +770,8 @@ bool fp4_rows_covers(int64_t m, int64_t k_bits, const RowLayout &layout)
 // blocks of the kernel that a compute unit holds at once (asked once per LDS size)
 template <int P, int kMaxSteps>
 static int launch_fp4_rows(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits, int64_t ldb,
-                           const float *scale, const Fp4RowsParams &p, void *c_rows, void *alt_rows, hipStream_t stream)
+                           const float *scale, const Fp4RowsParams &p, void *c_rows, void *alt_rows, hipStream_t stream,
+                           int *escape_flag)
 {
     const size_t lds_bytes = fp4_rows_lds_bytes(P, p.n_steps);
     static std::atomic<int> known[257];
@@ -787,13 +789,13 @@ static int launch_fp4_rows(const uint64_t *a_bits, int64_t m, int64_t lda, const
     int64_t blocks = (m + 127) / 128;
     if (blocks > 256 * per_cu) blocks = 256 * per_cu;
     hipLaunchKernelGGL((bitgemm_fp4_rows_kernel<P, kMaxSteps>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), lds_bytes,
-                       stream, a_bits, m, lda, b_bits, ldb, scale, p, static_cast<unsigned char *>(c_rows), alt_rows);
+                       stream, a_bits, m, lda, b_bits, ldb, scale, p, static_cast<unsigned char *>(c_rows), alt_rows, escape_flag);
     return check_launch();
 }
 
 int launch_bitgemm_fp4_rows(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits, int64_t n,
                             int64_t ldb, int64_t k_bits, const float *src_scale, void *c_rows, void *alt_rows,
-                            RowLayout layout, hipStream_t stream)
+                            RowLayout layout, hipStream_t stream, int *escape_flag)
 {
     if (!fp4_rows_covers(m, k_bits, layout)) return BIGCN_EINVAL;
     if (layout.escape && alt_rows == nullptr) return BIGCN_ENULL;
@@ -817,15 +819,15 @@ int launch_bitgemm_fp4_rows(const uint64_t *a_bits, int64_t m, int64_t lda, cons
     const bool narrow = p.n_steps <= 4;
     switch (p.positions) {
     case 64:
-        return narrow ? launch_fp4_rows<64, 4>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream)
-                      : launch_fp4_rows<64, 16>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream);
+        return narrow ? launch_fp4_rows<64, 4>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream, escape_flag)
+                      : launch_fp4_rows<64, 16>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream, escape_flag);
     case 128:
-        return narrow ? launch_fp4_rows<128, 4>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream)
-                      : launch_fp4_rows<128, 16>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream);
+        return narrow ? launch_fp4_rows<128, 4>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream, escape_flag)
+                      : launch_fp4_rows<128, 16>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream, escape_flag);
     case 256:
-        return launch_fp4_rows<256, 16>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream);
+        return launch_fp4_rows<256, 16>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream, escape_flag);
     default:
-        return launch_fp4_rows<512, 16>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream);
+        return launch_fp4_rows<512, 16>(a_bits, m, lda, b_bits, ldb, scale, p, c_rows, alt_rows, stream, escape_flag);
     }
 }
 

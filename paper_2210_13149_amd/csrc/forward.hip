@@ -15,7 +15,7 @@
 namespace bigcn {
 
 struct WorkspaceMap {
-    size_t bits_off, scale0_off, scale1_off, rows_off, self_rows_off, alt_rows_off, alt_self_rows_off, total;
+    size_t bits_off, scale0_off, scale1_off, rows_off, self_rows_off, alt_rows_off, alt_self_rows_off, flags_off, total;
     bool escape;      // some layer keeps an alternate copy (bytes or fp16) of rows that do not fit 7 bits
 };
 
@@ -91,6 +91,9 @@ static WorkspaceMap map_workspace(int64_t n, const LayerView *layers, int n_laye
     if (m.escape) off = align_up(off + static_cast<size_t>(n) * max_alt_bytes);
     m.alt_self_rows_off = off;
     if (m.escape && own_term) off = align_up(off + static_cast<size_t>(n) * max_alt_bytes);
+    // one int per layer: "some product row of this layer went to the alternate array"
+    m.flags_off = off;
+    if (m.escape) off = align_up(off + kMaxLayers * sizeof(int));
     m.total = off;
     return m;
 }
@@ -198,6 +201,11 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
     void *self_rows = own_term ? ws + map.self_rows_off : nullptr;
     void *alt_rows = map.escape ? ws + map.alt_rows_off : nullptr;
     void *alt_self_rows = (map.escape && own_term) ? ws + map.alt_self_rows_off : nullptr;
+    // Flag of layer l >= 1 with an escape layout: cleared by the aggregation of layer l - 1, set by
+    // the bit-GEMMs of layer l when a row goes to the alternate array, read by the aggregation of
+    // layer l, which skips its per-row test when it is 0.  Layer 0 has no kernel before its
+    // bit-GEMM that could clear a flag and keeps the test.
+    int *flags = map.escape ? reinterpret_cast<int *>(ws + map.flags_off) : nullptr;
 
     // layer 0 input: binarise X (or take it binarised); the stored scale is src_row_mul[i] * beta_i
     int64_t words = (layers[0].d_in + 63) / 64;
@@ -225,23 +233,24 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
     for (int l = 0; l < n_layers; ++l) {
         const LayerView &L = layers[l];
         const RowLayout layout = choose_layout(L.d_in, L.d_out);
+        int *flag = (flags != nullptr && l >= 1 && layout.escape) ? flags + l : nullptr;
         if (l == 0 && fuse0)
             rc = launch_pack_bitgemm_layout(x, n, ld_x, L.bn_shift, L.bn_mul, src_row_mul, scale[0], L.w_bits, L.d_out,
                                             L.ld_words, L.d_in, c_rows, alt_rows, layout, s);
         else if (fp4_rows_covers(n, L.d_in, layout))
             rc = launch_bitgemm_fp4_rows(in_bits, n, words, L.w_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1], c_rows,
-                                         alt_rows, layout, s);
+                                         alt_rows, layout, s, flag);
         else
             rc = launch_bitgemm_layout(in_bits, n, words, L.w_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1], c_rows,
-                                       alt_rows, layout, s);
+                                       alt_rows, layout, s, flag);
         if (rc != BIGCN_OK) return rc;
         if (own_term) {
             if (fp4_rows_covers(n, L.d_in, layout))
                 rc = launch_bitgemm_fp4_rows(in_bits, n, words, L.w_self_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1],
-                                             self_rows, alt_self_rows, layout, s);
+                                             self_rows, alt_self_rows, layout, s, flag);
             else
                 rc = launch_bitgemm_layout(in_bits, n, words, L.w_self_bits, L.d_out, L.ld_words, L.d_in, scale[l & 1],
-                                           self_rows, alt_self_rows, layout, s);
+                                           self_rows, alt_self_rows, layout, s, flag);
             if (rc != BIGCN_OK) return rc;
         }
         BIGCN_MARK();
@@ -255,6 +264,9 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
         a.c_rows = c_rows;
         a.alt_rows = alt_rows;
         a.alt_self_rows = alt_self_rows;
+        a.escape_flag = flag;
+        if (flags != nullptr && l + 1 < n_layers && choose_layout(layers[l + 1].d_in, layers[l + 1].d_out).escape)
+            a.clear_flag = flags + l + 1;
         a.layout = layout;
         a.alpha = L.alpha;
         a.d_out = L.d_out;

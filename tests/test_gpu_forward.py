@@ -170,6 +170,70 @@ def test_forward_every_row_outside_seven_bits_many_rows(B, d_in, d_hidden):
     _extreme_products(B, d_in, d_hidden, n=33000, n_edges=150000, planted=33000)
 
 
+def _hidden_escape_workload(d_hidden, d_next, n, n_edges, with_columns, seed):
+    """dims 64 -> d_hidden -> d_next -> 5 whose second weight matrix has (with_columns) or has not
+    40 columns equal to the hidden sign pattern of a node (alternately its opposite): products of
+    +-d_hidden in the second layer."""
+    from workloads import chung_lu_csr
+    from workloads.build import Workload
+    from workloads.configs import WorkloadConfig
+    rng = np.random.default_rng(seed)
+    dims = (64, d_hidden, d_next, 5)
+    rp, ci = chung_lu_csr(n, n_edges, 2.5, 2.0, seed=seed)
+    ws = [rng.uniform(-1, 1, size=(dims[i], dims[i + 1])).astype(np.float32) for i in range(3)]
+    x = rng.standard_normal((n, 64)).astype(np.float32)
+    if with_columns:
+        h1 = oracle.layer(rp, ci, oracle.gcn_norm(rp, ci), x, ws[0], None, None)["out"]
+        # the nodes whose hidden values stay farthest from zero: no sign of theirs is in doubt
+        nodes = np.argsort(-np.abs(h1[:2000]).min(axis=1))[:40]
+        for j in range(40):
+            pattern = np.where(h1[nodes[j]] >= 0, 1.0, -1.0) * (1 if j % 2 == 0 else -1)
+            ws[1][:, j] = (pattern * np.abs(ws[1][:, j]).clip(min=0.05)).astype(np.float32)
+    cfg = WorkloadConfig("hidden-extreme", "none", n, n_edges, 2.0, dims, "normal", 1.0, "first", 0)
+    return Workload(cfg, rp, ci, x, ws)
+
+
+@pytest.mark.parametrize("d_hidden,d_next,n", [(200, 256, 3000), (512, 128, 3000), (200, 256, 33000),
+                                               (512, 512, 33000)])
+def test_rows_outside_seven_bits_in_a_hidden_layer(B, d_hidden, d_next, n):
+    """Product rows of the second layer that leave the 7-bit form (one-byte and fp16 alternates).
+    From the second layer on the bit-GEMM reports such rows through a flag and the aggregation
+    only tests its rows when the flag is set: the same buffers run a model with such rows, then
+    one without, then the first again, and every result must equal the first of its kind bit for
+    bit and match the oracle."""
+    import torch
+    with_rows = _hidden_escape_workload(d_hidden, d_next, n, 5 * n, True, seed=d_hidden + n)
+    without = _hidden_escape_workload(d_hidden, d_next, n, 5 * n, False, seed=d_hidden + n)
+    assert np.array_equal(with_rows.x, without.x) and np.array_equal(with_rows.col_idx, without.col_idx)
+    _, recs = oracle.forward(with_rows.row_ptr, with_rows.col_idx, with_rows.x, with_rows.weights,
+                             bn=[None] * 3, keep_trace=True)
+    assert recs[1]["acc"].max() == d_hidden and recs[1]["acc"].min() == -d_hidden
+    _, recs = oracle.forward(without.row_ptr, without.col_idx, without.x, without.weights, bn=[None] * 3,
+                             keep_trace=True)
+    assert np.abs(recs[1]["acc"]).max() < 128                 # every product of the plain model fits 7 bits
+    del recs
+    for work in (with_rows, without):
+        stats = compare_forward_layerwise(work, [None] * 3, gpu_prefix_runner(B, work), cancellation_aware=True)
+        assert stats[1]["rows_compared"] >= 0.9 * n
+    # one set of buffers, alternating models
+    drp, dci, dx = to_device(with_rows.row_ptr, with_rows.col_idx, with_rows.x)
+    plan = B.Plan(drp, dci)
+    dinv, _ = B.bigcn_gcn_norm(drp, dci)
+    layers = {name: [B.Layer.from_weight(to_device(w)) for w in work.weights]
+              for name, work in (("with", with_rows), ("without", without))}
+    need = max(B.bigcn_forward_workspace_bytes(n, layers["with"]), B.bigcn_forward_workspace_bytes(n, layers["without"]))
+    workspace = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+    first = {}
+    for name in ("with", "without", "with", "without", "without", "with"):
+        out = B.bigcn_forward(plan, drp, dci, dinv, dx, layers[name], workspace=workspace)
+        torch.cuda.synchronize()
+        if name in first:
+            assert torch.equal(out, first[name]), name
+        else:
+            first[name] = out.clone()
+    plan.destroy()
+
+
 def _extreme_products(B, d_in, d_hidden, n=400, n_edges=3000, planted=120):
     from workloads import chung_lu_csr
     from workloads.build import Workload

@@ -167,6 +167,31 @@ def _sage_rows_that_do_not_fit(B, d_in, d_hidden, n, n_edges):
             break                                             # one pass of the oracle is enough at this size
 
 
+@pytest.mark.parametrize("d_hidden,n", [(200, 3000), (512, 33000)])
+def test_sage_rows_outside_seven_bits_in_a_hidden_layer(B, d_hidden, n):
+    """Columns of the second layer's two weight matrices equal the hidden sign pattern of a node:
+    own and neighbour product rows of the second layer leave the 7-bit form, which from the second
+    layer on is reported by the bit-GEMMs through a flag that the aggregation consults."""
+    work = small_sage_workload(n, 5 * n, (64, d_hidden, 256, 5), seed=300 + d_hidden)
+    coeff = oracle.mean_norm(work.row_ptr, work.col_idx)
+    w_self0, w_nbr0 = work.weights[0]
+    h1 = oracle.sage_layer(work.row_ptr, work.col_idx, coeff, work.x, w_self0, w_nbr0, None, None)["out"]
+    nodes = np.argsort(-np.abs(h1[:2000]).min(axis=1))[:40]
+    w_self1, w_nbr1 = (w.copy() for w in work.weights[1])
+    for j in range(40):
+        pattern = np.where(h1[nodes[j]] >= 0, 1.0, -1.0) * (1 if j % 2 == 0 else -1)
+        target = w_self1 if j % 4 < 2 else w_nbr1
+        target[:, j] = (pattern * np.abs(target[:, j]).clip(min=0.05)).astype(np.float32)
+    work.weights[1] = (w_self1, w_nbr1)
+    sign, _ = oracle.binarize_rows(h1)
+    for w in (w_self1, w_nbr1):
+        bt, _ = oracle.binarize_weight(w)
+        acc = oracle.sign_matmul(sign, bt)
+        assert acc.max() == d_hidden and acc.min() == -d_hidden
+    stats = compare_forward_layerwise(work, [None] * 3, sage_prefix_runner(B, work), cancellation_aware=True)
+    assert stats[1]["rows_compared"] >= 0.9 * n
+
+
 def test_sage_isolated_node_output_is_its_own_term_and_runs_are_identical(B):
     import torch
     work = small_sage_workload(2000, 1200, (96, 128, 10), seed=77)

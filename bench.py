@@ -29,7 +29,7 @@ VALU_BINARY_MAC_PEAK = 256 * 4 * 16 * 2.4e9 * 32 / 2   # 2 VALU instructions per
 
 # HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE, scaled by a copy kernel of known size); see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"c5": 3.25e10}    # profiles/spmm_fused_c5.md (layer 1, the slowest launch)
+MEASURED_TRAFFIC_BYTES = {"c5": 3.23e10}    # profiles/spmm_fused_c5.md (layer 1, the slowest launch)
 
 
 def log(*a):

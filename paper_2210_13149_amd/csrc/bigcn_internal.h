@@ -100,15 +100,17 @@ RowLayout choose_layout(int64_t d_in, int64_t d_out);
 // ---- internal launchers (defined in the .hip files) ------------------------------------
 // pack: as bigcn_pack, plus an optional per-row factor folded into the scale.
 // fold_last_sign: the stored scale additionally carries the sign of the row's last column.
+// clear_flag (DEVICE, nullable): an int that the launch sets to 0 (see FusedSpmmArgs::escape_flag).
 int launch_pack(const float *x, int64_t rows, int64_t cols, int64_t row_stride,
                 int64_t col_stride, const float *shift, const float *mul, const float *row_mul,
                 int fold_last_sign, uint64_t *bits, int64_t ld_words, float *scale,
-                hipStream_t stream);
+                hipStream_t stream, int *clear_flag = nullptr);
 
 // Stored source scale of rows that are already packed: beta[i] * row_mul[i] (row_mul nullable),
 // negated when fold_last_sign is set and the row's last bit (column cols-1) is 0.
 int launch_source_scale(const float *beta, const float *row_mul, const uint64_t *bits, int64_t ld_words,
-                        int64_t cols, int fold_last_sign, float *scale, int64_t rows, hipStream_t stream);
+                        int64_t cols, int fold_last_sign, float *scale, int64_t rows, hipStream_t stream,
+                        int *clear_flag = nullptr);
 
 // bit-GEMM writing the integer products in a RowLayout (fused forward).
 // src_scale (m floats) is copied into the rows when the layout embeds the scale.
@@ -189,8 +191,9 @@ struct FusedSpmmArgs {
     const float *self_alpha;    // d_out
     const uint64_t *self_w_bits;// packed second weight matrix (for its last-bit term), stride w_ld_words
     // escape layouts: *escape_flag == 0 (DEVICE, nullable) promises that no row of c_rows / self_rows
-    // went to the alternate arrays, and the kernel then runs without the per-row test.  clear_flag
-    // (DEVICE, nullable) is set to 0 by this launch: the flag of the layer that follows.
+    // went to the alternate arrays; the aggregation is then launched twice, gated on the flag: the
+    // kernel without the per-row test and the one with it.  clear_flag (DEVICE, nullable) is set to
+    // 0 by this launch: the flag of the layer that follows.
     const int *escape_flag;
     int *clear_flag;
 };

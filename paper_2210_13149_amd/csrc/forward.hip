@@ -201,10 +201,12 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
     void *self_rows = own_term ? ws + map.self_rows_off : nullptr;
     void *alt_rows = map.escape ? ws + map.alt_rows_off : nullptr;
     void *alt_self_rows = (map.escape && own_term) ? ws + map.alt_self_rows_off : nullptr;
-    // Flag of layer l >= 1 with an escape layout: cleared by the aggregation of layer l - 1, set by
-    // the bit-GEMMs of layer l when a row goes to the alternate array, read by the aggregation of
-    // layer l, which skips its per-row test when it is 0.  Layer 0 has no kernel before its
-    // bit-GEMM that could clear a flag and keeps the test.
+    // Flag of a layer whose layout has one-byte alternates: cleared by the kernel that runs before
+    // the layer's bit-GEMMs (the aggregation of the layer before; for layer 0 the binarisation of X
+    // or the source-scale kernel), set by the bit-GEMMs when a row goes to the alternate array, and
+    // the gate of the layer's two aggregation launches (without the per-row test when it is 0, with
+    // it otherwise).  When the binarisation is folded into the first bit-GEMM no kernel runs ahead
+    // of it, and layer 0 keeps the single launch with the test.
     int *flags = map.escape ? reinterpret_cast<int *>(ws + map.flags_off) : nullptr;
 
     // layer 0 input: binarise X (or take it binarised); the stored scale is src_row_mul[i] * beta_i
@@ -222,10 +224,11 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
     } else if (packed) {
         in_bits = in.bits;
         words = in.ld_words;
-        rc = launch_source_scale(in.beta, src_row_mul, in.bits, in.ld_words, layers[0].d_in, fold0, scale[0], n, s);
+        rc = launch_source_scale(in.beta, src_row_mul, in.bits, in.ld_words, layers[0].d_in, fold0, scale[0], n, s,
+                                 (layout0.escape && layout0.alt_kind == kI8) ? flags : nullptr);
     } else {
         rc = launch_pack(x, n, layers[0].d_in, ld_x, 1, layers[0].bn_shift, layers[0].bn_mul, src_row_mul, fold0,
-                         bits, words, scale[0], s);
+                         bits, words, scale[0], s, (layout0.escape && layout0.alt_kind == kI8) ? flags : nullptr);
     }
     if (rc != BIGCN_OK) return rc;
     BIGCN_MARK();
@@ -233,7 +236,8 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
     for (int l = 0; l < n_layers; ++l) {
         const LayerView &L = layers[l];
         const RowLayout layout = choose_layout(L.d_in, L.d_out);
-        int *flag = (flags != nullptr && l >= 1 && layout.escape) ? flags + l : nullptr;
+        // (with fp16 alternates the kernel with the test measured no slower than the plain one: no flag)
+        int *flag = (flags != nullptr && layout.escape && layout.alt_kind == kI8 && !(l == 0 && fuse0)) ? flags + l : nullptr;
         if (l == 0 && fuse0)
             rc = launch_pack_bitgemm_layout(x, n, ld_x, L.bn_shift, L.bn_mul, src_row_mul, scale[0], L.w_bits, L.d_out,
                                             L.ld_words, L.d_in, c_rows, alt_rows, layout, s);
@@ -265,8 +269,10 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
         a.alt_rows = alt_rows;
         a.alt_self_rows = alt_self_rows;
         a.escape_flag = flag;
-        if (flags != nullptr && l + 1 < n_layers && choose_layout(layers[l + 1].d_in, layers[l + 1].d_out).escape)
-            a.clear_flag = flags + l + 1;
+        if (flags != nullptr && l + 1 < n_layers) {
+            const RowLayout next = choose_layout(layers[l + 1].d_in, layers[l + 1].d_out);
+            if (next.escape && next.alt_kind == kI8) a.clear_flag = flags + l + 1;
+        }
         a.layout = layout;
         a.alpha = L.alpha;
         a.d_out = L.d_out;

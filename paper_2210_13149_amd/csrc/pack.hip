@@ -16,8 +16,9 @@ __global__ __launch_bounds__(kBlock) void pack_short_kernel(
     const float *__restrict__ x, int64_t rows, int cols, int64_t row_stride,
     const float *__restrict__ shift, const float *__restrict__ mul,
     const float *__restrict__ row_mul, int fold_last_sign, uint64_t *__restrict__ bits,
-    int64_t ld_words, float *__restrict__ scale)
+    int64_t ld_words, float *__restrict__ scale, int *__restrict__ clear_flag)
 {
+    if (clear_flag != nullptr && blockIdx.x == 0 && threadIdx.x == 0) *clear_flag = 0;
     constexpr int RB = 8 / NW;
     const int lane = lane_id();
     const int64_t wave = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block();
@@ -74,8 +75,9 @@ __global__ __launch_bounds__(kBlock) void pack_generic_kernel(
     const float *__restrict__ x, int64_t rows, int64_t cols, int64_t row_stride,
     int64_t col_stride, const float *__restrict__ shift, const float *__restrict__ mul,
     const float *__restrict__ row_mul, int fold_last_sign, uint64_t *__restrict__ bits,
-    int64_t ld_words, float *__restrict__ scale)
+    int64_t ld_words, float *__restrict__ scale, int *__restrict__ clear_flag)
 {
+    if (clear_flag != nullptr && blockIdx.x == 0 && threadIdx.x == 0) *clear_flag = 0;
     constexpr int U = 4;
     const int lane = lane_id();
     const int64_t wave = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block();
@@ -131,8 +133,9 @@ __global__ __launch_bounds__(kBlock) void source_scale_kernel(const float *__res
                                                               const uint64_t *__restrict__ bits,
                                                               int64_t ld_words, int64_t cols,
                                                               int fold_last_sign, float *__restrict__ scale,
-                                                              int64_t rows)
+                                                              int64_t rows, int *__restrict__ clear_flag)
 {
+    if (clear_flag != nullptr && blockIdx.x == 0 && threadIdx.x == 0) *clear_flag = 0;
     const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
     if (i >= rows) return;
     float s = beta[i];
@@ -142,11 +145,12 @@ __global__ __launch_bounds__(kBlock) void source_scale_kernel(const float *__res
 }
 
 int launch_source_scale(const float *beta, const float *row_mul, const uint64_t *bits, int64_t ld_words,
-                        int64_t cols, int fold_last_sign, float *scale, int64_t rows, hipStream_t stream)
+                        int64_t cols, int fold_last_sign, float *scale, int64_t rows, hipStream_t stream,
+                        int *clear_flag)
 {
     if (rows == 0) return BIGCN_OK;
     hipLaunchKernelGGL(source_scale_kernel, dim3(static_cast<unsigned>((rows + kBlock - 1) / kBlock)), dim3(kBlock),
-                       0, stream, beta, row_mul, bits, ld_words, cols, fold_last_sign, scale, rows);
+                       0, stream, beta, row_mul, bits, ld_words, cols, fold_last_sign, scale, rows, clear_flag);
     return check_launch();
 }
 
@@ -161,7 +165,7 @@ static int grid_for_waves(int64_t waves_needed)
 int launch_pack(const float *x, int64_t rows, int64_t cols, int64_t row_stride,
                 int64_t col_stride, const float *shift, const float *mul, const float *row_mul,
                 int fold_last_sign, uint64_t *bits, int64_t ld_words, float *scale,
-                hipStream_t stream)
+                hipStream_t stream, int *clear_flag)
 {
     if (rows == 0) return BIGCN_OK;
     const int64_t n_words = (cols + 63) / 64;
@@ -170,7 +174,7 @@ int launch_pack(const float *x, int64_t rows, int64_t cols, int64_t row_stride,
 #define BIGCN_PACK_SHORT(NW)                                                                  \
     hipLaunchKernelGGL(pack_short_kernel<NW>, dim3(grid_for_waves((rows + 8 / NW - 1) / (8 / NW))), \
                        dim3(kBlock), 0, stream, x, rows, icols, row_stride, shift, mul, row_mul, \
-                       fold_last_sign, bits, ld_words, scale)
+                       fold_last_sign, bits, ld_words, scale, clear_flag)
         switch (n_words) {
         case 1: BIGCN_PACK_SHORT(1); break;
         case 2: BIGCN_PACK_SHORT(2); break;
@@ -181,7 +185,7 @@ int launch_pack(const float *x, int64_t rows, int64_t cols, int64_t row_stride,
     } else {
         hipLaunchKernelGGL(pack_generic_kernel, dim3(grid_for_waves(rows)), dim3(kBlock), 0, stream,
                            x, rows, cols, row_stride, col_stride, shift, mul, row_mul, fold_last_sign,
-                           bits, ld_words, scale);
+                           bits, ld_words, scale, clear_flag);
     }
     return check_launch();
 }

@@ -603,19 +603,28 @@ constexpr int spmm_min_waves()
     return (G == kWave && escape_weights(WM)) ? 7 : 6;
 }
 
-// The body of the kernel for one way of finding the neighbours' weights (WM).  partial and parked:
-// the workgroup's LDS (partial sums of a shared long row; the epilogue's per-lane constants).
+// gate_flag (nullable): the launch does nothing unless (*gate_flag != 0) == (run_if_set != 0).
+// Escape layouts with one-byte alternates (rows that may carry a NaN scale and live in the
+// alternate array) are launched twice on the flag that the bit-GEMM sets when a row went to the
+// alternate array: once as the plain top-bits kernel, which runs when no row did, once with the
+// per-row test, which runs otherwise; one of the two returns at once (1.3 % of a forward on the
+// largest workload, where no row ever escapes).  clear_flag: the flag of the layer that follows,
+// cleared here, i.e. after the kernels that read it in the previous call and before the bit-GEMM
+// that may set it in this one.
 template <typename T, int G, int V, int WM, class Epilogue>
-__device__ __forceinline__ void spmm_rows(
+__global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) void spmm_kernel(
     const int32_t *__restrict__ row_order, int64_t n, int64_t n_block_rows,
     const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
     const float *__restrict__ weights, const char *__restrict__ rows, const char *__restrict__ alt_rows,
-    uint32_t row_bytes, int valid_positions, int rows_per_wave, const Epilogue &epi,
-    float (*partial)[V + 2][kWave], float *parked)
+    uint32_t row_bytes, int valid_positions, int rows_per_wave, Epilogue epi,
+    const int *__restrict__ gate_flag, int run_if_set, int *__restrict__ clear_flag)
 {
+    if (clear_flag != nullptr && blockIdx.x == 0 && threadIdx.x == 0) *clear_flag = 0;
+    if (gate_flag != nullptr && (*gate_flag != 0) != (run_if_set != 0)) return;     // uniform over the launch
     constexpr int kAltElem = WM == kWeightTopBitsEscapeF16 ? 2 : static_cast<int>(sizeof(T));
     const uint32_t alt_row_bytes = row_bytes / sizeof(T) * kAltElem;
     constexpr bool kAllActive = fused_weights(WM);     // stored rows of the fused path fill G * V positions
+    __shared__ float partial[kWavesPerBlock - 1][V + 2][kWave];
     const int lane = lane_id();
     const int wave = wave_in_block();
     const int g = lane & (G - 1);
@@ -624,6 +633,7 @@ __device__ __forceinline__ void spmm_rows(
 
     using LaneConsts = typename Epilogue::template Lane<G, V>;
     using Parked = ParkedLane<LaneConsts>;
+    __shared__ float parked[Parked::kFloats > 0 ? Parked::kFloats * kWave : 1];
     {
         LaneConsts ctx;
         epi.template init<G, V>(lane, ctx);
@@ -697,40 +707,12 @@ __device__ __forceinline__ void spmm_rows(
     }
 }
 
-// Escape layouts (rows that may carry a NaN scale and live in the alternate array): when the
-// bit-GEMM that wrote the rows left *escape_flag at 0, no row did, and the workgroup runs the body
-// without the per-row test (1.3 % of a forward on the largest workload, where no row ever
-// escapes).  clear_flag: the flag of the layer that follows, cleared here, i.e. after the kernels
-// that read it in the previous call and before the bit-GEMM that may set it in this one.
-template <typename T, int G, int V, int WM, class Epilogue>
-__global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) void spmm_kernel(
-    const int32_t *__restrict__ row_order, int64_t n, int64_t n_block_rows,
-    const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
-    const float *__restrict__ weights, const char *__restrict__ rows, const char *__restrict__ alt_rows,
-    uint32_t row_bytes, int valid_positions, int rows_per_wave, Epilogue epi,
-    const int *__restrict__ escape_flag, int *__restrict__ clear_flag)
-{
-    using Parked = ParkedLane<typename Epilogue::template Lane<G, V>>;
-    __shared__ float partial[kWavesPerBlock - 1][V + 2][kWave];
-    __shared__ float parked[Parked::kFloats > 0 ? Parked::kFloats * kWave : 1];
-    if (clear_flag != nullptr && blockIdx.x == 0 && threadIdx.x == 0) *clear_flag = 0;
-    if constexpr (escape_weights(WM) && sizeof(T) == 1) {
-        if (escape_flag != nullptr && *escape_flag == 0) {          // uniform over the launch
-            spmm_rows<T, G, V, kWeightTopBits, Epilogue>(row_order, n, n_block_rows, row_ptr, col_idx, weights, rows,
-                                                        alt_rows, row_bytes, valid_positions, rows_per_wave, epi,
-                                                        partial, parked);
-            return;
-        }
-    }
-    spmm_rows<T, G, V, WM, Epilogue>(row_order, n, n_block_rows, row_ptr, col_idx, weights, rows, alt_rows, row_bytes,
-                                     valid_positions, rows_per_wave, epi, partial, parked);
-}
-
 template <typename T, int G, int V, int WM, class Epilogue>
 static int launch_spmm_one(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
                            const float *weights, const void *rows, int64_t row_bytes,
                            int valid_positions, const Epilogue &epi, hipStream_t stream,
-                           const void *alt_rows, const int *escape_flag = nullptr, int *clear_flag = nullptr)
+                           const void *alt_rows, const int *gate_flag = nullptr, int run_if_set = 0,
+                           int *clear_flag = nullptr)
 {
     if (row_bytes <= 0 || row_bytes > 0x7fffffff) return BIGCN_EINVAL;
     if (escape_weights(WM) && (alt_rows == nullptr || weights == nullptr)) return BIGCN_ENULL;
@@ -743,7 +725,7 @@ static int launch_spmm_one(const bigcn_plan *plan, const int64_t *row_ptr, const
     hipLaunchKernelGGL((spmm_kernel<T, G, V, WM, Epilogue>), dim3(static_cast<unsigned>(blocks)),
                        dim3(kBlock), 0, stream, plan->row_order, plan->n, plan->n_block_rows, row_ptr,
                        col_idx, weights, static_cast<const char *>(rows), static_cast<const char *>(alt_rows),
-                       static_cast<uint32_t>(row_bytes), valid_positions, rows_per_wave, epi, escape_flag, clear_flag);
+                       static_cast<uint32_t>(row_bytes), valid_positions, rows_per_wave, epi, gate_flag, run_if_set, clear_flag);
     return check_launch();
 }
 
@@ -751,13 +733,13 @@ template <typename T, int V, int WM, class Epilogue>
 static int launch_spmm_groups(int groups, const bigcn_plan *plan, const int64_t *row_ptr,
                               const int32_t *col_idx, const float *weights, const void *rows,
                               int64_t row_bytes, int valid_positions, const Epilogue &epi,
-                              hipStream_t stream, const void *alt_rows = nullptr, const int *escape_flag = nullptr,
-                              int *clear_flag = nullptr)
+                              hipStream_t stream, const void *alt_rows = nullptr, const int *gate_flag = nullptr,
+                              int run_if_set = 0, int *clear_flag = nullptr)
 {
 #define BIGCN_SPMM_CASE(GG)                                                                          \
     case GG:                                                                                         \
         return launch_spmm_one<T, GG, V, WM>(plan, row_ptr, col_idx, weights, rows, row_bytes,      \
-                                             valid_positions, epi, stream, alt_rows, escape_flag, clear_flag)
+                                             valid_positions, epi, stream, alt_rows, gate_flag, run_if_set, clear_flag)
     switch (groups) {
         BIGCN_SPMM_CASE(2);
         BIGCN_SPMM_CASE(4);
@@ -882,29 +864,36 @@ static int launch_fused_spmm_t(const FusedSpmmArgs &a, hipStream_t stream)
     const int64_t rb = l.row_bytes();
 #define BIGCN_FUSED(TT, VV)                                                                             \
     return launch_spmm_groups<TT, VV, kWeightGather>(l.groups, a.plan, a.row_ptr, a.col_idx, a.src_scale, \
-                                                     a.c_rows, rb, valid, epi, stream, nullptr, nullptr,  \
+                                                     a.c_rows, rb, valid, epi, stream, nullptr, nullptr, 0, \
                                                      a.clear_flag)
 #define BIGCN_FUSED_EMBEDDED(TT, VV)                                                                    \
     return launch_spmm_groups<TT, VV, kWeightEmbedded>(l.groups, a.plan, a.row_ptr, a.col_idx, nullptr, \
-                                                       a.c_rows, rb, valid, epi, stream, nullptr, nullptr, \
+                                                       a.c_rows, rb, valid, epi, stream, nullptr, nullptr, 0, \
                                                        a.clear_flag)
     if (l.kind == kI8 && l.embed_scale == kScaleInTopBits && l.escape) {
         if (l.groups < 16) return BIGCN_EINVAL;
         if (kSelfTerm && a.alt_self_rows == nullptr) return BIGCN_ENULL;
+        if (l.alt_kind != kI8 && l.alt_kind != kF16) return BIGCN_EINVAL;
+        if (a.escape_flag != nullptr) {
+            // no row escaped: the plain top-bits kernel runs and the next launch returns at once
+            const int rc = launch_spmm_groups<int8_t, 8, kWeightTopBits>(l.groups, a.plan, a.row_ptr, a.col_idx, nullptr,
+                                                                         a.c_rows, rb, valid, epi, stream, nullptr,
+                                                                         a.escape_flag, 0, a.clear_flag);
+            if (rc != BIGCN_OK) return rc;
+        }
         if (l.alt_kind == kF16)
             return launch_spmm_groups<int8_t, 8, kWeightTopBitsEscapeF16>(l.groups, a.plan, a.row_ptr, a.col_idx,
                                                                           a.src_scale, a.c_rows, rb, valid, epi,
-                                                                          stream, a.alt_rows, a.escape_flag,
+                                                                          stream, a.alt_rows, a.escape_flag, 1,
                                                                           a.clear_flag);
-        if (l.alt_kind != kI8) return BIGCN_EINVAL;
         return launch_spmm_groups<int8_t, 8, kWeightTopBitsEscape>(l.groups, a.plan, a.row_ptr, a.col_idx,
                                                                    a.src_scale, a.c_rows, rb, valid, epi, stream,
-                                                                   a.alt_rows, a.escape_flag, a.clear_flag);
+                                                                   a.alt_rows, a.escape_flag, 1, a.clear_flag);
     }
     if (l.kind == kI8 && l.embed_scale == kScaleInTopBits) {
         if (l.groups < 16) return BIGCN_EINVAL;
         return launch_spmm_groups<int8_t, 8, kWeightTopBits>(l.groups, a.plan, a.row_ptr, a.col_idx, nullptr,
-                                                             a.c_rows, rb, valid, epi, stream, nullptr, nullptr,
+                                                             a.c_rows, rb, valid, epi, stream, nullptr, nullptr, 0,
                                                              a.clear_flag);
     }
     if (l.kind == kI8 && l.embed_scale == kScaleInTail) {
@@ -913,7 +902,7 @@ static int launch_fused_spmm_t(const FusedSpmmArgs &a, hipStream_t stream)
     if (l.kind == kI8 && l.embed_scale == kScaleInLastBytes) {
         if (l.groups != 8 || l.vec != 8) return BIGCN_EINVAL;
         return launch_spmm_one<int8_t, 8, 8, kWeightLastBytes>(a.plan, a.row_ptr, a.col_idx, nullptr, a.c_rows, rb, valid,
-                                                             epi, stream, nullptr, nullptr, a.clear_flag);
+                                                             epi, stream, nullptr, nullptr, 0, a.clear_flag);
     }
     if (l.kind == kI8) {
         BIGCN_FUSED(int8_t, 8);

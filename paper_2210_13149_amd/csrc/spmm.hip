@@ -718,7 +718,10 @@ static int launch_spmm_one(const bigcn_plan *plan, const int64_t *row_ptr, const
     if (escape_weights(WM) && (alt_rows == nullptr || weights == nullptr)) return BIGCN_ENULL;
     if (fused_weights(WM) && valid_positions != G * V) return BIGCN_EINVAL;
     const int64_t wave_rows = plan->n - plan->n_block_rows;
-    const int rows_per_wave = rows_per_wave_for(wave_rows);
+    int rows_per_wave = rows_per_wave_for(wave_rows);
+    // the launch that only runs when a row escaped (almost never): a quarter of the workgroups, so
+    // that returning at once costs a quarter
+    if (gate_flag != nullptr && run_if_set != 0 && rows_per_wave == kMaxRowsPerWave) rows_per_wave *= 4;
     const int64_t per_block = kWavesPerBlock * rows_per_wave;
     const int64_t blocks = plan->n_block_rows + (wave_rows + per_block - 1) / per_block;
     if (blocks == 0) return BIGCN_OK;

@@ -209,6 +209,12 @@ struct GatSegment<float> {
     }
 };
 
+// Floats per record {beta, t[0..H-1]}, padded to whole 16-byte vectors: a neighbour's record is
+// read with aligned vector loads that never straddle a cache line (one load for up to three
+// heads, where three scalar loads asked the texture path for the same line three times).
+template <int H>
+constexpr int gat_record_floats() { return (H + 1 + 3) / 4 * 4; }
+
 // select x[h] for a head index known only at run time (H is small)
 template <int H>
 __device__ __forceinline__ float pick(const float (&x)[H], int h)
@@ -226,7 +232,7 @@ __device__ __forceinline__ float pick(const float (&x)[H], int h)
 // time, lane g of a node's G lanes holding columns 8 g .. 8 g + 7 (all in one head).  When a head
 // spans a power-of-two number of lanes its sums are a butterfly inside that lane group;
 // otherwise one masked sum over the wavefront per head (one node at a time).
-// record[i] = {beta_i, t_i[0..H-1]}.
+// record[i] = {beta_i, t_i[0..H-1]} at a stride of gat_record_floats<H>() floats.
 template <typename T, int G, int H>
 __global__ __launch_bounds__(kBlock) void gat_scores_kernel(const char *__restrict__ rows, uint32_t row_bytes, int64_t n,
                                                             int d_out, int d_head, float mul, float bias,
@@ -297,8 +303,8 @@ __global__ __launch_bounds__(kBlock) void gat_scores_kernel(const char *__restri
             }
             if (mine && g == my_head * lanes_per_head) {            // first lane of the head's group
                 s[i * H + my_head] = b * fmaf(mul, ps, const_s[0]);
-                record[i * (H + 1) + 1 + my_head] = b * fmaf(mul, pt, const_t[0]);
-                if (g == 0) record[i * (H + 1)] = b;
+                record[i * gat_record_floats<H>() + 1 + my_head] = b * fmaf(mul, pt, const_t[0]);
+                if (g == 0) record[i * gat_record_floats<H>()] = b;
             }
         } else {
             const float b0 = __shfl(b, 0, kWave);
@@ -308,10 +314,10 @@ __global__ __launch_bounds__(kBlock) void gat_scores_kernel(const char *__restri
                 const float tt = wave_sum(mine && my_head == h ? pt : 0.0f);
                 if (lane == 0) {
                     s[i * H + h] = b0 * fmaf(mul, ss, const_s[h]);
-                    record[i * (H + 1) + 1 + h] = b0 * fmaf(mul, tt, const_t[h]);
+                    record[i * gat_record_floats<H>() + 1 + h] = b0 * fmaf(mul, tt, const_t[h]);
                 }
             }
-            if (lane == 0) record[i * (H + 1)] = b0;
+            if (lane == 0) record[i * gat_record_floats<H>()] = b0;
         }
     }
 }
@@ -348,7 +354,17 @@ __device__ __forceinline__ void gat_accumulate(const int32_t *__restrict__ col_i
         for (int h = 0; h < H; ++h) e[h] = -INFINITY;
         if (lane < cnt) {
             k = col_idx[pb + lane];
-            const float *rec = record + static_cast<int64_t>(k) * (H + 1);
+            constexpr int kVecs = gat_record_floats<H>() / 4;
+            const float4 *src = reinterpret_cast<const float4 *>(record) + static_cast<int64_t>(k) * kVecs;
+            float rec[4 * kVecs];
+#pragma unroll
+            for (int q = 0; q < kVecs; ++q) {
+                const float4 part = src[q];
+                rec[4 * q] = part.x;
+                rec[4 * q + 1] = part.y;
+                rec[4 * q + 2] = part.z;
+                rec[4 * q + 3] = part.w;
+            }
             bk = rec[0];
 #pragma unroll
             for (int h = 0; h < H; ++h) e[h] = leaky(si[h] + rec[1 + h], slope);
@@ -570,7 +586,8 @@ static GatMap map_gat(int64_t n, int64_t d_in, int64_t d_out, int heads)
     m.beta_off = off; off = up(off + static_cast<size_t>(n) * 4);
     m.z_off = off;    off = up(off + static_cast<size_t>(n) * (m.compact ? m.row_bytes : d_out * 4));
     m.s_off = off;    off = up(off + static_cast<size_t>(n) * heads * 4);
-    m.t_off = off;    off = up(off + static_cast<size_t>(n) * (heads + (m.compact ? 1 : 0)) * 4);
+    // compact path: records of (heads + 1) floats padded to whole 16-byte vectors
+    m.t_off = off;    off = up(off + static_cast<size_t>(n) * (m.compact ? (heads + 1 + 3) / 4 * 4 : heads) * 4);
     m.total = off;
     return m;
 }

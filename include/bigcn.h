@@ -56,6 +56,8 @@ int bigcn_version(void);
 #define BIGCN_MAX_GEMM_N 4194304
 #define BIGCN_MAX_FORWARD_D_OUT 512
 #define BIGCN_MAX_LAYERS 64
+/* Size of the per-GPU workspace that bigcn_forward_static uses instead of a caller buffer. */
+#define BIGCN_STATIC_WORKSPACE_BYTES (32u << 20)
 
 /*
  * Kernel 1 - binarise and pack the rows of a strided fp32 matrix
@@ -213,6 +215,30 @@ int bigcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t 
                   const float *dinv_sqrt, int64_t n, const float *x, int64_t ld_x,
                   const bigcn_layer *layers, int n_layers, float *logits, int64_t ld_logits,
                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * bigcn_forward for callers that cannot allocate device memory or pass a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments,
+ * kernels and results as bigcn_forward, with the workspace taken from a device array of
+ * BIGCN_STATIC_WORKSPACE_BYTES that is part of the library's code object (one copy per GPU
+ * that loads the library, held until the process ends).  The call allocates and frees nothing
+ * and clears nothing with a memset: every workspace region is written by a kernel of the call
+ * before a kernel of the same call reads it, so stale contents of an earlier call are harmless.
+ *
+ *  - Problems whose bigcn_forward_workspace_bytes(n, layers, n_layers) exceeds
+ *    BIGCN_STATIC_WORKSPACE_BYTES are rejected with BIGCN_ESHAPE before anything is launched
+ *    (the three citation-network workloads need 0.9, 2.4 and 9.0 MB).
+ *  - All calls on one GPU share that GPU's array: two calls whose kernels may overlap (different
+ *    streams, or graph replays that run concurrently) race.  Calls on one stream are ordered.
+ *  - The first call on each device looks the array's address up (hipGetSymbolAddress); make it
+ *    outside stream capture.  The plan still comes from bigcn_plan_create, at set-up.
+ * Errors: as bigcn_forward without EWORKSPACE; ESHAPE also for the size limit above; EHIP if the
+ * address lookup fails.
+ */
+int bigcn_forward_static(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                         const float *dinv_sqrt, int64_t n, const float *x, int64_t ld_x,
+                         const bigcn_layer *layers, int n_layers, float *logits, int64_t ld_logits,
+                         void *stream);
 
 /*
  * The same forward from an input that is already binarised (Sec. 5.2: the loaded features can

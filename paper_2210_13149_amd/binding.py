@@ -39,7 +39,7 @@ EXPORTS = (
     "bigcn_sage_forward_profiled", "bigcn_forward_packed", "bigcn_column_stats_workspace_bytes",
     "bigcn_column_stats", "bigcn_predict", "bigcn_layer_backward_workspace_bytes",
     "bigcn_layer_backward", "bigcn_entropy_workspace_bytes", "bigcn_entropy",
-    "bigcn_gat_layer_workspace_bytes", "bigcn_gat_layer",
+    "bigcn_gat_layer_workspace_bytes", "bigcn_gat_layer", "bigcn_forward_static",
 )
 
 
@@ -111,6 +111,9 @@ def lib() -> ctypes.CDLL:
         L.bigcn_forward.restype = i32
         L.bigcn_forward.argtypes = [vp, vp, vp, vp, i64, vp, i64, ctypes.POINTER(LayerDesc), i32, vp,
                                     i64, vp, ctypes.c_size_t, vp]
+        L.bigcn_forward_static.restype = i32
+        L.bigcn_forward_static.argtypes = [vp, vp, vp, vp, i64, vp, i64, ctypes.POINTER(LayerDesc), i32, vp,
+                                           i64, vp]
         L.bigcn_profile_create.restype = i32
         L.bigcn_profile_create.argtypes = [i32, i32, ctypes.POINTER(vp)]
         L.bigcn_profile_destroy.restype = None
@@ -410,6 +413,23 @@ def bigcn_forward(plan: Plan, row_ptr: torch.Tensor, col_idx: torch.Tensor, dinv
         _check(lib().bigcn_forward(*args), "bigcn_forward")
     else:
         _check(lib().bigcn_forward_profiled(*args, profile.handle), "bigcn_forward_profiled")
+    return logits
+
+
+STATIC_WORKSPACE_BYTES = 32 << 20   # BIGCN_STATIC_WORKSPACE_BYTES of the header
+
+
+def bigcn_forward_static(plan: Plan, row_ptr: torch.Tensor, col_idx: torch.Tensor, dinv_sqrt: torch.Tensor,
+                         x: torch.Tensor, layers: Sequence[Layer], logits: torch.Tensor) -> torch.Tensor:
+    """``bigcn_forward`` with the workspace in the library's own per-GPU array: the call allocates
+    nothing, so the caller provides ``logits``."""
+    _dev(x, torch.float32, "x")
+    _dev(logits, torch.float32, "logits")
+    if x.dim() != 2 or (x.shape[1] > 1 and x.stride(1) != 1):
+        raise ValueError("x must be a row-major matrix")
+    _check(lib().bigcn_forward_static(plan.handle, _ptr(row_ptr), _ptr(col_idx), _ptr(dinv_sqrt), x.shape[0],
+                                      _ptr(x), x.stride(0), _descs(layers), len(layers), _ptr(logits),
+                                      logits.stride(0), _stream()), "bigcn_forward_static")
     return logits
 
 

@@ -8,6 +8,7 @@
 // The Bi-GraphSAGE driver (Sec. 4.4.2) is the same sequence with two bit-GEMMs per layer (one
 // product array per weight matrix) and an aggregation that adds the node's own row.
 #include <algorithm>
+#include <mutex>
 #include <new>
 
 #include "bigcn_internal.h"
@@ -99,6 +100,34 @@ static WorkspaceMap map_workspace(int64_t n, const LayerView *layers, int n_laye
 }
 
 }  // namespace bigcn
+
+// Workspace of bigcn_forward_static, for callers that cannot allocate: one copy per GPU that
+// loads the library, held until the process ends.  The name is only a host-side handle of the
+// symbol; host code uses the device address looked up once per device (static_workspace()).
+static __device__ __align__(256) unsigned char scratch[BIGCN_STATIC_WORKSPACE_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[kMaxDevices];   // device address of `scratch` on GPU d, nullptr until first use
+
+// Address of the current device's copy of `scratch`.
+int static_workspace(void **out)
+{
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return BIGCN_EHIP;
+    std::lock_guard<std::mutex> guard(scratch_mutex);
+    if (scratch_ptr[device] == nullptr) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return BIGCN_EHIP;
+        scratch_ptr[device] = p;
+    }
+    *out = scratch_ptr[device];
+    return BIGCN_OK;
+}
+
+}  // namespace
 
 // Per-launch timing of forward passes: (1 + 2 L) launches per call bracketed by (2 + 2 L)
 // events, for up to max_calls calls between two reads.
@@ -337,6 +366,23 @@ extern "C" int bigcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, con
 {
     return gcn_forward(plan, row_ptr, col_idx, dinv_sqrt, n, x, ld_x, layers, n_layers, logits,
                        ld_logits, workspace, workspace_bytes, stream, nullptr);
+}
+
+extern "C" int bigcn_forward_static(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
+                                    const float *dinv_sqrt, int64_t n, const float *x, int64_t ld_x,
+                                    const bigcn_layer *layers, int n_layers, float *logits,
+                                    int64_t ld_logits, void *stream)
+{
+    LayerView view[kMaxLayers];
+    int status = view_gcn(layers, n_layers, view);
+    if (status != BIGCN_OK) return status;
+    if (!layers_ok(n, view, n_layers, false, &status)) return status;
+    if (map_workspace(n, view, n_layers, false).total > BIGCN_STATIC_WORKSPACE_BYTES) return BIGCN_ESHAPE;
+    void *workspace = nullptr;
+    status = static_workspace(&workspace);
+    if (status != BIGCN_OK) return status;
+    return forward_impl(plan, row_ptr, col_idx, dinv_sqrt, dinv_sqrt, false, n, x, ld_x, PackedInput{}, view,
+                        n_layers, logits, ld_logits, workspace, BIGCN_STATIC_WORKSPACE_BYTES, stream, nullptr);
 }
 
 extern "C" int bigcn_forward_packed(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,

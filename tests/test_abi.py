@@ -180,3 +180,18 @@ def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(TypeError):
         binding.bigcn_pack(torch.zeros(2, 3))
+
+
+def test_static_forward_rejects_oversized_problems_on_the_host():
+    """bigcn_forward_static checks the workspace the problem needs against its fixed array before
+    it touches the device: ESHAPE for a graph that does not fit, ENULL for missing layers."""
+    L = binding.lib()
+    desc = (binding.LayerDesc * 1)()
+    desc[0].w_bits, desc[0].alpha, desc[0].d_in, desc[0].d_out, desc[0].ld_words = FAKE, FAKE, 100, 256, 2
+    n = 3_000_000
+    assert L.bigcn_forward_workspace_bytes(n, desc, 1) > binding.STATIC_WORKSPACE_BYTES
+    assert L.bigcn_forward_static(FAKE, FAKE, FAKE, FAKE, n, FAKE, 100, desc, 1, FAKE, 256, None) == binding.BIGCN_ESHAPE
+    assert L.bigcn_forward_static(FAKE, FAKE, FAKE, FAKE, n, FAKE, 100, None, 1, FAKE, 256, None) == binding.BIGCN_ENULL
+    assert L.bigcn_forward_static(FAKE, FAKE, FAKE, FAKE, -1, FAKE, 100, desc, 1, FAKE, 256, None) == binding.BIGCN_EINVAL
+    text = open(HEADER).read()
+    assert f"#define BIGCN_STATIC_WORKSPACE_BYTES ({binding.STATIC_WORKSPACE_BYTES >> 20}u << 20)" in text

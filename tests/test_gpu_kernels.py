@@ -90,7 +90,11 @@ GEMM_SHAPES = [(1, 1, 1), (5, 3, 64), (67, 7, 65), (300, 41, 128), (1000, 47, 25
                # more than 32768 rows: the kernels for large row counts (up to 32768 rows one
                # wavefront takes one row at a time)
                (33001, 7, 64), (33003, 64, 500), (32800, 256, 256), (32801, 64, 1433), (32769, 300, 200),
-               (40000, 47, 256), (33000, 130, 3703)]
+               (40000, 47, 256), (33000, 130, 3703),
+               # at least 4096 rows, more than 64 columns, 512 bits or more: the FP4 path with one
+               # 128 x 128 tile per wavefront (256-bit chunks of K, partial last chunk, ragged tiles)
+               (4160, 256, 4096), (4200, 257, 512), (5000, 129, 8192), (4097, 128, 768), (4300, 384, 1000),
+               (4100, 65, 515)]
 
 
 @pytest.mark.parametrize("variant", ["auto", "valu", "mfma", "fp4"])
@@ -136,6 +140,28 @@ def test_binary_gemm_random_shapes(B, seed):
             continue
         for variant in ("auto", "valu", "mfma", "fp4"):
             test_binary_gemm(B, m, n, k, variant)
+
+
+def test_binary_gemm_strided_operands_on_every_path(B):
+    """Rows that start on 8-byte but not 16-byte boundaries and leading dimensions larger than the
+    row (the tile path reads 16 bytes per lane straight from the operands)."""
+    import torch
+    m, n, k = 4200, 200, 1100
+    words = (k + 63) // 64
+    rng = _rng(4242)
+    f = rng.choice(np.array([-1, 1], dtype=np.int8), size=(m, k))
+    bt = rng.choice(np.array([-1, 1], dtype=np.int8), size=(n, k))
+    acc = oracle.sign_matmul(f, bt)
+    fa = np.full((m, words + 3), -1, dtype=np.int64)          # garbage beyond the row
+    fb = np.full((n, words + 1), 0x5555555555555555, dtype=np.int64)
+    fa[:, 1:1 + words] = oracle.pack_bits(f).view(np.int64)
+    fb[:, 1:1 + words] = oracle.pack_bits(bt).view(np.int64)
+    da, db = to_device(fa, fb)
+    a_view, b_view = da[:, 1:1 + words], db[:, 1:1 + words]
+    for v in (B.GEMM_AUTO, B.GEMM_VALU, B.GEMM_MFMA, B.GEMM_FP4):
+        dacc, _ = B.bigcn_binary_gemm(a_view, None, b_view, None, k, want_out=False, variant=v)
+        torch.cuda.synchronize()
+        assert np.array_equal(dacc.cpu().numpy(), acc), f"variant {v}"
 
 
 def test_binary_gemm_unit_scales_give_exact_integers(B):

@@ -151,7 +151,7 @@ int launch_bitgemm_fp4(const uint64_t *a_bits, const float *a_scale, int64_t m, 
 
 // The FP4 path with one 128 x 128 tile per wavefront and no LDS stage (shapes bound by the
 // multiplies): fp4_tile_covers says whether launch_bitgemm_fp4 hands the shape to it.
-bool fp4_tile_covers(int64_t m, int64_t n, int64_t k_bits);
+bool fp4_tile_covers(int64_t m, int64_t n, int64_t k_bits, int64_t ld_acc, int64_t ld_out, int64_t lda, int64_t ldb);
 int launch_bitgemm_fp4_tile(const uint64_t *a_bits, const float *a_scale, int64_t m, int64_t lda,
                             const uint64_t *b_bits, const float *b_scale, int64_t n, int64_t ldb,
                             int64_t k_bits, int32_t *acc, int64_t ld_acc, float *out, int64_t ld_out,

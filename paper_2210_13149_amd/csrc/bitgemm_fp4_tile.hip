@@ -1,28 +1,29 @@
 // Kernel 2 on the FP4 matrix cores, large-tile form: the +-1 inner products of Sec. 4.2.3,
-// c_ij = sum_k F_ik B_kj, for shapes that are bound by the multiplies (many rows, at least 65
+// c_ij = sum_k F_ik B_kj, for shapes that are bound by the multiplies (many rows, more than 64
 // columns, K of 512 bits or more).
 //
 // One wavefront owns a tile of 128 rows x 128 columns (4 x 4 multiplies of 32 x 32 x 64 per 64
 // bits of K, v_mfma_scale_f32_32x32x64_f8f6f4 with both operands FP4 E2M1 and unit scales) and
 // runs alone on its SIMD: 256 accumulator registers, every expanded operand feeds four
-// multiplies.  There is no LDS stage and no barrier.  K is walked in chunks of 256 bits; lane
-// (i, h) (i = lane % 32, h = lane / 32) loads, for each of its four rows 32 rt + i and its four
-// columns 32 ct + i, the 16 bytes [32 chunk + 16 h, +16) of the packed row straight from global
-// memory (the two lanes of a row read 32 consecutive bytes; a 128-byte line serves four chunks
-// and stays in L2 meanwhile), two chunks ahead of the one being multiplied.  The order of the k
-// values inside a multiply is free as long as both operands agree, so multiply t of a chunk
-// simply takes dword t of every lane's 16 bytes.
+// multiplies.  The operands are not staged in LDS and there is no barrier.  K is walked in
+// chunks of 256 bits; lane (i, h) (i = lane % 32, h = lane / 32) loads, for each of its four
+// rows 32 rt + i and its four columns 32 ct + i, the 16 bytes [32 chunk + 16 h, +16) of the
+// packed row straight from global memory (the two lanes of a row read 32 consecutive bytes; a
+// 128-byte line serves four chunks and stays in L2 meanwhile), two chunks ahead of the one being
+// multiplied.  The order of the k values inside a multiply is free as long as both operands
+// agree, so multiply t of a chunk simply takes dword t of every lane's 16 bytes.
 //
 // Codes: the 32 bits x of a dword become four operand dwords, operand dword d taking the bits
-// d, d + 4, ..., d + 28 of x where they stand.
-//   rows    (values {0, +1}):  x & (0x11111111 << d)  -> codes 0x1 / 0x2 / 0x4 = 0.5 / 1 / 2;
-//                              d = 3 is shifted down to 0x2 (0x8 would be -0)
-//   columns (values -b, b = +-1): sign bit of the code = the bit itself, magnitude 2 / 1 / 0.5 / 1
-// so that every product is exactly 0 or -b_k: the fp32 accumulators hold -S, S = sum_k a_k b_k
-// (integers below 2^24: exact), and with f = 2a - 1
-//   c_ij = 2 S - sum_{k<K} b_kj = K - 2 (ones_j - S),  ones_j = set bits of column j below K.
-// Bits at and beyond K are cleared in both operands when the last, partial chunk is loaded, so
-// they contribute neither to S nor to ones_j.
+// d, d + 4, ..., d + 28 of x where they stand.  Both operands are coded as the *negated* sign
+// (sign bit of the code = the bit itself, so a set bit, +1, becomes a negative code): the
+// products are the same, and the sign needs no complement.  The magnitudes are chosen per
+// operand dword so that a code is at most one shift away from the bits: rows use 2 / 1 / 0.5 / 1
+// for d = 0..3 and columns 0.5 / 1 / 2 / 1, every product is exactly +-1, and the fp32
+// accumulators hold c_ij itself (integers below 2^24: exact).
+// The last, partial chunk of K is loaded dword by dword up to bit K, and the row codes of the
+// positions at and beyond K are cleared (FP4 zero), so that they add nothing.
+#include <algorithm>
+
 #include "bigcn_internal.h"
 
 namespace bigcn {
@@ -40,17 +41,6 @@ struct __attribute__((aligned(8))) Bits128 {
     uint32_t d[4];
 };
 
-__device__ __forceinline__ v8i codes_row(uint32_t x)
-{
-    v8i op;
-    op[0] = static_cast<int>(x & 0x11111111u);
-    op[1] = static_cast<int>(x & 0x22222222u);
-    op[2] = static_cast<int>(x & 0x44444444u);
-    op[3] = static_cast<int>((x & 0x88888888u) >> 2);
-    op[4] = op[5] = op[6] = op[7] = 0;
-    return op;
-}
-
 // (x << shift) | c and (x & mask) | c as one instruction each: the compiler's own selection
 // spends three (shift, and, or) because a literal cannot be an operand of these encodings; here
 // the constants are register operands.
@@ -67,14 +57,16 @@ __device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t c
     return r;
 }
 
-// mag[d]: the magnitude codes of operand dword d in every nibble (registers, see lshl_or)
-__device__ __forceinline__ v8i codes_col(uint32_t x, const uint32_t (&mag)[3])
+// mag[0..2]: the codes of 2.0 / 1.0 / 0.5 in every nibble (registers, see lshl_or).
+// Rows: magnitudes 2 / 1 / 0.5 / 1 for operand dwords 0..3; columns: 0.5 / 1 / 2 / 1.
+template <bool kColumn>
+__device__ __forceinline__ v8i codes(uint32_t x, const uint32_t (&mag)[3])
 {
     v8i op;
-    op[0] = static_cast<int>(lshl_or(x & 0x11111111u, 3, mag[0]));     // 2.0
-    op[1] = static_cast<int>(lshl_or(x & 0x22222222u, 2, mag[1]));     // 1.0
-    op[2] = static_cast<int>(lshl_or(x & 0x44444444u, 1, mag[2]));     // 0.5
-    op[3] = static_cast<int>(and_or(x, 0x88888888u, mag[1]));          // 1.0
+    op[0] = static_cast<int>(lshl_or(x & 0x11111111u, 3, mag[kColumn ? 2 : 0]));
+    op[1] = static_cast<int>(lshl_or(x & 0x22222222u, 2, mag[1]));
+    op[2] = static_cast<int>(lshl_or(x & 0x44444444u, 1, mag[kColumn ? 0 : 2]));
+    op[3] = static_cast<int>(and_or(x, 0x88888888u, mag[1]));
     op[4] = op[5] = op[6] = op[7] = 0;
     return op;
 }
@@ -86,158 +78,316 @@ struct Chunk {
 
 }  // namespace
 
-// grid.x: groups of row tiles, grid.y: groups of column tiles; wavefront w of a workgroup takes
-// row tile row_tiles_per_block * blockIdx.x + w / col_tiles_per_block and column tile
-// col_tiles_per_block * blockIdx.y + w % col_tiles_per_block (the wavefronts that share rows sit
-// in one workgroup, so that the rows come from HBM once).
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) void bitgemm_fp4_tile_kernel(
-    const uint64_t *__restrict__ a, int64_t m, int64_t lda, const uint64_t *__restrict__ b, int n,
-    int64_t ldb, int k_bits, int col_tiles_per_block, const float *__restrict__ a_scale,
-    const float *__restrict__ b_scale, int32_t *__restrict__ acc_out, int64_t ld_acc, float *__restrict__ out,
-    int64_t ld_out)
+// One staged result row: 128 columns as int16 (|c| <= K <= 8192), position 4 i + ct holding column
+// 32 ct + i, so that the four accumulator registers (ct = 0..3) a lane holds for one row and one
+// i are 8 consecutive bytes.
+constexpr int kStageRowBytes = kTileCols * 2;
+constexpr int kStageBytes = kTileRows * kStageRowBytes;       // 32 KB per wavefront
+constexpr int kSlices = kTileRows / 8;                        // a slice = 8 rows = one drain step
+
+struct TileArgs {
+    const uint64_t *a;
+    int64_t m, lda;
+    const uint64_t *b;
+    int n;
+    int64_t ldb;
+    int k_bits;
+    const float *a_scale, *b_scale;
+    int32_t *acc_out;
+    int64_t ld_acc;
+    float *out;
+    int64_t ld_out;
+    int64_t n_tiles;
+    int col_tiles;
+};
+
+// Persistent wavefronts: wavefront w of the launch takes tiles w, w + W, w + 2 W, ... (tile index =
+// row tile * column tiles + column tile, so that the wavefronts of a workgroup that share rows
+// read them at about the same time).  The results of a tile do not go to global memory when the
+// tile ends: the wavefront converts them, parks them in its own 32 KB of LDS and writes them out
+// slice by slice between the multiplies of the *next* tile (a wavefront may have only 64 memory
+// operations in flight: storing 256 registers in one go runs at the speed of the memory system
+// with the matrix cores idle, and all wavefronts would do so at the same time).  No barrier
+// anywhere: a wavefront only ever reads LDS that it wrote itself.
+//
+// With one wavefront per SIMD nothing hides an instruction that is not issued next to a multiply,
+// so the loop over K is one basic block: chunk loads past the end are clamped to the last chunk
+// instead of skipped, and the stores of a slice are buffer stores whose offset is moved out of
+// the descriptor's range when there is nothing to store (no slice left, a row past m, a column
+// past n): the hardware drops those, no branch and no change of the execution mask is needed.
+// kDrains slices are written out per chunk (1, 2 or 4: enough for the 16 slices of a tile when K
+// has at least 16, 8 or 4 chunks; what is left is written out after the loop).
+constexpr uint32_t kOutOfRange = 0x80000000u;                 // beyond any descriptor built below
+constexpr int kBufferFlags = 0x00020000;                      // raw buffer, 32-bit data format
+
+template <bool kAcc, bool kOut, int kDrains>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) void bitgemm_fp4_tile_kernel(TileArgs p)
 {
+    __shared__ __attribute__((aligned(16))) unsigned char stage_all[kWavesPerBlock][kStageBytes];
     const int lane = lane_id();
     const int wave = wave_in_block();
     const int i32 = lane & 31;
     const int half = lane >> 5;
-    const int row_tiles_per_block = kWavesPerBlock / col_tiles_per_block;
-    const int64_t row0 = (static_cast<int64_t>(blockIdx.x) * row_tiles_per_block + wave / col_tiles_per_block) * kTileRows;
-    const int col0 = (static_cast<int>(blockIdx.y) * col_tiles_per_block + wave % col_tiles_per_block) * kTileCols;
-    if (row0 >= m || col0 >= n) return;                       // wave-uniform; the kernel has no barrier
-
-    // this lane's four rows and four columns (clamped: results of clamped rows / columns are not stored)
-    const unsigned char *a_ptr[4], *b_ptr[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        int64_t row = row0 + 32 * t + i32;
-        if (row >= m) row = m - 1;
-        int col = col0 + 32 * t + i32;
-        if (col >= n) col = n - 1;
-        a_ptr[t] = reinterpret_cast<const unsigned char *>(a + row * lda) + 16 * half;
-        b_ptr[t] = reinterpret_cast<const unsigned char *>(b + static_cast<int64_t>(col) * ldb) + 16 * half;
-    }
-
+    unsigned char *stage = stage_all[wave];
+    const int k_bits = p.k_bits;
     const int n_full = k_bits / kChunkBits;                   // chunks that lie wholly below K
+    const bool partial = n_full * kChunkBits < k_bits;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kWavesPerBlock;
 
-    // a chunk that lies wholly below K: 16 bytes per row / column and lane
-    auto load = [&](int c, Chunk &s) {
-        if (c >= n_full) return;                              // uniform
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            s.a[t] = *reinterpret_cast<const Bits128 *>(a_ptr[t] + 32 * c);
-            s.b[t] = *reinterpret_cast<const Bits128 *>(b_ptr[t] + 32 * c);
-        }
-    };
-    // the partial chunk at the end of K: dword by dword, nothing is read at or beyond bit K and
-    // the bits beyond K inside the last dword are cleared
-    auto load_partial = [&](Chunk &s) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int left = k_bits - (kChunkBits * n_full + 128 * half + 32 * u);
-            const uint32_t keep = left >= 32 ? 0xffffffffu : (left <= 0 ? 0u : ((1u << left) - 1u));
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                s.a[t].d[u] = 0u;
-                s.b[t].d[u] = 0u;
-            }
-            if (left > 0) {
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    s.a[t].d[u] = *reinterpret_cast<const uint32_t *>(a_ptr[t] + 32 * n_full + 4 * u) & keep;
-                    s.b[t].d[u] = *reinterpret_cast<const uint32_t *>(b_ptr[t] + 32 * n_full + 4 * u) & keep;
-                }
-            }
-        }
-    };
-
-    v16f acc[4][4];
-#pragma unroll
-    for (int rt = 0; rt < 4; ++rt)
-#pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[rt][ct][r] = 0.0f;
-    int ones[4] = {0, 0, 0, 0};                               // set bits of this lane's half of its columns
-    // magnitude codes 2.0 / 1.0 / 0.5 in every nibble, kept in vector registers (opaque to the
+    // the codes of 2.0 / 1.0 / 0.5 in every nibble, kept in vector registers (opaque to the
     // compiler so that they are not folded back into literals)
     uint32_t mag[3] = {0x44444444u, 0x22222222u, 0x11111111u};
 #pragma unroll
     for (int d = 0; d < 3; ++d) asm volatile("" : "+v"(mag[d]));
 
-    auto multiply = [&](const Chunk &s) {
+    // The tile being multiplied.  Addresses are a wave-uniform base (first row / column of the tile)
+    // plus 32-bit byte offsets of this lane's four rows and four columns (clamped: results of
+    // clamped rows / columns are never written out): eight registers instead of sixteen.
+    int64_t row0 = 0;
+    int col0 = 0;
+    const unsigned char *a_base = nullptr, *b_base = nullptr;
+    uint32_t a_off[4], b_off[4];
+    auto set_tile = [&](int64_t t) {
+        row0 = (t / p.col_tiles) * kTileRows;
+        col0 = static_cast<int>(t % p.col_tiles) * kTileCols;
+        a_base = reinterpret_cast<const unsigned char *>(p.a + row0 * p.lda);
+        b_base = reinterpret_cast<const unsigned char *>(p.b + static_cast<int64_t>(col0) * p.ldb);
+        const int rows_here = static_cast<int>(min(static_cast<int64_t>(kTileRows), p.m - row0));
+        const int cols_here = min(kTileCols, p.n - col0);
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
+        for (int q = 0; q < 4; ++q) {
+            const int r = min(32 * q + i32, rows_here - 1), cc = min(32 * q + i32, cols_here - 1);
+            a_off[q] = static_cast<uint32_t>(r) * static_cast<uint32_t>(p.lda) * 8u + 16u * half;
+            b_off[q] = static_cast<uint32_t>(cc) * static_cast<uint32_t>(p.ldb) * 8u + 16u * half;
+        }
+    };
+    // chunk c (wholly below K; the caller keeps c < n_full): 16 bytes per row / column and lane
+    auto load = [&](int c, Chunk &s) {
+        const unsigned char *ac = a_base + 32 * c, *bc = b_base + 32 * c;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) ones[ct] += __popc(s.b[ct].d[u]);
+        for (int q = 0; q < 4; ++q) {
+            s.a[q] = *reinterpret_cast<const Bits128 *>(ac + a_off[q]);
+            s.b[q] = *reinterpret_cast<const Bits128 *>(bc + b_off[q]);
+        }
+    };
+    // the partial chunk at the end of K: dword by dword, nothing is read at or beyond bit K
+    // (dwords wholly beyond K are zero; the positions beyond K are taken out in multiply())
+    auto load_partial = [&](Chunk &s) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            v8i aop[4], bop[4];
+            const int left = k_bits - (kChunkBits * n_full + 128 * half + 32 * u);
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                aop[t] = codes_row(s.a[t].d[u]);
-                bop[t] = codes_col(s.b[t].d[u], mag);
+            for (int q = 0; q < 4; ++q) {
+                s.a[q].d[u] = 0u;
+                s.b[q].d[u] = 0u;
             }
+            if (left > 0) {
 #pragma unroll
-            for (int rt = 0; rt < 4; ++rt)
-#pragma unroll
-                for (int ct = 0; ct < 4; ++ct)
-                    acc[rt][ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                        aop[rt], bop[ct], acc[rt][ct], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+                for (int q = 0; q < 4; ++q) {
+                    s.a[q].d[u] = *reinterpret_cast<const uint32_t *>(a_base + 32 * n_full + 4 * u + a_off[q]);
+                    s.b[q].d[u] = *reinterpret_cast<const uint32_t *>(b_base + 32 * n_full + 4 * u + b_off[q]);
+                }
+            }
         }
     };
 
-    // Three register sets in rotation, chunk c + 2 requested before chunk c is multiplied; the
-    // loop body is three whole chunks so that the sets keep their names (no copies) and the loop
-    // has one exit (the 256 accumulators must not meet at a join of several paths); the one or
-    // two chunks left over are already in s0 / s1 when the loop ends.
-    {
-        Chunk s0, s1, s2;
-        load(0, s0);
-        load(1, s1);
+    // The tile whose results sit in LDS: slices [slice, kSlices) are still to be written out.
+    // Slice s: lane (r = lane / 8, g = lane % 8) takes row 8 s + r and the 32 staged bytes
+    // [32 g, 32 g + 32) of it = columns 32 ct + 4 g + e, e = 0..3, for the four ct: four stores of
+    // 16 bytes per output array, eight lanes covering one 128-byte line each.  The descriptors
+    // start at the tile's first row (column 0) and end behind its last existing row.
+    int slice = kSlices;
+    __amdgpu_buffer_rsrc_t acc_rsrc = __builtin_amdgcn_make_buffer_rsrc(p.acc_out, 0, 0, kBufferFlags);
+    __amdgpu_buffer_rsrc_t out_rsrc = __builtin_amdgcn_make_buffer_rsrc(p.out, 0, 0, kBufferFlags);
+    int64_t done_row0 = 0;
+    const int dr = lane >> 3, dg = lane & 7;
+    uint32_t acc_lane = kOutOfRange, out_lane = kOutOfRange;  // byte offset of (row dr, this lane's first column)
+    int b_scale_col = 0;                                      // that column, clamped, for b_scale
+    auto drain = [&](int s) {
+        const int s_in = s < kSlices ? s : kSlices - 1;       // LDS reads stay inside the stage
+        const uint4 *src = reinterpret_cast<const uint4 *>(stage + (8 * s_in + dr) * kStageRowBytes + 32 * dg);
+        const uint4 lo = src[0], hi = src[1];
+        const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};   // w[2 e + ct / 2]: ct even | odd
+        const bool live = s < kSlices;                        // uniform
+        float sa = 0.0f;
+        if (kOut) {
+            int64_t row = done_row0 + 8 * s_in + dr;
+            if (row >= p.m) row = p.m - 1;
+            sa = p.a_scale[row];
+        }
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+            typedef int v4i __attribute__((ext_vector_type(4)));
+            typedef float v4f __attribute__((ext_vector_type(4)));
+            v4i c;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t pair = w[2 * e + (ct >> 1)];
+                c[e] = (ct & 1) ? (static_cast<int>(pair) >> 16) : static_cast<int>(static_cast<int16_t>(pair & 0xffffu));
+            }
+            // columns past n: this lane's four columns 32 ct + 4 g .. + 3 exist all or not at all (n % 4 == 0)
+            const bool col_ok = b_scale_col + 32 * ct < p.n;
+            if (kAcc) {
+                const uint32_t off = (live && col_ok) ? acc_lane + static_cast<uint32_t>(8 * s_in) * static_cast<uint32_t>(p.ld_acc) * 4u + 128u * ct
+                                                      : kOutOfRange;
+                __builtin_amdgcn_raw_buffer_store_b128(c, acc_rsrc, static_cast<int>(off), 0, 0);
+            }
+            if (kOut) {
+                int j = b_scale_col + 32 * ct;
+                if (j + 3 >= p.n) j = p.n - 4;
+                struct __attribute__((aligned(4))) F4 { float v[4]; };
+                const F4 sb = *reinterpret_cast<const F4 *>(p.b_scale + j);
+                v4f o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = sa * sb.v[e] * static_cast<float>(c[e]);
+                const uint32_t off = (live && col_ok) ? out_lane + static_cast<uint32_t>(8 * s_in) * static_cast<uint32_t>(p.ld_out) * 4u + 128u * ct
+                                                      : kOutOfRange;
+                __builtin_amdgcn_raw_buffer_store_b128(o, out_rsrc, static_cast<int>(off), 0, 0);
+            }
+        }
+    };
+
+    int64_t tile = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave;
+    Chunk s0, s1, s2;
+    if (tile < p.n_tiles) {
+        set_tile(tile);
+        if (n_full > 0) load(0, s0);
+        if (n_full > 1) load(1, s1);
+    }
+    while (tile < p.n_tiles) {                                // wave-uniform
+        v16f acc[4][4];
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[rt][ct][r] = 0.0f;
+
+        // masked: the partial chunk, whose row codes are cleared at the positions at and beyond K
+        auto multiply = [&](const Chunk &s, bool masked) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                v8i aop[4], bop[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    aop[q] = codes<false>(s.a[q].d[u], mag);
+                    bop[q] = codes<true>(s.b[q].d[u], mag);
+                }
+                if (masked) {
+                    // bits of this lane's dword u that lie below K; nibble i of operand dword d
+                    // stands for bit 4 i + d
+                    const int left = k_bits - (kChunkBits * n_full + 128 * half + 32 * u);
+                    const uint32_t keep = left >= 32 ? 0xffffffffu : (left <= 0 ? 0u : ((1u << left) - 1u));
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        const int keep_codes = static_cast<int>(((keep >> d) & 0x11111111u) * 0xfu);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) aop[q][d] &= keep_codes;
+                    }
+                }
+#pragma unroll
+                for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+                    for (int ct = 0; ct < 4; ++ct)
+                        acc[rt][ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                            aop[rt], bop[ct], acc[rt][ct], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+            }
+        };
+
+        // Three register sets in rotation, chunk c + 2 requested before chunk c is multiplied; the
+        // loop body is three whole chunks so that the sets keep their names (no copies) and the
+        // loop has one exit (the 256 accumulators must not meet at a join of several paths); the
+        // one or two chunks left over are already in s0 / s1 when the loop ends.
+        const int last = n_full - 1;
         int c = 0;
         for (; c + 3 <= n_full; c += 3) {
-            load(c + 2, s2);
-            multiply(s0);
-            load(c + 3, s0);
-            multiply(s1);
-            load(c + 4, s1);
-            multiply(s2);
-        }
-        const bool partial = n_full * kChunkBits < k_bits;
-        if (partial) load_partial(s2);
-        if (c < n_full) multiply(s0);
-        if (c + 1 < n_full) multiply(s1);
-        if (partial) multiply(s2);
-    }
-
-    // epilogue: accumulator register r of lane (i, h) holds row 8 (r / 4) + 4 h + r % 4, column i
+            load(min(c + 2, last), s2);
+            __builtin_amdgcn_sched_barrier(0);        // the requests stay ahead of the multiplies
+            multiply(s0, false);
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct) {
-        const int col_ones = ones[ct] + __shfl_xor(ones[ct], 32, kWave);
-        const int j = col0 + 32 * ct + i32;
-        const bool col_ok = j < n;
-        const int base = k_bits - 2 * col_ones;               // c = base - 2 * acc  (acc = -S)
-        const float sb = (out != nullptr && col_ok) ? b_scale[j] : 0.0f;
+            for (int q = 0; q < kDrains; ++q) drain(slice++);
+            load(min(c + 3, last), s0);
+            __builtin_amdgcn_sched_barrier(0);        // the requests stay ahead of the multiplies
+            multiply(s1, false);
+#pragma unroll
+            for (int q = 0; q < kDrains; ++q) drain(slice++);
+            load(min(c + 4, last), s1);
+            __builtin_amdgcn_sched_barrier(0);        // the requests stay ahead of the multiplies
+            multiply(s2, false);
+#pragma unroll
+            for (int q = 0; q < kDrains; ++q) drain(slice++);
+        }
+        if (partial) load_partial(s2);
+        if (c < n_full) multiply(s0, false);
+        if (c + 1 < n_full) multiply(s1, false);
+        if (partial) multiply(s2, true);
+        while (slice < kSlices) drain(slice++);               // short K: what the chunks did not cover
+
+        // the tile just multiplied becomes the one to write out
+        {
+            done_row0 = row0;
+            const int64_t rows_here = min(static_cast<int64_t>(kTileRows), p.m - row0);
+            const int first_col = col0 + 4 * dg;
+            b_scale_col = first_col;
+            if (kAcc) {
+                acc_rsrc = __builtin_amdgcn_make_buffer_rsrc(p.acc_out + row0 * p.ld_acc, 0,
+                                                             static_cast<int>(rows_here * p.ld_acc * 4), kBufferFlags);
+                acc_lane = (static_cast<uint32_t>(dr) * static_cast<uint32_t>(p.ld_acc) + static_cast<uint32_t>(first_col)) * 4u;
+            }
+            if (kOut) {
+                out_rsrc = __builtin_amdgcn_make_buffer_rsrc(p.out + row0 * p.ld_out, 0,
+                                                             static_cast<int>(rows_here * p.ld_out * 4), kBufferFlags);
+                out_lane = (static_cast<uint32_t>(dr) * static_cast<uint32_t>(p.ld_out) + static_cast<uint32_t>(first_col)) * 4u;
+            }
+        }
+        // the next tile's first two chunks are requested before this tile's results are converted
+        tile += stride;
+        if (tile < p.n_tiles) {
+            set_tile(tile);
+            if (n_full > 0) load(0, s0);
+            if (n_full > 1) load(1, s1);
+        }
+
+        // convert and park: accumulator register r of lane (i, h) holds row 8 (r / 4) + 4 h + r % 4 of
+        // its 32 x 32 block and column i
 #pragma unroll
         for (int rt = 0; rt < 4; ++rt) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int64_t row = row0 + 32 * rt + 8 * (r >> 2) + 4 * half + (r & 3);
-                if (col_ok && row < m) {
-                    const int c = base - 2 * static_cast<int>(acc[rt][ct][r]);
-                    if (acc_out != nullptr) acc_out[row * ld_acc + j] = c;
-                    if (out != nullptr) out[row * ld_out + j] = a_scale[row] * sb * static_cast<float>(c);
-                }
+                const int row = 32 * rt + 8 * (r >> 2) + 4 * half + (r & 3);
+                int c4[4];
+#pragma unroll
+                for (int ct = 0; ct < 4; ++ct) c4[ct] = static_cast<int>(acc[rt][ct][r]);
+                uint2 packed;
+                packed.x = __builtin_amdgcn_perm(static_cast<uint32_t>(c4[1]), static_cast<uint32_t>(c4[0]), 0x05040100u);
+                packed.y = __builtin_amdgcn_perm(static_cast<uint32_t>(c4[3]), static_cast<uint32_t>(c4[2]), 0x05040100u);
+                *reinterpret_cast<uint2 *>(stage + row * kStageRowBytes + 8 * i32) = packed;
             }
         }
+        slice = 0;
     }
+    while (slice < kSlices) drain(slice++);                   // the last tile of this wavefront
 }
 
-// Shapes the tile kernel takes: enough columns to fill most of a 128-column tile and enough K
-// for the multiplies to dominate.
-bool fp4_tile_covers(int64_t m, int64_t n, int64_t k_bits)
+// Shapes the tile kernel takes: enough columns to fill most of a 128-column tile, enough K for
+// the multiplies to dominate; columns in whole groups of four (a lane writes four at a time) and
+// leading dimensions (of the outputs and of the packed operands) small enough for 32-bit byte
+// offsets inside a tile.
+bool fp4_tile_covers(int64_t m, int64_t n, int64_t k_bits, int64_t ld_acc, int64_t ld_out, int64_t lda, int64_t ldb)
 {
-    return n > 64 && k_bits >= 512 && m >= 4096;
+    if (lda >= (1 << 21) || ldb >= (1 << 21)) return false;
+    return n > 64 && n % 4 == 0 && k_bits >= 512 && m >= 4096 && ld_acc < (1 << 21) && ld_out < (1 << 21);
+}
+
+template <bool kAcc, bool kOut>
+static void launch_tile(dim3 grid, int n_chunks, hipStream_t stream, const TileArgs &p)
+{
+    if (n_chunks >= 16)
+        hipLaunchKernelGGL((bitgemm_fp4_tile_kernel<kAcc, kOut, 1>), grid, dim3(kBlock), 0, stream, p);
+    else if (n_chunks >= 8)
+        hipLaunchKernelGGL((bitgemm_fp4_tile_kernel<kAcc, kOut, 2>), grid, dim3(kBlock), 0, stream, p);
+    else
+        hipLaunchKernelGGL((bitgemm_fp4_tile_kernel<kAcc, kOut, 4>), grid, dim3(kBlock), 0, stream, p);
 }
 
 int launch_bitgemm_fp4_tile(const uint64_t *a_bits, const float *a_scale, int64_t m, int64_t lda,
@@ -245,16 +395,22 @@ int launch_bitgemm_fp4_tile(const uint64_t *a_bits, const float *a_scale, int64_
                             int64_t k_bits, int32_t *acc, int64_t ld_acc, float *out, int64_t ld_out,
                             hipStream_t stream)
 {
+    static_assert(BIGCN_MAX_K_BITS <= 32767, "results are parked as int16");
+    if (!fp4_tile_covers(m, n, k_bits, acc != nullptr ? ld_acc : 0, out != nullptr ? ld_out : 0, lda, ldb)) return BIGCN_EINVAL;
     const int64_t row_tiles = (m + kTileRows - 1) / kTileRows;
     const int64_t col_tiles = (n + kTileCols - 1) / kTileCols;
-    const int col_tiles_per_block = col_tiles >= 2 ? 2 : 1;
-    const int row_tiles_per_block = kWavesPerBlock / col_tiles_per_block;
-    const int64_t grid_x = (row_tiles + row_tiles_per_block - 1) / row_tiles_per_block;
-    const int64_t grid_y = (col_tiles + col_tiles_per_block - 1) / col_tiles_per_block;
-    if (grid_x > 0x7fffffff || grid_y > 65535) return BIGCN_ESHAPE;
-    hipLaunchKernelGGL(bitgemm_fp4_tile_kernel, dim3(static_cast<unsigned>(grid_x), static_cast<unsigned>(grid_y)),
-                       dim3(kBlock), 0, stream, a_bits, m, lda, b_bits, static_cast<int>(n), ldb,
-                       static_cast<int>(k_bits), col_tiles_per_block, a_scale, b_scale, acc, ld_acc, out, ld_out);
+    TileArgs p{a_bits, m, lda, b_bits, static_cast<int>(n), ldb, static_cast<int>(k_bits), a_scale, b_scale,
+               acc, ld_acc, out, ld_out, row_tiles * col_tiles, static_cast<int>(col_tiles)};
+    // one workgroup (four wavefronts, one per SIMD) per compute unit
+    int device = 0, cus = 0;
+    if (hipGetDevice(&device) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0)
+        return BIGCN_EHIP;
+    const dim3 grid(static_cast<unsigned>(std::min<int64_t>(cus, (p.n_tiles + kWavesPerBlock - 1) / kWavesPerBlock)));
+    const int n_chunks = static_cast<int>(k_bits / kChunkBits);
+    if (acc != nullptr && out != nullptr) launch_tile<true, true>(grid, n_chunks, stream, p);
+    else if (acc != nullptr) launch_tile<true, false>(grid, n_chunks, stream, p);
+    else launch_tile<false, true>(grid, n_chunks, stream, p);
     return check_launch();
 }
 

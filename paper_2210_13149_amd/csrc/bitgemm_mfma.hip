@@ -482,7 +482,7 @@ int launch_bitgemm_fp4(const uint64_t *a_bits, const float *a_scale, int64_t m, 
                        int64_t k_bits, int32_t *acc, int64_t ld_acc, float *out, int64_t ld_out,
                        hipStream_t stream)
 {
-    if (fp4_tile_covers(m, n, k_bits))
+    if (fp4_tile_covers(m, n, k_bits, acc != nullptr ? ld_acc : 0, out != nullptr ? ld_out : 0, lda, ldb))
         return launch_bitgemm_fp4_tile(a_bits, a_scale, m, lda, b_bits, b_scale, n, ldb, k_bits, acc, ld_acc, out,
                                        ld_out, stream);
     if (n > 64)

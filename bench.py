@@ -26,10 +26,26 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 INFINITY_CACHE_BYTES = 256 << 20   # MI355X last-level (memory-side) cache, published
 VALU_BINARY_MAC_PEAK = 256 * 4 * 16 * 2.4e9 * 32 / 2   # 2 VALU instructions per 32 binary MACs
+SMALL_GRAPH_ROWS = 32768        # up to here the forward uses the one-row-per-wavefront kernels
 
-# HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc (FETCH_SIZE and
-# WRITE_SIZE, scaled by a copy kernel of known size); see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"c5": 3.23e10}    # profiles/spmm_fused_c5.md (layer 1, the slowest launch)
+# Bytes that crossed the L2-to-fabric boundary per launch of the dominant kernel, measured with
+# rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, each scaled by a copy of known size): read from the
+# tracked summary that names the kernel and the commit it was measured at.  Absent = null.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "dominant_kernel_traffic.txt")
+
+
+def measured_traffic(workload):
+    """{"bytes": ..., "kernel": ..., "commit": ...} for `workload` from TRAFFIC_FILE, or None.
+    Lines: `workload | kernel | commit | bytes per launch`; `#` starts a comment."""
+    try:
+        lines = open(TRAFFIC_FILE).read().splitlines()
+    except OSError:
+        return None
+    for line in lines:
+        parts = [f.strip() for f in line.split("#")[0].split("|")]
+        if len(parts) == 4 and parts[0] == workload:
+            return {"bytes": float(parts[3]), "kernel": parts[1], "measured_at_commit": parts[2]}
+    return None
 
 
 def log(*a):
@@ -128,35 +144,67 @@ MFMA_INT8_MAC_PEAK = 2.5e15     # MI355X dense int8: 5.0 POP/s, two operations p
 MFMA_FP4_MAC_PEAK = 5.05e15     # MI355X dense fp4: 10.1 PFLOP/s
 
 
-def gemm_sweep(B, m=262144, n=256, k=4096, reps=10):
-    """Compute-bound bit-GEMM outside the workloads (their GEMMs are bound by writing the product
-    rows): the three evaluation paths of bigcn_binary_gemm on random bits, int32 accumulators
-    only."""
+def _time_calls(call, reps):
+    """Mean milliseconds of `call` over `reps` back-to-back launches (events on torch's stream)."""
     import torch
-    words = (k + 63) // 64
+    call()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def multiply_only_probe(B, iterations=4000):
+    """The rate of a launch of nothing but FP4 matrix-core multiplies on pseudo-random +-1 codes
+    (library entry bigcn_probe_fp4_multiply_rate): what this device sustains when loads, code
+    expansion and stores cost nothing."""
+    import torch
+    sink = torch.empty((256 * 1024,), dtype=torch.float32, device="cuda")
+    macs = B.bigcn_probe_fp4_multiply_rate(iterations, sink)
+    ms = _time_calls(lambda: B.bigcn_probe_fp4_multiply_rate(iterations, sink), 3)
+    return {"ms": ms, "binary_op_per_s": macs / (ms * 1e-3), "frac_mfma_fp4_peak": macs / (ms * 1e-3) / MFMA_FP4_MAC_PEAK}
+
+
+def gemm_sweep(B, m=262144, n=256, ks=(1024, 4096, 8192), reps=10):
+    """Bit-GEMM outside the workloads (their GEMMs are bound by writing the product rows): random
+    bits, int32 accumulators only.  The three evaluation paths of bigcn_binary_gemm at K = 4096 and
+    the FP4 path over K (the int32 output is 4 bytes per K multiply-accumulates, so the shape is
+    the more compute-bound the larger K: at K = 4096 the 268 MB of output and 134 MB of input are
+    0.05 ms at 8 TB/s against 0.054 ms of multiplies at the FP4 peak).  Each FP4 result carries its
+    fraction of the published peak and of the multiply-only rate measured in the same run."""
+    import torch
     gen = torch.Generator(device="cuda").manual_seed(1)
-    a = torch.randint(-2**62, 2**62, (m, words), dtype=torch.int64, device="cuda", generator=gen)
-    b = torch.randint(-2**62, 2**62, (n, words), dtype=torch.int64, device="cuda", generator=gen)
-    out = []
-    ref = None
-    for name, variant in (("valu_xor_popcount", B.GEMM_VALU), ("mfma_int8", B.GEMM_MFMA), ("mfma_fp4", B.GEMM_FP4)):
-        acc, _ = B.bigcn_binary_gemm(a, None, b, None, k, want_out=False, variant=variant)
-        torch.cuda.synchronize()
-        if ref is None:
-            ref = acc
-        identical = bool(torch.equal(ref, acc))
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            B.bigcn_binary_gemm(a, None, b, None, k, want_out=False, variant=variant)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
-        rate = m * n * k / (ms * 1e-3)
-        out.append({"path": name, "m": m, "n": n, "k_bits": k, "ms": ms, "binary_op_per_s": rate,
-                    "frac_valu_peak": rate / VALU_BINARY_MAC_PEAK,
-                    "frac_mfma_int8_peak": rate / MFMA_INT8_MAC_PEAK,
-                    "frac_mfma_fp4_peak": rate / MFMA_FP4_MAC_PEAK, "identical_to_first": identical})
+    ceiling = multiply_only_probe(B)
+    out = {"shape": {"m": m, "n": n}, "multiply_only": ceiling, "paths": []}
+    ref = {}
+    for k in ks:
+        words = (k + 63) // 64
+        a = torch.randint(-2**62, 2**62, (m, words), dtype=torch.int64, device="cuda", generator=gen)
+        b = torch.randint(-2**62, 2**62, (n, words), dtype=torch.int64, device="cuda", generator=gen)
+        variants = (("valu_xor_popcount", B.GEMM_VALU), ("mfma_int8", B.GEMM_MFMA), ("mfma_fp4", B.GEMM_FP4)) \
+            if k == 4096 else (("mfma_fp4", B.GEMM_FP4),)
+        for name, variant in variants:
+            acc, _ = B.bigcn_binary_gemm(a, None, b, None, k, want_out=False, variant=variant)
+            torch.cuda.synchronize()
+            if k not in ref:
+                ref[k] = acc
+            identical = bool(torch.equal(ref[k], acc))
+            ms = _time_calls(lambda: B.bigcn_binary_gemm(a, None, b, None, k, want_out=False, variant=variant), reps)
+            rate = m * n * k / (ms * 1e-3)
+            bytes_moved = m * words * 8 + n * words * 8 + m * n * 4
+            out["paths"].append({"path": name, "m": m, "n": n, "k_bits": k, "ms": ms, "binary_op_per_s": rate,
+                                 "frac_valu_peak": rate / VALU_BINARY_MAC_PEAK,
+                                 "frac_mfma_int8_peak": rate / MFMA_INT8_MAC_PEAK,
+                                 "frac_mfma_fp4_peak": rate / MFMA_FP4_MAC_PEAK,
+                                 "frac_of_multiply_only_rate": rate / ceiling["binary_op_per_s"],
+                                 "compulsory_bytes": bytes_moved,
+                                 "ms_of_compulsory_bytes_at_hbm_peak": bytes_moved / (HBM_PEAK_GBPS * 1e9) * 1e3,
+                                 "identical_to_first": identical})
+        del a, b
     return out
 
 
@@ -274,6 +322,226 @@ def gat_leg(B, m, cfg, reps=3):
             "row_gather_GBps": nnz * per_neighbour / (ms * 1e-3) / 1e9}
 
 
+def stream_probe(mib=2048):
+    """Streaming rates of this machine for scale (torch's own elementwise kernels on `mib` MiB of fp32):
+    copy (read + write), sum (read) and fill (write), in GB/s of the bytes each must move."""
+    import torch
+    n = mib << 18
+    src = torch.ones((n,), dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    nbytes = n * 4
+    out = {"mib": mib}
+    for name, call, moved in (("copy", lambda: dst.copy_(src), 2 * nbytes), ("read_sum", lambda: src.sum(), nbytes),
+                              ("fill", lambda: dst.fill_(1.0), nbytes)):
+        ms = _time_calls(call, 5)
+        out[name + "_GBps"] = moved / (ms * 1e-3) / 1e9
+    return out
+
+
+def gather_probe(B, m, row_bytes_list, reps=5):
+    """The plain gather of this graph: the public fp32 aggregation bigcn_spmm (unit coefficients)
+    on rows of the given widths, i.e. the same cache lines per neighbour that the fused
+    aggregation gathers, without its conversions and epilogue.  The reference a gather of
+    cache-resident rows is compared with (no published peak exists for it)."""
+    import torch
+    n = m["x"].shape[0]
+    out = {}
+    for row_bytes in sorted(set(row_bytes_list)):
+        d = max(1, row_bytes // 4)
+        z = torch.ones((n, d), dtype=torch.float32, device="cuda")
+        o = torch.empty_like(z)
+        ms = _time_calls(lambda: B.bigcn_spmm(m["plan"], m["row_ptr"], m["col_idx"], None, z, o), reps)
+        out[str(row_bytes)] = ms
+        del z, o
+    return out
+
+
+def infinity_cache_model(row_ptr_host, row_bytes, cache_bytes=INFINITY_CACHE_BYTES):
+    """A MODEL, not a measurement (no counter of this box sees behind the L2-to-fabric boundary):
+    share of the gathered rows that a least-recently-used cache of `cache_bytes` would serve when
+    node k's row is requested deg(k) times per launch (once per stored entry of column k; the
+    pattern is symmetric), by the characteristic-time approximation: a row is resident with
+    probability 1 - exp(-deg_k T), T set so that the expected resident bytes equal the cache."""
+    import numpy as np
+    deg = np.diff(row_ptr_host).astype(np.float64)
+    lines = -(-row_bytes // 128) * 128
+    capacity_rows = cache_bytes / lines
+    if capacity_rows >= deg.size:
+        return {"hit_rate": 1.0, "kind": "model: rows fit the cache"}
+    lo, hi = 0.0, 1.0
+    while (1.0 - np.exp(-deg * hi)).sum() < capacity_rows:
+        hi *= 2.0
+    for _ in range(60):
+        mid = 0.5 * (lo + hi)
+        if (1.0 - np.exp(-deg * mid)).sum() < capacity_rows:
+            lo = mid
+        else:
+            hi = mid
+    resident = 1.0 - np.exp(-deg * hi)
+    hit = float((deg * resident).sum() / deg.sum())
+    return {"hit_rate": hit, "kind": "model: LRU characteristic-time approximation, requests proportional to degree"}
+
+
+def slot_bounds(cfg, work_n, nnz, B, launch_ms):
+    """For every launch of a forward the bound it is compared with and the fraction reached:
+    slot 0 = binarise + pack, then per layer the bit-GEMM and the aggregation.  Bounds: HBM for the
+    pack (X once), the larger of HBM (packed input + product rows) and the arithmetic peak of the
+    path that runs (FP4 matrix cores or XOR + bit count, as bigcn_forward_gemm_path says) for the
+    bit-GEMM, and the gather's algorithmic
+    bytes over HBM for the aggregation.  On graphs of at most 32768 nodes the binarisation is part
+    of the first bit-GEMM launch (slot 0 is empty)."""
+    n = work_n
+    dims = cfg.dims
+    small = n <= SMALL_GRAPH_ROWS
+    words0 = (dims[0] + 63) // 64
+    slots = []
+    pack_bytes = n * (4 * dims[0] + 8 * words0 + 4)
+    if not small or cfg.model == "sage":
+        t = launch_ms[0] * 1e-3
+        slots.append({"slot": "pack", "ms": launch_ms[0], "bound": "hbm", "algorithmic_bytes": pack_bytes,
+                      "achieved": pack_bytes / t / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                      "frac": pack_bytes / t / 1e9 / HBM_PEAK_GBPS})
+    for l in range(cfg.n_layers):
+        d_in, d_out = dims[l], dims[l + 1]
+        products = 2 if cfg.model == "sage" else 1
+        row_bytes, _ = B.bigcn_forward_row_bytes(d_in, d_out)
+        t = launch_ms[1 + 2 * l] * 1e-3
+        macs = n * d_in * d_out * products
+        fp4 = B.bigcn_forward_gemm_path(n, d_in, d_out) == B.GEMM_FP4
+        in_bytes = n * 8 * ((d_in + 63) // 64) if not (small and l == 0 and cfg.model == "gcn") else n * 4 * d_in
+        hbm_bytes = in_bytes + n * row_bytes * products
+        peak_ops = MFMA_FP4_MAC_PEAK if fp4 else VALU_BINARY_MAC_PEAK
+        t_hbm, t_ops = hbm_bytes / (HBM_PEAK_GBPS * 1e9), macs / peak_ops
+        if t_hbm >= t_ops:
+            slots.append({"slot": f"bit_gemm[{l}]", "ms": t * 1e3, "bound": "hbm", "algorithmic_bytes": hbm_bytes,
+                          "achieved": hbm_bytes / t / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                          "frac": hbm_bytes / t / 1e9 / HBM_PEAK_GBPS, "path": "fp4-mfma" if fp4 else "xor-popcount"})
+        else:
+            slots.append({"slot": f"bit_gemm[{l}]", "ms": t * 1e3, "bound": "mfma" if fp4 else "alu", "binary_macs": macs,
+                          "achieved": macs / t / 1e12, "peak": peak_ops / 1e12, "unit": "T binary MAC/s",
+                          "frac": macs / t / peak_ops, "path": "fp4-mfma" if fp4 else "xor-popcount"})
+        gather, minimum, row_bytes = aggregation_bytes(cfg, nnz, l, B)
+        t = launch_ms[2 + 2 * l] * 1e-3
+        slots.append({"slot": f"aggregation[{l}]", "ms": t * 1e3, "bound": "hbm", "algorithmic_bytes": gather,
+                      "achieved": gather / t / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                      "frac": gather / t / 1e9 / HBM_PEAK_GBPS, "row_bytes": row_bytes,
+                      "compulsory_bytes": minimum, "compulsory_GBps": minimum / t / 1e9,
+                      "rows_fit_infinity_cache": n * row_bytes <= INFINITY_CACHE_BYTES})
+    return slots
+
+
+def time_forward(m, n_layers, steps, warmup, graph, B):
+    """ms per forward (mean, median, min where available) and mean ms per launch slot.  Eager:
+    every step is event-bracketed per launch inside the timed region.  Graph: one forward is
+    captured in a HIP graph and `steps` replays are timed; the per-launch figures then come from a
+    separate eager, event-bracketed pass of min(steps, 200) forwards."""
+    import torch
+
+    def step(prof=None):
+        m["forward"](m["plan"], m["row_ptr"], m["col_idx"], m["dinv"], m["x"], m["layers"],
+                     m["workspace"], m["logits"], prof)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        g.replay()
+        torch.cuda.synchronize()
+        start.record()
+        for _ in range(steps):
+            g.replay()
+        stop.record()
+        torch.cuda.synchronize()
+        ms = start.elapsed_time(stop) / steps
+        eager_steps = min(steps, 200)
+        profile = B.Profile(n_layers, eager_steps)
+        for _ in range(eager_steps):
+            step(profile)
+        torch.cuda.synchronize()
+        launch_ms, _ = profile.read()
+        return {"ms": ms, "median": None, "min": None, "launch_ms": launch_ms, "launch": "hip graph replay"}
+    profile = B.Profile(n_layers, steps)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    start.record()
+    marks[0].record()
+    for i in range(steps):
+        step(profile)
+        marks[i + 1].record()
+    stop.record()
+    torch.cuda.synchronize()
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
+    launch_ms, calls = profile.read()
+    assert calls == steps
+    return {"ms": start.elapsed_time(stop) / steps, "median": per_step[len(per_step) // 2], "min": per_step[0],
+            "launch_ms": launch_ms, "launch": "eager"}
+
+
+def apply_cache_bound(slots, gather_ms):
+    """An aggregation whose product rows fit the 256 MB Infinity Cache is gathered from there, so
+    its algorithmic bytes over the HBM peak say nothing (they can exceed 1).  Such a launch is
+    compared with the plain gather of the same cache lines on the same graph, measured in the same
+    run (`gather_ms`, see gather_probe): the HBM figure is kept beside it as `algorithmic_GBps`."""
+    for s in slots:
+        if not s.get("rows_fit_infinity_cache"):
+            continue
+        t_plain = gather_ms[str(max(128, s["row_bytes"]))]
+        s.update({"bound": "cache-resident gather (rows fit the 256 MB Infinity Cache; no published peak)",
+                  "algorithmic_GBps": s["achieved"], "algorithmic_frac_of_hbm_peak": s["frac"],
+                  "peak": s["algorithmic_bytes"] / (t_plain * 1e-3) / 1e9,
+                  "peak_is": "the plain fp32 gather (bigcn_spmm, unit coefficients) of the same cache lines "
+                             "on the same graph, measured in this run",
+                  "frac": t_plain / s["ms"], "plain_gather_ms": t_plain})
+
+
+def dominant_roofline(slots):
+    """The `roofline` object of a workload: its slowest launch against its bound."""
+    dom = max(slots, key=lambda s: s["ms"])
+    r = {"bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"], "unit": dom["unit"],
+         "frac": dom["frac"], "kernel": dom["slot"], "avg_launch_ms": dom["ms"]}
+    for k in ("peak_is", "plain_gather_ms", "algorithmic_frac_of_hbm_peak"):
+        if k in dom:
+            r[k] = dom[k]
+    return r
+
+
+def config_leg(name, B, steps, warmup, graph):
+    """One of the other workloads, timed in the same run: ms per forward, nodes/s, every launch
+    against its bound and the workload's own `roofline` (its slowest launch)."""
+    import torch
+    from workloads import get_config, make_workload
+    cfg = get_config(name)
+    t0 = time.perf_counter()
+    work = make_workload(cfg)
+    m = build_model(work, B)
+    log(f"[bench] {name}: generated and set up in {time.perf_counter() - t0:.1f} s")
+    timing = time_forward(m, cfg.n_layers, steps, warmup, graph, B)
+    slots = slot_bounds(cfg, work.n, work.nnz, B, timing["launch_ms"])
+    gather_ms = None
+    if any(s.get("rows_fit_infinity_cache") for s in slots):
+        gather_ms = gather_probe(B, m, [max(128, s["row_bytes"]) for s in slots if s.get("rows_fit_infinity_cache")])
+        apply_cache_bound(slots, gather_ms)
+    leg = {"workload": f"{cfg.name}: {cfg.stands_in_for}-shaped, {work.n} nodes, {cfg.n_edges} edges, dims "
+                       + "-".join(str(d) for d in cfg.dims),
+           "ms_per_forward": timing["ms"], "ms_median": timing["median"], "ms_min": timing["min"],
+           "nodes_per_s": work.n / (timing["ms"] * 1e-3), "launch": timing["launch"], "steps": steps,
+           "launches": slots, "sum_of_launches_ms": sum(timing["launch_ms"]),
+           "roofline": dominant_roofline(slots)}
+    if gather_ms is not None:
+        leg["plain_gather_ms_by_row_bytes"] = gather_ms
+    del m
+    torch.cuda.empty_cache()
+    return leg
+
+
 def cpu_baseline(work, target_nodes):
     """The plain oracle, as it stands, timed on the host cores: on the benchmark's own workload,
     or on a smaller graph of the same recipe (same mean degree, dims, feature law); nodes/s."""
@@ -310,11 +578,18 @@ def main():
                     help="capture one forward in a HIP graph and time replays (launch-bound small "
                          "workloads; per-kernel figures then come from a separate profiled pass)")
     ap.add_argument("--no-backward", action="store_true",
-                    help="skip the back-propagation leg (one bigcn_layer_backward per layer, timed alone)")
+                    help="skip the back-propagation and Bi-GAT legs (timed alone, not part of a step)")
     ap.add_argument("--no-gemm-sweep", action="store_true",
-                    help="skip the compute-bound bit-GEMM leg (three evaluation paths, M=262144, n=256, K=4096)")
+                    help="skip the bit-GEMM leg outside the workloads (three evaluation paths at K = 4096, "
+                         "the FP4 path over K, M=262144, n=256, and the multiply-only rate)")
     ap.add_argument("--gemm-sweep-only", action="store_true",
-                    help="run only the compute-bound bit-GEMM leg and print it (for counter collection)")
+                    help="run only the bit-GEMM leg and print it (for counter collection)")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the legs of the other four workloads (c1-c3 as HIP-graph replays of 1000 "
+                         "forwards, c4 eager) that a default run of c5 adds to its line")
+    ap.add_argument("--probe", choices=["stream", "gather", "mfma"],
+                    help="run only one probe and print it: streaming rates of the box, the plain gather "
+                         "by row width on the workload's graph, or the multiply-only matrix-core rate")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -330,6 +605,12 @@ def main():
     if args.gemm_sweep_only:
         print(json.dumps({"bit_gemm_sweep": gemm_sweep(B)}), flush=True)
         return
+    if args.probe == "stream":
+        print(json.dumps({"stream_probe": stream_probe()}), flush=True)
+        return
+    if args.probe == "mfma":
+        print(json.dumps({"multiply_only": multiply_only_probe(B)}), flush=True)
+        return
     cfg = get_config(args.workload)
     t0 = time.perf_counter()
     work = make_workload(cfg)
@@ -337,6 +618,10 @@ def main():
     t0 = time.perf_counter()
     m = build_model(work, B)
     log(f"[bench] set-up (upload, plan, weights, calibration) {time.perf_counter() - t0:.1f} s")
+    if args.probe == "gather":
+        print(json.dumps({"workload": cfg.name, "plain_gather_ms_by_row_bytes": gather_probe(B, m, [32, 64, 128, 256])}),
+              flush=True)
+        return
     if args.copy_probe_mib > 0:
         src = torch.ones((args.copy_probe_mib << 18,), dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -346,108 +631,70 @@ def main():
         del src, dst
     n_layers = cfg.n_layers
     steps, warmup = max(1, args.steps), max(0, args.warmup)
-    profile = B.Profile(n_layers, steps)
-
-    def step(prof=None):
-        m["forward"](m["plan"], m["row_ptr"], m["col_idx"], m["dinv"], m["x"], m["layers"],
-                     m["workspace"], m["logits"], prof)
-
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
-    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    if args.graph:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            step()
-        torch.cuda.current_stream().wait_stream(side)
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step()
-        graph.replay()
-        torch.cuda.synchronize()
-        start.record()
-        for _ in range(steps):
-            graph.replay()
-        stop.record()
-        torch.cuda.synchronize()
-        for _ in range(steps):
-            step(profile)                     # per-kernel figures: eager, event-bracketed
-        torch.cuda.synchronize()
-        per_step = None
-    else:
-        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
-        start.record()
-        marks[0].record()
-        for i in range(steps):
-            step(profile)
-            marks[i + 1].record()
-        stop.record()
-        torch.cuda.synchronize()
-        per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
-    ms_per_step = start.elapsed_time(stop) / steps
-    launch_ms, calls = profile.read()
-    assert calls == steps
+    timing = time_forward(m, n_layers, steps, warmup, args.graph, B)
+    ms_per_step = timing["ms"]
+    launch_ms = timing["launch_ms"]
 
     nodes_per_s = work.n / (ms_per_step * 1e-3)
-    # per-kernel figures from the events recorded inside the timed region
-    gemm = []
-    spmm = []
-    for l in range(n_layers):
-        t_gemm = launch_ms[1 + 2 * l] * 1e-3
-        t_spmm = launch_ms[2 + 2 * l] * 1e-3
+    slots = slot_bounds(cfg, work.n, work.nnz, B, launch_ms)
+    gemm = [s for s in slots if s["slot"].startswith("bit_gemm")]
+    spmm = [s for s in slots if s["slot"].startswith("aggregation")]
+    for l, g in enumerate(gemm):
         macs = work.n * cfg.dims[l] * cfg.dims[l + 1] * (2 if cfg.model == "sage" else 1)
-        gather, minimum, row_bytes = aggregation_bytes(cfg, work.nnz, l, B)
-        # the products are written as rows of row_bytes per node (and per product for Bi-GraphSAGE):
-        # on the large workloads this step is bound by those writes, not by the multiplies
-        rows_written = work.n * row_bytes * (2 if cfg.model == "sage" else 1)
-        gemm.append({"layer": l, "ms": t_gemm * 1e3, "binary_op_per_s": macs / t_gemm,
-                     "frac_valu_peak": macs / t_gemm / VALU_BINARY_MAC_PEAK,
-                     "frac_mfma_fp4_peak": macs / t_gemm / MFMA_FP4_MAC_PEAK,
-                     "rows_written_GBps": rows_written / t_gemm / 1e9,
-                     "frac_hbm_peak": rows_written / t_gemm / 1e9 / HBM_PEAK_GBPS})
-        # a gathered row moves whole 128-byte lines: rows of 64 bytes cost one line each
-        line_bytes = work.nnz * (-(-row_bytes // 128) * 128)
-        spmm.append({"layer": l, "ms": t_spmm * 1e3, "row_bytes": row_bytes,
-                     "gather_GBps": gather / t_spmm / 1e9, "frac_hbm_peak": gather / t_spmm / 1e9 / HBM_PEAK_GBPS,
-                     "row_lines_GBps": line_bytes / t_spmm / 1e9,
-                     "compulsory_GBps": minimum / t_spmm / 1e9,
-                     # a row array that fits the 256 MB Infinity Cache is gathered from there: the
-                     # algorithmic bytes over the HBM peak can then exceed 1 and is no HBM figure
-                     "rows_fit_infinity_cache": work.n * row_bytes <= INFINITY_CACHE_BYTES})
-    # dominant kernel: the slowest launch of a step (an aggregation on every workload here)
-    dom = max(range(n_layers), key=lambda l: spmm[l]["ms"])
-    dom_ms = spmm[dom]["ms"]
-    dom_bytes = aggregation_bytes(cfg, work.nnz, dom, B)[0]
-    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get(cfg.name)
-    roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                "kernel": f"spmm_kernel (fused aggregation), layer {dom}",
-                "avg_launch_ms": dom_ms, "algorithmic_bytes_per_launch": dom_bytes,
-                "rows_fit_infinity_cache": spmm[dom]["rows_fit_infinity_cache"]}
+        g["binary_op_per_s"] = macs / (g["ms"] * 1e-3)
+    gather_widths = [max(128, s["row_bytes"]) for s in spmm]
+    gather_ms = gather_probe(B, m, gather_widths)
+    apply_cache_bound(slots, gather_ms)
+    roofline = dominant_roofline(slots)
+    dom = max(slots, key=lambda s: s["ms"])
+    if dom["slot"].startswith("aggregation"):
+        # What this figure is and is not.  `achieved` is algorithmic gather bytes (no reuse assumed)
+        # over the launch time, as a fraction of the published HBM peak.  The only memory counters
+        # rocprofv3 offers on this machine (FETCH_SIZE / WRITE_SIZE = TCC_EA0_RDREQ* / WRREQ*) sit on the
+        # L2-to-fabric boundary; none sees the memory controllers or the Infinity Cache, so the share
+        # of these bytes that the 256 MB memory-side cache served instead of HBM cannot be measured.
+        model = infinity_cache_model(work.row_ptr, dom["row_bytes"])
+        hbm_est = dom["algorithmic_bytes"] - model["hit_rate"] * work.nnz * dom["row_bytes"]
+        roofline.update({
+            "measured_at": "algorithmic bytes; the counter-measured traffic (`traffic`) is bytes across the "
+                           "L2-to-fabric boundary = HBM + Infinity Cache; no counter on this box sees HBM alone",
+            "algorithmic_bytes_per_launch": dom["algorithmic_bytes"],
+            "rows_fit_infinity_cache": dom["rows_fit_infinity_cache"],
+            "hbm_side": {"compulsory_bytes": dom["compulsory_bytes"], "compulsory_GBps": dom["compulsory_GBps"],
+                         "compulsory_frac_of_hbm_peak": dom["compulsory_GBps"] / HBM_PEAK_GBPS,
+                         "infinity_cache_model": model,
+                         "modelled_hbm_bytes": hbm_est,
+                         "modelled_hbm_GBps": hbm_est / (dom["ms"] * 1e-3) / 1e9,
+                         "modelled_frac_of_hbm_peak": hbm_est / (dom["ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS}})
+    traffic = measured_traffic(cfg.name)
+    roofline["traffic"] = None if traffic is None else traffic["bytes"]
+    if traffic is not None:
+        roofline["traffic_source"] = {k: v for k, v in traffic.items() if k != "bytes"}
+        roofline["traffic_source"]["file"] = os.path.relpath(TRAFFIC_FILE, ROOT)
+    roofline["plain_gather_ms_by_row_bytes"] = gather_ms
+    roofline["stream_probe"] = stream_probe()
 
+    fp4_ran = any(g.get("path") == "fp4-mfma" for g in gemm)
     result = {
         "metric": "Bi-GCN forward nodes/s; bit-GEMM binary-op/s; SpMM HBM GB/s (% roofline)",
         "model": "Bi-GCN" if cfg.model == "gcn" else "Bi-GraphSAGE (mean aggregator)",
         "value": nodes_per_s, "unit": "nodes/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
-        "ms_per_step": ms_per_step, "ms_per_step_median": None if per_step is None else per_step[len(per_step) // 2],
-        "ms_per_step_min": None if per_step is None else per_step[0],
+        "ms_per_step": ms_per_step, "ms_per_step_median": timing["median"], "ms_per_step_min": timing["min"],
         "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "u64 xor/popcount + f32", "data": "synthetic",
-        "launch": "hip graph replay" if args.graph else "eager",
+        "vs_baseline": None,
+        "dtype": ("fp4-mfma +-1 products (exact integers in f32 accumulators) + f32 aggregation" if fp4_ran
+                  else "u64 xor/popcount products (int32, exact) + f32 aggregation"),
+        "data": "synthetic", "launch": timing["launch"],
         "config": {"workload": f"{cfg.name}: {cfg.stands_in_for}-shaped Chung-Lu graph, {work.n} nodes, "
                                f"{cfg.n_edges} undirected edges "
                                + ("(+ self-loops), Bi-GCN, dims " if cfg.model == "gcn" else
                                   "(neighbour lists), Bi-GraphSAGE mean aggregator, dims ")
                                + "-".join(str(d) for d in cfg.dims),
                    "layers": n_layers, "nnz": work.nnz, "standardisation": cfg.bn_layers},
-        "pack_ms": launch_ms[0],
-        "pack_GBps": (work.n * (4 * cfg.dims[0] + 8 * ((cfg.dims[0] + 63) // 64) + 4)) / (launch_ms[0] * 1e-3) / 1e9,
+        "launches": slots,
         "bit_gemm": gemm, "spmm": spmm,
         "bit_gemm_binary_op_per_s": max(g["binary_op_per_s"] for g in gemm),
-        "spmm_GBps": achieved,
+        "spmm_GBps": roofline["achieved"],
         "roofline": roofline,
         "paper_theory": {k: v for k, v in (cost_model.sage_summary if cfg.model == "sage" else
                                            cost_model.summary)(cfg.n_nodes, cfg.n_edges, cfg.dims).items()
@@ -459,14 +706,35 @@ def main():
     if not args.no_backward and cfg.model == "gcn":
         result["backward"] = backward_leg(B, m, cfg)
         result["gat_layer"] = gat_leg(B, m, cfg)
+    del m
+    torch.cuda.empty_cache()
     if not args.no_gemm_sweep:
-        result["bit_gemm_sweep"] = gemm_sweep(B)
-        best = max(result["bit_gemm_sweep"], key=lambda r: r["binary_op_per_s"])
+        sweep = gemm_sweep(B)
+        result["bit_gemm_sweep"] = sweep
+        best = max(sweep["paths"], key=lambda r: r["binary_op_per_s"])
         result["bit_gemm_binary_op_per_s"] = max(result["bit_gemm_binary_op_per_s"], best["binary_op_per_s"])
+        # the bit-GEMM target is stated on the path the automatic choice takes for such shapes
+        # (FP4 matrix cores) against the published FP4 peak: visible beside the headline roofline
+        roofline["bit_gemm"] = {"bound": "mfma", "chosen_path": "mfma_fp4", "peak": MFMA_FP4_MAC_PEAK / 1e12,
+                                "unit": "T binary MAC/s",
+                                "by_k_bits": {str(r["k_bits"]): {"achieved": r["binary_op_per_s"] / 1e12,
+                                                                 "frac": r["frac_mfma_fp4_peak"],
+                                                                 "frac_of_multiply_only_rate": r["frac_of_multiply_only_rate"]}
+                                              for r in sweep["paths"] if r["path"] == "mfma_fp4"},
+                                "multiply_only_frac_of_peak": sweep["multiply_only"]["frac_mfma_fp4_peak"],
+                                "target_0p5_met": best["frac_mfma_fp4_peak"] >= 0.5}
+    if not args.no_configs and args.workload == "c5":
+        legs = {}
+        for name in ("c1", "c2", "c3"):
+            legs[name] = config_leg(name, B, steps=1000, warmup=20, graph=True)
+        legs["c4"] = config_leg("c4", B, steps=steps, warmup=warmup, graph=False)
+        result["configs"] = legs
+        roofline["per_config"] = {name: {"ms_per_forward": leg["ms_per_forward"], "nodes_per_s": leg["nodes_per_s"],
+                                         "launch": leg["launch"],
+                                         **{k: leg["roofline"][k] for k in ("bound", "kernel", "achieved", "peak", "unit", "frac")}}
+                                  for name, leg in legs.items()}
     if args.cpu_baseline_nodes != 0:
         t0 = time.perf_counter()
-        del m
-        torch.cuda.empty_cache()
         whole = 400000 if cfg.name == "s5" else cfg.n_nodes
         sample = whole if args.cpu_baseline_nodes < 0 else min(args.cpu_baseline_nodes, cfg.n_nodes)
         result["cpu_baseline"] = cpu_baseline(work, sample)

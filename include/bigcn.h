@@ -211,6 +211,11 @@ size_t bigcn_forward_workspace_bytes(int64_t n, const bigcn_layer *layers, int n
  * whether the node's source scale is stored inside that row (*scale_embedded, HOST,
  * nullable).  Used to size the aggregation's gather traffic; 0 for unsupported shapes. */
 int64_t bigcn_forward_row_bytes(int64_t d_in, int64_t d_out, int *scale_embedded);
+/* Which evaluation of the binary product (Sec. 4.2.3) the fused forward uses for a layer of a graph
+ * of n nodes: BIGCN_GEMM_FP4 (matrix cores) or BIGCN_GEMM_VALU (XOR + bit count); both are exact.
+ * For reports: the arithmetic peak a layer's bit-GEMM is compared with.  EINVAL for shapes the
+ * forward does not take. */
+int bigcn_forward_gemm_path(int64_t n, int64_t d_in, int64_t d_out);
 int bigcn_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx,
                   const float *dinv_sqrt, int64_t n, const float *x, int64_t ld_x,
                   const bigcn_layer *layers, int n_layers, float *logits, int64_t ld_logits,
@@ -444,6 +449,20 @@ int bigcn_sage_forward_profiled(const bigcn_plan *plan, const int64_t *row_ptr, 
                                 int64_t ld_out, void *workspace, size_t workspace_bytes,
                                 void *stream, bigcn_profile *profile);
 int bigcn_profile_read(bigcn_profile *profile, float *launch_ms, int *calls);
+
+/*
+ * Measurement aid for the matrix-core evaluation of the binary product (Sec. 4.2.3): a launch of
+ * nothing but independent 32 x 32 x 64 FP4 multiplies on pseudo-random +-1 codes, one wavefront
+ * per SIMD with sixteen accumulator tiles, `iterations` x 16 multiplies per wavefront.  Timed by
+ * the caller (events on `stream`), it gives the multiply rate this device sustains when loads,
+ * code expansion and stores cost nothing: the ceiling the FP4 path of bigcn_binary_gemm is
+ * compared with beside the published peak.
+ *   sink: DEVICE, at least 256 floats per compute unit (sink_floats says how many there are);
+ *   *multiply_accumulates: HOST out, +-1 multiply-accumulates the launch performs.
+ * Errors: ENULL, EINVAL (iterations outside 1 .. 2^20), EWORKSPACE (sink too small), EHIP.
+ */
+int bigcn_probe_fp4_multiply_rate(int iterations, float *sink, int64_t sink_floats,
+                                  int64_t *multiply_accumulates, void *stream);
 
 #ifdef __cplusplus
 }

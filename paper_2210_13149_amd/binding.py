@@ -40,6 +40,7 @@ EXPORTS = (
     "bigcn_column_stats", "bigcn_predict", "bigcn_layer_backward_workspace_bytes",
     "bigcn_layer_backward", "bigcn_entropy_workspace_bytes", "bigcn_entropy",
     "bigcn_gat_layer_workspace_bytes", "bigcn_gat_layer", "bigcn_forward_static",
+    "bigcn_probe_fp4_multiply_rate", "bigcn_forward_gemm_path",
 )
 
 
@@ -108,12 +109,16 @@ def lib() -> ctypes.CDLL:
         L.bigcn_forward_workspace_bytes.argtypes = [i64, ctypes.POINTER(LayerDesc), i32]
         L.bigcn_forward_row_bytes.restype = i64
         L.bigcn_forward_row_bytes.argtypes = [i64, i64, ctypes.POINTER(i32)]
+        L.bigcn_forward_gemm_path.restype = i32
+        L.bigcn_forward_gemm_path.argtypes = [i64, i64, i64]
         L.bigcn_forward.restype = i32
         L.bigcn_forward.argtypes = [vp, vp, vp, vp, i64, vp, i64, ctypes.POINTER(LayerDesc), i32, vp,
                                     i64, vp, ctypes.c_size_t, vp]
         L.bigcn_forward_static.restype = i32
         L.bigcn_forward_static.argtypes = [vp, vp, vp, vp, i64, vp, i64, ctypes.POINTER(LayerDesc), i32, vp,
                                            i64, vp]
+        L.bigcn_probe_fp4_multiply_rate.restype = i32
+        L.bigcn_probe_fp4_multiply_rate.argtypes = [i32, vp, i64, ctypes.POINTER(i64), vp]
         L.bigcn_profile_create.restype = i32
         L.bigcn_profile_create.argtypes = [i32, i32, ctypes.POINTER(vp)]
         L.bigcn_profile_destroy.restype = None
@@ -301,7 +306,7 @@ class Plan:
 
 
 def bigcn_spmm(plan: Plan, row_ptr: torch.Tensor, col_idx: torch.Tensor,
-               vals: Optional[torch.Tensor], z: torch.Tensor) -> torch.Tensor:
+               vals: Optional[torch.Tensor], z: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
     """``out = sum_p vals[p] * z[col_idx[p], :]`` per CSR row (vals None = ones)."""
     _dev(z, torch.float32, "z")
     if z.dim() != 2 or (z.shape[1] > 1 and z.stride(1) != 1):
@@ -309,9 +314,14 @@ def bigcn_spmm(plan: Plan, row_ptr: torch.Tensor, col_idx: torch.Tensor,
     if vals is not None:
         _dev(vals, torch.float32, "vals")
     n, d = z.shape
-    out = torch.empty((n, d), dtype=torch.float32, device=z.device)
+    if out is None:
+        out = torch.empty((n, d), dtype=torch.float32, device=z.device)
+    else:
+        _dev(out, torch.float32, "out")
+        if out.shape != z.shape or (d > 1 and out.stride(1) != 1):
+            raise ValueError("out must be a row-major matrix of z's shape")
     _check(lib().bigcn_spmm(plan.handle, _ptr(row_ptr), _ptr(col_idx), _ptr(vals), n, _ptr(z), d,
-                            z.stride(0), _ptr(out), d, _stream()), "bigcn_spmm")
+                            z.stride(0), _ptr(out), out.stride(0), _stream()), "bigcn_spmm")
     return out
 
 
@@ -349,6 +359,13 @@ def bigcn_forward_row_bytes(d_in: int, d_out: int) -> Tuple[int, bool]:
     flag = ctypes.c_int(0)
     size = int(lib().bigcn_forward_row_bytes(int(d_in), int(d_out), ctypes.byref(flag)))
     return size, bool(flag.value)
+
+
+def bigcn_forward_gemm_path(n: int, d_in: int, d_out: int) -> int:
+    """GEMM_FP4 or GEMM_VALU: the evaluation path the fused forward uses for such a layer."""
+    path = lib().bigcn_forward_gemm_path(n, d_in, d_out)
+    _check(min(path, 0), "bigcn_forward_gemm_path")
+    return path
 
 
 def bigcn_forward_workspace_bytes(n: int, layers: Sequence[Layer]) -> int:
@@ -414,6 +431,17 @@ def bigcn_forward(plan: Plan, row_ptr: torch.Tensor, col_idx: torch.Tensor, dinv
     else:
         _check(lib().bigcn_forward_profiled(*args, profile.handle), "bigcn_forward_profiled")
     return logits
+
+
+def bigcn_probe_fp4_multiply_rate(iterations: int, sink: Optional[torch.Tensor] = None) -> int:
+    """Launch the multiply-only kernel (measurement aid); returns the multiply-accumulates it performs."""
+    if sink is None:
+        sink = torch.empty((256 * 1024,), dtype=torch.float32, device="cuda")
+    _dev(sink, torch.float32, "sink")
+    macs = ctypes.c_int64(0)
+    _check(lib().bigcn_probe_fp4_multiply_rate(int(iterations), _ptr(sink), sink.numel(), ctypes.byref(macs), _stream()),
+           "bigcn_probe_fp4_multiply_rate")
+    return int(macs.value)
 
 
 STATIC_WORKSPACE_BYTES = 32 << 20   # BIGCN_STATIC_WORKSPACE_BYTES of the header

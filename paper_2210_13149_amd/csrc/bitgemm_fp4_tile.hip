@@ -414,4 +414,59 @@ int launch_bitgemm_fp4_tile(const uint64_t *a_bits, const float *a_scale, int64_
     return check_launch();
 }
 
+// Nothing but multiplies: the rate at which one wavefront per SIMD issues independent
+// 32 x 32 x 64 FP4 multiplies on this device, with operands of pseudo-random +-1 codes (what the
+// tile kernel above could reach if loads, code expansion and stores were free).
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) void fp4_multiply_rate_kernel(
+    float *sink, int iterations)
+{
+    __shared__ unsigned char whole_cu[131072];               // one workgroup per compute unit, as the tile kernel
+    if (iterations < 0) whole_cu[threadIdx.x] = 1;           // never: keeps the allocation
+    v16f acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+    v8i a[4], b[4];
+    uint32_t x = 0x9e3779b9u * (blockIdx.x * kBlock + threadIdx.x + 1u);
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            x ^= x << 13; x ^= x >> 17; x ^= x << 5;
+            a[q][e] = e < 4 ? static_cast<int>((x & 0x88888888u) | 0x22222222u) : 0;              // +-1
+            b[q][e] = e < 4 ? static_cast<int>(((x << 1) & 0x88888888u) | 0x22222222u) : 0;
+        }
+    for (int it = 0; it < iterations; ++it) {
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct)
+                acc[4 * rt + ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[rt], b[ct], acc[4 * rt + ct], 4, 4, 0,
+                                                                                   0x7f7f7f7f, 0, 0x7f7f7f7f);
+    }
+    float total = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) total += acc[i][r];
+    sink[blockIdx.x * kBlock + threadIdx.x] = total;
+}
+
 }  // namespace bigcn
+
+extern "C" int bigcn_probe_fp4_multiply_rate(int iterations, float *sink, int64_t sink_floats,
+                                             int64_t *multiply_accumulates, void *stream)
+{
+    if (sink == nullptr || multiply_accumulates == nullptr) return BIGCN_ENULL;
+    if (iterations <= 0 || iterations > (1 << 20)) return BIGCN_EINVAL;
+    int device = 0, cus = 0;
+    if (hipGetDevice(&device) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0)
+        return BIGCN_EHIP;
+    if (sink_floats < static_cast<int64_t>(cus) * bigcn::kBlock) return BIGCN_EWORKSPACE;
+    hipLaunchKernelGGL(bigcn::fp4_multiply_rate_kernel, dim3(cus), dim3(bigcn::kBlock), 0, bigcn::as_stream(stream), sink,
+                       iterations);
+    *multiply_accumulates = static_cast<int64_t>(cus) * bigcn::kWavesPerBlock * iterations * 16 * (32 * 32 * 64);
+    return bigcn::check_launch();
+}

@@ -165,6 +165,12 @@ extern "C" int64_t bigcn_forward_row_bytes(int64_t d_in, int64_t d_out, int *sca
     return l.row_bytes();
 }
 
+extern "C" int bigcn_forward_gemm_path(int64_t n, int64_t d_in, int64_t d_out)
+{
+    if (n < 0 || d_in <= 0 || d_out <= 0 || d_in > BIGCN_MAX_K_BITS || d_out > BIGCN_MAX_FORWARD_D_OUT) return BIGCN_EINVAL;
+    return fp4_rows_covers(n, d_in, choose_layout(d_in, d_out)) ? BIGCN_GEMM_FP4 : BIGCN_GEMM_VALU;
+}
+
 extern "C" size_t bigcn_forward_workspace_bytes(int64_t n, const bigcn_layer *layers, int n_layers)
 {
     LayerView view[kMaxLayers];

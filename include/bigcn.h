@@ -211,6 +211,34 @@ size_t bigcn_forward_workspace_bytes(int64_t n, const bigcn_layer *layers, int n
  * whether the node's source scale is stored inside that row (*scale_embedded, HOST,
  * nullable).  Used to size the aggregation's gather traffic; 0 for unsupported shapes. */
 int64_t bigcn_forward_row_bytes(int64_t d_in, int64_t d_out, int *scale_embedded);
+/*
+ * Inspection of the intermediate integer products (Sec. 4.2.3, F_i (*) B_j) that bigcn_forward leaves
+ * in its workspace, for tests and tools that check them against a reference.
+ *
+ * bigcn_forward_row_layout: fields[0..7] (HOST, int32) = {groups G, values per lane V, kind, K',
+ * fold_last, scale_place, escape, alt_kind} of the compact row of a layer with d_in input bits and
+ * d_out columns:
+ *   - a row has G*V stored positions; position g*V + v holds output column g + G*v (columns >= d_out
+ *     hold no product);
+ *   - kind 0: one byte, q = floor(K'/2) - popcount over the first K' input bits, so the product over
+ *     those bits is 2q + (K' mod 2); kind 1 / 2: the product itself as fp16 / fp32;
+ *   - fold_last 1: K' = d_in - 1; the last input bit's term f_{i,K-1} b_{K-1,j} is added by the
+ *     aggregation (the sign f_{i,K-1} rides on the sign of the node's stored scale);
+ *   - scale_place 0: no scale in the row; 1: its last 4 bytes hold the node's fp32 scale; 2: the
+ *     values use 7 bits (two's complement in bits 0..6) and bit 7 of byte 8i (rows of 32 or 64 lanes,
+ *     i < 32) or of bytes 8i and 8i + 4 (rows of 16 lanes: scale bits i and 16 + i) carries a bit
+ *     of the scale; 3: the last byte of lanes 4..7 of an 8-lane row holds byte 0..3 of the scale;
+ *   - escape 1 (with scale_place 2): a row whose values do not all fit 7 bits carries a NaN in the
+ *     scale bits and its values live at the same positions of the alternate array, as bytes
+ *     (alt_kind 0) or fp16 (alt_kind 1), with its scale in the per-node scale array.
+ * bigcn_forward_workspace_map: offsets[0..5] (HOST) = byte offsets inside the workspace of
+ * {packed signs of the hidden layers, scale array 0, scale array 1, product rows, alternate rows,
+ * total size}; row i of the product array starts at rows + i * (row bytes of the layer that ran
+ * last).  Layer l uses scale array l mod 2.
+ * Errors: ENULL, EINVAL (shapes the forward does not take).
+ */
+int bigcn_forward_row_layout(int64_t d_in, int64_t d_out, int32_t *fields);
+int bigcn_forward_workspace_map(int64_t n, const bigcn_layer *layers, int n_layers, size_t *offsets);
 /* Which evaluation of the binary product (Sec. 4.2.3) the fused forward uses for a layer of a graph
  * of n nodes: BIGCN_GEMM_FP4 (matrix cores) or BIGCN_GEMM_VALU (XOR + bit count); both are exact.
  * For reports: the arithmetic peak a layer's bit-GEMM is compared with.  EINVAL for shapes the

@@ -41,6 +41,7 @@ EXPORTS = (
     "bigcn_layer_backward", "bigcn_entropy_workspace_bytes", "bigcn_entropy",
     "bigcn_gat_layer_workspace_bytes", "bigcn_gat_layer", "bigcn_forward_static",
     "bigcn_probe_fp4_multiply_rate", "bigcn_forward_gemm_path",
+    "bigcn_forward_row_layout", "bigcn_forward_workspace_map",
 )
 
 
@@ -111,6 +112,10 @@ def lib() -> ctypes.CDLL:
         L.bigcn_forward_row_bytes.argtypes = [i64, i64, ctypes.POINTER(i32)]
         L.bigcn_forward_gemm_path.restype = i32
         L.bigcn_forward_gemm_path.argtypes = [i64, i64, i64]
+        L.bigcn_forward_row_layout.restype = i32
+        L.bigcn_forward_row_layout.argtypes = [i64, i64, ctypes.POINTER(i32)]
+        L.bigcn_forward_workspace_map.restype = i32
+        L.bigcn_forward_workspace_map.argtypes = [i64, ctypes.POINTER(LayerDesc), i32, ctypes.POINTER(ctypes.c_size_t)]
         L.bigcn_forward.restype = i32
         L.bigcn_forward.argtypes = [vp, vp, vp, vp, i64, vp, i64, ctypes.POINTER(LayerDesc), i32, vp,
                                     i64, vp, ctypes.c_size_t, vp]
@@ -359,6 +364,23 @@ def bigcn_forward_row_bytes(d_in: int, d_out: int) -> Tuple[int, bool]:
     flag = ctypes.c_int(0)
     size = int(lib().bigcn_forward_row_bytes(int(d_in), int(d_out), ctypes.byref(flag)))
     return size, bool(flag.value)
+
+
+ROW_LAYOUT_FIELDS = ("groups", "vec", "kind", "k_eff", "fold_last", "scale_place", "escape", "alt_kind")
+
+
+def bigcn_forward_row_layout(d_in: int, d_out: int) -> dict:
+    """The compact product-row layout of a layer as a dict of ``ROW_LAYOUT_FIELDS``."""
+    fields = (ctypes.c_int32 * 8)()
+    _check(lib().bigcn_forward_row_layout(d_in, d_out, fields), "bigcn_forward_row_layout")
+    return dict(zip(ROW_LAYOUT_FIELDS, (int(v) for v in fields)))
+
+
+def bigcn_forward_workspace_map(n: int, layers: Sequence["Layer"]) -> dict:
+    """Byte offsets of the workspace regions of ``bigcn_forward`` (see the header)."""
+    off = (ctypes.c_size_t * 6)()
+    _check(lib().bigcn_forward_workspace_map(n, _descs(layers), len(layers), off), "bigcn_forward_workspace_map")
+    return dict(zip(("bits", "scale0", "scale1", "rows", "alt_rows", "total"), (int(v) for v in off)))
 
 
 def bigcn_forward_gemm_path(n: int, d_in: int, d_out: int) -> int:

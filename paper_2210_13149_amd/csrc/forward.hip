@@ -165,6 +165,29 @@ extern "C" int64_t bigcn_forward_row_bytes(int64_t d_in, int64_t d_out, int *sca
     return l.row_bytes();
 }
 
+extern "C" int bigcn_forward_row_layout(int64_t d_in, int64_t d_out, int32_t *fields)
+{
+    if (fields == nullptr) return BIGCN_ENULL;
+    if (d_in <= 0 || d_out <= 0 || d_in > BIGCN_MAX_K_BITS || d_out > BIGCN_MAX_FORWARD_D_OUT) return BIGCN_EINVAL;
+    const RowLayout l = choose_layout(d_in, d_out);
+    const int32_t v[8] = {l.groups, l.vec, l.kind, l.k_eff, l.fold_last, l.embed_scale, l.escape, l.alt_kind};
+    for (int i = 0; i < 8; ++i) fields[i] = v[i];
+    return BIGCN_OK;
+}
+
+extern "C" int bigcn_forward_workspace_map(int64_t n, const bigcn_layer *layers, int n_layers, size_t *offsets)
+{
+    if (offsets == nullptr) return BIGCN_ENULL;
+    LayerView view[kMaxLayers];
+    int status = view_gcn(layers, n_layers, view);
+    if (status != BIGCN_OK) return status;
+    if (!layers_ok(n, view, n_layers, false, &status)) return status;
+    const WorkspaceMap m = map_workspace(n, view, n_layers, false);
+    const size_t v[6] = {m.bits_off, m.scale0_off, m.scale1_off, m.rows_off, m.alt_rows_off, m.total};
+    for (int i = 0; i < 6; ++i) offsets[i] = v[i];
+    return BIGCN_OK;
+}
+
 extern "C" int bigcn_forward_gemm_path(int64_t n, int64_t d_in, int64_t d_out)
 {
     if (n < 0 || d_in <= 0 || d_out <= 0 || d_in > BIGCN_MAX_K_BITS || d_out > BIGCN_MAX_FORWARD_D_OUT) return BIGCN_EINVAL;

@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import assert_close, compare_forward_layerwise, to_device
+from helpers import assert_close, close, compare_forward_layerwise, compare_forward_teacher_forced, to_device
 from workloads import get_config, make_workload, scaled_config
 
 pytestmark = pytest.mark.gpu
@@ -65,11 +65,13 @@ def gpu_prefix_runner(B, work):
 def test_forward_matches_oracle(B, name, n_scaled):
     cfg = get_config(name) if n_scaled is None else scaled_config(name, n_scaled)
     work = make_workload(cfg)
+    teacher = compare_forward_teacher_forced(work, calibration_spec(work), gpu_prefix_runner(B, work))
+    assert all(t['rows_compared'] == work.n for t in teacher)
     stats = compare_forward_layerwise(work, calibration_spec(work), gpu_prefix_runner(B, work))
     print(name, stats)
     # a legal sign flip removes its two-hop neighbourhood from the comparison of later layers;
     # most rows must still take part in the comparison of the logits
-    assert stats[-1]["rows_compared"] >= 0.5 * work.n
+    assert stats[-1]["rows_compared"] >= 0.9 * work.n
 
 
 def test_forward_without_standardisation_and_repeatability(B):
@@ -77,7 +79,10 @@ def test_forward_without_standardisation_and_repeatability(B):
     work = make_workload(scaled_config("c5", 5000))
     bn = [None] * work.config.n_layers
     run = gpu_prefix_runner(B, work)
+    teacher = compare_forward_teacher_forced(work, bn, gpu_prefix_runner(B, work))
+    assert all(t["rows_compared"] == work.n for t in teacher)
     stats = compare_forward_layerwise(work, bn, run)
+    # mean degree 50 on 5000 nodes: one legal sign flip reaches a quarter of the graph in two hops
     assert stats[-1]["rows_compared"] >= 0.5 * work.n
     a, b = run(work.config.n_layers, bn), run(work.config.n_layers, bn)
     assert np.array_equal(a, b)
@@ -93,9 +98,12 @@ def test_bigcn_model_wrapper_reuses_buffers(B):
     first = model.forward(dx).clone()
     second = model.forward(dx)
     assert torch.equal(first, second) and second.data_ptr() == model.logits.data_ptr()
+    # the wrapper is the plain entry point on buffers it keeps: same bits as bigcn_forward, whose
+    # result the layer-by-layer comparisons of this file hold to the oracle
+    direct = B.bigcn_forward(model.plan, drp, dci, model.dinv_sqrt, dx, model.layers)
+    assert torch.equal(first, direct)
     ref, _ = oracle.forward(work.row_ptr, work.col_idx, work.x, work.weights, bn=bn)
-    ok = np.abs(first.cpu().numpy() - ref) <= 1e-5 * np.abs(ref) + 1e-6
-    assert ok.mean() > 0.9
+    assert close(first.cpu().numpy(), ref).all(axis=1).mean() >= 0.99
 
 
 def test_forward_layer_chain_equals_separate_kernels(B):
@@ -213,6 +221,8 @@ def test_rows_outside_seven_bits_in_a_hidden_layer(B, d_hidden, d_next, n):
     assert np.abs(recs[1]["acc"]).max() < 128                 # every product of the plain model fits 7 bits
     del recs
     for work in (with_rows, without):
+        teacher = compare_forward_teacher_forced(work, [None] * 3, gpu_prefix_runner(B, work), own_sum_bound=True)
+        assert all(t['rows_compared'] == work.n for t in teacher)
         stats = compare_forward_layerwise(work, [None] * 3, gpu_prefix_runner(B, work), cancellation_aware=True)
         assert stats[1]["rows_compared"] >= 0.9 * n
     # one set of buffers, alternating models
@@ -256,6 +266,8 @@ def _extreme_products(B, d_in, d_hidden, n=400, n_edges=3000, planted=120):
     bn = [None, None]
     _, recs = oracle.forward(rp, ci, x, [w0, w1], bn=bn, keep_trace=True)
     assert recs[0]["acc"].max() == d_in and recs[0]["acc"].min() == -d_in
+    teacher = compare_forward_teacher_forced(work, bn, gpu_prefix_runner(B, work), own_sum_bound=True)
+    assert all(t['rows_compared'] == work.n for t in teacher)
     stats = compare_forward_layerwise(work, bn, gpu_prefix_runner(B, work), cancellation_aware=True)
     assert stats[-1]["rows_compared"] >= 0.5 * n
 
@@ -290,6 +302,8 @@ def test_forward_on_degenerate_graphs_and_extreme_widths(B, kind, dims):
     cfg = WorkloadConfig(kind, "none", n, (ci.size - n) // 2, 2.0, tuple(dims), "normal", 1.0, "first", 0)
     work = Workload(cfg, rp, ci, x, weights)
     bn = [None] * (len(dims) - 1)
+    teacher = compare_forward_teacher_forced(work, bn, gpu_prefix_runner(B, work), own_sum_bound=True)
+    assert all(t['rows_compared'] == work.n for t in teacher)
     stats = compare_forward_layerwise(work, bn, gpu_prefix_runner(B, work), cancellation_aware=True)
     assert stats[0]["rows_compared"] == n
     if kind == "isolated":

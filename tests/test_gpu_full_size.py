@@ -14,7 +14,7 @@ import pytest
 
 import oracle
 
-from helpers import assert_close, compare_forward_layerwise, to_device
+from helpers import assert_close, compare_forward_layerwise, compare_forward_teacher_forced, to_device
 from test_gpu_forward import calibration_spec, gpu_prefix_runner
 from workloads import make_workload
 
@@ -46,12 +46,16 @@ def test_full_size_forward_matches_oracle(B, name):
     work = make_workload(name)
     say(f"{name}: {work.n} nodes, {work.nnz} stored entries")
     run = gpu_prefix_runner(B, work)
+    teacher = compare_forward_teacher_forced(work, calibration_spec(work), gpu_prefix_runner(B, work), log=say)
+    assert all(t['rows_compared'] == work.n for t in teacher)
     stats = compare_forward_layerwise(work, calibration_spec(work), run, log=say)
     say(f"{name}: {stats}")
     print(name, stats)
-    # every layer compared on at least half of the nodes, the first on all of them
+    # free-running comparison: the first layer on all nodes, later layers on the nodes that no legal
+    # sign flip reaches (observed: c4 all, c5 84 % of the logits); the teacher-forced comparison
+    # above covers every row of every layer
     assert stats[0]["rows_compared"] == work.n
-    assert all(s["rows_compared"] >= 0.5 * work.n for s in stats)
+    assert all(s["rows_compared"] >= 0.75 * work.n for s in stats)
     # at most a few in a million hidden activations may fall on the other side of a threshold
     for s, d in zip(stats[:-1], work.config.dims[1:-1]):
         assert s["sign_flips"] <= 5e-6 * work.n * d + 5
@@ -69,11 +73,13 @@ def test_full_size_sage_forward_matches_oracle(B, name):
     work = make_workload(name)
     say(f"{name}: {work.n} nodes, {work.nnz} stored entries")
     run = sage_prefix_runner(B, work)
+    teacher = compare_forward_teacher_forced(work, ["calibrate"] * work.config.n_layers, sage_prefix_runner(B, work), log=say)
+    assert all(t['rows_compared'] == work.n for t in teacher)
     stats = compare_forward_layerwise(work, ["calibrate"] * work.config.n_layers, run, log=say)
     say(f"{name}: {stats}")
     print(name, stats)
     assert stats[0]["rows_compared"] == work.n
-    assert all(s["rows_compared"] >= 0.5 * work.n for s in stats)
+    assert all(s["rows_compared"] >= 0.75 * work.n for s in stats)
     for s, d in zip(stats[:-1], work.config.dims[1:-1]):
         assert s["sign_flips"] <= 5e-6 * work.n * d + 5
 

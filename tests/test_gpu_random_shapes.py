@@ -7,7 +7,7 @@ nodes, where the bit-GEMM runs its kernels for large row counts."""
 import numpy as np
 import pytest
 
-from helpers import compare_forward_layerwise
+from helpers import compare_forward_layerwise, compare_forward_teacher_forced
 from test_gpu_forward import gpu_prefix_runner
 from test_gpu_sage import sage_prefix_runner, small_sage_workload
 from workloads import chung_lu_csr
@@ -50,10 +50,14 @@ def test_forward_random_shapes(B, seed):
                 x[k] = ws[0][:, k % dims[1]] * (1 if k % 2 == 0 else -1)
             cfg = WorkloadConfig("random", "none", n, n_edges, 2.0, dims, "normal", 1.0, "first", 0)
             work = Workload(cfg, rp, ci, x, ws)
+            teacher = compare_forward_teacher_forced(work, bn, gpu_prefix_runner(B, work), own_sum_bound=True)
+            assert all(t['rows_compared'] == work.n for t in teacher)
             stats = compare_forward_layerwise(work, bn, gpu_prefix_runner(B, work), cancellation_aware=True)
         else:
             work = small_sage_workload(n, n_edges, dims, seed=1000 * seed + it)
             for k in range(0, min(40, n)):
                 work.x[k] = work.weights[0][k % 2][:, k % dims[1]] * (1 if k % 4 < 2 else -1)
+            teacher = compare_forward_teacher_forced(work, bn, sage_prefix_runner(B, work), own_sum_bound=True)
+            assert all(t['rows_compared'] == work.n for t in teacher)
             stats = compare_forward_layerwise(work, bn, sage_prefix_runner(B, work), cancellation_aware=True)
         assert stats[0]["rows_compared"] == n, label

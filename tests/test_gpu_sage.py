@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import compare_forward_layerwise, to_device
+from helpers import compare_forward_layerwise, compare_forward_teacher_forced, to_device
 from workloads import chung_lu_csr, make_workload, scaled_config
 from workloads.build import Workload
 from workloads.configs import WorkloadConfig
@@ -101,7 +101,7 @@ def test_sage_forward_matches_oracle(B, name, n_scaled):
     stats = compare_forward_layerwise(work, bn, sage_prefix_runner(B, work))
     print(name, stats)
     assert stats[0]["rows_compared"] == work.n
-    assert stats[-1]["rows_compared"] >= 0.5 * work.n
+    assert stats[-1]["rows_compared"] >= 0.9 * work.n
 
 
 # d_in / d_out pairs chosen to reach: one-byte rows with and without the embedded scale (in the
@@ -161,6 +161,8 @@ def _sage_rows_that_do_not_fit(B, d_in, d_hidden, n, n_edges):
     acc = oracle.sign_matmul(sign, bt)
     assert acc.max() == d_in and acc.min() == -d_in
     for bn in ([None, None], ["calibrate", "calibrate"]):
+        teacher = compare_forward_teacher_forced(work, bn, sage_prefix_runner(B, work), own_sum_bound=True)
+        assert all(t['rows_compared'] == work.n for t in teacher)
         stats = compare_forward_layerwise(work, bn, sage_prefix_runner(B, work), cancellation_aware=True)
         assert stats[0]["rows_compared"] == n and stats[-1]["rows_compared"] >= 0.5 * n
         if n > 10000:
@@ -188,6 +190,8 @@ def test_sage_rows_outside_seven_bits_in_a_hidden_layer(B, d_hidden, n):
         bt, _ = oracle.binarize_weight(w)
         acc = oracle.sign_matmul(sign, bt)
         assert acc.max() == d_hidden and acc.min() == -d_hidden
+    teacher = compare_forward_teacher_forced(work, [None] * 3, sage_prefix_runner(B, work), own_sum_bound=True)
+    assert all(t['rows_compared'] == work.n for t in teacher)
     stats = compare_forward_layerwise(work, [None] * 3, sage_prefix_runner(B, work), cancellation_aware=True)
     assert stats[1]["rows_compared"] >= 0.9 * n
 
@@ -220,8 +224,10 @@ def test_sage_model_wrapper_and_error_paths(B):
     first = model.forward(dx).clone()
     second = model.forward(dx)
     assert torch.equal(first, second) and second.data_ptr() == model.out.data_ptr()
+    direct = B.bigcn_sage_forward(model.plan, drp, dci, model.inv_deg, dx, model.layers)
+    assert torch.equal(first, direct)          # the wrapper is the plain entry point on kept buffers
     ok = np.abs(first.cpu().numpy() - ref) <= 1e-5 * np.abs(ref) + 1e-6
-    assert ok.mean() > 0.9
+    assert ok.all(axis=1).mean() >= 0.99
     # workspace too small / wrong layer chain are reported, not executed
     with pytest.raises(B.BigcnError) as err:
         B.bigcn_sage_forward(model.plan, drp, dci, model.inv_deg, dx, model.layers,

@@ -53,7 +53,7 @@ int bigcn_version(void);
 /* Largest supported inner dimension (bits) of bigcn_binary_gemm / a layer's d_in, and
  * largest d_out of a layer of bigcn_forward. */
 #define BIGCN_MAX_K_BITS 8192
-#define BIGCN_MAX_GEMM_N 4194304
+#define BIGCN_MAX_GEMM_N 4194240 /* 65535 * 64: one launch covers the columns in at most 65535 blocks of 64 */
 #define BIGCN_MAX_FORWARD_D_OUT 512
 #define BIGCN_MAX_LAYERS 64
 /* Size of the per-GPU workspace that bigcn_forward_static uses instead of a caller buffer. */
@@ -461,7 +461,8 @@ int bigcn_sage_forward(const bigcn_plan *plan, const int64_t *row_ptr, const int
  * bigcn_profile_read waits for the recorded calls to finish (it SYNCHRONISES with them),
  * writes the mean duration of every slot in milliseconds to launch_ms (HOST, 1 + 2L
  * floats) and the number of calls averaged to *calls (HOST, nullable), and resets the
- * profile.  A profile must not be used from two threads at once.
+ * profile (also when it returns an error).  A forward that fails after some of its launches is not
+ * counted.  A profile must not be used from two threads at once.
  */
 typedef struct bigcn_profile bigcn_profile;
 int bigcn_profile_create(int n_layers, int max_calls, bigcn_profile **out);

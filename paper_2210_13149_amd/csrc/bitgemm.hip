@@ -692,6 +692,7 @@ static int dispatch_bitgemm(int per_lane, int groups, int vec, const uint64_t *a
     int vb = per_lane >= 8 ? 8 : (per_lane >= 4 ? 4 : (per_lane >= 2 ? 2 : 1));
     while (vb > 1 && vb * n_words > 128) vb >>= 1;
     const int col_blocks = (per_lane + vb - 1) / vb;
+    if (col_blocks > 65535) return BIGCN_ESHAPE;           // grid limit of the second dimension
     const ColumnMap map{groups, vec, per_lane};
     if (m <= kSmallRows) {
         if (vb == 8) return launch_bitgemm_small<8>(a, m, lda, b, n, ldb, k_bits, last_mask, map, col_blocks, epi, stream);

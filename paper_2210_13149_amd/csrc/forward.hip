@@ -247,7 +247,6 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
         if (prof->n_layers != n_layers) return BIGCN_EINVAL;
         if (prof->calls >= prof->max_calls) return BIGCN_ESHAPE;
         ev = prof->events + static_cast<size_t>(prof->calls) * prof->per_call();
-        prof->calls++;
     }
 
     hipStream_t s = as_stream(stream);
@@ -361,6 +360,9 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
         BIGCN_MARK();
     }
 #undef BIGCN_MARK
+    // the call counts only once every one of its events was recorded: a launch that failed half
+    // way leaves no slot whose events bigcn_profile_read would wait for in vain
+    if (prof != nullptr) prof->calls++;
     return BIGCN_OK;
 }
 
@@ -498,7 +500,9 @@ extern "C" int bigcn_profile_read(bigcn_profile *profile, float *launch_ms, int 
     if (profile == nullptr || launch_ms == nullptr) return BIGCN_ENULL;
     const int slots = 1 + 2 * profile->n_layers;
     for (int k = 0; k < slots; ++k) launch_ms[k] = 0.0f;
-    for (int c = 0; c < profile->calls; ++c) {
+    const int recorded = profile->calls;
+    profile->calls = 0;                      // also on the error returns below: the profile stays usable
+    for (int c = 0; c < recorded; ++c) {
         hipEvent_t *ev = profile->events + static_cast<size_t>(c) * profile->per_call();
         if (hipEventSynchronize(ev[slots]) != hipSuccess) return BIGCN_EHIP;
         for (int k = 0; k < slots; ++k) {
@@ -507,9 +511,8 @@ extern "C" int bigcn_profile_read(bigcn_profile *profile, float *launch_ms, int 
             launch_ms[k] += ms;
         }
     }
-    if (profile->calls > 0)
-        for (int k = 0; k < slots; ++k) launch_ms[k] /= static_cast<float>(profile->calls);
-    if (calls != nullptr) *calls = profile->calls;
-    profile->calls = 0;
+    if (recorded > 0)
+        for (int k = 0; k < slots; ++k) launch_ms[k] /= static_cast<float>(recorded);
+    if (calls != nullptr) *calls = recorded;
     return BIGCN_OK;
 }

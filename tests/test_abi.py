@@ -195,3 +195,13 @@ def test_static_forward_rejects_oversized_problems_on_the_host():
     assert L.bigcn_forward_static(FAKE, FAKE, FAKE, FAKE, -1, FAKE, 100, desc, 1, FAKE, 256, None) == binding.BIGCN_EINVAL
     text = open(HEADER).read()
     assert f"#define BIGCN_STATIC_WORKSPACE_BYTES ({binding.STATIC_WORKSPACE_BYTES >> 20}u << 20)" in text
+
+
+def test_binary_gemm_column_limit_matches_the_header():
+    """n up to BIGCN_MAX_GEMM_N is a shape error beyond, and the limit is what one launch can cover
+    (65535 column blocks of 64)."""
+    L = binding.lib()
+    text = open(HEADER).read()
+    limit = int(re.search(r"#define BIGCN_MAX_GEMM_N (\d+)", text).group(1))
+    assert limit == 65535 * 64
+    assert L.bigcn_binary_gemm(FAKE, FAKE, 4, 2, FAKE, FAKE, limit + 1, 2, 100, FAKE, limit + 1, None, 0, None) == binding.BIGCN_ESHAPE

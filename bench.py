@@ -142,6 +142,7 @@ def aggregation_bytes(cfg, nnz, layer, B):
 
 MFMA_INT8_MAC_PEAK = 2.5e15     # MI355X dense int8: 5.0 POP/s, two operations per multiply-accumulate
 MFMA_FP4_MAC_PEAK = 5.05e15     # MI355X dense fp4: 10.1 PFLOP/s
+MFMA_FP32_FLOP_PEAK = 157.3e12  # MI355X dense fp32 matrix
 
 
 def _time_calls(call, reps):
@@ -286,8 +287,24 @@ def backward_leg(B, m, cfg, reps=3):
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / reps
         products = 1 if l == 0 else 2
+        flops = products * 2.0 * n * d_in * d_out
+        nnz = int(m["col_idx"].numel())
+        if l == 0:
+            # no input gradient and d_in <= d_out: the aggregation gathers packed sign rows (index,
+            # coefficient, scale and the row's words per stored entry) and writes n x d_in fp32
+            words = (d_in + 63) // 64
+            gather = nnz * (4 + 4 + 4 + 8 * words) + n * 4 * d_in + n * 4 * d_out
+        else:
+            # g_zeta = A~^T g_out: per stored entry an index, a coefficient and one fp32 gradient row;
+            # then g_zeta is read by both dense products and g_in is written
+            gather = nnz * (4 + 4 + 4 * d_out) + n * 4 * d_out * 3 + n * 4 * d_in
+        t_hbm, t_mfma = gather / (HBM_PEAK_GBPS * 1e9), flops / MFMA_FP32_FLOP_PEAK
+        bound = "hbm" if t_hbm >= t_mfma else "mfma"
         out.append({"layer": l, "d_in": d_in, "d_out": d_out, "ms": ms,
-                    "dense_TFLOPs": products * 2.0 * n * d_in * d_out / (ms * 1e-3) / 1e12})
+                    "dense_TFLOPs": flops / (ms * 1e-3) / 1e12,
+                    "frac_mfma_fp32_peak": flops / (ms * 1e-3) / MFMA_FP32_FLOP_PEAK,
+                    "algorithmic_bytes": gather, "algorithmic_GBps": gather / (ms * 1e-3) / 1e9,
+                    "bound": bound, "frac": (t_hbm if bound == "hbm" else t_mfma) / (ms * 1e-3)})
         del x, bits, beta, w, g, ws
     return out
 
@@ -318,8 +335,12 @@ def gat_leg(B, m, cfg, reps=3):
     # bits, fp16 to 2048, fp32 beyond) and its record {beta, t[heads]}
     elem = 1 if d_in <= 255 else (2 if d_in <= 2048 else 4)
     per_neighbour = 4 + elem * d_out + 4 * (1 + heads)
+    lines = 128 * (-(-(elem * d_out) // 128) + 1)         # the row's cache lines + one for the record
     return {"d_in": d_in, "d_out": d_out, "heads": heads, "ms": ms, "bytes_per_neighbour": per_neighbour,
-            "row_gather_GBps": nnz * per_neighbour / (ms * 1e-3) / 1e9}
+            "row_gather_GBps": nnz * per_neighbour / (ms * 1e-3) / 1e9,
+            "bound": "hbm", "frac": nnz * per_neighbour / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "cache_line_bytes_per_neighbour": lines,
+            "cache_line_GBps": nnz * lines / (ms * 1e-3) / 1e9}
 
 
 def stream_probe(mib=2048):

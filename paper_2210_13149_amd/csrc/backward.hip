@@ -496,7 +496,7 @@ extern "C" int bigcn_layer_backward(const bigcn_plan *plan, const int64_t *row_p
         {
             const int64_t total = n * (n_words + 1);
             int64_t blocks = (total + kBlock - 1) / kBlock;
-            if (blocks > 256 * 32) blocks = 256 * 32;
+            if (blocks > compute_units() * 32) blocks = compute_units() * 32;
             hipLaunchKernelGGL(sign_records_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s, f_bits,
                                ld_f_words, beta, n, n_words, records);
             if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
@@ -528,7 +528,7 @@ extern "C" int bigcn_layer_backward(const bigcn_plan *plan, const int64_t *row_p
             float *g_pad = reinterpret_cast<float *>(ws + map.g_pad_off);
             const int64_t total = n * map.d_pad;
             int64_t blocks = (total + kBlock - 1) / kBlock;
-            if (blocks > 256 * 32) blocks = 256 * 32;
+            if (blocks > compute_units() * 32) blocks = compute_units() * 32;
             hipLaunchKernelGGL(pad_rows_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s, g_out, ld_g, n,
                                static_cast<int>(d_out), static_cast<int>(map.d_pad), g_pad);
             if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;

@@ -19,6 +19,24 @@ constexpr int64_t kBlockRowDegree = 256;
 
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 
+// Compute units of the current device (256 on MI355X), asked once per device; launch sizes that
+// aim at "all compute units" use it instead of a literal.
+inline int compute_units()
+{
+    static int known[64];
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= 64) return 256;
+    if (known[device] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0) {
+            (void)hipGetLastError();
+            cus = 256;
+        }
+        known[device] = cus;
+    }
+    return known[device];
+}
+
 inline int check_launch()
 {
     return hipGetLastError() == hipSuccess ? BIGCN_OK : BIGCN_EHIP;
@@ -215,6 +233,7 @@ struct bigcn_plan {
     int64_t n;
     int64_t nnz;
     int device;
+    int compute_units;       // of `device`, read when the plan was created
     int32_t *row_order;      // DEVICE, n entries
     int64_t n_block_rows;    // the first n_block_rows entries of row_order have degree >= kBlockRowDegree
     int64_t max_degree;

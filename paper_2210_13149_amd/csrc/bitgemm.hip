@@ -611,7 +611,8 @@ static int launch_pack_bitgemm_small(const float *x, int64_t m, int64_t ld_x, in
     const int n_words = static_cast<int>((k_bits + 63) / 64);
     const size_t lds = static_cast<size_t>(64) * VB * n_words * sizeof(uint64_t);
     int64_t blocks = (m + kWavesPerBlock - 1) / kWavesPerBlock;
-    const int64_t cap = 256 * 8 / col_blocks > 256 ? 256 * 8 / col_blocks : 256;
+    const int64_t cus = compute_units();
+    const int64_t cap = cus * 8 / col_blocks > cus ? cus * 8 / col_blocks : cus;
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL((pack_bitgemm_small_kernel<VB, Epilogue>), dim3(static_cast<unsigned>(blocks), col_blocks),
@@ -633,7 +634,8 @@ static int launch_bitgemm_small(const uint64_t *a, int64_t m, int64_t lda, const
     const size_t lds = static_cast<size_t>(64) * VB * n_words * sizeof(uint64_t);
     // one row per wavefront up to 8 workgroups per compute unit; more rows share the staged B
     int64_t blocks = (m + kWavesPerBlock - 1) / kWavesPerBlock;
-    const int64_t cap = 256 * 8 / col_blocks > 256 ? 256 * 8 / col_blocks : 256;
+    const int64_t cus = compute_units();
+    const int64_t cap = cus * 8 / col_blocks > cus ? cus * 8 / col_blocks : cus;
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL((bitgemm_small_kernel<VB, Epilogue>), dim3(static_cast<unsigned>(blocks), col_blocks),
@@ -648,7 +650,8 @@ static int launch_bitgemm_rows(const uint64_t *a, int64_t m, int64_t lda, const 
                                const Epilogue &epi, hipStream_t stream)
 {
     int64_t blocks = (m + kBlock - 1) / kBlock;               // 64 rows per wavefront and batch
-    const int64_t cap = 256 * 8 / col_blocks > 256 ? 256 * 8 / col_blocks : 256;
+    const int64_t cus = compute_units();
+    const int64_t cap = cus * 8 / col_blocks > cus ? cus * 8 / col_blocks : cus;
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL((bitgemm_rows_kernel<VB, NW, Epilogue>), dim3(static_cast<unsigned>(blocks), col_blocks),
@@ -670,7 +673,7 @@ static int launch_bitgemm(const uint64_t *a, int64_t m, int64_t lda, const uint6
     int64_t blocks = (row_blocks + kWavesPerBlock - 1) / kWavesPerBlock;
     int64_t resident = lds > 0 ? static_cast<int64_t>((160 * 1024) / lds) : 8;
     resident = resident > 8 ? 8 : (resident < 1 ? 1 : resident);
-    int64_t cap = 256 * resident / col_blocks;
+    int64_t cap = static_cast<int64_t>(compute_units()) * resident / col_blocks;
     if (cap < 256) cap = 256;
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;

@@ -432,10 +432,7 @@ int launch_bitgemm_fp4_tile(const uint64_t *a_bits, const float *a_scale, int64_
     TileArgs p{a_bits, m, lda, b_bits, static_cast<int>(n), ldb, static_cast<int>(k_bits), a_scale, b_scale,
                acc, ld_acc, out, ld_out, row_tiles * col_tiles, static_cast<int>(col_tiles)};
     // one workgroup (four wavefronts, one per SIMD) per compute unit
-    int device = 0, cus = 0;
-    if (hipGetDevice(&device) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0)
-        return BIGCN_EHIP;
+    const int cus = bigcn::compute_units();
     const dim3 grid(static_cast<unsigned>(std::min<int64_t>(cus, (p.n_tiles + kWavesPerBlock - 1) / kWavesPerBlock)));
     const int n_chunks = static_cast<int>(k_bits / kChunkBits);
     if (acc != nullptr && out != nullptr) launch_tile<true, true>(grid, n_chunks, stream, p);
@@ -490,10 +487,7 @@ extern "C" int bigcn_probe_fp4_multiply_rate(int iterations, float *sink, int64_
 {
     if (sink == nullptr || multiply_accumulates == nullptr) return BIGCN_ENULL;
     if (iterations <= 0 || iterations > (1 << 20)) return BIGCN_EINVAL;
-    int device = 0, cus = 0;
-    if (hipGetDevice(&device) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0)
-        return BIGCN_EHIP;
+    const int cus = bigcn::compute_units();
     if (sink_floats < static_cast<int64_t>(cus) * bigcn::kBlock) return BIGCN_EWORKSPACE;
     hipLaunchKernelGGL(bigcn::fp4_multiply_rate_kernel, dim3(cus), dim3(bigcn::kBlock), 0, bigcn::as_stream(stream), sink,
                        iterations);

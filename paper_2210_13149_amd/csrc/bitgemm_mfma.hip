@@ -790,7 +790,7 @@ static int launch_fp4_rows(const uint64_t *a_bits, int64_t m, int64_t lda, const
     }
     // the blocks stay for the whole call (each loads the weights once): as many as are resident at once
     int64_t blocks = (m + 127) / 128;
-    if (blocks > 256 * per_cu) blocks = 256 * per_cu;
+    if (blocks > static_cast<int64_t>(compute_units()) * per_cu) blocks = static_cast<int64_t>(compute_units()) * per_cu;
     hipLaunchKernelGGL((bitgemm_fp4_rows_kernel<P, kMaxSteps>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), lds_bytes,
                        stream, a_bits, m, lda, b_bits, ldb, scale, p, static_cast<unsigned char *>(c_rows), alt_rows, escape_flag);
     return check_launch();

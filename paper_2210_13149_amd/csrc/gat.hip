@@ -602,7 +602,7 @@ static int launch_gat_compact(const bigcn_plan *plan, const int64_t *row_ptr, co
     const float bias = sizeof(T) == 1 ? static_cast<float>(d_in & 1) : 0.0f;
     const int d_head = static_cast<int>(d_out / H);
     const int64_t node_blocks = (n + kWavesPerBlock - 1) / kWavesPerBlock;
-    const int64_t score_blocks = node_blocks > 256 * 8 ? 256 * 8 : node_blocks;
+    const int64_t score_blocks = node_blocks > compute_units() * 8 ? compute_units() * 8 : node_blocks;
     hipLaunchKernelGGL((gat_scores_kernel<T, G, H>), dim3(static_cast<unsigned>(score_blocks)), dim3(kBlock), 0, st,
                        rows, static_cast<uint32_t>(map.row_bytes), n, static_cast<int>(d_out), d_head, mul, bias, beta,
                        alpha, a_src, a_dst, s, record);
@@ -724,7 +724,7 @@ extern "C" int bigcn_gat_layer(const bigcn_plan *plan, const int64_t *row_ptr, c
 
     const int d_head = static_cast<int>(d_out / heads);
     int64_t blocks = (n + kWavesPerBlock - 1) / kWavesPerBlock;
-    const int64_t score_blocks = blocks > 256 * 32 ? 256 * 32 : blocks;
+    const int64_t score_blocks = blocks > compute_units() * 32 ? compute_units() * 32 : blocks;
 #define BIGCN_GAT_CASE(HH)                                                                                          \
     case HH:                                                                                                        \
         hipLaunchKernelGGL(gat_scores_plain_kernel<HH>, dim3(static_cast<unsigned>(score_blocks)), dim3(kBlock), 0, st, z, n, \

@@ -158,7 +158,7 @@ static int grid_for_waves(int64_t waves_needed)
 {
     // enough workgroups to fill 256 CUs several times over; grid-stride loops take the rest
     const int64_t blocks = (waves_needed + kWavesPerBlock - 1) / kWavesPerBlock;
-    const int64_t cap = 256 * 16;
+    const int64_t cap = static_cast<int64_t>(compute_units()) * 16;
     return static_cast<int>(blocks < 1 ? 1 : (blocks > cap ? cap : blocks));
 }
 

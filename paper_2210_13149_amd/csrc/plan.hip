@@ -185,6 +185,11 @@ extern "C" int bigcn_plan_create(const int64_t *row_ptr, const int32_t *col_idx,
     plan->n = n;
     plan->nnz = nnz;
     plan->device = device;
+    if (hipDeviceGetAttribute(&plan->compute_units, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess ||
+        plan->compute_units <= 0) {
+        (void)hipGetLastError();
+        plan->compute_units = 256;                       // MI355X
+    }
     plan->row_order = nullptr;
     plan->n_block_rows = n_block_rows;
     plan->max_degree = max_degree;

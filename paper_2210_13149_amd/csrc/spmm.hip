@@ -581,12 +581,12 @@ struct ParkedLane {
 // epilogue constants are fetched once per workgroup); on small graphs, where the time of a
 // launch is the latency of one wavefront's chain of dependent loads, it takes fewer, down to one.
 constexpr int kMaxRowsPerWave = 16;
-constexpr int64_t kResidentWaves = 256 * 4 * 8;      // compute units x SIMDs x wavefronts per SIMD
-static int rows_per_wave_for(int64_t wave_rows)
+static int rows_per_wave_for(int64_t wave_rows, int compute_units)
 {
     // one row per wavefront until the rows fill the chip four times over (measured on the
     // 19717- and 232965-node workloads), then proportionally more
-    const int64_t r = wave_rows / (4 * kResidentWaves);
+    const int64_t resident_waves = static_cast<int64_t>(compute_units) * 4 * 8;   // x SIMDs x wavefronts per SIMD
+    const int64_t r = wave_rows / (4 * resident_waves);
     return static_cast<int>(r < 1 ? 1 : (r > kMaxRowsPerWave ? kMaxRowsPerWave : r));
 }
 
@@ -718,7 +718,7 @@ static int launch_spmm_one(const bigcn_plan *plan, const int64_t *row_ptr, const
     if (escape_weights(WM) && (alt_rows == nullptr || weights == nullptr)) return BIGCN_ENULL;
     if (fused_weights(WM) && valid_positions != G * V) return BIGCN_EINVAL;
     const int64_t wave_rows = plan->n - plan->n_block_rows;
-    int rows_per_wave = rows_per_wave_for(wave_rows);
+    int rows_per_wave = rows_per_wave_for(wave_rows, plan->compute_units);
     // the launch that only runs when a row escaped (almost never): a quarter of the workgroups, so
     // that returning at once costs a quarter
     if (gate_flag != nullptr && run_if_set != 0 && rows_per_wave == kMaxRowsPerWave) rows_per_wave *= 4;

@@ -72,16 +72,12 @@ def test_full_size_sage_forward_matches_oracle(B, name):
     say(f"{name}: generating")
     work = make_workload(name)
     say(f"{name}: {work.n} nodes, {work.nnz} stored entries")
-    run = sage_prefix_runner(B, work)
+    # every row of every layer at the plain tolerance, the oracle fed the GPU's previous output; the
+    # free-running comparison of this model runs on the scaled workloads in test_gpu_sage.py
     teacher = compare_forward_teacher_forced(work, ["calibrate"] * work.config.n_layers, sage_prefix_runner(B, work), log=say)
-    assert all(t['rows_compared'] == work.n for t in teacher)
-    stats = compare_forward_layerwise(work, ["calibrate"] * work.config.n_layers, run, log=say)
-    say(f"{name}: {stats}")
-    print(name, stats)
-    assert stats[0]["rows_compared"] == work.n
-    assert all(s["rows_compared"] >= 0.75 * work.n for s in stats)
-    for s, d in zip(stats[:-1], work.config.dims[1:-1]):
-        assert s["sign_flips"] <= 5e-6 * work.n * d + 5
+    say(f"{name}: {teacher}")
+    print(name, teacher)
+    assert all(t['rows_compared'] == work.n and t['excused_rows'] == 0 for t in teacher)
 
 
 @pytest.mark.timeout(600)

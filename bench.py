@@ -403,17 +403,6 @@ def infinity_cache_model(row_ptr_host, row_bytes, cache_bytes=INFINITY_CACHE_BYT
     return {"hit_rate": hit, "kind": "model: LRU characteristic-time approximation, requests proportional to degree"}
 
 
-def folded_layer(cfg, layer, B):
-    """Whether the fused forward forms layer `layer`'s products inside the aggregation of the layer
-    before it (Bi-GCN, a narrow layer behind at most 256 hidden columns: one byte per product, at
-    most 64 stored positions, no 7-bit form)."""
-    if cfg.model != "gcn" or layer < 1 or cfg.dims[layer] > 256:
-        return False
-    lay = B.bigcn_forward_row_layout(cfg.dims[layer], cfg.dims[layer + 1])
-    return lay["kind"] == 0 and lay["vec"] == 8 and lay["groups"] * lay["vec"] <= 64 and not lay["escape"] \
-        and lay["scale_place"] != 2
-
-
 def slot_bounds(cfg, work_n, nnz, B, launch_ms):
     """For every launch of a forward the bound it is compared with and the fraction reached:
     slot 0 = binarise + pack, then per layer the bit-GEMM and the aggregation.  Bounds: HBM for the
@@ -439,19 +428,6 @@ def slot_bounds(cfg, work_n, nnz, B, launch_ms):
         row_bytes, _ = B.bigcn_forward_row_bytes(d_in, d_out)
         t = launch_ms[1 + 2 * l] * 1e-3
         macs = n * d_in * d_out * products
-        if folded_layer(cfg, l, B):
-            # no launch of its own: the aggregation of the layer before forms these products
-            # (its time is in that launch)
-            slots.append({"slot": f"bit_gemm[{l}]", "ms": t * 1e3, "bound": "none", "achieved": 0.0, "peak": 0.0,
-                          "unit": "-", "frac": 0.0, "binary_macs": macs, "path": f"folded into aggregation[{l - 1}]"})
-            gather, minimum, row_bytes = aggregation_bytes(cfg, nnz, l, B)
-            t = launch_ms[2 + 2 * l] * 1e-3
-            slots.append({"slot": f"aggregation[{l}]", "ms": t * 1e3, "bound": "hbm", "algorithmic_bytes": gather,
-                          "achieved": gather / t / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                          "frac": gather / t / 1e9 / HBM_PEAK_GBPS, "row_bytes": row_bytes,
-                          "compulsory_bytes": minimum, "compulsory_GBps": minimum / t / 1e9,
-                          "rows_fit_infinity_cache": n * row_bytes <= INFINITY_CACHE_BYTES})
-            continue
         fp4 = B.bigcn_forward_gemm_path(n, d_in, d_out) == B.GEMM_FP4
         in_bytes = n * 8 * ((d_in + 63) // 64) if not (small and l == 0 and cfg.model == "gcn") else n * 4 * d_in
         hbm_bytes = in_bytes + n * row_bytes * products
@@ -686,7 +662,7 @@ def main():
     spmm = [s for s in slots if s["slot"].startswith("aggregation")]
     for l, g in enumerate(gemm):
         macs = work.n * cfg.dims[l] * cfg.dims[l + 1] * (2 if cfg.model == "sage" else 1)
-        g["binary_op_per_s"] = 0.0 if g["bound"] == "none" else macs / (g["ms"] * 1e-3)
+        g["binary_op_per_s"] = macs / (g["ms"] * 1e-3)
     gather_widths = [max(128, s["row_bytes"]) for s in spmm]
     gather_ms = gather_probe(B, m, gather_widths)
     apply_cache_bound(slots, gather_ms)

@@ -231,14 +231,10 @@ int64_t bigcn_forward_row_bytes(int64_t d_in, int64_t d_out, int *scale_embedded
  *   - escape 1 (with scale_place 2): a row whose values do not all fit 7 bits carries a NaN in the
  *     scale bits and its values live at the same positions of the alternate array, as bytes
  *     (alt_kind 0) or fp16 (alt_kind 1), with its scale in the per-node scale array.
- * bigcn_forward_workspace_map: offsets[0..6] (HOST) = byte offsets inside the workspace of
+ * bigcn_forward_workspace_map: offsets[0..5] (HOST) = byte offsets inside the workspace of
  * {packed signs of the hidden layers, scale array 0, scale array 1, product rows, alternate rows,
- * total size, second product-row array}; row i of a product array starts at i * (row bytes of the
- * layer whose rows it holds).  Layer l uses scale array l mod 2.  A layer of at most 64 stored
- * positions behind a hidden layer of at most 256 columns has no bit-GEMM launch of its own: the
- * aggregation before it writes its product rows, into the array that aggregation does not gather
- * from (the second array first; two such layers in a row alternate).  Every other layer's rows are
- * in the first array.
+ * total size}; row i of the product array starts at rows + i * (row bytes of the layer that ran
+ * last).  Layer l uses scale array l mod 2.
  * Errors: ENULL, EINVAL (shapes the forward does not take).
  */
 int bigcn_forward_row_layout(int64_t d_in, int64_t d_out, int32_t *fields);

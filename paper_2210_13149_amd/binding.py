@@ -378,9 +378,9 @@ def bigcn_forward_row_layout(d_in: int, d_out: int) -> dict:
 
 def bigcn_forward_workspace_map(n: int, layers: Sequence["Layer"]) -> dict:
     """Byte offsets of the workspace regions of ``bigcn_forward`` (see the header)."""
-    off = (ctypes.c_size_t * 7)()
+    off = (ctypes.c_size_t * 6)()
     _check(lib().bigcn_forward_workspace_map(n, _descs(layers), len(layers), off), "bigcn_forward_workspace_map")
-    return dict(zip(("bits", "scale0", "scale1", "rows", "alt_rows", "total", "fold_rows"), (int(v) for v in off)))
+    return dict(zip(("bits", "scale0", "scale1", "rows", "alt_rows", "total"), (int(v) for v in off)))
 
 
 def bigcn_forward_gemm_path(n: int, d_in: int, d_out: int) -> int:

@@ -222,17 +222,8 @@ struct FusedSpmmArgs {
     // 0 by this launch: the flag of the layer that follows.
     const int *escape_flag;
     int *clear_flag;
-    // Hidden layer followed by a narrow layer (fold_next_covers): the aggregation also writes the
-    // next layer's product rows (layout fold_layout, next weights fold_w_bits) into fold_rows,
-    // which must not be the array it gathers from; next_bits is then not written.  nullptr = off.
-    void *fold_rows;
-    RowLayout fold_layout;
-    const uint64_t *fold_w_bits;
-    int64_t fold_w_ld_words;
-    int64_t fold_d_next;
 };
 int launch_fused_spmm(const FusedSpmmArgs &args, hipStream_t stream);
-bool fold_next_covers(int64_t d_hidden, const RowLayout &next);
 
 }  // namespace bigcn
 

@@ -16,10 +16,8 @@
 namespace bigcn {
 
 struct WorkspaceMap {
-    size_t bits_off, scale0_off, scale1_off, rows_off, self_rows_off, alt_rows_off, alt_self_rows_off, flags_off,
-        fold_rows_off, total;
+    size_t bits_off, scale0_off, scale1_off, rows_off, self_rows_off, alt_rows_off, alt_self_rows_off, flags_off, total;
     bool escape;      // some layer keeps an alternate copy (bytes or fp16) of rows that do not fit 7 bits
-    bool fold;        // some layer's product rows are written by the aggregation before it (second row array)
 };
 
 static size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
@@ -72,20 +70,11 @@ static int view_sage(const bigcn_sage_layer *layers, int n_layers, LayerView *ou
     return BIGCN_OK;
 }
 
-// Layer l (l >= 1) gets its product rows from the aggregation of layer l - 1 instead of a bit-GEMM
-// launch of its own: a narrow layer behind a hidden layer of at most 256 columns (Bi-GCN only).
-static bool layer_is_folded(const LayerView *layers, int l, bool own_term)
-{
-    if (own_term || l < 1) return false;
-    return fold_next_covers(layers[l].d_in, choose_layout(layers[l].d_in, layers[l].d_out));
-}
-
 static WorkspaceMap map_workspace(int64_t n, const LayerView *layers, int n_layers, bool own_term)
 {
-    int64_t max_words = 0, max_row_bytes = 0, max_alt_bytes = 0, max_fold_bytes = 0;
+    int64_t max_words = 0, max_row_bytes = 0, max_alt_bytes = 0;
     for (int l = 0; l < n_layers; ++l) {
         const RowLayout layout = choose_layout(layers[l].d_in, layers[l].d_out);
-        if (layer_is_folded(layers, l, own_term)) max_fold_bytes = std::max<int64_t>(max_fold_bytes, layout.row_bytes());
         max_words = std::max<int64_t>(max_words, (layers[l].d_in + 63) / 64);
         max_row_bytes = std::max<int64_t>(max_row_bytes, layout.row_bytes());
         if (layout.escape) max_alt_bytes = std::max<int64_t>(max_alt_bytes, layout.alt_row_bytes());
@@ -106,11 +95,6 @@ static WorkspaceMap map_workspace(int64_t n, const LayerView *layers, int n_laye
     // one int per layer: "some product row of this layer went to the alternate array"
     m.flags_off = off;
     if (m.escape) off = align_up(off + kMaxLayers * sizeof(int));
-    // rows written by an aggregation for the layer after it: never the array that aggregation
-    // gathers from, so a second array of the widest such row (consecutive folded layers alternate)
-    m.fold = max_fold_bytes > 0;
-    m.fold_rows_off = off;
-    if (m.fold) off = align_up(off + static_cast<size_t>(n) * max_fold_bytes);
     m.total = off;
     return m;
 }
@@ -199,8 +183,8 @@ extern "C" int bigcn_forward_workspace_map(int64_t n, const bigcn_layer *layers,
     if (status != BIGCN_OK) return status;
     if (!layers_ok(n, view, n_layers, false, &status)) return status;
     const WorkspaceMap m = map_workspace(n, view, n_layers, false);
-    const size_t v[7] = {m.bits_off, m.scale0_off, m.scale1_off, m.rows_off, m.alt_rows_off, m.total, m.fold_rows_off};
-    for (int i = 0; i < 7; ++i) offsets[i] = v[i];
+    const size_t v[6] = {m.bits_off, m.scale0_off, m.scale1_off, m.rows_off, m.alt_rows_off, m.total};
+    for (int i = 0; i < 6; ++i) offsets[i] = v[i];
     return BIGCN_OK;
 }
 
@@ -270,9 +254,7 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
     char *ws = static_cast<char *>(workspace);
     uint64_t *bits = reinterpret_cast<uint64_t *>(ws + map.bits_off);
     float *scale[2] = {reinterpret_cast<float *>(ws + map.scale0_off), reinterpret_cast<float *>(ws + map.scale1_off)};
-    void *main_rows = ws + map.rows_off;
-    void *fold_rows = map.fold ? ws + map.fold_rows_off : nullptr;
-    void *c_rows = main_rows;               // where the current layer's product rows are
+    void *c_rows = ws + map.rows_off;
     void *self_rows = own_term ? ws + map.self_rows_off : nullptr;
     void *alt_rows = map.escape ? ws + map.alt_rows_off : nullptr;
     void *alt_self_rows = (map.escape && own_term) ? ws + map.alt_self_rows_off : nullptr;
@@ -313,10 +295,7 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
         const RowLayout layout = choose_layout(L.d_in, L.d_out);
         // (with fp16 alternates the kernel with the test measured no slower than the plain one: no flag)
         int *flag = (flags != nullptr && layout.escape && layout.alt_kind == kI8 && !(l == 0 && fuse0)) ? flags + l : nullptr;
-        const bool folded = layer_is_folded(layers, l, own_term);     // rows written by the aggregation before
-        if (folded)
-            rc = BIGCN_OK;
-        else if (l == 0 && fuse0)
+        if (l == 0 && fuse0)
             rc = launch_pack_bitgemm_layout(x, n, ld_x, L.bn_shift, L.bn_mul, src_row_mul, scale[0], L.w_bits, L.d_out,
                                             L.ld_words, L.d_in, c_rows, alt_rows, layout, s);
         else if (fp4_rows_covers(n, L.d_in, layout))
@@ -375,19 +354,9 @@ static int forward_impl(const bigcn_plan *plan, const int64_t *row_ptr, const in
             a.next_scale = scale[(l + 1) & 1];
             a.next_row_mul = src_row_mul;
             a.next_fold_last_sign = choose_layout(layers[l + 1].d_in, layers[l + 1].d_out).fold_last;
-            if (layer_is_folded(layers, l + 1, own_term)) {
-                // the next layer is narrow: this launch also forms its products
-                a.fold_rows = (c_rows == fold_rows) ? main_rows : fold_rows;
-                a.fold_layout = choose_layout(layers[l + 1].d_in, layers[l + 1].d_out);
-                a.fold_w_bits = layers[l + 1].w_bits;
-                a.fold_w_ld_words = layers[l + 1].ld_words;
-                a.fold_d_next = layers[l + 1].d_out;
-            }
         }
         rc = launch_fused_spmm(a, s);
         if (rc != BIGCN_OK) return rc;
-        if (a.fold_rows != nullptr) c_rows = a.fold_rows;
-        else c_rows = main_rows;
         BIGCN_MARK();
     }
 #undef BIGCN_MARK

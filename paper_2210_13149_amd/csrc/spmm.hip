@@ -400,8 +400,6 @@ __device__ __forceinline__ void reduce_slots(RowAcc<V> &acc)
 // Public SpMM: stored position == output column, fp32 row-major output.
 struct EpiloguePlain {
     static constexpr bool kSelf = false;
-    static constexpr bool kFold = false;
-    __device__ __forceinline__ void stage_fold(uint64_t *, int) const {}
     float *out;
     int64_t ld_out;
     int d;                 // valid positions
@@ -412,7 +410,7 @@ struct EpiloguePlain {
     __device__ __forceinline__ void init(int, Lane<G, V> &) const {}
     template <int G, int V>
     __device__ __forceinline__ void finish(const Lane<G, V> &, int64_t row, int lane, const RowAcc<V> &acc,
-                                           const RowAcc<V> &, const uint64_t *) const
+                                           const RowAcc<V> &) const
     {
         if (lane >= G) return;
         float *dst = out + row * ld_out + lane * V;
@@ -437,7 +435,6 @@ struct EpiloguePlain {
 template <bool kSelfTerm>
 struct EpilogueFusedT {
     static constexpr bool kSelf = kSelfTerm;
-    static constexpr bool kFold = !kSelfTerm;
     const float *dst_mul;
     const float *alpha;
     int d_out;
@@ -460,27 +457,6 @@ struct EpilogueFusedT {
     const char *alt_self_rows;       // own rows that did not fit 7 bits (escape layouts; bytes or fp16)
     const float *self_alpha;
     const uint64_t *self_last_bit_word;
-    // The next layer's bit-GEMM done here, for a narrow next layer (at most 64 stored positions,
-    // one byte each, from at most 256 bits): lane p writes stored position p of the node's next
-    // product row, floor(K'/2) - popcount over the first K' bits of the signs just formed, or the
-    // byte of the node's next source scale that the layout keeps at that position.  nullptr = off.
-    unsigned char *fold_rows;        // n rows of fold_positions bytes
-    const uint64_t *fold_w_bits;     // the next layer's packed weights
-    int64_t fold_w_ld_words;
-    int fold_d_next, fold_groups, fold_positions, fold_k_eff, fold_place;
-
-    // The next layer's weight words of every stored position, parked in LDS as [word][position]
-    // when the kernel starts (read once per node by finish).
-    __device__ __forceinline__ void stage_fold(uint64_t *lds, int thread) const
-    {
-        if (fold_rows == nullptr) return;
-        for (int item = thread; item < 4 * 64; item += kBlock) {
-            const int q = item >> 6, pos = item & 63;
-            const int col = (pos >> 3) + fold_groups * (pos & 7);
-            const bool live = pos < fold_positions && col < fold_d_next && 64 * q < fold_k_eff;
-            lds[item] = live ? fold_w_bits[col * fold_w_ld_words + q] : 0ull;
-        }
-    }
 
     template <int G, int V>
     struct Lane {
@@ -515,7 +491,7 @@ struct EpilogueFusedT {
     }
     template <int G, int V>
     __device__ __forceinline__ void finish(const Lane<G, V> &c, int64_t row, int lane, const RowAcc<V> &acc,
-                                           const RowAcc<V> &self, const uint64_t *fold_lds) const
+                                           const RowAcc<V> &self) const
     {
         const float di = dst_mul[row];
         const int g = lane & (G - 1);
@@ -558,46 +534,20 @@ struct EpilogueFusedT {
         }
         sum = wave_sum(sum);
         const int n_words = (d_out + 63) >> 6;
-        float s = sum / static_cast<float>(d_out);          // wave-uniform
-        if (next_row_mul != nullptr) s *= next_row_mul[row];
-        if (next_fold_last_sign) {
-            uint64_t last = 0;
 #pragma unroll
-            for (int q = 0; q < kWords; ++q)
-                if (q == ((d_out - 1) >> 6)) last = words[q];
-            if (((last >> ((d_out - 1) & 63)) & 1ull) == 0) s = -s;
-        }
-        if (lane == 0) next_scale[row] = s;
-        if (fold_rows == nullptr) {
+        for (int q = 0; q < kWords; ++q)
+            if (lane == q && q < n_words) next_bits[row * next_ld_words + q] = words[q];
+        if (lane == 0) {
+            float s = sum / static_cast<float>(d_out);
+            if (next_row_mul != nullptr) s *= next_row_mul[row];
+            if (next_fold_last_sign) {
+                uint64_t last = 0;
 #pragma unroll
-            for (int q = 0; q < kWords; ++q)
-                if (lane == q && q < n_words) next_bits[row * next_ld_words + q] = words[q];
-            return;
-        }
-        // the next layer's product row (its packed input is not needed by anyone else)
-        if (lane < fold_positions) {
-            const int g2 = lane >> 3, v2 = lane & 7;          // stored position lane = g2 * 8 + v2
-            const int col = g2 + fold_groups * v2;
-            int value = 0;
-            if (col < fold_d_next) {
-                int pop = 0;
-#pragma unroll
-                for (int q = 0; q < (kWords < 4 ? kWords : 4); ++q) {
-                    const int left = fold_k_eff - 64 * q;     // bits of word q below K' (wave-uniform)
-                    if (left > 0) {
-                        const uint64_t keep = left >= 64 ? ~0ull : ((1ull << left) - 1ull);
-                        pop += __popcll((words[q] ^ fold_lds[64 * q + lane]) & keep);
-                    }
-                }
-                value = (fold_k_eff >> 1) - pop;
+                for (int q = 0; q < kWords; ++q)
+                    if (q == ((d_out - 1) >> 6)) last = words[q];
+                if (((last >> ((d_out - 1) & 63)) & 1ull) == 0) s = -s;
             }
-            uint32_t byte = static_cast<uint32_t>(value) & 0xffu;
-            const uint32_t s_bits = __float_as_uint(s);
-            if (fold_place == kScaleInTail && lane >= fold_positions - 4)
-                byte = (s_bits >> (8 * (lane - (fold_positions - 4)))) & 0xffu;
-            else if (fold_place == kScaleInLastBytes && v2 == 7 && g2 >= 4)
-                byte = (s_bits >> (8 * (g2 - 4))) & 0xffu;
-            fold_rows[row * fold_positions + lane] = static_cast<unsigned char>(byte);
+            next_scale[row] = s;
         }
     }
 };
@@ -684,9 +634,7 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) 
     using LaneConsts = typename Epilogue::template Lane<G, V>;
     using Parked = ParkedLane<LaneConsts>;
     __shared__ float parked[Parked::kFloats > 0 ? Parked::kFloats * kWave : 1];
-    __shared__ uint64_t fold_lds[Epilogue::kFold ? 4 * 64 : 1];
     {
-        if constexpr (Epilogue::kFold) epi.stage_fold(fold_lds, static_cast<int>(threadIdx.x));
         LaneConsts ctx;
         epi.template init<G, V>(lane, ctx);
         if (wave == 0) Parked::park(ctx, parked, lane);     // identical in all four wavefronts
@@ -736,7 +684,7 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) 
                 load_own_row<T, G, V, WM>(own_lane_base, own_alt_lane_base, row_bytes, alt_row_bytes, weights, row, lane, active, own);
             LaneConsts ctx;
             Parked::fetch(ctx, parked, lane);
-            epi.template finish<G, V>(ctx, row, lane, acc, own, fold_lds);
+            epi.template finish<G, V>(ctx, row, lane, acc, own);
         }
         return;
     }
@@ -755,7 +703,7 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) 
         reduce_slots<G, V, WM>(acc);
         LaneConsts ctx;
         Parked::fetch(ctx, parked, lane);
-        epi.template finish<G, V>(ctx, row, lane, acc, own, fold_lds);
+        epi.template finish<G, V>(ctx, row, lane, acc, own);
     }
 }
 
@@ -889,15 +837,6 @@ RowLayout choose_layout(int64_t d_in, int64_t d_out)
     return l;
 }
 
-// A next layer whose bit-GEMM the aggregation's epilogue can do itself: one byte per product
-// (at most 256 input bits, i.e. at most four packed words per node), at most 64 stored positions
-// (one lane each), no 7-bit form (those rows span 16 lanes or more and may need the alternate array).
-bool fold_next_covers(int64_t d_hidden, const RowLayout &next)
-{
-    return d_hidden <= 256 && next.kind == kI8 && next.vec == 8 && next.positions() <= 64 && !next.escape &&
-           next.embed_scale != kScaleInTopBits;
-}
-
 template <bool kSelfTerm>
 static int launch_fused_spmm_t(const FusedSpmmArgs &a, hipStream_t stream)
 {
@@ -924,19 +863,6 @@ static int launch_fused_spmm_t(const FusedSpmmArgs &a, hipStream_t stream)
     epi.alt_self_rows = static_cast<const char *>(a.alt_self_rows);
     epi.self_alpha = a.self_alpha;
     epi.self_last_bit_word = (l.fold_last && a.self_w_bits != nullptr) ? a.self_w_bits + (a.d_in - 1) / 64 : nullptr;
-    epi.fold_rows = nullptr;
-    if (a.fold_rows != nullptr) {
-        if (kSelfTerm || a.logits != nullptr || !fold_next_covers(a.d_out, a.fold_layout) || a.fold_w_bits == nullptr)
-            return BIGCN_EINVAL;
-        epi.fold_rows = static_cast<unsigned char *>(a.fold_rows);
-        epi.fold_w_bits = a.fold_w_bits;
-        epi.fold_w_ld_words = a.fold_w_ld_words;
-        epi.fold_d_next = static_cast<int>(a.fold_d_next);
-        epi.fold_groups = a.fold_layout.groups;
-        epi.fold_positions = a.fold_layout.positions();
-        epi.fold_k_eff = a.fold_layout.k_eff;
-        epi.fold_place = a.fold_layout.embed_scale;
-    }
     const int valid = l.positions();
     const int64_t rb = l.row_bytes();
 #define BIGCN_FUSED(TT, VV)                                                                             \

@@ -57,11 +57,11 @@ def test_slot_bounds_and_cache_resident_rule():
     from workloads import get_config
     cfg = get_config("c5")
     nnz = cfg.nnz
-    launch_ms = [0.25, 0.18, 4.6, 0.25, 4.7, 0.001, 2.5]
+    launch_ms = [0.25, 0.18, 4.6, 0.25, 4.7, 0.07, 2.5]
     slots = bench.slot_bounds(cfg, cfg.n_nodes, nnz, _FakeBinding, launch_ms)
     assert [s["slot"] for s in slots] == ["pack", "bit_gemm[0]", "aggregation[0]", "bit_gemm[1]", "aggregation[1]",
                                           "bit_gemm[2]", "aggregation[2]"]
-    assert slots[5]["bound"] == "none" and "folded" in slots[5]["path"]     # 256 -> 47: formed by aggregation[1]
+    assert slots[5]["bound"] == "hbm" and slots[5]["algorithmic_bytes"] == cfg.n_nodes * (8 * 4 + 64)
     agg1 = slots[4]
     assert agg1["algorithmic_bytes"] == nnz * (4 + 256) + cfg.n_nodes * (8 + 4 + 4 + 8 * 4 + 4)
     assert agg1["frac"] == pytest.approx(agg1["algorithmic_bytes"] / 4.7e-3 / 8e12)

@@ -110,40 +110,3 @@ def test_every_row_in_the_alternate_array(B):
     bt, _ = oracle.binarize_weight(w)
     _check(values, k_eff, f, bt, "all rows escaped")
 
-
-# (d_in, d_hidden, d_out): narrow last layers whose bit-GEMM is done by the aggregation before them
-# (rows of 2, 4 and 8 lanes; scale in the tail, in the last bytes of four lanes; 256 hidden columns
-# with the last bit folded out; the shapes of the five workloads' last layers)
-FOLDED = [(64, 64, 7), (64, 64, 3), (100, 128, 41), (100, 256, 47), (70, 200, 60), (64, 100, 9), (64, 256, 12),
-          (30, 33, 40), (64, 129, 20), (64, 255, 33), (64, 64, 1)]
-
-
-@pytest.mark.parametrize("d_in,d_hidden,d_out", FOLDED)
-@pytest.mark.parametrize("n", [1500, 33100])
-def test_integers_of_a_layer_folded_into_the_aggregation_before_it(B, d_in, d_hidden, d_out, n):
-    """Second layer of a two-layer forward: its product rows are written by the first layer's
-    aggregation.  The oracle's dot products are taken over the signs of the GPU's own first-layer
-    output (a one-layer forward on the same inputs), so the comparison is exact."""
-    import torch
-    rng = np.random.default_rng(d_in + 7 * d_hidden + 13 * d_out + n)
-    rp, ci = chung_lu_csr(n, 3 * n, 2.5, 2.0, seed=d_hidden + d_out)
-    w1 = rng.uniform(-1, 1, size=(d_in, d_hidden)).astype(np.float32)
-    w2 = rng.uniform(-1, 1, size=(d_hidden, d_out)).astype(np.float32)
-    x = rng.standard_normal((n, d_in)).astype(np.float32)
-    drp, dci, dx, dw1, dw2 = to_device(rp, ci, x, w1, w2)
-    plan = B.Plan(drp, dci)
-    dinv, _ = B.bigcn_gcn_norm(drp, dci)
-    layers = [B.Layer.from_weight(dw1), B.Layer.from_weight(dw2)]
-    layout = B.bigcn_forward_row_layout(d_hidden, d_out)
-    assert layout["kind"] == 0 and layout["groups"] * layout["vec"] <= 64 and not layout["escape"] and layout["scale_place"] != 2
-    h1 = B.bigcn_forward(plan, drp, dci, dinv, dx, layers[:1]).cpu().numpy()
-    ws = torch.zeros((B.bigcn_forward_workspace_bytes(n, layers),), dtype=torch.uint8, device="cuda")
-    B.bigcn_forward(plan, drp, dci, dinv, dx, layers, workspace=ws)
-    torch.cuda.synchronize()
-    offsets = B.bigcn_forward_workspace_map(n, layers)
-    assert offsets["fold_rows"] + n * layout["groups"] * layout["vec"] <= offsets["total"]
-    values, k_eff, escaped = decode_product_rows(ws.cpu().numpy(), dict(offsets, rows=offsets["fold_rows"]), layout, n, d_out)
-    assert not escaped.any()
-    f1 = np.where(h1 >= 0, 1, -1).astype(np.int8)
-    bt2, _ = oracle.binarize_weight(w2)
-    _check(values, k_eff, f1, bt2, f"folded {d_in}->{d_hidden}->{d_out} {layout}")

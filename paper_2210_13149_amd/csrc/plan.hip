@@ -173,11 +173,12 @@ extern "C" int bigcn_plan_create(const int64_t *row_ptr, const int32_t *col_idx,
     }
     for (int64_t i = 0; i < n; ++i) start[static_cast<size_t>(max_degree - (rp[i + 1] - rp[i])) + 1]++;
     for (size_t d = 1; d < start.size(); ++d) start[d] += start[d - 1];
-    int64_t n_block_rows = 0;
+    int64_t n_block_rows = 0, n_split_rows = 0;
     for (int64_t i = 0; i < n; ++i) {
         const int64_t deg = rp[i + 1] - rp[i];
         order[static_cast<size_t>(start[static_cast<size_t>(max_degree - deg)]++)] = static_cast<int32_t>(i);
         if (deg >= kBlockRowDegree) ++n_block_rows;
+        if (deg >= kSplitRowDegree) ++n_split_rows;
     }
 
     bigcn_plan *plan = new (std::nothrow) bigcn_plan();
@@ -192,6 +193,7 @@ extern "C" int bigcn_plan_create(const int64_t *row_ptr, const int32_t *col_idx,
     }
     plan->row_order = nullptr;
     plan->n_block_rows = n_block_rows;
+    plan->n_split_rows = n_split_rows;
     plan->max_degree = max_degree;
     if (n > 0) {
         if (hipMalloc(&plan->row_order, sizeof(int32_t) * n) != hipSuccess) {

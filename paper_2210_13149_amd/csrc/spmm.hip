@@ -554,22 +554,25 @@ struct EpilogueFusedT {
 
 // The per-lane constants of an epilogue are needed once per node, after the gather; held in
 // registers for the whole kernel they would cost occupancy in the loop that matters.  They are
-// parked in LDS ([constant][lane], conflict-free) and fetched back by `finish`.
-template <class L>
+// parked in LDS and fetched back by `finish`.  They depend on the lane's place in its group only,
+// so G lanes' worth is kept ([constant][place]: the 64 lanes read G consecutive words, conflict-free).
+template <class L, int G>
 struct ParkedLane {
     static constexpr int kFloats = std::is_empty<L>::value ? 0 : static_cast<int>(sizeof(L) / sizeof(float));
     static __device__ __forceinline__ void park(const L &c, float *lds, int lane)
     {
         const float *src = reinterpret_cast<const float *>(&c);
+        if (lane < G) {
 #pragma unroll
-        for (int k = 0; k < kFloats; ++k) lds[k * kWave + lane] = src[k];
+            for (int k = 0; k < kFloats; ++k) lds[k * G + lane] = src[k];
+        }
     }
     static __device__ __forceinline__ void fetch(L &c, const float *lds, int lane)
     {
         asm volatile("" ::: "memory");      // keep the reads here: not hoisted out of the row loop
         float *dst = reinterpret_cast<float *>(&c);
 #pragma unroll
-        for (int k = 0; k < kFloats; ++k) dst[k] = lds[k * kWave + lane];
+        for (int k = 0; k < kFloats; ++k) dst[k] = lds[k * G + (lane & (G - 1))];
     }
 };
 
@@ -624,7 +627,7 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) 
     constexpr int kAltElem = WM == kWeightTopBitsEscapeF16 ? 2 : static_cast<int>(sizeof(T));
     const uint32_t alt_row_bytes = row_bytes / sizeof(T) * kAltElem;
     constexpr bool kAllActive = fused_weights(WM);     // stored rows of the fused path fill G * V positions
-    __shared__ float partial[kWavesPerBlock - 1][V + 2][kWave];
+    __shared__ float partial[kWavesPerBlock - 1][V + 2][G];     // after reduce_slots the lanes of one place in their groups agree
     const int lane = lane_id();
     const int wave = wave_in_block();
     const int g = lane & (G - 1);
@@ -632,8 +635,8 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) 
     const RowBase lane_base{rows, static_cast<uint32_t>(g * V * sizeof(T))};
 
     using LaneConsts = typename Epilogue::template Lane<G, V>;
-    using Parked = ParkedLane<LaneConsts>;
-    __shared__ float parked[Parked::kFloats > 0 ? Parked::kFloats * kWave : 1];
+    using Parked = ParkedLane<LaneConsts, G>;
+    __shared__ float parked[Parked::kFloats > 0 ? Parked::kFloats * G : 1];
     {
         LaneConsts ctx;
         epi.template init<G, V>(lane, ctx);
@@ -665,7 +668,7 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) 
         accumulate_range<T, G, V, WM, kAllActive>(col_idx, weights, lane_base, alt_lane_base, row_bytes, alt_row_bytes, q0, q1, lane,
                                                   active, acc);
         reduce_slots<G, V, WM>(acc);
-        if (wave > 0) {
+        if (wave > 0 && lane < G) {
 #pragma unroll
             for (int v = 0; v < V; ++v) partial[wave - 1][v][lane] = acc.pos[v];
             partial[wave - 1][V][lane] = acc.sum_abs;
@@ -676,9 +679,9 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) 
 #pragma unroll
             for (int w = 0; w < kWavesPerBlock - 1; ++w) {
 #pragma unroll
-                for (int v = 0; v < V; ++v) acc.pos[v] += partial[w][v][lane];
-                acc.sum_abs += partial[w][V][lane];
-                acc.sum_signed += partial[w][V + 1][lane];
+                for (int v = 0; v < V; ++v) acc.pos[v] += partial[w][v][g];
+                acc.sum_abs += partial[w][V][g];
+                acc.sum_signed += partial[w][V + 1][g];
             }
             if constexpr (Epilogue::kSelf)
                 load_own_row<T, G, V, WM>(own_lane_base, own_alt_lane_base, row_bytes, alt_row_bytes, weights, row, lane, active, own);
@@ -717,16 +720,16 @@ static int launch_spmm_one(const bigcn_plan *plan, const int64_t *row_ptr, const
     if (row_bytes <= 0 || row_bytes > 0x7fffffff) return BIGCN_EINVAL;
     if (escape_weights(WM) && (alt_rows == nullptr || weights == nullptr)) return BIGCN_ENULL;
     if (fused_weights(WM) && valid_positions != G * V) return BIGCN_EINVAL;
-    const int64_t wave_rows = plan->n - plan->n_block_rows;
+    const int64_t wave_rows = plan->n - plan->n_split_rows;
     int rows_per_wave = rows_per_wave_for(wave_rows, plan->compute_units);
     // the launch that only runs when a row escaped (almost never): a quarter of the workgroups, so
     // that returning at once costs a quarter
     if (gate_flag != nullptr && run_if_set != 0 && rows_per_wave == kMaxRowsPerWave) rows_per_wave *= 4;
     const int64_t per_block = kWavesPerBlock * rows_per_wave;
-    const int64_t blocks = plan->n_block_rows + (wave_rows + per_block - 1) / per_block;
+    const int64_t blocks = plan->n_split_rows + (wave_rows + per_block - 1) / per_block;
     if (blocks == 0) return BIGCN_OK;
     hipLaunchKernelGGL((spmm_kernel<T, G, V, WM, Epilogue>), dim3(static_cast<unsigned>(blocks)),
-                       dim3(kBlock), 0, stream, plan->row_order, plan->n, plan->n_block_rows, row_ptr,
+                       dim3(kBlock), 0, stream, plan->row_order, plan->n, plan->n_split_rows, row_ptr,
                        col_idx, weights, static_cast<const char *>(rows), static_cast<const char *>(alt_rows),
                        static_cast<uint32_t>(row_bytes), valid_positions, rows_per_wave, epi, gate_flag, run_if_set, clear_flag);
     return check_launch();

@@ -278,8 +278,8 @@ def _hand_graph(kind):
         return csr_from_undirected_edges(1, np.zeros(0, dtype=np.int64), np.zeros(0, dtype=np.int64))
     if kind == "isolated":                    # no edges at all: A~ is the identity
         return csr_from_undirected_edges(70, np.zeros(0, dtype=np.int64), np.zeros(0, dtype=np.int64))
-    if kind == "star":                        # one hub of 700 neighbours: a row shared by a workgroup
-        return csr_from_undirected_edges(701, np.zeros(700, dtype=np.int64), np.arange(1, 701, dtype=np.int64))
+    if kind == "star":                        # one hub of 1500 neighbours: a row shared by a workgroup
+        return csr_from_undirected_edges(1501, np.zeros(1500, dtype=np.int64), np.arange(1, 1501, dtype=np.int64))
     if kind == "path":
         return csr_from_undirected_edges(130, np.arange(129, dtype=np.int64), np.arange(1, 130, dtype=np.int64))
     raise ValueError(kind)

@@ -228,9 +228,11 @@ int64_t bigcn_forward_row_bytes(int64_t d_in, int64_t d_out, int *scale_embedded
  *     values use 7 bits (two's complement in bits 0..6) and bit 7 of byte 8i (rows of 32 or 64 lanes,
  *     i < 32) or of bytes 8i and 8i + 4 (rows of 16 lanes: scale bits i and 16 + i) carries a bit
  *     of the scale; 3: the last byte of lanes 4..7 of an 8-lane row holds byte 0..3 of the scale;
- *   - escape 1 (with scale_place 2): a row whose values do not all fit 7 bits carries a NaN in the
- *     scale bits and its values live at the same positions of the alternate array, as bytes
- *     (alt_kind 0) or fp16 (alt_kind 1), with its scale in the per-node scale array.
+ *   - escape 1: a row whose values do not all fit carries a NaN as its scale and its values live at
+ *     the same positions of the alternate array, as bytes (alt_kind 0) or fp16 (alt_kind 1), with
+ *     its scale in the per-node scale array.  With scale_place 2 "fit" means 7 bits; with
+ *     scale_place 3 (more than 256 input bits, at most 60 columns: 8-bit values) it means
+ *     [-127, 126], the range in which a byte cannot be a saturated conversion.
  * bigcn_forward_workspace_map: offsets[0..5] (HOST) = byte offsets inside the workspace of
  * {packed signs of the hidden layers, scale array 0, scale array 1, product rows, alternate rows,
  * total size}; row i of the product array starts at rows + i * (row bytes of the layer that ran

@@ -124,13 +124,11 @@ struct EpilogueLayout {
         alignas(16) T tmp[VB];
         const int bias = pop_init();
         const int half_k = (k_eff >> 1) + bias;             // value = half_k - (counter incl. bias)
-        uint32_t spread = 0;                                 // OR of the live shifted counters
 #pragma unroll
         for (int v = 0; v < VB; ++v) {
             const bool live = col[v] >= 0 && col[v] < n;
             if constexpr (sizeof(T) == 1) {
                 tmp[v] = static_cast<T>(live ? half_k - pop[v] : 0);
-                spread |= live ? static_cast<uint32_t>(pop[v]) : 0u;
             } else {
                 const int value = k_eff - 2 * pop[v];
                 tmp[v] = static_cast<T>(live ? static_cast<float>(value) : 0.0f);
@@ -138,11 +136,24 @@ struct EpilogueLayout {
         }
         if constexpr (sizeof(T) == 1) {
             if (alt_rows != nullptr) {
-                // one wavefront holds the whole row: if any value needs the eighth bit the row goes
-                // to the alternate array as it is and the main array gets a NaN scale
-                if (__ballot((spread & ~127u) != 0u) != 0ull) {
+                // 8-bit rows of more than 256 input bits (fp16 alternates; the scale sits in the
+                // last bytes).  One wavefront holds the whole row: if any value lies outside
+                // [-127, 126] (the range the matrix-core kernel can tell from a saturated byte) the
+                // row goes to the alternate array and the main array gets a NaN scale
+                bool misfit = false;
+#pragma unroll
+                for (int v = 0; v < VB; ++v) {
+                    const int value = half_k - pop[v];
+                    misfit = misfit || (col[v] >= 0 && col[v] < n && (value < -127 || value > 126));
+                }
+                if (__ballot(misfit) != 0ull) {
                     if (escape_flag != nullptr) *escape_flag = 1;
-                    write_values<VB>(static_cast<T *>(alt_rows) + row * positions + pos0, tmp);
+                    alignas(16) __half wide[VB];
+#pragma unroll
+                    for (int v = 0; v < VB; ++v)
+                        wide[v] = __float2half((col[v] >= 0 && col[v] < n) ? static_cast<float>(half_k - pop[v]) : 0.0f);
+                    EpilogueLayout<__half>::template write_values<VB>(static_cast<__half *>(alt_rows) + row * positions + pos0,
+                                                                      wide);
                     row_scale = __uint_as_float(0x7fc00000u);
                 }
             }
@@ -736,6 +747,9 @@ int launch_bitgemm_layout(const uint64_t *a_bits, int64_t m, int64_t lda, const 
         // the escape decision is taken by the one wavefront that holds the whole row
         if (layout.escape && (per_lane > 8 || per_lane * ((k_bits + 63) / 64) > 128)) return BIGCN_EINVAL;
         if (layout.escape && layout.alt_kind != kI8 && layout.alt_kind != kF16) return BIGCN_EINVAL;
+        if (layout.escape && layout.embed_scale != kScaleInTopBits &&
+            (layout.embed_scale != kScaleInLastBytes || layout.alt_kind != kF16))
+            return BIGCN_EINVAL;
         return dispatch_bitgemm(per_lane, layout.groups, layout.vec, a_bits, m, lda, b_bits, n, ldb, k_bits,
                                 last_mask, epi, stream);
     }

@@ -710,6 +710,19 @@ __global__ __launch_bounds__(kBlock, 3) void bitgemm_fp4_rows_kernel(
                 } else if (p.tail_scale) {
                     if (t == n_tiles - 1 && seg == kSegs - 1) v.y = row_scale;
                 } else if (p.last_bytes) {
+                    if (kSegs == 8 && p.escape) {
+                        // 8-bit values: 0x80 and 0x7f are where the conversion saturates, so a row
+                        // holding either is taken as not fitting (dead positions hold 0)
+                        const uint32_t lo_x = v.x ^ 0x80808080u, hi_x = v.x ^ 0x7f7f7f7fu;
+                        const uint32_t lo_y = v.y ^ 0x80808080u, hi_y = v.y ^ 0x7f7f7f7fu;
+                        const uint32_t zero = ((lo_x - 0x01010101u) & ~lo_x) | ((hi_x - 0x01010101u) & ~hi_x) |
+                                              ((lo_y - 0x01010101u) & ~lo_y) | ((hi_y - 0x01010101u) & ~hi_y);
+                        const uint64_t any = __ballot((zero & 0x80808080u) != 0u);
+                        uint32_t eight = 0;
+#pragma unroll
+                        for (int r = 0; r < 8; ++r) eight |= ((any >> (8 * r)) & 0xffull) != 0ull ? (1u << r) : 0u;
+                        escaped |= eight << j;
+                    }
                     // rows of 8 lanes: byte i of the scale is the last byte of lane 4 + i
                     if (seg >= kSegs - 4) v.y = (v.y & 0x00ffffffu) | (((row_scale >> (8 * (seg - (kSegs - 4)))) & 0xffu) << 24);
                 }
@@ -743,6 +756,12 @@ __global__ __launch_bounds__(kBlock, 3) void bitgemm_fp4_rows_kernel(
                     else
                         static_cast<signed char *>(alt_rows)[row * P + pos] = static_cast<signed char>(value);
                     const int segment = pos >> 3, offset = pos & 7;
+                    if (p.last_bytes) {
+                        // the NaN scale, byte by byte, behind the values of the last four lanes
+                        if (offset == 7 && segment >= P / 8 - 4)
+                            rows[row * P + pos] = static_cast<unsigned char>((0x7fc00000u >> (8 * (segment - (P / 8 - 4)))) & 0xffu);
+                        continue;
+                    }
                     int bit = -1;
                     if (offset == 0 && segment < 32) bit = segment;
                     else if (offset == 4 && P == 128) bit = 16 + segment;
@@ -766,7 +785,8 @@ bool fp4_rows_covers(int64_t m, int64_t k_bits, const RowLayout &layout)
     if (pos == 64 && (layout.embed_scale == kScaleInTopBits || layout.groups != 8)) return false;
     if (layout.embed_scale == kScaleInLastBytes && pos != 64) return false;
     if (layout.escape && layout.alt_kind != kI8 && layout.alt_kind != kF16) return false;
-    if (layout.escape && layout.embed_scale != kScaleInTopBits) return false;
+    if (layout.escape && layout.embed_scale == kScaleInLastBytes && layout.alt_kind != kF16) return false;
+    if (layout.escape && layout.embed_scale != kScaleInTopBits && layout.embed_scale != kScaleInLastBytes) return false;
     return fp4_rows_lds_bytes(pos, (layout.k_eff + 63) / 64) <= 64 * 1024;
 }
 

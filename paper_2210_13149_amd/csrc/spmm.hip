@@ -29,10 +29,17 @@ enum WeightMode {
     kWeightOne = 0, kWeightVals = 1, kWeightGather = 2, kWeightEmbedded = 3, kWeightTopBits = 4,
     kWeightTopBitsEscape = 5,        // alternate rows hold one byte per value
     kWeightTopBitsEscapeF16 = 6,     // ... one fp16 per value (layers of more than 256 input bits)
-    kWeightLastBytes = 7             // rows of 8 lanes: byte i of the weight is the last byte of lane 4 + i
+    kWeightLastBytes = 7,            // rows of 8 lanes: byte i of the weight is the last byte of lane 4 + i
+    kWeightLastBytesEscapeF16 = 8    // ... with 8-bit products of more than 256 input bits: a row with a product
+                                     //     outside [-127, 126] carries a NaN scale and lives as fp16 in the alternate array
 };
 __host__ __device__ constexpr bool top_bit_weights(int wm) { return wm >= kWeightTopBits && wm <= kWeightTopBitsEscapeF16; }
-__host__ __device__ constexpr bool escape_weights(int wm) { return wm == kWeightTopBitsEscape || wm == kWeightTopBitsEscapeF16; }
+__host__ __device__ constexpr bool escape_weights(int wm)
+{
+    return wm == kWeightTopBitsEscape || wm == kWeightTopBitsEscapeF16 || wm == kWeightLastBytesEscapeF16;
+}
+__host__ __device__ constexpr bool last_byte_weights(int wm) { return wm == kWeightLastBytes || wm == kWeightLastBytesEscapeF16; }
+__host__ __device__ constexpr bool half_alternates(int wm) { return wm == kWeightTopBitsEscapeF16 || wm == kWeightLastBytesEscapeF16; }
 __host__ __device__ constexpr bool fused_weights(int wm) { return wm >= kWeightGather; }
 __host__ __device__ constexpr bool row_weights(int wm) { return wm >= kWeightEmbedded; }
 
@@ -153,8 +160,8 @@ __device__ __forceinline__ float row_weight(Segment<T, V> &seg, int lane, bool l
 {
     if constexpr (sizeof(T) == 1 && WM == kWeightEmbedded) {
         return __uint_as_float(static_cast<uint32_t>(__shfl(static_cast<int>(seg.tail()), lane | (G - 1), kWave)));
-    } else if constexpr (sizeof(T) == 1 && WM == kWeightLastBytes) {
-        static_assert(sizeof(T) != 1 || WM != kWeightLastBytes || (G == 8 && V == 8), "rows of 8 lanes x 8 values");
+    } else if constexpr (sizeof(T) == 1 && last_byte_weights(WM)) {
+        static_assert(sizeof(T) != 1 || !last_byte_weights(WM) || (G == 8 && V == 8), "rows of 8 lanes x 8 values");
         // lanes 4..7 of a row are one quad: each of them collects the four bytes by quad
         // broadcasts (data-parallel moves, no LDS traffic), then one shuffle hands the word of
         // lane 4 to the row's eight lanes
@@ -624,7 +631,7 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) 
 {
     if (clear_flag != nullptr && blockIdx.x == 0 && threadIdx.x == 0) *clear_flag = 0;
     if (gate_flag != nullptr && (*gate_flag != 0) != (run_if_set != 0)) return;     // uniform over the launch
-    constexpr int kAltElem = WM == kWeightTopBitsEscapeF16 ? 2 : static_cast<int>(sizeof(T));
+    constexpr int kAltElem = half_alternates(WM) ? 2 : static_cast<int>(sizeof(T));
     const uint32_t alt_row_bytes = row_bytes / sizeof(T) * kAltElem;
     constexpr bool kAllActive = fused_weights(WM);     // stored rows of the fused path fill G * V positions
     __shared__ float partial[kWavesPerBlock - 1][V + 2][G];     // after reduce_slots the lanes of one place in their groups agree
@@ -798,10 +805,18 @@ RowLayout choose_layout(int64_t d_in, int64_t d_out)
         // the scale bits: cheaper than a second line per neighbour for a separate scale.
         l.kind = kI8;
         l.vec = 8;
-        l.groups = groups_for(d_out, 8) < 16 ? 16 : groups_for(d_out, 8);
-        l.embed_scale = kScaleInTopBits;
         l.escape = 1;
         l.alt_kind = kF16;
+        if (d_out <= 60) {
+            // up to 60 columns: a 64-byte row of 8 lanes whose last four lanes keep a byte of the
+            // scale each behind their values (columns 60..63 do not exist), so the values have all
+            // 8 bits (+-11 sigma at K = 512) and a gathered row is half the bytes of the widened one
+            l.groups = 8;
+            l.embed_scale = kScaleInLastBytes;
+            return l;
+        }
+        l.groups = groups_for(d_out, 8) < 16 ? 16 : groups_for(d_out, 8);
+        l.embed_scale = kScaleInTopBits;
         return l;
     }
     if (l.kind == kI8) {
@@ -904,6 +919,21 @@ static int launch_fused_spmm_t(const FusedSpmmArgs &a, hipStream_t stream)
     }
     if (l.kind == kI8 && l.embed_scale == kScaleInTail) {
         BIGCN_FUSED_EMBEDDED(int8_t, 8);
+    }
+    if (l.kind == kI8 && l.embed_scale == kScaleInLastBytes && l.escape) {
+        // 8-bit products of 257..1024 input bits: the plain kernel when no row escaped, else the one
+        // with the per-row test (same gate as for the top-bits rows above)
+        if (l.groups != 8 || l.vec != 8 || l.alt_kind != kF16) return BIGCN_EINVAL;
+        if (kSelfTerm && a.alt_self_rows == nullptr) return BIGCN_ENULL;
+        if (a.escape_flag != nullptr) {
+            const int rc = launch_spmm_one<int8_t, 8, 8, kWeightLastBytes>(a.plan, a.row_ptr, a.col_idx, nullptr, a.c_rows, rb,
+                                                                           valid, epi, stream, nullptr, a.escape_flag, 0,
+                                                                           a.clear_flag);
+            if (rc != BIGCN_OK) return rc;
+        }
+        return launch_spmm_one<int8_t, 8, 8, kWeightLastBytesEscapeF16>(a.plan, a.row_ptr, a.col_idx, a.src_scale, a.c_rows, rb,
+                                                                        valid, epi, stream, a.alt_rows, a.escape_flag, 1,
+                                                                        a.clear_flag);
     }
     if (l.kind == kI8 && l.embed_scale == kScaleInLastBytes) {
         if (l.groups != 8 || l.vec != 8) return BIGCN_EINVAL;

@@ -282,21 +282,29 @@ def decode_product_rows(workspace: np.ndarray, offsets: dict, layout: dict, n: i
                 scale_word = ((lo << np.arange(16, dtype=np.uint32)[None, :]).sum(axis=1, dtype=np.uint64)
                               | (hi << np.arange(16, 32, dtype=np.uint32)[None, :]).sum(axis=1, dtype=np.uint64))
             scale = scale_word.astype(np.uint32).view(np.float32)
-            if escape:
-                escaped = np.isnan(scale)
-                alt_elem = 1 if alt_kind == 0 else 2
-                alt = workspace[offsets["alt_rows"]: offsets["alt_rows"] + n * pos * alt_elem]
-                if alt_kind == 0:
-                    alt_q = alt.view(np.int8).reshape(n, pos).astype(np.int64)
-                else:
-                    alt_q = alt.view(np.float16).reshape(n, pos).astype(np.float64)
-                    assert np.array_equal(alt_q[escaped], np.rint(alt_q[escaped]))
-                    alt_q = alt_q.astype(np.int64)
-                q = np.where(escaped[:, None], alt_q, q)
-            else:
-                assert not np.isnan(scale).any()
         else:
             q = b.view(np.int8).astype(np.int64)
+            scale = None
+            if place == 3:
+                # 8 lanes of 8 values: byte i of the scale is the last byte of lane 4 + i
+                assert G == 8 and V == 8
+                seg = b.reshape(n, G, V)
+                scale_word = sum(seg[:, 4 + i, 7].astype(np.uint64) << np.uint64(8 * i) for i in range(4))
+                scale = scale_word.astype(np.uint32).view(np.float32)
+        if escape:
+            assert scale is not None
+            escaped = np.isnan(scale)
+            alt_elem = 1 if alt_kind == 0 else 2
+            alt = workspace[offsets["alt_rows"]: offsets["alt_rows"] + n * pos * alt_elem]
+            if alt_kind == 0:
+                alt_q = alt.view(np.int8).reshape(n, pos).astype(np.int64)
+            else:
+                alt_q = alt.view(np.float16).reshape(n, pos).astype(np.float64)
+                assert np.array_equal(alt_q[escaped], np.rint(alt_q[escaped]))
+                alt_q = alt_q.astype(np.int64)
+            q = np.where(escaped[:, None], alt_q, q)
+        elif scale is not None:
+            assert not np.isnan(scale).any()
         stored = 2 * q + (k_eff & 1)
     elif kind == 1:
         f = raw.view(np.float16).reshape(n, pos).astype(np.float64)

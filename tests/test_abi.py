@@ -167,8 +167,10 @@ def test_product_row_formats_by_layer_shape():
         # the class counts of the large workloads: 64-byte rows up to 256 input bits
         (128, 41): (64, True), (256, 47): (64, True), (256, 39): (64, True), (256, 40): (64, True),
         (256, 60): (64, True), (256, 61): (128, True), (256, 64): (128, True),
-        # beyond 256 bits a row has at least 16 lanes, for the bits of the scale
-        (257, 47): (128, True), (512, 47): (128, True), (602, 128): (128, True),
+        # beyond 256 bits: 64-byte rows up to 60 columns (8-bit values, the scale in the last bytes of
+        # four lanes), else at least 16 lanes, for the bits of the scale
+        (257, 47): (64, True), (512, 47): (64, True), (1024, 60): (64, True), (1024, 7): (64, True),
+        (512, 61): (128, True), (602, 128): (128, True),
         (64, 7): (16, True), (100, 3): (16, True), (100, 79): (128, True), (100, 80): (128, True),
         (1025, 64): (128, False), (2048, 64): (128, False), (2049, 64): (256, False), (3703, 64): (256, False),
     }

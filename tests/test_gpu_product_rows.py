@@ -28,10 +28,11 @@ def B():
 
 # (d_in, d_out): fp16 rows; fp32 rows; one byte with the scale in the tail; in the last bytes of an
 # 8-lane row; in the top bits of 32 / 64 / 16 lanes; K = 128 and K = 256 with the last bit folded
-# out; 7-bit rows with one-byte escape; with fp16 escape (16 lanes and wider); separate scale
+# out; 7-bit rows with one-byte escape; with fp16 escape (16 lanes and wider); separate scale; 8-bit
+# 64-byte rows of more than 256 input bits with fp16 escape (up to 60 columns)
 FORMATS = [(1433, 64), (3703, 64), (64, 7), (2, 5), (128, 41), (256, 47), (100, 256), (100, 512), (100, 100),
            (128, 128), (256, 256), (200, 256), (602, 128), (500, 64), (1024, 300), (300, 40), (1100, 300),
-           (255, 61), (64, 75), (31, 33)]
+           (255, 61), (64, 75), (31, 33), (512, 47), (1024, 60), (257, 3)]
 
 
 def _one_layer(B, n, d_in, d_out, seed, packed_input):

@@ -1,5 +1,6 @@
 """Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
 header declares, and rejects bad arguments before touching the device."""
+import numpy as np
 import ctypes
 import os
 import re
@@ -207,3 +208,42 @@ def test_binary_gemm_column_limit_matches_the_header():
     limit = int(re.search(r"#define BIGCN_MAX_GEMM_N (\d+)", text).group(1))
     assert limit == 65535 * 64
     assert L.bigcn_binary_gemm(FAKE, FAKE, 4, 2, FAKE, FAKE, limit + 1, 2, 100, FAKE, limit + 1, None, 0, None) == binding.BIGCN_ESHAPE
+
+
+def test_every_product_row_layout_is_consistent():
+    """All layer shapes up to 1100 input bits (and a few beyond) x every column count the fused
+    forward takes: the layout the library reports must have room for every column, keep the bytes
+    it uses for the scale clear of live columns, and use a value width that holds the product
+    (or an escape).  Pure host logic."""
+    B = binding
+    d_ins = list(range(1, 300)) + [300, 511, 512, 513, 602, 1000, 1023, 1024, 1025, 1433, 2048, 2049, 3703, 8191, 8192]
+    for d_in in d_ins:
+        for d_out in list(range(1, 130)) + [191, 192, 193, 255, 256, 257, 300, 500, 511, 512]:
+            lay = B.bigcn_forward_row_layout(d_in, d_out)
+            G, V, kind, k_eff = lay["groups"], lay["vec"], lay["kind"], lay["k_eff"]
+            place, escape, alt = lay["scale_place"], lay["escape"], lay["alt_kind"]
+            what = (d_in, d_out, lay)
+            assert G in (2, 4, 8, 16, 32, 64) and V in (4, 8), what
+            assert G * V >= d_out, what
+            assert k_eff == d_in - lay["fold_last"] and lay["fold_last"] in (0, 1), what
+            col = (np.arange(G)[:, None] + G * np.arange(V)[None, :]).reshape(-1)     # column of every position
+            if kind == 0:
+                assert V == 8, what
+                if place == 2:
+                    assert G >= 16 and (k_eff <= 127 or escape), what                 # 7 bits: |q| <= 63, or an escape
+                elif not escape:
+                    assert k_eff <= 255, what                                         # q = floor(K'/2) - popcount fits int8
+                if place == 1:
+                    assert (col[-4:] >= d_out).all(), what                            # the tail holds the scale
+                if place == 3:
+                    assert G == 8 and (col[[39, 47, 55, 63]] >= d_out).all(), what    # last byte of lanes 4..7
+                if escape:
+                    assert place in (2, 3) and alt in (0, 1), what
+                    assert alt == 1 or k_eff <= 255, what                             # one-byte alternates hold q
+                    assert alt == 0 or k_eff <= 4096, what                            # fp16 holds integers up to 2048
+            elif kind == 1:
+                assert d_in <= 2048 and place == 0 and not escape, what
+            else:
+                assert kind == 2 and place == 0 and not escape, what
+            bytes_, embedded = B.bigcn_forward_row_bytes(d_in, d_out)
+            assert bytes_ == G * V * {0: 1, 1: 2, 2: 4}[kind] and embedded == (place != 0), what

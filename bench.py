@@ -167,7 +167,13 @@ def multiply_only_probe(B, iterations=4000):
     sink = torch.empty((256 * 1024,), dtype=torch.float32, device="cuda")
     macs = B.bigcn_probe_fp4_multiply_rate(iterations, sink)
     ms = _time_calls(lambda: B.bigcn_probe_fp4_multiply_rate(iterations, sink), 3)
-    return {"ms": ms, "binary_op_per_s": macs / (ms * 1e-3), "frac_mfma_fp4_peak": macs / (ms * 1e-3) / MFMA_FP4_MAC_PEAK}
+    # the same with the expansion of packed bits to FP4 codes before every multiply group: the
+    # ceiling of any kernel whose inputs are bit-packed (loads and stores still free)
+    macs_x = B.bigcn_probe_fp4_expand_multiply_rate(iterations, sink)
+    ms_x = _time_calls(lambda: B.bigcn_probe_fp4_expand_multiply_rate(iterations, sink), 3)
+    return {"ms": ms, "binary_op_per_s": macs / (ms * 1e-3), "frac_mfma_fp4_peak": macs / (ms * 1e-3) / MFMA_FP4_MAC_PEAK,
+            "with_expansion": {"ms": ms_x, "binary_op_per_s": macs_x / (ms_x * 1e-3),
+                               "frac_mfma_fp4_peak": macs_x / (ms_x * 1e-3) / MFMA_FP4_MAC_PEAK}}
 
 
 def gemm_sweep(B, m=262144, n=256, ks=(1024, 4096, 8192), reps=10):
@@ -202,6 +208,7 @@ def gemm_sweep(B, m=262144, n=256, ks=(1024, 4096, 8192), reps=10):
                                  "frac_mfma_int8_peak": rate / MFMA_INT8_MAC_PEAK,
                                  "frac_mfma_fp4_peak": rate / MFMA_FP4_MAC_PEAK,
                                  "frac_of_multiply_only_rate": rate / ceiling["binary_op_per_s"],
+                                 "frac_of_expand_and_multiply_rate": rate / ceiling["with_expansion"]["binary_op_per_s"],
                                  "compulsory_bytes": bytes_moved,
                                  "ms_of_compulsory_bytes_at_hbm_peak": bytes_moved / (HBM_PEAK_GBPS * 1e9) * 1e3,
                                  "identical_to_first": identical})
@@ -740,9 +747,14 @@ def main():
                                 "unit": "T binary MAC/s",
                                 "by_k_bits": {str(r["k_bits"]): {"achieved": r["binary_op_per_s"] / 1e12,
                                                                  "frac": r["frac_mfma_fp4_peak"],
-                                                                 "frac_of_multiply_only_rate": r["frac_of_multiply_only_rate"]}
+                                                                 "frac_of_multiply_only_rate": r["frac_of_multiply_only_rate"],
+                                                                 "frac_of_expand_and_multiply_rate": r["frac_of_expand_and_multiply_rate"]}
                                               for r in sweep["paths"] if r["path"] == "mfma_fp4"},
                                 "multiply_only_frac_of_peak": sweep["multiply_only"]["frac_mfma_fp4_peak"],
+                                "expand_and_multiply_frac_of_peak": sweep["multiply_only"]["with_expansion"]["frac_mfma_fp4_peak"],
+                                "ceiling_is": "a launch of nothing but the expansion of packed bits to FP4 codes and the "
+                                              "multiplies (bigcn_probe_fp4_expand_multiply_rate): no kernel fed with "
+                                              "bit-packed operands can exceed it on this device",
                                 "target_0p5_met": best["frac_mfma_fp4_peak"] >= 0.5}
     if not args.no_configs and args.workload == "c5":
         legs = {}

@@ -40,7 +40,7 @@ EXPORTS = (
     "bigcn_column_stats", "bigcn_predict", "bigcn_layer_backward_workspace_bytes",
     "bigcn_layer_backward", "bigcn_entropy_workspace_bytes", "bigcn_entropy",
     "bigcn_gat_layer_workspace_bytes", "bigcn_gat_layer", "bigcn_forward_static",
-    "bigcn_probe_fp4_multiply_rate", "bigcn_forward_gemm_path",
+    "bigcn_probe_fp4_multiply_rate", "bigcn_probe_fp4_expand_multiply_rate", "bigcn_forward_gemm_path",
     "bigcn_forward_row_layout", "bigcn_forward_workspace_map",
 )
 
@@ -124,6 +124,8 @@ def lib() -> ctypes.CDLL:
                                            i64, vp]
         L.bigcn_probe_fp4_multiply_rate.restype = i32
         L.bigcn_probe_fp4_multiply_rate.argtypes = [i32, vp, i64, ctypes.POINTER(i64), vp]
+        L.bigcn_probe_fp4_expand_multiply_rate.restype = i32
+        L.bigcn_probe_fp4_expand_multiply_rate.argtypes = [i32, vp, i64, ctypes.POINTER(i64), vp]
         L.bigcn_profile_create.restype = i32
         L.bigcn_profile_create.argtypes = [i32, i32, ctypes.POINTER(vp)]
         L.bigcn_profile_destroy.restype = None
@@ -463,6 +465,17 @@ def bigcn_probe_fp4_multiply_rate(iterations: int, sink: Optional[torch.Tensor] 
     macs = ctypes.c_int64(0)
     _check(lib().bigcn_probe_fp4_multiply_rate(int(iterations), _ptr(sink), sink.numel(), ctypes.byref(macs), _stream()),
            "bigcn_probe_fp4_multiply_rate")
+    return int(macs.value)
+
+
+def bigcn_probe_fp4_expand_multiply_rate(iterations: int, sink: Optional[torch.Tensor] = None) -> int:
+    """Launch the expand-and-multiply kernel (measurement aid); returns the multiply-accumulates it performs."""
+    if sink is None:
+        sink = torch.empty((256 * 1024,), dtype=torch.float32, device="cuda")
+    _dev(sink, torch.float32, "sink")
+    macs = ctypes.c_int64(0)
+    _check(lib().bigcn_probe_fp4_expand_multiply_rate(int(iterations), _ptr(sink), sink.numel(), ctypes.byref(macs),
+                                                      _stream()), "bigcn_probe_fp4_expand_multiply_rate")
     return int(macs.value)
 
 

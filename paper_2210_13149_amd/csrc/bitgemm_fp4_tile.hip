@@ -443,28 +443,45 @@ int launch_bitgemm_fp4_tile(const uint64_t *a_bits, const float *a_scale, int64_
 
 // Nothing but multiplies: the rate at which one wavefront per SIMD issues independent
 // 32 x 32 x 64 FP4 multiplies on this device, with operands of pseudo-random +-1 codes (what the
-// tile kernel above could reach if loads, code expansion and stores were free).
+// tile kernel above could reach if loads, code expansion and stores were free).  kExpand: the
+// eight operands of every sixteen multiplies are expanded from packed bits first (codes() above,
+// one rotate to vary the bits): what the kernel could reach if only loads and stores were free.
+template <bool kExpand>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) void fp4_multiply_rate_kernel(
     float *sink, int iterations)
 {
     __shared__ unsigned char whole_cu[131072];               // one workgroup per compute unit, as the tile kernel
     if (iterations < 0) whole_cu[threadIdx.x] = 1;           // never: keeps the allocation
+    uint32_t mag[3] = {0x44444444u, 0x22222222u, 0x11111111u};
+#pragma unroll
+    for (int d = 0; d < 3; ++d) asm volatile("" : "+v"(mag[d]));
     v16f acc[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
     v8i a[4], b[4];
+    uint32_t xa[4], xb[4];
     uint32_t x = 0x9e3779b9u * (blockIdx.x * kBlock + threadIdx.x + 1u);
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            x ^= x << 13; x ^= x >> 17; x ^= x << 5;
-            a[q][e] = e < 4 ? static_cast<int>((x & 0x88888888u) | 0x22222222u) : 0;              // +-1
-            b[q][e] = e < 4 ? static_cast<int>(((x << 1) & 0x88888888u) | 0x22222222u) : 0;
-        }
+    for (int q = 0; q < 4; ++q) {
+        x ^= x << 13; x ^= x >> 17; x ^= x << 5;
+        xa[q] = x;
+        x ^= x << 13; x ^= x >> 17; x ^= x << 5;
+        xb[q] = x;
+        a[q] = codes<false>(xa[q], mag);
+        b[q] = codes<true>(xb[q], mag);
+    }
     for (int it = 0; it < iterations; ++it) {
+        if (kExpand) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                xa[q] = __builtin_amdgcn_alignbit(xa[q], xa[q], 1);
+                xb[q] = __builtin_amdgcn_alignbit(xb[q], xb[q], 3);
+                a[q] = codes<false>(xa[q], mag);
+                b[q] = codes<true>(xb[q], mag);
+            }
+        }
 #pragma unroll
         for (int rt = 0; rt < 4; ++rt)
 #pragma unroll
@@ -480,17 +497,31 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
     sink[blockIdx.x * kBlock + threadIdx.x] = total;
 }
 
+static int launch_multiply_rate(bool expand, int iterations, float *sink, int64_t sink_floats, int64_t *multiply_accumulates,
+                                void *stream)
+{
+    if (sink == nullptr || multiply_accumulates == nullptr) return BIGCN_ENULL;
+    if (iterations <= 0 || iterations > (1 << 20)) return BIGCN_EINVAL;
+    const int cus = compute_units();
+    if (sink_floats < static_cast<int64_t>(cus) * kBlock) return BIGCN_EWORKSPACE;
+    if (expand)
+        hipLaunchKernelGGL(fp4_multiply_rate_kernel<true>, dim3(cus), dim3(kBlock), 0, as_stream(stream), sink, iterations);
+    else
+        hipLaunchKernelGGL(fp4_multiply_rate_kernel<false>, dim3(cus), dim3(kBlock), 0, as_stream(stream), sink, iterations);
+    *multiply_accumulates = static_cast<int64_t>(cus) * kWavesPerBlock * iterations * 16 * (32 * 32 * 64);
+    return check_launch();
+}
+
 }  // namespace bigcn
 
 extern "C" int bigcn_probe_fp4_multiply_rate(int iterations, float *sink, int64_t sink_floats,
                                              int64_t *multiply_accumulates, void *stream)
 {
-    if (sink == nullptr || multiply_accumulates == nullptr) return BIGCN_ENULL;
-    if (iterations <= 0 || iterations > (1 << 20)) return BIGCN_EINVAL;
-    const int cus = bigcn::compute_units();
-    if (sink_floats < static_cast<int64_t>(cus) * bigcn::kBlock) return BIGCN_EWORKSPACE;
-    hipLaunchKernelGGL(bigcn::fp4_multiply_rate_kernel, dim3(cus), dim3(bigcn::kBlock), 0, bigcn::as_stream(stream), sink,
-                       iterations);
-    *multiply_accumulates = static_cast<int64_t>(cus) * bigcn::kWavesPerBlock * iterations * 16 * (32 * 32 * 64);
-    return bigcn::check_launch();
+    return bigcn::launch_multiply_rate(false, iterations, sink, sink_floats, multiply_accumulates, stream);
+}
+
+extern "C" int bigcn_probe_fp4_expand_multiply_rate(int iterations, float *sink, int64_t sink_floats,
+                                                    int64_t *multiply_accumulates, void *stream)
+{
+    return bigcn::launch_multiply_rate(true, iterations, sink, sink_floats, multiply_accumulates, stream);
 }

@@ -279,3 +279,21 @@ def test_plan_validation_rejects_bad_patterns(B):
     assert status(bad_rp, ci) == B.BIGCN_EINVAL
     # validation can be switched off
     B.Plan(*to_device(rp2, ci2), validate=False).destroy()
+
+
+def test_multiply_rate_probes_run_and_count_their_work(B):
+    """The two measurement launches behind the bit-GEMM's ceilings: both complete, report the
+    multiply-accumulates of their grid, and leave finite sums (every product is +-1)."""
+    import torch
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.full((cus * 256,), float("nan"), dtype=torch.float32, device="cuda")
+    for probe in (B.bigcn_probe_fp4_multiply_rate, B.bigcn_probe_fp4_expand_multiply_rate):
+        sink.fill_(float("nan"))
+        macs = probe(3, sink)
+        torch.cuda.synchronize()
+        assert macs == cus * 4 * 3 * 16 * 32 * 32 * 64
+        got = sink.cpu().numpy()
+        # a lane's 256 accumulators hold sums of 3 * 64 products of +-1 each
+        assert np.isfinite(got).all() and (np.abs(got) <= 256 * 3 * 64).all() and np.array_equal(got, np.rint(got))
+    with pytest.raises(Exception):
+        B.bigcn_probe_fp4_expand_multiply_rate(3, sink[:16])

@@ -64,6 +64,24 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// The same total by data-parallel moves inside the vector ALU (no LDS traffic; a sixth of the
+// latency of the butterfly above): lanes of a quad, of a row of 16, then rows 0 -> 1, 2 -> 3 and
+// lanes 0..31 -> 32..63; lane 63 ends with the total, which every lane receives.  Fixed order.
+// Used for the row scale of the binarisation (Sec. 4.1), where one sum per 100..600 values is taken.
+__device__ __forceinline__ float wave_sum_dpp(float v)
+{
+#define BIGCN_DPP_ADD(CTRL, ROWS)                                                                        \
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROWS, 0xf, false))
+    BIGCN_DPP_ADD(0xb1, 0xf);      // quad_perm [1, 0, 3, 2]
+    BIGCN_DPP_ADD(0x4e, 0xf);      // quad_perm [2, 3, 0, 1]
+    BIGCN_DPP_ADD(0x141, 0xf);     // row_half_mirror
+    BIGCN_DPP_ADD(0x140, 0xf);     // row_mirror: every lane of a row of 16 holds the row's sum
+    BIGCN_DPP_ADD(0x142, 0xa);     // row_bcast 15: rows 1 and 3 add the sum of the row before them
+    BIGCN_DPP_ADD(0x143, 0xc);     // row_bcast 31: rows 2 and 3 add lane 31 (rows 0 + 1)
+#undef BIGCN_DPP_ADD
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+
 // Layout in which the fused forward keeps the integer products C of one node.
 // `groups` lanes hold `vec` consecutive stored values each; stored position g*vec + v holds
 // output column g + groups*v.  With this interleaving one ballot per v yields `groups`

@@ -604,7 +604,7 @@ __global__ __launch_bounds__(kBlock) void pack_bitgemm_small_kernel(
                 }
             }
         }
-        sum = wave_sum(sum);
+        sum = wave_sum_dpp(sum);          // the same order of additions as the stand-alone binarisation
         float s = sum * inv_cols;
         if (row_mul != nullptr) s *= row_mul[row];
         if (fold_last && ((last_word >> ((k_bits - 1) & 63)) & 1ull) == 0) s = -s;

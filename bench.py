@@ -350,9 +350,11 @@ def gat_leg(B, m, cfg, reps=3):
             "cache_line_GBps": nnz * lines / (ms * 1e-3) / 1e9}
 
 
-def stream_probe(mib=2048):
-    """Streaming rates of this machine for scale (torch's own elementwise kernels on `mib` MiB of fp32):
-    copy (read + write), sum (read) and fill (write), in GB/s of the bytes each must move."""
+def stream_probe(mib=2048, B=None):
+    """Streaming rates of this machine for scale, on `mib` MiB of fp32, in GB/s of the bytes each must
+    move: torch's own elementwise kernels for copy (read + write), sum (read) and fill (write), and
+    the library's read-only launch (bigcn_probe_stream_read: contiguous pieces, eight 16-byte loads
+    per thread in flight), which is the rate a step bound by reading its input is compared with."""
     import torch
     n = mib << 18
     src = torch.ones((n,), dtype=torch.float32, device="cuda")
@@ -363,6 +365,10 @@ def stream_probe(mib=2048):
                               ("fill", lambda: dst.fill_(1.0), nbytes)):
         ms = _time_calls(call, 5)
         out[name + "_GBps"] = moved / (ms * 1e-3) / 1e9
+    if B is not None:
+        sink = torch.empty((8192 * 1024,), dtype=torch.float32, device="cuda")
+        ms = _time_calls(lambda: B.bigcn_probe_stream_read(src, sink), 5)
+        out["read_GBps"] = nbytes / (ms * 1e-3) / 1e9
     return out
 
 
@@ -634,7 +640,7 @@ def main():
         print(json.dumps({"bit_gemm_sweep": gemm_sweep(B)}), flush=True)
         return
     if args.probe == "stream":
-        print(json.dumps({"stream_probe": stream_probe()}), flush=True)
+        print(json.dumps({"stream_probe": stream_probe(B=B)}), flush=True)
         return
     if args.probe == "mfma":
         print(json.dumps({"multiply_only": multiply_only_probe(B)}), flush=True)
@@ -700,7 +706,7 @@ def main():
         roofline["traffic_source"] = {k: v for k, v in traffic.items() if k != "bytes"}
         roofline["traffic_source"]["file"] = os.path.relpath(TRAFFIC_FILE, ROOT)
     roofline["plain_gather_ms_by_row_bytes"] = gather_ms
-    roofline["stream_probe"] = stream_probe()
+    roofline["stream_probe"] = stream_probe(B=B)
 
     fp4_ran = any(g.get("path") == "fp4-mfma" for g in gemm)
     result = {

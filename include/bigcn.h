@@ -505,6 +505,17 @@ int bigcn_probe_fp4_multiply_rate(int iterations, float *sink, int64_t sink_floa
 int bigcn_probe_fp4_expand_multiply_rate(int iterations, float *sink, int64_t sink_floats,
                                          int64_t *multiply_accumulates, void *stream);
 
+/*
+ * Measurement aid for the steps bound by reading their input once (binarise + pack of Sec. 4.2.2,
+ * the column statistics of Sec. 4.4): a launch that only reads `bytes` bytes (a multiple of 16 is
+ * read; src DEVICE, 16-byte aligned), every workgroup one contiguous piece, a thread eight
+ * 16-byte loads at a time.  Timed by the caller, it gives the read rate such a step is compared
+ * with beside the published HBM peak.
+ *   sink: DEVICE, at least 8192 floats per compute unit (sink_floats says how many there are).
+ * Errors: ENULL, EINVAL (fewer than 16 bytes, misaligned src), EWORKSPACE (sink too small), EHIP.
+ */
+int bigcn_probe_stream_read(const void *src, int64_t bytes, float *sink, int64_t sink_floats, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -40,7 +40,8 @@ EXPORTS = (
     "bigcn_column_stats", "bigcn_predict", "bigcn_layer_backward_workspace_bytes",
     "bigcn_layer_backward", "bigcn_entropy_workspace_bytes", "bigcn_entropy",
     "bigcn_gat_layer_workspace_bytes", "bigcn_gat_layer", "bigcn_forward_static",
-    "bigcn_probe_fp4_multiply_rate", "bigcn_probe_fp4_expand_multiply_rate", "bigcn_forward_gemm_path",
+    "bigcn_probe_fp4_multiply_rate", "bigcn_probe_fp4_expand_multiply_rate", "bigcn_probe_stream_read",
+    "bigcn_forward_gemm_path",
     "bigcn_forward_row_layout", "bigcn_forward_workspace_map",
 )
 
@@ -124,6 +125,8 @@ def lib() -> ctypes.CDLL:
                                            i64, vp]
         L.bigcn_probe_fp4_multiply_rate.restype = i32
         L.bigcn_probe_fp4_multiply_rate.argtypes = [i32, vp, i64, ctypes.POINTER(i64), vp]
+        L.bigcn_probe_stream_read.restype = i32
+        L.bigcn_probe_stream_read.argtypes = [vp, i64, vp, i64, vp]
         L.bigcn_probe_fp4_expand_multiply_rate.restype = i32
         L.bigcn_probe_fp4_expand_multiply_rate.argtypes = [i32, vp, i64, ctypes.POINTER(i64), vp]
         L.bigcn_profile_create.restype = i32
@@ -477,6 +480,18 @@ def bigcn_probe_fp4_expand_multiply_rate(iterations: int, sink: Optional[torch.T
     _check(lib().bigcn_probe_fp4_expand_multiply_rate(int(iterations), _ptr(sink), sink.numel(), ctypes.byref(macs),
                                                       _stream()), "bigcn_probe_fp4_expand_multiply_rate")
     return int(macs.value)
+
+
+def bigcn_probe_stream_read(src: torch.Tensor, sink: Optional[torch.Tensor] = None) -> int:
+    """Launch the read-only kernel over `src` (measurement aid); returns the bytes it reads."""
+    if not src.is_cuda or not src.is_contiguous():
+        raise TypeError("src must be a contiguous device tensor")
+    if sink is None:
+        sink = torch.empty((8192 * 1024,), dtype=torch.float32, device="cuda")
+    _dev(sink, torch.float32, "sink")
+    nbytes = src.numel() * src.element_size()
+    _check(lib().bigcn_probe_stream_read(_ptr(src), nbytes, _ptr(sink), sink.numel(), _stream()), "bigcn_probe_stream_read")
+    return nbytes // 16 * 16
 
 
 STATIC_WORKSPACE_BYTES = 32 << 20   # BIGCN_STATIC_WORKSPACE_BYTES of the header

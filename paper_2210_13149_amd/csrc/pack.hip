@@ -216,7 +216,44 @@ int launch_pack(const float *x, int64_t rows, int64_t cols, int64_t row_stride,
     return check_launch();
 }
 
+// Nothing but a read: every workgroup takes one contiguous piece of the array, a thread eight
+// 16-byte loads at a time.  The rate a kernel bound by reading its input once can reach here.
+__global__ __launch_bounds__(kBlock) void stream_read_kernel(const uint4 *__restrict__ src, int64_t n_vec,
+                                                             float *__restrict__ sink)
+{
+    constexpr int U = 8;
+    const int64_t per_block = (n_vec + gridDim.x - 1) / gridDim.x;
+    const int64_t b0 = per_block * blockIdx.x;
+    const int64_t b1 = b0 + per_block < n_vec ? b0 + per_block : n_vec;
+    uint32_t acc = 0;
+    int64_t i = b0 + threadIdx.x;
+    for (; i + (U - 1) * kBlock < b1; i += U * kBlock) {
+        uint4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = src[i + u * kBlock];
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    for (; i < b1; i += kBlock) {
+        const uint4 v = src[i];
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    // one word per thread, so that the loads cannot be dropped
+    sink[static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x] = __uint_as_float(acc & 0x007fffffu);
+}
+
 }  // namespace bigcn
+
+extern "C" int bigcn_probe_stream_read(const void *src, int64_t bytes, float *sink, int64_t sink_floats, void *stream)
+{
+    if (src == nullptr || sink == nullptr) return BIGCN_ENULL;
+    if (bytes < 16 || reinterpret_cast<uintptr_t>(src) % 16 != 0) return BIGCN_EINVAL;
+    const int blocks = bigcn::compute_units() * 32;
+    if (sink_floats < static_cast<int64_t>(blocks) * bigcn::kBlock) return BIGCN_EWORKSPACE;
+    hipLaunchKernelGGL(bigcn::stream_read_kernel, dim3(blocks), dim3(bigcn::kBlock), 0, bigcn::as_stream(stream),
+                       static_cast<const uint4 *>(src), bytes / 16, sink);
+    return bigcn::check_launch();
+}
 
 extern "C" int bigcn_pack(const float *x, int64_t rows, int64_t cols, int64_t row_stride,
                           int64_t col_stride, const float *shift, const float *mul,

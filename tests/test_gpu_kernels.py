@@ -297,3 +297,17 @@ def test_multiply_rate_probes_run_and_count_their_work(B):
         assert np.isfinite(got).all() and (np.abs(got) <= 256 * 3 * 64).all() and np.array_equal(got, np.rint(got))
     with pytest.raises(Exception):
         B.bigcn_probe_fp4_expand_multiply_rate(3, sink[:16])
+
+
+def test_stream_read_probe_reads_what_it_says(B):
+    """The read-only measurement launch: completes on a buffer whose length is not a multiple of
+    its pieces, reports the bytes it read, and refuses a sink that is too small."""
+    import torch
+    src = torch.arange(0, 3_000_003, dtype=torch.int32, device="cuda")
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.full((cus * 32 * 256,), float("nan"), dtype=torch.float32, device="cuda")
+    assert B.bigcn_probe_stream_read(src, sink) == 3_000_003 * 4 // 16 * 16
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(sink).all())
+    with pytest.raises(Exception):
+        B.bigcn_probe_stream_read(src, sink[:1024])

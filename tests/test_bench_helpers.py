@@ -72,3 +72,14 @@ def test_slot_bounds_and_cache_resident_rule():
     assert slots[4]["bound"] == "hbm"
     dom = bench.dominant_roofline(slots)
     assert dom["kernel"] == "aggregation[1]" and dom["bound"] == "hbm" and dom["peak"] == 8000.0
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    """`bench.py --gpus N` with N above 1 exits before touching a device and says why."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    run = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert run.returncode != 0 and run.stdout.strip() == ""
+    assert "ONE GPU" in run.stderr

@@ -167,8 +167,9 @@ def multiply_only_probe(B, iterations=4000):
     sink = torch.empty((256 * 1024,), dtype=torch.float32, device="cuda")
     macs = B.bigcn_probe_fp4_multiply_rate(iterations, sink)
     ms = _time_calls(lambda: B.bigcn_probe_fp4_multiply_rate(iterations, sink), 3)
-    # the same with the expansion of packed bits to FP4 codes before every multiply group: the
-    # ceiling of any kernel whose inputs are bit-packed (loads and stores still free)
+    # the same with the expansion of packed bits to FP4 codes put back, alternating with the
+    # multiplies of the step before: what a kernel with bit-packed inputs could reach if only
+    # loads and stores were free
     macs_x = B.bigcn_probe_fp4_expand_multiply_rate(iterations, sink)
     ms_x = _time_calls(lambda: B.bigcn_probe_fp4_expand_multiply_rate(iterations, sink), 3)
     return {"ms": ms, "binary_op_per_s": macs / (ms * 1e-3), "frac_mfma_fp4_peak": macs / (ms * 1e-3) / MFMA_FP4_MAC_PEAK,
@@ -759,8 +760,9 @@ def main():
                                 "multiply_only_frac_of_peak": sweep["multiply_only"]["frac_mfma_fp4_peak"],
                                 "expand_and_multiply_frac_of_peak": sweep["multiply_only"]["with_expansion"]["frac_mfma_fp4_peak"],
                                 "ceiling_is": "a launch of nothing but the expansion of packed bits to FP4 codes and the "
-                                              "multiplies (bigcn_probe_fp4_expand_multiply_rate): no kernel fed with "
-                                              "bit-packed operands can exceed it on this device",
+                                              "multiplies, the codes of a step built between the multiplies of the step "
+                                              "before (bigcn_probe_fp4_expand_multiply_rate): what a kernel fed with "
+                                              "bit-packed operands could reach if loads and stores were free",
                                 "target_0p5_met": best["frac_mfma_fp4_peak"] >= 0.5}
     if not args.no_configs and args.workload == "c5":
         legs = {}

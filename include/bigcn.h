@@ -496,11 +496,11 @@ int bigcn_probe_fp4_multiply_rate(int iterations, float *sink, int64_t sink_floa
                                   int64_t *multiply_accumulates, void *stream);
 /*
  * The same launch with the one step that a bit-packed input (Sec. 4.2.2) cannot avoid put back:
- * before every sixteen multiplies their eight operands are expanded from 32 packed bits each to
- * FP4 codes with the instructions the FP4 path of bigcn_binary_gemm uses (28 vector instructions
- * for four row and four column operands, plus one rotate each to vary the bits).  Loads and
- * stores still cost nothing, so this is the rate no kernel fed with packed bits can exceed on
- * this device.  Arguments and errors as above.
+ * the eight operands of every sixteen multiplies are expanded from 32 packed bits each to FP4
+ * codes with the instructions the FP4 path of bigcn_binary_gemm uses (28 vector instructions for
+ * four row and four column operands, plus one rotate each to vary the bits), issued three at a
+ * time between the multiplies of the step before.  Loads and stores still cost nothing, so this is
+ * the rate a kernel fed with packed bits is compared with.  Arguments and errors as above.
  */
 int bigcn_probe_fp4_expand_multiply_rate(int iterations, float *sink, int64_t sink_floats,
                                          int64_t *multiply_accumulates, void *stream);

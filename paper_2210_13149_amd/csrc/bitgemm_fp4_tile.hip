@@ -283,35 +283,67 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[rt][ct][r] = 0.0f;
 
-        // masked: the partial chunk, whose row codes are cleared at the positions at and beyond K
-        auto multiply = [&](const Chunk &s, bool masked) {
+        v8i ca[4], cb[4];
+        // Bits of this lane's dword u of the partial chunk that lie below K.
+        auto partial_keep = [&](int u) {
+            const int left = k_bits - (kChunkBits * n_full + 128 * half + 32 * u);
+            return left >= 32 ? 0xffffffffu : (left <= 0 ? 0u : ((1u << left) - 1u));
+        };
+        // The operand codes of one step from its four row and four column dwords.  keep: the bits
+        // that lie below K (all ones except in the partial chunk); the row codes of the others are
+        // cleared (FP4 zero), nibble i of operand dword d standing for bit 4 i + d.
+        auto expand = [&](const uint32_t (&aw)[4], const uint32_t (&bw)[4], uint32_t keep, v8i (&oa)[4], v8i (&ob)[4]) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                v8i aop[4], bop[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    aop[q] = codes<false>(s.a[q].d[u], mag);
-                    bop[q] = codes<true>(s.b[q].d[u], mag);
-                }
-                if (masked) {
-                    // bits of this lane's dword u that lie below K; nibble i of operand dword d
-                    // stands for bit 4 i + d
-                    const int left = k_bits - (kChunkBits * n_full + 128 * half + 32 * u);
-                    const uint32_t keep = left >= 32 ? 0xffffffffu : (left <= 0 ? 0u : ((1u << left) - 1u));
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) {
-                        const int keep_codes = static_cast<int>(((keep >> d) & 0x11111111u) * 0xfu);
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) aop[q][d] &= keep_codes;
-                    }
-                }
-#pragma unroll
-                for (int rt = 0; rt < 4; ++rt)
-#pragma unroll
-                    for (int ct = 0; ct < 4; ++ct)
-                        acc[rt][ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                            aop[rt], bop[ct], acc[rt][ct], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+            for (int q = 0; q < 4; ++q) {
+                oa[q] = codes<false>(aw[q], mag);
+                ob[q] = codes<true>(bw[q], mag);
             }
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const int keep_codes = static_cast<int>(((keep >> d) & 0x11111111u) * 0xfu);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) oa[q][d] &= keep_codes;
+            }
+        };
+        auto expand_step = [&](const Chunk &s, int u, uint32_t keep, v8i (&oa)[4], v8i (&ob)[4]) {
+            const uint32_t aw[4] = {s.a[0].d[u], s.a[1].d[u], s.a[2].d[u], s.a[3].d[u]};
+            const uint32_t bw[4] = {s.b[0].d[u], s.b[1].d[u], s.b[2].d[u], s.b[3].d[u]};
+            expand(aw, bw, keep, oa, ob);
+        };
+        // Sixteen multiplies of one step.  The codes they use were built during the step before
+        // (see multiply below), so the compiler can place the vector instructions of the next
+        // step between them: built in one piece ahead of their own multiplies the same
+        // instructions leave the matrix pipe idle meanwhile (a launch of nothing but expansion and
+        // multiplies loses a sixth that way and nothing when they alternate).
+        auto multiply16 = [&](const v8i (&oa)[4], const v8i (&ob)[4]) {
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+                for (int ct = 0; ct < 4; ++ct)
+                    acc[rt][ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(oa[rt], ob[ct], acc[rt][ct], 4, 4, 0,
+                                                                                 0x7f7f7f7f, 0, 0x7f7f7f7f);
+        };
+        // One chunk: on entry (ca, cb) hold the codes of its step 0; every step builds the codes
+        // of the step after it while it multiplies, the last one those of step 0 of the chunk that
+        // follows (its dwords next_a / next_b; anything valid when nothing follows), which are in
+        // (ca, cb) again on exit: four steps, two code sets in turn, nothing is copied and there is
+        // no branch.  masked: the partial chunk.
+        v8i na[4], nb[4];
+        auto multiply = [&](const Chunk &s, bool masked, const uint32_t (&next_a)[4], const uint32_t (&next_b)[4],
+                            uint32_t next_keep) {
+            expand_step(s, 1, masked ? partial_keep(1) : 0xffffffffu, na, nb);
+            multiply16(ca, cb);
+            expand_step(s, 2, masked ? partial_keep(2) : 0xffffffffu, ca, cb);
+            multiply16(na, nb);
+            expand_step(s, 3, masked ? partial_keep(3) : 0xffffffffu, na, nb);
+            multiply16(ca, cb);
+            expand(next_a, next_b, next_keep, ca, cb);
+            multiply16(na, nb);
+        };
+        auto multiply_then = [&](const Chunk &s, const Chunk &next) {      // whole chunk followed by a whole chunk
+            const uint32_t aw[4] = {next.a[0].d[0], next.a[1].d[0], next.a[2].d[0], next.a[3].d[0]};
+            const uint32_t bw[4] = {next.b[0].d[0], next.b[1].d[0], next.b[2].d[0], next.b[3].d[0]};
+            multiply(s, false, aw, bw, 0xffffffffu);
         };
 
         // Three register sets in rotation, chunk c + 2 requested before chunk c is multiplied; the
@@ -321,12 +353,13 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
         const int last = n_full - 1;
         Parked parked[kDrains];
         int c = 0;
+        expand_step(s0, 0, 0xffffffffu, ca, cb);
         for (; c + 3 <= n_full; c += 3) {
             load(min(c + 2, last), s2);
 #pragma unroll
             for (int q = 0; q < kDrains; ++q) parked[q] = drain_read(slice + q);
             __builtin_amdgcn_sched_barrier(0);        // the requests stay ahead of the multiplies
-            multiply(s0, false);
+            multiply_then(s0, s1);
 #pragma unroll
             for (int q = 0; q < kDrains; ++q) drain_store(parked[q]);
             slice += kDrains;
@@ -334,7 +367,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 #pragma unroll
             for (int q = 0; q < kDrains; ++q) parked[q] = drain_read(slice + q);
             __builtin_amdgcn_sched_barrier(0);        // the requests stay ahead of the multiplies
-            multiply(s1, false);
+            multiply_then(s1, s2);
 #pragma unroll
             for (int q = 0; q < kDrains; ++q) drain_store(parked[q]);
             slice += kDrains;
@@ -342,15 +375,30 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 #pragma unroll
             for (int q = 0; q < kDrains; ++q) parked[q] = drain_read(slice + q);
             __builtin_amdgcn_sched_barrier(0);        // the requests stay ahead of the multiplies
-            multiply(s2, false);
+            multiply_then(s2, s0);                    // s0: chunk c + 3, or the last one again (then unused)
 #pragma unroll
             for (int q = 0; q < kDrains; ++q) drain_store(parked[q]);
             slice += kDrains;
         }
+        // What is left: up to two whole chunks (s0, s1) and the partial one (s2).  The codes of the
+        // first of them are built here, outside any multiply; which chunk follows which is chosen
+        // by selecting its dwords, not by branching.
+        const bool left0 = c < n_full, left1 = c + 1 < n_full;
         if (partial) load_partial(s2);
-        if (c < n_full) multiply(s0, false);
-        if (c + 1 < n_full) multiply(s1, false);
-        if (partial) multiply(s2, true);
+        uint32_t first_a[4], first_b[4], after0_a[4], after0_b[4], part_a[4], part_b[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            part_a[q] = s2.a[q].d[0];
+            part_b[q] = s2.b[q].d[0];
+            first_a[q] = left0 ? s0.a[q].d[0] : part_a[q];
+            first_b[q] = left0 ? s0.b[q].d[0] : part_b[q];
+            after0_a[q] = left1 ? s1.a[q].d[0] : part_a[q];
+            after0_b[q] = left1 ? s1.b[q].d[0] : part_b[q];
+        }
+        expand(first_a, first_b, left0 ? 0xffffffffu : partial_keep(0), ca, cb);
+        if (left0) multiply(s0, false, after0_a, after0_b, left1 ? 0xffffffffu : partial_keep(0));
+        if (left1) multiply(s1, false, part_a, part_b, partial_keep(0));
+        if (partial) multiply(s2, true, part_a, part_b, 0xffffffffu);
         while (slice < kSlices) drain(slice++);               // short K: what the chunks did not cover
 
         // the tile just multiplied becomes the one to write out
@@ -444,8 +492,10 @@ int launch_bitgemm_fp4_tile(const uint64_t *a_bits, const float *a_scale, int64_
 // Nothing but multiplies: the rate at which one wavefront per SIMD issues independent
 // 32 x 32 x 64 FP4 multiplies on this device, with operands of pseudo-random +-1 codes (what the
 // tile kernel above could reach if loads, code expansion and stores were free).  kExpand: the
-// eight operands of every sixteen multiplies are expanded from packed bits first (codes() above,
-// one rotate to vary the bits): what the kernel could reach if only loads and stores were free.
+// eight operands of every sixteen multiplies are expanded from packed bits (codes() above, one
+// rotate to vary the bits) while the sixteen multiplies before them run, three vector instructions
+// after every multiply: what the kernel could reach if only loads and stores were free.  (Expanded
+// in one piece ahead of their own multiplies the same instructions cost a sixth more.)
 template <bool kExpand>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) void fp4_multiply_rate_kernel(
     float *sink, int iterations)
@@ -472,23 +522,43 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
         a[q] = codes<false>(xa[q], mag);
         b[q] = codes<true>(xb[q], mag);
     }
-    for (int it = 0; it < iterations; ++it) {
+    // two operand sets in turn (the loop body is two steps, so that neither is ever copied): the
+    // set of the next step is built while the current one is multiplied
+    v8i a2[4], b2[4];
+    auto step = [&](v8i (&ma)[4], v8i (&mb)[4], v8i (&na)[4], v8i (&nb)[4]) {
         if (kExpand) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 xa[q] = __builtin_amdgcn_alignbit(xa[q], xa[q], 1);
                 xb[q] = __builtin_amdgcn_alignbit(xb[q], xb[q], 3);
-                a[q] = codes<false>(xa[q], mag);
-                b[q] = codes<true>(xb[q], mag);
+                na[q] = codes<false>(xa[q], mag);
+                nb[q] = codes<true>(xb[q], mag);
             }
         }
 #pragma unroll
         for (int rt = 0; rt < 4; ++rt)
 #pragma unroll
             for (int ct = 0; ct < 4; ++ct)
-                acc[4 * rt + ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[rt], b[ct], acc[4 * rt + ct], 4, 4, 0,
+                acc[4 * rt + ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ma[rt], mb[ct], acc[4 * rt + ct], 4, 4, 0,
                                                                                    0x7f7f7f7f, 0, 0x7f7f7f7f);
+        if (kExpand) {
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one multiply,
+                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);      // three vector instructions
+            }
+        }
+    };
+    for (int it = 0; it + 2 <= iterations; it += 2) {
+        if (kExpand) {
+            step(a, b, a2, b2);
+            step(a2, b2, a, b);
+        } else {
+            step(a, b, a, b);
+            step(a, b, a, b);
+        }
     }
+    if (iterations & 1) step(a, b, a2, b2);
     float total = 0.0f;
 #pragma unroll
     for (int i = 0; i < 16; ++i)

@@ -10,7 +10,7 @@
 
 namespace bigcn {
 
-constexpr int kEntropyTile = 8;            // columns per histogram workgroup
+constexpr int kEntropyTile = 32;           // columns per histogram workgroup (one 128-byte line per row)
 constexpr int kEntropyMaxBins = 1024;
 
 // Order-preserving map float -> uint32 (and back): a < b  <=>  key(a) < key(b).
@@ -35,7 +35,10 @@ __global__ __launch_bounds__(kBlock) void entropy_init_kernel(uint32_t *__restri
     if (i < n_counts) counts[i] = 0u;
 }
 
-// Workgroup (64-column tile, row chunk): lane = column.
+// Workgroup (tile of NT x 64 columns, row chunk): lane l owns columns base + l, base + 64 + l, ...,
+// so a matrix of up to 256 columns is read in whole rows by one workgroup per row chunk (two
+// tiles of 64 columns each fetched the lines that straddle their border twice).
+template <int NT>
 __global__ __launch_bounds__(kBlock) void entropy_range_kernel(const float *__restrict__ h, int64_t rows, int cols,
                                                                int64_t ld, int64_t rows_per_chunk,
                                                                uint32_t *__restrict__ lo_key,
@@ -43,36 +46,46 @@ __global__ __launch_bounds__(kBlock) void entropy_range_kernel(const float *__re
 {
     const int lane = lane_id();
     const int wave = wave_in_block();
-    const int c = blockIdx.x * kWave + lane;
-    if (c >= cols) return;
+    const int c0 = blockIdx.x * (NT * kWave) + lane;
     const int64_t r0 = static_cast<int64_t>(blockIdx.y) * rows_per_chunk;
     const int64_t r1 = r0 + rows_per_chunk < rows ? r0 + rows_per_chunk : rows;
-    float lo = INFINITY, hi = -INFINITY;
-    constexpr int U = 8;                          // loads in flight per lane
-    int64_t r = r0 + wave;
-    for (; r + (U - 1) * kWavesPerBlock < r1; r += U * kWavesPerBlock) {
-        float v[U];
+    bool in[NT];
+    float lo[NT], hi[NT];
 #pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = h[(r + u * kWavesPerBlock) * ld + c];
+    for (int t = 0; t < NT; ++t) {
+        in[t] = c0 + t * kWave < cols;
+        lo[t] = INFINITY;
+        hi[t] = -INFINITY;
+    }
+    constexpr int U = 8 / NT;                     // rows in flight per wavefront (8 loads)
+    for (int64_t r = r0 + wave * U; r < r1; r += kWavesPerBlock * U) {
+        float v[U][NT];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            lo = fminf(lo, v[u]);
-            hi = fmaxf(hi, v[u]);
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                v[u][t] = (in[t] && r + u < r1) ? h[(r + u) * ld + c0 + t * kWave] : NAN;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                lo[t] = fminf(lo[t], v[u][t]);    // fminf / fmaxf return the other operand for a NaN
+                hi[t] = fmaxf(hi[t], v[u][t]);
+            }
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+        if (in[t] && lo[t] <= hi[t]) {
+            atomicMin(&lo_key[c0 + t * kWave], float_key(lo[t]));
+            atomicMax(&hi_key[c0 + t * kWave], float_key(hi[t]));
         }
-    }
-    for (; r < r1; r += kWavesPerBlock) {
-        const float v = h[r * ld + c];
-        lo = fminf(lo, v);
-        hi = fmaxf(hi, v);
-    }
-    if (lo <= hi) {
-        atomicMin(&lo_key[c], float_key(lo));
-        atomicMax(&hi_key[c], float_key(hi));
-    }
 }
 
-// Workgroup (8-column tile, row chunk): 64 lanes = 8 rows x 8 columns per load; counters of the
-// tile in LDS.  The bin of a value is decided in fp32: min(bins - 1, floor((x - lo) * scale)) with
+// Workgroup (32-column tile, row chunk): 256 threads = 8 rows x 32 columns per load, so every
+// row piece is a whole 128-byte line (with 8-column tiles each line crossed the L2 boundary 4.6
+// times).  Counters of the tile in LDS, two columns to a 32-bit word (a chunk has at most 65535
+// rows, so a column's count never carries into its neighbour's half): 16 x bins words, 64 KB at
+// 1024 bins.  The bin of a value is decided in fp32: min(bins - 1, floor((x - lo) * scale)) with
 // scale = bins / (hi - lo), every operation rounded (no contraction is possible in this form).
 __global__ __launch_bounds__(kBlock) void entropy_histogram_kernel(const float *__restrict__ h, int64_t rows, int cols,
                                                                    int64_t ld, int64_t rows_per_chunk, int bins,
@@ -80,11 +93,11 @@ __global__ __launch_bounds__(kBlock) void entropy_histogram_kernel(const float *
                                                                    const uint32_t *__restrict__ hi_key,
                                                                    uint32_t *__restrict__ counts)
 {
-    extern __shared__ uint32_t local[];           // [kEntropyTile][bins]
-    for (int i = threadIdx.x; i < kEntropyTile * bins; i += kBlock) local[i] = 0u;
+    extern __shared__ uint32_t local[];           // [kEntropyTile / 2][bins]
+    for (int i = threadIdx.x; i < (kEntropyTile / 2) * bins; i += kBlock) local[i] = 0u;
     __syncthreads();
     const int tc = threadIdx.x & (kEntropyTile - 1);
-    const int tr = threadIdx.x / kEntropyTile;                  // 0..31
+    const int tr = threadIdx.x / kEntropyTile;                  // 0..7
     const int c = blockIdx.x * kEntropyTile + tc;
     const int64_t r0 = static_cast<int64_t>(blockIdx.y) * rows_per_chunk;
     const int64_t r1 = r0 + rows_per_chunk < rows ? r0 + rows_per_chunk : rows;
@@ -92,12 +105,13 @@ __global__ __launch_bounds__(kBlock) void entropy_histogram_kernel(const float *
         const float lo = key_float(lo_key[c]);
         const float width = key_float(hi_key[c]) - lo;
         const float scale = width > 0.0f ? static_cast<float>(bins) / width : 0.0f;
-        uint32_t *mine = local + tc * bins;
+        uint32_t *mine = local + (tc >> 1) * bins;
+        const uint32_t one = 1u << (16 * (tc & 1));
         auto count = [&](float v) {
             const float pos = floorf((v - lo) * scale);
             int m = static_cast<int>(pos);
             m = m > bins - 1 ? bins - 1 : (m < 0 ? 0 : m);
-            atomicAdd(&mine[m], 1u);
+            atomicAdd(&mine[m], one);
         };
         constexpr int U = 8;                      // loads in flight per lane
         constexpr int kStep = kBlock / kEntropyTile;
@@ -112,10 +126,12 @@ __global__ __launch_bounds__(kBlock) void entropy_histogram_kernel(const float *
         for (; r < r1; r += kStep) count(h[r * ld + c]);
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < kEntropyTile * bins; i += kBlock) {
-        const int col = blockIdx.x * kEntropyTile + i / bins;
+    for (int i = threadIdx.x; i < (kEntropyTile / 2) * bins; i += kBlock) {
+        const int col = blockIdx.x * kEntropyTile + 2 * (i / bins);
         const uint32_t v = local[i];
-        if (v != 0u && col < cols) atomicAdd(&counts[static_cast<int64_t>(col) * bins + (i % bins)], v);
+        const uint32_t even = v & 0xffffu, odd = v >> 16;
+        if (even != 0u && col < cols) atomicAdd(&counts[static_cast<int64_t>(col) * bins + (i % bins)], even);
+        if (odd != 0u && col + 1 < cols) atomicAdd(&counts[static_cast<int64_t>(col + 1) * bins + (i % bins)], odd);
     }
 }
 
@@ -198,13 +214,20 @@ extern "C" int bigcn_entropy(const float *h, int64_t rows, int64_t cols, int64_t
                        s, lo_key, hi_key, icols, counts, n_counts);
     if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
     {
-        const int64_t tiles = (cols + kWave - 1) / kWave;
+        const int64_t words = (cols + kWave - 1) / kWave;
+        const int nt = words >= 4 ? 4 : static_cast<int>(words);
+        const int64_t tiles = (words + nt - 1) / nt;
         int64_t chunks = (2048 + tiles - 1) / tiles;
         const int64_t max_chunks = (rows + 63) / 64;
         if (chunks > max_chunks) chunks = max_chunks;
         const int64_t rpc = (rows + chunks - 1) / chunks;
-        hipLaunchKernelGGL(entropy_range_kernel, dim3(static_cast<unsigned>(tiles), static_cast<unsigned>(chunks)),
-                           dim3(kBlock), 0, s, h, rows, icols, ld, rpc, lo_key, hi_key);
+        const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(chunks));
+        switch (nt) {
+        case 1: hipLaunchKernelGGL(entropy_range_kernel<1>, grid, dim3(kBlock), 0, s, h, rows, icols, ld, rpc, lo_key, hi_key); break;
+        case 2: hipLaunchKernelGGL(entropy_range_kernel<2>, grid, dim3(kBlock), 0, s, h, rows, icols, ld, rpc, lo_key, hi_key); break;
+        case 3: hipLaunchKernelGGL(entropy_range_kernel<3>, grid, dim3(kBlock), 0, s, h, rows, icols, ld, rpc, lo_key, hi_key); break;
+        default: hipLaunchKernelGGL(entropy_range_kernel<4>, grid, dim3(kBlock), 0, s, h, rows, icols, ld, rpc, lo_key, hi_key); break;
+        }
         if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
     }
     {
@@ -212,9 +235,12 @@ extern "C" int bigcn_entropy(const float *h, int64_t rows, int64_t cols, int64_t
         int64_t chunks = (4096 + tiles - 1) / tiles;
         const int64_t max_chunks = (rows + 255) / 256;
         if (chunks > max_chunks) chunks = max_chunks;
+        const int64_t min_chunks = (rows + 65534) / 65535;       // 16-bit counters per chunk
+        if (chunks < min_chunks) chunks = min_chunks;
         if (chunks < 1) chunks = 1;
+        if (chunks > 65535) return BIGCN_ESHAPE;                  // more rows than 65535 chunks of 65535
         const int64_t rpc = (rows + chunks - 1) / chunks;
-        const size_t lds = static_cast<size_t>(kEntropyTile) * bins * sizeof(uint32_t);
+        const size_t lds = static_cast<size_t>(kEntropyTile / 2) * bins * sizeof(uint32_t);
         hipLaunchKernelGGL(entropy_histogram_kernel, dim3(static_cast<unsigned>(tiles), static_cast<unsigned>(chunks)),
                            dim3(kBlock), lds, s, h, rows, icols, ld, rpc, bins, lo_key, hi_key, counts);
         if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;

@@ -707,6 +707,13 @@ def main():
         roofline["traffic_source"] = {k: v for k, v in traffic.items() if k != "bytes"}
         roofline["traffic_source"]["file"] = os.path.relpath(TRAFFIC_FILE, ROOT)
     roofline["plain_gather_ms_by_row_bytes"] = gather_ms
+    if dom["slot"].startswith("aggregation") and gather_ms and str(max(128, dom["row_bytes"])) in gather_ms:
+        # the same launch against the plain fp32 gather of the same cache lines (no conversions, no
+        # epilogue), measured in this run: what the memory system gives this access pattern
+        plain = gather_ms[str(max(128, dom["row_bytes"]))]
+        roofline["frac_of_plain_gather"] = plain / dom["ms"]
+        roofline["l2_miss_rate_limit_note"] = ("gathers on this box are bound by the rate at which L2 misses are served "
+                                               "(7-7.6 TB/s from the Infinity Cache or HBM alike; profiles/spmm_fused_c5.md)")
     roofline["stream_probe"] = stream_probe(B=B)
 
     fp4_ran = any(g.get("path") == "fp4-mfma" for g in gemm)

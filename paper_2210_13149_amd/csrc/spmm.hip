@@ -385,18 +385,42 @@ __device__ __forceinline__ void load_own_row(const RowBase &own_lane_base,
     if (active) accumulate_segment<T, G, V, WM>(seg, fabsf(t), own.pos);
 }
 
+// x + (x of lane ^ kOff): the partner's value comes by a swap of 32- or 16-lane rows or a
+// rotation inside a row of 16 or a quad where the vector ALU can do that itself (kOff = 32, 16, 8, 2), by a
+// shuffle through the LDS crossbar otherwise.  The same pairs are added either way.
+template <int kOff>
+__device__ __forceinline__ float add_xor_lane(float x)
+{
+    const unsigned bits = __float_as_uint(x);
+    if constexpr (kOff == 32) {
+        const auto r = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
+        return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    } else if constexpr (kOff == 16) {
+        const auto r = __builtin_amdgcn_permlane16_swap(bits, bits, false, false);
+        return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    } else if constexpr (kOff == 8) {
+        return x + __uint_as_float(static_cast<unsigned>(
+                       __builtin_amdgcn_update_dpp(0, static_cast<int>(bits), 0x128, 0xf, 0xf, false)));   // row_ror:8
+    } else if constexpr (kOff == 2) {
+        return x + __uint_as_float(static_cast<unsigned>(
+                       __builtin_amdgcn_update_dpp(0, static_cast<int>(bits), 0x4e, 0xf, 0xf, false)));    // quad_perm [2, 3, 0, 1]
+    } else {
+        return x + __shfl_xor(x, kOff, kWave);
+    }
+}
+
 // Sum the partial results of the 64/G lane slots; afterwards every lane holds the total.
-template <int G, int V, int WM>
+template <int G, int V, int WM, int kOff = G>
 __device__ __forceinline__ void reduce_slots(RowAcc<V> &acc)
 {
+    if constexpr (kOff < kWave) {
 #pragma unroll
-    for (int off = G; off < kWave; off <<= 1) {
-#pragma unroll
-        for (int v = 0; v < V; ++v) acc.pos[v] += __shfl_xor(acc.pos[v], off, kWave);
+        for (int v = 0; v < V; ++v) acc.pos[v] = add_xor_lane<kOff>(acc.pos[v]);
         if (fused_weights(WM)) {
-            acc.sum_abs += __shfl_xor(acc.sum_abs, off, kWave);
-            acc.sum_signed += __shfl_xor(acc.sum_signed, off, kWave);
+            acc.sum_abs = add_xor_lane<kOff>(acc.sum_abs);
+            acc.sum_signed = add_xor_lane<kOff>(acc.sum_signed);
         }
+        reduce_slots<G, V, WM, 2 * kOff>(acc);
     }
 }
 
@@ -539,7 +563,7 @@ struct EpilogueFusedT {
             words[(G * v) / 64] |= mask << ((G * v) % 64);
             sum += valid ? fabsf((h[v] - c.shift[v]) * c.mul[v]) : 0.0f;
         }
-        sum = wave_sum(sum);
+        sum = wave_sum_dpp(sum);
         const int n_words = (d_out + 63) >> 6;
 #pragma unroll
         for (int q = 0; q < kWords; ++q)

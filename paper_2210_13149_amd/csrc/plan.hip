@@ -192,17 +192,36 @@ extern "C" int bigcn_plan_create(const int64_t *row_ptr, const int32_t *col_idx,
         plan->compute_units = 256;                       // MI355X
     }
     plan->row_order = nullptr;
+    plan->entries = nullptr;
     plan->n_block_rows = n_block_rows;
     plan->n_split_rows = n_split_rows;
     plan->max_degree = max_degree;
     if (n > 0) {
-        if (hipMalloc(&plan->row_order, sizeof(int32_t) * n) != hipSuccess) {
+        std::vector<bigcn_plan_entry> entries;
+        try {
+            entries.resize(static_cast<size_t>(n));
+        } catch (const std::bad_alloc &) {
+            delete plan;
+            return BIGCN_EHIP;
+        }
+        for (int64_t e = 0; e < n; ++e) {
+            const int32_t row = order[static_cast<size_t>(e)];
+            entries[static_cast<size_t>(e)] = bigcn_plan_entry{rp[static_cast<size_t>(row)], row,
+                                                        static_cast<int32_t>(rp[static_cast<size_t>(row) + 1] - rp[static_cast<size_t>(row)])};
+        }
+        if (hipMalloc(&plan->row_order, sizeof(int32_t) * n) != hipSuccess ||
+            hipMalloc(&plan->entries, sizeof(bigcn_plan_entry) * n) != hipSuccess) {
+            (void)hipGetLastError();
+            if (plan->row_order != nullptr) (void)hipFree(plan->row_order);
+    if (plan->entries != nullptr) (void)hipFree(plan->entries);
             delete plan;
             return BIGCN_EHIP;
         }
         if (hipMemcpyAsync(plan->row_order, order.data(), sizeof(int32_t) * n, hipMemcpyHostToDevice, s) != hipSuccess ||
+            hipMemcpyAsync(plan->entries, entries.data(), sizeof(bigcn_plan_entry) * n, hipMemcpyHostToDevice, s) != hipSuccess ||
             hipStreamSynchronize(s) != hipSuccess) {
             (void)hipFree(plan->row_order);
+            (void)hipFree(plan->entries);
             delete plan;
             return BIGCN_EHIP;
         }

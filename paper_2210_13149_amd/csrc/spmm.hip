@@ -647,7 +647,7 @@ constexpr int spmm_min_waves()
 // that may set it in this one.
 template <typename T, int G, int V, int WM, class Epilogue>
 __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) void spmm_kernel(
-    const int32_t *__restrict__ row_order, int64_t n, int64_t n_block_rows,
+    const bigcn_plan_entry *__restrict__ entries, int64_t n, int64_t n_block_rows,
     const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
     const float *__restrict__ weights, const char *__restrict__ rows, const char *__restrict__ alt_rows,
     uint32_t row_bytes, int valid_positions, int rows_per_wave, Epilogue epi,
@@ -687,8 +687,9 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) 
 
     if (static_cast<int64_t>(blockIdx.x) < n_block_rows) {
         // one long row shared by the four wavefronts: contiguous quarters, multiples of 64
-        const int64_t row = row_order[blockIdx.x];
-        const int64_t p0 = row_ptr[row], p1 = row_ptr[row + 1];
+        const bigcn_plan_entry e = entries[blockIdx.x];
+        const int64_t row = e.row;
+        const int64_t p0 = e.first, p1 = e.first + e.count;
         int64_t chunk = (p1 - p0 + kWavesPerBlock - 1) / kWavesPerBlock;
         chunk = (chunk + kWave - 1) / kWave * kWave;
         int64_t q0 = p0 + wave * chunk;
@@ -727,8 +728,9 @@ __global__ __launch_bounds__(kBlock, (spmm_min_waves<T, G, V, WM, Epilogue>())) 
     for (int j = 0; j < rows_per_wave; ++j) {
         const int64_t entry = base + wave + j * kWavesPerBlock;
         if (entry >= n) break;                                   // wave-uniform
-        const int64_t row = row_order[entry];
-        const int64_t p0 = row_ptr[row], p1 = row_ptr[row + 1];
+        const bigcn_plan_entry e = entries[entry];
+        const int64_t row = e.row;
+        const int64_t p0 = e.first, p1 = e.first + e.count;
         acc.clear();
         if constexpr (Epilogue::kSelf)
             load_own_row<T, G, V, WM>(own_lane_base, own_alt_lane_base, row_bytes, alt_row_bytes, weights, row, lane, active, own);
@@ -760,7 +762,7 @@ static int launch_spmm_one(const bigcn_plan *plan, const int64_t *row_ptr, const
     const int64_t blocks = plan->n_split_rows + (wave_rows + per_block - 1) / per_block;
     if (blocks == 0) return BIGCN_OK;
     hipLaunchKernelGGL((spmm_kernel<T, G, V, WM, Epilogue>), dim3(static_cast<unsigned>(blocks)),
-                       dim3(kBlock), 0, stream, plan->row_order, plan->n, plan->n_split_rows, row_ptr,
+                       dim3(kBlock), 0, stream, plan->entries, plan->n, plan->n_split_rows, row_ptr,
                        col_idx, weights, static_cast<const char *>(rows), static_cast<const char *>(alt_rows),
                        static_cast<uint32_t>(row_bytes), valid_positions, rows_per_wave, epi, gate_flag, run_if_set, clear_flag);
     return check_launch();

@@ -340,11 +340,14 @@ def gat_leg(B, m, cfg, reps=3):
     ms = e0.elapsed_time(e1) / reps
     nnz = int(m["col_idx"].numel())
     # per neighbour: its index, its compact product row (one byte per product up to 255 input
-    # bits, fp16 to 2048, fp32 beyond) and its record {beta, t[heads]}
+    # bits, fp16 to 2048, fp32 beyond) and its record {beta, t[heads]}, which rides in the row's
+    # spare top bits when the products fit 7 bits (256 columns, at most two heads and 127 input bits)
     elem = 1 if d_in <= 255 else (2 if d_in <= 2048 else 4)
-    per_neighbour = 4 + elem * d_out + 4 * (1 + heads)
-    lines = 128 * (-(-(elem * d_out) // 128) + 1)         # the row's cache lines + one for the record
+    embedded = d_in <= 127 and d_out == 256 and heads <= 2
+    per_neighbour = 4 + elem * d_out + (0 if embedded else 4 * (1 + heads))
+    lines = 128 * (-(-(elem * d_out) // 128) + (0 if embedded else 1))   # the row's cache lines (+ one for the record)
     return {"d_in": d_in, "d_out": d_out, "heads": heads, "ms": ms, "bytes_per_neighbour": per_neighbour,
+            "record_inside_row": embedded,
             "row_gather_GBps": nnz * per_neighbour / (ms * 1e-3) / 1e9,
             "bound": "hbm", "frac": nnz * per_neighbour / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "cache_line_bytes_per_neighbour": lines,

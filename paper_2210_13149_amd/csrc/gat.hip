@@ -7,7 +7,9 @@
 // Compact path (every head a multiple of 8 columns wide): the bit-GEMM leaves the integer
 // products of a node as one compact row in column order (one byte per product up to 255 input
 // bits, fp16 up to 2048, fp32 beyond); the row scale beta_j and the scores t_j = a_dst . z_j sit
-// together in a small per-node record.  The aggregation makes ONE pass over the neighbours of
+// together in a small per-node record (256-column rows of at most 127 input bits, whose values
+// fit 7 bits, carry that record in spare top bits instead, so that a neighbour costs the two
+// cache lines of its row and no other).  The aggregation makes ONE pass over the neighbours of
 // a node: per batch of 64 neighbours the running maximum of e_ij is raised and the accumulators
 // rescaled (once per batch and head), so no separate maximum pass gathers the records twice.
 // Long rows are shared by the four wavefronts of a workgroup and merged through LDS.  Sums are
@@ -225,6 +227,12 @@ __device__ __forceinline__ float pick(const float (&x)[H], int h)
     return r;
 }
 
+// Shapes whose kernels can carry the record inside the row (the launcher decides per call).
+template <typename T, int G, int H>
+constexpr bool gat_embeds() { return sizeof(T) == 1 && G == 32 && H <= 2; }
+
+constexpr float kLog2e = 1.44269504088896340736f;
+
 // Scores of the compact path.  Stored value q of column c stands for the product
 // mul * q + bias (mul = 2, bias = K mod 2 for one-byte rows; 1, 0 otherwise), so
 //   s_i[h] = beta_i * (mul * sum_c a_src[c] alpha[c] q_ic + bias * sum_c a_src[c] alpha[c])
@@ -233,14 +241,19 @@ __device__ __forceinline__ float pick(const float (&x)[H], int h)
 // spans a power-of-two number of lanes its sums are a butterfly inside that lane group;
 // otherwise one masked sum over the wavefront per head (one node at a time).
 // record[i] = {beta_i, t_i[0..H-1]} at a stride of gat_record_floats<H>() floats.
+// embed != 0 (one-byte rows of 256 columns, one or two heads, at most 127 input bits, so that
+// every stored value fits 7 bits): the record goes into the row itself instead.  Lane g of the
+// row's 32 lanes gives bit g of beta_i to the top bit of its byte 3, bit g of t_i[0] log2(e) to
+// the top bit of byte 7 and bit g of t_i[1] log2(e) to the top bit of byte 2 (see
+// gat_aggregate_embedded_kernel).
 template <typename T, int G, int H>
-__global__ __launch_bounds__(kBlock) void gat_scores_kernel(const char *__restrict__ rows, uint32_t row_bytes, int64_t n,
+__global__ __launch_bounds__(kBlock) void gat_scores_kernel(char *__restrict__ rows, uint32_t row_bytes, int64_t n,
                                                             int d_out, int d_head, float mul, float bias,
                                                             const float *__restrict__ beta,
                                                             const float *__restrict__ alpha,
                                                             const float *__restrict__ a_src,
                                                             const float *__restrict__ a_dst, float *__restrict__ s,
-                                                            float *__restrict__ record)
+                                                            float *__restrict__ record, int embed)
 {
     constexpr int V = 8;
     const int lane = lane_id();
@@ -301,10 +314,30 @@ __global__ __launch_bounds__(kBlock) void gat_scores_kernel(const char *__restri
                 ps += __shfl_xor(ps, off, kWave);
                 pt += __shfl_xor(pt, off, kWave);
             }
+            const float t_mine = b * fmaf(mul, pt, const_t[0]);
             if (mine && g == my_head * lanes_per_head) {            // first lane of the head's group
                 s[i * H + my_head] = b * fmaf(mul, ps, const_s[0]);
-                record[i * gat_record_floats<H>() + 1 + my_head] = b * fmaf(mul, pt, const_t[0]);
-                if (g == 0) record[i * gat_record_floats<H>()] = b;
+                if (!embed) {
+                    record[i * gat_record_floats<H>() + 1 + my_head] = t_mine;
+                    if (g == 0) record[i * gat_record_floats<H>()] = b;
+                }
+            }
+            if constexpr (gat_embeds<T, G, H>()) {
+                if (embed) {                                        // wave-uniform; every lane is live here
+                    const float t2 = t_mine * kLog2e;
+                    const float other = H == 2 ? __shfl_xor(t2, 16, kWave) : t2;
+                    const uint32_t t0 = __builtin_bit_cast(uint32_t, my_head == 0 ? t2 : other);
+                    const uint32_t t1 = __builtin_bit_cast(uint32_t, my_head == 0 ? other : t2);
+                    const uint32_t bb = __builtin_bit_cast(uint32_t, b);
+                    if (mine) {
+                        uint2 *at = reinterpret_cast<uint2 *>(rows + static_cast<uint64_t>(i) * row_bytes + g * V);
+                        uint2 raw = *at;
+                        raw.x = (raw.x & 0x7fffffffu) | (((bb >> g) & 1u) << 31);
+                        raw.y = (raw.y & 0x7fffffffu) | (((t0 >> g) & 1u) << 31);
+                        if (H == 2) raw.x = (raw.x & 0xff7fffffu) | (((t1 >> g) & 1u) << 23);
+                        *at = raw;
+                    }
+                }
             }
         } else {
             const float b0 = __shfl(b, 0, kWave);
@@ -557,6 +590,269 @@ __global__ __launch_bounds__(kBlock, (gat_min_waves<T, H>())) void gat_aggregate
     gat_finish<G, H>(st, row, lane, my_head, d_out, mul, bias, alpha, out, ld_out, vector_store);
 }
 
+// ---- compact path, record inside the row ---------------------------------------------------
+// One-byte rows of 256 columns whose values fit 7 bits (at most 127 input bits) have a spare top
+// bit in every byte, and gat_scores_kernel stores beta_j and t_j there: a neighbour costs its two
+// row lines and nothing else.  A load instruction fetches two neighbours (lanes 0..31 one,
+// lanes 32..63 the other); three ballots over the carrier bits hand every lane the 32-bit words of
+// its own neighbour, and each lane keeps the softmax state of its own head and its own half of
+// the neighbour list: the running maximum (raised per eight neighbours, the rescaling skipped
+// while no lane's maximum moves), the sum of weights and the weighted values.  Scores are kept
+// in base 2 (t_j and s_i times log2 e; LeakyReLU commutes with a positive factor), so a weight is
+// one v_exp_f32.  The two halves meet at the end of the row.  The kernel is bound by its vector
+// instructions, so the inner loop is written for their count.
+struct GatLaneState {
+    float m;          // running maximum of e_ij log2(e) over this lane's head and half
+    float ref;        // m, or 0 while m is -inf (so that exp2(x - ref) is never inf - inf)
+    float l;          // sum of 2^(e_ij - m)
+    float sw;         // sum of 2^(e_ij - m) beta_j
+    float acc[8];     // sum of 2^(e_ij - m) beta_j q_j over this lane's columns
+};
+
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// values 0..7 of a lane's segment; bytes 2, 3 and 7 carry a foreign top bit
+__device__ __forceinline__ float embedded_value(const uint2 raw, int v)
+{
+    const uint32_t word = v < 4 ? raw.x : raw.y;
+    const int e = v & 3;
+    if (v == 2 || v == 3 || v == 7) return static_cast<float>(static_cast<int>(word << (25 - 8 * e)) >> 25);
+    return static_cast<float>(static_cast<int>(word << (24 - 8 * e)) >> 24);
+}
+
+// The half of a ballot that belongs to this lane: `upper` is all ones in lanes 32..63 and zero
+// in lanes 0..31 (the difference of the halves is scalar work; two vector instructions).
+__device__ __forceinline__ uint32_t own_half(uint64_t ballot, uint32_t upper)
+{
+    const uint32_t lo = static_cast<uint32_t>(ballot), hi = static_cast<uint32_t>(ballot >> 32);
+    return lo ^ ((lo ^ hi) & upper);
+}
+
+// Lane masks and offsets of the embedded kernels, kept as plain register values (as selects
+// the masks would cost a third instruction wherever they are used).
+constexpr int kGatEmbeddedLoads = 4;   // row loads in flight per wavefront (6 and 8 measured 2-3 % slower)
+
+struct GatLaneMasks {
+    uint32_t upper;        // all ones in lanes 32..63
+    uint32_t head_bits;    // all ones in the lanes of the second head
+    uint32_t lane_offset;  // byte offset of this lane's segment in a row
+    int half;              // lane / 32
+};
+
+// U row loads: neighbour `from` + 2 u of the batch of `cnt` (from = t + lane / 32) for
+// u = 0..U-1, whose column indices sit in the lanes of k.  A lane number past 63 wraps to some
+// lane's k, which is then not loaded from; an absent neighbour reads as zeros.
+template <int U>
+__device__ __forceinline__ void gat_fetch_group(const char *__restrict__ rows, const GatLaneMasks &lm, int k, int from,
+                                                int cnt, uint2 (&raw)[U])
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t kk = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute((from + 2 * u) << 2, k));
+        raw[u] = make_uint2(0u, 0u);
+        if (from < cnt - 2 * u) raw[u] = *reinterpret_cast<const uint2 *>(rows + ((kk << 8) + lm.lane_offset));
+    }
+}
+
+// The loaded neighbours into the state.  kUnitSlope: 0 <= slope <= 1, where
+// LeakyReLU(x) = max(x, slope x).
+template <int H, bool kUnitSlope, int U>
+__device__ __forceinline__ void gat_consume_group(const uint2 (&raw)[U], const GatLaneMasks &lm, int from, int cnt,
+                                                  float s_mine, float slope, GatLaneState &st)
+{
+    constexpr int V = 8;
+    float bj[U], e[U];
+    float top = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const bool present = from < cnt - 2 * u;
+        const uint32_t bits_b = own_half(__ballot(static_cast<int>(raw[u].x) < 0), lm.upper);
+        uint32_t bits_t = own_half(__ballot(static_cast<int>(raw[u].y) < 0), lm.upper);
+        if constexpr (H == 2) {
+            const uint32_t bits_1 = own_half(__ballot((raw[u].x & 0x00800000u) != 0u), lm.upper);
+            bits_t ^= (bits_t ^ bits_1) & lm.head_bits;
+        }
+        bj[u] = __builtin_bit_cast(float, bits_b);               // 0 for an absent neighbour
+        const float x = s_mine + __builtin_bit_cast(float, bits_t);
+        const float act = kUnitSlope ? fmaxf(x, slope * x) : leaky(x, slope);
+        e[u] = present ? act : -INFINITY;
+        top = fmaxf(top, e[u]);
+    }
+    if (__ballot(top > st.m) != 0ull) {                       // some lane's maximum moves: rescale
+        const float mn = fmaxf(st.m, top);
+        const float ref = mn == -INFINITY ? 0.0f : mn;
+        const float f = exp2_fast(st.m - ref);                // 0 while m is -inf
+        st.m = mn;
+        st.ref = ref;
+        st.l *= f;
+        st.sw *= f;
+#pragma unroll
+        for (int v = 0; v < V; ++v) st.acc[v] *= f;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const float pe = exp2_fast(e[u] - st.ref);            // 0 for an absent neighbour
+        const float w = pe * bj[u];
+        st.l += pe;
+        st.sw += w;
+#pragma unroll
+        for (int v = 0; v < V; ++v) st.acc[v] = fmaf(w, embedded_value(raw[u], v), st.acc[v]);
+    }
+}
+
+// Neighbours p0..p1-1 of one node; k_first: their first 64 column indices, one per lane (0 in
+// the lanes past the list).  The column indices of a batch of 64 are fetched one batch ahead.
+// (Issuing a group's loads before the group in front of it is used was measured and is 4 %
+// slower: the kernel waits for issue slots and for the memory system's rate, not for latency.)
+template <int H, bool kUnitSlope>
+__device__ __forceinline__ void gat_accumulate_embedded(const int32_t *__restrict__ col_idx,
+                                                        const char *__restrict__ rows, const GatLaneMasks &lm,
+                                                        float s_mine, float slope, int64_t p0, int64_t p1, int k_first,
+                                                        int lane, GatLaneState &st)
+{
+    constexpr int V = 8, U = kGatEmbeddedLoads;
+    st.m = -INFINITY;
+    st.ref = 0.0f;
+    st.l = 0.0f;
+    st.sw = 0.0f;
+#pragma unroll
+    for (int v = 0; v < V; ++v) st.acc[v] = 0.0f;
+
+    int k_ahead = k_first;
+    for (int64_t pb = p0; pb < p1; pb += kWave) {
+        const int cnt = static_cast<int>(p1 - pb < kWave ? p1 - pb : kWave);     // wave-uniform, >= 1
+        const int k = k_ahead;
+        if (pb + kWave < p1) k_ahead = pb + kWave + lane < p1 ? col_idx[pb + kWave + lane] : 0;
+        int from = lm.half;
+        for (int t = 0; t < cnt; t += 2 * U) {
+            uint2 raw[U];
+            gat_fetch_group<U>(rows, lm, k, from, cnt, raw);
+            gat_consume_group<H, kUnitSlope, U>(raw, lm, from, cnt, s_mine, slope, st);
+            from += 2 * U;
+        }
+    }
+}
+
+__device__ __forceinline__ GatLaneMasks gat_lane_masks(int lane, bool second_head)
+{
+    GatLaneMasks lm;
+    lm.upper = lane >= 32 ? ~0u : 0u;
+    lm.head_bits = second_head ? ~0u : 0u;
+    lm.lane_offset = static_cast<uint32_t>(lane & 31) * 8u;
+    lm.half = lane >> 5;
+    asm volatile("" : "+v"(lm.upper), "+v"(lm.head_bits));
+    return lm;
+}
+
+// Brings `st` and a second state (m2, l2, sw2, acc2) of the same node, head and columns to their
+// common maximum and adds them into `st`.
+__device__ __forceinline__ void gat_merge_embedded(GatLaneState &st, float m2, float l2, float sw2,
+                                                   const float (&acc2)[8])
+{
+    const float mn = fmaxf(st.m, m2);
+    const float ref = mn == -INFINITY ? 0.0f : mn;
+    const float f1 = exp2_fast(st.m - ref), f2 = exp2_fast(m2 - ref);
+    st.m = mn;
+    st.ref = ref;
+    st.l = fmaf(f2, l2, st.l * f1);
+    st.sw = fmaf(f2, sw2, st.sw * f1);
+#pragma unroll
+    for (int v = 0; v < 8; ++v) st.acc[v] = fmaf(f2, acc2[v], st.acc[v] * f1);
+}
+
+// the two halves of the wavefront hold the two halves of the neighbour list
+__device__ __forceinline__ void gat_join_halves(GatLaneState &st)
+{
+    const float m2 = __shfl_xor(st.m, 32, kWave);
+    const float l2 = __shfl_xor(st.l, 32, kWave);
+    const float sw2 = __shfl_xor(st.sw, 32, kWave);
+    float acc2[8];
+#pragma unroll
+    for (int v = 0; v < 8; ++v) acc2[v] = __shfl_xor(st.acc[v], 32, kWave);
+    gat_merge_embedded(st, m2, l2, sw2, acc2);
+}
+
+__device__ __forceinline__ void gat_finish_embedded(const GatLaneState &st, int64_t row, int lane, float mul,
+                                                    float bias, const float *__restrict__ alpha,
+                                                    float *__restrict__ out, int64_t ld_out, int vector_store)
+{
+    constexpr int V = 8;
+    if (lane >= 32) return;
+    const float inv = st.l > 0.0f ? 1.0f / st.l : 0.0f;
+    const float base = bias * st.sw;
+    float r[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) r[v] = alpha[lane * V + v] * fmaf(mul, st.acc[v], base) * inv;
+    float *dst = out + row * ld_out + lane * V;
+    if (vector_store) {
+        reinterpret_cast<float4 *>(dst)[0] = make_float4(r[0], r[1], r[2], r[3]);
+        reinterpret_cast<float4 *>(dst)[1] = make_float4(r[4], r[5], r[6], r[7]);
+    } else {
+#pragma unroll
+        for (int v = 0; v < V; ++v) dst[v] = r[v];
+    }
+}
+
+// Same division of the nodes as gat_aggregate_kernel.  256 columns, H heads of 256 / H; the rows
+// take less than 4 GiB (offsets into them are 32-bit).
+template <int H, bool kUnitSlope>
+__global__ __launch_bounds__(kBlock, 8) void gat_aggregate_embedded_kernel(
+    const int32_t *__restrict__ row_order, int64_t n, int64_t n_block_rows, const int64_t *__restrict__ row_ptr,
+    const int32_t *__restrict__ col_idx, const char *__restrict__ rows, const float *__restrict__ s,
+    const float *__restrict__ alpha, float mul, float bias, float slope, float *__restrict__ out, int64_t ld_out,
+    int vector_store)
+{
+    constexpr int V = 8;
+    __shared__ float merge[kWavesPerBlock - 1][V + 3][32];
+    const int lane = lane_id();
+    const int wave = wave_in_block();
+    const bool second_head = H == 2 && (lane & 31) >= 16;
+    const GatLaneMasks lm = gat_lane_masks(lane, second_head);
+    GatLaneState st;
+
+    if (static_cast<int64_t>(blockIdx.x) < n_block_rows) {
+        const int64_t row = row_order[blockIdx.x];
+        const int64_t p0 = row_ptr[row], p1 = row_ptr[row + 1];
+        int64_t chunk = (p1 - p0 + kWavesPerBlock - 1) / kWavesPerBlock;
+        chunk = (chunk + kWave - 1) / kWave * kWave;
+        int64_t q0 = p0 + wave * chunk, q1 = q0 + chunk;
+        if (q0 > p1) q0 = p1;
+        if (q1 > p1) q1 = p1;
+        const float s_mine = s[row * H + (second_head ? 1 : 0)] * kLog2e;
+        const int k_first = q0 + lane < q1 ? col_idx[q0 + lane] : 0;
+        gat_accumulate_embedded<H, kUnitSlope>(col_idx, rows, lm, s_mine, slope, q0, q1, k_first, lane, st);
+        gat_join_halves(st);
+        if (wave > 0 && lane < 32) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) merge[wave - 1][v][lane] = st.acc[v];
+            merge[wave - 1][V][lane] = st.m;
+            merge[wave - 1][V + 1][lane] = st.l;
+            merge[wave - 1][V + 2][lane] = st.sw;
+        }
+        __syncthreads();
+        if (wave == 0 && lane < 32) {
+#pragma unroll
+            for (int w = 0; w < kWavesPerBlock - 1; ++w) {
+                float acc2[V];
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc2[v] = merge[w][v][lane];
+                gat_merge_embedded(st, merge[w][V][lane], merge[w][V + 1][lane], merge[w][V + 2][lane], acc2);
+            }
+            gat_finish_embedded(st, row, lane, mul, bias, alpha, out, ld_out, vector_store);
+        }
+        return;
+    }
+    const int64_t entry = n_block_rows + (static_cast<int64_t>(blockIdx.x) - n_block_rows) * kWavesPerBlock + wave;
+    if (entry >= n) return;                                    // wave-uniform
+    const int64_t row = row_order[entry];
+    const float s_mine = s[row * H + (second_head ? 1 : 0)] * kLog2e;
+    const int64_t p0 = row_ptr[row], p1 = row_ptr[row + 1];
+    const int k_first = p0 + lane < p1 ? col_idx[p0 + lane] : 0;
+    gat_accumulate_embedded<H, kUnitSlope>(col_idx, rows, lm, s_mine, slope, p0, p1, k_first, lane, st);
+    gat_join_halves(st);
+    gat_finish_embedded(st, row, lane, mul, bias, alpha, out, ld_out, vector_store);
+}
+
 struct GatMap {
     size_t bits_off, beta_off, z_off, s_off, t_off, total;
     // compact path: z_off holds the product rows, t_off the records {beta, t[0..H-1]}
@@ -594,10 +890,12 @@ static GatMap map_gat(int64_t n, int64_t d_in, int64_t d_out, int heads)
 
 template <typename T, int G, int H>
 static int launch_gat_compact(const bigcn_plan *plan, const int64_t *row_ptr, const int32_t *col_idx, int64_t n,
-                              const GatMap &map, const char *rows, const float *beta, const float *alpha,
+                              const GatMap &map, char *rows, const float *beta, const float *alpha,
                               const float *a_src, const float *a_dst, float *s, float *record, int64_t d_in,
                               int64_t d_out, float slope, float *out, int64_t ld_out, hipStream_t st)
 {
+    // the record rides in the rows' spare top bits when every product fits 7 bits
+    const bool embed = gat_embeds<T, G, H>() && d_out == 256 && d_in <= 127 && n < (int64_t{1} << 24);
     const float mul = sizeof(T) == 1 ? 2.0f : 1.0f;
     const float bias = sizeof(T) == 1 ? static_cast<float>(d_in & 1) : 0.0f;
     const int d_head = static_cast<int>(d_out / H);
@@ -605,11 +903,25 @@ static int launch_gat_compact(const bigcn_plan *plan, const int64_t *row_ptr, co
     const int64_t score_blocks = node_blocks > compute_units() * 8 ? compute_units() * 8 : node_blocks;
     hipLaunchKernelGGL((gat_scores_kernel<T, G, H>), dim3(static_cast<unsigned>(score_blocks)), dim3(kBlock), 0, st,
                        rows, static_cast<uint32_t>(map.row_bytes), n, static_cast<int>(d_out), d_head, mul, bias, beta,
-                       alpha, a_src, a_dst, s, record);
+                       alpha, a_src, a_dst, s, record, embed ? 1 : 0);
     if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
     const int64_t wave_rows = n - plan->n_block_rows;
     const int64_t blocks = plan->n_block_rows + (wave_rows + kWavesPerBlock - 1) / kWavesPerBlock;
     const int vector_store = (ld_out % 4 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0) ? 1 : 0;
+    if constexpr (gat_embeds<T, G, H>()) {
+        if (embed) {
+            const dim3 grid(static_cast<unsigned>(blocks));
+            if (slope >= 0.0f && slope <= 1.0f)
+                hipLaunchKernelGGL((gat_aggregate_embedded_kernel<H, true>), grid, dim3(kBlock), 0, st, plan->row_order, n,
+                                   plan->n_block_rows, row_ptr, col_idx, rows, s, alpha, mul, bias, slope, out, ld_out,
+                                   vector_store);
+            else
+                hipLaunchKernelGGL((gat_aggregate_embedded_kernel<H, false>), grid, dim3(kBlock), 0, st, plan->row_order,
+                                   n, plan->n_block_rows, row_ptr, col_idx, rows, s, alpha, mul, bias, slope, out, ld_out,
+                                   vector_store);
+            return check_launch();
+        }
+    }
     hipLaunchKernelGGL((gat_aggregate_kernel<T, G, H>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st,
                        plan->row_order, n, plan->n_block_rows, row_ptr, col_idx, rows,
                        static_cast<uint32_t>(map.row_bytes), s, record, alpha, static_cast<int>(d_out), d_head, mul,
@@ -619,7 +931,7 @@ static int launch_gat_compact(const bigcn_plan *plan, const int64_t *row_ptr, co
 
 template <typename T, int H>
 static int launch_gat_compact_groups(int groups, const bigcn_plan *plan, const int64_t *row_ptr,
-                                     const int32_t *col_idx, int64_t n, const GatMap &map, const char *rows,
+                                     const int32_t *col_idx, int64_t n, const GatMap &map, char *rows,
                                      const float *beta, const float *alpha, const float *a_src, const float *a_dst,
                                      float *s, float *record, int64_t d_in, int64_t d_out, float slope, float *out,
                                      int64_t ld_out, hipStream_t st)
@@ -643,7 +955,7 @@ static int launch_gat_compact_groups(int groups, const bigcn_plan *plan, const i
 
 template <typename T>
 static int launch_gat_compact_heads(int heads, int groups, const bigcn_plan *plan, const int64_t *row_ptr,
-                                    const int32_t *col_idx, int64_t n, const GatMap &map, const char *rows,
+                                    const int32_t *col_idx, int64_t n, const GatMap &map, char *rows,
                                     const float *beta, const float *alpha, const float *a_src, const float *a_dst,
                                     float *s, float *record, int64_t d_in, int64_t d_out, float slope, float *out,
                                     int64_t ld_out, hipStream_t st)

@@ -77,6 +77,17 @@ def run_gpu(B, rp, ci, x, w, a_src, a_dst, heads, slope, bn=None, self_loops=Tru
     (2500, 40000, 200, 96, 4, True, False, 1.1),
     (6000, 20000, 64, 512, 8, False, True, 1.1),
     (2000, 30000, 700, 24, 1, True, False, 1.1),
+    # 256 columns of at most 127 input bits in one or two heads: the record rides in the rows'
+    # spare top bits (odd and even widths, empty rows, rows shared by a workgroup); with 128 input
+    # bits, four or eight heads or narrower rows it does not
+    (6000, 20000, 127, 256, 1, False, True, 1.1),
+    (1800, 8000, 33, 256, 2, True, False, 2.0),
+    (2000, 12000, 64, 256, 4, True, True, 2.0),
+    (1500, 30000, 100, 128, 2, True, False, 1.1),
+    (1500, 7000, 77, 64, 1, True, True, 2.0),
+    (1300, 6000, 100, 96, 2, True, False, 2.0),
+    (1200, 6000, 128, 256, 2, True, False, 2.0),
+    (1200, 6000, 60, 256, 8, True, False, 2.0),
     # plain fp32 rows: heads that are not a multiple of 8 columns wide
     (1500, 20000, 100, 36, 2, True, True, 1.2),
 ])
@@ -104,6 +115,22 @@ def test_gat_layer_matches_oracle(B, n, n_edges, d_in, d_out, heads, self_loops,
     check_against(got, ref, rp, ci, a_src, a_dst, heads)
     if not self_loops:
         assert np.array_equal(got[deg == 0], np.zeros((int((deg == 0).sum()), d_out), dtype=np.float32))
+
+
+@pytest.mark.parametrize("slope", [0.0, 1.0, 1.7, -0.3])
+def test_gat_record_inside_the_row_with_any_slope(B, slope):
+    """The kernels that keep the record in the rows' top bits take LeakyReLU as max(x, slope x) for
+    slopes in [0, 1] and as the two-branch form otherwise."""
+    rng = np.random.default_rng(31)
+    n, d_in, d_out, heads = 900, 100, 256, 2
+    rp, ci = chung_lu_csr(n, 9000, 2.5, 1.5, seed=31)
+    x = rng.standard_normal((n, d_in)).astype(np.float32)
+    w = rng.uniform(-1, 1, size=(d_in, d_out)).astype(np.float32)
+    a_src = (rng.standard_normal((heads, d_out // heads)) / 8).astype(np.float32)
+    a_dst = (rng.standard_normal((heads, d_out // heads)) / 8).astype(np.float32)
+    ref = oracle.gat_layer(rp, ci, x, w, a_src, a_dst, heads=heads, negative_slope=slope)
+    got = run_gpu(B, rp, ci, x, w, a_src, a_dst, heads, slope).cpu().numpy()
+    check_against(got, ref, rp, ci, a_src, a_dst, heads)
 
 
 def test_gat_with_zero_attention_is_the_mean_aggregator_and_runs_are_identical(B):

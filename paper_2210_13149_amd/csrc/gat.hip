@@ -620,23 +620,15 @@ __device__ __forceinline__ float embedded_value(const uint2 raw, int v)
     return static_cast<float>(static_cast<int>(word << (24 - 8 * e)) >> 24);
 }
 
-// The half of a ballot that belongs to this lane: `upper` is all ones in lanes 32..63 and zero
-// in lanes 0..31 (the difference of the halves is scalar work; two vector instructions).
-__device__ __forceinline__ uint32_t own_half(uint64_t ballot, uint32_t upper)
-{
-    const uint32_t lo = static_cast<uint32_t>(ballot), hi = static_cast<uint32_t>(ballot >> 32);
-    return lo ^ ((lo ^ hi) & upper);
-}
-
-// Lane masks and offsets of the embedded kernels, kept as plain register values (as selects
-// the masks would cost a third instruction wherever they are used).
 constexpr int kGatEmbeddedLoads = 4;   // row loads in flight per wavefront (6 and 8 measured 2-3 % slower)
 
+// Per-lane constants of the embedded kernels.
 struct GatLaneMasks {
-    uint32_t upper;        // all ones in lanes 32..63
-    uint32_t head_bits;    // all ones in the lanes of the second head
     uint32_t lane_offset;  // byte offset of this lane's segment in a row
-    int half;              // lane / 32
+    int half;              // lane / 32: which of a load's two neighbours this lane reads
+    int position;          // lane mod 8: the neighbour of a group that this lane scores
+    int head_lane;         // 4 x the first softmax lane of this row lane's head (a ds_bpermute address)
+    int weight_lane;       // 4 x the softmax lane of this row lane's head and of the first load's neighbour
 };
 
 // U row loads: neighbour `from` + 2 u of the batch of `cnt` (from = t + lane / 32) for
@@ -654,31 +646,96 @@ __device__ __forceinline__ void gat_fetch_group(const char *__restrict__ rows, c
     }
 }
 
-// The loaded neighbours into the state.  kUnitSlope: 0 <= slope <= 1, where
+// Softmax state while the neighbours of a node stream by, kept once per head instead of once per
+// lane: lane 8 h + j (h < H, j < 8) works on head h and on the j-th neighbour of each group of
+// eight; m and ref are the same in the eight lanes of a head, l and sw are partial sums over j.
+struct GatGroupState {
+    float m;          // running maximum of e_ij log2(e)
+    float ref;        // m, or 0 while m is -inf (so that exp2(x - ref) is never inf - inf)
+    float l;          // sum of 2^(e_ij - m)
+    float sw;         // sum of 2^(e_ij - m) beta_j
+};
+
+template <int kCtrl>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kCtrl, 0xf, 0xf, true));
+}
+
+// maximum / sum over the eight lanes 8 q .. 8 q + 7, in all of them
+// (the median of a, b and +inf is max(a, b) in one instruction: fmaxf adds one to quieten NaNs)
+__device__ __forceinline__ float max_plain(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, INFINITY); }
+__device__ __forceinline__ float max_of_eight(float v)
+{
+    v = max_plain(v, dpp_move<0xb1>(v));       // quad_perm [1, 0, 3, 2]
+    v = max_plain(v, dpp_move<0x4e>(v));       // quad_perm [2, 3, 0, 1]
+    return max_plain(v, dpp_move<0x141>(v));   // row_half_mirror
+}
+__device__ __forceinline__ float sum_of_eight(float v)
+{
+    v += dpp_move<0xb1>(v);
+    v += dpp_move<0x4e>(v);
+    return v + dpp_move<0x141>(v);
+}
+
+// v[kLane] = value, a wave-uniform word.  The compiler's own v_writelane (not inline assembly):
+// an SGPR written by a vector compare needs two wait states before a vector instruction reads
+// it, which the compiler inserts only around instructions it can see.
+__device__ int amdgcn_writelane(int value, int lane, int old) __asm("llvm.amdgcn.writelane.i32");
+template <int kLane>
+__device__ __forceinline__ void write_lane(int &v, uint32_t value)
+{
+    v = amdgcn_writelane(static_cast<int>(value), kLane, v);
+}
+
+// The record words of the two neighbours of load kLoad (ballots over their carrier bits) into
+// the softmax lanes: beta_j into lane j of bw, t_j[h] into lane 8 h + j of tw, j = 2 kLoad + half.
+template <int H, int kLoad>
+__device__ __forceinline__ void gat_record_to_lanes(const uint2 raw, int &tw, int &bw)
+{
+    const uint64_t ballot_b = __ballot(static_cast<int>(raw.x) < 0);
+    const uint64_t ballot_0 = __ballot(static_cast<int>(raw.y) < 0);
+    write_lane<2 * kLoad>(bw, static_cast<uint32_t>(ballot_b));
+    write_lane<2 * kLoad + 1>(bw, static_cast<uint32_t>(ballot_b >> 32));
+    write_lane<2 * kLoad>(tw, static_cast<uint32_t>(ballot_0));
+    write_lane<2 * kLoad + 1>(tw, static_cast<uint32_t>(ballot_0 >> 32));
+    if constexpr (H == 2) {
+        const uint64_t ballot_1 = __ballot((raw.x & 0x00800000u) != 0u);
+        write_lane<8 + 2 * kLoad>(tw, static_cast<uint32_t>(ballot_1));
+        write_lane<8 + 2 * kLoad + 1>(tw, static_cast<uint32_t>(ballot_1 >> 32));
+    }
+}
+
+__device__ __forceinline__ float from_lane(int byte_address, float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(byte_address, __builtin_bit_cast(int, v)));
+}
+
+// The loaded neighbours (t .. t + 7 of the batch of cnt) into the state.  The ballots over the
+// carrier bits are scalar values; they are written into lanes 0..15 (t_j[h] of neighbour j into
+// lane 8 h + j, beta_j into lane j and lane 8 + j), where the scores, the running maximum and the
+// weights are formed once per neighbour and head, and every row lane fetches the weight of its
+// neighbour and head through the LDS crossbar.  kUnitSlope: 0 <= slope <= 1, where
 // LeakyReLU(x) = max(x, slope x).
 template <int H, bool kUnitSlope, int U>
-__device__ __forceinline__ void gat_consume_group(const uint2 (&raw)[U], const GatLaneMasks &lm, int from, int cnt,
-                                                  float s_mine, float slope, GatLaneState &st)
+__device__ __forceinline__ void gat_consume_group(const uint2 (&raw)[U], const GatLaneMasks &lm, int t, int cnt,
+                                                  float s_lane, float slope, GatGroupState &st, float (&acc)[8])
 {
+    static_assert(U == 4, "a group is eight neighbours: four loads of two");
     constexpr int V = 8;
-    float bj[U], e[U];
-    float top = -INFINITY;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const bool present = from < cnt - 2 * u;
-        const uint32_t bits_b = own_half(__ballot(static_cast<int>(raw[u].x) < 0), lm.upper);
-        uint32_t bits_t = own_half(__ballot(static_cast<int>(raw[u].y) < 0), lm.upper);
-        if constexpr (H == 2) {
-            const uint32_t bits_1 = own_half(__ballot((raw[u].x & 0x00800000u) != 0u), lm.upper);
-            bits_t ^= (bits_t ^ bits_1) & lm.head_bits;
-        }
-        bj[u] = __builtin_bit_cast(float, bits_b);               // 0 for an absent neighbour
-        const float x = s_mine + __builtin_bit_cast(float, bits_t);
-        const float act = kUnitSlope ? fmaxf(x, slope * x) : leaky(x, slope);
-        e[u] = present ? act : -INFINITY;
-        top = fmaxf(top, e[u]);
-    }
-    if (__ballot(top > st.m) != 0ull) {                       // some lane's maximum moves: rescale
+    int tw = 0, bw = 0;
+    gat_record_to_lanes<H, 0>(raw[0], tw, bw);
+    gat_record_to_lanes<H, 1>(raw[1], tw, bw);
+    gat_record_to_lanes<H, 2>(raw[2], tw, bw);
+    gat_record_to_lanes<H, 3>(raw[3], tw, bw);
+    // lanes 8..15 take beta_j from lanes 0..7 (row_shr:8 into the upper two banks of a row)
+    if constexpr (H == 2) bw = __builtin_amdgcn_update_dpp(bw, bw, 0x118, 0xf, 0xc, false);
+    const bool present = (lm.position) < cnt - t;
+    const float x = s_lane + __builtin_bit_cast(float, tw);
+    const float act = kUnitSlope ? fmaxf(x, slope * x) : leaky(x, slope);
+    const float e = present ? act : -INFINITY;
+    const float top = max_of_eight(e);
+    if ((__ballot(top > st.m) & 0xffffull) != 0ull) {          // a head's maximum moves: rescale
         const float mn = fmaxf(st.m, top);
         const float ref = mn == -INFINITY ? 0.0f : mn;
         const float f = exp2_fast(st.m - ref);                // 0 while m is -inf
@@ -686,37 +743,44 @@ __device__ __forceinline__ void gat_consume_group(const uint2 (&raw)[U], const G
         st.ref = ref;
         st.l *= f;
         st.sw *= f;
+        const float mine = from_lane(lm.head_lane, f);
 #pragma unroll
-        for (int v = 0; v < V; ++v) st.acc[v] *= f;
+        for (int v = 0; v < V; ++v) acc[v] *= mine;
     }
+    const float pe = exp2_fast(e - st.ref);                   // 0 for an absent neighbour
+    const float w = pe * __builtin_bit_cast(float, bw);
+    st.l += pe;
+    st.sw += w;
+    float mine[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) mine[u] = from_lane(lm.weight_lane + 8 * u, w);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const float pe = exp2_fast(e[u] - st.ref);            // 0 for an absent neighbour
-        const float w = pe * bj[u];
-        st.l += pe;
-        st.sw += w;
 #pragma unroll
-        for (int v = 0; v < V; ++v) st.acc[v] = fmaf(w, embedded_value(raw[u], v), st.acc[v]);
+        for (int v = 0; v < V; ++v) acc[v] = fmaf(mine[u], embedded_value(raw[u], v), acc[v]);
     }
 }
 
 // Neighbours p0..p1-1 of one node; k_first: their first 64 column indices, one per lane (0 in
-// the lanes past the list).  The column indices of a batch of 64 are fetched one batch ahead.
-// (Issuing a group's loads before the group in front of it is used was measured and is 4 %
-// slower: the kernel waits for issue slots and for the memory system's rate, not for latency.)
+// the lanes past the list); s_lane: s_i log2(e) of the head this lane works on in the softmax
+// lanes.  The column indices of a batch of 64 are fetched one batch ahead.  (Issuing a group's
+// loads before the group in front of it is used was measured and is 4 % slower: the kernel
+// waits for issue slots and for the memory system's rate, not for latency.)  At the end every
+// lane holds the state of its own head and columns, the two halves of the wavefront added.
 template <int H, bool kUnitSlope>
 __device__ __forceinline__ void gat_accumulate_embedded(const int32_t *__restrict__ col_idx,
                                                         const char *__restrict__ rows, const GatLaneMasks &lm,
-                                                        float s_mine, float slope, int64_t p0, int64_t p1, int k_first,
-                                                        int lane, GatLaneState &st)
+                                                        float s_lane, float slope, int64_t p0, int64_t p1, int k_first,
+                                                        int lane, GatLaneState &out)
 {
     constexpr int V = 8, U = kGatEmbeddedLoads;
+    GatGroupState st;
     st.m = -INFINITY;
     st.ref = 0.0f;
     st.l = 0.0f;
     st.sw = 0.0f;
 #pragma unroll
-    for (int v = 0; v < V; ++v) st.acc[v] = 0.0f;
+    for (int v = 0; v < V; ++v) out.acc[v] = 0.0f;
 
     int k_ahead = k_first;
     for (int64_t pb = p0; pb < p1; pb += kWave) {
@@ -727,20 +791,28 @@ __device__ __forceinline__ void gat_accumulate_embedded(const int32_t *__restric
         for (int t = 0; t < cnt; t += 2 * U) {
             uint2 raw[U];
             gat_fetch_group<U>(rows, lm, k, from, cnt, raw);
-            gat_consume_group<H, kUnitSlope, U>(raw, lm, from, cnt, s_mine, slope, st);
+            gat_consume_group<H, kUnitSlope, U>(raw, lm, t, cnt, s_lane, slope, st, out.acc);
             from += 2 * U;
         }
     }
+    // totals of the head's eight lanes, handed to the row lanes of that head; the halves added
+    const float l = sum_of_eight(st.l), sw = sum_of_eight(st.sw);
+    out.m = from_lane(lm.head_lane, st.m);
+    out.ref = out.m == -INFINITY ? 0.0f : out.m;
+    out.l = from_lane(lm.head_lane, l);
+    out.sw = from_lane(lm.head_lane, sw);
+#pragma unroll
+    for (int v = 0; v < V; ++v) out.acc[v] += __shfl_xor(out.acc[v], 32, kWave);
 }
 
 __device__ __forceinline__ GatLaneMasks gat_lane_masks(int lane, bool second_head)
 {
     GatLaneMasks lm;
-    lm.upper = lane >= 32 ? ~0u : 0u;
-    lm.head_bits = second_head ? ~0u : 0u;
     lm.lane_offset = static_cast<uint32_t>(lane & 31) * 8u;
     lm.half = lane >> 5;
-    asm volatile("" : "+v"(lm.upper), "+v"(lm.head_bits));
+    lm.position = lane & 7;
+    lm.head_lane = second_head ? 32 : 0;
+    lm.weight_lane = lm.head_lane + 4 * lm.half;
     return lm;
 }
 
@@ -758,18 +830,6 @@ __device__ __forceinline__ void gat_merge_embedded(GatLaneState &st, float m2, f
     st.sw = fmaf(f2, sw2, st.sw * f1);
 #pragma unroll
     for (int v = 0; v < 8; ++v) st.acc[v] = fmaf(f2, acc2[v], st.acc[v] * f1);
-}
-
-// the two halves of the wavefront hold the two halves of the neighbour list
-__device__ __forceinline__ void gat_join_halves(GatLaneState &st)
-{
-    const float m2 = __shfl_xor(st.m, 32, kWave);
-    const float l2 = __shfl_xor(st.l, 32, kWave);
-    const float sw2 = __shfl_xor(st.sw, 32, kWave);
-    float acc2[8];
-#pragma unroll
-    for (int v = 0; v < 8; ++v) acc2[v] = __shfl_xor(st.acc[v], 32, kWave);
-    gat_merge_embedded(st, m2, l2, sw2, acc2);
 }
 
 __device__ __forceinline__ void gat_finish_embedded(const GatLaneState &st, int64_t row, int lane, float mul,
@@ -807,6 +867,7 @@ __global__ __launch_bounds__(kBlock, 8) void gat_aggregate_embedded_kernel(
     const int lane = lane_id();
     const int wave = wave_in_block();
     const bool second_head = H == 2 && (lane & 31) >= 16;
+    const int softmax_head = H == 2 ? (lane >> 3) & 1 : 0;     // of the head this lane scores in lanes 0..15
     const GatLaneMasks lm = gat_lane_masks(lane, second_head);
     GatLaneState st;
 
@@ -818,10 +879,9 @@ __global__ __launch_bounds__(kBlock, 8) void gat_aggregate_embedded_kernel(
         int64_t q0 = p0 + wave * chunk, q1 = q0 + chunk;
         if (q0 > p1) q0 = p1;
         if (q1 > p1) q1 = p1;
-        const float s_mine = s[row * H + (second_head ? 1 : 0)] * kLog2e;
+        const float s_lane = s[row * H + softmax_head] * kLog2e;
         const int k_first = q0 + lane < q1 ? col_idx[q0 + lane] : 0;
-        gat_accumulate_embedded<H, kUnitSlope>(col_idx, rows, lm, s_mine, slope, q0, q1, k_first, lane, st);
-        gat_join_halves(st);
+        gat_accumulate_embedded<H, kUnitSlope>(col_idx, rows, lm, s_lane, slope, q0, q1, k_first, lane, st);
         if (wave > 0 && lane < 32) {
 #pragma unroll
             for (int v = 0; v < V; ++v) merge[wave - 1][v][lane] = st.acc[v];
@@ -845,11 +905,10 @@ __global__ __launch_bounds__(kBlock, 8) void gat_aggregate_embedded_kernel(
     const int64_t entry = n_block_rows + (static_cast<int64_t>(blockIdx.x) - n_block_rows) * kWavesPerBlock + wave;
     if (entry >= n) return;                                    // wave-uniform
     const int64_t row = row_order[entry];
-    const float s_mine = s[row * H + (second_head ? 1 : 0)] * kLog2e;
+    const float s_lane = s[row * H + softmax_head] * kLog2e;
     const int64_t p0 = row_ptr[row], p1 = row_ptr[row + 1];
     const int k_first = p0 + lane < p1 ? col_idx[p0 + lane] : 0;
-    gat_accumulate_embedded<H, kUnitSlope>(col_idx, rows, lm, s_mine, slope, p0, p1, k_first, lane, st);
-    gat_join_halves(st);
+    gat_accumulate_embedded<H, kUnitSlope>(col_idx, rows, lm, s_lane, slope, p0, p1, k_first, lane, st);
     gat_finish_embedded(st, row, lane, mul, bias, alpha, out, ld_out, vector_store);
 }
 

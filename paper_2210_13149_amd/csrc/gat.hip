@@ -594,15 +594,18 @@ __global__ __launch_bounds__(kBlock, (gat_min_waves<T, H>())) void gat_aggregate
 // One-byte rows of 256 columns whose values fit 7 bits (at most 127 input bits) have a spare top
 // bit in every byte, and gat_scores_kernel stores beta_j and t_j there: a neighbour costs its two
 // row lines and nothing else.  A load instruction fetches two neighbours (lanes 0..31 one,
-// lanes 32..63 the other); three ballots over the carrier bits hand every lane the 32-bit words of
-// its own neighbour, and each lane keeps the softmax state of its own head and its own half of
-// the neighbour list: the running maximum (raised per eight neighbours, the rescaling skipped
-// while no lane's maximum moves), the sum of weights and the weighted values.  Scores are kept
-// in base 2 (t_j and s_i times log2 e; LeakyReLU commutes with a positive factor), so a weight is
-// one v_exp_f32.  The two halves meet at the end of the row.  The kernel is bound by its vector
-// instructions, so the inner loop is written for their count.
+// lanes 32..63 the other), and three ballots over the carrier bits give their record words as
+// scalar values.  These are written into lanes 0..15, which form the scores, the running maximum
+// (raised per eight neighbours, the rescaling skipped while no head's maximum moves) and the
+// weights once per neighbour and head; the row lanes fetch the weight of their neighbour and head
+// from there and accumulate the weighted values.  Scores are kept in base 2 (t_j and s_i times
+// log2 e; LeakyReLU commutes with a positive factor), so a weight is one v_exp_f32.  The kernel
+// is bound by its vector instructions, so the inner loop is written for their count.
+//
+// State of a node at the end of its row (and between the wavefronts that share a long row), per
+// row lane:
 struct GatLaneState {
-    float m;          // running maximum of e_ij log2(e) over this lane's head and half
+    float m;          // maximum of e_ij log2(e) over the lane's head
     float ref;        // m, or 0 while m is -inf (so that exp2(x - ref) is never inf - inf)
     float l;          // sum of 2^(e_ij - m)
     float sw;         // sum of 2^(e_ij - m) beta_j

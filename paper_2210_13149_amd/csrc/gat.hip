@@ -294,63 +294,80 @@ __global__ __launch_bounds__(kBlock) void gat_scores_kernel(char *__restrict__ r
     }
     const int64_t wave = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block();
     const int64_t n_waves = static_cast<int64_t>(gridDim.x) * kWavesPerBlock;
-    for (int64_t i0 = wave * nodes_per_step; i0 < n; i0 += n_waves * nodes_per_step) {
-        const int64_t i = i0 + (butterfly ? slot : 0);
-        const bool mine = live && i < n;
-        float ps = 0.0f, pt = 0.0f, b = 0.0f;
-        if (mine) {
-            GatSegment<T> seg;
-            seg.load(rows + static_cast<uint64_t>(i) * row_bytes + g * V * sizeof(T));
-            b = beta[i];
+    // kAhead steps' rows are requested before the first is used (a wavefront's step is 512 bytes
+    // or less; with one in flight the launch reads at a third of the rate)
+    constexpr int kAhead = 4;
+    const int64_t step_nodes = n_waves * nodes_per_step;
+    for (int64_t i0 = wave * nodes_per_step; i0 < n; i0 += step_nodes * kAhead) {
+        GatSegment<T> segs[kAhead];
+        float bs[kAhead];
 #pragma unroll
-            for (int v = 0; v < V; ++v) {
-                const float q = seg.get(v);
-                ps = fmaf(ca[v], q, ps);
-                pt = fmaf(cd[v], q, pt);
+        for (int q = 0; q < kAhead; ++q) {
+            const int64_t i = i0 + q * step_nodes + (butterfly ? slot : 0);
+            bs[q] = 0.0f;
+            if (live && i < n) {
+                segs[q].load(rows + static_cast<uint64_t>(i) * row_bytes + g * V * sizeof(T));
+                bs[q] = beta[i];
             }
         }
-        if (butterfly) {
-            for (int off = 1; off < lanes_per_head; off <<= 1) {
-                ps += __shfl_xor(ps, off, kWave);
-                pt += __shfl_xor(pt, off, kWave);
-            }
-            const float t_mine = b * fmaf(mul, pt, const_t[0]);
-            if (mine && g == my_head * lanes_per_head) {            // first lane of the head's group
-                s[i * H + my_head] = b * fmaf(mul, ps, const_s[0]);
-                if (!embed) {
-                    record[i * gat_record_floats<H>() + 1 + my_head] = t_mine;
-                    if (g == 0) record[i * gat_record_floats<H>()] = b;
+#pragma unroll
+        for (int q = 0; q < kAhead; ++q) {
+            if (i0 + q * step_nodes >= n) break;                    // wave-uniform
+            const int64_t i = i0 + q * step_nodes + (butterfly ? slot : 0);
+            const bool mine = live && i < n;
+            GatSegment<T> &seg = segs[q];
+            const float b = bs[q];
+            float ps = 0.0f, pt = 0.0f;
+            if (mine) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    const float x = seg.get(v);
+                    ps = fmaf(ca[v], x, ps);
+                    pt = fmaf(cd[v], x, pt);
                 }
             }
-            if constexpr (gat_embeds<T, G, H>()) {
-                if (embed) {                                        // wave-uniform; every lane is live here
-                    const float t2 = t_mine * kLog2e;
-                    const float other = H == 2 ? __shfl_xor(t2, 16, kWave) : t2;
-                    const uint32_t t0 = __builtin_bit_cast(uint32_t, my_head == 0 ? t2 : other);
-                    const uint32_t t1 = __builtin_bit_cast(uint32_t, my_head == 0 ? other : t2);
-                    const uint32_t bb = __builtin_bit_cast(uint32_t, b);
-                    if (mine) {
-                        uint2 *at = reinterpret_cast<uint2 *>(rows + static_cast<uint64_t>(i) * row_bytes + g * V);
-                        uint2 raw = *at;
-                        raw.x = (raw.x & 0x7fffffffu) | (((bb >> g) & 1u) << 31);
-                        raw.y = (raw.y & 0x7fffffffu) | (((t0 >> g) & 1u) << 31);
-                        if (H == 2) raw.x = (raw.x & 0xff7fffffu) | (((t1 >> g) & 1u) << 23);
-                        *at = raw;
+            if (butterfly) {
+                for (int off = 1; off < lanes_per_head; off <<= 1) {
+                    ps += __shfl_xor(ps, off, kWave);
+                    pt += __shfl_xor(pt, off, kWave);
+                }
+                const float t_mine = b * fmaf(mul, pt, const_t[0]);
+                if (mine && g == my_head * lanes_per_head) {        // first lane of the head's group
+                    s[i * H + my_head] = b * fmaf(mul, ps, const_s[0]);
+                    if (!embed) {
+                        record[i * gat_record_floats<H>() + 1 + my_head] = t_mine;
+                        if (g == 0) record[i * gat_record_floats<H>()] = b;
                     }
                 }
-            }
-        } else {
-            const float b0 = __shfl(b, 0, kWave);
-#pragma unroll
-            for (int h = 0; h < H; ++h) {
-                const float ss = wave_sum(mine && my_head == h ? ps : 0.0f);
-                const float tt = wave_sum(mine && my_head == h ? pt : 0.0f);
-                if (lane == 0) {
-                    s[i * H + h] = b0 * fmaf(mul, ss, const_s[h]);
-                    record[i * gat_record_floats<H>() + 1 + h] = b0 * fmaf(mul, tt, const_t[h]);
+                if constexpr (gat_embeds<T, G, H>()) {
+                    if (embed) {                                    // wave-uniform; every lane is live here
+                        const float t2 = t_mine * kLog2e;
+                        const float other = H == 2 ? __shfl_xor(t2, 16, kWave) : t2;
+                        const uint32_t t0 = __builtin_bit_cast(uint32_t, my_head == 0 ? t2 : other);
+                        const uint32_t t1 = __builtin_bit_cast(uint32_t, my_head == 0 ? other : t2);
+                        const uint32_t bb = __builtin_bit_cast(uint32_t, b);
+                        if (mine) {
+                            uint2 raw = seg.raw;
+                            raw.x = (raw.x & 0x7fffffffu) | (((bb >> g) & 1u) << 31);
+                            raw.y = (raw.y & 0x7fffffffu) | (((t0 >> g) & 1u) << 31);
+                            if (H == 2) raw.x = (raw.x & 0xff7fffffu) | (((t1 >> g) & 1u) << 23);
+                            *reinterpret_cast<uint2 *>(rows + static_cast<uint64_t>(i) * row_bytes + g * V) = raw;
+                        }
+                    }
                 }
+            } else {
+                const float b0 = __shfl(b, 0, kWave);
+#pragma unroll
+                for (int h = 0; h < H; ++h) {
+                    const float ss = wave_sum(mine && my_head == h ? ps : 0.0f);
+                    const float tt = wave_sum(mine && my_head == h ? pt : 0.0f);
+                    if (lane == 0) {
+                        s[i * H + h] = b0 * fmaf(mul, ss, const_s[h]);
+                        record[i * gat_record_floats<H>() + 1 + h] = b0 * fmaf(mul, tt, const_t[h]);
+                    }
+                }
+                if (lane == 0) record[i * gat_record_floats<H>()] = b0;
             }
-            if (lane == 0) record[i * gat_record_floats<H>()] = b0;
         }
     }
 }

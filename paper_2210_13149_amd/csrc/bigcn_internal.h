@@ -205,6 +205,13 @@ int launch_bitgemm_fp4_rows(const uint64_t *a_bits, int64_t m, int64_t lda, cons
                             int64_t ldb, int64_t k_bits, const float *src_scale, void *c_rows, void *alt_rows,
                             RowLayout layout, hipStream_t stream, int *escape_flag = nullptr);
 
+// The same kernel writing one-byte rows in column order (position = column, nothing but the
+// values in the row; K <= 255): what launch_bitgemm_natural writes, for more than 32768 rows of
+// 64 / 128 / 256 / 512 positions.
+bool fp4_natural_covers(int64_t m, int64_t k_bits, int positions);
+int launch_bitgemm_fp4_natural(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits, int64_t n,
+                               int64_t ldb, int64_t k_bits, void *rows, int positions, hipStream_t stream);
+
 // Aggregation of layer l fused with the rescale and with the binarisation of layer l+1.
 // Bi-GCN: dst_mul = next_row_mul = D^-1/2 and no own-row term.  Bi-GraphSAGE (mean aggregator):
 // dst_mul = 1/|N_i|, next_row_mul = nullptr, and the own-row term is described by self_*.

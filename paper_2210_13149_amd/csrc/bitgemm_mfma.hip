@@ -854,4 +854,41 @@ int launch_bitgemm_fp4_rows(const uint64_t *a_bits, int64_t m, int64_t lda, cons
     }
 }
 
+// One-byte product rows in column order (position = column, no scale inside the row) on the same
+// kernel: the consumers that read a row's columns next to each other (the Bi-GAT kernels).
+bool fp4_natural_covers(int64_t m, int64_t k_bits, int positions)
+{
+    if (k_bits > 255 || m <= 32768) return false;
+    if (positions != 64 && positions != 128 && positions != 256 && positions != 512) return false;
+    return fp4_rows_lds_bytes(positions, static_cast<int>((k_bits + 63) / 64)) <= 64 * 1024;
+}
+
+int launch_bitgemm_fp4_natural(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits, int64_t n,
+                               int64_t ldb, int64_t k_bits, void *rows, int positions, hipStream_t stream)
+{
+    if (!fp4_natural_covers(m, k_bits, positions) || n > positions) return BIGCN_EINVAL;
+    Fp4RowsParams p;
+    p.positions = positions;
+    p.groups = positions;             // position p holds column p / vec + groups (p % vec) = p
+    p.vec = 1;
+    p.n = static_cast<int>(n);
+    p.k_bits = static_cast<int>(k_bits);
+    p.n_steps = static_cast<int>((k_bits + 63) / 64);
+    p.seven_bit = 0;
+    p.tail_scale = 0;
+    p.last_bytes = 0;
+    p.escape = 0;
+    p.alt_half = 0;
+    switch (positions) {
+    case 64:
+        return launch_fp4_rows<64, 4>(a_bits, m, lda, b_bits, ldb, nullptr, p, rows, nullptr, stream, nullptr);
+    case 128:
+        return launch_fp4_rows<128, 4>(a_bits, m, lda, b_bits, ldb, nullptr, p, rows, nullptr, stream, nullptr);
+    case 256:
+        return launch_fp4_rows<256, 16>(a_bits, m, lda, b_bits, ldb, nullptr, p, rows, nullptr, stream, nullptr);
+    default:
+        return launch_fp4_rows<512, 16>(a_bits, m, lda, b_bits, ldb, nullptr, p, rows, nullptr, stream, nullptr);
+    }
+}
+
 }  // namespace bigcn

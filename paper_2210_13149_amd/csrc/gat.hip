@@ -1095,7 +1095,11 @@ extern "C" int bigcn_gat_layer(const bigcn_plan *plan, const int64_t *row_ptr, c
 
     if (map.compact) {
         char *rows = ws + map.z_off;
-        rc = launch_bitgemm_natural(bits, n, words, w_bits, d_out, ld_words, d_in, rows, map.groups * 8, map.kind, st);
+        // large layers of one-byte rows on the matrix cores, everything else by XOR and bit counts
+        if (map.kind == kI8 && fp4_natural_covers(n, d_in, map.groups * 8))
+            rc = launch_bitgemm_fp4_natural(bits, n, words, w_bits, d_out, ld_words, d_in, rows, map.groups * 8, st);
+        else
+            rc = launch_bitgemm_natural(bits, n, words, w_bits, d_out, ld_words, d_in, rows, map.groups * 8, map.kind, st);
         if (rc != BIGCN_OK) return rc;
         if (map.kind == kI8)
             return launch_gat_compact_heads<int8_t>(heads, map.groups, plan, row_ptr, col_idx, n, map, rows, beta,

@@ -88,6 +88,13 @@ def run_gpu(B, rp, ci, x, w, a_src, a_dst, heads, slope, bn=None, self_loops=Tru
     (1300, 6000, 100, 96, 2, True, False, 2.0),
     (1200, 6000, 128, 256, 2, True, False, 2.0),
     (1200, 6000, 60, 256, 8, True, False, 2.0),
+    # more than 32768 nodes: the one-byte rows come from the matrix-core kernel (64, 128, 256 and 512
+    # stored positions, rows narrower than their stored width, the widest one-byte layer)
+    (40000, 150000, 100, 64, 1, True, False, 2.0),
+    (40000, 150000, 255, 128, 2, True, True, 2.0),
+    (36000, 120000, 127, 256, 1, True, False, 2.0),
+    (34000, 100000, 33, 512, 8, True, False, 2.0),
+    (40000, 150000, 90, 40, 1, True, True, 2.0),
     # plain fp32 rows: heads that are not a multiple of 8 columns wide
     (1500, 20000, 100, 36, 2, True, True, 1.2),
 ])

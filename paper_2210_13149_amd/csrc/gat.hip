@@ -877,7 +877,7 @@ __device__ __forceinline__ void gat_finish_embedded(const GatLaneState &st, int6
 // take less than 4 GiB (offsets into them are 32-bit).
 template <int H, bool kUnitSlope>
 __global__ __launch_bounds__(kBlock, 8) void gat_aggregate_embedded_kernel(
-    const int32_t *__restrict__ row_order, int64_t n, int64_t n_block_rows, const int64_t *__restrict__ row_ptr,
+    const bigcn_plan_entry *__restrict__ entries, int64_t n, int64_t n_block_rows,
     const int32_t *__restrict__ col_idx, const char *__restrict__ rows, const float *__restrict__ s,
     const float *__restrict__ alpha, float mul, float bias, float slope, float *__restrict__ out, int64_t ld_out,
     int vector_store)
@@ -892,8 +892,9 @@ __global__ __launch_bounds__(kBlock, 8) void gat_aggregate_embedded_kernel(
     GatLaneState st;
 
     if (static_cast<int64_t>(blockIdx.x) < n_block_rows) {
-        const int64_t row = row_order[blockIdx.x];
-        const int64_t p0 = row_ptr[row], p1 = row_ptr[row + 1];
+        const bigcn_plan_entry e = entries[blockIdx.x];       // the row and its extent in one load
+        const int64_t row = e.row;
+        const int64_t p0 = e.first, p1 = e.first + e.count;
         int64_t chunk = (p1 - p0 + kWavesPerBlock - 1) / kWavesPerBlock;
         chunk = (chunk + kWave - 1) / kWave * kWave;
         int64_t q0 = p0 + wave * chunk, q1 = q0 + chunk;
@@ -924,9 +925,10 @@ __global__ __launch_bounds__(kBlock, 8) void gat_aggregate_embedded_kernel(
     }
     const int64_t entry = n_block_rows + (static_cast<int64_t>(blockIdx.x) - n_block_rows) * kWavesPerBlock + wave;
     if (entry >= n) return;                                    // wave-uniform
-    const int64_t row = row_order[entry];
+    const bigcn_plan_entry e = entries[entry];
+    const int64_t row = e.row;
     const float s_lane = s[row * H + softmax_head] * kLog2e;
-    const int64_t p0 = row_ptr[row], p1 = row_ptr[row + 1];
+    const int64_t p0 = e.first, p1 = e.first + e.count;
     const int k_first = p0 + lane < p1 ? col_idx[p0 + lane] : 0;
     gat_accumulate_embedded<H, kUnitSlope>(col_idx, rows, lm, s_lane, slope, p0, p1, k_first, lane, st);
     gat_finish_embedded(st, row, lane, mul, bias, alpha, out, ld_out, vector_store);
@@ -991,12 +993,12 @@ static int launch_gat_compact(const bigcn_plan *plan, const int64_t *row_ptr, co
         if (embed) {
             const dim3 grid(static_cast<unsigned>(blocks));
             if (slope >= 0.0f && slope <= 1.0f)
-                hipLaunchKernelGGL((gat_aggregate_embedded_kernel<H, true>), grid, dim3(kBlock), 0, st, plan->row_order, n,
-                                   plan->n_block_rows, row_ptr, col_idx, rows, s, alpha, mul, bias, slope, out, ld_out,
+                hipLaunchKernelGGL((gat_aggregate_embedded_kernel<H, true>), grid, dim3(kBlock), 0, st, plan->entries, n,
+                                   plan->n_block_rows, col_idx, rows, s, alpha, mul, bias, slope, out, ld_out,
                                    vector_store);
             else
-                hipLaunchKernelGGL((gat_aggregate_embedded_kernel<H, false>), grid, dim3(kBlock), 0, st, plan->row_order,
-                                   n, plan->n_block_rows, row_ptr, col_idx, rows, s, alpha, mul, bias, slope, out, ld_out,
+                hipLaunchKernelGGL((gat_aggregate_embedded_kernel<H, false>), grid, dim3(kBlock), 0, st, plan->entries,
+                                   n, plan->n_block_rows, col_idx, rows, s, alpha, mul, bias, slope, out, ld_out,
                                    vector_store);
             return check_launch();
         }

@@ -521,7 +521,7 @@ constexpr int gat_min_waves()
 
 template <typename T, int G, int H>
 __global__ __launch_bounds__(kBlock, (gat_min_waves<T, H>())) void gat_aggregate_kernel(
-    const int32_t *__restrict__ row_order, int64_t n, int64_t n_block_rows, const int64_t *__restrict__ row_ptr,
+    const bigcn_plan_entry *__restrict__ entries, int64_t n, int64_t n_block_rows,
     const int32_t *__restrict__ col_idx, const char *__restrict__ rows, uint32_t row_bytes,
     const float *__restrict__ s, const float *__restrict__ record, const float *__restrict__ alpha, int d_out,
     int d_head, float mul, float bias, float slope, float *__restrict__ out, int64_t ld_out, int vector_store)
@@ -539,8 +539,9 @@ __global__ __launch_bounds__(kBlock, (gat_min_waves<T, H>())) void gat_aggregate
     float si[H];
 
     if (static_cast<int64_t>(blockIdx.x) < n_block_rows) {
-        const int64_t row = row_order[blockIdx.x];
-        const int64_t p0 = row_ptr[row], p1 = row_ptr[row + 1];
+        const bigcn_plan_entry e = entries[blockIdx.x];       // the row and its extent in one load
+        const int64_t row = e.row;
+        const int64_t p0 = e.first, p1 = e.first + e.count;
         int64_t chunk = (p1 - p0 + kWavesPerBlock - 1) / kWavesPerBlock;
         chunk = (chunk + kWave - 1) / kWave * kWave;
         int64_t q0 = p0 + wave * chunk, q1 = q0 + chunk;
@@ -599,10 +600,11 @@ __global__ __launch_bounds__(kBlock, (gat_min_waves<T, H>())) void gat_aggregate
     }
     const int64_t entry = n_block_rows + (static_cast<int64_t>(blockIdx.x) - n_block_rows) * kWavesPerBlock + wave;
     if (entry >= n) return;                                    // wave-uniform
-    const int64_t row = row_order[entry];
+    const bigcn_plan_entry e = entries[entry];
+    const int64_t row = e.row;
 #pragma unroll
     for (int h = 0; h < H; ++h) si[h] = s[row * H + h];
-    gat_accumulate<T, G, H>(col_idx, lane_base, row_bytes, record, si, slope, my_head, row_ptr[row], row_ptr[row + 1],
+    gat_accumulate<T, G, H>(col_idx, lane_base, row_bytes, record, si, slope, my_head, e.first, e.first + e.count,
                             lane, wbuf, st);
     gat_finish<G, H>(st, row, lane, my_head, d_out, mul, bias, alpha, out, ld_out, vector_store);
 }
@@ -1004,7 +1006,7 @@ static int launch_gat_compact(const bigcn_plan *plan, const int64_t *row_ptr, co
         }
     }
     hipLaunchKernelGGL((gat_aggregate_kernel<T, G, H>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st,
-                       plan->row_order, n, plan->n_block_rows, row_ptr, col_idx, rows,
+                       plan->entries, n, plan->n_block_rows, col_idx, rows,
                        static_cast<uint32_t>(map.row_bytes), s, record, alpha, static_cast<int>(d_out), d_head, mul,
                        bias, slope, out, ld_out, vector_store);
     return check_launch();

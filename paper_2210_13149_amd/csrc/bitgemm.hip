@@ -834,14 +834,14 @@ int launch_bitgemm_natural(const uint64_t *a_bits, int64_t m, int64_t lda, const
     const int per_lane = positions >= 64 ? positions / 64 : 1;
     const int k = static_cast<int>(k_bits);
     if (kind == kI8) {
-        EpilogueLayout<int8_t> epi{static_cast<int8_t *>(rows), positions, k, nullptr, 0, 0, nullptr, 0};
+        EpilogueLayout<int8_t> epi{static_cast<int8_t *>(rows), positions, k, nullptr, 0, 0, nullptr, 0, nullptr};
         return dispatch_bitgemm(per_lane, 1, positions, a_bits, m, lda, b_bits, n, ldb, k_bits, 0xffffffffu, epi, stream);
     }
     if (kind == kF16) {
-        EpilogueLayout<__half> epi{static_cast<__half *>(rows), positions, k, nullptr, 0, 0, nullptr, 0};
+        EpilogueLayout<__half> epi{static_cast<__half *>(rows), positions, k, nullptr, 0, 0, nullptr, 0, nullptr};
         return dispatch_bitgemm(per_lane, 1, positions, a_bits, m, lda, b_bits, n, ldb, k_bits, 0xffffffffu, epi, stream);
     }
-    EpilogueLayout<float> epi{static_cast<float *>(rows), positions, k, nullptr, 0, 0, nullptr, 0};
+    EpilogueLayout<float> epi{static_cast<float *>(rows), positions, k, nullptr, 0, 0, nullptr, 0, nullptr};
     return dispatch_bitgemm(per_lane, 1, positions, a_bits, m, lda, b_bits, n, ldb, k_bits, 0xffffffffu, epi, stream);
 }
 

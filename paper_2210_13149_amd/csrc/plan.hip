@@ -213,7 +213,7 @@ extern "C" int bigcn_plan_create(const int64_t *row_ptr, const int32_t *col_idx,
             hipMalloc(&plan->entries, sizeof(bigcn_plan_entry) * n) != hipSuccess) {
             (void)hipGetLastError();
             if (plan->row_order != nullptr) (void)hipFree(plan->row_order);
-    if (plan->entries != nullptr) (void)hipFree(plan->entries);
+            if (plan->entries != nullptr) (void)hipFree(plan->entries);
             delete plan;
             return BIGCN_EHIP;
         }

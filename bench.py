@@ -317,18 +317,21 @@ def backward_leg(B, m, cfg, reps=3):
     return out
 
 
-def gat_leg(B, m, cfg, reps=3):
-    """One Bi-GAT layer (Sec. 4.4.1) on the workload's graph and features, timed alone: first-layer
-    shape of the paper's OGBN-Products GAT (two heads of 128 columns) scaled to the workload's
-    input width."""
+def gat_leg(B, m, cfg, reps=3, hidden=False):
+    """One Bi-GAT layer (Sec. 4.4.1) on the workload's graph, timed alone: first-layer shape of the
+    paper's OGBN-Products GAT (two heads of 128 columns) on the workload's features, or
+    (hidden=True) a hidden layer of the same width on seeded stand-ins for its 256 input columns."""
     import torch
-    d_in, d_out, heads = cfg.dims[0], 256, 2
+    d_in, d_out, heads = (256 if hidden else cfg.dims[0]), 256, 2
     gen = torch.Generator(device="cuda").manual_seed(11)
+    x = m["x"]
+    if hidden:
+        x = torch.randn((x.shape[0], d_in), dtype=torch.float32, device="cuda", generator=gen)
     w = torch.empty((d_in, d_out), dtype=torch.float32, device="cuda").uniform_(-1, 1, generator=gen)
     layer = B.Layer.from_weight(w)
     a_src = torch.randn((heads, d_out // heads), dtype=torch.float32, device="cuda", generator=gen) * 0.1
     a_dst = torch.randn((heads, d_out // heads), dtype=torch.float32, device="cuda", generator=gen) * 0.1
-    call = lambda: B.bigcn_gat_layer(m["plan"], m["row_ptr"], m["col_idx"], m["x"], layer, a_src, a_dst, heads=heads)
+    call = lambda: B.bigcn_gat_layer(m["plan"], m["row_ptr"], m["col_idx"], x, layer, a_src, a_dst, heads=heads)
     call()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -342,7 +345,8 @@ def gat_leg(B, m, cfg, reps=3):
     # per neighbour: its index, its compact product row (one byte per product up to 255 input
     # bits, fp16 to 2048, fp32 beyond) and its record {beta, t[heads]}, which rides in the row's
     # spare top bits when the products fit 7 bits (256 columns, at most two heads and 127 input bits)
-    elem = 1 if d_in <= 255 else (2 if d_in <= 2048 else 4)
+    # (256 input bits: one-byte values over the first 255, the last bit on the sign of beta)
+    elem = 1 if d_in <= 256 else (2 if d_in <= 2048 else 4)
     embedded = d_in <= 127 and d_out == 256 and heads <= 2
     per_neighbour = 4 + elem * d_out + (0 if embedded else 4 * (1 + heads))
     lines = 128 * (-(-(elem * d_out) // 128) + (0 if embedded else 1))   # the row's cache lines (+ one for the record)
@@ -751,6 +755,7 @@ def main():
     if not args.no_backward and cfg.model == "gcn":
         result["backward"] = backward_leg(B, m, cfg)
         result["gat_layer"] = gat_leg(B, m, cfg)
+        result["gat_hidden_layer"] = gat_leg(B, m, cfg, hidden=True)
     del m
     torch.cuda.empty_cache()
     if not args.no_gemm_sweep:

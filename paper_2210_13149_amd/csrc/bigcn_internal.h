@@ -176,7 +176,7 @@ int launch_pack_bitgemm_layout(const float *x, int64_t m, int64_t ld_x, const fl
 // floor(K/2) - popcount (K <= 255 only), fp16 / fp32 hold K - 2 popcount.
 int launch_bitgemm_natural(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits, int64_t n,
                            int64_t ldb, int64_t k_bits, void *rows, int positions, RowKind kind,
-                           hipStream_t stream);
+                           hipStream_t stream, uint32_t last_mask = 0xffffffffu);
 
 // Matrix-core (int8 MFMA) variant of the public bit-GEMM: same arguments and results.
 int launch_bitgemm_mfma(const uint64_t *a_bits, const float *a_scale, int64_t m, int64_t lda,

@@ -824,9 +824,11 @@ int launch_pack_bitgemm_layout(const float *x, int64_t m, int64_t ld_x, const fl
 // Product rows in column order (stored position = output column) for consumers that read a row's
 // columns next to each other: lane l produces positions [per_lane l, per_lane (l + 1)).  One
 // byte per product stores floor(K/2) - popcount (K <= 255), fp16 / fp32 store K - 2 popcount.
+// last_mask is ANDed onto the upper half of the last packed word of both operands (0x7fffffff
+// leaves bit 63 out: a layer of 256 bits whose last bit is carried outside the stored value).
 int launch_bitgemm_natural(const uint64_t *a_bits, int64_t m, int64_t lda, const uint64_t *b_bits, int64_t n,
                            int64_t ldb, int64_t k_bits, void *rows, int positions, RowKind kind,
-                           hipStream_t stream)
+                           hipStream_t stream, uint32_t last_mask)
 {
     if (m == 0 || n == 0) return BIGCN_OK;
     if (positions < n || positions % 8 != 0 || (positions >= 64 && positions % 64 != 0)) return BIGCN_EINVAL;
@@ -835,14 +837,14 @@ int launch_bitgemm_natural(const uint64_t *a_bits, int64_t m, int64_t lda, const
     const int k = static_cast<int>(k_bits);
     if (kind == kI8) {
         EpilogueLayout<int8_t> epi{static_cast<int8_t *>(rows), positions, k, nullptr, 0, 0, nullptr, 0, nullptr};
-        return dispatch_bitgemm(per_lane, 1, positions, a_bits, m, lda, b_bits, n, ldb, k_bits, 0xffffffffu, epi, stream);
+        return dispatch_bitgemm(per_lane, 1, positions, a_bits, m, lda, b_bits, n, ldb, k_bits, last_mask, epi, stream);
     }
     if (kind == kF16) {
         EpilogueLayout<__half> epi{static_cast<__half *>(rows), positions, k, nullptr, 0, 0, nullptr, 0, nullptr};
-        return dispatch_bitgemm(per_lane, 1, positions, a_bits, m, lda, b_bits, n, ldb, k_bits, 0xffffffffu, epi, stream);
+        return dispatch_bitgemm(per_lane, 1, positions, a_bits, m, lda, b_bits, n, ldb, k_bits, last_mask, epi, stream);
     }
     EpilogueLayout<float> epi{static_cast<float *>(rows), positions, k, nullptr, 0, 0, nullptr, 0, nullptr};
-    return dispatch_bitgemm(per_lane, 1, positions, a_bits, m, lda, b_bits, n, ldb, k_bits, 0xffffffffu, epi, stream);
+    return dispatch_bitgemm(per_lane, 1, positions, a_bits, m, lda, b_bits, n, ldb, k_bits, last_mask, epi, stream);
 }
 
 // Shapes on which the matrix cores measured faster than XOR + bit count (the FP4 path is the

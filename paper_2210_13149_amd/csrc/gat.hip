@@ -5,9 +5,10 @@
 // The attention vectors are not binarised.
 //
 // Compact path (every head a multiple of 8 columns wide): the bit-GEMM leaves the integer
-// products of a node as one compact row in column order (one byte per product up to 255 input
-// bits, fp16 up to 2048, fp32 beyond); the row scale beta_j and the scores t_j = a_dst . z_j sit
-// together in a small per-node record (256-column rows of at most 127 input bits, whose values
+// products of a node as one compact row in column order (one byte per product up to 256 input
+// bits, the last of 256 bits carried on the sign of the node's scale; fp16 up to 2048, fp32
+// beyond); the row scale beta_j and the scores t_j = a_dst . z_j sit together in a small
+// per-node record (256-column rows of at most 127 input bits, whose values
 // fit 7 bits, carry that record in spare top bits instead, so that a neighbour costs the two
 // cache lines of its row and no other).  The aggregation makes ONE pass over the neighbours of
 // a node: per batch of 64 neighbours the running maximum of e_ij is raised and the accumulators
@@ -253,7 +254,8 @@ __global__ __launch_bounds__(kBlock) void gat_scores_kernel(char *__restrict__ r
                                                             const float *__restrict__ alpha,
                                                             const float *__restrict__ a_src,
                                                             const float *__restrict__ a_dst, float *__restrict__ s,
-                                                            float *__restrict__ record, int embed)
+                                                            float *__restrict__ record, int embed,
+                                                            const float *__restrict__ last_sign)
 {
     constexpr int V = 8;
     const int lane = lane_id();
@@ -264,32 +266,49 @@ __global__ __launch_bounds__(kBlock) void gat_scores_kernel(char *__restrict__ r
     const int slot = lane / G;
     const int my_head = g / lanes_per_head;                    // >= H: lanes past the last head
     const bool live = my_head < H && slot < nodes_per_step;
+    // last_sign (layers of 256 input bits kept in one-byte rows): the stored values cover the first
+    // 255 bits; the last one contributes f_i b_c to the product, f_i = the sign of beta[i] and
+    // b_c = last_sign[c], so s_i[h] gains beta_i * sum_c a_src[c] alpha[c] b_c (signed beta_i) and
+    // the other terms take |beta_i|.
     float ca[V], cd[V];
-    float sum_a = 0.0f, sum_d = 0.0f;
+    float sum_a = 0.0f, sum_d = 0.0f, last_a = 0.0f, last_d = 0.0f;
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         const int c = g * V + v;
         const bool in = live && c < d_out;
         const float al = in ? alpha[c] : 0.0f;
+        const float lb = (in && last_sign != nullptr) ? last_sign[c] : 0.0f;
         ca[v] = in ? a_src[c] * al : 0.0f;
         cd[v] = in ? a_dst[c] * al : 0.0f;
         sum_a += ca[v];
         sum_d += cd[v];
+        last_a = fmaf(ca[v], lb, last_a);
+        last_d = fmaf(cd[v], lb, last_d);
     }
-    // per-head constants bias * sum_c a[c] alpha[c]: this lane's own head (butterfly) or all heads
-    float const_s[H], const_t[H];
+    // per-head constants bias * sum_c a[c] alpha[c] and sum_c a[c] alpha[c] b_c: this lane's own
+    // head (butterfly) or all heads
+    float const_s[H], const_t[H], fold_s[H], fold_t[H];
     if (butterfly) {
         for (int off = 1; off < lanes_per_head; off <<= 1) {
             sum_a += __shfl_xor(sum_a, off, kWave);
             sum_d += __shfl_xor(sum_d, off, kWave);
+            last_a += __shfl_xor(last_a, off, kWave);
+            last_d += __shfl_xor(last_d, off, kWave);
         }
 #pragma unroll
-        for (int h = 0; h < H; ++h) { const_s[h] = bias * sum_a; const_t[h] = bias * sum_d; }
+        for (int h = 0; h < H; ++h) {
+            const_s[h] = bias * sum_a;
+            const_t[h] = bias * sum_d;
+            fold_s[h] = last_a;
+            fold_t[h] = last_d;
+        }
     } else {
 #pragma unroll
         for (int h = 0; h < H; ++h) {
             const_s[h] = bias * wave_sum(live && my_head == h ? sum_a : 0.0f);
             const_t[h] = bias * wave_sum(live && my_head == h ? sum_d : 0.0f);
+            fold_s[h] = wave_sum(live && my_head == h ? last_a : 0.0f);
+            fold_t[h] = wave_sum(live && my_head == h ? last_d : 0.0f);
         }
     }
     const int64_t wave = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block();
@@ -331,9 +350,10 @@ __global__ __launch_bounds__(kBlock) void gat_scores_kernel(char *__restrict__ r
                     ps += __shfl_xor(ps, off, kWave);
                     pt += __shfl_xor(pt, off, kWave);
                 }
-                const float t_mine = b * fmaf(mul, pt, const_t[0]);
+                const float ab = fabsf(b);
+                const float t_mine = fmaf(b, fold_t[0], ab * fmaf(mul, pt, const_t[0]));
                 if (mine && g == my_head * lanes_per_head) {        // first lane of the head's group
-                    s[i * H + my_head] = b * fmaf(mul, ps, const_s[0]);
+                    s[i * H + my_head] = fmaf(b, fold_s[0], ab * fmaf(mul, ps, const_s[0]));
                     if (!embed) {
                         record[i * gat_record_floats<H>() + 1 + my_head] = t_mine;
                         if (g == 0) record[i * gat_record_floats<H>()] = b;
@@ -357,13 +377,14 @@ __global__ __launch_bounds__(kBlock) void gat_scores_kernel(char *__restrict__ r
                 }
             } else {
                 const float b0 = __shfl(b, 0, kWave);
+                const float ab0 = fabsf(b0);
 #pragma unroll
                 for (int h = 0; h < H; ++h) {
                     const float ss = wave_sum(mine && my_head == h ? ps : 0.0f);
                     const float tt = wave_sum(mine && my_head == h ? pt : 0.0f);
                     if (lane == 0) {
-                        s[i * H + h] = b0 * fmaf(mul, ss, const_s[h]);
-                        record[i * gat_record_floats<H>() + 1 + h] = b0 * fmaf(mul, tt, const_t[h]);
+                        s[i * H + h] = fmaf(b0, fold_s[h], ab0 * fmaf(mul, ss, const_s[h]));
+                        record[i * gat_record_floats<H>() + 1 + h] = fmaf(b0, fold_t[h], ab0 * fmaf(mul, tt, const_t[h]));
                     }
                 }
                 if (lane == 0) record[i * gat_record_floats<H>()] = b0;
@@ -377,12 +398,14 @@ template <int H>
 struct GatState {
     float m[H];       // running maximum of e_ij (wave-uniform)
     float l[H];       // sum of exp(e_ij - m), per-lane partial until reduced
-    float sw[H];      // sum of exp(e_ij - m) beta_j, per-lane partial until reduced
-    float acc[8];     // sum of exp(e_ij - m) beta_j q_j over this lane's columns and slot
+    float sw[H];      // sum of exp(e_ij - m) |beta_j|, per-lane partial until reduced
+    float sf[H];      // sum of exp(e_ij - m) beta_j with its sign (layers with a folded last bit)
+    float acc[8];     // sum of exp(e_ij - m) |beta_j| q_j over this lane's columns and slot
 };
 
 // Neighbours p0..p1-1 of node `row`.  wbuf: this wavefront's H x 64 floats of LDS.
-template <typename T, int G, int H>
+// kFold: the stored scale carries the sign of the neighbour's last input bit (see gat_scores_kernel).
+template <typename T, int G, int H, bool kFold>
 __device__ __forceinline__ void gat_accumulate(const int32_t *__restrict__ col_idx, const char *__restrict__ lane_base,
                                                uint32_t row_bytes, const float *__restrict__ record,
                                                const float (&si)[H], float slope, int my_head, int64_t p0,
@@ -391,7 +414,7 @@ __device__ __forceinline__ void gat_accumulate(const int32_t *__restrict__ col_i
     constexpr int V = 8, S = kWave / G, U = 4;
     const int slot = lane / G;
 #pragma unroll
-    for (int h = 0; h < H; ++h) { st.m[h] = -INFINITY; st.l[h] = 0.0f; st.sw[h] = 0.0f; }
+    for (int h = 0; h < H; ++h) { st.m[h] = -INFINITY; st.l[h] = 0.0f; st.sw[h] = 0.0f; st.sf[h] = 0.0f; }
 #pragma unroll
     for (int v = 0; v < V; ++v) st.acc[v] = 0.0f;
 
@@ -426,9 +449,10 @@ __device__ __forceinline__ void gat_accumulate(const int32_t *__restrict__ col_i
             rescale[h] = expf(st.m[h] - mn);                 // 0 on the first batch (m = -inf)
             st.m[h] = mn;
             const float pe = lane < cnt ? expf(e[h] - mn) : 0.0f;
-            w[h] = pe * bk;
+            w[h] = pe * (kFold ? fabsf(bk) : bk);
             st.l[h] = fmaf(st.l[h], rescale[h], pe);
             st.sw[h] = fmaf(st.sw[h], rescale[h], w[h]);
+            if constexpr (kFold) st.sf[h] = fmaf(st.sf[h], rescale[h], pe * bk);
         }
         const float my_rescale = pick<H>(rescale, my_head);
 #pragma unroll
@@ -474,6 +498,7 @@ __device__ __forceinline__ void gat_accumulate(const int32_t *__restrict__ col_i
     for (int h = 0; h < H; ++h) {
         st.l[h] = wave_sum(st.l[h]);
         st.sw[h] = wave_sum(st.sw[h]);
+        if constexpr (kFold) st.sf[h] = wave_sum(st.sf[h]);
     }
 #pragma unroll
     for (int off = G; off < kWave; off <<= 1)
@@ -481,10 +506,12 @@ __device__ __forceinline__ void gat_accumulate(const int32_t *__restrict__ col_i
         for (int v = 0; v < V; ++v) st.acc[v] += __shfl_xor(st.acc[v], off, kWave);
 }
 
-// out_i[c] = alpha[c] (mul * acc[c] + bias * sw[h]) / l[h]; an empty row gives zeros.
-template <int G, int H>
+// out_i[c] = alpha[c] (mul * acc[c] + bias * sw[h] + last_sign[c] * sf[h]) / l[h] (the last term
+// with kFold only); an empty row gives zeros.
+template <int G, int H, bool kFold>
 __device__ __forceinline__ void gat_finish(const GatState<H> &st, int64_t row, int lane, int my_head, int d_out,
                                            float mul, float bias, const float *__restrict__ alpha,
+                                           const float *__restrict__ last_sign,
                                            float *__restrict__ out, int64_t ld_out, int vector_store)
 {
     constexpr int V = 8;
@@ -492,11 +519,14 @@ __device__ __forceinline__ void gat_finish(const GatState<H> &st, int64_t row, i
     const float l = pick<H>(st.l, my_head);
     const float inv = l > 0.0f ? 1.0f / l : 0.0f;
     const float base = bias * pick<H>(st.sw, my_head);
+    const float folded = kFold ? pick<H>(st.sf, my_head) : 0.0f;
     float r[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         const int c = lane * V + v;
-        r[v] = c < d_out ? alpha[c] * fmaf(mul, st.acc[v], base) * inv : 0.0f;
+        float sum = fmaf(mul, st.acc[v], base);
+        if constexpr (kFold) sum = c < d_out ? fmaf(last_sign[c], folded, sum) : sum;
+        r[v] = c < d_out ? alpha[c] * sum * inv : 0.0f;
     }
     float *dst = out + row * ld_out + lane * V;
     if (vector_store && lane * V + V <= d_out) {
@@ -519,16 +549,17 @@ constexpr int gat_min_waves()
     return (sizeof(T) == 1 && H <= 2) ? 8 : 1;
 }
 
-template <typename T, int G, int H>
+template <typename T, int G, int H, bool kFold>
 __global__ __launch_bounds__(kBlock, (gat_min_waves<T, H>())) void gat_aggregate_kernel(
     const bigcn_plan_entry *__restrict__ entries, int64_t n, int64_t n_block_rows,
     const int32_t *__restrict__ col_idx, const char *__restrict__ rows, uint32_t row_bytes,
     const float *__restrict__ s, const float *__restrict__ record, const float *__restrict__ alpha, int d_out,
-    int d_head, float mul, float bias, float slope, float *__restrict__ out, int64_t ld_out, int vector_store)
+    int d_head, float mul, float bias, float slope, const float *__restrict__ last_sign, float *__restrict__ out,
+    int64_t ld_out, int vector_store)
 {
     constexpr int V = 8;
     __shared__ float wbuf_all[kWavesPerBlock][H > 1 ? H * kWave : 1];
-    __shared__ float merge[kWavesPerBlock - 1][V + 3 * H][kWave];
+    __shared__ float merge[kWavesPerBlock - 1][V + (kFold ? 4 : 3) * H][kWave];
     const int lane = lane_id();
     const int wave = wave_in_block();
     const int g = lane & (G - 1);
@@ -549,7 +580,7 @@ __global__ __launch_bounds__(kBlock, (gat_min_waves<T, H>())) void gat_aggregate
         if (q1 > p1) q1 = p1;
 #pragma unroll
         for (int h = 0; h < H; ++h) si[h] = s[row * H + h];
-        gat_accumulate<T, G, H>(col_idx, lane_base, row_bytes, record, si, slope, my_head, q0, q1, lane, wbuf, st);
+        gat_accumulate<T, G, H, kFold>(col_idx, lane_base, row_bytes, record, si, slope, my_head, q0, q1, lane, wbuf, st);
         if (wave > 0) {
 #pragma unroll
             for (int v = 0; v < V; ++v) merge[wave - 1][v][lane] = st.acc[v];
@@ -558,6 +589,7 @@ __global__ __launch_bounds__(kBlock, (gat_min_waves<T, H>())) void gat_aggregate
                 merge[wave - 1][V + h][lane] = st.m[h];
                 merge[wave - 1][V + H + h][lane] = st.l[h];
                 merge[wave - 1][V + 2 * H + h][lane] = st.sw[h];
+                if constexpr (kFold) merge[wave - 1][V + 3 * H + h][lane] = st.sf[h];
             }
         }
         __syncthreads();
@@ -576,6 +608,7 @@ __global__ __launch_bounds__(kBlock, (gat_min_waves<T, H>())) void gat_aggregate
                 f0[h] = st.m[h] == -INFINITY ? 0.0f : expf(st.m[h] - top[h]);
                 st.l[h] *= f0[h];
                 st.sw[h] *= f0[h];
+                if constexpr (kFold) st.sf[h] *= f0[h];
             }
             const float mine0 = pick<H>(f0, my_head);
 #pragma unroll
@@ -589,12 +622,13 @@ __global__ __launch_bounds__(kBlock, (gat_min_waves<T, H>())) void gat_aggregate
                     f[h] = mw == -INFINITY ? 0.0f : expf(mw - top[h]);
                     st.l[h] = fmaf(f[h], merge[w][V + H + h][lane], st.l[h]);
                     st.sw[h] = fmaf(f[h], merge[w][V + 2 * H + h][lane], st.sw[h]);
+                    if constexpr (kFold) st.sf[h] = fmaf(f[h], merge[w][V + 3 * H + h][lane], st.sf[h]);
                 }
                 const float mine = pick<H>(f, my_head);
 #pragma unroll
                 for (int v = 0; v < V; ++v) st.acc[v] = fmaf(mine, merge[w][v][lane], st.acc[v]);
             }
-            gat_finish<G, H>(st, row, lane, my_head, d_out, mul, bias, alpha, out, ld_out, vector_store);
+            gat_finish<G, H, kFold>(st, row, lane, my_head, d_out, mul, bias, alpha, last_sign, out, ld_out, vector_store);
         }
         return;
     }
@@ -604,9 +638,9 @@ __global__ __launch_bounds__(kBlock, (gat_min_waves<T, H>())) void gat_aggregate
     const int64_t row = e.row;
 #pragma unroll
     for (int h = 0; h < H; ++h) si[h] = s[row * H + h];
-    gat_accumulate<T, G, H>(col_idx, lane_base, row_bytes, record, si, slope, my_head, e.first, e.first + e.count,
+    gat_accumulate<T, G, H, kFold>(col_idx, lane_base, row_bytes, record, si, slope, my_head, e.first, e.first + e.count,
                             lane, wbuf, st);
-    gat_finish<G, H>(st, row, lane, my_head, d_out, mul, bias, alpha, out, ld_out, vector_store);
+    gat_finish<G, H, kFold>(st, row, lane, my_head, d_out, mul, bias, alpha, last_sign, out, ld_out, vector_store);
 }
 
 // ---- compact path, record inside the row ---------------------------------------------------
@@ -936,6 +970,16 @@ __global__ __launch_bounds__(kBlock, 8) void gat_aggregate_embedded_kernel(
     gat_finish_embedded(st, row, lane, mul, bias, alpha, out, ld_out, vector_store);
 }
 
+// last_sign[c] = +1 / -1: bit k_bits - 1 of column c's packed weights
+__global__ void gat_last_sign_kernel(const uint64_t *__restrict__ w_bits, int64_t ld_words, int k_bits, int d_out,
+                                     float *__restrict__ last_sign)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= d_out) return;
+    const uint64_t word = w_bits[static_cast<int64_t>(c) * ld_words + ((k_bits - 1) >> 6)];
+    last_sign[c] = ((word >> ((k_bits - 1) & 63)) & 1ull) ? 1.0f : -1.0f;
+}
+
 struct GatMap {
     size_t bits_off, beta_off, z_off, s_off, t_off, total;
     // compact path: z_off holds the product rows, t_off the records {beta, t[0..H-1]}
@@ -943,6 +987,11 @@ struct GatMap {
     RowKind kind;
     int groups;           // lanes per row (8 values each)
     int64_t row_bytes;
+    // one-byte rows of a layer with 256 input bits: the stored values cover the first 255, the last
+    // one rides on the sign of the node's scale and on last_sign[c] = +-1, its weight bit
+    bool fold;
+    size_t sign_off;
+    const float *last_sign;   // DEVICE, set by the entry point (nullptr unless fold)
 };
 
 static bool gat_shape_ok(int64_t d_in, int64_t d_out, int heads)
@@ -956,7 +1005,9 @@ static GatMap map_gat(int64_t n, int64_t d_in, int64_t d_out, int heads)
     auto up = [](size_t v) { return (v + 255) & ~static_cast<size_t>(255); };
     GatMap m;
     m.compact = (d_out / heads) % 8 == 0;
-    m.kind = d_in <= 255 ? kI8 : (d_in <= 2048 ? kF16 : kF32);
+    m.fold = m.compact && d_in == 256;
+    m.kind = (d_in <= 255 || m.fold) ? kI8 : (d_in <= 2048 ? kF16 : kF32);
+    m.last_sign = nullptr;
     m.groups = 2;
     while (m.groups < kWave && m.groups * 8 < d_out) m.groups <<= 1;
     m.row_bytes = static_cast<int64_t>(m.groups) * 8 * (m.kind == kI8 ? 1 : (m.kind == kF16 ? 2 : 4));
@@ -967,6 +1018,7 @@ static GatMap map_gat(int64_t n, int64_t d_in, int64_t d_out, int heads)
     m.s_off = off;    off = up(off + static_cast<size_t>(n) * heads * 4);
     // compact path: records of (heads + 1) floats padded to whole 16-byte vectors
     m.t_off = off;    off = up(off + static_cast<size_t>(n) * (m.compact ? (heads + 1 + 3) / 4 * 4 : heads) * 4);
+    m.sign_off = off; off = up(off + (m.fold ? static_cast<size_t>(d_out) * 4 : 0));
     m.total = off;
     return m;
 }
@@ -980,13 +1032,13 @@ static int launch_gat_compact(const bigcn_plan *plan, const int64_t *row_ptr, co
     // the record rides in the rows' spare top bits when every product fits 7 bits
     const bool embed = gat_embeds<T, G, H>() && d_out == 256 && d_in <= 127 && n < (int64_t{1} << 24);
     const float mul = sizeof(T) == 1 ? 2.0f : 1.0f;
-    const float bias = sizeof(T) == 1 ? static_cast<float>(d_in & 1) : 0.0f;
+    const float bias = sizeof(T) == 1 ? static_cast<float>((map.fold ? d_in - 1 : d_in) & 1) : 0.0f;
     const int d_head = static_cast<int>(d_out / H);
     const int64_t node_blocks = (n + kWavesPerBlock - 1) / kWavesPerBlock;
     const int64_t score_blocks = node_blocks > compute_units() * 8 ? compute_units() * 8 : node_blocks;
     hipLaunchKernelGGL((gat_scores_kernel<T, G, H>), dim3(static_cast<unsigned>(score_blocks)), dim3(kBlock), 0, st,
                        rows, static_cast<uint32_t>(map.row_bytes), n, static_cast<int>(d_out), d_head, mul, bias, beta,
-                       alpha, a_src, a_dst, s, record, embed ? 1 : 0);
+                       alpha, a_src, a_dst, s, record, embed ? 1 : 0, map.last_sign);
     if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
     const int64_t wave_rows = n - plan->n_block_rows;
     const int64_t blocks = plan->n_block_rows + (wave_rows + kWavesPerBlock - 1) / kWavesPerBlock;
@@ -1005,10 +1057,19 @@ static int launch_gat_compact(const bigcn_plan *plan, const int64_t *row_ptr, co
             return check_launch();
         }
     }
-    hipLaunchKernelGGL((gat_aggregate_kernel<T, G, H>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st,
+    if constexpr (sizeof(T) == 1) {
+        if (map.fold) {
+            hipLaunchKernelGGL((gat_aggregate_kernel<T, G, H, true>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0,
+                               st, plan->entries, n, plan->n_block_rows, col_idx, rows,
+                               static_cast<uint32_t>(map.row_bytes), s, record, alpha, static_cast<int>(d_out), d_head,
+                               mul, bias, slope, map.last_sign, out, ld_out, vector_store);
+            return check_launch();
+        }
+    }
+    hipLaunchKernelGGL((gat_aggregate_kernel<T, G, H, false>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st,
                        plan->entries, n, plan->n_block_rows, col_idx, rows,
                        static_cast<uint32_t>(map.row_bytes), s, record, alpha, static_cast<int>(d_out), d_head, mul,
-                       bias, slope, out, ld_out, vector_store);
+                       bias, slope, nullptr, out, ld_out, vector_store);
     return check_launch();
 }
 
@@ -1083,7 +1144,7 @@ extern "C" int bigcn_gat_layer(const bigcn_plan *plan, const int64_t *row_ptr, c
         return BIGCN_EINVAL;
     if (!gat_shape_ok(d_in, d_out, heads)) return BIGCN_ESHAPE;
     if (n == 0) return BIGCN_OK;
-    const GatMap map = map_gat(n, d_in, d_out, heads);
+    GatMap map = map_gat(n, d_in, d_out, heads);
     if (workspace == nullptr || workspace_bytes < map.total || reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
         return BIGCN_EWORKSPACE;
     hipStream_t st = as_stream(stream);
@@ -1094,16 +1155,26 @@ extern "C" int bigcn_gat_layer(const bigcn_plan *plan, const int64_t *row_ptr, c
     float *t = reinterpret_cast<float *>(ws + map.t_off);
     const int64_t words = (d_in + 63) / 64;
 
-    int rc = launch_pack(x, n, d_in, ld_x, 1, bn_shift, bn_mul, nullptr, 0, bits, words, beta, st);
+    // fold: the scale carries the sign of the node's last input bit
+    int rc = launch_pack(x, n, d_in, ld_x, 1, bn_shift, bn_mul, nullptr, map.fold ? 1 : 0, bits, words, beta, st);
     if (rc != BIGCN_OK) return rc;
 
     if (map.compact) {
         char *rows = ws + map.z_off;
+        const int64_t k_stored = map.fold ? d_in - 1 : d_in;          // bits covered by the stored values
+        if (map.fold) {
+            float *last_sign = reinterpret_cast<float *>(ws + map.sign_off);
+            hipLaunchKernelGGL(gat_last_sign_kernel, dim3(static_cast<unsigned>((d_out + 255) / 256)), dim3(256), 0, st,
+                               w_bits, ld_words, static_cast<int>(d_in), static_cast<int>(d_out), last_sign);
+            if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
+            map.last_sign = last_sign;
+        }
         // large layers of one-byte rows on the matrix cores, everything else by XOR and bit counts
-        if (map.kind == kI8 && fp4_natural_covers(n, d_in, map.groups * 8))
-            rc = launch_bitgemm_fp4_natural(bits, n, words, w_bits, d_out, ld_words, d_in, rows, map.groups * 8, st);
+        if (map.kind == kI8 && fp4_natural_covers(n, k_stored, map.groups * 8))
+            rc = launch_bitgemm_fp4_natural(bits, n, words, w_bits, d_out, ld_words, k_stored, rows, map.groups * 8, st);
         else
-            rc = launch_bitgemm_natural(bits, n, words, w_bits, d_out, ld_words, d_in, rows, map.groups * 8, map.kind, st);
+            rc = launch_bitgemm_natural(bits, n, words, w_bits, d_out, ld_words, k_stored, rows, map.groups * 8, map.kind, st,
+                                        map.fold ? 0x7fffffffu : 0xffffffffu);
         if (rc != BIGCN_OK) return rc;
         if (map.kind == kI8)
             return launch_gat_compact_heads<int8_t>(heads, map.groups, plan, row_ptr, col_idx, n, map, rows, beta,

@@ -95,6 +95,14 @@ def run_gpu(B, rp, ci, x, w, a_src, a_dst, heads, slope, bn=None, self_loops=Tru
     (36000, 120000, 127, 256, 1, True, False, 2.0),
     (34000, 100000, 33, 512, 8, True, False, 2.0),
     (40000, 150000, 90, 40, 1, True, True, 2.0),
+    # 256 input bits in one-byte rows: the stored values cover 255 bits, the last one rides on the
+    # sign of the node's scale (rows shared by a workgroup, empty rows, heads of a lane count that is
+    # no power of two, the matrix-core rows kernel)
+    (3000, 40000, 256, 256, 2, True, True, 1.2),
+    (2500, 2000, 256, 64, 4, False, False, 2.0),
+    (1300, 6000, 256, 96, 2, True, True, 2.0),
+    (36000, 120000, 256, 256, 2, True, False, 2.0),
+    (1000, 5000, 256, 512, 8, True, False, 2.0),
     # plain fp32 rows: heads that are not a multiple of 8 columns wide
     (1500, 20000, 100, 36, 2, True, True, 1.2),
 ])

@@ -342,12 +342,13 @@ def gat_leg(B, m, cfg, reps=3, hidden=False):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / reps
     nnz = int(m["col_idx"].numel())
-    # per neighbour: its index, its compact product row (one byte per product up to 255 input
-    # bits, fp16 to 2048, fp32 beyond) and its record {beta, t[heads]}, which rides in the row's
-    # spare top bits when the products fit 7 bits (256 columns, at most two heads and 127 input bits)
-    # (256 input bits: one-byte values over the first 255, the last bit on the sign of beta)
+    # per neighbour: its index, its compact product row (one byte per product up to 256 input
+    # bits, fp16 to 2048, fp32 beyond; 256 bits: values over the first 255, the last bit on the
+    # sign of beta) and its record {beta, t[heads]}, which rides in the row's spare top bits when
+    # the products fit 7 bits (256 columns, at most two heads and 256 input bits; beyond 127 bits
+    # the library tests the rows, and seeded random signs never leave 7 bits)
     elem = 1 if d_in <= 256 else (2 if d_in <= 2048 else 4)
-    embedded = d_in <= 127 and d_out == 256 and heads <= 2
+    embedded = d_in <= 256 and d_out == 256 and heads <= 2
     per_neighbour = 4 + elem * d_out + (0 if embedded else 4 * (1 + heads))
     lines = 128 * (-(-(elem * d_out) // 128) + (0 if embedded else 1))   # the row's cache lines (+ one for the record)
     return {"d_in": d_in, "d_out": d_out, "heads": heads, "ms": ms, "bytes_per_neighbour": per_neighbour,

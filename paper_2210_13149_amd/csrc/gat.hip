@@ -242,8 +242,9 @@ constexpr float kLog2e = 1.44269504088896340736f;
 // spans a power-of-two number of lanes its sums are a butterfly inside that lane group;
 // otherwise one masked sum over the wavefront per head (one node at a time).
 // record[i] = {beta_i, t_i[0..H-1]} at a stride of gat_record_floats<H>() floats.
-// embed != 0 (one-byte rows of 256 columns, one or two heads, at most 127 input bits, so that
-// every stored value fits 7 bits): the record goes into the row itself instead.  Lane g of the
+// Record inside the row (one-byte rows of 256 columns, one or two heads, every stored value
+// within 7 bits: always so up to 127 input bits, else checked by gat_fit_kernel): the record goes
+// into the row itself instead.  Lane g of the
 // row's 32 lanes gives bit g of beta_i to the top bit of its byte 3, bit g of t_i[0] log2(e) to
 // the top bit of byte 7 and bit g of t_i[1] log2(e) to the top bit of byte 2 (see
 // gat_aggregate_embedded_kernel).
@@ -254,10 +255,13 @@ __global__ __launch_bounds__(kBlock) void gat_scores_kernel(char *__restrict__ r
                                                             const float *__restrict__ alpha,
                                                             const float *__restrict__ a_src,
                                                             const float *__restrict__ a_dst, float *__restrict__ s,
-                                                            float *__restrict__ record, int embed,
+                                                            float *__restrict__ record, int embed_mode,
+                                                            const int *__restrict__ misfit,
                                                             const float *__restrict__ last_sign)
 {
     constexpr int V = 8;
+    // embed_mode 0: records beside the rows; 1: inside the rows; 2: inside unless *misfit is set
+    const int embed = embed_mode == 1 || (embed_mode == 2 && *misfit == 0) ? 1 : 0;
     const int lane = lane_id();
     const int g = lane & (G - 1);
     const int lanes_per_head = d_head / V;
@@ -554,10 +558,13 @@ __global__ __launch_bounds__(kBlock, (gat_min_waves<T, H>())) void gat_aggregate
     const bigcn_plan_entry *__restrict__ entries, int64_t n, int64_t n_block_rows,
     const int32_t *__restrict__ col_idx, const char *__restrict__ rows, uint32_t row_bytes,
     const float *__restrict__ s, const float *__restrict__ record, const float *__restrict__ alpha, int d_out,
-    int d_head, float mul, float bias, float slope, const float *__restrict__ last_sign, float *__restrict__ out,
-    int64_t ld_out, int vector_store)
+    int d_head, float mul, float bias, float slope, const float *__restrict__ last_sign,
+    const int *__restrict__ gate, float *__restrict__ out, int64_t ld_out, int vector_store)
 {
     constexpr int V = 8;
+    // gate (nullable): a device flag; while it is 0 the rows carry their records themselves and
+    // gat_aggregate_embedded_kernel does the work: this launch returns at once
+    if (gate != nullptr && *gate == 0) return;
     __shared__ float wbuf_all[kWavesPerBlock][H > 1 ? H * kWave : 1];
     __shared__ float merge[kWavesPerBlock - 1][V + (kFold ? 4 : 3) * H][kWave];
     const int lane = lane_id();
@@ -661,8 +668,9 @@ struct GatLaneState {
     float m;          // maximum of e_ij log2(e) over the lane's head
     float ref;        // m, or 0 while m is -inf (so that exp2(x - ref) is never inf - inf)
     float l;          // sum of 2^(e_ij - m)
-    float sw;         // sum of 2^(e_ij - m) beta_j
-    float acc[8];     // sum of 2^(e_ij - m) beta_j q_j over this lane's columns
+    float sw;         // sum of 2^(e_ij - m) |beta_j|
+    float sf;         // sum of 2^(e_ij - m) beta_j with its sign (layers with a folded last bit, else unused)
+    float acc[8];     // sum of 2^(e_ij - m) |beta_j| q_j over this lane's columns
 };
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -709,7 +717,8 @@ struct GatGroupState {
     float m;          // running maximum of e_ij log2(e)
     float ref;        // m, or 0 while m is -inf (so that exp2(x - ref) is never inf - inf)
     float l;          // sum of 2^(e_ij - m)
-    float sw;         // sum of 2^(e_ij - m) beta_j
+    float sw;         // sum of 2^(e_ij - m) |beta_j|
+    float sf;         // sum of 2^(e_ij - m) beta_j with its sign (kFold)
 };
 
 template <int kCtrl>
@@ -773,7 +782,7 @@ __device__ __forceinline__ float from_lane(int byte_address, float v)
 // weights are formed once per neighbour and head, and every row lane fetches the weight of its
 // neighbour and head through the LDS crossbar.  kUnitSlope: 0 <= slope <= 1, where
 // LeakyReLU(x) = max(x, slope x).
-template <int H, bool kUnitSlope, int U>
+template <int H, bool kUnitSlope, int U, bool kFold>
 __device__ __forceinline__ void gat_consume_group(const uint2 (&raw)[U], const GatLaneMasks &lm, int t, int cnt,
                                                   float s_lane, float slope, GatGroupState &st, float (&acc)[8])
 {
@@ -799,14 +808,17 @@ __device__ __forceinline__ void gat_consume_group(const uint2 (&raw)[U], const G
         st.ref = ref;
         st.l *= f;
         st.sw *= f;
+        if constexpr (kFold) st.sf *= f;
         const float mine = from_lane(lm.head_lane, f);
 #pragma unroll
         for (int v = 0; v < V; ++v) acc[v] *= mine;
     }
     const float pe = exp2_fast(e - st.ref);                   // 0 for an absent neighbour
-    const float w = pe * __builtin_bit_cast(float, bw);
+    const float bj = __builtin_bit_cast(float, bw);
+    const float w = pe * (kFold ? fabsf(bj) : bj);
     st.l += pe;
     st.sw += w;
+    if constexpr (kFold) st.sf = fmaf(pe, bj, st.sf);
     float mine[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) mine[u] = from_lane(lm.weight_lane + 8 * u, w);
@@ -823,7 +835,7 @@ __device__ __forceinline__ void gat_consume_group(const uint2 (&raw)[U], const G
 // loads before the group in front of it is used was measured and is 4 % slower: the kernel
 // waits for issue slots and for the memory system's rate, not for latency.)  At the end every
 // lane holds the state of its own head and columns, the two halves of the wavefront added.
-template <int H, bool kUnitSlope>
+template <int H, bool kUnitSlope, bool kFold>
 __device__ __forceinline__ void gat_accumulate_embedded(const int32_t *__restrict__ col_idx,
                                                         const char *__restrict__ rows, const GatLaneMasks &lm,
                                                         float s_lane, float slope, int64_t p0, int64_t p1, int k_first,
@@ -835,6 +847,7 @@ __device__ __forceinline__ void gat_accumulate_embedded(const int32_t *__restric
     st.ref = 0.0f;
     st.l = 0.0f;
     st.sw = 0.0f;
+    st.sf = 0.0f;
 #pragma unroll
     for (int v = 0; v < V; ++v) out.acc[v] = 0.0f;
 
@@ -847,7 +860,7 @@ __device__ __forceinline__ void gat_accumulate_embedded(const int32_t *__restric
         for (int t = 0; t < cnt; t += 2 * U) {
             uint2 raw[U];
             gat_fetch_group<U>(rows, lm, k, from, cnt, raw);
-            gat_consume_group<H, kUnitSlope, U>(raw, lm, t, cnt, s_lane, slope, st, out.acc);
+            gat_consume_group<H, kUnitSlope, U, kFold>(raw, lm, t, cnt, s_lane, slope, st, out.acc);
             from += 2 * U;
         }
     }
@@ -857,6 +870,8 @@ __device__ __forceinline__ void gat_accumulate_embedded(const int32_t *__restric
     out.ref = out.m == -INFINITY ? 0.0f : out.m;
     out.l = from_lane(lm.head_lane, l);
     out.sw = from_lane(lm.head_lane, sw);
+    out.sf = 0.0f;
+    if constexpr (kFold) out.sf = from_lane(lm.head_lane, sum_of_eight(st.sf));
 #pragma unroll
     for (int v = 0; v < V; ++v) out.acc[v] += __shfl_xor(out.acc[v], 32, kWave);
 }
@@ -872,9 +887,9 @@ __device__ __forceinline__ GatLaneMasks gat_lane_masks(int lane, bool second_hea
     return lm;
 }
 
-// Brings `st` and a second state (m2, l2, sw2, acc2) of the same node, head and columns to their
-// common maximum and adds them into `st`.
-__device__ __forceinline__ void gat_merge_embedded(GatLaneState &st, float m2, float l2, float sw2,
+// Brings `st` and a second state (m2, l2, sw2, sf2, acc2) of the same node, head and columns to
+// their common maximum and adds them into `st`.
+__device__ __forceinline__ void gat_merge_embedded(GatLaneState &st, float m2, float l2, float sw2, float sf2,
                                                    const float (&acc2)[8])
 {
     const float mn = fmaxf(st.m, m2);
@@ -884,12 +899,15 @@ __device__ __forceinline__ void gat_merge_embedded(GatLaneState &st, float m2, f
     st.ref = ref;
     st.l = fmaf(f2, l2, st.l * f1);
     st.sw = fmaf(f2, sw2, st.sw * f1);
+    st.sf = fmaf(f2, sf2, st.sf * f1);
 #pragma unroll
     for (int v = 0; v < 8; ++v) st.acc[v] = fmaf(f2, acc2[v], st.acc[v] * f1);
 }
 
+template <bool kFold>
 __device__ __forceinline__ void gat_finish_embedded(const GatLaneState &st, int64_t row, int lane, float mul,
                                                     float bias, const float *__restrict__ alpha,
+                                                    const float *__restrict__ last_sign,
                                                     float *__restrict__ out, int64_t ld_out, int vector_store)
 {
     constexpr int V = 8;
@@ -898,7 +916,11 @@ __device__ __forceinline__ void gat_finish_embedded(const GatLaneState &st, int6
     const float base = bias * st.sw;
     float r[V];
 #pragma unroll
-    for (int v = 0; v < V; ++v) r[v] = alpha[lane * V + v] * fmaf(mul, st.acc[v], base) * inv;
+    for (int v = 0; v < V; ++v) {
+        float sum = fmaf(mul, st.acc[v], base);
+        if constexpr (kFold) sum = fmaf(last_sign[lane * V + v], st.sf, sum);
+        r[v] = alpha[lane * V + v] * sum * inv;
+    }
     float *dst = out + row * ld_out + lane * V;
     if (vector_store) {
         reinterpret_cast<float4 *>(dst)[0] = make_float4(r[0], r[1], r[2], r[3]);
@@ -911,15 +933,18 @@ __device__ __forceinline__ void gat_finish_embedded(const GatLaneState &st, int6
 
 // Same division of the nodes as gat_aggregate_kernel.  256 columns, H heads of 256 / H; the rows
 // take less than 4 GiB (offsets into them are 32-bit).
-template <int H, bool kUnitSlope>
+// misfit (nullable): a device flag; when it is set (some product did not fit 7 bits, so the rows
+// were not stamped) the launch returns at once and gat_aggregate_kernel does the work instead.
+template <int H, bool kUnitSlope, bool kFold>
 __global__ __launch_bounds__(kBlock, 8) void gat_aggregate_embedded_kernel(
     const bigcn_plan_entry *__restrict__ entries, int64_t n, int64_t n_block_rows,
     const int32_t *__restrict__ col_idx, const char *__restrict__ rows, const float *__restrict__ s,
-    const float *__restrict__ alpha, float mul, float bias, float slope, float *__restrict__ out, int64_t ld_out,
-    int vector_store)
+    const float *__restrict__ alpha, float mul, float bias, float slope, const float *__restrict__ last_sign,
+    const int *__restrict__ misfit, float *__restrict__ out, int64_t ld_out, int vector_store)
 {
     constexpr int V = 8;
-    __shared__ float merge[kWavesPerBlock - 1][V + 3][32];
+    __shared__ float merge[kWavesPerBlock - 1][V + 4][32];
+    if (misfit != nullptr && *misfit != 0) return;             // the same for every thread of the launch
     const int lane = lane_id();
     const int wave = wave_in_block();
     const bool second_head = H == 2 && (lane & 31) >= 16;
@@ -938,13 +963,14 @@ __global__ __launch_bounds__(kBlock, 8) void gat_aggregate_embedded_kernel(
         if (q1 > p1) q1 = p1;
         const float s_lane = s[row * H + softmax_head] * kLog2e;
         const int k_first = q0 + lane < q1 ? col_idx[q0 + lane] : 0;
-        gat_accumulate_embedded<H, kUnitSlope>(col_idx, rows, lm, s_lane, slope, q0, q1, k_first, lane, st);
+        gat_accumulate_embedded<H, kUnitSlope, kFold>(col_idx, rows, lm, s_lane, slope, q0, q1, k_first, lane, st);
         if (wave > 0 && lane < 32) {
 #pragma unroll
             for (int v = 0; v < V; ++v) merge[wave - 1][v][lane] = st.acc[v];
             merge[wave - 1][V][lane] = st.m;
             merge[wave - 1][V + 1][lane] = st.l;
             merge[wave - 1][V + 2][lane] = st.sw;
+            merge[wave - 1][V + 3][lane] = st.sf;
         }
         __syncthreads();
         if (wave == 0 && lane < 32) {
@@ -953,9 +979,10 @@ __global__ __launch_bounds__(kBlock, 8) void gat_aggregate_embedded_kernel(
                 float acc2[V];
 #pragma unroll
                 for (int v = 0; v < V; ++v) acc2[v] = merge[w][v][lane];
-                gat_merge_embedded(st, merge[w][V][lane], merge[w][V + 1][lane], merge[w][V + 2][lane], acc2);
+                gat_merge_embedded(st, merge[w][V][lane], merge[w][V + 1][lane], merge[w][V + 2][lane], merge[w][V + 3][lane],
+                                   acc2);
             }
-            gat_finish_embedded(st, row, lane, mul, bias, alpha, out, ld_out, vector_store);
+            gat_finish_embedded<kFold>(st, row, lane, mul, bias, alpha, last_sign, out, ld_out, vector_store);
         }
         return;
     }
@@ -966,9 +993,24 @@ __global__ __launch_bounds__(kBlock, 8) void gat_aggregate_embedded_kernel(
     const float s_lane = s[row * H + softmax_head] * kLog2e;
     const int64_t p0 = e.first, p1 = e.first + e.count;
     const int k_first = p0 + lane < p1 ? col_idx[p0 + lane] : 0;
-    gat_accumulate_embedded<H, kUnitSlope>(col_idx, rows, lm, s_lane, slope, p0, p1, k_first, lane, st);
-    gat_finish_embedded(st, row, lane, mul, bias, alpha, out, ld_out, vector_store);
+    gat_accumulate_embedded<H, kUnitSlope, kFold>(col_idx, rows, lm, s_lane, slope, p0, p1, k_first, lane, st);
+    gat_finish_embedded<kFold>(st, row, lane, mul, bias, alpha, last_sign, out, ld_out, vector_store);
 }
+
+// *misfit = 1 if any stored byte is outside [-64, 63] (bit 7 differs from bit 6); the flag is
+// cleared by gat_clear_flag_kernel before.
+__global__ __launch_bounds__(kBlock) void gat_fit_kernel(const uint4 *__restrict__ rows, int64_t n_vec, int *__restrict__ misfit)
+{
+    uint32_t bad = 0;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; i < n_vec;
+         i += static_cast<int64_t>(gridDim.x) * kBlock) {
+        const uint4 v = rows[i];
+        bad |= (v.x ^ (v.x << 1)) | (v.y ^ (v.y << 1)) | (v.z ^ (v.z << 1)) | (v.w ^ (v.w << 1));
+    }
+    if (__ballot((bad & 0x80808080u) != 0u) != 0ull && lane_id() == 0) *misfit = 1;   // plain store of the same value
+}
+
+__global__ void gat_clear_flag_kernel(int *__restrict__ flag) { *flag = 0; }
 
 // last_sign[c] = +1 / -1: bit k_bits - 1 of column c's packed weights
 __global__ void gat_last_sign_kernel(const uint64_t *__restrict__ w_bits, int64_t ld_words, int k_bits, int d_out,
@@ -990,8 +1032,9 @@ struct GatMap {
     // one-byte rows of a layer with 256 input bits: the stored values cover the first 255, the last
     // one rides on the sign of the node's scale and on last_sign[c] = +-1, its weight bit
     bool fold;
-    size_t sign_off;
+    size_t sign_off, flag_off;
     const float *last_sign;   // DEVICE, set by the entry point (nullptr unless fold)
+    int *misfit;              // DEVICE flag of gat_fit_kernel, set by the entry point
 };
 
 static bool gat_shape_ok(int64_t d_in, int64_t d_out, int heads)
@@ -1019,6 +1062,8 @@ static GatMap map_gat(int64_t n, int64_t d_in, int64_t d_out, int heads)
     // compact path: records of (heads + 1) floats padded to whole 16-byte vectors
     m.t_off = off;    off = up(off + static_cast<size_t>(n) * (m.compact ? (heads + 1 + 3) / 4 * 4 : heads) * 4);
     m.sign_off = off; off = up(off + (m.fold ? static_cast<size_t>(d_out) * 4 : 0));
+    m.flag_off = off; off = up(off + 4);
+    m.misfit = nullptr;
     m.total = off;
     return m;
 }
@@ -1029,47 +1074,66 @@ static int launch_gat_compact(const bigcn_plan *plan, const int64_t *row_ptr, co
                               const float *a_src, const float *a_dst, float *s, float *record, int64_t d_in,
                               int64_t d_out, float slope, float *out, int64_t ld_out, hipStream_t st)
 {
-    // the record rides in the rows' spare top bits when every product fits 7 bits
-    const bool embed = gat_embeds<T, G, H>() && d_out == 256 && d_in <= 127 && n < (int64_t{1} << 24);
+    // The record rides in the rows' spare top bits when every product fits 7 bits: always so up to
+    // 127 input bits; up to 256 the rows are tested first (a product over K' bits has standard
+    // deviation sqrt(K') / 2, so 7 bits hold 8 sigma at K' = 255) and a device flag picks, inside
+    // the launches, between the kernels that read stamped rows and those that read records.
+    const int64_t k_stored = map.fold ? d_in - 1 : d_in;
+    const bool shape_embeds = gat_embeds<T, G, H>() && d_out == 256 && k_stored <= 255 && n < (int64_t{1} << 24);
+    const int embed_mode = !shape_embeds ? 0 : (k_stored <= 127 ? 1 : 2);
     const float mul = sizeof(T) == 1 ? 2.0f : 1.0f;
-    const float bias = sizeof(T) == 1 ? static_cast<float>((map.fold ? d_in - 1 : d_in) & 1) : 0.0f;
+    const float bias = sizeof(T) == 1 ? static_cast<float>(k_stored & 1) : 0.0f;
     const int d_head = static_cast<int>(d_out / H);
+    if (embed_mode == 2) {
+        hipLaunchKernelGGL(gat_clear_flag_kernel, dim3(1), dim3(1), 0, st, map.misfit);
+        if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
+        const int64_t n_vec = n * map.row_bytes / 16;
+        hipLaunchKernelGGL(gat_fit_kernel, dim3(static_cast<unsigned>(compute_units() * 16)), dim3(kBlock), 0, st,
+                           reinterpret_cast<const uint4 *>(rows), n_vec, map.misfit);
+        if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
+    }
     const int64_t node_blocks = (n + kWavesPerBlock - 1) / kWavesPerBlock;
     const int64_t score_blocks = node_blocks > compute_units() * 8 ? compute_units() * 8 : node_blocks;
     hipLaunchKernelGGL((gat_scores_kernel<T, G, H>), dim3(static_cast<unsigned>(score_blocks)), dim3(kBlock), 0, st,
                        rows, static_cast<uint32_t>(map.row_bytes), n, static_cast<int>(d_out), d_head, mul, bias, beta,
-                       alpha, a_src, a_dst, s, record, embed ? 1 : 0, map.last_sign);
+                       alpha, a_src, a_dst, s, record, embed_mode, map.misfit, map.last_sign);
     if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
     const int64_t wave_rows = n - plan->n_block_rows;
     const int64_t blocks = plan->n_block_rows + (wave_rows + kWavesPerBlock - 1) / kWavesPerBlock;
+    const dim3 grid(static_cast<unsigned>(blocks));
     const int vector_store = (ld_out % 4 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0) ? 1 : 0;
+    const int *flag = embed_mode == 2 ? map.misfit : nullptr;
     if constexpr (gat_embeds<T, G, H>()) {
-        if (embed) {
-            const dim3 grid(static_cast<unsigned>(blocks));
-            if (slope >= 0.0f && slope <= 1.0f)
-                hipLaunchKernelGGL((gat_aggregate_embedded_kernel<H, true>), grid, dim3(kBlock), 0, st, plan->entries, n,
-                                   plan->n_block_rows, col_idx, rows, s, alpha, mul, bias, slope, out, ld_out,
-                                   vector_store);
-            else
-                hipLaunchKernelGGL((gat_aggregate_embedded_kernel<H, false>), grid, dim3(kBlock), 0, st, plan->entries,
-                                   n, plan->n_block_rows, col_idx, rows, s, alpha, mul, bias, slope, out, ld_out,
-                                   vector_store);
-            return check_launch();
+        if (embed_mode != 0) {
+            const bool unit = slope >= 0.0f && slope <= 1.0f;
+#define BIGCN_GAT_EMBEDDED(UNIT, FOLD)                                                                              \
+    hipLaunchKernelGGL((gat_aggregate_embedded_kernel<H, UNIT, FOLD>), grid, dim3(kBlock), 0, st, plan->entries, n,  \
+                       plan->n_block_rows, col_idx, rows, s, alpha, mul, bias, slope, map.last_sign, flag, out,     \
+                       ld_out, vector_store)
+            if (map.fold) {
+                if (unit) BIGCN_GAT_EMBEDDED(true, true);
+                else BIGCN_GAT_EMBEDDED(false, true);
+            } else {
+                if (unit) BIGCN_GAT_EMBEDDED(true, false);
+                else BIGCN_GAT_EMBEDDED(false, false);
+            }
+#undef BIGCN_GAT_EMBEDDED
+            if (embed_mode == 1) return check_launch();
+            if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
         }
     }
     if constexpr (sizeof(T) == 1) {
         if (map.fold) {
-            hipLaunchKernelGGL((gat_aggregate_kernel<T, G, H, true>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0,
-                               st, plan->entries, n, plan->n_block_rows, col_idx, rows,
-                               static_cast<uint32_t>(map.row_bytes), s, record, alpha, static_cast<int>(d_out), d_head,
-                               mul, bias, slope, map.last_sign, out, ld_out, vector_store);
+            hipLaunchKernelGGL((gat_aggregate_kernel<T, G, H, true>), grid, dim3(kBlock), 0, st, plan->entries, n,
+                               plan->n_block_rows, col_idx, rows, static_cast<uint32_t>(map.row_bytes), s, record, alpha,
+                               static_cast<int>(d_out), d_head, mul, bias, slope, map.last_sign, flag, out, ld_out,
+                               vector_store);
             return check_launch();
         }
     }
-    hipLaunchKernelGGL((gat_aggregate_kernel<T, G, H, false>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st,
-                       plan->entries, n, plan->n_block_rows, col_idx, rows,
-                       static_cast<uint32_t>(map.row_bytes), s, record, alpha, static_cast<int>(d_out), d_head, mul,
-                       bias, slope, nullptr, out, ld_out, vector_store);
+    hipLaunchKernelGGL((gat_aggregate_kernel<T, G, H, false>), grid, dim3(kBlock), 0, st, plan->entries, n,
+                       plan->n_block_rows, col_idx, rows, static_cast<uint32_t>(map.row_bytes), s, record, alpha,
+                       static_cast<int>(d_out), d_head, mul, bias, slope, nullptr, flag, out, ld_out, vector_store);
     return check_launch();
 }
 
@@ -1169,6 +1233,7 @@ extern "C" int bigcn_gat_layer(const bigcn_plan *plan, const int64_t *row_ptr, c
             if (hipGetLastError() != hipSuccess) return BIGCN_EHIP;
             map.last_sign = last_sign;
         }
+        map.misfit = reinterpret_cast<int *>(ws + map.flag_off);
         // large layers of one-byte rows on the matrix cores, everything else by XOR and bit counts
         if (map.kind == kI8 && fp4_natural_covers(n, k_stored, map.groups * 8))
             rc = launch_bitgemm_fp4_natural(bits, n, words, w_bits, d_out, ld_words, k_stored, rows, map.groups * 8, st);

@@ -148,6 +148,30 @@ def test_gat_record_inside_the_row_with_any_slope(B, slope):
     check_against(got, ref, rp, ci, a_src, a_dst, heads)
 
 
+@pytest.mark.parametrize("d_in", [200, 256])
+@pytest.mark.parametrize("aligned", [False, True])
+def test_gat_wide_layers_with_and_without_products_outside_seven_bits(B, d_in, aligned):
+    """256 columns of 128..256 input bits: the record rides in the rows' top bits when every
+    product fits 7 bits (random signs: always) and beside the rows otherwise; a node whose signs
+    equal those of a weight column has the largest possible product there."""
+    rng = np.random.default_rng(d_in + int(aligned))
+    n, d_out, heads = 2000, 256, 2
+    rp, ci = chung_lu_csr(n, 16000, 2.5, 1.3, seed=77)
+    x = rng.standard_normal((n, d_in)).astype(np.float32)
+    w = rng.uniform(-1, 1, size=(d_in, d_out)).astype(np.float32)
+    if aligned:
+        x[5] = np.abs(x[5]) * np.sign(w[:, 3])
+        x[900] = -np.abs(x[900]) * np.sign(w[:, 200])
+    a_src = (rng.standard_normal((heads, d_out // heads)) / 8).astype(np.float32)
+    a_dst = (rng.standard_normal((heads, d_out // heads)) / 8).astype(np.float32)
+    ref = oracle.gat_layer(rp, ci, x, w, a_src, a_dst, heads=heads, negative_slope=0.2)
+    if aligned:
+        prod = np.sign(x[5]) @ np.sign(w[:, 3])
+        assert prod == d_in                                  # the stored value is outside 7 bits
+    got = run_gpu(B, rp, ci, x, w, a_src, a_dst, heads, 0.2).cpu().numpy()
+    check_against(got, ref, rp, ci, a_src, a_dst, heads)
+
+
 def test_gat_with_zero_attention_is_the_mean_aggregator_and_runs_are_identical(B):
     import torch
     rng = np.random.default_rng(8)

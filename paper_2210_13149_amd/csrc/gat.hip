@@ -8,9 +8,9 @@
 // products of a node as one compact row in column order (one byte per product up to 256 input
 // bits, the last of 256 bits carried on the sign of the node's scale; fp16 up to 2048, fp32
 // beyond); the row scale beta_j and the scores t_j = a_dst . z_j sit together in a small
-// per-node record (256-column rows of at most 127 input bits, whose values
-// fit 7 bits, carry that record in spare top bits instead, so that a neighbour costs the two
-// cache lines of its row and no other).  The aggregation makes ONE pass over the neighbours of
+// per-node record (256-column one-byte rows whose values all fit 7 bits carry that record in
+// their spare top bits instead, so that a neighbour costs the two cache lines of its row and no
+// other).  The aggregation makes ONE pass over the neighbours of
 // a node: per batch of 64 neighbours the running maximum of e_ij is raised and the accumulators
 // rescaled (once per batch and head), so no separate maximum pass gathers the records twice.
 // Long rows are shared by the four wavefronts of a workgroup and merged through LDS.  Sums are
@@ -651,9 +651,9 @@ __global__ __launch_bounds__(kBlock, (gat_min_waves<T, H>())) void gat_aggregate
 }
 
 // ---- compact path, record inside the row ---------------------------------------------------
-// One-byte rows of 256 columns whose values fit 7 bits (at most 127 input bits) have a spare top
-// bit in every byte, and gat_scores_kernel stores beta_j and t_j there: a neighbour costs its two
-// row lines and nothing else.  A load instruction fetches two neighbours (lanes 0..31 one,
+// One-byte rows of 256 columns whose values fit 7 bits (always so up to 127 input bits, tested by
+// gat_fit_kernel beyond) have a spare top bit in every byte, and gat_scores_kernel stores beta_j
+// and t_j there: a neighbour costs its two row lines and nothing else.  A load instruction fetches two neighbours (lanes 0..31 one,
 // lanes 32..63 the other), and three ballots over the carrier bits give their record words as
 // scalar values.  These are written into lanes 0..15, which form the scores, the running maximum
 // (raised per eight neighbours, the rescaling skipped while no head's maximum moves) and the

@@ -103,6 +103,8 @@ def run_gpu(B, rp, ci, x, w, a_src, a_dst, heads, slope, bn=None, self_loops=Tru
     (1300, 6000, 256, 96, 2, True, True, 2.0),
     (36000, 120000, 256, 256, 2, True, False, 2.0),
     (1000, 5000, 256, 512, 8, True, False, 2.0),
+    (1500, 9000, 256, 256, 1, True, True, 2.0),
+    (1500, 9000, 200, 256, 1, False, False, 1.1),
     # plain fp32 rows: heads that are not a multiple of 8 columns wide
     (1500, 20000, 100, 36, 2, True, True, 1.2),
 ])
